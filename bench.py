@@ -1,0 +1,173 @@
+#!/usr/bin/env python3
+"""Benchmark of the Stripe block executor on one MI355X.
+
+A step is one evaluation of one Stripe block (one stripe_block_run) on
+synthetic seeded inputs that are resident in HBM before the timed region.
+Default workload: the dense contraction block C[m,n] += A[m,k]*B[k,n],
+M=N=K=4096, bf16 inputs, fp32 accumulate (the configuration the headline
+metric is quoted on).  Other configurations can be timed with --workload;
+the memory-bound ones rotate through several buffer sets so that the 256 MB
+Infinity Cache cannot serve them.
+
+Prints ONE JSON line with the throughput, the roofline record of the kernel
+(measured live with HIP events on the launch stream) and the CPU oracle timed
+on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK = {"bf16_mfma_tflops": 2500.0, "int8_mfma_tops": 5000.0, "hbm_gbs": 8000.0}
+
+# workload -> (metric unit, bound, arithmetic dtype)
+KIND = {
+    "gemm_bf16_4096": ("TFLOP/s", "mfma", "bf16"),
+    "resnet_conv_bf16": ("TFLOP/s", "hbm", "bf16"),
+    "conv7x7_s2_int8": ("TOP/s", "hbm", "int8"),
+    "maxpool_f32": ("GB/s", "hbm", "f32"),
+    "tiny_conv_f32": ("TFLOP/s", "hbm", "f32"),
+}
+
+
+def oracle_sample(name, root, inputs, cores):
+    """Time the oracle, as it stands, on a slab of the workload's outputs."""
+    import numpy as np
+    from oracle import stripe_oracle as O
+    from paper_1903_06498_amd import workloads as W
+    first = root.child
+    lo, hi = [0] * len(first.ranges), list(first.ranges)
+    if name == "gemm_bf16_4096":
+        hi[0] = 16                       # 16 full output rows, every k: 268 M points
+        sample, split = "16 of 4096 output rows (all n, all k), literal loops", 1
+    elif name == "resnet_conv_bf16":
+        hi[0] = 2                        # 2 of 32 images: 231 M points
+        sample, split = "2 of 32 images", 1
+    elif name == "conv7x7_s2_int8":
+        hi[0] = 2
+        sample, split = "2 of 16 images", 1
+    elif name == "maxpool_f32":
+        hi[0] = 32
+        sample, split = "all 32 images", 0
+    else:
+        sample, split = "the whole block", 1
+    np_ins = [W.to_numpy(t).ravel() for t in inputs]
+    t0 = time.perf_counter()
+    res = O.evaluate(root, np_ins, window=(lo, hi), threads=cores, split_index=split)
+    dt = time.perf_counter() - t0
+    return res, dt, sample, (lo, hi)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="gemm_bf16_4096", choices=sorted(KIND))
+    ap.add_argument("--path", default="auto", help="force a kernel family (auto, generic, mfma_gemm, mfma_conv, pool)")
+    ap.add_argument("--cpu-baseline", type=int, default=1, help="0 skips the oracle timing (profiling runs)")
+    ap.add_argument("--rotate", type=int, default=-1, help="buffer sets to rotate through (-1: 1 for gemm, enough to exceed 512 MB otherwise)")
+    ap.add_argument("--traffic-bytes", type=float, default=None, help="HBM bytes per launch from rocprofv3 counters, if measured")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (every box here has one); --gpus must be 1")
+
+    import torch
+    from paper_1903_06498_amd import binding as B
+    from paper_1903_06498_amd import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the HIP library has no CPU fallback")
+    dev = torch.device("cuda:0")
+    name = args.workload
+    unit, bound, dtype = KIND[name]
+    root = W.config_block(name)
+    inputs = W.config_inputs(name)
+    blk = B.StripeBlock(root, args.path)
+    info = blk.info
+    ext = W.output_extent(root)
+    odt = torch.int32 if root.refs[-1].dtype == "i32" else torch.float32
+
+    set_bytes = sum(t.numel() * t.element_size() for t in inputs) + ext * 4
+    n_sets = args.rotate
+    if n_sets < 1:
+        n_sets = 1 if bound == "mfma" else max(2, int(640e6 // set_bytes) + 1)
+    sets = []
+    for _ in range(n_sets):
+        sets.append(([t.to(dev) for t in inputs], torch.zeros(ext, dtype=odt, device=dev)))
+    torch.cuda.synchronize()
+
+    stream = torch.cuda.current_stream()
+    for i in range(args.warmup):
+        ins, out = sets[i % n_sets]
+        blk.run(ins, out, stream.cuda_stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for i in range(args.steps):
+        ins, out = sets[i % n_sets]
+        blk.run(ins, out, stream.cuda_stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    gpu_ms = ev0.elapsed_time(ev1)
+    ms_per_step = wall_ms / args.steps
+    kernel_s = gpu_ms / args.steps * 1e-3      # average launch duration over the timed region (events on the launch stream)
+
+    work = info["work_points"]
+    flops = 2.0 * work
+    nbytes = float(info["algorithmic_bytes"])
+    if unit == "GB/s":
+        value = nbytes / (ms_per_step * 1e-3) / 1e9
+    else:
+        value = flops / (ms_per_step * 1e-3) / 1e12
+    if bound == "mfma":
+        peak = PEAK["int8_mfma_tops"] if dtype == "int8" else PEAK["bf16_mfma_tflops"]
+        achieved = flops / kernel_s / 1e12
+        roof = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+                "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes}
+    else:
+        achieved = nbytes / kernel_s / 1e9
+        roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
+                "frac": round(achieved / PEAK["hbm_gbs"], 4), "traffic": args.traffic_bytes}
+    roof["kernel"] = info["kernel"]
+    roof["kernel_us"] = round(kernel_s * 1e6, 2)
+    roof["algorithmic_bytes"] = info["algorithmic_bytes"]
+    roof["algorithmic_flops"] = int(flops)
+
+    cpu = None
+    if args.cpu_baseline:
+        cores = min(16, os.cpu_count() or 1)
+        res, dt, sample, _ = oracle_sample(name, root, inputs, cores)
+        if unit == "GB/s":
+            frac = res.n_points / max(1, work)
+            cpu_value = nbytes * frac / dt / 1e9
+        else:
+            cpu_value = 2.0 * res.n_points / dt / 1e12
+        cpu = {"value": float(f"{cpu_value:.6g}"), "unit": unit, "cores": cores, "kind": "oracle",
+               "sample": f"{sample}: {res.n_points} points in {dt:.2f} s"}
+
+    line = {
+        "metric": "Stripe block throughput: TFLOP/s (% of MFMA peak) for conv/matmul blocks, GB/s for max blocks",
+        "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": name, "path": info["path_name"], "kernel": info["kernel"],
+                   "tile": [info["tile_m"], info["tile_n"], info["tile_k"]], "grid": info["grid"],
+                   "buffer_sets": n_sets, "hull_points": info["hull_points"], "work_points": work},
+        "roofline": roof, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+    blk.close()
+
+
+if __name__ == "__main__":
+    main()

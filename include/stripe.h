@@ -1,0 +1,190 @@
+/*
+ * stripe.h -- C ABI of the MI355X (gfx950) executor for one Stripe block.
+ *
+ * A Stripe block (paper, Section 3.2) is a parallel polyhedral block
+ * (Section 3.1.2, Definition 2): a list of indexes with one range each, a
+ * list of affine constraints "expr >= 0", a single statement list, and the
+ * buffers it reads and writes, each with an aggregation operation.  Blocks
+ * nest (Section 3.1.3): a statement may be another block, which sees its
+ * parent's buffers only through refinements -- offset, sized and strided
+ * views -- and its parent's indexes only as explicitly passed affine values
+ * (Figure 5b).  This library evaluates such a nest whose leaf statement list
+ * is  load, [load, mul|add,] store  on one GPU.
+ *
+ * All descriptor memory is HOST memory owned by the caller; create() copies
+ * what it needs, so the descriptor may be freed right after it returns.
+ * Buffers handed to run() are DEVICE pointers owned by the caller.  No
+ * function throws or aborts; every failure is a status code, with detail in
+ * stripe_last_error().  Apart from that thread-local string the library keeps
+ * no global state; handles are independent of each other.
+ */
+#ifndef STRIPE_H
+#define STRIPE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  STRIPE_OK = 0,
+  STRIPE_ERR_NULL = 1,            /* a required pointer argument is NULL */
+  STRIPE_ERR_INVALID_DESC = 2,    /* malformed descriptor (counts, ranges, shapes, type mix) */
+  STRIPE_ERR_UNSUPPORTED = 3,     /* a legal block this library cannot run (yet) */
+  STRIPE_ERR_OUT_OF_BOUNDS = 4,   /* an access inside the polyhedron may leave its buffer or view */
+  STRIPE_ERR_ASSIGN_CONFLICT = 5, /* 'assign' level whose iterations are not provably disjoint */
+  STRIPE_ERR_HIP = 6,             /* a HIP runtime call failed */
+  STRIPE_ERR_NOMEM = 7
+} stripe_status_t;
+
+typedef enum { STRIPE_I8 = 0, STRIPE_I32 = 1, STRIPE_BF16 = 2, STRIPE_F32 = 3 } stripe_dtype_t;
+
+/* Aggregation operations (Section 2.1 last sentence; Section 3.2: 'assign'
+ * declares that no two iterations write the same element). */
+typedef enum { STRIPE_AGG_ASSIGN = 0, STRIPE_AGG_ADD = 1, STRIPE_AGG_MAX = 2, STRIPE_AGG_MIN = 3 } stripe_agg_t;
+
+/* Leaf statement lists (Section 3.2 "intrinsics"; Figure 5 lines 0-3 of the inner block):
+ *   MUL : $a = load(in0); $b = load(in1); $o = mul($a,$b); out = store($o)
+ *   ADD : the same with add
+ *   COPY: $a = load(in0); out = store($a)                                   */
+typedef enum { STRIPE_INTR_MUL = 0, STRIPE_INTR_COPY = 1, STRIPE_INTR_ADD = 2 } stripe_intrinsic_t;
+
+typedef enum { STRIPE_IN = 0, STRIPE_OUT = 1 } stripe_dir_t;
+
+/* Which kernel family runs the block (reported by stripe_block_query). */
+typedef enum {
+  STRIPE_PATH_AUTO = 0,      /* create: let the planner choose */
+  STRIPE_PATH_GENERIC = 1,   /* affine-index contraction, any legal block */
+  STRIPE_PATH_MFMA_GEMM = 2, /* nested-tile dense contraction on matrix cores */
+  STRIPE_PATH_MFMA_CONV = 3, /* nested-tile convolution-shaped contraction on matrix cores */
+  STRIPE_PATH_POOL = 4       /* max aggregation over a window of one input */
+} stripe_path_t;
+
+/*
+ * One refinement (Section 3.2, "refinements"; Figure 5 "in I[3*x - 1, 4*y - 1, 0]
+ * i8(5, 6, 8):(128, 8, 1)"): a buffer as one nesting level sees it.
+ *   access_coeff [ndim][n_vars] row-major, access_const [ndim]:
+ *       per dimension the affine origin of the view, in this level's variables
+ *       (own indexes first, then passed values), measured from the origin of
+ *       the view the level itself received.  The absolute coordinate of a
+ *       leaf access is the sum over all levels.
+ *   sizes [ndim]: extent of the view handed to this level's statements
+ *       (root level: the extent of the buffer itself; leaf: all 1).  A view
+ *       may hang over the edge of its parent (halo tiles); only accesses that
+ *       are executed must fall inside every enclosing view and the buffer.
+ *   strides [ndim]: in elements, non-negative, identical at every level.
+ *   agg: aggregation of the output at this level; each level carries the
+ *       nest's single operation or ASSIGN.  Ignored for inputs.
+ */
+typedef struct {
+  stripe_dir_t dir;
+  stripe_dtype_t dtype;
+  stripe_agg_t agg;
+  int32_t ndim;                /* 1..8 */
+  const int64_t* access_coeff;
+  const int64_t* access_const;
+  const int64_t* sizes;
+  const int64_t* strides;
+} stripe_refinement_t;
+
+/*
+ * One nesting level (Section 3.2 first paragraph; Figure 5).
+ * The outermost descriptor is the declaring root block ("block []:1"):
+ * n_idx = n_passed = n_constraints = 0, its refinements give the buffers'
+ * extents, strides and element types, access_const is the element offset of
+ * the origin (normally 0) and access_coeff is unused.  Below it come 1..6
+ * block levels; the last one (child == NULL) holds the intrinsic.
+ * Every level lists the same buffers in the same order: inputs first (one for
+ * COPY, two for MUL/ADD), the single output last.
+ * Element types: inputs i8/i32 with an i32 output, or bf16/f32 with an f32
+ * output.  Integer arithmetic is exact two's-complement int32 (operands
+ * sign-extended before the multiply); float blocks accumulate in fp32.
+ */
+typedef struct stripe_block_desc {
+  int32_t n_idx;
+  const int64_t* ranges;        /* [n_idx]; index j takes 0 .. ranges[j]-1; 0 = empty block */
+  int32_t n_passed;
+  const int64_t* passed_coeff;  /* [n_passed][parent n_vars]: value = row . parent vars + const */
+  const int64_t* passed_const;  /* [n_passed] */
+  int32_t n_constraints;
+  const int64_t* cons_coeff;    /* [n_constraints][n_vars]: row . vars + const >= 0 */
+  const int64_t* cons_const;    /* [n_constraints] */
+  int32_t n_refs;
+  const stripe_refinement_t* refs;
+  stripe_intrinsic_t intrinsic; /* leaf only */
+  const struct stripe_block_desc* child;
+} stripe_block_desc_t;          /* n_vars of a level = n_idx + n_passed */
+
+typedef struct stripe_block stripe_block_t; /* opaque handle */
+
+/* What the planner decided; algorithmic figures count in-polyhedron points only. */
+typedef struct {
+  int32_t path;               /* stripe_path_t actually used */
+  int32_t n_idx;              /* indexes after flattening and merging */
+  int32_t n_out_idx;          /* indexes the output address depends on */
+  int32_t n_red_idx;          /* reduction indexes */
+  int64_t hull_points;        /* product of the flattened ranges */
+  int64_t work_points;        /* points meeting all constraints; -1 if not counted */
+  int64_t output_elements;    /* distinct output elements the hull can write */
+  int64_t algorithmic_bytes;  /* each input and output element once */
+  int32_t tile_m, tile_n, tile_k;   /* workgroup tile of the nested-tile paths, else 0 */
+  int32_t frag_m, frag_n, frag_k;   /* matrix-core fragment, else 0 */
+  int32_t lds_bytes;
+  int32_t workgroup_size;
+  int64_t grid;               /* workgroups per launch */
+  char kernel[64];            /* name of the kernel variant */
+} stripe_block_info_t;
+
+/*
+ * Validate, flatten and plan a block (host only, no GPU call).
+ * Flattening composes refinement offsets down the nest and substitutes passed
+ * values (Section 3.1.3), so a tiled nest and its un-tiled form plan alike.
+ * Every access is proven to stay inside its buffer and views for all points
+ * of the polyhedron, otherwise STRIPE_ERR_OUT_OF_BOUNDS.
+ * On success *out receives a handle the caller must release with
+ * stripe_block_destroy().
+ */
+stripe_status_t stripe_block_create(const stripe_block_desc_t* desc, stripe_block_t** out);
+
+/* As stripe_block_create, but forces a kernel family (STRIPE_PATH_AUTO = planner's
+ * choice).  STRIPE_ERR_UNSUPPORTED if the block does not have that family's shape. */
+stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, stripe_path_t path,
+                                             stripe_block_t** out);
+
+/*
+ * Launch the block on `hip_stream` (a hipStream_t; NULL = the default stream)
+ * of the current device.  inputs[i] is the DEVICE pointer of the i-th input
+ * refinement's buffer origin, output that of the output buffer; element types
+ * and extents as declared at the root.  Output elements no iteration writes
+ * keep their contents; written elements are overwritten (prior contents do
+ * not enter the aggregation).  Asynchronous: returns after enqueueing; only
+ * launch errors are reported.  Calls on different handles may overlap; two
+ * overlapping calls that write the same output buffer race.
+ */
+stripe_status_t stripe_block_run(stripe_block_t* blk, const void* const* inputs, void* output,
+                                 void* hip_stream);
+
+stripe_status_t stripe_block_query(const stripe_block_t* blk, stripe_block_info_t* info);
+
+void stripe_block_destroy(stripe_block_t* blk);
+
+const char* stripe_status_string(stripe_status_t status);
+
+/* Detail of the last failure on the calling thread ("" if none).  The pointer
+ * stays valid until the next failing call on this thread. */
+const char* stripe_last_error(void);
+
+/*
+ * Bandwidth yardstick: copies n_bytes (a multiple of 16, both pointers
+ * 16-byte aligned DEVICE memory) with a plain grid-stride 16-byte-per-lane
+ * kernel on `hip_stream`.  Used to scale hardware traffic counters and to
+ * state the achievable HBM rate next to the pooling kernels.
+ */
+stripe_status_t stripe_device_copy(const void* src, void* dst, size_t n_bytes, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* STRIPE_H */

@@ -1,0 +1,231 @@
+// Generic affine-index contraction kernel (gfx950): evaluates any legal flat
+// Stripe block.  Output indexes are spread over the grid, reduction indexes
+// are walked inside the kernel; every constraint is an integer affine test
+// per point (paper Section 3.2: ranges plus affine constraints); values that
+// land on one output element are combined with the aggregation operation
+// (Definition 2, rule 3) and elements no point writes are left alone.
+//
+// Two lane mappings:
+//   lanes == 1 : one lane per output element.  The fastest grid index is the
+//                output index with the smallest output stride, so stores -- and
+//                loads of inputs that follow that index -- coalesce.
+//   lanes == 64: one wavefront per output element; the 64 lanes stride through
+//                the flattened reduction space (innermost reduction index =
+//                smallest input stride, so a wavefront reads consecutive
+//                elements) and a cross-lane butterfly finishes the aggregation.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace stripe {
+namespace {
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<int8_t> {
+  using Acc = int32_t;
+  static __device__ __forceinline__ int32_t load(const void* p, int64_t i) { return (int32_t)((const int8_t*)p)[i]; }
+};
+template <>
+struct Elem<int32_t> {
+  using Acc = int32_t;
+  static __device__ __forceinline__ int32_t load(const void* p, int64_t i) { return ((const int32_t*)p)[i]; }
+};
+template <>
+struct Elem<uint16_t> {  // bf16 bit pattern: the upper half of an fp32
+  using Acc = float;
+  static __device__ __forceinline__ float load(const void* p, int64_t i) {
+    return __uint_as_float(((uint32_t)((const uint16_t*)p)[i]) << 16);
+  }
+};
+template <>
+struct Elem<float> {
+  using Acc = float;
+  static __device__ __forceinline__ float load(const void* p, int64_t i) { return ((const float*)p)[i]; }
+};
+
+template <int AGG, typename A>
+__device__ __forceinline__ A combine(A acc, A v) {
+  if (AGG == STRIPE_AGG_MAX) return v > acc ? v : acc;
+  if (AGG == STRIPE_AGG_MIN) return v < acc ? v : acc;
+  return acc + v;
+}
+
+template <typename TIn, int INTR, int AGG, int LANES>
+__global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, const void* __restrict__ in0,
+                                                      const void* __restrict__ in1, void* __restrict__ out) {
+  using Acc = typename Elem<TIn>::Acc;
+  const int lane = threadIdx.x & 63;
+  int64_t t = (LANES == 1) ? (int64_t)blockIdx.x * 256 + threadIdx.x
+                           : (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= p.n_outputs) return;  // lanes == 64: uniform per wavefront
+
+  int64_t offA = p.a_base, offB = p.b_base, offO = p.o_base;
+  int64_t cv[kGenCons];
+#pragma unroll
+  for (int q = 0; q < kGenCons; ++q) cv[q] = p.cons_const[q];
+  for (int j = 0; j < p.n_out; ++j) {
+    const int64_t rng = p.out_range[j];
+    const int64_t o = t % rng;
+    t /= rng;
+    offA += p.a_out[j] * o;
+    offB += p.b_out[j] * o;
+    offO += p.o_out[j] * o;
+#pragma unroll
+    for (int q = 0; q < kGenCons; ++q) cv[q] += (int64_t)p.cons_out[q][j] * o;
+  }
+
+  Acc acc = 0;
+  bool touched = false;
+
+  auto visit = [&](int64_t oa, int64_t ob) {
+    const Acc a = Elem<TIn>::load(in0, oa);
+    Acc v = a;
+    if (INTR != STRIPE_INTR_COPY) {
+      const Acc b = Elem<TIn>::load(in1, ob);
+      v = (INTR == STRIPE_INTR_MUL) ? a * b : a + b;
+    }
+    acc = touched ? combine<AGG, Acc>(acc, v) : v;
+    touched = true;
+  };
+
+  if (LANES == 1) {
+    const uint32_t inner = p.inner_range;
+    const uint32_t outer_total = p.red_total / inner;
+    for (uint32_t ro = 0; ro < outer_total; ++ro) {
+      int64_t oa = offA, ob = offB;
+      int64_t cw[kGenCons];
+#pragma unroll
+      for (int q = 0; q < kGenCons; ++q) cw[q] = cv[q];
+      uint32_t rest = ro;
+      for (int j = 1; j < p.n_red; ++j) {
+        const uint32_t rng = (uint32_t)p.red_range[j];
+        const uint32_t rj = rest % rng;
+        rest /= rng;
+        oa += p.a_red[j] * rj;
+        ob += p.b_red[j] * rj;
+#pragma unroll
+        for (int q = 0; q < kGenCons; ++q) cw[q] += (int64_t)p.cons_red[q][j] * rj;
+      }
+      const int64_t sa = p.a_red[0], sb = p.b_red[0];
+      for (uint32_t r0 = 0; r0 < inner; ++r0) {
+        bool ok = true;
+#pragma unroll
+        for (int q = 0; q < kGenCons; ++q) ok = ok && (cw[q] + (int64_t)p.cons_red[q][0] * r0 >= 0);
+        if (ok) visit(oa + sa * r0, ob + sb * r0);
+      }
+    }
+    if (touched) ((Acc*)out)[offO] = acc;
+  } else {
+    for (uint32_t r = lane; r < p.red_total; r += 64) {
+      int64_t oa = offA, ob = offB;
+      int64_t cw[kGenCons];
+#pragma unroll
+      for (int q = 0; q < kGenCons; ++q) cw[q] = cv[q];
+      uint32_t rest = r;
+      for (int j = 0; j < p.n_red; ++j) {
+        const uint32_t rng = (uint32_t)p.red_range[j];
+        const uint32_t rj = rest % rng;
+        rest /= rng;
+        oa += p.a_red[j] * rj;
+        ob += p.b_red[j] * rj;
+#pragma unroll
+        for (int q = 0; q < kGenCons; ++q) cw[q] += (int64_t)p.cons_red[q][j] * rj;
+      }
+      bool ok = true;
+#pragma unroll
+      for (int q = 0; q < kGenCons; ++q) ok = ok && (cw[q] >= 0);
+      if (ok) visit(oa, ob);
+    }
+    // butterfly over the 64 lanes; a lane that saw no point contributes nothing
+#pragma unroll
+    for (int m = 32; m >= 1; m >>= 1) {
+      const Acc other = __shfl_xor(acc, m, 64);
+      const int other_touched = __shfl_xor((int)touched, m, 64);
+      if (other_touched) {
+        acc = touched ? combine<AGG, Acc>(acc, other) : other;
+        touched = true;
+      }
+    }
+    if (lane == 0 && touched) ((Acc*)out)[offO] = acc;
+  }
+}
+
+template <typename TIn, int INTR, int AGG>
+hipError_t launch_lanes(const GenericParams& p, const void* a, const void* b, void* o, hipStream_t s) {
+  if (p.lanes == 64) {
+    const int64_t grid = (p.n_outputs + 3) / 4;
+    hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 64>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+  } else {
+    const int64_t grid = (p.n_outputs + 255) / 256;
+    hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 1>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+  }
+  return hipGetLastError();
+}
+
+template <typename TIn, int INTR>
+hipError_t launch_agg(int agg, const GenericParams& p, const void* a, const void* b, void* o, hipStream_t s) {
+  switch (agg) {
+    case STRIPE_AGG_MAX: return launch_lanes<TIn, INTR, STRIPE_AGG_MAX>(p, a, b, o, s);
+    case STRIPE_AGG_MIN: return launch_lanes<TIn, INTR, STRIPE_AGG_MIN>(p, a, b, o, s);
+    default: return launch_lanes<TIn, INTR, STRIPE_AGG_ADD>(p, a, b, o, s);  // assign: single writer, any op
+  }
+}
+
+template <typename TIn>
+hipError_t launch_intr(int intr, int agg, const GenericParams& p, const void* a, const void* b, void* o, hipStream_t s) {
+  switch (intr) {
+    case STRIPE_INTR_COPY: return launch_agg<TIn, STRIPE_INTR_COPY>(agg, p, a, b, o, s);
+    case STRIPE_INTR_ADD: return launch_agg<TIn, STRIPE_INTR_ADD>(agg, p, a, b, o, s);
+    default: return launch_agg<TIn, STRIPE_INTR_MUL>(agg, p, a, b, o, s);
+  }
+}
+
+}  // namespace
+
+hipError_t launch_generic(const Plan& plan, const void* in0, const void* in1, void* out, hipStream_t stream) {
+  const GenericParams& p = plan.gen;
+  if (p.n_outputs <= 0) return hipErrorInvalidValue;
+  const int64_t blocks = p.lanes == 64 ? (p.n_outputs + 3) / 4 : (p.n_outputs + 255) / 256;
+  if (blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+  const int intr = plan.flat.intrinsic, agg = plan.flat.agg;
+  switch (plan.in_dtype) {
+    case STRIPE_I8: return launch_intr<int8_t>(intr, agg, p, in0, in1, out, stream);
+    case STRIPE_I32: return launch_intr<int32_t>(intr, agg, p, in0, in1, out, stream);
+    case STRIPE_BF16: return launch_intr<uint16_t>(intr, agg, p, in0, in1, out, stream);
+    default: return launch_intr<float>(intr, agg, p, in0, in1, out, stream);
+  }
+}
+
+void generic_info(const Plan& plan, stripe_block_info_t* info) {
+  const GenericParams& p = plan.gen;
+  info->path = STRIPE_PATH_GENERIC;
+  info->tile_m = info->tile_n = info->tile_k = 0;
+  info->frag_m = info->frag_n = info->frag_k = 0;
+  info->lds_bytes = 0;
+  info->workgroup_size = 256;
+  info->grid = p.lanes == 64 ? (p.n_outputs + 3) / 4 : (p.n_outputs + 255) / 256;
+  snprintf(info->kernel, sizeof info->kernel, "generic_affine_%s", p.lanes == 64 ? "wave_per_output" : "lane_per_output");
+}
+
+// ---------------------------------------------------------------------------
+// Bandwidth yardstick: plain 16-byte-per-lane grid-stride copy.
+// ---------------------------------------------------------------------------
+namespace {
+__global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+}  // namespace
+
+hipError_t launch_copy(const void* src, void* dst, size_t n_bytes, hipStream_t stream) {
+  const size_t n16 = n_bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 32) blocks = 256 * 32;
+  hipLaunchKernelGGL(copy_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4*)src, (uint4*)dst, n16);
+  return hipGetLastError();
+}
+
+}  // namespace stripe

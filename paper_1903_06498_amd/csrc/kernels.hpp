@@ -1,0 +1,59 @@
+// Launchers of the HIP kernel families (gfx950).  Each *_select() decides on
+// the host whether the family covers the shape and fills the launch record
+// and the query info; each launch_*() enqueues on the given stream.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdlib>
+#include <cstring>
+
+#include "plan.hpp"
+
+namespace stripe {
+
+// Tuning overrides for measurements: STRIPE_TUNE="key=value,key=value" is read
+// when a handle is created; without it every family uses its default variant.
+inline int tune_int(const char* key, int dflt) {
+  const char* s = std::getenv("STRIPE_TUNE");
+  if (!s) return dflt;
+  const size_t n = std::strlen(key);
+  for (const char* f = std::strstr(s, key); f; f = std::strstr(f + 1, key))
+    if ((f == s || f[-1] == ',') && f[n] == '=') return std::atoi(f + n + 1);
+  return dflt;
+}
+
+// ---- generic affine-index contraction (any legal block) -------------------
+hipError_t launch_generic(const Plan& plan, const void* in0, const void* in1, void* out, hipStream_t stream);
+void generic_info(const Plan& plan, stripe_block_info_t* info);
+
+// ---- nested-tile dense contraction on matrix cores ------------------------
+struct GemmLaunch {
+  int variant = -1;
+  int64_t grid = 0;
+  mutable int lds_enabled_on = -1;  // device on which the kernel's large LDS size has been enabled
+};
+bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info);
+hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t stream);
+
+// ---- nested-tile convolution-shaped contraction on matrix cores -----------
+struct ConvLaunch {
+  int variant = -1;
+  int64_t grid = 0;
+  mutable int lds_enabled_on = -1;
+};
+bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
+hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);
+
+// ---- max aggregation over a 2-d window ------------------------------------
+struct PoolLaunch {
+  int variant = -1;
+  int64_t grid = 0;
+};
+bool pool_select(const Pool2dShape& p, int dtype, PoolLaunch* l, stripe_block_info_t* info);
+hipError_t launch_pool(const Pool2dShape& p, const PoolLaunch& l, const void* in, void* out, hipStream_t stream);
+
+// ---- bandwidth yardstick ---------------------------------------------------
+hipError_t launch_copy(const void* src, void* dst, size_t n_bytes, hipStream_t stream);
+
+}  // namespace stripe

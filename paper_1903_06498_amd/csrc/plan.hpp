@@ -1,0 +1,118 @@
+// Host-side planner of the Stripe block executor: descriptor -> flat affine
+// form -> canonical form -> kernel family and launch parameters.
+// Integer arithmetic only; runs once per handle at create time.
+#pragma once
+
+#include <cstdint>
+#include <string>
+#include <vector>
+
+#include "../../include/stripe.h"
+
+namespace stripe {
+
+constexpr int kMaxFlatIdx = 24;  // indexes of all levels together
+constexpr int kMaxDims = 8;
+constexpr int kMaxRefs = 3;
+constexpr int kMaxLevels = 8;    // root + 7
+
+// sum_j c[j] * idx[j] + k over the flat index list
+struct Affine {
+  int64_t c[kMaxFlatIdx];
+  int64_t k;
+};
+
+struct FlatRef {
+  int dir = 0, dtype = 0, ndim = 0;
+  int64_t sizes[kMaxDims] = {};    // extents of the buffer (root level)
+  int64_t strides[kMaxDims] = {};
+  Affine coord[kMaxDims];          // absolute coordinate of the leaf access, per dimension
+  Affine addr;                     // element address from the buffer origin
+  int64_t elements = 0;            // product of sizes
+};
+
+// 0 <= rel < size must hold at every executed point (a leaf access inside an enclosing view)
+struct RangeCheck {
+  Affine rel;
+  int64_t size;
+  int ref, dim, level;
+};
+
+struct FlatBlock {
+  int n_idx = 0;
+  int64_t range[kMaxFlatIdx] = {};
+  int level_of[kMaxFlatIdx] = {};   // nesting level that declared the index (1-based; 0 after merging)
+  std::vector<Affine> cons;         // each >= 0
+  int n_refs = 0;
+  FlatRef ref[kMaxRefs];
+  std::vector<RangeCheck> checks;   // buffer bounds and view containment
+  int agg = STRIPE_AGG_ASSIGN;      // the nest's one aggregation (ASSIGN if every level says assign)
+  int level_agg[kMaxLevels] = {};   // output aggregation declared per level
+  int n_levels = 0;
+  int intrinsic = STRIPE_INTR_MUL;
+  bool int_mode = false;
+  bool empty = false;               // some range is 0 or the constraints exclude every point
+};
+
+struct GemmShape {       // C[m,n] (+)= A[m,k] * B[k,n]
+  int64_t M, N, K;
+  int64_t a_m, a_k, b_k, b_n, c_m, c_n;   // element strides
+  int64_t a_base, b_base, c_base;
+};
+
+struct Conv2dShape {     // O[n,y,x,k] (+)= I[n, s*y+i-p, s*x+j-q, c] * F[i,j,k,c]  (any strides)
+  int64_t N, Ho, Wo, Co, R, S, Ci, H, W;
+  int64_t stride_y, stride_x, pad_y, pad_x;
+  int64_t i_n, i_y, i_x, i_c;             // input element strides
+  int64_t f_r, f_s, f_k, f_c;             // filter element strides
+  int64_t o_n, o_y, o_x, o_k;             // output element strides
+  int64_t i_base, f_base, o_base;
+};
+
+struct Pool2dShape {     // O[n,y,x,c] = agg over in-bounds taps of I[n, s*y+i-p, s*x+j-q, c]
+  int64_t N, Ho, Wo, C, R, S, H, W;
+  int64_t stride_y, stride_x, pad_y, pad_x;
+  int64_t i_n, i_y, i_x, i_c, o_n, o_y, o_x, o_c;
+  int64_t i_base, o_base;
+};
+
+// Parameters of the generic affine-index kernel (passed by value as kernel argument).
+constexpr int kGenIdx = 8;
+constexpr int kGenCons = 8;
+struct GenericParams {
+  int32_t n_out, n_red, lanes, pad_;
+  int32_t out_range[kGenIdx], red_range[kGenIdx];
+  int64_t a_out[kGenIdx], b_out[kGenIdx], o_out[kGenIdx];
+  int64_t a_red[kGenIdx], b_red[kGenIdx];
+  int64_t a_base, b_base, o_base;
+  int32_t cons_out[kGenCons][kGenIdx], cons_red[kGenCons][kGenIdx];
+  int64_t cons_const[kGenCons];
+  int64_t n_outputs;
+  uint32_t red_total, inner_range;
+};
+
+struct Plan {
+  FlatBlock flat;                  // canonical form
+  stripe_block_info_t info = {};
+  bool noop = false;               // empty iteration space: run() launches nothing
+  GenericParams gen = {};
+  GemmShape gemm = {};
+  Conv2dShape conv = {};
+  Pool2dShape pool = {};
+  int in_dtype = 0;
+};
+
+// Each returns STRIPE_OK or an error with `err` filled.
+stripe_status_t flatten(const stripe_block_desc_t* root, FlatBlock* out, std::string* err);
+stripe_status_t prove_checks(const FlatBlock& fb, std::string* err);
+stripe_status_t check_assign_levels(const FlatBlock& fb, std::string* err);
+void canonicalize(FlatBlock* fb);
+stripe_status_t make_plan(const FlatBlock& canonical, stripe_path_t forced, Plan* plan, std::string* err);
+
+bool match_gemm(const FlatBlock& fb, GemmShape* g);
+bool match_conv2d(const FlatBlock& fb, Conv2dShape* c);
+bool match_pool2d(const FlatBlock& fb, Pool2dShape* p);
+
+int64_t count_points(const FlatBlock& fb, int64_t enumeration_cap);
+
+}  // namespace stripe

@@ -1,0 +1,192 @@
+// Max aggregation over a 2-d window of one input (gfx950), HBM-bound.
+//
+// Block shape (paper Section 2.1 "the max of a maxpool"; Section 3.2 for the
+// constraints):  O[n,y,x,c] = max over taps (i,j) with
+//   0 <= s*y + i - p < H  and  0 <= s*x + j - q < W   of  I[n, s*y+i-p, s*x+j-q, c].
+// Out-of-range taps are not part of the iteration space: they are skipped,
+// never read and never replaced by a padding value.
+//
+// Mapping: channels are contiguous, so a lane owns 4 channels (one 16-byte
+// load) of one output column; 16 lanes cover the 256 bytes of a 64-channel
+// pixel.  A workgroup of 128 lanes owns 128 consecutive (column, channel-quad)
+// items and walks TY output rows downwards, keeping the per-row maxima of
+// the R - stride input rows two neighbouring windows share in registers, so a
+// strip reads each of its input rows once.  Rows are split interior/boundary
+// only through predicates on whole rows and whole columns (Section 2.3,
+// "Separating Interior and Boundary Tiles"): the tap loops carry no per-tap
+// constraint arithmetic.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace stripe {
+namespace {
+
+struct PoolParams {
+  int32_t N, H, W, Ho, Wo, C4;       // C4 = channels / 4
+  int32_t pad_y, pad_x;
+  int32_t items;                      // Wo * C4
+  int32_t blocks_per_row, y_strips;
+  int64_t i_n, i_y, i_x, o_n, o_y, o_x;  // element strides (channel stride is 1)
+  int64_t i_base, o_base;
+};
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x4 max4(f32x4 a, f32x4 b) {
+  f32x4 r;
+  r.x = b.x > a.x ? b.x : a.x;
+  r.y = b.y > a.y ? b.y : a.y;
+  r.z = b.z > a.z ? b.z : a.z;
+  r.w = b.w > a.w ? b.w : a.w;
+  return r;
+}
+
+// Workgroups that share input rows should share an L2: consecutive hardware
+// workgroup ids go round-robin over the 8 XCDs, so give every XCD one
+// contiguous range of logical ids.
+__device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned grid) {
+  if (grid % 8u) return b;
+  return (b % 8u) * (grid / 8u) + b / 8u;
+}
+
+template <int R, int S, int ST, int TY, bool NT>
+__global__ __launch_bounds__(128) void pool_max_f32_kernel(const PoolParams p, const float* __restrict__ in,
+                                                          float* __restrict__ out) {
+  constexpr int CARRY = R > ST ? R - ST : 0;  // input rows two consecutive windows share
+  const unsigned b = xcd_contiguous(blockIdx.x, gridDim.x);
+  const int bx = b % p.blocks_per_row;
+  const int rest = b / p.blocks_per_row;
+  const int ys = rest % p.y_strips;
+  const int n = rest / p.y_strips;
+  const int item = bx * 128 + threadIdx.x;
+  if (item >= p.items) return;
+  const int c4 = item % p.C4;
+  const int xo = item / p.C4;
+
+  const float* inb = in + p.i_base + (int64_t)n * p.i_n + c4 * 4;
+  float* outb = out + p.o_base + (int64_t)n * p.o_n + (int64_t)xo * p.o_x + c4 * 4;
+
+  const int x0 = xo * ST - p.pad_x;
+  bool xv[S];
+  int64_t xoff[S];
+#pragma unroll
+  for (int j = 0; j < S; ++j) {
+    const int xc = x0 + j;
+    xv[j] = xc >= 0 && xc < p.W;
+    xoff[j] = (int64_t)xc * p.i_x;
+  }
+  const float ninf = -__builtin_huge_valf();
+  const f32x4 lowest = {ninf, ninf, ninf, ninf};
+
+  auto row_max = [&](int y) -> f32x4 {
+    f32x4 m = lowest;
+    if (y >= 0 && y < p.H) {
+      const float* rp = inb + (int64_t)y * p.i_y;
+#pragma unroll
+      for (int j = 0; j < S; ++j)
+        if (xv[j]) {
+          const f32x4 v = NT ? __builtin_nontemporal_load((const f32x4*)(rp + xoff[j]))
+                              : *(const f32x4*)(rp + xoff[j]);
+          m = max4(m, v);
+        }
+    }
+    return m;
+  };
+
+  const int yo0 = ys * TY;
+  f32x4 hm[R];
+#pragma unroll
+  for (int i = 0; i < CARRY; ++i) hm[i] = row_max(yo0 * ST - p.pad_y + i);
+#pragma unroll
+  for (int ty = 0; ty < TY; ++ty) {
+    const int yo = yo0 + ty;
+    const int ybase = yo * ST - p.pad_y;
+    const bool live = yo < p.Ho;
+#pragma unroll
+    for (int i = CARRY; i < R; ++i) hm[i] = live ? row_max(ybase + i) : lowest;
+    f32x4 m = hm[0];
+#pragma unroll
+    for (int i = 1; i < R; ++i) m = max4(m, hm[i]);
+    if (live) {
+      f32x4* dst = (f32x4*)(outb + (int64_t)yo * p.o_y);
+      if (NT) __builtin_nontemporal_store(m, dst);
+      else *dst = m;
+    }
+#pragma unroll
+    for (int i = 0; i < CARRY; ++i) hm[i] = hm[i + ST];
+  }
+}
+
+PoolParams make_params(const Pool2dShape& s, int ty) {
+  PoolParams p;
+  p.N = (int)s.N; p.H = (int)s.H; p.W = (int)s.W; p.Ho = (int)s.Ho; p.Wo = (int)s.Wo; p.C4 = (int)(s.C / 4);
+  p.pad_y = (int)s.pad_y; p.pad_x = (int)s.pad_x;
+  p.items = p.Wo * p.C4;
+  p.blocks_per_row = (p.items + 127) / 128;
+  p.y_strips = (p.Ho + ty - 1) / ty;
+  p.i_n = s.i_n; p.i_y = s.i_y; p.i_x = s.i_x; p.o_n = s.o_n; p.o_y = s.o_y; p.o_x = s.o_x;
+  p.i_base = s.i_base; p.o_base = s.o_base;
+  return p;
+}
+
+constexpr int kTyChoices[] = {2, 4, 7, 8, 14};
+
+template <int TY, bool NT>
+hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st) {
+  hipLaunchKernelGGL((pool_max_f32_kernel<3, 3, 2, TY, NT>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+// variant = index into kTyChoices * 2 + nontemporal flag
+bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_info_t* info) {
+  if (dtype != STRIPE_F32) return false;
+  if (s.R != 3 || s.S != 3 || s.stride_y != 2 || s.stride_x != 2) return false;
+  if (s.i_c != 1 || s.o_c != 1 || s.C % 4) return false;
+  // every window must hold at least one in-range tap, so every output is written
+  if (s.pad_y >= s.R || s.pad_x >= s.S) return false;
+  if ((s.Ho - 1) * s.stride_y - s.pad_y > s.H - 1 || (s.Wo - 1) * s.stride_x - s.pad_x > s.W - 1) return false;
+  // 16-byte loads and stores
+  for (int64_t v : {s.i_n, s.i_y, s.i_x, s.o_n, s.o_y, s.o_x, s.i_base, s.o_base})
+    if (v % 4) return false;
+  if (s.N > 0x7fffffff / 4 || s.H > 0x3fffffff || s.W > 0x3fffffff || s.Wo * (s.C / 4) > 0x3fffffff) return false;
+  int ty_idx = 2;  // 7 rows per strip
+  const int want = tune_int("pool_ty", 0);
+  for (int i = 0; i < (int)(sizeof kTyChoices / sizeof kTyChoices[0]); ++i)
+    if (kTyChoices[i] == want) ty_idx = i;
+  const int nt = tune_int("pool_nt", 1) ? 1 : 0;
+  const int ty = kTyChoices[ty_idx];
+  const PoolParams p = make_params(s, ty);
+  const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
+  if (grid > 0x7fffffffLL) return false;
+  l->variant = ty_idx * 2 + nt;
+  l->grid = grid;
+  info->path = STRIPE_PATH_POOL;
+  info->tile_m = ty;          // output rows per strip
+  info->tile_n = 128;         // (column, channel-quad) items per workgroup
+  info->tile_k = 0;
+  info->frag_m = info->frag_n = info->frag_k = 0;
+  info->lds_bytes = 0;
+  info->workgroup_size = 128;
+  info->grid = grid;
+  snprintf(info->kernel, sizeof info->kernel, "pool_max_f32_3x3s2_ty%d%s", ty, nt ? "_nt" : "");
+  return true;
+}
+
+hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in, void* out, hipStream_t st) {
+  if (((uintptr_t)in % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
+  const int ty_idx = l.variant / 2;
+  const bool nt = l.variant % 2;
+  const PoolParams p = make_params(s, kTyChoices[ty_idx]);
+  switch (ty_idx) {
+    case 0: return nt ? launch_ty<2, true>(p, l.grid, in, out, st) : launch_ty<2, false>(p, l.grid, in, out, st);
+    case 1: return nt ? launch_ty<4, true>(p, l.grid, in, out, st) : launch_ty<4, false>(p, l.grid, in, out, st);
+    case 2: return nt ? launch_ty<7, true>(p, l.grid, in, out, st) : launch_ty<7, false>(p, l.grid, in, out, st);
+    case 3: return nt ? launch_ty<8, true>(p, l.grid, in, out, st) : launch_ty<8, false>(p, l.grid, in, out, st);
+    default: return nt ? launch_ty<14, true>(p, l.grid, in, out, st) : launch_ty<14, false>(p, l.grid, in, out, st);
+  }
+}
+
+}  // namespace stripe

@@ -77,9 +77,12 @@ def evaluate(root, inputs, exact=lambda v: Fraction(v)):
     return out
 
 
-def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32", agg="add", intrinsic="mul"):
+def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32", agg="add", intrinsic="mul",
+                 injective_out=False, max_range=4):
     """A random tiny block (every range <= 4, small integer coefficients).
 
+    With injective_out every output dimension is moved by exactly one index
+    (the shape the GPU library accepts without atomics).
     Accesses are made in-bounds by measuring, per buffer dimension, the
     extreme coordinates over the executed points and sizing/offsetting the
     root buffer to contain them.  Views of intermediate levels are sized the
@@ -91,16 +94,36 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
     dirs = ["in"] * n_in + ["out"]
     dts = [dtype_in] * n_in + [dtype_out]
 
-    def rand_level(var_count):
-        return [[[rng.randint(-1, 2) for _ in range(var_count)] for _ in range(nd)] for nd in ndims]
-
-    lv_specs = []
     n_levels = 2 if nested else 1
-    parent_nv = 0
+    shapes = []
     for li in range(n_levels):
         n_idx = rng.randint(1, 3 if nested else 4)
-        ranges = [rng.randint(1, 4 if not nested else 3) for _ in range(n_idx)]
+        ranges = [rng.randint(1, max_range if not nested else max(2, max_range - 1)) for _ in range(n_idx)]
         n_passed = rng.randint(0, 2) if li > 0 else 0
+        shapes.append((n_idx, ranges, n_passed))
+
+    out_dim_of = {}   # (level, index) -> output dimension, when the output map is made injective
+    if injective_out:
+        cand = [(li, j) for li, (n_idx, _, _) in enumerate(shapes) for j in range(n_idx)]
+        rng.shuffle(cand)
+        chosen = cand[:rng.randint(1, min(3, len(cand)))]
+        for d, key in enumerate(chosen):
+            out_dim_of[key] = d
+        ndims[n_in] = len(chosen)
+
+    def rand_level(li, var_count):
+        acc = [[[rng.randint(-1, 2) for _ in range(var_count)] for _ in range(nd)] for nd in ndims]
+        if injective_out:
+            acc[n_in] = [[0] * var_count for _ in range(ndims[n_in])]
+            for (l2, j), d in out_dim_of.items():
+                if l2 == li:
+                    acc[n_in][d][j] = rng.choice([1, 1, 2, -1])
+        return acc
+
+    lv_specs = []
+    parent_nv = 0
+    for li in range(n_levels):
+        n_idx, ranges, n_passed = shapes[li]
         passed_coeff = [[rng.randint(-1, 2) for _ in range(parent_nv)] for _ in range(n_passed)]
         passed_const = [rng.randint(-1, 1) for _ in range(n_passed)]
         nv = n_idx + n_passed
@@ -108,7 +131,7 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
         cons_coeff = [[rng.randint(-1, 1) for _ in range(nv)] for _ in range(n_cons)]
         cons_const = [rng.randint(0, 3) for _ in range(n_cons)]
         lv_specs.append(dict(n_idx=n_idx, ranges=ranges, passed_coeff=passed_coeff, passed_const=passed_const,
-                             cons_coeff=cons_coeff, cons_const=cons_const, acc=rand_level(nv)))
+                             cons_coeff=cons_coeff, cons_const=cons_const, acc=rand_level(li, nv)))
         parent_nv = nv
 
     # Build with provisional sizes, measure extremes, then fix sizes and offsets.
@@ -177,7 +200,7 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
                 in_lo[r][d] = inner if in_lo[r][d] is None else min(in_lo[r][d], inner)
                 in_hi[r][d] = inner if in_hi[r][d] is None else max(in_hi[r][d], inner)
     if not any_point:
-        return random_block(rng, nested, dtype_in, dtype_out, agg, intrinsic)
+        return random_block(rng, nested, dtype_in, dtype_out, agg, intrinsic, injective_out, max_range)
     if nested:
         # The inner level's constant places its coordinate at the start of the
         # outer level's view; the outer level's constant places the total

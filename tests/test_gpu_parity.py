@@ -1,0 +1,241 @@
+"""GPU parity: the HIP library, called through its C ABI, against the CPU oracle
+on the same seeded inputs.  Tolerances are stated in tests/util.py.
+
+Small cases span several tiles plus ragged tails and are compared element by
+element; the benchmark-size cases run in the launch configuration bench.py
+times and are compared on oracle-computed slabs plus size-independent
+properties (identity operand, all-ones tap counts).
+"""
+import random
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import stripe_oracle as O
+from paper_1903_06498_amd import binding as B
+from paper_1903_06498_amd import workloads as W
+from tests import brute
+from tests.util import SENTINEL_F, SENTINEL_I, compare, parity, run_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def taps(y, s, p, R, H):
+    return sum(1 for i in range(R) if 0 <= s * y + i - p < H)
+
+
+# ------------------------------------------------------------------ generic path
+def test_tiny_conv_f32_config():
+    name = "tiny_conv_f32"
+    info, score = parity(W.config_block(name), W.config_inputs(name), what=name)
+    say(f"{name}: {info['kernel']} rel err {score:.2e}")
+    assert info["work_points"] == 270848
+
+
+@pytest.mark.parametrize("form", ["flat", "tiled"])
+def test_figure5_forms_int8(form):
+    blk = W.fig5_flat() if form == "flat" else W.fig5_tiled()
+    ins = [W.seeded_tensor((12, 16, 8), "i8", 0), W.seeded_tensor((3, 3, 16, 8), "i8", 1)]
+    info, _ = parity(blk, ins, what=f"fig5 {form}")
+    assert info["work_points"] == 200192 and info["n_idx"] == 6
+
+
+@pytest.mark.parametrize("seed", range(60))
+def test_random_tiny_blocks_generic(seed):
+    """Random small (nested) integer blocks, passed values, constraints, negative
+    coefficients: bit-exact, untouched elements kept; or rejected at create."""
+    rng = random.Random(1000 + seed)
+    agg = ["add", "max", "min"][seed % 3]
+    intrinsic = ["mul", "copy", "add"][(seed // 3) % 3]
+    blk = brute.random_block(rng, seed % 2 == 1, "i32", "i32", agg, intrinsic, injective_out=True, max_range=6)
+    nrng = np.random.default_rng(seed)
+    ins = [torch.from_numpy(nrng.integers(-3, 4, size=int(np.prod(r.sizes)), dtype=np.int32)) for r in blk.refs[:-1]]
+    try:
+        gpu = run_gpu(blk, ins, "generic")
+    except B.StripeError as e:
+        assert e.status in (3, 5), str(e)   # several writers through output indexes, or assign with a reduction
+        pytest.skip(f"rejected at create: {e}")
+    res = O.evaluate(blk, [W.to_numpy(t) for t in ins], out=np.full(W.output_extent(blk), SENTINEL_I, np.int64))
+    assert np.array_equal(gpu.astype(np.int64), res.out)
+
+
+@pytest.mark.parametrize("dtype,lanes_hint", [("f32", "conv"), ("bf16", "conv"), ("i8", "conv")])
+def test_generic_conv_shapes(dtype, lanes_hint):
+    """Ragged, asymmetric convolution on the generic kernel (wave-per-output mapping)."""
+    N, H, Wd, Ci, Co, R, S, s, p = 2, 19, 13, 24, 10, 3, 5, 2, 2
+    odt = "i32" if dtype == "i8" else "f32"
+    blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, s, p, dtype, odt)
+    ins = [W.seeded_tensor((N, H, Wd, Ci), dtype, 0), W.seeded_tensor((R, S, Co, Ci), dtype, 1)]
+    info, score = parity(blk, ins, "generic", what=f"generic conv {dtype}")
+    say(f"generic conv {dtype}: {info['kernel']} score {score:.2e}")
+
+
+def test_generic_filter_layout_k_innermost():
+    N, H, Wd, Ci, Co, R, S = 1, 9, 8, 5, 32, 3, 3
+    blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, 1, 1, "f32", "f32", filter_layout="RSCK")
+    ins = [W.seeded_tensor((N, H, Wd, Ci), "f32", 0), W.seeded_tensor((R, S, Ci, Co), "f32", 1)]
+    info, _ = parity(blk, ins, "generic", what="RSCK conv")
+    assert "lane_per_output" in info["kernel"]
+
+
+@pytest.mark.parametrize("M,N,K,dtype", [(70, 90, 130, "f32"), (65, 33, 257, "bf16"), (40, 50, 60, "i8"), (1, 1, 1, "f32")])
+def test_generic_matmul_ragged(M, N, K, dtype):
+    odt = "i32" if dtype == "i8" else "f32"
+    blk = W.matmul_block(M, N, K, dtype, odt)
+    ins = [W.seeded_tensor((M, K), dtype, 0), W.seeded_tensor((K, N), dtype, 1)]
+    parity(blk, ins, "generic", what=f"generic matmul {dtype}")
+
+
+def test_unwritten_elements_keep_their_contents():
+    bufs = [W.Buffer("A", "in", "i32", (70,)), W.Buffer("O", "out", "i32", (70,))]
+    blk = W.flat_block(bufs, dict(x=70, r=3), [(["x"], "assign"), (["x"], "add")],
+                       constraints=["x + r - 40 >= 0"], intrinsic="copy")
+    a = torch.arange(70, dtype=torch.int32)
+    gpu = run_gpu(blk, [a])
+    want = np.array([SENTINEL_I if x < 38 else x * sum(1 for r in range(3) if x + r >= 40) for x in range(70)])
+    assert np.array_equal(gpu.astype(np.int64), want)
+    res = O.evaluate(blk, [a.numpy()], out=np.full(70, SENTINEL_I, np.int64))
+    assert np.array_equal(res.out, want)
+
+
+def test_empty_block_launches_nothing():
+    blk = W.matmul_block(3, 0, 5, "f32", "f32")
+    blk.refs[1].sizes = [5, 1]
+    blk.refs[2].sizes = [3, 1]
+    gpu = run_gpu(blk, [torch.zeros(15), torch.zeros(5)])
+    assert np.all(gpu == np.float32(SENTINEL_F))
+
+
+# ------------------------------------------------------------------ pooling path
+@pytest.mark.parametrize("N,H,Wd,C", [(2, 30, 26, 8), (1, 7, 9, 4), (3, 33, 35, 64), (1, 112, 112, 64)])
+def test_pool_path_small(N, H, Wd, C):
+    blk = W.maxpool_block(N, H, Wd, C, 3, 2, 1)
+    x = W.seeded_tensor((N, H, Wd, C), "f32", 0)
+    info, _ = parity(blk, [x], what=f"pool {N}x{H}x{Wd}x{C}")
+    assert info["path_name"] == "pool", info
+    ref = torch.nn.functional.max_pool2d(x.permute(0, 3, 1, 2), 3, 2, 1).permute(0, 2, 3, 1).contiguous()
+    gpu = run_gpu(blk, [x])
+    assert np.array_equal(gpu.reshape(ref.shape), ref.numpy())
+
+
+@pytest.mark.parametrize("ty", [2, 4, 8, 14])
+def test_pool_strip_heights(ty, monkeypatch):
+    monkeypatch.setenv("STRIPE_TUNE", f"pool_ty={ty},pool_nt=0")
+    blk = W.maxpool_block(2, 45, 27, 12, 3, 2, 1)
+    x = W.seeded_tensor((2, 45, 27, 12), "f32", 3)
+    info, _ = parity(blk, [x], what=f"pool ty={ty}")
+    assert f"ty{ty}" in info["kernel"] and not info["kernel"].endswith("_nt")
+
+
+def test_pool_all_negative_and_generic_agree():
+    blk = W.maxpool_block(2, 21, 17, 8, 3, 2, 1)
+    x = -torch.abs(W.seeded_tensor((2, 21, 17, 8), "f32", 1)) - 1
+    a = run_gpu(blk, [x], "pool")
+    b = run_gpu(blk, [x], "generic")
+    assert np.array_equal(a, b) and np.all(a < 0)
+
+
+def test_maxpool_config_full_size():
+    name = "maxpool_f32"
+    blk, ins = W.config_block(name), W.config_inputs(name)
+    info, _ = parity(blk, ins, threads=16, what=name)
+    say(f"{name}: {info['kernel']} grid {info['grid']}")
+    assert info["path_name"] == "pool" and info["work_points"] == 57116672
+
+
+# ------------------------------------------------------------------ dense contraction path
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 768, 320), (1024, 512, 128)])
+def test_gemm_mfma_small(M, N, K):
+    blk = W.matmul_block(M, N, K, "bf16", "f32")
+    ins = [W.seeded_tensor((M, K), "bf16", 0), W.seeded_tensor((K, N), "bf16", 1)]
+    info, score = parity(blk, ins, threads=8, what=f"gemm {M}x{N}x{K}")
+    say(f"gemm {M}x{N}x{K}: {info['kernel']} err/bound {score:.3f}")
+    assert info["path_name"] == "mfma_gemm"
+
+
+@pytest.mark.parametrize("swz", [0, 1])
+def test_gemm_mfma_position_sensitive(swz, monkeypatch):
+    """A[m,k] = small integers depending on (m,k), B = shifted identity: every
+    output equals one specific input element, exactly, so any mix-up of rows,
+    columns, fragments or tiles shows."""
+    monkeypatch.setenv("STRIPE_TUNE", f"gemm_swz={swz}")
+    M = N = 512
+    K = 512
+    a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.bfloat16)
+    shift = 37
+    b = torch.zeros((K, N), dtype=torch.bfloat16)
+    b[(torch.arange(N) + shift) % K, torch.arange(N)] = 1.0
+    blk = W.matmul_block(M, N, K, "bf16", "f32")
+    gpu, sb = run_gpu(blk, [a, b], return_block=True)
+    assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"].endswith(f"swz{swz}")
+    want = a.float()[:, (torch.arange(N) + shift) % K].numpy()
+    assert np.array_equal(gpu.reshape(M, N), want)
+
+
+def test_gemm_config_full_size():
+    """4096^3 in the benchmark's launch configuration: oracle slabs + identity property."""
+    name = "gemm_bf16_4096"
+    blk, ins = W.config_block(name), W.config_inputs(name)
+    gpu, sb = run_gpu(blk, ins, return_block=True)
+    say(f"{name}: {sb.info['kernel']} grid {sb.info['grid']}")
+    assert sb.info["path_name"] == "mfma_gemm"
+    np_ins = [W.to_numpy(t).ravel() for t in ins]
+    # rows 0, 1337, 4095 (all n) and columns 255..257 (all m), every k
+    for lo, hi in [([0, 0, 0], [1, 4096, 4096]), ([1337, 0, 0], [1338, 4096, 4096]),
+                   ([4095, 0, 0], [4096, 4096, 4096]), ([0, 255, 0], [4096, 258, 4096])]:
+        res = O.evaluate(blk, np_ins, window=(lo, hi), threads=16, split_index=1 if hi[0] - lo[0] == 1 else 0)
+        score = compare(blk, ins, gpu, res, what=f"{name} window {lo}")
+        say(f"  window {lo}..{hi}: err/bound {score:.3f}")
+    # identity operand passes A through bit-exactly, at full size
+    eye = torch.eye(4096, dtype=torch.bfloat16)
+    gpu = run_gpu(blk, [ins[0], eye])
+    assert np.array_equal(gpu.reshape(4096, 4096), ins[0].float().numpy())
+
+
+# ------------------------------------------------------------------ convolution configs at full size
+def test_resnet_conv_config_full_size():
+    name = "resnet_conv_bf16"
+    blk, ins = W.config_block(name), W.config_inputs(name)
+    gpu, sb = run_gpu(blk, ins, return_block=True)
+    say(f"{name}: {sb.info['kernel']} grid {sb.info['grid']}")
+    assert sb.info["work_points"] == 3611820032
+    np_ins = [W.to_numpy(t).ravel() for t in ins]
+    full = [32, 56, 56, 3, 3, 64, 64]
+    for lo, hi in [([0, 0, 0, 0, 0, 0, 0], [1] + full[1:]), ([31, 49, 0, 0, 0, 0, 0], [32] + full[1:]),
+                   ([13, 0, 50, 0, 0, 0, 0], [14, 56, 56, 3, 3, 64, 64])]:
+        res = O.evaluate(blk, np_ins, window=(lo, hi), threads=16, split_index=1)
+        score = compare(blk, ins, gpu, res, what=f"{name} window {lo}")
+        say(f"  window {lo}: err/bound {score:.3f}")
+    # all-ones: O = Ci * cy * cx exactly (in-bounds tap count), every element
+    ones = [torch.ones_like(ins[0]), torch.ones_like(ins[1])]
+    gpu = run_gpu(blk, ones).reshape(32, 56, 56, 64)
+    cy = np.array([taps(y, 1, 1, 3, 56) for y in range(56)])
+    want = 64.0 * cy[:, None] * cy[None, :]
+    assert np.array_equal(gpu, np.broadcast_to(want[None, :, :, None], gpu.shape))
+
+
+def test_int8_conv_config_full_size():
+    name = "conv7x7_s2_int8"
+    blk, ins = W.config_block(name), W.config_inputs(name)
+    gpu, sb = run_gpu(blk, ins, return_block=True)
+    say(f"{name}: {sb.info['kernel']} grid {sb.info['grid']}")
+    assert sb.info["work_points"] == 1859432448
+    np_ins = [W.to_numpy(t).ravel() for t in ins]
+    full = [16, 112, 112, 7, 7, 3, 64]
+    for lo, hi in [([15, 0, 0, 0, 0, 0, 0], [16] + full[1:]), ([0, 0, 0, 0, 0, 0, 0], [1, 12] + full[2:]),
+                   ([7, 100, 0, 0, 0, 0, 0], [8, 112] + full[2:])]:
+        res = O.evaluate(blk, np_ins, window=(lo, hi), threads=16, split_index=1)
+        compare(blk, ins, gpu, res, what=f"{name} window {lo}")
+    # all -128: O = 16384 * 3 * cy * cx exactly
+    lowest = [torch.full_like(ins[0], -128), torch.full_like(ins[1], -128)]
+    gpu = run_gpu(blk, lowest).reshape(16, 112, 112, 64)
+    cy = np.array([taps(y, 2, 3, 7, 224) for y in range(112)])
+    want = 16384 * 3 * cy[:, None] * cy[None, :]
+    assert np.array_equal(gpu, np.broadcast_to(want[None, :, :, None], gpu.shape))

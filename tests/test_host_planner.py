@@ -1,0 +1,133 @@
+"""Host-side checks of the HIP library that need no GPU: it loads, exports every
+symbol include/stripe.h declares, and its planner (flatten, bounds proof,
+canonical form, kernel-family choice) behaves as documented.  No kernel runs."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1903_06498_amd import binding as B
+from paper_1903_06498_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "stripe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(stripe_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert "stripe_block_create" in names and "stripe_block_run" in names
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in stripe.h but not exported"
+    assert set(names) == set(B.EXPORTS)
+
+
+def test_benchmark_configs_plan_with_the_documented_work_figures():
+    want = {"tiny_conv_f32": (294912, 270848, 29184), "gemm_bf16_4096": (4096 ** 3, 4096 ** 3, 134217728),
+            "resnet_conv_bf16": (3699376128, 3611820032, 38608896),
+            "conv7x7_s2_int8": (1888223232, 1859432448, 53798080), "maxpool_f32": (57802752, 57116672, 128450560)}
+    for name, (hull, work, nbytes) in want.items():
+        blk = B.StripeBlock(W.config_block(name))
+        assert (blk.info["hull_points"], blk.info["work_points"], blk.info["algorithmic_bytes"]) == (hull, work, nbytes), name
+        blk.close()
+    assert B.StripeBlock(W.config_block("gemm_bf16_4096")).info["path_name"] == "mfma_gemm"
+    assert B.StripeBlock(W.config_block("maxpool_f32")).info["path_name"] == "pool"
+
+
+def test_tiled_and_flat_forms_of_the_worked_example_plan_alike():
+    a = B.StripeBlock(W.fig5_flat()).info
+    b = B.StripeBlock(W.fig5_tiled()).info
+    for key in ("n_idx", "n_out_idx", "n_red_idx", "hull_points", "work_points", "output_elements", "kernel", "grid"):
+        assert a[key] == b[key], key
+    assert a["work_points"] == 200192 and a["hull_points"] == 12 * 16 * 9 * 8 * 16
+
+
+def test_non_dividing_tile_with_overflow_constraint_merges_back():
+    """x split as 5*xo + xi over a range of 12 (quotient rounded up to 3) with the
+    overflow removed by 11 - 5*xo - xi >= 0 plans like the un-tiled block."""
+    bufs = [W.Buffer("A", "in", "f32", (12, 7)), W.Buffer("B", "in", "f32", (7,)), W.Buffer("O", "out", "f32", (12,))]
+    flat = W.flat_block(bufs, dict(x=12, k=7), [(["x", "k"], "assign"), (["k"], "assign"), (["x"], "add")])
+    outer = W.make_level(dict(xo=3), [(["5*xo", "0"], "assign", (5, 7)), (["0"], "assign", (7,)),
+                                      (["5*xo"], "add", (5,))], buffers=bufs)
+    inner = W.make_level(dict(xi=5, k=7), [(["xi", "k"], "assign"), (["k"], "assign"), (["xi"], "add")],
+                         buffers=bufs, passed=dict(xb="5*xo"), parent=outer, constraints=["11 - xb - xi >= 0"],
+                         intrinsic="mul")
+    outer.child = inner
+    tiled = W.make_root(bufs, outer)
+    a, b = B.StripeBlock(flat).info, B.StripeBlock(tiled).info
+    assert (a["n_idx"], a["hull_points"], a["work_points"]) == (b["n_idx"], b["hull_points"], b["work_points"]) == (2, 84, 84)
+
+
+def status_of(block, path="auto"):
+    try:
+        B.StripeBlock(block, path).close()
+        return 0
+    except B.StripeError as e:
+        assert e.detail
+        return e.status
+
+
+def test_out_of_bounds_blocks_are_rejected():
+    blk = W.conv2d_block(1, 6, 6, 2, 2, 3, 3, 1, 1, "f32", "f32")
+    assert status_of(blk) == 0
+    blk.child.cons_coeff, blk.child.cons_const = blk.child.cons_coeff[1:], blk.child.cons_const[1:]
+    assert status_of(blk) == 4
+    big = W.conv2d_block(64, 300, 300, 16, 16, 3, 3, 1, 1, "f32", "f32")   # too large to enumerate: proven symbolically
+    assert status_of(big) == 0
+    big.child.cons_coeff, big.child.cons_const = big.child.cons_coeff[:3], big.child.cons_const[:3]
+    assert status_of(big) == 4
+    tiled = W.fig5_tiled()
+    tiled.child.refs[0].sizes = [4, 6, 8]      # the halo view is 5 x 6 x 8
+    assert status_of(tiled) == 4
+
+
+def test_assign_and_multi_writer_rules():
+    bufs = [W.Buffer("A", "in", "f32", (4, 3)), W.Buffer("O", "out", "f32", (4,))]
+    ok = W.flat_block(bufs, dict(a=4, r=1), [(["a", "r"], "assign"), (["a"], "assign")], intrinsic="copy")
+    bad = W.flat_block(bufs, dict(a=4, r=3), [(["a", "r"], "assign"), (["a"], "assign")], intrinsic="copy")
+    assert status_of(ok) == 0 and status_of(bad) == 5
+    tiled = W.fig5_tiled()
+    tiled.child.refs[-1].agg = "assign"          # disjoint output tiles: a legal claim
+    assert status_of(tiled) == 0
+    bufs2 = [W.Buffer("A", "in", "f32", (6,)), W.Buffer("B", "in", "f32", (3,)), W.Buffer("O", "out", "f32", (8,))]
+    scatter = W.flat_block(bufs2, dict(x=6, i=3), [(["x"], "assign"), (["i"], "assign"), (["x + i"], "add")])
+    assert status_of(scatter) == 3               # O[x+i]: needs atomics, not built
+
+
+def test_malformed_descriptors():
+    blk = W.matmul_block(4, 4, 4, "f32", "f32")
+    blk.refs[0].dtype = blk.child.refs[0].dtype = "i8"
+    assert status_of(blk) == 2                   # integer input, float output
+    blk = W.matmul_block(4, 4, 4, "f32", "f32")
+    blk.child.refs[1].strides = [1, 4]
+    assert status_of(blk) == 2                   # a view must keep its parent's strides
+    blk = W.matmul_block(4, 4, 4, "f32", "f32")
+    blk.child.intrinsic = "copy"
+    assert status_of(blk) == 2
+    blk = W.matmul_block(4, 4, 4, "f32", "f32")
+    blk.child.ranges[0] = -1
+    assert status_of(blk) == 2
+    h = ctypes.c_void_p()
+    assert B.lib.stripe_block_create(None, ctypes.byref(h)) == 1
+    assert B.stripe_last_error() != ""
+    assert B.stripe_status_string(4) == "access may leave its buffer or view"
+
+
+def test_forcing_a_family_the_block_does_not_have_is_refused():
+    assert status_of(W.config_block("maxpool_f32"), "mfma_gemm") == 3
+    assert status_of(W.config_block("gemm_bf16_4096"), "pool") == 3
+    assert status_of(W.matmul_block(100, 100, 100, "bf16", "f32"), "mfma_gemm") == 3   # not tile-divisible
+    assert B.StripeBlock(W.matmul_block(100, 100, 100, "bf16", "f32")).info["path_name"] == "generic"
+
+
+def test_tune_override_selects_variants(monkeypatch):
+    monkeypatch.setenv("STRIPE_TUNE", "pool_ty=4,pool_nt=0")
+    assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty4"
+    monkeypatch.delenv("STRIPE_TUNE")
+    assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty7_nt"

@@ -1,0 +1,104 @@
+"""Helpers shared by the GPU parity tests: upload, run through the C ABI, compare.
+
+Tolerances (stated once, used everywhere):
+  integer blocks      bit-exact
+  max / min blocks    exact equality of values (order-independent operation)
+  fp32-input blocks   max |g - r| / max(|r|, rms(r)) <= 1e-4 against the fp64 oracle
+  bf16-input blocks   |g - r| <= 4e-3 * sqrt(K) * max|a| * max|b|, K = reduction points per output
+Elements no iteration writes must keep the sentinel the output was filled with.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+import torch
+
+from oracle import stripe_oracle as O
+from paper_1903_06498_amd import binding as B
+from paper_1903_06498_amd import workloads as W
+
+SENTINEL_I = -123456789
+SENTINEL_F = -9.87654321e30
+
+_TORCH = {"i8": torch.int8, "i32": torch.int32, "bf16": torch.bfloat16, "f32": torch.float32}
+
+
+def run_gpu(root, inputs, path="auto", return_block=False):
+    """inputs: torch CPU tensors in the declared element types.  Returns the flat output image (numpy)."""
+    dev = torch.device("cuda:0")
+    blk = B.StripeBlock(root, path)
+    ext = W.output_extent(root)
+    odt = root.refs[-1].dtype
+    out = torch.full((ext,), SENTINEL_I if odt == "i32" else SENTINEL_F, dtype=_TORCH[odt], device=dev)
+    dins = []
+    for r, t in zip(root.refs[:-1], inputs):
+        assert t.dtype == _TORCH[r.dtype], (r.name, t.dtype)
+        dins.append(t.contiguous().to(dev))
+    blk.run(dins, out)
+    torch.cuda.synchronize()
+    res = out.cpu().numpy()
+    if return_block:
+        return res, blk
+    blk.close()
+    return res
+
+
+def reduction_points(root) -> int:
+    """Hull reduction points per output element: product of ranges of indexes the output does not depend on."""
+    k = 1
+    for lv in root.levels()[1:]:
+        o = lv.refs[-1]
+        for j, rng in enumerate(lv.ranges):
+            if all(row[j] == 0 for row in o.access_coeff):
+                k *= rng
+    return k
+
+
+def compare(root, inputs, gpu_out, oracle_res, what=""):
+    """Element-by-element comparison on the touched set; sentinel check on the rest."""
+    touched = oracle_res.touched.astype(bool)
+    odt = root.refs[-1].dtype
+    agg = {lv.refs[-1].agg for lv in root.levels()} - {"assign"}
+    agg = agg.pop() if agg else "assign"
+    g, r = gpu_out[touched], oracle_res.out[touched]
+    if odt == "i32":
+        assert np.array_equal(g.astype(np.int64), r), f"{what}: integer block not bit-exact"
+        return 0.0
+    in_dt = root.refs[0].dtype
+    if agg in ("max", "min") and root.levels()[-1].intrinsic == "copy":
+        assert np.array_equal(g.astype(np.float64), r), f"{what}: max/min block not exact"
+        return 0.0
+    err = np.abs(g.astype(np.float64) - r)
+    if in_dt == "bf16":
+        K = reduction_points(root)
+        amax = max(float(np.max(np.abs(t.float().numpy()))) for t in inputs[:1])
+        bmax = float(np.max(np.abs(inputs[1].float().numpy()))) if len(inputs) > 1 else 1.0
+        bound = 4e-3 * math.sqrt(K) * amax * bmax
+        assert err.max() <= bound, f"{what}: bf16 error {err.max():.3e} > bound {bound:.3e}"
+        return float(err.max() / bound)
+    rms = math.sqrt(float(np.mean(r * r))) if r.size else 1.0
+    rel = err / np.maximum(np.abs(r), rms if rms > 0 else 1.0)
+    assert rel.max() <= 1e-4, f"{what}: fp32 relative error {rel.max():.3e} > 1e-4"
+    return float(rel.max())
+
+
+def check_untouched(gpu_out, oracle_res, odt):
+    untouched = ~oracle_res.touched.astype(bool)
+    if untouched.any():
+        want = SENTINEL_I if odt == "i32" else np.float32(SENTINEL_F)
+        assert np.all(gpu_out[untouched] == want), "an element no iteration writes was modified"
+
+
+def parity(root, inputs, path="auto", window=None, threads=8, split_index=0, what=""):
+    """Run GPU and oracle on the same inputs and compare.  With a window the
+    oracle computes only a slab of outputs and only that slab is compared."""
+    gpu, blk = run_gpu(root, inputs, path, return_block=True)
+    info = dict(blk.info)
+    blk.close()
+    res = O.evaluate(root, [W.to_numpy(t).ravel() for t in inputs], window=window, threads=threads,
+                     split_index=split_index)
+    score = compare(root, inputs, gpu, res, what)
+    if window is None:
+        check_untouched(gpu, res, root.refs[-1].dtype)
+    return info, score
