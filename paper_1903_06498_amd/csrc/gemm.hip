@@ -39,9 +39,13 @@ constexpr int B_STAGE = BN * ROW_BYTES;            // 32 KB
 constexpr int STAGE = A_STAGE + B_STAGE;           // 64 KB, two stages = 128 KB of the 160 KB LDS
 constexpr int THREADS = 512;
 
-// Which 16-byte slot of its 128-byte row chunk c of row r lives in.
+// Which 16-byte slot of its 128-byte row chunk c of row r lives in.  LDS has 64
+// four-byte banks, i.e. two 128-byte rows per bank sweep; a fragment read puts
+// 16 consecutive rows of one chunk into one sweep, the B transposition writes
+// rows 8 apart.  Keying the swizzle on (row>>1) and (row>>4) separates both.
 template <int SWZ>
 __device__ __forceinline__ int slot(int row, int c) {
+  if (SWZ == 2) return c ^ (((row >> 1) ^ (row >> 4)) & 7);
   return c ^ ((row >> SWZ) & 7);
 }
 
@@ -61,7 +65,7 @@ __device__ __forceinline__ void tile_of(unsigned b, unsigned grid, int tiles_m, 
 }
 
 template <int SWZ>
-__global__ __launch_bounds__(THREADS, 1) void gemm_bf16_kernel(const GemmParams p, const uint16_t* __restrict__ A,
+__global__ __launch_bounds__(THREADS, 1) void gemm_bf16_w8_kernel(const GemmParams p, const uint16_t* __restrict__ A,
                                                                const uint16_t* __restrict__ B, float* __restrict__ C) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
@@ -73,8 +77,10 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_kernel(const GemmParams 
   // A tile: 256 rows x 8 chunks of 16 B; lane t takes chunk t&7 of rows (t>>3) + 64*i.
   const int a_c = t & 7, a_r0 = t >> 3;
   const uint16_t* a_g = A + p.a_base + ((int64_t)tm * BM + a_r0) * p.a_m + a_c * 8;
-  // B tile: 64 k x 256 n; lane t takes the 4(k) x 8(n) patch at k = 4*(t>>5), n = 8*(t&31).
-  const int b_nb = t & 31, b_kq = t >> 5;
+  // B tile: 64 k x 256 n; a lane takes a 4(k) x 8(n) patch.  Within a wavefront 8 lanes
+  // step through k quads and 8 through n blocks: global reads are 128-byte row segments
+  // and the transposed LDS writes of one instruction spread over all banks.
+  const int b_kq = (lane & 7) + 8 * (wave & 1), b_nb = (lane >> 3) + 8 * (wave >> 1);
   const uint16_t* b_g = B + p.b_base + (int64_t)(b_kq * 4) * p.b_k + (int64_t)tn * BN + b_nb * 8;
 
   u32x4 ra[4], rb[4];
@@ -168,6 +174,418 @@ __global__ __launch_bounds__(THREADS, 1) void gemm_bf16_kernel(const GemmParams 
       }
 }
 
+// ---------------------------------------------------------------------------
+// Four-wavefront variant: 2 x 2 wavefronts of 128 x 128 (4 x 4 fragments, 256
+// accumulator registers, one wavefront per SIMD).  Per 16 matrix instructions a
+// wavefront reads 8 fragments from LDS instead of 12, which is what keeps the
+// LDS pipe below saturation.  With a single wavefront per SIMD nothing hides a
+// stall, so the K loop is software-pipelined by hand:
+//   * global -> register loads run two K tiles ahead (two staging sets),
+//   * the register -> LDS stores of the next tile are spread over K steps 0..2,
+//   * one barrier before K step 3, after which the first fragments of the next
+//     tile are read while step 3's matrix instructions run,
+//   * fragments are double-buffered across K steps.
+// ---------------------------------------------------------------------------
+constexpr int W4_THREADS = 256;
+
+#define SGB(mask, n) __builtin_amdgcn_sched_group_barrier(mask, n, 0)
+constexpr int SG_MFMA = 0x008, SG_VMEM_RD = 0x020, SG_DS_RD = 0x100, SG_DS_WR = 0x200, SG_VALU = 0x002;
+
+// LDS map of the four-wavefront kernel: [A stage 0 | A stage 1 | B stage 0 | B stage 1],
+// 32 KB each, so that a stage toggle and a 32-row fragment step are immediate
+// offsets of the LDS instruction.  Swizzle key (row>>1)&7: it does not change
+// when 32 or 64 is added to the row, so one address register serves all
+// fragments (and one all store rows) of an operand.
+constexpr int W4_A0 = 0, W4_B0 = 2 * A_STAGE, W4_STAGE = A_STAGE;  // B_STAGE == A_STAGE
+
+struct W4Ctx {
+  const uint16_t* a_panel;   // uniform: first element of this workgroup's 256-row panel of A
+  const uint16_t* b_panel;   // uniform: first element of this workgroup's 256-column panel of B
+  unsigned a_off, b_off;     // per-lane element offsets into the panels
+  unsigned a_rowstep, b_rowstep;  // uniform: 32 rows of A, 1 row of B, in elements
+  unsigned a_st, b_st;       // per-lane LDS byte address of the lane's first store slot (stage 0; b_st includes W4_B0)
+  unsigned a_fr, b_fr;       // per-lane LDS byte address of the lane's first fragment chunk (stage 0, K step 0; b_fr includes W4_B0)
+};
+
+__device__ __forceinline__ void w4_load_tile(const W4Ctx& c, int kt, unsigned b_kstep, u32x4 (&ga)[8], u32x4 (&gb)[8]) {
+  const uint16_t* ap = c.a_panel + kt * BK;
+  const uint16_t* bp = c.b_panel + (size_t)kt * b_kstep;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ga[i] = *(const u32x4*)((ap + (size_t)i * c.a_rowstep) + c.a_off);  // uniform base + lane offset
+#pragma unroll
+  for (int i = 0; i < 8; ++i) gb[i] = *(const u32x4*)((bp + (size_t)i * c.b_rowstep) + c.b_off);
+}
+
+template <int STAGE_N, int I0, int I1>
+__device__ __forceinline__ void w4_store_a(const W4Ctx& c, unsigned char* lds, const u32x4 (&ga)[8]) {
+#pragma unroll
+  for (int i = I0; i < I1; ++i) *(u32x4*)(lds + c.a_st + (W4_A0 + STAGE_N * W4_STAGE + i * 32 * ROW_BYTES)) = ga[i];
+}
+
+// transpose column pair d of the 8(k) x 8(n) patch: dword d of gb[i] holds n = 2d (low) and 2d+1 (high) at k = i.
+// Rows 2d and 2d+1 of the patch have swizzle key (key of row 0) ^ d.
+template <int STAGE_N, int D0, int D1>
+__device__ __forceinline__ void w4_store_b(const W4Ctx& c, unsigned char* lds, const u32x4 (&gb)[8]) {
+#pragma unroll
+  for (int d = D0; d < D1; ++d) {
+    u32x4 even, odd;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      even[j] = (gb[2 * j][d] & 0xffffu) | (gb[2 * j + 1][d] << 16);
+      odd[j] = (gb[2 * j][d] >> 16) | (gb[2 * j + 1][d] & 0xffff0000u);
+    }
+    const unsigned at = (c.b_st ^ (d << 4)) + (STAGE_N * W4_STAGE + 2 * d * ROW_BYTES);   // b_st already holds W4_B0
+    *(u32x4*)(lds + at) = even;
+    *(u32x4*)(lds + at + ROW_BYTES) = odd;
+  }
+}
+
+template <int STAGE_N, int S>
+__device__ __forceinline__ void w4_read_frags(const W4Ctx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
+  const unsigned a = c.a_fr ^ (S << 5), b = c.b_fr ^ (S << 5);   // chunk 2*S + half: flips slot bits 1..2
+#pragma unroll
+  for (int i = 0; i < 4; ++i) af[i] = *(const bf16x8*)(lds + a + (W4_A0 + STAGE_N * W4_STAGE + i * 32 * ROW_BYTES));
+#pragma unroll
+  for (int j = 0; j < 4; ++j) bf[j] = *(const bf16x8*)(lds + b + (STAGE_N * W4_STAGE + j * 32 * ROW_BYTES));   // b_fr already holds W4_B0
+}
+
+__device__ __forceinline__ void w4_mfma16(const bf16x8 (&af)[4], const bf16x8 (&bf)[4], f32x16 (&acc)[4][4]) {
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bf[j], acc[i][j], 0, 0, 0);
+}
+
+// One K tile.  CUR = LDS stage holding this tile; gl_* = staging set loaded now
+// (tile kt+2), gs_* = staging set stored now (tile kt+1, loaded one iteration ago).
+template <int CUR, bool HAVE_NEXT, bool HAVE_NEXT2>
+__device__ __forceinline__ void w4_iteration(const W4Ctx& c, unsigned char* lds, int kt, unsigned b_kstep,
+                                             u32x4 (&gl_a)[8], u32x4 (&gl_b)[8], u32x4 (&gs_a)[8], u32x4 (&gs_b)[8],
+                                             bf16x8 (&af)[2][4], bf16x8 (&bf)[2][4], f32x16 (&acc)[4][4]) {
+  constexpr int NXT = CUR ^ 1;
+  constexpr bool have_next = HAVE_NEXT, have_next2 = HAVE_NEXT2;
+
+  // ---- K step 0: fragments of step 1, loads of tile kt+2, A stores of tile kt+1
+  w4_read_frags<CUR, 1>(c, lds, af[1], bf[1]);
+  if (have_next2) w4_load_tile(c, kt + 2, b_kstep, gl_a, gl_b);
+  w4_mfma16(af[0], bf[0], acc);
+  if (have_next) w4_store_a<NXT, 0, 8>(c, lds, gs_a);
+#pragma unroll
+  for (int r = 0; r < 8; ++r) { SGB(SG_MFMA, 1); SGB(SG_DS_RD, 1); SGB(SG_VMEM_RD, 2); }
+#pragma unroll
+  for (int r = 0; r < 8; ++r) { SGB(SG_MFMA, 1); SGB(SG_DS_WR, 1); }
+
+  // ---- K step 1: fragments of step 2, B stores (column pairs 0, 1)
+  w4_read_frags<CUR, 2>(c, lds, af[0], bf[0]);
+  w4_mfma16(af[1], bf[1], acc);
+  if (have_next) w4_store_b<NXT, 0, 2>(c, lds, gs_b);
+#pragma unroll
+  for (int r = 0; r < 8; ++r) { SGB(SG_MFMA, 1); SGB(SG_DS_RD, 1); }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) { SGB(SG_MFMA, 2); SGB(SG_VALU, 4); SGB(SG_DS_WR, 1); }
+
+  // ---- K step 2: fragments of step 3, B stores (column pairs 2, 3)
+  w4_read_frags<CUR, 3>(c, lds, af[1], bf[1]);
+  w4_mfma16(af[0], bf[0], acc);
+  if (have_next) w4_store_b<NXT, 2, 4>(c, lds, gs_b);
+#pragma unroll
+  for (int r = 0; r < 8; ++r) { SGB(SG_MFMA, 1); SGB(SG_DS_RD, 1); }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) { SGB(SG_MFMA, 2); SGB(SG_VALU, 4); SGB(SG_DS_WR, 1); }
+
+  // ---- the next tile is complete in LDS once every wavefront has passed here
+  __syncthreads();
+
+  // ---- K step 3: first fragments of the next tile
+  if (have_next) w4_read_frags<NXT, 0>(c, lds, af[0], bf[0]);
+  w4_mfma16(af[1], bf[1], acc);
+#pragma unroll
+  for (int r = 0; r < 8; ++r) { SGB(SG_MFMA, 1); SGB(SG_DS_RD, 1); }
+  SGB(SG_MFMA, 8);
+}
+
+__global__ __launch_bounds__(W4_THREADS, 1) void gemm_bf16_w4_kernel(const GemmParams p, const uint16_t* __restrict__ A,
+                                                                     const uint16_t* __restrict__ B, float* __restrict__ C) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tm, tn;
+  tile_of(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, &tm, &tn);
+
+  W4Ctx c;
+  // A tile: 256 rows x 8 chunks of 16 B; lane t takes chunk t&7 of rows (t>>3) + 32*i.
+  const int a_c = t & 7, a_r0 = t >> 3;
+  c.a_panel = A + p.a_base + (int64_t)tm * BM * p.a_m;
+  c.a_off = (unsigned)(a_r0 * p.a_m) + a_c * 8;
+  c.a_rowstep = (unsigned)(32 * p.a_m);
+  c.a_st = a_r0 * ROW_BYTES + ((a_c ^ ((a_r0 >> 1) & 7)) << 4);
+  // B tile: 64 k x 256 n; a lane takes the 8(k) x 8(n) patch at k = 8*(lane&7), n = 8*((lane>>3) + 8*wave):
+  // global reads are 128-byte row segments, transposed rows are whole 16-byte chunks.
+  const int b_kq = lane & 7, b_nb = (lane >> 3) + 8 * wave;
+  c.b_panel = B + p.b_base + (int64_t)tn * BN;
+  c.b_off = (unsigned)(b_kq * 8 * p.b_k) + b_nb * 8;
+  c.b_rowstep = (unsigned)p.b_k;
+  c.b_st = W4_B0 + b_nb * 8 * ROW_BYTES + ((b_kq ^ ((b_nb * 4) & 7)) << 4);
+  const unsigned b_kstep = (unsigned)(BK * p.b_k);
+  // fragments: lane l supplies row (l & 31) and the 8 k values of chunk 2*s + (l >> 5)
+  const int fr = lane & 31, fh = lane >> 5;
+  c.a_fr = (wm * 128 + fr) * ROW_BYTES + ((fh ^ ((fr >> 1) & 7)) << 4);
+  c.b_fr = W4_B0 + (wn * 128 + fr) * ROW_BYTES + ((fh ^ ((fr >> 1) & 7)) << 4);
+
+  u32x4 ga[2][8], gb[2][8];
+  bf16x8 af[2][4], bf[2][4];
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // prologue: tile 0 -> LDS stage 0, tile 1 -> staging set 1, first fragments
+  w4_load_tile(c, 0, b_kstep, ga[0], gb[0]);
+  w4_load_tile(c, 1, b_kstep, ga[1], gb[1]);
+  w4_store_a<0, 0, 8>(c, lds, ga[0]);
+  w4_store_b<0, 0, 4>(c, lds, gb[0]);
+  __syncthreads();
+  w4_read_frags<0, 0>(c, lds, af[0], bf[0]);
+
+  // k_tiles is even and >= 2 (checked on the host).  The steady-state loop has no
+  // conditions in its body; the last two tiles run as a peeled tail.
+  const int last2 = p.k_tiles - 2;
+  for (int kt = 0; kt < last2; kt += 2) {
+    w4_iteration<0, true, true>(c, lds, kt, b_kstep, ga[0], gb[0], ga[1], gb[1], af, bf, acc);
+    w4_iteration<1, true, true>(c, lds, kt + 1, b_kstep, ga[1], gb[1], ga[0], gb[0], af, bf, acc);
+  }
+  w4_iteration<0, true, false>(c, lds, last2, b_kstep, ga[0], gb[0], ga[1], gb[1], af, bf, acc);
+  w4_iteration<1, false, false>(c, lds, last2 + 1, b_kstep, ga[1], gb[1], ga[0], gb[0], af, bf, acc);
+
+  // epilogue: accumulator element v of lane l is row 8*(v/4) + 4*(l>>5) + v%4, column l&31
+  float* c_g = C + p.c_base + ((int64_t)tm * BM + wm * 128 + 4 * fh) * p.c_m + (int64_t)tn * BN + wn * 128 + fr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = 32 * i + 8 * (v / 4) + (v % 4);
+        __builtin_nontemporal_store(acc[i][j][v], c_g + (int64_t)r * p.c_m + 32 * j);
+      }
+}
+
+// ---------------------------------------------------------------------------
+// Direct-to-LDS variant (the gfx950 way): both operands go global -> LDS with
+// 16-byte-per-lane LDS-direct loads, no staging registers and no LDS store
+// instructions; A fragments are read with 16-byte LDS reads, B fragments --
+// B is stored as it lies in memory, [k][n] -- with the transposing 8-byte LDS
+// read, two per fragment.  K tiles of 32 in a four-stage LDS ring: loads run
+// three tiles ahead of the matrix instructions.
+//
+// LDS map: A stages at 0, 16 KB each (256 rows x 64 B, chunk c of row r in slot
+// c ^ ((r>>2)&3)); B stages at 64 KB, 16 KB each (32 k rows x 512 B, chunk c of
+// row k in slot c ^ (4*(k&3))).  An LDS-direct load writes 1 KB per wavefront,
+// lane i at +16*i, so the swizzle is applied by choosing which global chunk a
+// lane fetches.
+//
+// Transposing read (measured lane layout): within 16 lanes, lane p supplies the
+// address of 4 consecutive 16-bit values; lane i receives, for j = 0..3, value
+// (i & 3) of the address given by lane (i >> 2) + 4*j.  Lane p = q + 4*j
+// therefore points at B[k0 + j][n0 + 4*q .. +3] and lane i gets column n0 + i
+// at k0..k0+3.
+// ---------------------------------------------------------------------------
+constexpr int D_BK = 32, D_STAGES = 4, D_A_STAGE = BM * D_BK * 2, D_B_STAGE = D_BK * BN * 2;
+constexpr int D_B0 = D_STAGES * D_A_STAGE;                     // 64 KB
+constexpr int D_LDS = D_STAGES * (D_A_STAGE + D_B_STAGE);      // 128 KB
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef __attribute__((ext_vector_type(8))) short s16x8;
+
+struct DCtx {
+  const uint16_t* a_src;   // per-lane global address of the lane's first A chunk (tile 0, load 0)
+  const uint16_t* b_src;   // per-lane global address of the lane's first B chunk (tile 0, load 0)
+  size_t a_step, b_step;   // element distance between two of the lane's loads within a tile
+  size_t b_kstep;          // element distance of one K tile in B
+  unsigned a_fr;           // LDS byte address of the lane's A fragment chunk (stage 0, K step 0, fragment 0)
+  unsigned b_fr[4];        // LDS byte address of the lane's B fragment j (stage 0, K step 0, first read)
+  unsigned wave_lds;       // LDS byte offset of this wavefront's 1 KB load slot within a stage
+};
+
+// The LDS-direct loads are written as assembly on purpose: the compiler cannot
+// tell that a load into one ring stage does not alias the fragment reads of
+// another and would drain the whole load queue before every LDS read.  Here the
+// queue depth is managed by hand with the s_waitcnt in d_tile().  M0 carries
+// the wave-uniform LDS destination (lane i lands at +16*i).
+__device__ __forceinline__ void d_load_lds16(const uint16_t* src, unsigned lds_off) {
+  const unsigned uniform_off = __builtin_amdgcn_readfirstlane(lds_off);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform_off) : "memory", "m0");
+}
+
+template <int STAGE_N>
+__device__ __forceinline__ void d_issue_loads(const DCtx& c, int kt) {
+  const uint16_t* a = c.a_src + (size_t)kt * D_BK;
+  const uint16_t* b = c.b_src + (size_t)kt * c.b_kstep;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) d_load_lds16(a + u * c.a_step, STAGE_N * D_A_STAGE + u * 4096 + c.wave_lds);
+#pragma unroll
+  for (int u = 0; u < 4; ++u) d_load_lds16(b + u * c.b_step, D_B0 + STAGE_N * D_B_STAGE + u * 4096 + c.wave_lds);
+}
+
+// Fragment q of K step S of a stage: one 16-byte read for A rows 32q.., two transposing reads for B columns 32q..
+template <int STAGE_N, int S, int Q>
+__device__ __forceinline__ void d_read_frag(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
+  typedef __attribute__((address_space(3))) s16x4* lptr;
+  af[Q] = *(const bf16x8*)(lds + (c.a_fr ^ (S << 5)) + (STAGE_N * D_A_STAGE + Q * 32 * 64));
+  const unsigned char* p = lds + c.b_fr[Q] + (STAGE_N * D_B_STAGE + S * 16 * 512);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)p);
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 4 * 512));
+  bf[Q] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+}
+
+template <int STAGE_N, int S>
+__device__ __forceinline__ void d_read_frags(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
+  d_read_frag<STAGE_N, S, 0>(c, lds, af, bf);
+  d_read_frag<STAGE_N, S, 1>(c, lds, af, bf);
+  d_read_frag<STAGE_N, S, 2>(c, lds, af, bf);
+  d_read_frag<STAGE_N, S, 3>(c, lds, af, bf);
+}
+
+template <int Q>
+__device__ __forceinline__ void d_mfma_row(const bf16x8 (&af)[4], const bf16x8 (&bf)[4], f32x16 (&acc)[4][4]) {
+#pragma unroll
+  for (int j = 0; j < 4; ++j) acc[Q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[Q], bf[j], acc[Q][j], 0, 0, 0);
+}
+
+#define D_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+// One K tile of the ring, as eight groups of four matrix instructions.  The
+// scheduler may not move anything across a fence, so every group carries the
+// LDS reads (and, in the second half, the LDS-direct loads) written next to it:
+//   groups 0-3: K step 0 of this tile  + fragment reads of K step 1,
+//   barrier   : tile kt+1 complete in LDS (its loads were issued two tiles ago),
+//   groups 4-7: K step 1 of this tile  + fragment reads of K step 0 of tile kt+1
+//               + the loads of tile kt+3, two per group.
+// ISSUE: start the loads of tile kt+3 (after the barrier).  PENDING: how many
+// younger loads (8 per tile: those of tile kt+2) may still be in flight when
+// tile kt+1 must have landed.
+template <int STAGE_N, bool ISSUE, int PENDING, bool NEXT_FRAGS>
+__device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt, bf16x8 (&af)[2][4], bf16x8 (&bf)[2][4],
+                                       f32x16 (&acc)[4][4]) {
+  constexpr int NXT = (STAGE_N + 1) % D_STAGES;
+  constexpr int LD = (STAGE_N + 3) % D_STAGES;
+  const uint16_t* a = c.a_src + (size_t)(kt + 3) * D_BK;
+  const uint16_t* b = c.b_src + (size_t)(kt + 3) * c.b_kstep;
+  D_FENCE();
+  d_mfma_row<0>(af[0], bf[0], acc); d_read_frag<STAGE_N, 1, 0>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<1>(af[0], bf[0], acc); d_read_frag<STAGE_N, 1, 1>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<2>(af[0], bf[0], acc); d_read_frag<STAGE_N, 1, 2>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<3>(af[0], bf[0], acc); d_read_frag<STAGE_N, 1, 3>(c, lds, af[1], bf[1]); D_FENCE();
+  if (PENDING == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  else if (PENDING == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  D_FENCE();
+  d_mfma_row<0>(af[1], bf[1], acc);
+  if (NEXT_FRAGS) d_read_frag<NXT, 0, 0>(c, lds, af[0], bf[0]);
+  if (ISSUE) { d_load_lds16(a, LD * D_A_STAGE + c.wave_lds); d_load_lds16(a + c.a_step, LD * D_A_STAGE + 4096 + c.wave_lds); }
+  D_FENCE();
+  d_mfma_row<1>(af[1], bf[1], acc);
+  if (NEXT_FRAGS) d_read_frag<NXT, 0, 1>(c, lds, af[0], bf[0]);
+  if (ISSUE) { d_load_lds16(a + 2 * c.a_step, LD * D_A_STAGE + 8192 + c.wave_lds); d_load_lds16(a + 3 * c.a_step, LD * D_A_STAGE + 12288 + c.wave_lds); }
+  D_FENCE();
+  d_mfma_row<2>(af[1], bf[1], acc);
+  if (NEXT_FRAGS) d_read_frag<NXT, 0, 2>(c, lds, af[0], bf[0]);
+  if (ISSUE) { d_load_lds16(b, D_B0 + LD * D_B_STAGE + c.wave_lds); d_load_lds16(b + c.b_step, D_B0 + LD * D_B_STAGE + 4096 + c.wave_lds); }
+  D_FENCE();
+  d_mfma_row<3>(af[1], bf[1], acc);
+  if (NEXT_FRAGS) d_read_frag<NXT, 0, 3>(c, lds, af[0], bf[0]);
+  if (ISSUE) { d_load_lds16(b + 2 * c.b_step, D_B0 + LD * D_B_STAGE + 8192 + c.wave_lds); d_load_lds16(b + 3 * c.b_step, D_B0 + LD * D_B_STAGE + 12288 + c.wave_lds); }
+  D_FENCE();
+}
+
+__global__ __launch_bounds__(W4_THREADS, 1) void gemm_bf16_dma_kernel(const GemmParams p, const uint16_t* __restrict__ A,
+                                                                      const uint16_t* __restrict__ B, float* __restrict__ C) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  int tm, tn;
+  tile_of(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, &tm, &tn);
+
+  DCtx c;
+  // A loads: load u of wavefront w fills LDS rows 16*(4u+w) .. +15 of the stage (1 KB): lane -> row + lane/4, slot lane&3
+  {
+    const int row = 16 * wave + (lane >> 2);           // + 64*u
+    const int chunk = (lane & 3) ^ ((row >> 2) & 3);   // (row>>2)&3 does not change with u
+    c.a_src = A + p.a_base + ((int64_t)tm * BM + row) * p.a_m + chunk * 8;
+    c.a_step = (size_t)64 * p.a_m;
+  }
+  // B loads: load u of wavefront w fills k rows 2*(4u+w), +1: lane -> k = 2*(4u+w) + lane/32, slot lane&31
+  {
+    const int k = 2 * wave + (lane >> 5);               // + 8*u ; k&3 does not change with u
+    const int chunk = (lane & 31) ^ (4 * (k & 3));
+    c.b_src = B + p.b_base + (int64_t)k * p.b_k + (int64_t)tn * BN + chunk * 8;
+    c.b_step = (size_t)8 * p.b_k;
+    c.b_kstep = (size_t)D_BK * p.b_k;
+  }
+  c.wave_lds = wave * 1024;
+  // A fragments: lane supplies row (lane&31) (+32*i) and chunk 2*s + (lane>>5)
+  {
+    const int fr = lane & 31, fh = lane >> 5;
+    c.a_fr = (wm * 128 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4);
+  }
+  // B fragments: 16-lane group g, lane p in it: k = 8*(g>>1) + (p>>2) (+16*s, +4 second read),
+  // columns wn*128 + 32*j + 16*(g&1) + 4*(p&3) .. +3
+  {
+    const int g = lane >> 4, pl = lane & 15;
+    const int k = 8 * (g >> 1) + (pl >> 2);
+    const int low2 = 2 * (g & 1) + ((pl & 3) >> 1);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int chunk = (wn * 16 + 4 * j + low2) ^ (4 * (k & 3));
+      c.b_fr[j] = D_B0 + k * 512 + chunk * 16 + (pl & 1) * 8;
+    }
+  }
+
+  bf16x8 af[2][4], bf[2][4];
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+  // prologue: tiles 0, 1, 2 in flight, wait for tile 0   (k_tiles is a multiple of 4, checked on the host)
+  d_issue_loads<0>(c, 0);
+  d_issue_loads<1>(c, 1);
+  d_issue_loads<2>(c, 2);
+  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  __syncthreads();
+  d_read_frags<0, 0>(c, lds, af[0], bf[0]);
+
+  const int last4 = p.k_tiles - 4;
+  for (int kt = 0; kt < last4; kt += 4) {
+    d_tile<0, true, 8, true>(c, lds, kt, af, bf, acc);
+    d_tile<1, true, 8, true>(c, lds, kt + 1, af, bf, acc);
+    d_tile<2, true, 8, true>(c, lds, kt + 2, af, bf, acc);
+    d_tile<3, true, 8, true>(c, lds, kt + 3, af, bf, acc);
+  }
+  d_tile<0, true, 8, true>(c, lds, last4, af, bf, acc);        // issues the last tile's loads
+  d_tile<1, false, 8, true>(c, lds, last4 + 1, af, bf, acc);
+  d_tile<2, false, 0, true>(c, lds, last4 + 2, af, bf, acc);
+  d_tile<3, false, 0, false>(c, lds, last4 + 3, af, bf, acc);
+
+  const int fr = lane & 31, fh = lane >> 5;
+  float* c_g = C + p.c_base + ((int64_t)tm * BM + wm * 128 + 4 * fh) * p.c_m + (int64_t)tn * BN + wn * 128 + fr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int r = 32 * i + 8 * (v / 4) + (v % 4);
+        __builtin_nontemporal_store(acc[i][j][v], c_g + (int64_t)r * p.c_m + 32 * j);
+      }
+}
+
 GemmParams make_params(const GemmShape& g) {
   GemmParams p;
   p.tiles_m = (int)(g.M / BM);
@@ -187,32 +605,49 @@ bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_i
   if (g.M % BM || g.N % BN || g.K % BK || g.K < BK) return false;
   if (g.a_m % 8 || g.b_k % 8 || g.a_base % 8 || g.b_base % 8) return false;  // 16-byte global loads
   if (g.M / BM > 32767 || g.N / BN > 32767 || g.K / BK > 0x7fffffff / BK) return false;
-  l->variant = tune_int("gemm_swz", 1) ? 1 : 0;
+  int swz = tune_int("gemm_swz", 2);
+  if (swz < 0 || swz > 2) swz = 2;
+  int waves = tune_int("gemm_waves", 4) == 8 ? 8 : 4;
+  if ((g.K / BK) % 2) waves = 8;   // the four-wavefront pipeline consumes K tiles in pairs
+  const bool dma = tune_int("gemm_dma", 1) != 0 && g.K % (D_BK * D_STAGES) == 0 && g.K >= D_BK * D_STAGES;
+  l->variant = dma ? 20 : (waves == 8 ? 10 : 0) + swz;
   l->grid = (g.M / BM) * (g.N / BN);
   info->path = STRIPE_PATH_MFMA_GEMM;
-  info->tile_m = BM; info->tile_n = BN; info->tile_k = BK;
+  info->tile_m = BM; info->tile_n = BN; info->tile_k = dma ? D_BK : BK;
   info->frag_m = 32; info->frag_n = 32; info->frag_k = 16;
-  info->lds_bytes = 2 * STAGE;
-  info->workgroup_size = THREADS;
+  info->lds_bytes = dma ? D_LDS : 2 * STAGE;
+  info->workgroup_size = (waves == 8 && !dma) ? THREADS : W4_THREADS;
   info->grid = l->grid;
-  snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x64_mfma32x32x16_swz%d", l->variant);
+  if (dma) snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x32_mfma32x32x16_w4_lds_direct");
+  else snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x64_mfma32x32x16_w%d_swz%d", waves, swz);
   return true;
 }
 
 hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t st) {
   if (((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % 4)) return hipErrorInvalidValue;
   const GemmParams p = make_params(g);
-  auto kernel = l.variant == 1 ? gemm_bf16_kernel<1> : gemm_bf16_kernel<0>;
+  void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = nullptr;
+  switch (l.variant) {
+    case 0: case 1: case 2: kernel = gemm_bf16_w4_kernel; break;
+    case 20: kernel = gemm_bf16_dma_kernel; break;
+    case 10: kernel = gemm_bf16_w8_kernel<0>; break;
+    case 11: kernel = gemm_bf16_w8_kernel<1>; break;
+    default: kernel = gemm_bf16_w8_kernel<2>; break;
+  }
+  const int threads = (l.variant >= 10 && l.variant < 20) ? THREADS : W4_THREADS;
+  const int lds_bytes = l.variant == 20 ? D_LDS : 2 * STAGE;
+  GemmParams pk = p;
+  if (l.variant == 20) pk.k_tiles = (int)(g.K / D_BK);
   // more than 64 KB of dynamic LDS has to be enabled once per device
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev != l.lds_enabled_on) {
-    e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * STAGE);
+    e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
     if (e != hipSuccess) return e;
     l.lds_enabled_on = dev;
   }
-  hipLaunchKernelGGL(kernel, dim3((unsigned)l.grid), dim3(THREADS), 2 * STAGE, st, p, (const uint16_t*)a,
+  hipLaunchKernelGGL(kernel, dim3((unsigned)l.grid), dim3(threads), lds_bytes, st, pk, (const uint16_t*)a,
                      (const uint16_t*)b, (float*)c);
   return hipGetLastError();
 }
