@@ -9,12 +9,12 @@
 // Mapping: channels are contiguous, so a lane owns 4 channels (one 16-byte
 // load) of one output column; 16 lanes cover the 256 bytes of a 64-channel
 // pixel.  A workgroup of 128 lanes owns 128 consecutive (column, channel-quad)
-// items and walks TY output rows downwards, keeping the per-row maxima of
-// the R - stride input rows two neighbouring windows share in registers, so a
-// strip reads each of its input rows once.  Rows are split interior/boundary
-// only through predicates on whole rows and whole columns (Section 2.3,
-// "Separating Interior and Boundary Tiles"): the tap loops carry no per-tap
-// constraint arithmetic.
+// items and a strip of TY output rows; it reads each of the strip's
+// stride*(TY-1)+R input rows once (rows shared by neighbouring windows are
+// reused from registers).  Boundary handling is by clamped coordinates plus a
+// select, decided per whole row and whole column (Section 2.3, "Separating
+// Interior and Boundary Tiles"): the loads carry no per-tap constraint tests
+// and no branches.
 #include <hip/hip_runtime.h>
 
 #include "kernels.hpp"
@@ -27,6 +27,7 @@ struct PoolParams {
   int32_t pad_y, pad_x;
   int32_t items;                      // Wo * C4
   int32_t blocks_per_row, y_strips;
+  int32_t xcd_remap, pad_;
   int64_t i_n, i_y, i_x, o_n, o_y, o_x;  // element strides (channel stride is 1)
   int64_t i_base, o_base;
 };
@@ -53,8 +54,7 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned grid) {
 template <int R, int S, int ST, int TY, bool NT>
 __global__ __launch_bounds__(128) void pool_max_f32_kernel(const PoolParams p, const float* __restrict__ in,
                                                           float* __restrict__ out) {
-  constexpr int CARRY = R > ST ? R - ST : 0;  // input rows two consecutive windows share
-  const unsigned b = xcd_contiguous(blockIdx.x, gridDim.x);
+  const unsigned b = p.xcd_remap ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
   const int bx = b % p.blocks_per_row;
   const int rest = b / p.blocks_per_row;
   const int ys = rest % p.y_strips;
@@ -67,6 +67,11 @@ __global__ __launch_bounds__(128) void pool_max_f32_kernel(const PoolParams p, c
   const float* inb = in + p.i_base + (int64_t)n * p.i_n + c4 * 4;
   float* outb = out + p.o_base + (int64_t)n * p.o_n + (int64_t)xo * p.o_x + c4 * 4;
 
+  // Branch-free: every coordinate is clamped into the buffer so that all loads of
+  // the strip are issued unconditionally and back to back (they are independent;
+  // the memory system sees (ST*(TY-1)+R)*S sixteen-byte loads per lane in flight),
+  // then taps outside the iteration space are replaced by the identity of max.
+  constexpr int NR = ST * (TY - 1) + R;   // input rows a strip of TY output rows touches
   const int x0 = xo * ST - p.pad_x;
   bool xv[S];
   int64_t xoff[S];
@@ -74,47 +79,44 @@ __global__ __launch_bounds__(128) void pool_max_f32_kernel(const PoolParams p, c
   for (int j = 0; j < S; ++j) {
     const int xc = x0 + j;
     xv[j] = xc >= 0 && xc < p.W;
-    xoff[j] = (int64_t)xc * p.i_x;
+    xoff[j] = (int64_t)(xc < 0 ? 0 : (xc >= p.W ? p.W - 1 : xc)) * p.i_x;
   }
   const float ninf = -__builtin_huge_valf();
   const f32x4 lowest = {ninf, ninf, ninf, ninf};
-
-  auto row_max = [&](int y) -> f32x4 {
-    f32x4 m = lowest;
-    if (y >= 0 && y < p.H) {
-      const float* rp = inb + (int64_t)y * p.i_y;
-#pragma unroll
-      for (int j = 0; j < S; ++j)
-        if (xv[j]) {
-          const f32x4 v = NT ? __builtin_nontemporal_load((const f32x4*)(rp + xoff[j]))
-                              : *(const f32x4*)(rp + xoff[j]);
-          m = max4(m, v);
-        }
-    }
-    return m;
-  };
-
   const int yo0 = ys * TY;
-  f32x4 hm[R];
+  const int y0 = yo0 * ST - p.pad_y;
+
+  f32x4 v[NR][S];
 #pragma unroll
-  for (int i = 0; i < CARRY; ++i) hm[i] = row_max(yo0 * ST - p.pad_y + i);
+  for (int r = 0; r < NR; ++r) {
+    const int y = y0 + r;
+    const int yc = y < 0 ? 0 : (y >= p.H ? p.H - 1 : y);
+    const float* rp = inb + (int64_t)yc * p.i_y;
+#pragma unroll
+    for (int j = 0; j < S; ++j)
+      v[r][j] = NT ? __builtin_nontemporal_load((const f32x4*)(rp + xoff[j])) : *(const f32x4*)(rp + xoff[j]);
+  }
+  f32x4 hm[NR];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const int y = y0 + r;
+    const bool yv = y >= 0 && y < p.H;
+    f32x4 m = lowest;
+#pragma unroll
+    for (int j = 0; j < S; ++j) m = max4(m, (yv && xv[j]) ? v[r][j] : lowest);
+    hm[r] = m;
+  }
 #pragma unroll
   for (int ty = 0; ty < TY; ++ty) {
     const int yo = yo0 + ty;
-    const int ybase = yo * ST - p.pad_y;
-    const bool live = yo < p.Ho;
+    f32x4 m = hm[ty * ST];
 #pragma unroll
-    for (int i = CARRY; i < R; ++i) hm[i] = live ? row_max(ybase + i) : lowest;
-    f32x4 m = hm[0];
-#pragma unroll
-    for (int i = 1; i < R; ++i) m = max4(m, hm[i]);
-    if (live) {
+    for (int i = 1; i < R; ++i) m = max4(m, hm[ty * ST + i]);
+    if (yo < p.Ho) {
       f32x4* dst = (f32x4*)(outb + (int64_t)yo * p.o_y);
       if (NT) __builtin_nontemporal_store(m, dst);
       else *dst = m;
     }
-#pragma unroll
-    for (int i = 0; i < CARRY; ++i) hm[i] = hm[i + ST];
   }
 }
 
@@ -125,12 +127,14 @@ PoolParams make_params(const Pool2dShape& s, int ty) {
   p.items = p.Wo * p.C4;
   p.blocks_per_row = (p.items + 127) / 128;
   p.y_strips = (p.Ho + ty - 1) / ty;
+  p.xcd_remap = tune_int("pool_xcd", 0);
+  p.pad_ = 0;
   p.i_n = s.i_n; p.i_y = s.i_y; p.i_x = s.i_x; p.o_n = s.o_n; p.o_y = s.o_y; p.o_x = s.o_x;
   p.i_base = s.i_base; p.o_base = s.o_base;
   return p;
 }
 
-constexpr int kTyChoices[] = {2, 4, 7, 8, 14};
+constexpr int kTyChoices[] = {1, 2, 3, 4, 7};
 
 template <int TY, bool NT>
 hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st) {
@@ -152,11 +156,11 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   for (int64_t v : {s.i_n, s.i_y, s.i_x, s.o_n, s.o_y, s.o_x, s.i_base, s.o_base})
     if (v % 4) return false;
   if (s.N > 0x7fffffff / 4 || s.H > 0x3fffffff || s.W > 0x3fffffff || s.Wo * (s.C / 4) > 0x3fffffff) return false;
-  int ty_idx = 2;  // 7 rows per strip
+  int ty_idx = 1;  // 2 rows per strip
   const int want = tune_int("pool_ty", 0);
   for (int i = 0; i < (int)(sizeof kTyChoices / sizeof kTyChoices[0]); ++i)
     if (kTyChoices[i] == want) ty_idx = i;
-  const int nt = tune_int("pool_nt", 1) ? 1 : 0;
+  const int nt = tune_int("pool_nt", 0) ? 1 : 0;
   const int ty = kTyChoices[ty_idx];
   const PoolParams p = make_params(s, ty);
   const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
@@ -181,11 +185,11 @@ hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in
   const bool nt = l.variant % 2;
   const PoolParams p = make_params(s, kTyChoices[ty_idx]);
   switch (ty_idx) {
-    case 0: return nt ? launch_ty<2, true>(p, l.grid, in, out, st) : launch_ty<2, false>(p, l.grid, in, out, st);
-    case 1: return nt ? launch_ty<4, true>(p, l.grid, in, out, st) : launch_ty<4, false>(p, l.grid, in, out, st);
-    case 2: return nt ? launch_ty<7, true>(p, l.grid, in, out, st) : launch_ty<7, false>(p, l.grid, in, out, st);
-    case 3: return nt ? launch_ty<8, true>(p, l.grid, in, out, st) : launch_ty<8, false>(p, l.grid, in, out, st);
-    default: return nt ? launch_ty<14, true>(p, l.grid, in, out, st) : launch_ty<14, false>(p, l.grid, in, out, st);
+    case 0: return nt ? launch_ty<1, true>(p, l.grid, in, out, st) : launch_ty<1, false>(p, l.grid, in, out, st);
+    case 1: return nt ? launch_ty<2, true>(p, l.grid, in, out, st) : launch_ty<2, false>(p, l.grid, in, out, st);
+    case 2: return nt ? launch_ty<3, true>(p, l.grid, in, out, st) : launch_ty<3, false>(p, l.grid, in, out, st);
+    case 3: return nt ? launch_ty<4, true>(p, l.grid, in, out, st) : launch_ty<4, false>(p, l.grid, in, out, st);
+    default: return nt ? launch_ty<7, true>(p, l.grid, in, out, st) : launch_ty<7, false>(p, l.grid, in, out, st);
   }
 }
 

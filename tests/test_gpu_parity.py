@@ -125,7 +125,7 @@ def test_pool_path_small(N, H, Wd, C):
     assert np.array_equal(gpu.reshape(ref.shape), ref.numpy())
 
 
-@pytest.mark.parametrize("ty", [2, 4, 8, 14])
+@pytest.mark.parametrize("ty", [1, 2, 3, 7])
 def test_pool_strip_heights(ty, monkeypatch):
     monkeypatch.setenv("STRIPE_TUNE", f"pool_ty={ty},pool_nt=0")
     blk = W.maxpool_block(2, 45, 27, 12, 3, 2, 1)

@@ -127,7 +127,7 @@ def test_forcing_a_family_the_block_does_not_have_is_refused():
 
 
 def test_tune_override_selects_variants(monkeypatch):
-    monkeypatch.setenv("STRIPE_TUNE", "pool_ty=4,pool_nt=0")
-    assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty4"
+    monkeypatch.setenv("STRIPE_TUNE", "pool_ty=4,pool_nt=1")
+    assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty4_nt"
     monkeypatch.delenv("STRIPE_TUNE")
-    assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty7_nt"
+    assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty2"
