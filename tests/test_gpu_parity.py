@@ -199,6 +199,36 @@ def test_gemm_config_full_size():
     assert np.array_equal(gpu.reshape(4096, 4096), ins[0].float().numpy())
 
 
+# ------------------------------------------------------------------ convolution path (matrix cores)
+@pytest.mark.parametrize("N,H,Wd", [(2, 10, 13), (1, 7, 56), (3, 20, 64), (1, 2, 2), (2, 9, 33)])
+def test_conv_mfma_bf16_small(N, H, Wd):
+    """3x3, 64 -> 64 channels, 'same' padding: ragged strips, both pixel fragments, halo on all four sides."""
+    blk = W.conv2d_block(N, H, Wd, 64, 64, 3, 3, 1, 1, "bf16", "f32")
+    ins = [W.seeded_tensor((N, H, Wd, 64), "bf16", 0), W.seeded_tensor((3, 3, 64, 64), "bf16", 1)]
+    info, score = parity(blk, ins, what=f"conv mfma {N}x{H}x{Wd}")
+    say(f"conv mfma {N}x{H}x{Wd}: {info['kernel']} err/bound {score:.3f}")
+    assert info["path_name"] == "mfma_conv", info
+
+
+def test_conv_mfma_position_sensitive():
+    """Delta input: the output is the (flipped) filter patch, exactly -- catches any mix-up of taps, pixels or channels."""
+    N, H, Wd = 1, 9, 40
+    blk = W.conv2d_block(N, H, Wd, 64, 64, 3, 3, 1, 1, "bf16", "f32")
+    f = W.seeded_tensor((3, 3, 64, 64), "bf16", 1)
+    i = torch.zeros((N, H, Wd, 64), dtype=torch.bfloat16)
+    y0, x0, c0 = 4, 33, 17
+    i[0, y0, x0, c0] = 1.0
+    gpu, sb = run_gpu(blk, [i, f], return_block=True)
+    assert sb.info["path_name"] == "mfma_conv"
+    want = np.zeros((N, H, Wd, 64), np.float32)
+    for y in range(H):
+        for x in range(Wd):
+            a, b = y0 - y + 1, x0 - x + 1
+            if 0 <= a < 3 and 0 <= b < 3:
+                want[0, y, x, :] = f[a, b, :, c0].float().numpy()
+    assert np.array_equal(gpu.reshape(want.shape), want)
+
+
 # ------------------------------------------------------------------ convolution configs at full size
 def test_resnet_conv_config_full_size():
     name = "resnet_conv_bf16"
