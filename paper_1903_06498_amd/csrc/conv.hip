@@ -167,6 +167,7 @@ ConvParams make_params(const Conv2dShape& c, int rows) {
 
 bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info) {
   if (tune_int("conv_mfma", 1) == 0) return false;
+  if (in_dtype == STRIPE_I8) return conv_i8_select(c, in_dtype, l, info);
   if (in_dtype != STRIPE_BF16) return false;
   if (c.R != 3 || c.S != 3 || c.stride_y != 1 || c.stride_x != 1 || c.pad_y != 1 || c.pad_x != 1) return false;
   if (c.Ci != C_CI || c.Co != C_CO || c.Ho != c.H || c.Wo != c.W) return false;
@@ -197,6 +198,7 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
 }
 
 hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
+  if (l.variant == 100) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
   const int rows = l.variant;
   const ConvParams p = make_params(c, rows);

@@ -1,0 +1,205 @@
+// Strided int8 convolution-shaped contraction on the gfx950 matrix cores,
+// exact int32 accumulation:
+//   O[n,y,x,k] = sum over taps (i,j) and channels c of I[n, 2y+i-3, 2x+j-3, c] * F[i,j,k,c]
+// for a 7x7 filter, 3 input channels, 64 output channels; taps outside the
+// image are outside the iteration space (affine constraints, paper Section 3.2)
+// and are realised as zero operands, which is exact for integer sums.
+//
+// With only 3 channels the contraction index (i,j,c) is hostile to matrix
+// instructions, so the "microarchitectural transposition / stenciling" of
+// Section 2.3 is done explicitly in LDS: for every image row r and output
+// column x the 21 bytes I[r, 2x-3 .. 2x+3, 0..2] are laid out as one 32-byte,
+// 16-byte-aligned K vector E[r][x] (bytes 21..31 meet zero weights).  One
+// v_mfma_i32_16x16x64_i8 then consumes two filter rows (2 x 32 bytes of K) for
+// 16 output columns x 16 output channels; the 7 filter rows take 4 K steps (the
+// eighth row has zero weights).
+//
+// Nesting: outer block -> workgroup per strip of TY output rows of one image;
+// middle block -> the strip's 2*TY+5 image rows, expanded, in LDS (about 70 KB,
+// two workgroups per CU so one strip's stores overlap the next one's staging);
+// inner block -> one wavefront per output row, 7 x 4 fragments of 16 x 16.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace stripe {
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+constexpr int Q_TY = 4;                        // output rows per strip = wavefronts per workgroup
+constexpr int Q_ROWS = 2 * Q_TY + 5;           // image rows a strip touches
+constexpr int Q_CO = 64, Q_R = 7, Q_S = 7, Q_CI = 3;
+constexpr int Q_MAX_WO = 112;                  // 7 column fragments of 16
+constexpr int Q_BT_BYTES = 4 * Q_CO * 64;      // filter as K vectors: [K step][k][64 B]
+
+struct I8Params {
+  int32_t H, W, Ho, Wo, strips_per_image, raw_row_bytes;
+  int64_t i_n, i_y;            // input strides in elements (= bytes); pixels and channels are contiguous
+  int64_t o_n, o_y, o_x;       // output strides in elements; channels contiguous
+  int64_t i_base, f_base, o_base;
+};
+
+// LDS: [Bt: 16 KB][raw: Q_ROWS x raw_row_bytes][E: Q_ROWS x Wo x 32 B]
+__global__ __launch_bounds__(Q_TY * 64) void conv7x7s2_i8_kernel(const I8Params p, const int8_t* __restrict__ I,
+                                                               const int8_t* __restrict__ F, int32_t* __restrict__ O) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  unsigned char* bt = lds;
+  unsigned char* raw = lds + Q_BT_BYTES;
+  unsigned char* ex = raw + Q_ROWS * p.raw_row_bytes;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int n = blockIdx.x / p.strips_per_image;
+  const int y0 = (blockIdx.x % p.strips_per_image) * Q_TY;
+  const int row_chunks = p.raw_row_bytes / 16;          // 16 zero bytes, W*3 data bytes, >= 16 zero bytes
+  const int data_chunks = (p.W * Q_CI) / 16;
+
+  // ---- raw image rows 2*y0-3 .. 2*y0+2*TY+1, zero where outside the image ----
+  const int8_t* ig = I + p.i_base + (int64_t)n * p.i_n;
+  for (int q = t; q < Q_ROWS * row_chunks; q += Q_TY * 64) {
+    const int r = q / row_chunks, c = q - r * row_chunks;
+    const int y = 2 * y0 - 3 + r;
+    u32x4 v = {0u, 0u, 0u, 0u};
+    if (c >= 1 && c <= data_chunks && y >= 0 && y < p.H) v = *(const u32x4*)(ig + (int64_t)y * p.i_y + (c - 1) * 16);
+    *(u32x4*)(raw + r * p.raw_row_bytes + c * 16) = v;
+  }
+  // ---- the filter as it lies in memory (9,408 bytes), parked where E will be built later ----
+  const u32x4* fg = (const u32x4*)(F + p.f_base);
+  constexpr int F_BYTES = Q_R * Q_S * Q_CO * Q_CI;        // 9,408 = 588 chunks of 16
+  for (int q = t; q < F_BYTES / 16; q += Q_TY * 64) *(u32x4*)(ex + q * 16) = fg[q];
+  __syncthreads();
+  // ---- filter as K vectors: Bt[ks][k][0..31] = F[2ks][*][k][*] (21 B, then zeros), [32..63] = F[2ks+1][...] ----
+  for (int q = t; q < 8 * Q_CO; q += Q_TY * 64) {
+    const int i = q / Q_CO, k = q - i * Q_CO;           // filter row (7 = the all-zero eighth row), output channel
+    unsigned w[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    if (i < Q_R) {
+#pragma unroll
+      for (int b = 0; b < Q_S * Q_CI; ++b) {
+        const int j = b / Q_CI, c = b - j * Q_CI;
+        const unsigned byte = ex[((i * Q_S + j) * Q_CO + k) * Q_CI + c];
+        w[b >> 2] |= byte << (8 * (b & 3));
+      }
+    }
+    unsigned char* dst = bt + ((i >> 1) * Q_CO + k) * 64 + (i & 1) * 32;
+    *(u32x4*)dst = (u32x4){w[0], w[1], w[2], w[3]};
+    *(u32x4*)(dst + 16) = (u32x4){w[4], w[5], w[6], w[7]};
+  }
+  __syncthreads();
+
+  // ---- expand: E[r][x] = raw[r] bytes 16 + 6x - 9 .. +23 (16 + (2x-3)*3 is where column 2x-3 starts) ----
+  for (int q = t; q < Q_ROWS * p.Wo; q += Q_TY * 64) {
+    const int r = q / p.Wo, x = q - r * p.Wo;
+    const int start = 6 * x + 7;
+    const unsigned* src = (const unsigned*)(raw + r * p.raw_row_bytes + (start & ~3));
+    const unsigned sh = start & 3;
+    unsigned d[7];
+#pragma unroll
+    for (int u = 0; u < 7; ++u) d[u] = src[u];
+    unsigned e[6];
+#pragma unroll
+    for (int u = 0; u < 6; ++u) e[u] = __builtin_amdgcn_alignbyte(d[u + 1], d[u], sh);
+    e[5] &= 0x000000ffu;                                  // byte 20 is the last of the 21
+    // the two 16-byte halves of a vector swap places for every second group of 8 columns (bank spread)
+    unsigned char* dst = ex + (r * p.Wo + x) * 32;
+    const int flip = ((x >> 3) & 1) * 16;
+    *(u32x4*)(dst + flip) = (u32x4){e[0], e[1], e[2], e[3]};
+    *(u32x4*)(dst + (16 - flip)) = (u32x4){e[4], e[5], 0u, 0u};
+  }
+  __syncthreads();
+
+  // ---- one wavefront per output row ----
+  const int y = y0 + wave;
+  if (y >= p.Ho) return;
+  const int fr = lane & 15, kq = lane >> 4;              // fragment row / 16-byte K block of the lane
+  // B fragments stay in registers: [K step][channel fragment]
+  i32x4 bfr[4][4];
+#pragma unroll
+  for (int ks = 0; ks < 4; ++ks)
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf) bfr[ks][nf] = *(const i32x4*)(bt + (ks * Q_CO + nf * 16 + fr) * 64 + kq * 16);
+
+  const int n_mf = p.Wo / 16;
+  int32_t* og = O + p.o_base + (int64_t)n * p.o_n + (int64_t)y * p.o_y + fr;
+  for (int mf = 0; mf < n_mf; ++mf) {
+    const int x = mf * 16 + fr;
+    i32x4 acc[4];
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf) acc[nf] = (i32x4){0, 0, 0, 0};
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      int r = 2 * wave + 2 * ks + (kq >> 1);              // image row 2y + i - 3 relative to the strip's first row
+      r = r < Q_ROWS ? r : Q_ROWS - 1;                    // the eighth filter row has zero weights: any row will do
+      const int half = ((kq & 1) ^ ((x >> 3) & 1)) * 16;
+      const i32x4 a = *(const i32x4*)(ex + (r * p.Wo + x) * 32 + half);
+#pragma unroll
+      for (int nf = 0; nf < 4; ++nf) acc[nf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bfr[ks][nf], acc[nf], 0, 0, 0);
+    }
+    // accumulator element v of lane l: column 4*(l>>4) + v of the fragment, channel l&15
+#pragma unroll
+    for (int nf = 0; nf < 4; ++nf)
+#pragma unroll
+      for (int v = 0; v < 4; ++v)
+        __builtin_nontemporal_store(acc[nf][v], og + (int64_t)(mf * 16 + 4 * kq + v) * p.o_x + nf * 16);
+  }
+}
+
+I8Params make_params(const Conv2dShape& c) {
+  I8Params p;
+  p.H = (int)c.H; p.W = (int)c.W; p.Ho = (int)c.Ho; p.Wo = (int)c.Wo;
+  p.strips_per_image = (int)((c.Ho + Q_TY - 1) / Q_TY);
+  p.raw_row_bytes = 16 + (int)c.W * Q_CI + 16;
+  p.i_n = c.i_n; p.i_y = c.i_y;
+  p.o_n = c.o_n; p.o_y = c.o_y; p.o_x = c.o_x;
+  p.i_base = c.i_base; p.f_base = c.f_base; p.o_base = c.o_base;
+  return p;
+}
+
+int lds_bytes_for(const I8Params& p) { return Q_BT_BYTES + Q_ROWS * p.raw_row_bytes + Q_ROWS * p.Wo * 32; }
+
+}  // namespace
+
+bool conv_i8_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info) {
+  if (in_dtype != STRIPE_I8) return false;
+  if (c.R != Q_R || c.S != Q_S || c.stride_y != 2 || c.stride_x != 2 || c.pad_y != 3 || c.pad_x != 3) return false;
+  if (c.Ci != Q_CI || c.Co != Q_CO) return false;
+  if (c.W % 32 || c.Wo != c.W / 2 || c.Wo > Q_MAX_WO || c.H % 2 || c.Ho != c.H / 2) return false;   // whole 16-column fragments
+  // pixels and channels contiguous in a row, rows 16-byte aligned; filter [i][j][k][c] contiguous
+  if (c.i_c != 1 || c.i_x != Q_CI || c.i_y % 16 || c.i_n % 16 || c.i_base % 16) return false;
+  if (c.f_c != 1 || c.f_k != Q_CI || c.f_s != Q_CO * Q_CI || c.f_r != Q_S * Q_CO * Q_CI || c.f_base % 16) return false;
+  if (Q_ROWS * (c.W / 2) * 32 < Q_R * Q_S * Q_CO * Q_CI) return false;   // the raw filter is parked in E's space
+  if (c.o_k != 1) return false;
+  const I8Params p = make_params(c);
+  const int64_t grid = c.N * p.strips_per_image;
+  if (grid > 0x7fffffffLL || lds_bytes_for(p) > 160 * 1024) return false;
+  l->variant = 100;
+  l->grid = grid;
+  info->path = STRIPE_PATH_MFMA_CONV;
+  info->tile_m = Q_TY * (int)c.Wo;
+  info->tile_n = Q_CO;
+  info->tile_k = 4 * 64;
+  info->frag_m = 16; info->frag_n = 16; info->frag_k = 64;
+  info->lds_bytes = lds_bytes_for(p);
+  info->workgroup_size = Q_TY * 64;
+  info->grid = grid;
+  snprintf(info->kernel, sizeof info->kernel, "conv7x7s2_i8_c3k64_strip%d_mfma16x16x64", Q_TY);
+  return true;
+}
+
+hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
+  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
+  const I8Params p = make_params(c);
+  const int lds_bytes = lds_bytes_for(p);
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev != l.lds_enabled_on) {
+    e = hipFuncSetAttribute((const void*)conv7x7s2_i8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    if (e != hipSuccess) return e;
+    l.lds_enabled_on = dev;
+  }
+  hipLaunchKernelGGL(conv7x7s2_i8_kernel, dim3((unsigned)l.grid), dim3(Q_TY * 64), lds_bytes, st, p, (const int8_t*)in,
+                     (const int8_t*)flt, (int32_t*)out);
+  return hipGetLastError();
+}
+
+}  // namespace stripe

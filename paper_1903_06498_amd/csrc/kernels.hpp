@@ -44,6 +44,9 @@ struct ConvLaunch {
 };
 bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
 hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);
+// strided 7x7 int8 variant (dispatched to by conv_select / launch_conv)
+bool conv_i8_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
+hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);
 
 // ---- max aggregation over a 2-d window ------------------------------------
 struct PoolLaunch {

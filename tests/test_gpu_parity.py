@@ -229,6 +229,29 @@ def test_conv_mfma_position_sensitive():
     assert np.array_equal(gpu.reshape(want.shape), want)
 
 
+@pytest.mark.parametrize("N,H,Wd", [(2, 10, 64), (1, 6, 96), (1, 18, 224), (3, 4, 64)])
+def test_conv_mfma_int8_small(N, H, Wd):
+    """7x7 stride 2, 3 -> 64 channels, int8 -> int32: bit-exact, ragged strips, left/right/top/bottom halo."""
+    blk = W.conv2d_block(N, H, Wd, 3, 64, 7, 7, 2, 3, "i8", "i32")
+    ins = [W.seeded_tensor((N, H, Wd, 3), "i8", 0), W.seeded_tensor((7, 7, 64, 3), "i8", 1)]
+    info, _ = parity(blk, ins, what=f"conv int8 {N}x{H}x{Wd}")
+    assert info["path_name"] == "mfma_conv", info
+    gen = run_gpu(blk, ins, "generic")
+    assert np.array_equal(gen, run_gpu(blk, ins))
+
+
+def test_conv_mfma_int8_extreme_values():
+    """All operands -128: the largest magnitudes the block can produce, exact tap counts at every border."""
+    N, H, Wd = 1, 20, 64
+    blk = W.conv2d_block(N, H, Wd, 3, 64, 7, 7, 2, 3, "i8", "i32")
+    ins = [torch.full((N, H, Wd, 3), -128, dtype=torch.int8), torch.full((7, 7, 64, 3), -128, dtype=torch.int8)]
+    gpu = run_gpu(blk, ins).reshape(N, H // 2, Wd // 2, 64)
+    cy = np.array([taps(y, 2, 3, 7, H) for y in range(H // 2)])
+    cx = np.array([taps(x, 2, 3, 7, Wd) for x in range(Wd // 2)])
+    want = 16384 * 3 * cy[:, None] * cx[None, :]
+    assert np.array_equal(gpu, np.broadcast_to(want[None, :, :, None], gpu.shape))
+
+
 # ------------------------------------------------------------------ convolution configs at full size
 def test_resnet_conv_config_full_size():
     name = "resnet_conv_bf16"
