@@ -27,6 +27,16 @@ if ROOT not in sys.path:
 
 PEAK = {"bf16_mfma_tflops": 2500.0, "int8_mfma_tops": 5000.0, "hbm_gbs": 8000.0}
 
+# Memory traffic per launch (bytes): FETCH_SIZE + WRITE_SIZE from the two rocprofv3 --pmc runs summarised under
+# profiles/<workload>.md, each scaled by what the same counter reads for the 64 MiB copy kernel (x2.0 and x1.0).
+# They are properties of the default kernel variants; --traffic-bytes overrides them after a fresh profile.
+MEASURED_TRAFFIC = {
+    "gemm_bf16_4096": 201.6e6 + 67.2e6,
+    "resnet_conv_bf16": 16.9e6 + 25.7e6,
+    "conv7x7_s2_int8": 4.0e6 + 62.5e6,
+    "maxpool_f32": 133.5e6 + 25.7e6,
+}
+
 # workload -> (metric unit, bound, arithmetic dtype)
 KIND = {
     "gemm_bf16_4096": ("TFLOP/s", "mfma", "bf16"),
@@ -34,6 +44,7 @@ KIND = {
     "conv7x7_s2_int8": ("TOP/s", "hbm", "int8"),
     "maxpool_f32": ("GB/s", "hbm", "f32"),
     "tiny_conv_f32": ("TFLOP/s", "hbm", "f32"),
+    "device_copy": ("GB/s", "hbm", "u8"),     # the plain copy kernel: calibrates traffic counters and the HBM yardstick
 }
 
 
@@ -45,8 +56,8 @@ def oracle_sample(name, root, inputs, cores):
     first = root.child
     lo, hi = [0] * len(first.ranges), list(first.ranges)
     if name == "gemm_bf16_4096":
-        hi[0] = 16                       # 16 full output rows, every k: 268 M points
-        sample, split = "16 of 4096 output rows (all n, all k), literal loops", 1
+        hi[0] = 32                       # 32 full output rows, every k: 537 M points
+        sample, split = "32 of 4096 output rows (all n, all k), literal loops", 1
     elif name == "resnet_conv_bf16":
         hi[0] = 2                        # 2 of 32 images: 231 M points
         sample, split = "2 of 32 images", 1
@@ -63,6 +74,35 @@ def oracle_sample(name, root, inputs, cores):
     res = O.evaluate(root, np_ins, window=(lo, hi), threads=cores, split_index=split)
     dt = time.perf_counter() - t0
     return res, dt, sample, (lo, hi)
+
+
+def bench_copy(args, torch, B):
+    """stripe_device_copy of 64 MiB (128 MiB of traffic) over rotating buffer pairs."""
+    dev = torch.device("cuda:0")
+    n = 64 << 20
+    pairs = [(torch.ones(n, dtype=torch.uint8, device=dev), torch.empty(n, dtype=torch.uint8, device=dev))
+             for _ in range(args.rotate if args.rotate > 0 else 6)]
+    stream = torch.cuda.current_stream()
+    for i in range(args.warmup):
+        s, d = pairs[i % len(pairs)]
+        B.stripe_device_copy(s.data_ptr(), d.data_ptr(), n, stream.cuda_stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for i in range(args.steps):
+        s, d = pairs[i % len(pairs)]
+        B.stripe_device_copy(s.data_ptr(), d.data_ptr(), n, stream.cuda_stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) / args.steps * 1e3
+    gbs = 2 * n / us / 1e3
+    print(json.dumps({"metric": "device copy bandwidth (yardstick)", "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5),
+                      "higher_is_better": True, "dtype": "u8", "data": "synthetic",
+                      "config": {"workload": "device_copy", "bytes_read": n, "bytes_written": n, "buffer_sets": len(pairs)},
+                      "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
+                                   "frac": round(gbs / PEAK["hbm_gbs"], 4), "traffic": None, "kernel": "copy_kernel",
+                                   "kernel_us": round(us, 2)}}), flush=True)
 
 
 def main():
@@ -88,6 +128,8 @@ def main():
     dev = torch.device("cuda:0")
     name = args.workload
     unit, bound, dtype = KIND[name]
+    if name == "device_copy":
+        return bench_copy(args, torch, B)
     root = W.config_block(name)
     inputs = W.config_inputs(name)
     blk = B.StripeBlock(root, args.path)
@@ -123,6 +165,9 @@ def main():
     kernel_s = gpu_ms / args.steps * 1e-3      # average launch duration over the timed region (events on the launch stream)
 
     work = info["work_points"]
+    traffic = args.traffic_bytes
+    if traffic is None and args.path == "auto" and not os.environ.get("STRIPE_TUNE"):
+        traffic = MEASURED_TRAFFIC.get(name)
     flops = 2.0 * work
     nbytes = float(info["algorithmic_bytes"])
     if unit == "GB/s":
@@ -133,11 +178,11 @@ def main():
         peak = PEAK["int8_mfma_tops"] if dtype == "int8" else PEAK["bf16_mfma_tflops"]
         achieved = flops / kernel_s / 1e12
         roof = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
-                "frac": round(achieved / peak, 4), "traffic": args.traffic_bytes}
+                "frac": round(achieved / peak, 4), "traffic": traffic}
     else:
         achieved = nbytes / kernel_s / 1e9
         roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
-                "frac": round(achieved / PEAK["hbm_gbs"], 4), "traffic": args.traffic_bytes}
+                "frac": round(achieved / PEAK["hbm_gbs"], 4), "traffic": traffic}
     roof["kernel"] = info["kernel"]
     roof["kernel_us"] = round(kernel_s * 1e6, 2)
     roof["algorithmic_bytes"] = info["algorithmic_bytes"]
