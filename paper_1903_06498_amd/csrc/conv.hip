@@ -198,7 +198,7 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
 }
 
 hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
-  if (l.variant == 100) return launch_conv_i8(c, l, in, flt, out, st);
+  if (l.variant >= 100) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
   const int rows = l.variant;
   const ConvParams p = make_params(c, rows);

@@ -14,10 +14,9 @@
 // 16 output columns x 16 output channels; the 7 filter rows take 4 K steps (the
 // eighth row has zero weights).
 //
-// Nesting: outer block -> workgroup per strip of TY output rows of one image;
-// middle block -> the strip's 2*TY+5 image rows, expanded, in LDS (about 70 KB,
-// two workgroups per CU so one strip's stores overlap the next one's staging);
-// inner block -> one wavefront per output row, 7 x 4 fragments of 16 x 16.
+// Nesting: outer block -> strips of TY output rows of one image, walked by
+// persistent workgroups; middle block -> the strip's 2*TY+5 image rows, expanded,
+// in LDS; inner block -> one wavefront per output row, 7 x 4 fragments of 16 x 16.
 #include <hip/hip_runtime.h>
 
 #include "kernels.hpp"
@@ -28,48 +27,77 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
-constexpr int Q_TY = 4;                        // output rows per strip = wavefronts per workgroup
-constexpr int Q_ROWS = 2 * Q_TY + 5;           // image rows a strip touches
 constexpr int Q_CO = 64, Q_R = 7, Q_S = 7, Q_CI = 3;
 constexpr int Q_MAX_WO = 112;                  // 7 column fragments of 16
 constexpr int Q_BT_BYTES = 4 * Q_CO * 64;      // filter as K vectors: [K step][k][64 B]
 
 struct I8Params {
-  int32_t H, W, Ho, Wo, strips_per_image, raw_row_bytes;
+  int32_t H, W, Ho, Wo, strips_per_image, raw_row_bytes, total_strips, pad_;
   int64_t i_n, i_y;            // input strides in elements (= bytes); pixels and channels are contiguous
   int64_t o_n, o_y, o_x;       // output strides in elements; channels contiguous
   int64_t i_base, f_base, o_base;
 };
 
-// LDS: [Bt: 16 KB][raw: Q_ROWS x raw_row_bytes][E: Q_ROWS x Wo x 32 B]
+// Raw chunks of one strip, global -> registers (zero where outside the image or in the row padding).
+template <int Q_TY, int RAWQ>
+__device__ __forceinline__ void q_load_raw(const I8Params& p, const int8_t* __restrict__ I, int strip, int t, u32x4 (&rv)[RAWQ]) {
+  constexpr int Q_ROWS = 2 * Q_TY + 5, NT = Q_TY * 64;
+  const int row_chunks = p.raw_row_bytes / 16;          // 16 zero bytes, W*3 data bytes, 16 zero bytes
+  const int data_chunks = (p.W * Q_CI) / 16;
+  const int n = strip / p.strips_per_image;
+  const int y0 = (strip - n * p.strips_per_image) * Q_TY;
+  const int8_t* ig = I + p.i_base + (int64_t)n * p.i_n;
+#pragma unroll
+  for (int u = 0; u < RAWQ; ++u) {
+    const int q = t + u * NT;
+    const int r = q / row_chunks, c = q - r * row_chunks;
+    const int y = 2 * y0 - 3 + r;
+    rv[u] = (u32x4){0u, 0u, 0u, 0u};
+    if (strip < p.total_strips && q < Q_ROWS * row_chunks && c >= 1 && c <= data_chunks && y >= 0 && y < p.H)
+      rv[u] = *(const u32x4*)(ig + (int64_t)y * p.i_y + (c - 1) * 16);
+  }
+}
+
+// Persistent workgroups: each builds the filter's K vectors once, then walks strips
+// blockIdx.x, blockIdx.x + gridDim.x, ...  The raw rows of the next strip are fetched
+// into registers while the current strip is expanded, multiplied and stored, and the
+// stores of a strip (fire and forget) overlap the staging of the next one.
+// LDS: [Bt: 16 KB][raw: Q_ROWS x raw_row_bytes][E: Q_ROWS x Wo x 32 B][output transposition: 4 KB per wavefront]
+template <int Q_TY>   // output rows per strip = wavefronts per workgroup
 __global__ __launch_bounds__(Q_TY * 64) void conv7x7s2_i8_kernel(const I8Params p, const int8_t* __restrict__ I,
                                                                const int8_t* __restrict__ F, int32_t* __restrict__ O) {
+  constexpr int Q_ROWS = 2 * Q_TY + 5;           // image rows a strip touches
+  constexpr int NT = Q_TY * 64;
+  constexpr int RAWQ = 4, FQ = 5;                 // >= ceil(Q_ROWS*46/NT) and ceil(588/NT) for every strip height
+  constexpr int F_BYTES = Q_R * Q_S * Q_CO * Q_CI;   // 9,408 = 588 chunks of 16
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   unsigned char* bt = lds;
   unsigned char* raw = lds + Q_BT_BYTES;
   unsigned char* ex = raw + Q_ROWS * p.raw_row_bytes;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int n = blockIdx.x / p.strips_per_image;
-  const int y0 = (blockIdx.x % p.strips_per_image) * Q_TY;
-  const int row_chunks = p.raw_row_bytes / 16;          // 16 zero bytes, W*3 data bytes, >= 16 zero bytes
-  const int data_chunks = (p.W * Q_CI) / 16;
+  unsigned char* ot = ex + Q_ROWS * p.Wo * 32 + wave * 4096;   // this wavefront's output transposition buffer
+  const int row_chunks = p.raw_row_bytes / 16;
 
-  // ---- raw image rows 2*y0-3 .. 2*y0+2*TY+1, zero where outside the image ----
-  const int8_t* ig = I + p.i_base + (int64_t)n * p.i_n;
-  for (int q = t; q < Q_ROWS * row_chunks; q += Q_TY * 64) {
-    const int r = q / row_chunks, c = q - r * row_chunks;
-    const int y = 2 * y0 - 3 + r;
-    u32x4 v = {0u, 0u, 0u, 0u};
-    if (c >= 1 && c <= data_chunks && y >= 0 && y < p.H) v = *(const u32x4*)(ig + (int64_t)y * p.i_y + (c - 1) * 16);
-    *(u32x4*)(raw + r * p.raw_row_bytes + c * 16) = v;
-  }
-  // ---- the filter as it lies in memory (9,408 bytes), parked where E will be built later ----
+  // ---- first strip's rows and the filter as it lies in memory (parked where E is built later);
+  // all global loads of a lane are issued before the first LDS store so that their latencies overlap
+  int strip = blockIdx.x;
+  u32x4 rv[RAWQ], fv[FQ];
+  q_load_raw<Q_TY, RAWQ>(p, I, strip, t, rv);
   const u32x4* fg = (const u32x4*)(F + p.f_base);
-  constexpr int F_BYTES = Q_R * Q_S * Q_CO * Q_CI;        // 9,408 = 588 chunks of 16
-  for (int q = t; q < F_BYTES / 16; q += Q_TY * 64) *(u32x4*)(ex + q * 16) = fg[q];
+#pragma unroll
+  for (int u = 0; u < FQ; ++u) {
+    const int q = t + u * NT;
+    fv[u] = (u32x4){0u, 0u, 0u, 0u};
+    if (q < F_BYTES / 16) fv[u] = fg[q];
+  }
+#pragma unroll
+  for (int u = 0; u < FQ; ++u) {
+    const int q = t + u * NT;
+    if (q < F_BYTES / 16) *(u32x4*)(ex + q * 16) = fv[u];
+  }
   __syncthreads();
   // ---- filter as K vectors: Bt[ks][k][0..31] = F[2ks][*][k][*] (21 B, then zeros), [32..63] = F[2ks+1][...] ----
-  for (int q = t; q < 8 * Q_CO; q += Q_TY * 64) {
+  for (int q = t; q < 8 * Q_CO; q += NT) {
     const int i = q / Q_CO, k = q - i * Q_CO;           // filter row (7 = the all-zero eighth row), output channel
     unsigned w[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
     if (i < Q_R) {
@@ -85,76 +113,107 @@ __global__ __launch_bounds__(Q_TY * 64) void conv7x7s2_i8_kernel(const I8Params 
     *(u32x4*)(dst + 16) = (u32x4){w[4], w[5], w[6], w[7]};
   }
   __syncthreads();
-
-  // ---- expand: E[r][x] = raw[r] bytes 16 + 6x - 9 .. +23 (16 + (2x-3)*3 is where column 2x-3 starts) ----
-  for (int q = t; q < Q_ROWS * p.Wo; q += Q_TY * 64) {
-    const int r = q / p.Wo, x = q - r * p.Wo;
-    const int start = 6 * x + 7;
-    const unsigned* src = (const unsigned*)(raw + r * p.raw_row_bytes + (start & ~3));
-    const unsigned sh = start & 3;
-    unsigned d[7];
-#pragma unroll
-    for (int u = 0; u < 7; ++u) d[u] = src[u];
-    unsigned e[6];
-#pragma unroll
-    for (int u = 0; u < 6; ++u) e[u] = __builtin_amdgcn_alignbyte(d[u + 1], d[u], sh);
-    e[5] &= 0x000000ffu;                                  // byte 20 is the last of the 21
-    // the two 16-byte halves of a vector swap places for every second group of 8 columns (bank spread)
-    unsigned char* dst = ex + (r * p.Wo + x) * 32;
-    const int flip = ((x >> 3) & 1) * 16;
-    *(u32x4*)(dst + flip) = (u32x4){e[0], e[1], e[2], e[3]};
-    *(u32x4*)(dst + (16 - flip)) = (u32x4){e[4], e[5], 0u, 0u};
-  }
-  __syncthreads();
-
-  // ---- one wavefront per output row ----
-  const int y = y0 + wave;
-  if (y >= p.Ho) return;
+  // B fragments stay in registers for the workgroup's lifetime: [K step][channel fragment]
   const int fr = lane & 15, kq = lane >> 4;              // fragment row / 16-byte K block of the lane
-  // B fragments stay in registers: [K step][channel fragment]
   i32x4 bfr[4][4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
     for (int nf = 0; nf < 4; ++nf) bfr[ks][nf] = *(const i32x4*)(bt + (ks * Q_CO + nf * 16 + fr) * 64 + kq * 16);
 
-  const int n_mf = p.Wo / 16;
-  int32_t* og = O + p.o_base + (int64_t)n * p.o_n + (int64_t)y * p.o_y + fr;
-  for (int mf = 0; mf < n_mf; ++mf) {
-    const int x = mf * 16 + fr;
-    i32x4 acc[4];
+  for (; strip < p.total_strips; strip += gridDim.x) {
+    const int n = strip / p.strips_per_image;
+    const int y0 = (strip - n * p.strips_per_image) * Q_TY;
+    // ---- this strip's raw rows: registers -> LDS (rows back to back: r*raw_row_bytes + c*16 = q*16)
 #pragma unroll
-    for (int nf = 0; nf < 4; ++nf) acc[nf] = (i32x4){0, 0, 0, 0};
-#pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-      int r = 2 * wave + 2 * ks + (kq >> 1);              // image row 2y + i - 3 relative to the strip's first row
-      r = r < Q_ROWS ? r : Q_ROWS - 1;                    // the eighth filter row has zero weights: any row will do
-      const int half = ((kq & 1) ^ ((x >> 3) & 1)) * 16;
-      const i32x4 a = *(const i32x4*)(ex + (r * p.Wo + x) * 32 + half);
-#pragma unroll
-      for (int nf = 0; nf < 4; ++nf) acc[nf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(a, bfr[ks][nf], acc[nf], 0, 0, 0);
+    for (int u = 0; u < RAWQ; ++u) {
+      const int q = t + u * NT;
+      if (q < Q_ROWS * row_chunks) *(u32x4*)(raw + q * 16) = rv[u];
     }
-    // accumulator element v of lane l: column 4*(l>>4) + v of the fragment, channel l&15
+    __syncthreads();
+    // ---- next strip's raw rows: global -> registers, in flight during the rest of this iteration
+    q_load_raw<Q_TY, RAWQ>(p, I, strip + gridDim.x, t, rv);
+
+    // ---- expand: E[r][x] = raw[r] bytes 16 + 6x - 9 .. +23 (16 + (2x-3)*3 is where column 2x-3 starts) ----
+    for (int q = t; q < Q_ROWS * p.Wo; q += NT) {
+      const int r = q / p.Wo, x = q - r * p.Wo;
+      const int start = 6 * x + 7;
+      const unsigned* src = (const unsigned*)(raw + r * p.raw_row_bytes + (start & ~3));
+      const unsigned sh = start & 3;
+      unsigned d[7];
 #pragma unroll
-    for (int nf = 0; nf < 4; ++nf)
+      for (int u = 0; u < 7; ++u) d[u] = src[u];
+      unsigned e[6];
 #pragma unroll
-      for (int v = 0; v < 4; ++v)
-        __builtin_nontemporal_store(acc[nf][v], og + (int64_t)(mf * 16 + 4 * kq + v) * p.o_x + nf * 16);
+      for (int u = 0; u < 6; ++u) e[u] = __builtin_amdgcn_alignbyte(d[u + 1], d[u], sh);
+      e[5] &= 0x000000ffu;                                  // byte 20 is the last of the 21
+      // the two 16-byte halves of a vector swap places for every second group of 8 columns (bank spread)
+      unsigned char* dst = ex + (r * p.Wo + x) * 32;
+      const int flip = ((x >> 3) & 1) * 16;
+      *(u32x4*)(dst + flip) = (u32x4){e[0], e[1], e[2], e[3]};
+      *(u32x4*)(dst + (16 - flip)) = (u32x4){e[4], e[5], 0u, 0u};
+    }
+    __syncthreads();
+
+    // ---- one wavefront per output row ----
+    const int y = y0 + wave;
+    if (y < p.Ho) {
+      const int n_mf = p.Wo / 16;
+      int32_t* og = O + p.o_base + (int64_t)n * p.o_n + (int64_t)y * p.o_y;
+      for (int mf = 0; mf < n_mf; ++mf) {
+        const int x = mf * 16 + fr;
+        i32x4 acc[4];
+#pragma unroll
+        for (int nf = 0; nf < 4; ++nf) acc[nf] = (i32x4){0, 0, 0, 0};
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+          int r = 2 * wave + 2 * ks + (kq >> 1);              // image row 2y + i - 3 relative to the strip's first row
+          r = r < Q_ROWS ? r : Q_ROWS - 1;                    // the eighth filter row has zero weights: any row will do
+          const int half = ((kq & 1) ^ ((x >> 3) & 1)) * 16;
+          const i32x4 a = *(const i32x4*)(ex + (r * p.Wo + x) * 32 + half);
+#pragma unroll
+          // filter fragment as the row operand, pixels as the column operand: the result fragment is
+          // (channel, pixel) and a lane ends up with 4 consecutive channels of one pixel -> one 16-byte store
+          for (int nf = 0; nf < 4; ++nf) acc[nf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bfr[ks][nf], a, acc[nf], 0, 0, 0);
+        }
+        // accumulator element v of lane l: channel 4*(l>>4) + v of the fragment, pixel l&15.  The 16 x 64
+        // tile goes through a per-wavefront 4 KB LDS buffer (16-byte slots XOR-swizzled with the pixel) so that
+        // every store instruction writes 4 whole pixels = 1 KB of consecutive addresses when pixels are contiguous.
+#pragma unroll
+        for (int nf = 0; nf < 4; ++nf) *(i32x4*)(ot + fr * 256 + (((nf * 4 + kq) ^ fr) << 4)) = acc[nf];
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int px = 4 * j + kq;                        // pixel of the tile this lane stores for, slot fr
+          const i32x4 v = *(const i32x4*)(ot + px * 256 + ((fr ^ px) << 4));
+          *(i32x4*)(og + (int64_t)(mf * 16 + px) * p.o_x + fr * 4) = v;
+        }
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+    __syncthreads();   // E and raw are rewritten by the next strip
   }
 }
 
-I8Params make_params(const Conv2dShape& c) {
+I8Params make_params(const Conv2dShape& c, int Q_TY) {
   I8Params p;
   p.H = (int)c.H; p.W = (int)c.W; p.Ho = (int)c.Ho; p.Wo = (int)c.Wo;
   p.strips_per_image = (int)((c.Ho + Q_TY - 1) / Q_TY);
   p.raw_row_bytes = 16 + (int)c.W * Q_CI + 16;
+  p.total_strips = (int)c.N * p.strips_per_image;
+  p.pad_ = 0;
   p.i_n = c.i_n; p.i_y = c.i_y;
   p.o_n = c.o_n; p.o_y = c.o_y; p.o_x = c.o_x;
   p.i_base = c.i_base; p.f_base = c.f_base; p.o_base = c.o_base;
   return p;
 }
 
-int lds_bytes_for(const I8Params& p) { return Q_BT_BYTES + Q_ROWS * p.raw_row_bytes + Q_ROWS * p.Wo * 32; }
+int lds_bytes_for(const I8Params& p, int Q_TY) {
+  const int Q_ROWS = 2 * Q_TY + 5;
+  return Q_BT_BYTES + Q_ROWS * p.raw_row_bytes + Q_ROWS * p.Wo * 32 + Q_TY * 4096;
+}
+
+constexpr int kStripChoices[] = {2, 4, 7, 8};
 
 }  // namespace
 
@@ -166,40 +225,66 @@ bool conv_i8_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_bl
   // pixels and channels contiguous in a row, rows 16-byte aligned; filter [i][j][k][c] contiguous
   if (c.i_c != 1 || c.i_x != Q_CI || c.i_y % 16 || c.i_n % 16 || c.i_base % 16) return false;
   if (c.f_c != 1 || c.f_k != Q_CI || c.f_s != Q_CO * Q_CI || c.f_r != Q_S * Q_CO * Q_CI || c.f_base % 16) return false;
+
+  if (c.o_k != 1 || c.o_x % 4 || c.o_y % 4 || c.o_n % 4 || c.o_base % 4) return false;   // 16-byte stores
+  int Q_TY = tune_int("conv_i8_rows", 7);
+  bool known = false;
+  for (int v : kStripChoices) known = known || v == Q_TY;
+  if (!known) Q_TY = 7;
+  const int Q_ROWS = 2 * Q_TY + 5;
   if (Q_ROWS * (c.W / 2) * 32 < Q_R * Q_S * Q_CO * Q_CI) return false;   // the raw filter is parked in E's space
-  if (c.o_k != 1) return false;
-  const I8Params p = make_params(c);
-  const int64_t grid = c.N * p.strips_per_image;
-  if (grid > 0x7fffffffLL || lds_bytes_for(p) > 160 * 1024) return false;
-  l->variant = 100;
+  const I8Params p = make_params(c, Q_TY);
+  if (c.N * (int64_t)p.strips_per_image > 0x7fffffffLL || lds_bytes_for(p, Q_TY) > 160 * 1024) return false;
+  // persistent workgroups: as many as fit on the chip at once (LDS-limited), at most one per strip
+  const int per_cu = (160 * 1024) / lds_bytes_for(p, Q_TY);
+  int64_t grid = (int64_t)tune_int("conv_i8_wg_per_cu", per_cu > 2 ? 2 : per_cu) * 256;
+  if (grid > p.total_strips) grid = p.total_strips;
+  if (grid < 1) grid = 1;
+  if ((int64_t)Q_ROWS * (p.raw_row_bytes / 16) > 4 * Q_TY * 64) return false;   // a lane stages at most 4 row chunks
+  l->variant = 100 + Q_TY;
   l->grid = grid;
   info->path = STRIPE_PATH_MFMA_CONV;
   info->tile_m = Q_TY * (int)c.Wo;
   info->tile_n = Q_CO;
   info->tile_k = 4 * 64;
   info->frag_m = 16; info->frag_n = 16; info->frag_k = 64;
-  info->lds_bytes = lds_bytes_for(p);
+  info->lds_bytes = lds_bytes_for(p, Q_TY);
   info->workgroup_size = Q_TY * 64;
   info->grid = grid;
   snprintf(info->kernel, sizeof info->kernel, "conv7x7s2_i8_c3k64_strip%d_mfma16x16x64", Q_TY);
   return true;
 }
 
-hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
-  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
-  const I8Params p = make_params(c);
-  const int lds_bytes = lds_bytes_for(p);
+namespace {
+
+template <int Q_TY>
+hipError_t launch_rows(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
+  const I8Params p = make_params(c, Q_TY);
+  const int lds_bytes = lds_bytes_for(p, Q_TY);
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
   if (dev != l.lds_enabled_on) {
-    e = hipFuncSetAttribute((const void*)conv7x7s2_i8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+    e = hipFuncSetAttribute((const void*)conv7x7s2_i8_kernel<Q_TY>, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
     if (e != hipSuccess) return e;
     l.lds_enabled_on = dev;
   }
-  hipLaunchKernelGGL(conv7x7s2_i8_kernel, dim3((unsigned)l.grid), dim3(Q_TY * 64), lds_bytes, st, p, (const int8_t*)in,
+  hipLaunchKernelGGL(conv7x7s2_i8_kernel<Q_TY>, dim3((unsigned)l.grid), dim3(Q_TY * 64), lds_bytes, st, p, (const int8_t*)in,
                      (const int8_t*)flt, (int32_t*)out);
   return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
+  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
+  switch (l.variant - 100) {
+    case 2: return launch_rows<2>(c, l, in, flt, out, st);
+    case 7: return launch_rows<7>(c, l, in, flt, out, st);
+    case 8: return launch_rows<8>(c, l, in, flt, out, st);
+    case 4: return launch_rows<4>(c, l, in, flt, out, st);
+    default: return launch_rows<7>(c, l, in, flt, out, st);
+  }
 }
 
 }  // namespace stripe

@@ -419,110 +419,131 @@ __device__ __forceinline__ void d_load_lds16(const uint16_t* src, unsigned lds_o
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform_off) : "memory", "m0");
 }
 
-template <int STAGE_N>
-__device__ __forceinline__ void d_issue_loads(const DCtx& c, int kt) {
-  const uint16_t* a = c.a_src + (size_t)kt * D_BK;
-  const uint16_t* b = c.b_src + (size_t)kt * c.b_kstep;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) d_load_lds16(a + u * c.a_step, STAGE_N * D_A_STAGE + u * 4096 + c.wave_lds);
-#pragma unroll
-  for (int u = 0; u < 4; ++u) d_load_lds16(b + u * c.b_step, D_B0 + STAGE_N * D_B_STAGE + u * 4096 + c.wave_lds);
-}
-
-// Fragment q of K step S of a stage: one 16-byte read for A rows 32q.., two transposing reads for B columns 32q..
+// A fragment q of K step S of a stage: rows 32q.. of the wavefront's 128 rows, one 16-byte read.
 template <int STAGE_N, int S, int Q>
-__device__ __forceinline__ void d_read_frag(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
-  typedef __attribute__((address_space(3))) s16x4* lptr;
+__device__ __forceinline__ void d_read_a(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4]) {
   af[Q] = *(const bf16x8*)(lds + (c.a_fr ^ (S << 5)) + (STAGE_N * D_A_STAGE + Q * 32 * 64));
+}
+// B fragment q of K step S of a stage: columns 32q.. of the wavefront's columns, two transposing 8-byte reads.
+template <int STAGE_N, int S, int Q, int FN>
+__device__ __forceinline__ void d_read_b(const DCtx& c, const unsigned char* lds, bf16x8 (&bf)[FN]) {
+  typedef __attribute__((address_space(3))) s16x4* lptr;
   const unsigned char* p = lds + c.b_fr[Q] + (STAGE_N * D_B_STAGE + S * 16 * 512);
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)p);
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 4 * 512));
   bf[Q] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
-
-template <int STAGE_N, int S>
-__device__ __forceinline__ void d_read_frags(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[4]) {
-  d_read_frag<STAGE_N, S, 0>(c, lds, af, bf);
-  d_read_frag<STAGE_N, S, 1>(c, lds, af, bf);
-  d_read_frag<STAGE_N, S, 2>(c, lds, af, bf);
-  d_read_frag<STAGE_N, S, 3>(c, lds, af, bf);
+// fragments of group Q (of 4) of a K step: A fragment Q, and B fragment Q while there are any left
+template <int STAGE_N, int S, int Q, int FN>
+__device__ __forceinline__ void d_read_group(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[FN]) {
+  d_read_a<STAGE_N, S, Q>(c, lds, af);
+  if constexpr (Q < FN) d_read_b<STAGE_N, S, Q, FN>(c, lds, bf);
+}
+template <int STAGE_N, int S, int FN>
+__device__ __forceinline__ void d_read_frags(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[FN]) {
+  d_read_group<STAGE_N, S, 0, FN>(c, lds, af, bf);
+  d_read_group<STAGE_N, S, 1, FN>(c, lds, af, bf);
+  d_read_group<STAGE_N, S, 2, FN>(c, lds, af, bf);
+  d_read_group<STAGE_N, S, 3, FN>(c, lds, af, bf);
 }
 
-template <int Q>
-__device__ __forceinline__ void d_mfma_row(const bf16x8 (&af)[4], const bf16x8 (&bf)[4], f32x16 (&acc)[4][4]) {
+template <int Q, int FN>
+__device__ __forceinline__ void d_mfma_row(const bf16x8 (&af)[4], const bf16x8 (&bf)[FN], f32x16 (&acc)[4][FN]) {
 #pragma unroll
-  for (int j = 0; j < 4; ++j) acc[Q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[Q], bf[j], acc[Q][j], 0, 0, 0);
+  for (int j = 0; j < FN; ++j) acc[Q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[Q], bf[j], acc[Q][j], 0, 0, 0);
 }
 
 #define D_FENCE() __builtin_amdgcn_sched_barrier(0)
 
-// One K tile of the ring, as eight groups of four matrix instructions.  The
+// LDS-direct loads number G*PER .. G*PER+PER-1 of a tile (PER per group); loads 0..LPT/2-1 are A, the rest B
+template <int LD, int WAVES, int G>
+__device__ __forceinline__ void d_issue_group(const DCtx& c, const uint16_t* a, const uint16_t* b) {
+  constexpr int LPT = 32 / WAVES, HALF = LPT / 2, PER = LPT / 4 > 0 ? LPT / 4 : 1;
+#pragma unroll
+  for (int e = 0; e < PER; ++e) {
+    const int u = G * PER + e;
+    if (u < HALF) d_load_lds16(a + u * c.a_step, LD * D_A_STAGE + u * (1024 * WAVES) + c.wave_lds);
+    else if (u < LPT) d_load_lds16(b + (u - HALF) * c.b_step, D_B0 + LD * D_B_STAGE + (u - HALF) * (1024 * WAVES) + c.wave_lds);
+  }
+}
+
+template <int PENDING>
+__device__ __forceinline__ void d_wait_loads() {
+  if (PENDING == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else if (PENDING == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// One K tile of the ring, as eight groups of matrix instructions.  The
 // scheduler may not move anything across a fence, so every group carries the
 // LDS reads (and, in the second half, the LDS-direct loads) written next to it:
 //   groups 0-3: K step 0 of this tile  + fragment reads of K step 1,
 //   barrier   : tile kt+1 complete in LDS (its loads were issued two tiles ago),
 //   groups 4-7: K step 1 of this tile  + fragment reads of K step 0 of tile kt+1
-//               + the loads of tile kt+3, two per group.
+//               + the loads of tile kt+3.
 // ISSUE: start the loads of tile kt+3 (after the barrier).  PENDING: how many
-// younger loads (8 per tile: those of tile kt+2) may still be in flight when
-// tile kt+1 must have landed.
-template <int STAGE_N, bool ISSUE, int PENDING, bool NEXT_FRAGS>
-__device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt, bf16x8 (&af)[2][4], bf16x8 (&bf)[2][4],
-                                       f32x16 (&acc)[4][4]) {
+// younger loads (those of tile kt+2) may still be in flight when tile kt+1 must
+// have landed.
+template <int WAVES, int STAGE_N, bool ISSUE, int PENDING, bool NEXT_FRAGS>
+__device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt, bf16x8 (&af)[2][4],
+                                       bf16x8 (&bf)[2][WAVES == 4 ? 4 : 2], f32x16 (&acc)[4][WAVES == 4 ? 4 : 2]) {
+  constexpr int FN = WAVES == 4 ? 4 : 2;
   constexpr int NXT = (STAGE_N + 1) % D_STAGES;
   constexpr int LD = (STAGE_N + 3) % D_STAGES;
   const uint16_t* a = c.a_src + (size_t)(kt + 3) * D_BK;
   const uint16_t* b = c.b_src + (size_t)(kt + 3) * c.b_kstep;
   D_FENCE();
-  d_mfma_row<0>(af[0], bf[0], acc); d_read_frag<STAGE_N, 1, 0>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<1>(af[0], bf[0], acc); d_read_frag<STAGE_N, 1, 1>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<2>(af[0], bf[0], acc); d_read_frag<STAGE_N, 1, 2>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<3>(af[0], bf[0], acc); d_read_frag<STAGE_N, 1, 3>(c, lds, af[1], bf[1]); D_FENCE();
-  if (PENDING == 16) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-  else if (PENDING == 8) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  d_mfma_row<0, FN>(af[0], bf[0], acc); d_read_group<STAGE_N, 1, 0, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<1, FN>(af[0], bf[0], acc); d_read_group<STAGE_N, 1, 1, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<2, FN>(af[0], bf[0], acc); d_read_group<STAGE_N, 1, 2, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<3, FN>(af[0], bf[0], acc); d_read_group<STAGE_N, 1, 3, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  d_wait_loads<PENDING>();
   __syncthreads();
   D_FENCE();
-  d_mfma_row<0>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_frag<NXT, 0, 0>(c, lds, af[0], bf[0]);
-  if (ISSUE) { d_load_lds16(a, LD * D_A_STAGE + c.wave_lds); d_load_lds16(a + c.a_step, LD * D_A_STAGE + 4096 + c.wave_lds); }
+  d_mfma_row<0, FN>(af[1], bf[1], acc);
+  if (NEXT_FRAGS) d_read_group<NXT, 0, 0, FN>(c, lds, af[0], bf[0]);
+  if (ISSUE) d_issue_group<LD, WAVES, 0>(c, a, b);
   D_FENCE();
-  d_mfma_row<1>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_frag<NXT, 0, 1>(c, lds, af[0], bf[0]);
-  if (ISSUE) { d_load_lds16(a + 2 * c.a_step, LD * D_A_STAGE + 8192 + c.wave_lds); d_load_lds16(a + 3 * c.a_step, LD * D_A_STAGE + 12288 + c.wave_lds); }
+  d_mfma_row<1, FN>(af[1], bf[1], acc);
+  if (NEXT_FRAGS) d_read_group<NXT, 0, 1, FN>(c, lds, af[0], bf[0]);
+  if (ISSUE) d_issue_group<LD, WAVES, 1>(c, a, b);
   D_FENCE();
-  d_mfma_row<2>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_frag<NXT, 0, 2>(c, lds, af[0], bf[0]);
-  if (ISSUE) { d_load_lds16(b, D_B0 + LD * D_B_STAGE + c.wave_lds); d_load_lds16(b + c.b_step, D_B0 + LD * D_B_STAGE + 4096 + c.wave_lds); }
+  d_mfma_row<2, FN>(af[1], bf[1], acc);
+  if (NEXT_FRAGS) d_read_group<NXT, 0, 2, FN>(c, lds, af[0], bf[0]);
+  if (ISSUE) d_issue_group<LD, WAVES, 2>(c, a, b);
   D_FENCE();
-  d_mfma_row<3>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_frag<NXT, 0, 3>(c, lds, af[0], bf[0]);
-  if (ISSUE) { d_load_lds16(b + 2 * c.b_step, D_B0 + LD * D_B_STAGE + 8192 + c.wave_lds); d_load_lds16(b + 3 * c.b_step, D_B0 + LD * D_B_STAGE + 12288 + c.wave_lds); }
+  d_mfma_row<3, FN>(af[1], bf[1], acc);
+  if (NEXT_FRAGS) d_read_group<NXT, 0, 3, FN>(c, lds, af[0], bf[0]);
+  if (ISSUE) d_issue_group<LD, WAVES, 3>(c, a, b);
   D_FENCE();
 }
 
-__global__ __launch_bounds__(W4_THREADS, 1) void gemm_bf16_dma_kernel(const GemmParams p, const uint16_t* __restrict__ A,
+template <int WAVES>
+__global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const GemmParams p, const uint16_t* __restrict__ A,
                                                                       const uint16_t* __restrict__ B, float* __restrict__ C) {
+  constexpr int FN = WAVES == 4 ? 4 : 2;        // 32-column fragments per wavefront
+  constexpr int WN_WAVES = WAVES / 2;           // wavefronts side by side along n
+  constexpr int LPT = 32 / WAVES;               // LDS-direct loads per lane and tile
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN_WAVES, wn = wave % WN_WAVES;
   int tm, tn;
   tile_of(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, &tm, &tn);
 
   DCtx c;
-  // A loads: load u of wavefront w fills LDS rows 16*(4u+w) .. +15 of the stage (1 KB): lane -> row + lane/4, slot lane&3
+  // A loads: load u of wavefront w fills LDS rows 16*(WAVES*u+w) .. +15 of the stage (1 KB): lane -> row + lane/4, slot lane&3
   {
-    const int row = 16 * wave + (lane >> 2);           // + 64*u
+    const int row = 16 * wave + (lane >> 2);           // + 16*WAVES*u
     const int chunk = (lane & 3) ^ ((row >> 2) & 3);   // (row>>2)&3 does not change with u
     c.a_src = A + p.a_base + ((int64_t)tm * BM + row) * p.a_m + chunk * 8;
-    c.a_step = (size_t)64 * p.a_m;
+    c.a_step = (size_t)(16 * WAVES) * p.a_m;
   }
-  // B loads: load u of wavefront w fills k rows 2*(4u+w), +1: lane -> k = 2*(4u+w) + lane/32, slot lane&31
+  // B loads: load u of wavefront w fills k rows 2*(WAVES*u+w), +1: lane -> k = 2*(WAVES*u+w) + lane/32, slot lane&31
   {
-    const int k = 2 * wave + (lane >> 5);               // + 8*u ; k&3 does not change with u
+    const int k = 2 * wave + (lane >> 5);               // + 2*WAVES*u ; k&3 does not change with u
     const int chunk = (lane & 31) ^ (4 * (k & 3));
     c.b_src = B + p.b_base + (int64_t)k * p.b_k + (int64_t)tn * BN + chunk * 8;
-    c.b_step = (size_t)8 * p.b_k;
+    c.b_step = (size_t)(2 * WAVES) * p.b_k;
     c.b_kstep = (size_t)D_BK * p.b_k;
   }
   c.wave_lds = wave * 1024;
@@ -532,53 +553,59 @@ __global__ __launch_bounds__(W4_THREADS, 1) void gemm_bf16_dma_kernel(const Gemm
     c.a_fr = (wm * 128 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4);
   }
   // B fragments: 16-lane group g, lane p in it: k = 8*(g>>1) + (p>>2) (+16*s, +4 second read),
-  // columns wn*128 + 32*j + 16*(g&1) + 4*(p&3) .. +3
+  // columns wn*32*FN + 32*j + 16*(g&1) + 4*(p&3) .. +3
   {
     const int g = lane >> 4, pl = lane & 15;
     const int k = 8 * (g >> 1) + (pl >> 2);
     const int low2 = 2 * (g & 1) + ((pl & 3) >> 1);
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int chunk = (wn * 16 + 4 * j + low2) ^ (4 * (k & 3));
+      const int chunk = (wn * 4 * FN + 4 * (j < FN ? j : 0) + low2) ^ (4 * (k & 3));
       c.b_fr[j] = D_B0 + k * 512 + chunk * 16 + (pl & 1) * 8;
     }
   }
 
-  bf16x8 af[2][4], bf[2][4];
-  f32x16 acc[4][4];
+  bf16x8 af[2][4], bf[2][FN];
+  f32x16 acc[4][FN];
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // prologue: tiles 0, 1, 2 in flight, wait for tile 0   (k_tiles is a multiple of 4, checked on the host)
-  d_issue_loads<0>(c, 0);
-  d_issue_loads<1>(c, 1);
-  d_issue_loads<2>(c, 2);
-  asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+  {
+    const uint16_t* a = c.a_src;
+    const uint16_t* b = c.b_src;
+    d_issue_group<0, WAVES, 0>(c, a, b); d_issue_group<0, WAVES, 1>(c, a, b); d_issue_group<0, WAVES, 2>(c, a, b); d_issue_group<0, WAVES, 3>(c, a, b);
+    a += D_BK; b += c.b_kstep;
+    d_issue_group<1, WAVES, 0>(c, a, b); d_issue_group<1, WAVES, 1>(c, a, b); d_issue_group<1, WAVES, 2>(c, a, b); d_issue_group<1, WAVES, 3>(c, a, b);
+    a += D_BK; b += c.b_kstep;
+    d_issue_group<2, WAVES, 0>(c, a, b); d_issue_group<2, WAVES, 1>(c, a, b); d_issue_group<2, WAVES, 2>(c, a, b); d_issue_group<2, WAVES, 3>(c, a, b);
+  }
+  d_wait_loads<2 * LPT>();
   __syncthreads();
-  d_read_frags<0, 0>(c, lds, af[0], bf[0]);
+  d_read_frags<0, 0, FN>(c, lds, af[0], bf[0]);
 
   const int last4 = p.k_tiles - 4;
   for (int kt = 0; kt < last4; kt += 4) {
-    d_tile<0, true, 8, true>(c, lds, kt, af, bf, acc);
-    d_tile<1, true, 8, true>(c, lds, kt + 1, af, bf, acc);
-    d_tile<2, true, 8, true>(c, lds, kt + 2, af, bf, acc);
-    d_tile<3, true, 8, true>(c, lds, kt + 3, af, bf, acc);
+    d_tile<WAVES, 0, true, LPT, true>(c, lds, kt, af, bf, acc);
+    d_tile<WAVES, 1, true, LPT, true>(c, lds, kt + 1, af, bf, acc);
+    d_tile<WAVES, 2, true, LPT, true>(c, lds, kt + 2, af, bf, acc);
+    d_tile<WAVES, 3, true, LPT, true>(c, lds, kt + 3, af, bf, acc);
   }
-  d_tile<0, true, 8, true>(c, lds, last4, af, bf, acc);        // issues the last tile's loads
-  d_tile<1, false, 8, true>(c, lds, last4 + 1, af, bf, acc);
-  d_tile<2, false, 0, true>(c, lds, last4 + 2, af, bf, acc);
-  d_tile<3, false, 0, false>(c, lds, last4 + 3, af, bf, acc);
+  d_tile<WAVES, 0, true, LPT, true>(c, lds, last4, af, bf, acc);        // issues the last tile's loads
+  d_tile<WAVES, 1, false, LPT, true>(c, lds, last4 + 1, af, bf, acc);
+  d_tile<WAVES, 2, false, 0, true>(c, lds, last4 + 2, af, bf, acc);
+  d_tile<WAVES, 3, false, 0, false>(c, lds, last4 + 3, af, bf, acc);
 
   const int fr = lane & 31, fh = lane >> 5;
-  float* c_g = C + p.c_base + ((int64_t)tm * BM + wm * 128 + 4 * fh) * p.c_m + (int64_t)tn * BN + wn * 128 + fr;
+  float* c_g = C + p.c_base + ((int64_t)tm * BM + wm * 128 + 4 * fh) * p.c_m + (int64_t)tn * BN + wn * 32 * FN + fr;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
 #pragma unroll
-    for (int j = 0; j < 4; ++j)
+    for (int j = 0; j < FN; ++j)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int r = 32 * i + 8 * (v / 4) + (v % 4);
@@ -610,15 +637,16 @@ bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_i
   int waves = tune_int("gemm_waves", 4) == 8 ? 8 : 4;
   if ((g.K / BK) % 2) waves = 8;   // the four-wavefront pipeline consumes K tiles in pairs
   const bool dma = tune_int("gemm_dma", 1) != 0 && g.K % (D_BK * D_STAGES) == 0 && g.K >= D_BK * D_STAGES;
-  l->variant = dma ? 20 : (waves == 8 ? 10 : 0) + swz;
+  const int dma_waves = tune_int("gemm_dma_waves", 4) == 8 ? 8 : 4;
+  l->variant = dma ? (dma_waves == 8 ? 21 : 20) : (waves == 8 ? 10 : 0) + swz;
   l->grid = (g.M / BM) * (g.N / BN);
   info->path = STRIPE_PATH_MFMA_GEMM;
   info->tile_m = BM; info->tile_n = BN; info->tile_k = dma ? D_BK : BK;
   info->frag_m = 32; info->frag_n = 32; info->frag_k = 16;
   info->lds_bytes = dma ? D_LDS : 2 * STAGE;
-  info->workgroup_size = (waves == 8 && !dma) ? THREADS : W4_THREADS;
+  info->workgroup_size = dma ? dma_waves * 64 : (waves == 8 ? THREADS : W4_THREADS);
   info->grid = l->grid;
-  if (dma) snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x32_mfma32x32x16_w4_lds_direct");
+  if (dma) snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x32_mfma32x32x16_w%d_lds_direct", dma_waves);
   else snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x64_mfma32x32x16_w%d_swz%d", waves, swz);
   return true;
 }
@@ -629,15 +657,16 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
   void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = nullptr;
   switch (l.variant) {
     case 0: case 1: case 2: kernel = gemm_bf16_w4_kernel; break;
-    case 20: kernel = gemm_bf16_dma_kernel; break;
+    case 20: kernel = gemm_bf16_dma_kernel<4>; break;
+    case 21: kernel = gemm_bf16_dma_kernel<8>; break;
     case 10: kernel = gemm_bf16_w8_kernel<0>; break;
     case 11: kernel = gemm_bf16_w8_kernel<1>; break;
     default: kernel = gemm_bf16_w8_kernel<2>; break;
   }
-  const int threads = (l.variant >= 10 && l.variant < 20) ? THREADS : W4_THREADS;
-  const int lds_bytes = l.variant == 20 ? D_LDS : 2 * STAGE;
+  const int threads = (l.variant == 21 || (l.variant >= 10 && l.variant < 20)) ? THREADS : W4_THREADS;
+  const int lds_bytes = l.variant >= 20 ? D_LDS : 2 * STAGE;
   GemmParams pk = p;
-  if (l.variant == 20) pk.k_tiles = (int)(g.K / D_BK);
+  if (l.variant >= 20) pk.k_tiles = (int)(g.K / D_BK);
   // more than 64 KB of dynamic LDS has to be enabled once per device
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);

@@ -160,12 +160,14 @@ def test_gemm_mfma_small(M, N, K):
     assert info["path_name"] == "mfma_gemm"
 
 
-@pytest.mark.parametrize("swz", [0, 1, 2])
-def test_gemm_mfma_position_sensitive(swz, monkeypatch):
+@pytest.mark.parametrize("tune,name", [("gemm_dma_waves=4", "w4_lds_direct"), ("gemm_dma_waves=8", "w8_lds_direct"),
+                                       ("gemm_dma=0,gemm_waves=4", "w4_swz2"), ("gemm_dma=0,gemm_waves=8,gemm_swz=1", "w8_swz1"),
+                                       ("gemm_dma=0,gemm_waves=8,gemm_swz=0", "w8_swz0")])
+def test_gemm_mfma_position_sensitive(tune, name, monkeypatch):
     """A[m,k] = small integers depending on (m,k), B = shifted identity: every
     output equals one specific input element, exactly, so any mix-up of rows,
-    columns, fragments or tiles shows."""
-    monkeypatch.setenv("STRIPE_TUNE", f"gemm_swz={swz}")
+    columns, fragments, K steps or tiles shows.  Run on every GEMM kernel variant."""
+    monkeypatch.setenv("STRIPE_TUNE", tune)
     M = N = 512
     K = 512
     a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.bfloat16)
@@ -174,9 +176,11 @@ def test_gemm_mfma_position_sensitive(swz, monkeypatch):
     b[(torch.arange(N) + shift) % K, torch.arange(N)] = 1.0
     blk = W.matmul_block(M, N, K, "bf16", "f32")
     gpu, sb = run_gpu(blk, [a, b], return_block=True)
-    assert sb.info["path_name"] == "mfma_gemm"
+    assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"].endswith(name), sb.info["kernel"]
     want = a.float()[:, (torch.arange(N) + shift) % K].numpy()
     assert np.array_equal(gpu.reshape(M, N), want)
+    ins = [W.seeded_tensor((M, K), "bf16", 0), W.seeded_tensor((K, N), "bf16", 1)]
+    parity(blk, ins, what=f"gemm {tune}")
 
 
 def test_gemm_config_full_size():
