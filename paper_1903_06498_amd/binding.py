@@ -187,14 +187,22 @@ class StripeBlock:
     def __init__(self, block, path: str = "auto"):
         self.handle = stripe_block_create(block, path)
         self.info = stripe_block_query(self.handle)
+        self._n_in = len(block.refs) - 1
+        self._in_arr = (C.c_void_p * self._n_in)()      # reused on every run: marshalling cost matters for tiny blocks
 
     def run(self, inputs, output, stream: Optional[int] = None) -> None:
         if stream is None:
             import torch
             stream = torch.cuda.current_stream().cuda_stream
-        ptrs = [t if isinstance(t, int) else t.data_ptr() for t in inputs]
+        if len(inputs) != self._n_in:
+            raise ValueError(f"expected {self._n_in} inputs")
+        arr = self._in_arr
+        for i, t in enumerate(inputs):
+            arr[i] = t if isinstance(t, int) else t.data_ptr()
         out = output if isinstance(output, int) else output.data_ptr()
-        stripe_block_run(self.handle, ptrs, out, stream)
+        st = lib.stripe_block_run(self.handle, arr, out, stream)
+        if st != STRIPE_OK:
+            raise StripeError(st, stripe_last_error())
 
     def close(self) -> None:
         if self.handle is not None:

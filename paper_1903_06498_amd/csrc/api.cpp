@@ -52,6 +52,7 @@ stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, st
   }
   blk->n_inputs = fb.n_refs - 1;
   Plan& p = blk->plan;
+  if (tune_int("generic_i64", 0)) p.gen.narrow = 0;   // test hook: 64-bit index arithmetic in the generic kernel
   if (!p.noop) {
     const bool forced = path != STRIPE_PATH_AUTO;
     bool picked = false;

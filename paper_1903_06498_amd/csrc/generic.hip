@@ -15,6 +15,8 @@
 //                elements) and a cross-lane butterfly finishes the aggregation.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace stripe {
@@ -52,34 +54,51 @@ __device__ __forceinline__ A combine(A acc, A v) {
   return acc + v;
 }
 
-template <typename TIn, int INTR, int AGG, int LANES>
+// Bits of `m` moved to the position of their butterfly partner at distance d (d a power of two).
+__device__ __forceinline__ uint64_t swap_blocks(uint64_t m, int d) {
+  const uint64_t low = d == 32 ? 0x00000000ffffffffull : d == 16 ? 0x0000ffff0000ffffull : d == 8 ? 0x00ff00ff00ff00ffull
+                     : d == 4 ? 0x0f0f0f0f0f0f0f0full : d == 2 ? 0x3333333333333333ull : 0x5555555555555555ull;
+  return ((m & low) << d) | ((m >> d) & low);
+}
+
+// NARROW: the planner has shown that every element offset, every constraint
+// value and the output count fit in 32 bits, so all index arithmetic (and the
+// divisions that decode a flat position into indexes) runs in 32-bit.
+template <typename TIn, int INTR, int AGG, int LANES, bool NARROW>
 __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, const void* __restrict__ in0,
                                                       const void* __restrict__ in1, void* __restrict__ out) {
   using Acc = typename Elem<TIn>::Acc;
+  using I = typename std::conditional<NARROW, int32_t, int64_t>::type;    // offsets and constraint values
+  using U = typename std::conditional<NARROW, uint32_t, uint64_t>::type;  // flat output position
   const int lane = threadIdx.x & 63;
-  int64_t t = (LANES == 1) ? (int64_t)blockIdx.x * 256 + threadIdx.x
-                           : (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-  if (t >= p.n_outputs) return;  // lanes == 64: uniform per wavefront
+  U t;
+  if (LANES == 1) {
+    t = (U)blockIdx.x * 256 + threadIdx.x;
+  } else {
+    t = (U)blockIdx.x * 4 + (U)__builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));   // uniform per wavefront
+  }
+  if ((int64_t)t >= p.n_outputs) return;
 
-  int64_t offA = p.a_base, offB = p.b_base, offO = p.o_base;
-  int64_t cv[kGenCons];
+  I offA = (I)p.a_base, offB = (I)p.b_base, offO = (I)p.o_base;
+  I cv[kGenCons];
 #pragma unroll
-  for (int q = 0; q < kGenCons; ++q) cv[q] = p.cons_const[q];
+  for (int q = 0; q < kGenCons; ++q) cv[q] = (I)p.cons_const[q];
   for (int j = 0; j < p.n_out; ++j) {
-    const int64_t rng = p.out_range[j];
-    const int64_t o = t % rng;
-    t /= rng;
-    offA += p.a_out[j] * o;
-    offB += p.b_out[j] * o;
-    offO += p.o_out[j] * o;
+    const U rng = (U)p.out_range[j];
+    const U quot = t / rng;
+    const I o = (I)(t - quot * rng);
+    t = quot;
+    offA += (I)p.a_out[j] * o;
+    offB += (I)p.b_out[j] * o;
+    offO += (I)p.o_out[j] * o;
 #pragma unroll
-    for (int q = 0; q < kGenCons; ++q) cv[q] += (int64_t)p.cons_out[q][j] * o;
+    for (int q = 0; q < kGenCons; ++q) cv[q] += (I)p.cons_out[q][j] * o;
   }
 
   Acc acc = 0;
   bool touched = false;
 
-  auto visit = [&](int64_t oa, int64_t ob) {
+  auto visit = [&](I oa, I ob) {
     const Acc a = Elem<TIn>::load(in0, oa);
     Acc v = a;
     if (INTR != STRIPE_INTR_COPY) {
@@ -94,59 +113,70 @@ __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, con
     const uint32_t inner = p.inner_range;
     const uint32_t outer_total = p.red_total / inner;
     for (uint32_t ro = 0; ro < outer_total; ++ro) {
-      int64_t oa = offA, ob = offB;
-      int64_t cw[kGenCons];
+      I oa = offA, ob = offB;
+      I cw[kGenCons];
 #pragma unroll
       for (int q = 0; q < kGenCons; ++q) cw[q] = cv[q];
       uint32_t rest = ro;
       for (int j = 1; j < p.n_red; ++j) {
         const uint32_t rng = (uint32_t)p.red_range[j];
-        const uint32_t rj = rest % rng;
-        rest /= rng;
-        oa += p.a_red[j] * rj;
-        ob += p.b_red[j] * rj;
+        const uint32_t quot = rest / rng;
+        const I rj = (I)(rest - quot * rng);
+        rest = quot;
+        oa += (I)p.a_red[j] * rj;
+        ob += (I)p.b_red[j] * rj;
 #pragma unroll
-        for (int q = 0; q < kGenCons; ++q) cw[q] += (int64_t)p.cons_red[q][j] * rj;
+        for (int q = 0; q < kGenCons; ++q) cw[q] += (I)p.cons_red[q][j] * rj;
       }
-      const int64_t sa = p.a_red[0], sb = p.b_red[0];
+      const I sa = (I)p.a_red[0], sb = (I)p.b_red[0];
       for (uint32_t r0 = 0; r0 < inner; ++r0) {
         bool ok = true;
 #pragma unroll
-        for (int q = 0; q < kGenCons; ++q) ok = ok && (cw[q] + (int64_t)p.cons_red[q][0] * r0 >= 0);
-        if (ok) visit(oa + sa * r0, ob + sb * r0);
+        for (int q = 0; q < kGenCons; ++q) {
+          ok = ok && (cw[q] >= 0);
+          cw[q] += (I)p.cons_red[q][0];
+        }
+        if (ok) visit(oa, ob);
+        oa += sa;
+        ob += sb;
       }
     }
     if (touched) ((Acc*)out)[offO] = acc;
   } else {
     for (uint32_t r = lane; r < p.red_total; r += 64) {
-      int64_t oa = offA, ob = offB;
-      int64_t cw[kGenCons];
+      I oa = offA, ob = offB;
+      I cw[kGenCons];
 #pragma unroll
       for (int q = 0; q < kGenCons; ++q) cw[q] = cv[q];
       uint32_t rest = r;
       for (int j = 0; j < p.n_red; ++j) {
         const uint32_t rng = (uint32_t)p.red_range[j];
-        const uint32_t rj = rest % rng;
-        rest /= rng;
-        oa += p.a_red[j] * rj;
-        ob += p.b_red[j] * rj;
+        const uint32_t quot = rest / rng;
+        const I rj = (I)(rest - quot * rng);
+        rest = quot;
+        oa += (I)p.a_red[j] * rj;
+        ob += (I)p.b_red[j] * rj;
 #pragma unroll
-        for (int q = 0; q < kGenCons; ++q) cw[q] += (int64_t)p.cons_red[q][j] * rj;
+        for (int q = 0; q < kGenCons; ++q) cw[q] += (I)p.cons_red[q][j] * rj;
       }
       bool ok = true;
 #pragma unroll
       for (int q = 0; q < kGenCons; ++q) ok = ok && (cw[q] >= 0);
       if (ok) visit(oa, ob);
     }
-    // butterfly over the 64 lanes; a lane that saw no point contributes nothing
+    // Butterfly over the 64 lanes.  Which lanes hold a value is tracked in a
+    // wave-uniform mask, so only the values cross lanes; a lane whose partner
+    // saw no point takes nothing from it.
+    uint64_t mask = __ballot(touched);
 #pragma unroll
     for (int m = 32; m >= 1; m >>= 1) {
       const Acc other = __shfl_xor(acc, m, 64);
-      const int other_touched = __shfl_xor((int)touched, m, 64);
-      if (other_touched) {
+      const uint64_t partner = swap_blocks(mask, m);
+      if ((partner >> lane) & 1) {
         acc = touched ? combine<AGG, Acc>(acc, other) : other;
         touched = true;
       }
+      mask |= partner;
     }
     if (lane == 0 && touched) ((Acc*)out)[offO] = acc;
   }
@@ -156,10 +186,16 @@ template <typename TIn, int INTR, int AGG>
 hipError_t launch_lanes(const GenericParams& p, const void* a, const void* b, void* o, hipStream_t s) {
   if (p.lanes == 64) {
     const int64_t grid = (p.n_outputs + 3) / 4;
-    hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 64>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+    if (p.narrow)
+      hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 64, true>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+    else
+      hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 64, false>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
   } else {
     const int64_t grid = (p.n_outputs + 255) / 256;
-    hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 1>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+    if (p.narrow)
+      hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 1, true>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+    else
+      hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 1, false>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
   }
   return hipGetLastError();
 }
@@ -206,7 +242,8 @@ void generic_info(const Plan& plan, stripe_block_info_t* info) {
   info->lds_bytes = 0;
   info->workgroup_size = 256;
   info->grid = p.lanes == 64 ? (p.n_outputs + 3) / 4 : (p.n_outputs + 255) / 256;
-  snprintf(info->kernel, sizeof info->kernel, "generic_affine_%s", p.lanes == 64 ? "wave_per_output" : "lane_per_output");
+  snprintf(info->kernel, sizeof info->kernel, "generic_affine_%s%s", p.lanes == 64 ? "wave_per_output" : "lane_per_output",
+           p.narrow ? "" : "_i64");
 }
 
 // ---------------------------------------------------------------------------

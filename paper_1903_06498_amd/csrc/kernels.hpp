@@ -51,6 +51,9 @@ hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void*
 // ---- max aggregation over a 2-d window ------------------------------------
 struct PoolLaunch {
   int variant = -1;
+  int rows = 0;      // output rows per workgroup
+  int wg = 128;      // lanes per workgroup
+  bool lean = false; // strip kernel without selects (32-bit in-row offsets suffice)
   int64_t grid = 0;
 };
 bool pool_select(const Pool2dShape& p, int dtype, PoolLaunch* l, stripe_block_info_t* info);

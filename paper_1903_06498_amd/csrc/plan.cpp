@@ -803,6 +803,17 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
       if (sa > 1 || sb > 1) lane_per_output_coalesces = false;
     }
     g.lanes = (!lane_per_output_coalesces && g.red_total >= 64) ? 64 : 1;
+    // 32-bit index arithmetic when nothing the kernel computes can leave int32:
+    // largest |offset| of each tensor, largest |value| of each constraint, the output count.
+    auto reach = [&](const Affine& f) {
+      i128 m = f.k < 0 ? -(i128)f.k : (i128)f.k;
+      for (int j = 0; j < fb.n_idx; ++j) m += (f.c[j] < 0 ? -(i128)f.c[j] : (i128)f.c[j]) * (fb.range[j] - 1);
+      return m;
+    };
+    const i128 lim = (i128)0x3fffffff;   // one extra loop step past a range stays representable
+    bool narrow = (i128)outs + 256 <= lim && reach(A) <= lim && reach(o) <= lim && (!B || reach(*B) <= lim);
+    for (const Affine& c : fb.cons) narrow = narrow && reach(c) <= lim;
+    g.narrow = narrow ? 1 : 0;
   }
   if (path == STRIPE_PATH_GENERIC && !gen_ok) return bad(err, STRIPE_ERR_UNSUPPORTED, gen_why);
   if (!gen_ok) g.n_outputs = -1;  // marks "no generic fallback"

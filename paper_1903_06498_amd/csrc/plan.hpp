@@ -80,7 +80,8 @@ struct Pool2dShape {     // O[n,y,x,c] = agg over in-bounds taps of I[n, s*y+i-p
 constexpr int kGenIdx = 8;
 constexpr int kGenCons = 8;
 struct GenericParams {
-  int32_t n_out, n_red, lanes, pad_;
+  int32_t n_out, n_red, lanes;
+  int32_t narrow;                  // 1: offsets, constraint values and the output count all fit in 32 bits
   int32_t out_range[kGenIdx], red_range[kGenIdx];
   int64_t a_out[kGenIdx], b_out[kGenIdx], o_out[kGenIdx];
   int64_t a_red[kGenIdx], b_red[kGenIdx];

@@ -3,18 +3,27 @@
 // Block shape (paper Section 2.1 "the max of a maxpool"; Section 3.2 for the
 // constraints):  O[n,y,x,c] = max over taps (i,j) with
 //   0 <= s*y + i - p < H  and  0 <= s*x + j - q < W   of  I[n, s*y+i-p, s*x+j-q, c].
-// Out-of-range taps are not part of the iteration space: they are skipped,
-// never read and never replaced by a padding value.
+// Out-of-range taps are not part of the iteration space: they contribute
+// nothing, no address outside the image is read and no padding value enters.
 //
 // Mapping: channels are contiguous, so a lane owns 4 channels (one 16-byte
 // load) of one output column; 16 lanes cover the 256 bytes of a 64-channel
-// pixel.  A workgroup of 128 lanes owns 128 consecutive (column, channel-quad)
-// items and a strip of TY output rows; it reads each of the strip's
-// stride*(TY-1)+R input rows once (rows shared by neighbouring windows are
-// reused from registers).  Boundary handling is by clamped coordinates plus a
-// select, decided per whole row and whole column (Section 2.3, "Separating
-// Interior and Boundary Tiles"): the loads carry no per-tap constraint tests
-// and no branches.
+// pixel.  Three kernels share it:
+//   strip (default)   128 lanes own 128 consecutive (column, channel-quad)
+//                     items and TY output rows; all stride*(TY-1)+R input rows
+//                     are requested up front and rows shared by neighbouring
+//                     windows are reused from registers;
+//   strip with selects the same, with out-of-range taps replaced by -inf
+//                     (used when in-row offsets need more than 32 bits);
+//   rolling           a lane walks down a chunk of output rows and carries the
+//                     shared input row, so a chunk fetches every row once
+//                     (lowest L2 fetch traffic, slightly slower in time).
+// Boundary handling follows Section 2.3 ("Separating Interior and Boundary
+// Tiles") in spirit: the loads carry no per-tap constraint tests and no
+// branches.  A tap outside the iteration space is read at its coordinate
+// clamped into the image; the clamped tap is one the window holds anyway
+// (every window has an in-range row and column) and max is idempotent, so
+// the duplicate cannot change the result.
 #include <hip/hip_runtime.h>
 
 #include "kernels.hpp"
@@ -27,7 +36,8 @@ struct PoolParams {
   int32_t pad_y, pad_x;
   int32_t items;                      // Wo * C4
   int32_t blocks_per_row, y_strips;
-  int32_t xcd_remap, pad_;
+  int32_t xcd_remap;
+  int32_t rows;                      // output rows per workgroup (rolling kernel)
   int64_t i_n, i_y, i_x, o_n, o_y, o_x;  // element strides (channel stride is 1)
   int64_t i_base, o_base;
 };
@@ -120,15 +130,156 @@ __global__ __launch_bounds__(128) void pool_max_f32_kernel(const PoolParams p, c
   }
 }
 
-PoolParams make_params(const Pool2dShape& s, int ty) {
+// Rolling variant for R = 3, stride 2: a lane keeps its (column, channel-quad)
+// and walks down `rows` output rows.  Consecutive windows share one input row
+// (row 2y+1-p of output row y is row 2(y+1)-1-p of the next), whose horizontal
+// maximum is carried in registers, so inside a workgroup's chunk every input
+// row is fetched exactly once; the two new rows of the next output row are
+// requested before the current one is reduced and stored.
+//
+// The kernel is written to issue few vector instructions per byte, which
+// matters as much as the access pattern at this arithmetic intensity:
+//  * a tap outside the iteration space is read at its coordinate clamped into
+//    the image.  The clamped tap is a tap the window holds anyway (every
+//    window has at least one in-range row and column), and max is idempotent,
+//    so the duplicate leaves the result unchanged and no select is needed;
+//  * rows are uniform over a workgroup, so a row's base address lives in
+//    scalar registers and each load adds only a per-lane 32-bit byte offset;
+//  * the 3-way maxima map to three-operand max instructions.
+__device__ __forceinline__ f32x4 max3x4(f32x4 a, f32x4 b, f32x4 c) {
+  f32x4 r;
+  r.x = __builtin_fmaxf(__builtin_fmaxf(a.x, b.x), c.x);
+  r.y = __builtin_fmaxf(__builtin_fmaxf(a.y, b.y), c.y);
+  r.z = __builtin_fmaxf(__builtin_fmaxf(a.z, b.z), c.z);
+  r.w = __builtin_fmaxf(__builtin_fmaxf(a.w, b.w), c.w);
+  return r;
+}
+
+__global__ __launch_bounds__(512) void pool_max_f32_roll_kernel(const PoolParams p, const float* __restrict__ in,
+                                                               float* __restrict__ out) {
+  constexpr int ST = 2, S = 3;
+  const unsigned b = blockIdx.x;
+  const int bx = b % p.blocks_per_row;
+  const int rest = b / p.blocks_per_row;
+  const int ys = rest % p.y_strips;
+  const int n = rest / p.y_strips;
+  const int item = bx * (int)blockDim.x + threadIdx.x;
+  if (item >= p.items) return;
+  const int c4 = item % p.C4;
+  const int xo = item / p.C4;
+
+  // per-lane byte offsets inside a row (the host has checked that they fit in 32 bits)
+  uint32_t voff[S];
+#pragma unroll
+  for (int j = 0; j < S; ++j) {
+    const int xc = xo * ST - p.pad_x + j;
+    const int xcl = xc < 0 ? 0 : (xc >= p.W ? p.W - 1 : xc);
+    voff[j] = ((uint32_t)xcl * (uint32_t)p.i_x + (uint32_t)c4 * 4u) * 4u;
+  }
+  const uint32_t ooff = ((uint32_t)xo * (uint32_t)p.o_x + (uint32_t)c4 * 4u) * 4u;
+  // uniform bases
+  const char* ib = (const char*)(in + p.i_base + (int64_t)n * p.i_n);
+  char* ob = (char*)(out + p.o_base + (int64_t)n * p.o_n);
+
+  auto hload = [&](f32x4 (&v)[S], int y) {
+    const int yc = y < 0 ? 0 : (y >= p.H ? p.H - 1 : y);
+    const char* rp = ib + (int64_t)yc * p.i_y * 4;
+#pragma unroll
+    for (int j = 0; j < S; ++j) v[j] = *(const f32x4*)(rp + voff[j]);
+  };
+  const int yo0 = ys * p.rows;
+  auto store = [&](int yo, f32x4 m) { *(f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff) = m; };
+
+  const int yend = yo0 + p.rows < p.Ho ? yo0 + p.rows : p.Ho;   // yo0 < Ho by construction of the grid
+  int yi = yo0 * ST - p.pad_y;                                    // first input row of the current window
+  f32x4 c[S], a0[S], a1[S], b0[S], b1[S];
+  hload(c, yi);
+  hload(a0, yi + 1);
+  hload(a1, yi + 2);
+  f32x4 carried = max3x4(c[0], c[1], c[2]);
+  int yo = yo0;
+  // two output rows per trip so that the register sets swap roles without copies
+  for (; yo + 2 < yend; yo += 2, yi += 2 * ST) {
+    hload(b0, yi + 3);
+    hload(b1, yi + 4);
+    f32x4 h1 = max3x4(a1[0], a1[1], a1[2]);
+    store(yo, max3x4(carried, max3x4(a0[0], a0[1], a0[2]), h1));
+    carried = h1;
+    hload(a0, yi + 5);
+    hload(a1, yi + 6);
+    h1 = max3x4(b1[0], b1[1], b1[2]);
+    store(yo + 1, max3x4(carried, max3x4(b0[0], b0[1], b0[2]), h1));
+    carried = h1;
+  }
+  if (yo + 1 < yend) {   // two rows left
+    hload(b0, yi + 3);
+    hload(b1, yi + 4);
+    f32x4 h1 = max3x4(a1[0], a1[1], a1[2]);
+    store(yo, max3x4(carried, max3x4(a0[0], a0[1], a0[2]), h1));
+    store(yo + 1, max3x4(h1, max3x4(b0[0], b0[1], b0[2]), max3x4(b1[0], b1[1], b1[2])));
+  } else {               // one row left
+    store(yo, max3x4(carried, max3x4(a0[0], a0[1], a0[2]), max3x4(a1[0], a1[1], a1[2])));
+  }
+}
+
+// Strip kernel with the same instruction diet as the rolling kernel (clamped
+// duplicates instead of selects, uniform row bases, three-operand maxima):
+// 128 lanes own 128 (column, channel-quad) items and TY output rows, and all
+// loads of the strip are issued before the first reduction.
+template <int TY>
+__global__ __launch_bounds__(128) void pool_max_f32_strip_kernel(const PoolParams p, const float* __restrict__ in,
+                                                                float* __restrict__ out) {
+  constexpr int ST = 2, S = 3, R = 3, NR = ST * (TY - 1) + R;
+  const unsigned b = blockIdx.x;
+  const int bx = b % p.blocks_per_row;
+  const int rest = b / p.blocks_per_row;
+  const int ys = rest % p.y_strips;
+  const int n = rest / p.y_strips;
+  const int item = bx * 128 + threadIdx.x;
+  if (item >= p.items) return;
+  const int c4 = item % p.C4;
+  const int xo = item / p.C4;
+  uint32_t voff[S];
+#pragma unroll
+  for (int j = 0; j < S; ++j) {
+    const int xc = xo * ST - p.pad_x + j;
+    const int xcl = xc < 0 ? 0 : (xc >= p.W ? p.W - 1 : xc);
+    voff[j] = ((uint32_t)xcl * (uint32_t)p.i_x + (uint32_t)c4 * 4u) * 4u;
+  }
+  const uint32_t ooff = ((uint32_t)xo * (uint32_t)p.o_x + (uint32_t)c4 * 4u) * 4u;
+  const char* ib = (const char*)(in + p.i_base + (int64_t)n * p.i_n);
+  char* ob = (char*)(out + p.o_base + (int64_t)n * p.o_n);
+  const int yo0 = ys * TY;
+  const int y0 = yo0 * ST - p.pad_y;
+
+  f32x4 v[NR][S];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const int y = y0 + r;
+    const int yc = y < 0 ? 0 : (y >= p.H ? p.H - 1 : y);
+    const char* rp = ib + (int64_t)yc * p.i_y * 4;
+#pragma unroll
+    for (int j = 0; j < S; ++j) v[r][j] = *(const f32x4*)(rp + voff[j]);
+  }
+  f32x4 hm[NR];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) hm[r] = max3x4(v[r][0], v[r][1], v[r][2]);
+#pragma unroll
+  for (int ty = 0; ty < TY; ++ty) {
+    const int yo = yo0 + ty;
+    if (yo < p.Ho) *(f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff) = max3x4(hm[ty * ST], hm[ty * ST + 1], hm[ty * ST + 2]);
+  }
+}
+
+PoolParams make_params(const Pool2dShape& s, int ty, int wg) {
   PoolParams p;
   p.N = (int)s.N; p.H = (int)s.H; p.W = (int)s.W; p.Ho = (int)s.Ho; p.Wo = (int)s.Wo; p.C4 = (int)(s.C / 4);
   p.pad_y = (int)s.pad_y; p.pad_x = (int)s.pad_x;
   p.items = p.Wo * p.C4;
-  p.blocks_per_row = (p.items + 127) / 128;
+  p.blocks_per_row = (p.items + wg - 1) / wg;
   p.y_strips = (p.Ho + ty - 1) / ty;
   p.xcd_remap = tune_int("pool_xcd", 0);
-  p.pad_ = 0;
+  p.rows = ty;
   p.i_n = s.i_n; p.i_y = s.i_y; p.i_x = s.i_x; p.o_n = s.o_n; p.o_y = s.o_y; p.o_x = s.o_x;
   p.i_base = s.i_base; p.o_base = s.o_base;
   return p;
@@ -137,14 +288,20 @@ PoolParams make_params(const Pool2dShape& s, int ty) {
 constexpr int kTyChoices[] = {1, 2, 3, 4, 7};
 
 template <int TY, bool NT>
-hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st) {
+hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st, bool lean) {
+  if (lean && !NT) {
+    hipLaunchKernelGGL((pool_max_f32_strip_kernel<TY>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL((pool_max_f32_kernel<3, 3, 2, TY, NT>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
   return hipGetLastError();
 }
 
 }  // namespace
 
-// variant = index into kTyChoices * 2 + nontemporal flag
+// variant = index into kTyChoices * 2 + nontemporal flag for the strip kernel, kRollVariant for the rolling kernel
+constexpr int kRollVariant = 100;
+
 bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_info_t* info) {
   if (dtype != STRIPE_F32) return false;
   if (s.R != 3 || s.S != 3 || s.stride_y != 2 || s.stride_x != 2) return false;
@@ -156,16 +313,53 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   for (int64_t v : {s.i_n, s.i_y, s.i_x, s.o_n, s.o_y, s.o_x, s.i_base, s.o_base})
     if (v % 4) return false;
   if (s.N > 0x7fffffff / 4 || s.H > 0x3fffffff || s.W > 0x3fffffff || s.Wo * (s.C / 4) > 0x3fffffff) return false;
+  const bool row_offsets_fit = ((s.W - 1) * s.i_x + s.C) < ((int64_t)1 << 29) && ((s.Wo - 1) * s.o_x + s.C) < ((int64_t)1 << 29) &&
+                              s.i_x >= 0 && s.o_x >= 0;
+  if (tune_int("pool_roll", 0) && row_offsets_fit) {
+    int rows = tune_int("pool_roll_rows", 7);
+    if (rows < 1) rows = 1;
+    if (rows > s.Ho) rows = (int)s.Ho;
+    // workgroup size: the multiple of 64 (at most 512) that pads a row of items least; larger wins ties
+    const int64_t items = s.Wo * (s.C / 4);
+    int wg = tune_int("pool_roll_wg", 0);
+    if (wg < 64 || wg > 512 || wg % 64) {
+      int64_t best = -1;
+      for (int cand = 512; cand >= 64; cand -= 64) {
+        const int64_t padded = (items + cand - 1) / cand * cand;
+        if (best < 0 || padded < best) best = padded, wg = cand;
+      }
+    }
+    const PoolParams p = make_params(s, rows, wg);
+    const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
+    if (grid > 0x7fffffffLL) return false;
+    l->variant = kRollVariant;
+    l->rows = rows;
+    l->wg = wg;
+    l->grid = grid;
+    info->path = STRIPE_PATH_POOL;
+    info->tile_m = rows;
+    info->tile_n = wg;
+    info->tile_k = 0;
+    info->frag_m = info->frag_n = info->frag_k = 0;
+    info->lds_bytes = 0;
+    info->workgroup_size = wg;
+    info->grid = grid;
+    snprintf(info->kernel, sizeof info->kernel, "pool_max_f32_3x3s2_roll%d_wg%d", rows, wg);
+    return true;
+  }
   int ty_idx = 1;  // 2 rows per strip
   const int want = tune_int("pool_ty", 0);
   for (int i = 0; i < (int)(sizeof kTyChoices / sizeof kTyChoices[0]); ++i)
     if (kTyChoices[i] == want) ty_idx = i;
   const int nt = tune_int("pool_nt", 0) ? 1 : 0;
   const int ty = kTyChoices[ty_idx];
-  const PoolParams p = make_params(s, ty);
+  const PoolParams p = make_params(s, ty, 128);
   const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
   if (grid > 0x7fffffffLL) return false;
   l->variant = ty_idx * 2 + nt;
+  l->lean = row_offsets_fit && !nt && tune_int("pool_lean", 1);
+  l->rows = ty;
+  l->wg = 128;
   l->grid = grid;
   info->path = STRIPE_PATH_POOL;
   info->tile_m = ty;          // output rows per strip
@@ -175,21 +369,26 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   info->lds_bytes = 0;
   info->workgroup_size = 128;
   info->grid = grid;
-  snprintf(info->kernel, sizeof info->kernel, "pool_max_f32_3x3s2_ty%d%s", ty, nt ? "_nt" : "");
+  snprintf(info->kernel, sizeof info->kernel, "pool_max_f32_3x3s2_ty%d%s", ty, nt ? "_nt" : l->lean ? "" : "_sel");
   return true;
 }
 
 hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in, void* out, hipStream_t st) {
   if (((uintptr_t)in % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
+  if (l.variant == kRollVariant) {
+    const PoolParams p = make_params(s, l.rows, l.wg);
+    hipLaunchKernelGGL(pool_max_f32_roll_kernel, dim3((unsigned)l.grid), dim3(l.wg), 0, st, p, (const float*)in, (float*)out);
+    return hipGetLastError();
+  }
   const int ty_idx = l.variant / 2;
   const bool nt = l.variant % 2;
-  const PoolParams p = make_params(s, kTyChoices[ty_idx]);
+  const PoolParams p = make_params(s, kTyChoices[ty_idx], 128);
   switch (ty_idx) {
-    case 0: return nt ? launch_ty<1, true>(p, l.grid, in, out, st) : launch_ty<1, false>(p, l.grid, in, out, st);
-    case 1: return nt ? launch_ty<2, true>(p, l.grid, in, out, st) : launch_ty<2, false>(p, l.grid, in, out, st);
-    case 2: return nt ? launch_ty<3, true>(p, l.grid, in, out, st) : launch_ty<3, false>(p, l.grid, in, out, st);
-    case 3: return nt ? launch_ty<4, true>(p, l.grid, in, out, st) : launch_ty<4, false>(p, l.grid, in, out, st);
-    default: return nt ? launch_ty<7, true>(p, l.grid, in, out, st) : launch_ty<7, false>(p, l.grid, in, out, st);
+    case 0: return nt ? launch_ty<1, true>(p, l.grid, in, out, st, l.lean) : launch_ty<1, false>(p, l.grid, in, out, st, l.lean);
+    case 1: return nt ? launch_ty<2, true>(p, l.grid, in, out, st, l.lean) : launch_ty<2, false>(p, l.grid, in, out, st, l.lean);
+    case 2: return nt ? launch_ty<3, true>(p, l.grid, in, out, st, l.lean) : launch_ty<3, false>(p, l.grid, in, out, st, l.lean);
+    case 3: return nt ? launch_ty<4, true>(p, l.grid, in, out, st, l.lean) : launch_ty<4, false>(p, l.grid, in, out, st, l.lean);
+    default: return nt ? launch_ty<7, true>(p, l.grid, in, out, st, l.lean) : launch_ty<7, false>(p, l.grid, in, out, st, l.lean);
   }
 }
 

@@ -48,9 +48,11 @@ def test_figure5_forms_int8(form):
 
 
 @pytest.mark.parametrize("seed", range(60))
-def test_random_tiny_blocks_generic(seed):
+def test_random_tiny_blocks_generic(seed, monkeypatch):
     """Random small (nested) integer blocks, passed values, constraints, negative
-    coefficients: bit-exact, untouched elements kept; or rejected at create."""
+    coefficients: bit-exact, untouched elements kept; or rejected at create.
+    Every other group of seven seeds runs the 64-bit index variant."""
+    monkeypatch.setenv("STRIPE_TUNE", f"generic_i64={(seed // 7) % 2}")
     rng = random.Random(1000 + seed)
     agg = ["add", "max", "min"][seed % 3]
     intrinsic = ["mul", "copy", "add"][(seed // 3) % 3]
@@ -66,18 +68,24 @@ def test_random_tiny_blocks_generic(seed):
     assert np.array_equal(gpu.astype(np.int64), res.out)
 
 
+@pytest.mark.parametrize("wide", [0, 1])
 @pytest.mark.parametrize("dtype,lanes_hint", [("f32", "conv"), ("bf16", "conv"), ("i8", "conv")])
-def test_generic_conv_shapes(dtype, lanes_hint):
-    """Ragged, asymmetric convolution on the generic kernel (wave-per-output mapping)."""
+def test_generic_conv_shapes(dtype, lanes_hint, wide, monkeypatch):
+    """Ragged, asymmetric convolution on the generic kernel (wave-per-output mapping), with 32-bit index
+    arithmetic (the planner proves it is enough here) and with the 64-bit variant forced."""
+    monkeypatch.setenv("STRIPE_TUNE", f"generic_i64={wide}")
     N, H, Wd, Ci, Co, R, S, s, p = 2, 19, 13, 24, 10, 3, 5, 2, 2
     odt = "i32" if dtype == "i8" else "f32"
     blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, s, p, dtype, odt)
     ins = [W.seeded_tensor((N, H, Wd, Ci), dtype, 0), W.seeded_tensor((R, S, Co, Ci), dtype, 1)]
     info, score = parity(blk, ins, "generic", what=f"generic conv {dtype}")
+    assert info["kernel"].endswith("_i64") == bool(wide)
     say(f"generic conv {dtype}: {info['kernel']} score {score:.2e}")
 
 
-def test_generic_filter_layout_k_innermost():
+@pytest.mark.parametrize("wide", [0, 1])
+def test_generic_filter_layout_k_innermost(wide, monkeypatch):
+    monkeypatch.setenv("STRIPE_TUNE", f"generic_i64={wide}")
     N, H, Wd, Ci, Co, R, S = 1, 9, 8, 5, 32, 3, 3
     blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, 1, 1, "f32", "f32", filter_layout="RSCK")
     ins = [W.seeded_tensor((N, H, Wd, Ci), "f32", 0), W.seeded_tensor((R, S, Ci, Co), "f32", 1)]
@@ -125,13 +133,29 @@ def test_pool_path_small(N, H, Wd, C):
     assert np.array_equal(gpu.reshape(ref.shape), ref.numpy())
 
 
+@pytest.mark.parametrize("lean", [0, 1])
 @pytest.mark.parametrize("ty", [1, 2, 3, 7])
-def test_pool_strip_heights(ty, monkeypatch):
-    monkeypatch.setenv("STRIPE_TUNE", f"pool_ty={ty},pool_nt=0")
+def test_pool_strip_heights(ty, lean, monkeypatch):
+    """Strip heights that divide and do not divide the 23 output rows; with selects for out-of-range taps
+    (lean=0) and with clamped duplicate taps (lean=1, the default)."""
+    monkeypatch.setenv("STRIPE_TUNE", f"pool_roll=0,pool_ty={ty},pool_nt=0,pool_lean={lean}")
     blk = W.maxpool_block(2, 45, 27, 12, 3, 2, 1)
     x = W.seeded_tensor((2, 45, 27, 12), "f32", 3)
     info, _ = parity(blk, [x], what=f"pool ty={ty}")
-    assert f"ty{ty}" in info["kernel"] and not info["kernel"].endswith("_nt")
+    assert f"ty{ty}" in info["kernel"] and not info["kernel"].endswith("_nt") and info["kernel"].endswith("_sel") != bool(lean)
+
+
+@pytest.mark.parametrize("rows,wg", [(1, 0), (2, 64), (3, 128), (7, 0), (23, 512), (100, 0)])
+def test_pool_rolling_chunks(rows, wg, monkeypatch):
+    """The rolling kernel with chunks of 1 row (nothing carried), ragged last chunks, one chunk per image
+    (rows clamps to the 23 output rows) and several workgroup sizes; odd H and W give a ragged bottom and right."""
+    monkeypatch.setenv("STRIPE_TUNE", f"pool_roll=1,pool_roll_rows={rows},pool_roll_wg={wg}")
+    blk = W.maxpool_block(2, 45, 27, 12, 3, 2, 1)
+    x = W.seeded_tensor((2, 45, 27, 12), "f32", 3)
+    info, _ = parity(blk, [x], what=f"pool roll rows={rows}")
+    assert f"roll{min(rows, 23)}_" in info["kernel"], info["kernel"]
+    ref = torch.nn.functional.max_pool2d(x.permute(0, 3, 1, 2), 3, 2, 1).permute(0, 2, 3, 1).contiguous()
+    assert np.array_equal(run_gpu(blk, [x]).reshape(ref.shape), ref.numpy())
 
 
 def test_pool_all_negative_and_generic_agree():
