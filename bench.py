@@ -45,6 +45,7 @@ KIND = {
     "maxpool_f32": ("GB/s", "hbm", "f32"),
     "tiny_conv_f32": ("TFLOP/s", "hbm", "f32"),
     "device_copy": ("GB/s", "hbm", "u8"),     # the plain copy kernel: calibrates traffic counters and the HBM yardstick
+    "library_gemm": ("TFLOP/s", "mfma", "bf16"),  # torch.mm (the vendor BLAS) on the GEMM workload's operands: a yardstick
 }
 
 
@@ -105,6 +106,41 @@ def bench_copy(args, torch, B):
                                    "kernel_us": round(us, 2)}}), flush=True)
 
 
+def bench_library_gemm(args, torch, W):
+    """The vendor library's bf16 x bf16 -> fp32 GEMM on the same seeded operands, same box, same clocks."""
+    dev = torch.device("cuda:0")
+    a, b = [t.to(dev) for t in W.config_inputs("gemm_bf16_4096")]
+    a, b = fill_like(a, args.fill), fill_like(b, args.fill)
+    f = lambda: torch.mm(a, b, out_dtype=torch.float32)
+    for _ in range(args.warmup):
+        f()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(args.steps):
+        f()
+    ev1.record()
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) / args.steps * 1e3
+    tf = 2.0 * 4096 ** 3 / us / 1e6
+    print(json.dumps({"metric": "vendor library GEMM (yardstick)", "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5),
+                      "higher_is_better": True, "dtype": "bf16", "data": "synthetic",
+                      "config": {"workload": "library_gemm", "M": 4096, "N": 4096, "K": 4096, "fill": args.fill},
+                      "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK["bf16_mfma_tflops"],
+                                   "unit": "TFLOP/s", "frac": round(tf / PEAK["bf16_mfma_tflops"], 4), "traffic": None,
+                                   "kernel": "torch.mm(out_dtype=float32)", "kernel_us": round(us, 2)}}), flush=True)
+
+
+def fill_like(t, fill):
+    """--fill diagnostic: operands of the same shape with all-equal values (low switching activity in the
+    matrix cores).  The numbers of record use the seeded data ('config')."""
+    if fill == "config":
+        return t
+    import torch
+    return torch.zeros_like(t) if fill == "zeros" else torch.ones_like(t)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -114,6 +150,9 @@ def main():
     ap.add_argument("--path", default="auto", help="force a kernel family (auto, generic, mfma_gemm, mfma_conv, pool)")
     ap.add_argument("--cpu-baseline", type=int, default=1, help="0 skips the oracle timing (profiling runs)")
     ap.add_argument("--rotate", type=int, default=-1, help="buffer sets to rotate through (-1: 1 for gemm, enough to exceed 512 MB otherwise)")
+    ap.add_argument("--fill", default="config", choices=["config", "zeros", "ones"],
+                    help="diagnostic: replace the seeded inputs by constants (shows how far the chip's power management, "
+                         "not the kernel, sets the time); only 'config' is a valid measurement")
     ap.add_argument("--traffic-bytes", type=float, default=None, help="HBM bytes per launch from rocprofv3 counters, if measured")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -130,6 +169,8 @@ def main():
     unit, bound, dtype = KIND[name]
     if name == "device_copy":
         return bench_copy(args, torch, B)
+    if name == "library_gemm":
+        return bench_library_gemm(args, torch, W)
     root = W.config_block(name)
     inputs = W.config_inputs(name)
     blk = B.StripeBlock(root, args.path)
@@ -143,7 +184,7 @@ def main():
         n_sets = 1 if bound == "mfma" else max(2, int(640e6 // set_bytes) + 1)
     sets = []
     for _ in range(n_sets):
-        sets.append(([t.to(dev) for t in inputs], torch.zeros(ext, dtype=odt, device=dev)))
+        sets.append(([fill_like(t.to(dev), args.fill) for t in inputs], torch.zeros(ext, dtype=odt, device=dev)))
     torch.cuda.synchronize()
 
     stream = torch.cuda.current_stream()
@@ -166,7 +207,7 @@ def main():
 
     work = info["work_points"]
     traffic = args.traffic_bytes
-    if traffic is None and args.path == "auto" and not os.environ.get("STRIPE_TUNE"):
+    if traffic is None and args.path == "auto" and not os.environ.get("STRIPE_TUNE") and args.fill == "config":
         traffic = MEASURED_TRAFFIC.get(name)
     flops = 2.0 * work
     nbytes = float(info["algorithmic_bytes"])
@@ -189,7 +230,7 @@ def main():
     roof["algorithmic_flops"] = int(flops)
 
     cpu = None
-    if args.cpu_baseline:
+    if args.cpu_baseline and args.fill == "config":
         cores = min(16, os.cpu_count() or 1)
         res, dt, sample, _ = oracle_sample(name, root, inputs, cores)
         if unit == "GB/s":
@@ -204,7 +245,7 @@ def main():
         "metric": "Stripe block throughput: TFLOP/s (% of MFMA peak) for conv/matmul blocks, GB/s for max blocks",
         "value": round(value, 2), "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": dtype, "data": "synthetic",
+        "dtype": dtype, "data": "synthetic" if args.fill == "config" else f"diagnostic constant fill ({args.fill})",
         "config": {"workload": name, "path": info["path_name"], "kernel": info["kernel"],
                    "tile": [info["tile_m"], info["tile_n"], info["tile_k"]], "grid": info["grid"],
                    "buffer_sets": n_sets, "hull_points": info["hull_points"], "work_points": work},

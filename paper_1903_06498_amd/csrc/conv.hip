@@ -19,6 +19,8 @@
 // reads of 32 consecutive pixels / filter rows are bank-conflict free.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kernels.hpp"
 
 namespace stripe {
@@ -27,6 +29,7 @@ namespace {
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+typedef __attribute__((ext_vector_type(4))) float f32x4s;
 
 struct ConvParams {
   int32_t N, H, W, strips_per_image, rows, pad_;
@@ -144,6 +147,201 @@ __global__ __launch_bounds__(C_MAX_ROWS * 64) void conv3x3_bf16_kernel(const Con
     }
 }
 
+// ---------------------------------------------------------------------------
+// Four-wavefront variant: the same LDS images (filter + haloed strip of 7
+// output rows), but the strip's 7 x 2 x 2 output fragments are divided so that
+// every SIMD carries the same number of matrix instructions: wavefront w owns
+// pixel half w>>1 and channel half w&1 of all 7 rows (7 accumulator
+// fragments).  For one filter column j and one 16-channel K step the 9 pixel
+// fragments of the strip's 9 input rows are read once and serve the three
+// filter rows i (output row r uses input row r+i), so a wavefront issues 12
+// LDS fragment reads per 21 matrix instructions instead of 21 + 21.  Reads of
+// the next (j, K step) are issued before the matrix instructions of the
+// current one.  Staging index arithmetic is 32-bit with a reciprocal multiply
+// for the division by the patch width: at ~13 us per launch the integer work
+// of 35 staged chunks per lane is not free.
+// ---------------------------------------------------------------------------
+constexpr int W4_ROWS = 7;
+
+// TEAMS: 1 = four wavefronts, each walks the three row groups; 2 = eight wavefronts, two per SIMD: team 0
+// computes rows 0-1 then 2-3, team 1 rows 4-6, so that one wavefront's store phase (LDS transposition, address
+// arithmetic, stores) runs while the other keeps the SIMD's matrix pipe busy.
+template <int TEAMS>
+__global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const ConvParams p, const uint16_t* __restrict__ I,
+                                                                        const uint16_t* __restrict__ F, float* __restrict__ O) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  unsigned char* lf = lds;
+  unsigned char* lp = lds + C_FILTER_BYTES;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int n = blockIdx.x / p.strips_per_image;
+  const int y0 = (blockIdx.x - n * p.strips_per_image) * W4_ROWS;
+  const int PW = p.W + 2;
+  constexpr int PR = W4_ROWS + 2;
+
+  // ---- staging.  Every global load of the lane is in flight before the first LDS store.
+  // A lane keeps its 16-byte chunk index c = t&7 and walks pixels: filter rows (t>>3) + 32u (its LDS swizzle
+  // key does not depend on u), patch columns (t>>3) + 32*pass of every patch row.  Rows are uniform, so a row's
+  // base address is scalar and the loads add one per-lane byte offset; halo pixels and rows outside the image
+  // are loaded from a clamped address and replaced by zeros.
+  constexpr int NT = 256 * TEAMS;
+  constexpr int W4_FQ = C_TAPS * C_CO * 8 / NT;   // filter chunks per lane
+  constexpr int PPR = 2 / TEAMS;                  // passes over a patch row: the host admits only (W+2)*8 <= 512
+  const int c = t & 7, px = t >> 3;
+  const u32x4* fg = (const u32x4*)(F + p.f_base) + t;
+  u32x4 fv[W4_FQ], pv[PR][PPR];
+#pragma unroll
+  for (int u = 0; u < W4_FQ; ++u) fv[u] = fg[u * NT];
+  const char* ig = (const char*)(I + p.i_base + (int64_t)n * p.i_n);
+  uint32_t goff[PPR];
+  bool cvalid[PPR], cwrite[PPR];
+#pragma unroll
+  for (int k = 0; k < PPR; ++k) {
+    const int col = px + (NT / 8) * k, x = col - 1;
+    cvalid[k] = x >= 0 && x < p.W;
+    cwrite[k] = col < PW;
+    const int xc = x < 0 ? 0 : (x >= p.W ? p.W - 1 : x);
+    goff[k] = (uint32_t)(xc * (int)p.i_x + c * 8) * 2u;
+  }
+#pragma unroll
+  for (int r = 0; r < PR; ++r) {
+    const int y = y0 - 1 + r;
+    const int yc = y < 0 ? 0 : (y >= p.H ? p.H - 1 : y);
+    const char* rp = ig + (int64_t)yc * p.i_y * 2;
+#pragma unroll
+    for (int k = 0; k < PPR; ++k) pv[r][k] = *(const u32x4*)(rp + goff[k]);
+  }
+  {
+    unsigned char* dst = lf + px * 128 + ((c ^ ((px >> 1) & 7)) << 4);
+#pragma unroll
+    for (int u = 0; u < W4_FQ; ++u) *(u32x4*)(dst + u * (NT * 16)) = fv[u];
+  }
+#pragma unroll
+  for (int r = 0; r < PR; ++r) {
+    const int y = y0 - 1 + r;
+    const bool rvalid = y >= 0 && y < p.H;
+#pragma unroll
+    for (int k = 0; k < PPR; ++k) {
+      const int pix = r * PW + px + (NT / 8) * k;
+      const u32x4 zero = {0u, 0u, 0u, 0u};
+      const u32x4 v = (rvalid && cvalid[k]) ? pv[r][k] : zero;
+      if (cwrite[k]) *(u32x4*)(lp + pix * 128 + (swz(pix, c) << 4)) = v;
+    }
+  }
+  __syncthreads();
+
+  // ---- compute: wavefront = (pixel half mh, channel half nh), 7 rows
+  const int team = wave >> 2, mh = (wave >> 1) & 1, nh = wave & 1;
+  const int fr = lane & 31, fh = lane >> 5;
+  const int xcl = mh * 32 + fr < p.W ? mh * 32 + fr : p.W - 1;   // columns beyond W are computed on a clamped pixel, never stored
+  // LDS byte address of a fragment chunk = base ^ (K step << 5): the swizzle key only touches bits 4..6
+  const unsigned b_base = (unsigned)((nh * 32 + fr) * 128 + ((fh ^ ((fr >> 1) & 7)) << 4));
+
+  // store phase geometry.  Accumulator element v of lane l is pixel 8*(v/4) + 4*(l>>5) + v%4 of its 32-pixel
+  // fragment, channel l&31 of the wavefront's 32.  Each fragment goes through a 4 KB buffer of the wavefront
+  // ([pixel][32 channels], behind the patch) and leaves as 16-byte stores: 8 lanes write the 128 contiguous
+  // bytes of a pixel's channel half.
+  constexpr int OT_BYTES = 4096 / TEAMS, OT_PIXELS = 32 / TEAMS;    // a fragment leaves in TEAMS rounds of OT_PIXELS pixels
+  unsigned char* ot = lp + PR * PW * 128 + wave * OT_BYTES;
+  const int sp = lane >> 3, sc = lane & 7;          // store phase: pixel sp (+8j) of the fragment, channel quad sc
+  char* og = (char*)(O + p.o_base + (int64_t)n * p.o_n) + (nh * 32 + sc * 4) * 4;
+  unsigned char* wbase[4];     // write address of accumulator elements v = 0..3 (pixel 4*fh + v); + 1 KB per further 8 pixels
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int pixel = 4 * fh + v;
+    wbase[v] = ot + pixel * 128 + ((((fr >> 2) ^ pixel) << 4) | ((fr & 3) << 2));   // 16-byte slot = channel quad ^ (pixel & 7)
+  }
+  uint32_t ooff[4];          // pixel sp + 8j of the fragment
+  bool ovalid[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int x = mh * 32 + sp + 8 * j;
+    ovalid[j] = x < p.W;
+    ooff[j] = (uint32_t)((x < p.W ? x : 0) * (int)p.o_x) * 4u;
+  }
+
+  // Output rows are finished in three groups (3 + 2 + 2 rows) rather than all at the end, so that the stores
+  // of a group drain to memory while the next group is being computed.  Within a group of n rows, one filter
+  // column j and one 16-channel K step need the n+2 pixel fragments of the group's input rows (read once, used
+  // by the three filter rows i: output row r takes input row r+i) and 3 filter fragments for 3n matrix
+  // instructions; the fragments of the next (j, K step) are requested before the current ones are consumed.
+  auto row_group = [&](auto r0_tag, auto n_tag) {
+    constexpr int R0 = decltype(r0_tag)::value, NR = decltype(n_tag)::value;
+    f32x16 acc[NR];
+#pragma unroll
+    for (int r = 0; r < NR; ++r)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[r][v] = 0.f;
+    bf16x8 a[2][NR + 2], b[2][3];
+    unsigned a_base[NR + 2];
+    auto set_bases = [&](int tj) {
+#pragma unroll
+      for (int r = 0; r < NR + 2; ++r) {
+        const int pix = (R0 + r) * PW + xcl + tj;
+        a_base[r] = (unsigned)(pix * 128 + ((fh ^ ((pix >> 1) & 7)) << 4));
+      }
+    };
+    auto read_frags = [&](int buf, int tj, int s) {   // tj, s: compile-time after unrolling
+#pragma unroll
+      for (int r = 0; r < NR + 2; ++r) a[buf][r] = *(const bf16x8*)(lp + (a_base[r] ^ (unsigned)(s << 5)));
+#pragma unroll
+      for (int ti = 0; ti < 3; ++ti)
+        b[buf][ti] = *(const bf16x8*)(lf + (ti * 3 + tj) * (C_CO * 128) + (b_base ^ (unsigned)(s << 5)));
+    };
+    set_bases(0);
+    read_frags(0, 0, 0);
+#pragma unroll
+    for (int it = 0; it < 12; ++it) {       // it = tj * 4 + s
+      const int cur = it & 1;
+      __builtin_amdgcn_sched_barrier(0);
+      if (it + 1 < 12) {
+        if (((it + 1) & 3) == 0) set_bases((it + 1) >> 2);
+        read_frags(cur ^ 1, (it + 1) >> 2, (it + 1) & 3);
+      }
+#pragma unroll
+      for (int ti = 0; ti < 3; ++ti)
+#pragma unroll
+        for (int r = 0; r < NR; ++r)
+          acc[r] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[cur][r + ti], b[cur][ti], acc[r], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int r = 0; r < NR; ++r) {
+      const int y = y0 + R0 + r;
+      if (y < p.H) {                                   // uniform
+        char* orow = og + (int64_t)y * p.o_y * 4;
+#pragma unroll
+        for (int h = 0; h < TEAMS; ++h) {
+          constexpr int G = 4 / TEAMS;               // groups of 8 pixels per round
+#pragma unroll
+          for (int v = h * 4 * G; v < (h + 1) * 4 * G; ++v) *(float*)(wbase[v % 4] + (v / 4 - h * G) * 1024) = acc[r][v];
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int j = 0; j < G; ++j) {
+            const int pixel = sp + 8 * j;            // within the round; (pixel & 7) == sp either way
+            const f32x4s v = *(const f32x4s*)(ot + pixel * 128 + ((sc ^ (pixel & 7)) << 4));
+            if (ovalid[h * G + j]) __builtin_nontemporal_store(v, (f32x4s*)(orow + ooff[h * G + j]));
+          }
+          __builtin_amdgcn_wave_barrier();
+        }
+      }
+    }
+  };
+  if constexpr (TEAMS == 1) {
+    row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
+    row_group(std::integral_constant<int, 3>{}, std::integral_constant<int, 2>{});
+    row_group(std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{});
+  } else if (team == 0) {
+    row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
+    row_group(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{});
+  } else {
+    row_group(std::integral_constant<int, 4>{}, std::integral_constant<int, 3>{});
+  }
+}
+
+constexpr int W4_LDS_EXTRA = 4 * 4096;   // per-wavefront output transposition buffers
+
+constexpr int kConvW4Variant = 200;
+
 int rows_per_strip(const Conv2dShape& c) {
   // most rows such that the patch fits beside the filter in 160 KB and a strip has at most 7 wavefronts
   int rows = C_MAX_ROWS;
@@ -177,6 +375,27 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
   if (c.f_k != C_CI || c.f_s != C_CO * C_CI || c.f_r != 3 * C_CO * C_CI) return false;
   for (int64_t v : {c.i_n, c.i_y, c.i_x, c.i_base, c.f_base})
     if (v % 8) return false;
+  // four-wavefront kernel: strips of 7 rows, 32-bit element offsets inside an image
+  const bool offsets_fit = c.i_y >= 0 && c.i_x >= 0 && c.o_x >= 0 && (c.H * c.i_y + c.W * c.i_x + 64) < ((int64_t)1 << 30) &&
+                           (c.W * c.o_x + 64) < ((int64_t)1 << 30);
+  const int w4_lds = C_FILTER_BYTES + (W4_ROWS + 2) * ((int)c.W + 2) * 128 + W4_LDS_EXTRA;
+  const int w4_teams = tune_int("conv_w4_teams", 2) == 1 ? 1 : 2;
+  if (tune_int("conv_w4", 1) && offsets_fit && w4_lds <= 160 * 1024 && (c.W + 2) * 8 <= 512) {
+    const int64_t grid = c.N * ((c.Ho + W4_ROWS - 1) / W4_ROWS);
+    if (grid > 0x7fffffffLL) return false;
+    l->variant = kConvW4Variant + w4_teams;
+    l->grid = grid;
+    info->path = STRIPE_PATH_MFMA_CONV;
+    info->tile_m = W4_ROWS * (int)c.W;
+    info->tile_n = C_CO;
+    info->tile_k = C_TAPS * C_CI;
+    info->frag_m = 32; info->frag_n = 32; info->frag_k = 16;
+    info->lds_bytes = w4_lds;
+    info->workgroup_size = 256 * w4_teams;
+    info->grid = grid;
+    snprintf(info->kernel, sizeof info->kernel, "conv3x3_bf16_c64k64_strip7_w%d_mfma32x32x16", 4 * w4_teams);
+    return true;
+  }
   const int rows = rows_per_strip(c);
   // a lane stages at most 11 filter chunks and 11 patch chunks
   if ((int64_t)rows * 64 * 11 < C_TAPS * C_CO * 8 || (int64_t)rows * 64 * 11 < (int64_t)(rows + 2) * (c.W + 2) * 8) return false;
@@ -198,8 +417,29 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
 }
 
 hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
-  if (l.variant >= 100) return launch_conv_i8(c, l, in, flt, out, st);
+  if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
+  if (l.variant > kConvW4Variant) {
+    const bool two = l.variant == kConvW4Variant + 2;
+    const ConvParams pp = make_params(c, W4_ROWS);
+    const int lds_w4 = C_FILTER_BYTES + (W4_ROWS + 2) * ((int)c.W + 2) * 128 + W4_LDS_EXTRA;
+    const void* fn = two ? (const void*)conv3x3_bf16_w4_kernel<2> : (const void*)conv3x3_bf16_w4_kernel<1>;
+    int dev4 = -1;
+    hipError_t e4 = hipGetDevice(&dev4);
+    if (e4 != hipSuccess) return e4;
+    if (dev4 != l.lds_enabled_on) {
+      e4 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      if (e4 != hipSuccess) return e4;
+      l.lds_enabled_on = dev4;
+    }
+    if (two)
+      hipLaunchKernelGGL(conv3x3_bf16_w4_kernel<2>, dim3((unsigned)l.grid), dim3(512), lds_w4, st, pp, (const uint16_t*)in,
+                         (const uint16_t*)flt, (float*)out);
+    else
+      hipLaunchKernelGGL(conv3x3_bf16_w4_kernel<1>, dim3((unsigned)l.grid), dim3(256), lds_w4, st, pp, (const uint16_t*)in,
+                         (const uint16_t*)flt, (float*)out);
+    return hipGetLastError();
+  }
   const int rows = l.variant;
   const ConvParams p = make_params(c, rows);
   const int lds_bytes = C_FILTER_BYTES + (rows + 2) * ((int)c.W + 2) * 128;

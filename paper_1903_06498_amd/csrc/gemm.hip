@@ -433,24 +433,45 @@ __device__ __forceinline__ void d_read_b(const DCtx& c, const unsigned char* lds
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(p + 4 * 512));
   bf[Q] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
-// fragments of group Q (of 4) of a K step: A fragment Q, and B fragment Q while there are any left
-template <int STAGE_N, int S, int Q, int FN>
+// Fragment reads of a K step, spread over the four instruction groups that precede their first use.
+// The first matrix instruction of the next step needs every B fragment and A fragment 0, so those are
+// read first; the last group reads nothing, so that neither the barrier that follows group 3 (it waits
+// for the wavefront's outstanding LDS reads) nor the first group of the next step meets a read that has
+// only just been issued.
+template <int SCHED, int STAGE_N, int S, int Q, int FN>
 __device__ __forceinline__ void d_read_group(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[FN]) {
-  d_read_a<STAGE_N, S, Q>(c, lds, af);
-  if constexpr (Q < FN) d_read_b<STAGE_N, S, Q, FN>(c, lds, bf);
+  if constexpr (SCHED == 0) {   // plain order: group Q reads A fragment Q and B fragment Q
+    d_read_a<STAGE_N, S, Q>(c, lds, af);
+    if constexpr (Q < FN) d_read_b<STAGE_N, S, Q, FN>(c, lds, bf);
+  } else if constexpr (FN == 4) {
+    if constexpr (Q == 0) { d_read_b<STAGE_N, S, 0, FN>(c, lds, bf); d_read_b<STAGE_N, S, 1, FN>(c, lds, bf); }
+    if constexpr (Q == 1) { d_read_b<STAGE_N, S, 2, FN>(c, lds, bf); d_read_b<STAGE_N, S, 3, FN>(c, lds, bf); d_read_a<STAGE_N, S, 0>(c, lds, af); }
+    if constexpr (Q == 2) { d_read_a<STAGE_N, S, 1>(c, lds, af); d_read_a<STAGE_N, S, 2>(c, lds, af); d_read_a<STAGE_N, S, 3>(c, lds, af); }
+  } else {
+    if constexpr (Q == 0) { d_read_b<STAGE_N, S, 0, FN>(c, lds, bf); d_read_b<STAGE_N, S, 1, FN>(c, lds, bf); d_read_a<STAGE_N, S, 0>(c, lds, af); }
+    if constexpr (Q == 1) { d_read_a<STAGE_N, S, 1>(c, lds, af); d_read_a<STAGE_N, S, 2>(c, lds, af); }
+    if constexpr (Q == 2) { d_read_a<STAGE_N, S, 3>(c, lds, af); }
+  }
 }
 template <int STAGE_N, int S, int FN>
 __device__ __forceinline__ void d_read_frags(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[FN]) {
-  d_read_group<STAGE_N, S, 0, FN>(c, lds, af, bf);
-  d_read_group<STAGE_N, S, 1, FN>(c, lds, af, bf);
-  d_read_group<STAGE_N, S, 2, FN>(c, lds, af, bf);
-  d_read_group<STAGE_N, S, 3, FN>(c, lds, af, bf);
+  d_read_group<0, STAGE_N, S, 0, FN>(c, lds, af, bf);
+  d_read_group<0, STAGE_N, S, 1, FN>(c, lds, af, bf);
+  d_read_group<0, STAGE_N, S, 2, FN>(c, lds, af, bf);
+  d_read_group<0, STAGE_N, S, 3, FN>(c, lds, af, bf);
 }
 
 template <int Q, int FN>
 __device__ __forceinline__ void d_mfma_row(const bf16x8 (&af)[4], const bf16x8 (&bf)[FN], f32x16 (&acc)[4][FN]) {
 #pragma unroll
   for (int j = 0; j < FN; ++j) acc[Q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[Q], bf[j], acc[Q][j], 0, 0, 0);
+}
+
+// matrix instructions J0 .. J1-1 of accumulator row Q
+template <int Q, int J0, int J1, int FN>
+__device__ __forceinline__ void d_mfma_part(const bf16x8 (&af)[4], const bf16x8 (&bf)[FN], f32x16 (&acc)[4][FN]) {
+#pragma unroll
+  for (int j = J0; j < J1; ++j) acc[Q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[Q], bf[j], acc[Q][j], 0, 0, 0);
 }
 
 #define D_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -484,7 +505,7 @@ __device__ __forceinline__ void d_wait_loads() {
 // ISSUE: start the loads of tile kt+3 (after the barrier).  PENDING: how many
 // younger loads (those of tile kt+2) may still be in flight when tile kt+1 must
 // have landed.
-template <int WAVES, int STAGE_N, bool ISSUE, int PENDING, bool NEXT_FRAGS>
+template <int WAVES, int SCHED, int STAGE_N, bool ISSUE, int PENDING, bool NEXT_FRAGS>
 __device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt, bf16x8 (&af)[2][4],
                                        bf16x8 (&bf)[2][WAVES == 4 ? 4 : 2], f32x16 (&acc)[4][WAVES == 4 ? 4 : 2]) {
   constexpr int FN = WAVES == 4 ? 4 : 2;
@@ -493,32 +514,37 @@ __device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt
   const uint16_t* a = c.a_src + (size_t)(kt + 3) * D_BK;
   const uint16_t* b = c.b_src + (size_t)(kt + 3) * c.b_kstep;
   D_FENCE();
-  d_mfma_row<0, FN>(af[0], bf[0], acc); d_read_group<STAGE_N, 1, 0, FN>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<1, FN>(af[0], bf[0], acc); d_read_group<STAGE_N, 1, 1, FN>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<2, FN>(af[0], bf[0], acc); d_read_group<STAGE_N, 1, 2, FN>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<3, FN>(af[0], bf[0], acc); d_read_group<STAGE_N, 1, 3, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<0, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 0, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<1, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 1, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<2, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 2, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  // the barrier sits before the group's last matrix instruction, which then covers the barrier's latency
+  constexpr int EARLY = SCHED == 2 ? FN - 1 : FN;   // matrix instructions of group 3 issued before the barrier
+  d_mfma_part<3, 0, EARLY, FN>(af[0], bf[0], acc);
+  if constexpr (SCHED == 0) d_read_group<SCHED, STAGE_N, 1, 3, FN>(c, lds, af[1], bf[1]);
+  D_FENCE();
   d_wait_loads<PENDING>();
   __syncthreads();
   D_FENCE();
+  d_mfma_part<3, EARLY, FN, FN>(af[0], bf[0], acc);
   d_mfma_row<0, FN>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_group<NXT, 0, 0, FN>(c, lds, af[0], bf[0]);
+  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 0, FN>(c, lds, af[0], bf[0]);
   if (ISSUE) d_issue_group<LD, WAVES, 0>(c, a, b);
   D_FENCE();
   d_mfma_row<1, FN>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_group<NXT, 0, 1, FN>(c, lds, af[0], bf[0]);
+  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 1, FN>(c, lds, af[0], bf[0]);
   if (ISSUE) d_issue_group<LD, WAVES, 1>(c, a, b);
   D_FENCE();
   d_mfma_row<2, FN>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_group<NXT, 0, 2, FN>(c, lds, af[0], bf[0]);
+  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 2, FN>(c, lds, af[0], bf[0]);
   if (ISSUE) d_issue_group<LD, WAVES, 2>(c, a, b);
   D_FENCE();
   d_mfma_row<3, FN>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_group<NXT, 0, 3, FN>(c, lds, af[0], bf[0]);
+  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 3, FN>(c, lds, af[0], bf[0]);
   if (ISSUE) d_issue_group<LD, WAVES, 3>(c, a, b);
   D_FENCE();
 }
 
-template <int WAVES>
+template <int WAVES, int SCHED>
 __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const GemmParams p, const uint16_t* __restrict__ A,
                                                                       const uint16_t* __restrict__ B, float* __restrict__ C) {
   constexpr int FN = WAVES == 4 ? 4 : 2;        // 32-column fragments per wavefront
@@ -590,15 +616,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
 
   const int last4 = p.k_tiles - 4;
   for (int kt = 0; kt < last4; kt += 4) {
-    d_tile<WAVES, 0, true, LPT, true>(c, lds, kt, af, bf, acc);
-    d_tile<WAVES, 1, true, LPT, true>(c, lds, kt + 1, af, bf, acc);
-    d_tile<WAVES, 2, true, LPT, true>(c, lds, kt + 2, af, bf, acc);
-    d_tile<WAVES, 3, true, LPT, true>(c, lds, kt + 3, af, bf, acc);
+    d_tile<WAVES, SCHED, 0, true, LPT, true>(c, lds, kt, af, bf, acc);
+    d_tile<WAVES, SCHED, 1, true, LPT, true>(c, lds, kt + 1, af, bf, acc);
+    d_tile<WAVES, SCHED, 2, true, LPT, true>(c, lds, kt + 2, af, bf, acc);
+    d_tile<WAVES, SCHED, 3, true, LPT, true>(c, lds, kt + 3, af, bf, acc);
   }
-  d_tile<WAVES, 0, true, LPT, true>(c, lds, last4, af, bf, acc);        // issues the last tile's loads
-  d_tile<WAVES, 1, false, LPT, true>(c, lds, last4 + 1, af, bf, acc);
-  d_tile<WAVES, 2, false, 0, true>(c, lds, last4 + 2, af, bf, acc);
-  d_tile<WAVES, 3, false, 0, false>(c, lds, last4 + 3, af, bf, acc);
+  d_tile<WAVES, SCHED, 0, true, LPT, true>(c, lds, last4, af, bf, acc);        // issues the last tile's loads
+  d_tile<WAVES, SCHED, 1, false, LPT, true>(c, lds, last4 + 1, af, bf, acc);
+  d_tile<WAVES, SCHED, 2, false, 0, true>(c, lds, last4 + 2, af, bf, acc);
+  d_tile<WAVES, SCHED, 3, false, 0, false>(c, lds, last4 + 3, af, bf, acc);
 
   const int fr = lane & 31, fh = lane >> 5;
   float* c_g = C + p.c_base + ((int64_t)tm * BM + wm * 128 + 4 * fh) * p.c_m + (int64_t)tn * BN + wn * 32 * FN + fr;
@@ -638,7 +664,9 @@ bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_i
   if ((g.K / BK) % 2) waves = 8;   // the four-wavefront pipeline consumes K tiles in pairs
   const bool dma = tune_int("gemm_dma", 1) != 0 && g.K % (D_BK * D_STAGES) == 0 && g.K >= D_BK * D_STAGES;
   const int dma_waves = tune_int("gemm_dma_waves", 4) == 8 ? 8 : 4;
-  l->variant = dma ? (dma_waves == 8 ? 21 : 20) : (waves == 8 ? 10 : 0) + swz;
+  int sched = tune_int("gemm_sched", 1);   // 0: plain read order, 1: reads ahead of use, 2: also barrier before the last instruction of its group
+  if (sched < 0 || sched > 2 || dma_waves == 8) sched = 1;
+  l->variant = dma ? (dma_waves == 8 ? 21 : sched == 0 ? 22 : sched == 2 ? 23 : 20) : (waves == 8 ? 10 : 0) + swz;
   l->grid = (g.M / BM) * (g.N / BN);
   info->path = STRIPE_PATH_MFMA_GEMM;
   info->tile_m = BM; info->tile_n = BN; info->tile_k = dma ? D_BK : BK;
@@ -646,7 +674,8 @@ bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_i
   info->lds_bytes = dma ? D_LDS : 2 * STAGE;
   info->workgroup_size = dma ? dma_waves * 64 : (waves == 8 ? THREADS : W4_THREADS);
   info->grid = l->grid;
-  if (dma) snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x32_mfma32x32x16_w%d_lds_direct", dma_waves);
+  if (dma) snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x32_mfma32x32x16_w%d_lds_direct%s", dma_waves,
+                    sched == 0 ? "_s0" : sched == 2 ? "_s2" : "");
   else snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x64_mfma32x32x16_w%d_swz%d", waves, swz);
   return true;
 }
@@ -657,8 +686,10 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
   void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = nullptr;
   switch (l.variant) {
     case 0: case 1: case 2: kernel = gemm_bf16_w4_kernel; break;
-    case 20: kernel = gemm_bf16_dma_kernel<4>; break;
-    case 21: kernel = gemm_bf16_dma_kernel<8>; break;
+    case 20: kernel = gemm_bf16_dma_kernel<4, 1>; break;
+    case 21: kernel = gemm_bf16_dma_kernel<8, 1>; break;
+    case 22: kernel = gemm_bf16_dma_kernel<4, 0>; break;
+    case 23: kernel = gemm_bf16_dma_kernel<4, 2>; break;
     case 10: kernel = gemm_bf16_w8_kernel<0>; break;
     case 11: kernel = gemm_bf16_w8_kernel<1>; break;
     default: kernel = gemm_bf16_w8_kernel<2>; break;
