@@ -330,11 +330,12 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
     row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
     row_group(std::integral_constant<int, 3>{}, std::integral_constant<int, 2>{});
     row_group(std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{});
-  } else if (team == 0) {
-    row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 2>{});
-    row_group(std::integral_constant<int, 2>{}, std::integral_constant<int, 2>{});
+  } else if (team == 0) {   // a single row first: the sooner the first stores leave, the sooner the write stream starts
+    row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
+    row_group(std::integral_constant<int, 1>{}, std::integral_constant<int, 3>{});
   } else {
-    row_group(std::integral_constant<int, 4>{}, std::integral_constant<int, 3>{});
+    row_group(std::integral_constant<int, 4>{}, std::integral_constant<int, 1>{});
+    row_group(std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{});
   }
 }
 

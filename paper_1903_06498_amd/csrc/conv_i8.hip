@@ -32,7 +32,8 @@ constexpr int Q_MAX_WO = 112;                  // 7 column fragments of 16
 constexpr int Q_BT_BYTES = 4 * Q_CO * 64;      // filter as K vectors: [K step][k][64 B]
 
 struct I8Params {
-  int32_t H, W, Ho, Wo, strips_per_image, raw_row_bytes, total_strips, pad_;
+  int32_t H, W, Ho, Wo, strips_per_image, raw_row_bytes, total_strips;
+  uint32_t chunks_magic, wo_magic;   // ceil(2^32 / d) for d = chunks per raw row and Wo: q / d = umulhi(q, magic) for q < 2^16
   int64_t i_n, i_y;            // input strides in elements (= bytes); pixels and channels are contiguous
   int64_t o_n, o_y, o_x;       // output strides in elements; channels contiguous
   int64_t i_base, f_base, o_base;
@@ -50,7 +51,7 @@ __device__ __forceinline__ void q_load_raw(const I8Params& p, const int8_t* __re
 #pragma unroll
   for (int u = 0; u < RAWQ; ++u) {
     const int q = t + u * NT;
-    const int r = q / row_chunks, c = q - r * row_chunks;
+    const int r = (int)__umulhi((unsigned)q, p.chunks_magic), c = q - r * row_chunks;
     const int y = 2 * y0 - 3 + r;
     rv[u] = (u32x4){0u, 0u, 0u, 0u};
     if (strip < p.total_strips && q < Q_ROWS * row_chunks && c >= 1 && c <= data_chunks && y >= 0 && y < p.H)
@@ -62,7 +63,7 @@ __device__ __forceinline__ void q_load_raw(const I8Params& p, const int8_t* __re
 // blockIdx.x, blockIdx.x + gridDim.x, ...  The raw rows of the next strip are fetched
 // into registers while the current strip is expanded, multiplied and stored, and the
 // stores of a strip (fire and forget) overlap the staging of the next one.
-// LDS: [Bt: 16 KB][raw: Q_ROWS x raw_row_bytes][E: Q_ROWS x Wo x 32 B][output transposition: 4 KB per wavefront]
+// LDS: [Bt: 16 KB][raw: Q_ROWS x raw_row_bytes][E: Q_ROWS x Wo x 32 B][output transposition: 2 x 4 KB per wavefront]
 template <int Q_TY>   // output rows per strip = wavefronts per workgroup
 __global__ __launch_bounds__(Q_TY * 64) void conv7x7s2_i8_kernel(const I8Params p, const int8_t* __restrict__ I,
                                                                const int8_t* __restrict__ F, int32_t* __restrict__ O) {
@@ -75,7 +76,7 @@ __global__ __launch_bounds__(Q_TY * 64) void conv7x7s2_i8_kernel(const I8Params 
   unsigned char* raw = lds + Q_BT_BYTES;
   unsigned char* ex = raw + Q_ROWS * p.raw_row_bytes;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  unsigned char* ot = ex + Q_ROWS * p.Wo * 32 + wave * 4096;   // this wavefront's output transposition buffer
+  unsigned char* ot = ex + Q_ROWS * p.Wo * 32 + wave * 8192;   // this wavefront's two output transposition buffers
   const int row_chunks = p.raw_row_bytes / 16;
 
   // ---- first strip's rows and the filter as it lies in memory (parked where E is built later);
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(Q_TY * 64) void conv7x7s2_i8_kernel(const I8Params 
 
     // ---- expand: E[r][x] = raw[r] bytes 16 + 6x - 9 .. +23 (16 + (2x-3)*3 is where column 2x-3 starts) ----
     for (int q = t; q < Q_ROWS * p.Wo; q += NT) {
-      const int r = q / p.Wo, x = q - r * p.Wo;
+      const int r = (int)__umulhi((unsigned)q, p.wo_magic), x = q - r * p.Wo;
       const int start = 6 * x + 7;
       const unsigned* src = (const unsigned*)(raw + r * p.raw_row_bytes + (start & ~3));
       const unsigned sh = start & 3;
@@ -155,41 +156,63 @@ __global__ __launch_bounds__(Q_TY * 64) void conv7x7s2_i8_kernel(const I8Params 
     }
     __syncthreads();
 
-    // ---- one wavefront per output row ----
+    // ---- one wavefront per output row.  Software pipeline over the row's 16-column fragments: the K vectors
+    // of fragment mf+1 are requested before the matrix instructions of fragment mf, and the result tile of
+    // fragment mf leaves (LDS read-back + global stores) while fragment mf+1 is multiplied, through two
+    // alternating transposition buffers.
     const int y = y0 + wave;
     if (y < p.Ho) {
       const int n_mf = p.Wo / 16;
       int32_t* og = O + p.o_base + (int64_t)n * p.o_n + (int64_t)y * p.o_y;
-      for (int mf = 0; mf < n_mf; ++mf) {
+      // E row of K step ks for this lane: image row 2y + i - 3 relative to the strip's first row; the eighth
+      // filter row has zero weights, so any row will do for it
+      int erow[4];
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const int r = 2 * wave + 2 * ks + (kq >> 1);
+        erow[ks] = (r < Q_ROWS ? r : Q_ROWS - 1) * p.Wo;
+      }
+      auto load_a = [&](int mf, i32x4 (&a)[4]) {
         const int x = mf * 16 + fr;
+        const int half = ((kq & 1) ^ ((x >> 3) & 1)) * 16;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) a[ks] = *(const i32x4*)(ex + (erow[ks] + x) * 32 + half);
+      };
+      // a tile leaves: lane (px = 4j + kq, slot fr) reads 16 bytes and stores them; every store instruction
+      // writes 4 whole pixels = 1 KB of consecutive addresses when pixels are contiguous
+      auto drain = [&](int mf) {
+        const unsigned char* buf = ot + (mf & 1) * 4096;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int px = 4 * j + kq;
+          const i32x4 v = *(const i32x4*)(buf + px * 256 + ((fr ^ px) << 4));
+          *(i32x4*)(og + (int64_t)(mf * 16 + px) * p.o_x + fr * 4) = v;
+        }
+      };
+      i32x4 a_cur[4], a_nxt[4];
+      load_a(0, a_cur);
+      for (int mf = 0; mf < n_mf; ++mf) {
+        if (mf + 1 < n_mf) load_a(mf + 1, a_nxt);
         i32x4 acc[4];
 #pragma unroll
         for (int nf = 0; nf < 4; ++nf) acc[nf] = (i32x4){0, 0, 0, 0};
+        // filter fragment as the row operand, pixels as the column operand: the result fragment is
+        // (channel, pixel) and a lane ends up with 4 consecutive channels of one pixel
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-          int r = 2 * wave + 2 * ks + (kq >> 1);              // image row 2y + i - 3 relative to the strip's first row
-          r = r < Q_ROWS ? r : Q_ROWS - 1;                    // the eighth filter row has zero weights: any row will do
-          const int half = ((kq & 1) ^ ((x >> 3) & 1)) * 16;
-          const i32x4 a = *(const i32x4*)(ex + (r * p.Wo + x) * 32 + half);
+        for (int ks = 0; ks < 4; ++ks)
 #pragma unroll
-          // filter fragment as the row operand, pixels as the column operand: the result fragment is
-          // (channel, pixel) and a lane ends up with 4 consecutive channels of one pixel -> one 16-byte store
-          for (int nf = 0; nf < 4; ++nf) acc[nf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bfr[ks][nf], a, acc[nf], 0, 0, 0);
-        }
-        // accumulator element v of lane l: channel 4*(l>>4) + v of the fragment, pixel l&15.  The 16 x 64
-        // tile goes through a per-wavefront 4 KB LDS buffer (16-byte slots XOR-swizzled with the pixel) so that
-        // every store instruction writes 4 whole pixels = 1 KB of consecutive addresses when pixels are contiguous.
+          for (int nf = 0; nf < 4; ++nf) acc[nf] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bfr[ks][nf], a_cur[ks], acc[nf], 0, 0, 0);
+        if (mf > 0) drain(mf - 1);          // written one iteration ago: no wait on LDS
+        // accumulator element v of lane l: channel 4*(l>>4) + v of the fragment, pixel l&15 -> 16-byte slots
+        // XOR-swizzled with the pixel
+        unsigned char* buf = ot + (mf & 1) * 4096;
 #pragma unroll
-        for (int nf = 0; nf < 4; ++nf) *(i32x4*)(ot + fr * 256 + (((nf * 4 + kq) ^ fr) << 4)) = acc[nf];
+        for (int nf = 0; nf < 4; ++nf) *(i32x4*)(buf + fr * 256 + (((nf * 4 + kq) ^ fr) << 4)) = acc[nf];
         __builtin_amdgcn_wave_barrier();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int px = 4 * j + kq;                        // pixel of the tile this lane stores for, slot fr
-          const i32x4 v = *(const i32x4*)(ot + px * 256 + ((fr ^ px) << 4));
-          *(i32x4*)(og + (int64_t)(mf * 16 + px) * p.o_x + fr * 4) = v;
-        }
-        __builtin_amdgcn_wave_barrier();
+        for (int ks = 0; ks < 4; ++ks) a_cur[ks] = a_nxt[ks];
       }
+      drain(n_mf - 1);
     }
     __syncthreads();   // E and raw are rewritten by the next strip
   }
@@ -201,7 +224,8 @@ I8Params make_params(const Conv2dShape& c, int Q_TY) {
   p.strips_per_image = (int)((c.Ho + Q_TY - 1) / Q_TY);
   p.raw_row_bytes = 16 + (int)c.W * Q_CI + 16;
   p.total_strips = (int)c.N * p.strips_per_image;
-  p.pad_ = 0;
+  p.chunks_magic = (uint32_t)((((uint64_t)1 << 32) + (p.raw_row_bytes / 16) - 1) / (p.raw_row_bytes / 16));
+  p.wo_magic = (uint32_t)((((uint64_t)1 << 32) + p.Wo - 1) / p.Wo);
   p.i_n = c.i_n; p.i_y = c.i_y;
   p.o_n = c.o_n; p.o_y = c.o_y; p.o_x = c.o_x;
   p.i_base = c.i_base; p.f_base = c.f_base; p.o_base = c.o_base;
@@ -210,7 +234,7 @@ I8Params make_params(const Conv2dShape& c, int Q_TY) {
 
 int lds_bytes_for(const I8Params& p, int Q_TY) {
   const int Q_ROWS = 2 * Q_TY + 5;
-  return Q_BT_BYTES + Q_ROWS * p.raw_row_bytes + Q_ROWS * p.Wo * 32 + Q_TY * 4096;
+  return Q_BT_BYTES + Q_ROWS * p.raw_row_bytes + Q_ROWS * p.Wo * 32 + Q_TY * 8192;
 }
 
 constexpr int kStripChoices[] = {2, 4, 7, 8};
