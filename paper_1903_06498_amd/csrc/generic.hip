@@ -47,6 +47,40 @@ struct Elem<float> {
   static __device__ __forceinline__ float load(const void* p, int64_t i) { return ((const float*)p)[i]; }
 };
 
+// Identity of the aggregation: what an output element holds before the atomic combine pass.
+template <int AGG>
+__device__ __forceinline__ int32_t identity_of(int32_t) {
+  return AGG == STRIPE_AGG_MAX ? (int32_t)0x80000000 : AGG == STRIPE_AGG_MIN ? 0x7fffffff : 0;
+}
+template <int AGG>
+__device__ __forceinline__ float identity_of(float) {
+  return AGG == STRIPE_AGG_MAX ? -__builtin_huge_valf() : AGG == STRIPE_AGG_MIN ? __builtin_huge_valf() : 0.f;
+}
+
+// Atomic aggregation onto one output element.  Integer operations are exact in any order; float sums
+// depend on the order (the paper leaves the order of a floating-point aggregation open, Section 3.2);
+// float max/min are exact and use a compare-and-swap loop.
+template <int AGG>
+__device__ __forceinline__ void atomic_combine(int32_t* p, int32_t v) {
+  if (AGG == STRIPE_AGG_MAX) atomicMax(p, v);
+  else if (AGG == STRIPE_AGG_MIN) atomicMin(p, v);
+  else atomicAdd(p, v);
+}
+template <int AGG>
+__device__ __forceinline__ void atomic_combine(float* p, float v) {
+  if (AGG == STRIPE_AGG_MAX || AGG == STRIPE_AGG_MIN) {
+    unsigned* u = (unsigned*)p;
+    unsigned seen = __hip_atomic_load(u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    while (AGG == STRIPE_AGG_MAX ? v > __uint_as_float(seen) : v < __uint_as_float(seen)) {
+      const unsigned prev = atomicCAS(u, seen, __float_as_uint(v));
+      if (prev == seen) break;
+      seen = prev;
+    }
+  } else {
+    atomicAdd(p, v);
+  }
+}
+
 template <int AGG, typename A>
 __device__ __forceinline__ A combine(A acc, A v) {
   if (AGG == STRIPE_AGG_MAX) return v > acc ? v : acc;
@@ -61,12 +95,17 @@ __device__ __forceinline__ uint64_t swap_blocks(uint64_t m, int d) {
   return ((m & low) << d) | ((m >> d) & low);
 }
 
+// pass: 0 = the output map is injective on the output indexes, every lane (or wavefront) owns its element and
+// stores it; 1 and 2 = two launches for maps where several output-index tuples share an element: pass 1
+// writes the aggregation's identity to every element some point reaches (all writers write the same value),
+// pass 2 combines each tuple's partial result onto it atomically.  Elements no point reaches stay untouched.
+//
 // NARROW: the planner has shown that every element offset, every constraint
 // value and the output count fit in 32 bits, so all index arithmetic (and the
 // divisions that decode a flat position into indexes) runs in 32-bit.
 template <typename TIn, int INTR, int AGG, int LANES, bool NARROW>
 __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, const void* __restrict__ in0,
-                                                      const void* __restrict__ in1, void* __restrict__ out) {
+                                                      const void* __restrict__ in1, void* __restrict__ out, const int pass) {
   using Acc = typename Elem<TIn>::Acc;
   using I = typename std::conditional<NARROW, int32_t, int64_t>::type;    // offsets and constraint values
   using U = typename std::conditional<NARROW, uint32_t, uint64_t>::type;  // flat output position
@@ -99,6 +138,10 @@ __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, con
   bool touched = false;
 
   auto visit = [&](I oa, I ob) {
+    if (pass == 1) {        // identity pass: only whether the tuple has a point matters
+      touched = true;
+      return;
+    }
     const Acc a = Elem<TIn>::load(in0, oa);
     Acc v = a;
     if (INTR != STRIPE_INTR_COPY) {
@@ -107,6 +150,13 @@ __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, con
     }
     acc = touched ? combine<AGG, Acc>(acc, v) : v;
     touched = true;
+  };
+
+  auto finish = [&](I off) {
+    Acc* dst = (Acc*)out + off;
+    if (pass == 0) *dst = acc;
+    else if (pass == 1) *dst = identity_of<AGG>(Acc());
+    else atomic_combine<AGG>(dst, acc);
   };
 
   if (LANES == 1) {
@@ -141,7 +191,7 @@ __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, con
         ob += sb;
       }
     }
-    if (touched) ((Acc*)out)[offO] = acc;
+    if (touched) finish(offO);
   } else {
     for (uint32_t r = lane; r < p.red_total; r += 64) {
       I oa = offA, ob = offB;
@@ -178,24 +228,21 @@ __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, con
       }
       mask |= partner;
     }
-    if (lane == 0 && touched) ((Acc*)out)[offO] = acc;
+    if (lane == 0 && touched) finish(offO);
   }
 }
 
 template <typename TIn, int INTR, int AGG>
 hipError_t launch_lanes(const GenericParams& p, const void* a, const void* b, void* o, hipStream_t s) {
-  if (p.lanes == 64) {
-    const int64_t grid = (p.n_outputs + 3) / 4;
-    if (p.narrow)
-      hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 64, true>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
-    else
-      hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 64, false>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+  const int64_t grid = p.lanes == 64 ? (p.n_outputs + 3) / 4 : (p.n_outputs + 255) / 256;
+  void (*kernel)(const GenericParams, const void*, const void*, void*, const int) =
+      p.lanes == 64 ? (p.narrow ? generic_kernel<TIn, INTR, AGG, 64, true> : generic_kernel<TIn, INTR, AGG, 64, false>)
+                    : (p.narrow ? generic_kernel<TIn, INTR, AGG, 1, true> : generic_kernel<TIn, INTR, AGG, 1, false>);
+  if (p.atomic) {
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o, 1);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o, 2);
   } else {
-    const int64_t grid = (p.n_outputs + 255) / 256;
-    if (p.narrow)
-      hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 1, true>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
-    else
-      hipLaunchKernelGGL((generic_kernel<TIn, INTR, AGG, 1, false>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+    hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o, 0);
   }
   return hipGetLastError();
 }
@@ -242,8 +289,8 @@ void generic_info(const Plan& plan, stripe_block_info_t* info) {
   info->lds_bytes = 0;
   info->workgroup_size = 256;
   info->grid = p.lanes == 64 ? (p.n_outputs + 3) / 4 : (p.n_outputs + 255) / 256;
-  snprintf(info->kernel, sizeof info->kernel, "generic_affine_%s%s", p.lanes == 64 ? "wave_per_output" : "lane_per_output",
-           p.narrow ? "" : "_i64");
+  snprintf(info->kernel, sizeof info->kernel, "generic_affine_%s%s%s", p.lanes == 64 ? "wave_per_output" : "lane_per_output",
+           p.narrow ? "" : "_i64", p.atomic ? "_atomic" : "");
 }
 
 // ---------------------------------------------------------------------------

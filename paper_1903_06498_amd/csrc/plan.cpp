@@ -706,23 +706,28 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
     const int64_t x = o.c[a] < 0 ? -o.c[a] : o.c[a], y = o.c[b] < 0 ? -o.c[b] : o.c[b];
     return x != y ? x < y : a < b;
   });
-  {
-    i128 span = 0;
-    for (int j : out_idx) {
-      const i128 s = o.c[j] < 0 ? -(i128)o.c[j] : (i128)o.c[j];
-      if (s <= span)
-        return bad(err, STRIPE_ERR_UNSUPPORTED,
-                   "several index tuples write the same output element through different output indexes "
-                   "(needs atomic aggregation, not built)");
-      span += s * (fb.range[j] - 1);
-    }
+  bool injective = true;
+  i128 span = 0;
+  for (int j : out_idx) {
+    const i128 s = o.c[j] < 0 ? -(i128)o.c[j] : (i128)o.c[j];
+    if (s <= span) injective = false;
+    span += s * (fb.range[j] - 1);
+  }
+  if (!injective) {
+    // Several index tuples reach one output element through different output indexes (an access like
+    // O[x + i]).  The aggregation still defines the result (Definition 2, rule 3); the generic kernel then
+    // combines the per-tuple partial results with atomic operations.  'assign' allows a single writer only.
+    if (fb.agg == STRIPE_AGG_ASSIGN)
+      return bad(err, STRIPE_ERR_ASSIGN_CONFLICT, "'assign' output reached by several index tuples through different output indexes");
+    if (span + 1 < outs) info.output_elements = (int64_t)(span + 1);   // at most the addresses between the extremes
+    info.algorithmic_bytes -= (int64_t)(outs - info.output_elements) * dtype_bytes(fb.ref[R - 1].dtype);
   }
   if (fb.agg == STRIPE_AGG_ASSIGN && !red_idx.empty())
     return bad(err, STRIPE_ERR_ASSIGN_CONFLICT, "'assign' output with an index that does not move the output address");
 
-  const bool is_gemm = match_gemm(fb, &plan->gemm);
-  const bool is_conv = match_conv2d(fb, &plan->conv);
-  const bool is_pool = match_pool2d(fb, &plan->pool);
+  const bool is_gemm = injective && match_gemm(fb, &plan->gemm);
+  const bool is_conv = injective && match_conv2d(fb, &plan->conv);
+  const bool is_pool = injective && match_pool2d(fb, &plan->pool);
   stripe_path_t path = forced;
   if (path == STRIPE_PATH_AUTO) {
     path = is_gemm ? STRIPE_PATH_MFMA_GEMM : is_conv ? STRIPE_PATH_MFMA_CONV : is_pool ? STRIPE_PATH_POOL : STRIPE_PATH_GENERIC;
@@ -814,6 +819,7 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
     bool narrow = (i128)outs + 256 <= lim && reach(A) <= lim && reach(o) <= lim && (!B || reach(*B) <= lim);
     for (const Affine& c : fb.cons) narrow = narrow && reach(c) <= lim;
     g.narrow = narrow ? 1 : 0;
+    g.atomic = injective ? 0 : 1;
   }
   if (path == STRIPE_PATH_GENERIC && !gen_ok) return bad(err, STRIPE_ERR_UNSUPPORTED, gen_why);
   if (!gen_ok) g.n_outputs = -1;  // marks "no generic fallback"

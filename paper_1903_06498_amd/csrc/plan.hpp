@@ -90,6 +90,7 @@ struct GenericParams {
   int64_t cons_const[kGenCons];
   int64_t n_outputs;
   uint32_t red_total, inner_range;
+  int32_t atomic, pad_;            // 1: output map not injective on the output indexes -> identity pass + atomic combine
 };
 
 struct Plan {

@@ -97,7 +97,11 @@ def test_assign_and_multi_writer_rules():
     assert status_of(tiled) == 0
     bufs2 = [W.Buffer("A", "in", "f32", (6,)), W.Buffer("B", "in", "f32", (3,)), W.Buffer("O", "out", "f32", (8,))]
     scatter = W.flat_block(bufs2, dict(x=6, i=3), [(["x"], "assign"), (["i"], "assign"), (["x + i"], "add")])
-    assert status_of(scatter) == 3               # O[x+i]: needs atomics, not built
+    sb = B.StripeBlock(scatter)                  # O[x+i]: several (x, i) tuples share an element -> atomic combine
+    assert sb.info["kernel"].endswith("_atomic") and sb.info["output_elements"] == 8
+    scatter_assign = W.flat_block(bufs2, dict(x=6, i=3), [(["x"], "assign"), (["i"], "assign"), (["x + i"], "assign")])
+    assert status_of(scatter_assign) == 5        # 'assign' tolerates one writer only
+    assert status_of(scatter, "mfma_gemm") == 3
 
 
 def test_malformed_descriptors():
