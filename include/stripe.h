@@ -159,7 +159,10 @@ stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, st
  * refinement's buffer origin, output that of the output buffer; element types
  * and extents as declared at the root.  Output elements no iteration writes
  * keep their contents; written elements are overwritten (prior contents do
- * not enter the aggregation).  Asynchronous: returns after enqueueing; only
+ * not enter the aggregation).  A block whose output elements are shared
+ * between index tuples through different output indexes (O[x + i]) is run as
+ * two launches: the aggregation's identity to every reached element, then an
+ * atomic combine.  Asynchronous: returns after enqueueing; only
  * launch errors are reported.  Calls on different handles may overlap; two
  * overlapping calls that write the same output buffer race.
  */
@@ -183,6 +186,72 @@ const char* stripe_last_error(void);
  * state the achievable HBM rate next to the pooling kernels.
  */
 stripe_status_t stripe_device_copy(const void* src, void* dst, size_t n_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------------
+ * Autotiling (paper Section 3.3, Figures 4 and 5): host-only integer code.
+ *
+ * All three calls take the FLAT form of a block: the declaring root (no
+ * indexes) whose child is the leaf.  A tile gives one size per leaf index,
+ * 1 <= tile[j] <= ranges[j]; tile[j] == ranges[j] leaves index j whole.
+ *
+ * Cost model (Figure 4's caption): cache lines touched per unit of work.
+ * For every counted refinement the tile's view is the box its accesses span
+ * over one tile, overflow and halo included (constraints remove those
+ * accesses at run time but the view still holds them).  Lines of a view =
+ * product of its extents, the stride-1 dimension counted in whole lines
+ * (views taken as line-aligned); footprint = product of its extents.
+ *   cost = tiles * lines_per_tile / work,   tiles = prod ceil(range_j / tile_j),
+ * work = product of the ranges of the indexes in `tiled_idx` (the figure
+ * counts work in points of the tiled, spatial indexes: with 8 input
+ * channels, 16 output channels, lines of 8 elements and a 512-element cap
+ * this reproduces its 4.5 for the 3 x 4 tile and 4.666 for 6 x 2; dividing
+ * by multiply-accumulates instead scales every cost of a block by one
+ * constant).  A tile is inadmissible if its footprint exceeds the cap, or
+ * if it violates `multiple_of` / `power_of_two` (Section 3.3: memory cap,
+ * multiples of an earlier tensorisation, power-of-two pruning); a size equal
+ * to the whole range is always allowed.
+ */
+typedef struct {
+  int64_t line_elems;         /* cache line size in elements, >= 1 */
+  int64_t mem_cap_elems;      /* cap on the summed footprints of the counted views, in elements; 0 = no cap */
+  uint32_t counted_refs;      /* bit r: refinement r (descriptor order) counts toward lines and footprint */
+  uint32_t tiled_idx;         /* bit j: index j may be tiled by the search and counts as work */
+  int32_t power_of_two;       /* non-zero: the search tries power-of-two sizes only */
+  const int64_t* multiple_of; /* [n_idx] or NULL: tile[j] must be a multiple of multiple_of[j] (entries < 1 = 1) */
+} stripe_tile_model_t;
+
+typedef struct {
+  int64_t tiles;
+  int64_t lines_per_tile;
+  int64_t footprint_elems;
+  int64_t work;
+  double cost;
+  int32_t admissible;
+} stripe_tile_cost_t;
+
+/* Cost of one given tile.  STRIPE_ERR_INVALID_DESC if root is not a flat form or a size is out of range. */
+stripe_status_t stripe_tile_cost(const stripe_block_desc_t* root, const int64_t* tile, const stripe_tile_model_t* model,
+                                 stripe_tile_cost_t* out);
+
+/* Exhaustive search over the sizes of the indexes in model->tiled_idx (all others stay whole).
+ * best_tile[n_idx] receives the admissible tile of least cost; ties go to fewer tiles, then to the
+ * lexicographically larger tile.  STRIPE_ERR_UNSUPPORTED if no tile is admissible or the space
+ * exceeds 2^22 candidates. */
+stripe_status_t stripe_tile_search(const stripe_block_desc_t* root, const stripe_tile_model_t* model, int64_t* best_tile,
+                                   stripe_tile_cost_t* best);
+
+/*
+ * The tiling rewrite (Section 3.3; Figure 5a -> 5b): returns a new nest
+ * root -> outer block (ranges ceil(range_j / tile_j), refinements with the
+ * tile's views: offsets scaled by the tile size, sizes including the halo) ->
+ * inner block (ranges tile_j, accesses relative to the view, the original
+ * constraints with every tiled index replaced by "passed outer value + inner
+ * index", and one overflow constraint per index whose tile does not divide
+ * its range).  The result is semantically the input block.  It is HOST
+ * memory owned by the caller: release it with stripe_desc_free().
+ */
+stripe_status_t stripe_block_tile(const stripe_block_desc_t* root, const int64_t* tile, stripe_block_desc_t** out);
+void stripe_desc_free(stripe_block_desc_t* desc);
 
 #ifdef __cplusplus
 }

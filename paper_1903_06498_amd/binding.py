@@ -29,7 +29,8 @@ _AGG = {"assign": 0, "add": 1, "max": 2, "min": 3}
 _INTR = {"mul": 0, "copy": 1, "add": 2}
 
 EXPORTS = ("stripe_block_create", "stripe_block_create_for_path", "stripe_block_run", "stripe_block_query",
-           "stripe_block_destroy", "stripe_status_string", "stripe_last_error", "stripe_device_copy")
+           "stripe_block_destroy", "stripe_status_string", "stripe_last_error", "stripe_device_copy",
+           "stripe_tile_cost", "stripe_tile_search", "stripe_block_tile", "stripe_desc_free")
 
 
 class stripe_refinement_t(C.Structure):
@@ -60,6 +61,16 @@ class stripe_block_info_t(C.Structure):
                 ("kernel", C.c_char * 64)]
 
 
+class stripe_tile_model_t(C.Structure):
+    _fields_ = [("line_elems", C.c_int64), ("mem_cap_elems", C.c_int64), ("counted_refs", C.c_uint32),
+                ("tiled_idx", C.c_uint32), ("power_of_two", C.c_int32), ("multiple_of", C.POINTER(C.c_int64))]
+
+
+class stripe_tile_cost_t(C.Structure):
+    _fields_ = [("tiles", C.c_int64), ("lines_per_tile", C.c_int64), ("footprint_elems", C.c_int64),
+                ("work", C.c_int64), ("cost", C.c_double), ("admissible", C.c_int32)]
+
+
 class StripeError(RuntimeError):
     def __init__(self, status: int, detail: str):
         super().__init__(f"stripe: {STATUS_NAMES.get(status, status)}: {detail}")
@@ -71,6 +82,13 @@ def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1903_06498_amd.build` "
                           "(there is no CPU fallback)")
+    # PyTorch wheels bundle their own copy of the HIP runtime.  If this library pulled in the system's copy
+    # first, a later `import torch` would bring a second runtime into the process and every GPU call would
+    # fail ("no ROCm-capable device").  Loading torch first makes its runtime the one both sides share.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     handle = C.c_void_p
     lib.stripe_block_create.restype = C.c_int
@@ -89,6 +107,17 @@ def _load():
     lib.stripe_last_error.argtypes = []
     lib.stripe_device_copy.restype = C.c_int
     lib.stripe_device_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.stripe_tile_cost.restype = C.c_int
+    lib.stripe_tile_cost.argtypes = [C.POINTER(stripe_block_desc_t), C.POINTER(C.c_int64), C.POINTER(stripe_tile_model_t),
+                                     C.POINTER(stripe_tile_cost_t)]
+    lib.stripe_tile_search.restype = C.c_int
+    lib.stripe_tile_search.argtypes = [C.POINTER(stripe_block_desc_t), C.POINTER(stripe_tile_model_t), C.POINTER(C.c_int64),
+                                       C.POINTER(stripe_tile_cost_t)]
+    lib.stripe_block_tile.restype = C.c_int
+    lib.stripe_block_tile.argtypes = [C.POINTER(stripe_block_desc_t), C.POINTER(C.c_int64),
+                                      C.POINTER(C.POINTER(stripe_block_desc_t))]
+    lib.stripe_desc_free.restype = None
+    lib.stripe_desc_free.argtypes = [C.POINTER(stripe_block_desc_t)]
     return lib
 
 
@@ -179,6 +208,91 @@ def stripe_block_destroy(handle) -> None:
 def stripe_device_copy(src_ptr: int, dst_ptr: int, n_bytes: int, stream: int = 0) -> None:
     _check(lib.stripe_device_copy(C.c_void_p(int(src_ptr)), C.c_void_p(int(dst_ptr)), C.c_size_t(int(n_bytes)),
                                   C.c_void_p(int(stream))))
+
+
+# ---- autotiling (host only) ------------------------------------------------
+_DIR_NAMES = {v: k for k, v in _DIR.items()}
+_DTYPE_NAMES = {v: k for k, v in _DTYPE.items()}
+_AGG_NAMES = {v: k for k, v in _AGG.items()}
+_INTR_NAMES = {v: k for k, v in _INTR.items()}
+
+
+def _model(model: dict, n_idx: int, keep: list) -> stripe_tile_model_t:
+    """model: dict(line_elems, mem_cap_elems=0, counted_refs=[ref numbers], tiled_idx=[index numbers],
+    power_of_two=False, multiple_of=None or a list per index)."""
+    m = stripe_tile_model_t()
+    m.line_elems = int(model["line_elems"])
+    m.mem_cap_elems = int(model.get("mem_cap_elems", 0))
+    m.counted_refs = sum(1 << int(r) for r in model["counted_refs"])
+    m.tiled_idx = sum(1 << int(j) for j in model["tiled_idx"])
+    m.power_of_two = 1 if model.get("power_of_two") else 0
+    mult = model.get("multiple_of")
+    m.multiple_of = _i64(mult, keep) if mult is not None else None
+    if mult is not None and len(mult) != n_idx:
+        raise ValueError("multiple_of needs one entry per index")
+    return m
+
+
+def _cost_dict(c: stripe_tile_cost_t) -> dict:
+    return {name: getattr(c, name) for name, _ in stripe_tile_cost_t._fields_}
+
+
+def stripe_tile_cost(block, tile: Sequence[int], model: dict) -> dict:
+    keep: list = []
+    desc = marshal(block, keep)
+    out = stripe_tile_cost_t()
+    _check(lib.stripe_tile_cost(C.byref(desc), _i64(tile, keep), C.byref(_model(model, len(tile), keep)), C.byref(out)))
+    return _cost_dict(out)
+
+
+def stripe_tile_search(block, model: dict):
+    keep: list = []
+    desc = marshal(block, keep)
+    n = len(block.child.ranges)
+    best_tile = (C.c_int64 * n)()
+    out = stripe_tile_cost_t()
+    _check(lib.stripe_tile_search(C.byref(desc), C.byref(_model(model, n, keep)), best_tile, C.byref(out)))
+    return list(best_tile), _cost_dict(out)
+
+
+def unmarshal(desc: stripe_block_desc_t, parent_vars: int = 0, names=None):
+    """C descriptor -> workloads.Block (index and buffer names are not part of the C form: generic ones)."""
+    from .workloads import Block, Refinement
+    n_vars = desc.n_idx + desc.n_passed
+
+    def mat(ptr, n_rows, n_cols):
+        return [[int(ptr[r * n_cols + c]) for c in range(n_cols)] for r in range(n_rows)]
+
+    refs = []
+    for i in range(desc.n_refs):
+        r = desc.refs[i]
+        refs.append(Refinement(name=(names[i] if names else f"T{i}"), dir=_DIR_NAMES[r.dir], dtype=_DTYPE_NAMES[r.dtype],
+                               agg=_AGG_NAMES[r.agg], access_coeff=mat(r.access_coeff, r.ndim, n_vars),
+                               access_const=[int(r.access_const[d]) for d in range(r.ndim)],
+                               sizes=[int(r.sizes[d]) for d in range(r.ndim)], strides=[int(r.strides[d]) for d in range(r.ndim)]))
+    child = unmarshal(desc.child.contents, n_vars, names) if desc.child else None
+    return Block(idx_names=[f"i{j}" for j in range(desc.n_idx)], ranges=[int(desc.ranges[j]) for j in range(desc.n_idx)],
+                 passed_names=[f"p{j}" for j in range(desc.n_passed)], passed_coeff=mat(desc.passed_coeff, desc.n_passed, parent_vars),
+                 passed_const=[int(desc.passed_const[j]) for j in range(desc.n_passed)],
+                 cons_coeff=mat(desc.cons_coeff, desc.n_constraints, n_vars),
+                 cons_const=[int(desc.cons_const[j]) for j in range(desc.n_constraints)], refs=refs,
+                 intrinsic=_INTR_NAMES[desc.intrinsic] if child is None else None, child=child)
+
+
+def stripe_block_tile(block, tile: Sequence[int]):
+    """The tiling rewrite; returns the nest as a workloads.Block (the C result is freed before returning)."""
+    keep: list = []
+    desc = marshal(block, keep)
+    out = C.POINTER(stripe_block_desc_t)()
+    _check(lib.stripe_block_tile(C.byref(desc), _i64(tile, keep), C.byref(out)))
+    try:
+        return unmarshal(out.contents, 0, [r.name for r in block.refs])
+    finally:
+        lib.stripe_desc_free(out)
+
+
+def stripe_desc_free(desc_ptr) -> None:
+    lib.stripe_desc_free(desc_ptr)
 
 
 class StripeBlock:

@@ -30,6 +30,10 @@ stripe_status_t fail(stripe_status_t st, const std::string& msg) {
 
 }  // namespace
 
+namespace stripe {
+stripe_status_t api_fail(stripe_status_t st, const std::string& msg) { return fail(st, msg); }
+}  // namespace stripe
+
 extern "C" {
 
 stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, stripe_path_t path, stripe_block_t** out) {

@@ -117,4 +117,7 @@ bool match_pool2d(const FlatBlock& fb, Pool2dShape* p);
 
 int64_t count_points(const FlatBlock& fb, int64_t enumeration_cap);
 
+// Records the calling thread's error detail (what stripe_last_error() returns) and passes the status through.
+stripe_status_t api_fail(stripe_status_t st, const std::string& msg);
+
 }  // namespace stripe

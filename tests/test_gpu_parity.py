@@ -158,6 +158,30 @@ def test_empty_block_launches_nothing():
     assert np.all(gpu == np.float32(SENTINEL_F))
 
 
+# ------------------------------------------------------------------ blocks produced by the tiling rewrite
+@pytest.mark.parametrize("case", ["pool_ragged", "conv_bf16", "matmul_f32", "fig5_ragged"])
+def test_rewritten_nests_run_like_their_flat_forms(case):
+    """A nest made by stripe_block_tile (Section 3.3's rewrite; ragged tiles add overflow constraints) goes through
+    the same planner: it must land on the same kernel family as its flat form and match the oracle run on the NEST."""
+    if case == "pool_ragged":
+        flat, tile = W.maxpool_block(2, 45, 27, 12, 3, 2, 1), [1, 5, 4, 12, 3, 3]
+        ins = [W.seeded_tensor((2, 45, 27, 12), "f32", 3)]
+    elif case == "conv_bf16":
+        flat, tile = W.conv2d_block(2, 10, 13, 64, 64, 3, 3, 1, 1, "bf16", "f32"), [1, 4, 5, 3, 3, 64, 32]
+        ins = [W.seeded_tensor((2, 10, 13, 64), "bf16", 0), W.seeded_tensor((3, 3, 64, 64), "bf16", 1)]
+    elif case == "matmul_f32":
+        flat, tile = W.matmul_block(70, 90, 130, "f32", "f32"), [32, 16, 50]
+        ins = [W.seeded_tensor((70, 130), "f32", 0), W.seeded_tensor((130, 90), "f32", 1)]
+    else:
+        flat, tile = W.fig5_flat(), [5, 3, 3, 3, 8, 16]
+        ins = [W.seeded_tensor((12, 16, 8), "i8", 0), W.seeded_tensor((3, 3, 16, 8), "i8", 1)]
+    assert len(tile) == len(flat.child.ranges)
+    nest = B.stripe_block_tile(flat, tile)
+    info, _ = parity(nest, ins, what=f"tiled {case}")
+    flat_info = B.StripeBlock(flat).info
+    assert info["path_name"] == flat_info["path_name"] and info["work_points"] == flat_info["work_points"], (info, flat_info)
+
+
 # ------------------------------------------------------------------ pooling path
 @pytest.mark.parametrize("N,H,Wd,C", [(2, 30, 26, 8), (1, 7, 9, 4), (3, 33, 35, 64), (1, 112, 112, 64)])
 def test_pool_path_small(N, H, Wd, C):
