@@ -25,7 +25,8 @@ typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
 
 struct GemmParams {
   int32_t tiles_m, tiles_n, k_tiles, pad_;
-  int64_t a_m, b_k, c_m;      // row strides in elements (a_k = b_n = c_n = 1)
+  int32_t M, N;               // used by the variants that accept M, N that are not multiples of the tile
+  int64_t a_m, b_k, c_m;      // row strides in elements (a_k = b_n = c_n = 1); for a transposed B ([n][k], k contiguous) b_k holds its row stride
   int64_t a_base, b_base, c_base;
 };
 
@@ -407,7 +408,15 @@ struct DCtx {
   unsigned a_fr;           // LDS byte address of the lane's A fragment chunk (stage 0, K step 0, fragment 0)
   unsigned b_fr[4];        // LDS byte address of the lane's B fragment j (stage 0, K step 0, first read)
   unsigned wave_lds;       // LDS byte offset of this wavefront's 1 KB load slot within a stage
+  const uint16_t* a_ptr[4];  // ragged variants: the lane's load addresses one by one (rows clamped into the matrix)
+  const uint16_t* b_ptr[4];
 };
+
+// MODE bit 0: B is stored transposed, [n][k] with k contiguous (C = A * B^T as Linear layers and 1x1 convolutions
+// have it); its tile then lies in LDS exactly like A's and a fragment is one 16-byte read.
+// MODE bit 1: M and N need not be multiples of 256: loads of rows (or column chunks) past the edge are redirected
+// to the last valid one -- they only feed accumulators that are never stored -- and the stores are predicated.
+constexpr int D_BT = 1, D_RAGGED = 2;
 
 // The LDS-direct loads are written as assembly on purpose: the compiler cannot
 // tell that a load into one ring stage does not alias the fragment reads of
@@ -425,8 +434,12 @@ __device__ __forceinline__ void d_read_a(const DCtx& c, const unsigned char* lds
   af[Q] = *(const bf16x8*)(lds + (c.a_fr ^ (S << 5)) + (STAGE_N * D_A_STAGE + Q * 32 * 64));
 }
 // B fragment q of K step S of a stage: columns 32q.. of the wavefront's columns, two transposing 8-byte reads.
-template <int STAGE_N, int S, int Q, int FN>
+template <int STAGE_N, int S, int Q, int FN, int MODE = 0>
 __device__ __forceinline__ void d_read_b(const DCtx& c, const unsigned char* lds, bf16x8 (&bf)[FN]) {
+  if constexpr (MODE & D_BT) {
+    bf[Q] = *(const bf16x8*)(lds + (c.b_fr[Q] ^ (S << 5)) + STAGE_N * D_B_STAGE);
+    return;
+  }
   typedef __attribute__((address_space(3))) s16x4* lptr;
   const unsigned char* p = lds + c.b_fr[Q] + (STAGE_N * D_B_STAGE + S * 16 * 512);
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)p);
@@ -438,27 +451,27 @@ __device__ __forceinline__ void d_read_b(const DCtx& c, const unsigned char* lds
 // read first; the last group reads nothing, so that neither the barrier that follows group 3 (it waits
 // for the wavefront's outstanding LDS reads) nor the first group of the next step meets a read that has
 // only just been issued.
-template <int SCHED, int STAGE_N, int S, int Q, int FN>
+template <int SCHED, int STAGE_N, int S, int Q, int FN, int MODE = 0>
 __device__ __forceinline__ void d_read_group(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[FN]) {
   if constexpr (SCHED == 0) {   // plain order: group Q reads A fragment Q and B fragment Q
     d_read_a<STAGE_N, S, Q>(c, lds, af);
-    if constexpr (Q < FN) d_read_b<STAGE_N, S, Q, FN>(c, lds, bf);
+    if constexpr (Q < FN) d_read_b<STAGE_N, S, Q, FN, MODE>(c, lds, bf);
   } else if constexpr (FN == 4) {
-    if constexpr (Q == 0) { d_read_b<STAGE_N, S, 0, FN>(c, lds, bf); d_read_b<STAGE_N, S, 1, FN>(c, lds, bf); }
-    if constexpr (Q == 1) { d_read_b<STAGE_N, S, 2, FN>(c, lds, bf); d_read_b<STAGE_N, S, 3, FN>(c, lds, bf); d_read_a<STAGE_N, S, 0>(c, lds, af); }
+    if constexpr (Q == 0) { d_read_b<STAGE_N, S, 0, FN, MODE>(c, lds, bf); d_read_b<STAGE_N, S, 1, FN, MODE>(c, lds, bf); }
+    if constexpr (Q == 1) { d_read_b<STAGE_N, S, 2, FN, MODE>(c, lds, bf); d_read_b<STAGE_N, S, 3, FN, MODE>(c, lds, bf); d_read_a<STAGE_N, S, 0>(c, lds, af); }
     if constexpr (Q == 2) { d_read_a<STAGE_N, S, 1>(c, lds, af); d_read_a<STAGE_N, S, 2>(c, lds, af); d_read_a<STAGE_N, S, 3>(c, lds, af); }
   } else {
-    if constexpr (Q == 0) { d_read_b<STAGE_N, S, 0, FN>(c, lds, bf); d_read_b<STAGE_N, S, 1, FN>(c, lds, bf); d_read_a<STAGE_N, S, 0>(c, lds, af); }
+    if constexpr (Q == 0) { d_read_b<STAGE_N, S, 0, FN, MODE>(c, lds, bf); d_read_b<STAGE_N, S, 1, FN, MODE>(c, lds, bf); d_read_a<STAGE_N, S, 0>(c, lds, af); }
     if constexpr (Q == 1) { d_read_a<STAGE_N, S, 1>(c, lds, af); d_read_a<STAGE_N, S, 2>(c, lds, af); }
     if constexpr (Q == 2) { d_read_a<STAGE_N, S, 3>(c, lds, af); }
   }
 }
-template <int STAGE_N, int S, int FN>
+template <int STAGE_N, int S, int FN, int MODE = 0>
 __device__ __forceinline__ void d_read_frags(const DCtx& c, const unsigned char* lds, bf16x8 (&af)[4], bf16x8 (&bf)[FN]) {
-  d_read_group<0, STAGE_N, S, 0, FN>(c, lds, af, bf);
-  d_read_group<0, STAGE_N, S, 1, FN>(c, lds, af, bf);
-  d_read_group<0, STAGE_N, S, 2, FN>(c, lds, af, bf);
-  d_read_group<0, STAGE_N, S, 3, FN>(c, lds, af, bf);
+  d_read_group<0, STAGE_N, S, 0, FN, MODE>(c, lds, af, bf);
+  d_read_group<0, STAGE_N, S, 1, FN, MODE>(c, lds, af, bf);
+  d_read_group<0, STAGE_N, S, 2, FN, MODE>(c, lds, af, bf);
+  d_read_group<0, STAGE_N, S, 3, FN, MODE>(c, lds, af, bf);
 }
 
 template <int Q, int FN>
@@ -477,14 +490,21 @@ __device__ __forceinline__ void d_mfma_part(const bf16x8 (&af)[4], const bf16x8 
 #define D_FENCE() __builtin_amdgcn_sched_barrier(0)
 
 // LDS-direct loads number G*PER .. G*PER+PER-1 of a tile (PER per group); loads 0..LPT/2-1 are A, the rest B
-template <int LD, int WAVES, int G>
-__device__ __forceinline__ void d_issue_group(const DCtx& c, const uint16_t* a, const uint16_t* b) {
+// a, b: the lane's first A and B address of the tile (plain variants) or the tile's K offset in elements cast into
+// a pointer-sized integer (ragged variants, which add it to the per-load addresses).
+template <int LD, int WAVES, int G, int MODE = 0>
+__device__ __forceinline__ void d_issue_group(const DCtx& c, const uint16_t* a, const uint16_t* b, size_t a_koff = 0, size_t b_koff = 0) {
   constexpr int LPT = 32 / WAVES, HALF = LPT / 2, PER = LPT / 4 > 0 ? LPT / 4 : 1;
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int u = G * PER + e;
-    if (u < HALF) d_load_lds16(a + u * c.a_step, LD * D_A_STAGE + u * (1024 * WAVES) + c.wave_lds);
-    else if (u < LPT) d_load_lds16(b + (u - HALF) * c.b_step, D_B0 + LD * D_B_STAGE + (u - HALF) * (1024 * WAVES) + c.wave_lds);
+    if constexpr (MODE & D_RAGGED) {
+      if (u < HALF) d_load_lds16(c.a_ptr[u] + a_koff, LD * D_A_STAGE + u * (1024 * WAVES) + c.wave_lds);
+      else if (u < LPT) d_load_lds16(c.b_ptr[u - HALF] + b_koff, D_B0 + LD * D_B_STAGE + (u - HALF) * (1024 * WAVES) + c.wave_lds);
+    } else {
+      if (u < HALF) d_load_lds16(a + u * c.a_step, LD * D_A_STAGE + u * (1024 * WAVES) + c.wave_lds);
+      else if (u < LPT) d_load_lds16(b + (u - HALF) * c.b_step, D_B0 + LD * D_B_STAGE + (u - HALF) * (1024 * WAVES) + c.wave_lds);
+    }
   }
 }
 
@@ -505,7 +525,7 @@ __device__ __forceinline__ void d_wait_loads() {
 // ISSUE: start the loads of tile kt+3 (after the barrier).  PENDING: how many
 // younger loads (those of tile kt+2) may still be in flight when tile kt+1 must
 // have landed.
-template <int WAVES, int SCHED, int STAGE_N, bool ISSUE, int PENDING, bool NEXT_FRAGS>
+template <int WAVES, int SCHED, int STAGE_N, bool ISSUE, int PENDING, bool NEXT_FRAGS, int MODE = 0>
 __device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt, bf16x8 (&af)[2][4],
                                        bf16x8 (&bf)[2][WAVES == 4 ? 4 : 2], f32x16 (&acc)[4][WAVES == 4 ? 4 : 2]) {
   constexpr int FN = WAVES == 4 ? 4 : 2;
@@ -513,38 +533,39 @@ __device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt
   constexpr int LD = (STAGE_N + 3) % D_STAGES;
   const uint16_t* a = c.a_src + (size_t)(kt + 3) * D_BK;
   const uint16_t* b = c.b_src + (size_t)(kt + 3) * c.b_kstep;
+  const size_t a_koff = (size_t)(kt + 3) * D_BK, b_koff = (size_t)(kt + 3) * c.b_kstep;
   D_FENCE();
-  d_mfma_row<0, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 0, FN>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<1, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 1, FN>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<2, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 2, FN>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<0, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 0, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<1, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 1, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<2, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 2, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
   // the barrier sits before the group's last matrix instruction, which then covers the barrier's latency
   constexpr int EARLY = SCHED == 2 ? FN - 1 : FN;   // matrix instructions of group 3 issued before the barrier
   d_mfma_part<3, 0, EARLY, FN>(af[0], bf[0], acc);
-  if constexpr (SCHED == 0) d_read_group<SCHED, STAGE_N, 1, 3, FN>(c, lds, af[1], bf[1]);
+  if constexpr (SCHED == 0) d_read_group<SCHED, STAGE_N, 1, 3, FN, MODE>(c, lds, af[1], bf[1]);
   D_FENCE();
   d_wait_loads<PENDING>();
   __syncthreads();
   D_FENCE();
   d_mfma_part<3, EARLY, FN, FN>(af[0], bf[0], acc);
   d_mfma_row<0, FN>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 0, FN>(c, lds, af[0], bf[0]);
-  if (ISSUE) d_issue_group<LD, WAVES, 0>(c, a, b);
+  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 0, FN, MODE>(c, lds, af[0], bf[0]);
+  if (ISSUE) d_issue_group<LD, WAVES, 0, MODE>(c, a, b, a_koff, b_koff);
   D_FENCE();
   d_mfma_row<1, FN>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 1, FN>(c, lds, af[0], bf[0]);
-  if (ISSUE) d_issue_group<LD, WAVES, 1>(c, a, b);
+  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 1, FN, MODE>(c, lds, af[0], bf[0]);
+  if (ISSUE) d_issue_group<LD, WAVES, 1, MODE>(c, a, b, a_koff, b_koff);
   D_FENCE();
   d_mfma_row<2, FN>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 2, FN>(c, lds, af[0], bf[0]);
-  if (ISSUE) d_issue_group<LD, WAVES, 2>(c, a, b);
+  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 2, FN, MODE>(c, lds, af[0], bf[0]);
+  if (ISSUE) d_issue_group<LD, WAVES, 2, MODE>(c, a, b, a_koff, b_koff);
   D_FENCE();
   d_mfma_row<3, FN>(af[1], bf[1], acc);
-  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 3, FN>(c, lds, af[0], bf[0]);
-  if (ISSUE) d_issue_group<LD, WAVES, 3>(c, a, b);
+  if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 3, FN, MODE>(c, lds, af[0], bf[0]);
+  if (ISSUE) d_issue_group<LD, WAVES, 3, MODE>(c, a, b, a_koff, b_koff);
   D_FENCE();
 }
 
-template <int WAVES, int SCHED>
+template <int WAVES, int SCHED, int MODE = 0>
 __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const GemmParams p, const uint16_t* __restrict__ A,
                                                                       const uint16_t* __restrict__ B, float* __restrict__ C) {
   constexpr int FN = WAVES == 4 ? 4 : 2;        // 32-column fragments per wavefront
@@ -564,13 +585,40 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
     c.a_src = A + p.a_base + ((int64_t)tm * BM + row) * p.a_m + chunk * 8;
     c.a_step = (size_t)(16 * WAVES) * p.a_m;
   }
-  // B loads: load u of wavefront w fills k rows 2*(WAVES*u+w), +1: lane -> k = 2*(WAVES*u+w) + lane/32, slot lane&31
-  {
+  if constexpr (MODE & D_BT) {
+    // transposed B: rows are n, loaded and laid out like A's rows
+    const int row = 16 * wave + (lane >> 2);
+    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    c.b_src = B + p.b_base + ((int64_t)tn * BN + row) * p.b_k + chunk * 8;
+    c.b_step = (size_t)(16 * WAVES) * p.b_k;
+    c.b_kstep = (size_t)D_BK;
+  } else {
+    // B loads: load u of wavefront w fills k rows 2*(WAVES*u+w), +1: lane -> k = 2*(WAVES*u+w) + lane/32, slot lane&31
     const int k = 2 * wave + (lane >> 5);               // + 2*WAVES*u ; k&3 does not change with u
     const int chunk = (lane & 31) ^ (4 * (k & 3));
     c.b_src = B + p.b_base + (int64_t)k * p.b_k + (int64_t)tn * BN + chunk * 8;
     c.b_step = (size_t)(2 * WAVES) * p.b_k;
     c.b_kstep = (size_t)D_BK * p.b_k;
+  }
+  if constexpr (MODE & D_RAGGED) {
+    // one address per load, with the row (or, for a row-major B, the 8-column chunk) clamped into the matrix
+    constexpr int HALF_LOADS = 16 / WAVES;
+#pragma unroll
+    for (int u = 0; u < HALF_LOADS; ++u) {
+      const int row = 16 * wave + (lane >> 2) + 16 * WAVES * u;
+      const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+      const int64_t gm = (int64_t)tm * BM + row;
+      c.a_ptr[u] = A + p.a_base + (gm < p.M ? gm : p.M - 1) * p.a_m + chunk * 8;
+      if constexpr (MODE & D_BT) {
+        const int64_t gn = (int64_t)tn * BN + row;
+        c.b_ptr[u] = B + p.b_base + (gn < p.N ? gn : p.N - 1) * p.b_k + chunk * 8;
+      } else {
+        const int k = 2 * wave + (lane >> 5) + 2 * WAVES * u;
+        const int bchunk = (lane & 31) ^ (4 * (k & 3));
+        const int64_t gn = (int64_t)tn * BN + bchunk * 8;
+        c.b_ptr[u] = B + p.b_base + (int64_t)k * p.b_k + (gn + 8 <= p.N ? gn : p.N - 8);
+      }
+    }
   }
   c.wave_lds = wave * 1024;
   // A fragments: lane supplies row (lane&31) (+32*i) and chunk 2*s + (lane>>5)
@@ -578,6 +626,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
     const int fr = lane & 31, fh = lane >> 5;
     c.a_fr = (wm * 128 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4);
   }
+  if constexpr (MODE & D_BT) {
+    const int fr = lane & 31, fh = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      c.b_fr[j] = D_B0 + (wn * 32 * FN + 32 * (j < FN ? j : 0) + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4);
+  } else
   // B fragments: 16-lane group g, lane p in it: k = 8*(g>>1) + (p>>2) (+16*s, +4 second read),
   // columns wn*32*FN + 32*j + 16*(g&1) + 4*(p&3) .. +3
   {
@@ -604,27 +658,28 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
   {
     const uint16_t* a = c.a_src;
     const uint16_t* b = c.b_src;
-    d_issue_group<0, WAVES, 0>(c, a, b); d_issue_group<0, WAVES, 1>(c, a, b); d_issue_group<0, WAVES, 2>(c, a, b); d_issue_group<0, WAVES, 3>(c, a, b);
-    a += D_BK; b += c.b_kstep;
-    d_issue_group<1, WAVES, 0>(c, a, b); d_issue_group<1, WAVES, 1>(c, a, b); d_issue_group<1, WAVES, 2>(c, a, b); d_issue_group<1, WAVES, 3>(c, a, b);
-    a += D_BK; b += c.b_kstep;
-    d_issue_group<2, WAVES, 0>(c, a, b); d_issue_group<2, WAVES, 1>(c, a, b); d_issue_group<2, WAVES, 2>(c, a, b); d_issue_group<2, WAVES, 3>(c, a, b);
+    size_t ak = 0, bk = 0;
+    d_issue_group<0, WAVES, 0, MODE>(c, a, b, ak, bk); d_issue_group<0, WAVES, 1, MODE>(c, a, b, ak, bk); d_issue_group<0, WAVES, 2, MODE>(c, a, b, ak, bk); d_issue_group<0, WAVES, 3, MODE>(c, a, b, ak, bk);
+    a += D_BK; b += c.b_kstep; ak += D_BK; bk += c.b_kstep;
+    d_issue_group<1, WAVES, 0, MODE>(c, a, b, ak, bk); d_issue_group<1, WAVES, 1, MODE>(c, a, b, ak, bk); d_issue_group<1, WAVES, 2, MODE>(c, a, b, ak, bk); d_issue_group<1, WAVES, 3, MODE>(c, a, b, ak, bk);
+    a += D_BK; b += c.b_kstep; ak += D_BK; bk += c.b_kstep;
+    d_issue_group<2, WAVES, 0, MODE>(c, a, b, ak, bk); d_issue_group<2, WAVES, 1, MODE>(c, a, b, ak, bk); d_issue_group<2, WAVES, 2, MODE>(c, a, b, ak, bk); d_issue_group<2, WAVES, 3, MODE>(c, a, b, ak, bk);
   }
   d_wait_loads<2 * LPT>();
   __syncthreads();
-  d_read_frags<0, 0, FN>(c, lds, af[0], bf[0]);
+  d_read_frags<0, 0, FN, MODE>(c, lds, af[0], bf[0]);
 
   const int last4 = p.k_tiles - 4;
   for (int kt = 0; kt < last4; kt += 4) {
-    d_tile<WAVES, SCHED, 0, true, LPT, true>(c, lds, kt, af, bf, acc);
-    d_tile<WAVES, SCHED, 1, true, LPT, true>(c, lds, kt + 1, af, bf, acc);
-    d_tile<WAVES, SCHED, 2, true, LPT, true>(c, lds, kt + 2, af, bf, acc);
-    d_tile<WAVES, SCHED, 3, true, LPT, true>(c, lds, kt + 3, af, bf, acc);
+    d_tile<WAVES, SCHED, 0, true, LPT, true, MODE>(c, lds, kt, af, bf, acc);
+    d_tile<WAVES, SCHED, 1, true, LPT, true, MODE>(c, lds, kt + 1, af, bf, acc);
+    d_tile<WAVES, SCHED, 2, true, LPT, true, MODE>(c, lds, kt + 2, af, bf, acc);
+    d_tile<WAVES, SCHED, 3, true, LPT, true, MODE>(c, lds, kt + 3, af, bf, acc);
   }
-  d_tile<WAVES, SCHED, 0, true, LPT, true>(c, lds, last4, af, bf, acc);        // issues the last tile's loads
-  d_tile<WAVES, SCHED, 1, false, LPT, true>(c, lds, last4 + 1, af, bf, acc);
-  d_tile<WAVES, SCHED, 2, false, 0, true>(c, lds, last4 + 2, af, bf, acc);
-  d_tile<WAVES, SCHED, 3, false, 0, false>(c, lds, last4 + 3, af, bf, acc);
+  d_tile<WAVES, SCHED, 0, true, LPT, true, MODE>(c, lds, last4, af, bf, acc);        // issues the last tile's loads
+  d_tile<WAVES, SCHED, 1, false, LPT, true, MODE>(c, lds, last4 + 1, af, bf, acc);
+  d_tile<WAVES, SCHED, 2, false, 0, true, MODE>(c, lds, last4 + 2, af, bf, acc);
+  d_tile<WAVES, SCHED, 3, false, 0, false, MODE>(c, lds, last4 + 3, af, bf, acc);
 
   const int fr = lane & 31, fh = lane >> 5;
   float* c_g = C + p.c_base + ((int64_t)tm * BM + wm * 128 + 4 * fh) * p.c_m + (int64_t)tn * BN + wn * 32 * FN + fr;
@@ -635,17 +690,25 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int r = 32 * i + 8 * (v / 4) + (v % 4);
-        __builtin_nontemporal_store(acc[i][j][v], c_g + (int64_t)r * p.c_m + 32 * j);
+        if constexpr (MODE & D_RAGGED) {
+          const int64_t gm = (int64_t)tm * BM + wm * 128 + 4 * fh + r, gn = (int64_t)tn * BN + wn * 32 * FN + fr + 32 * j;
+          if (gm < p.M && gn < p.N) __builtin_nontemporal_store(acc[i][j][v], c_g + (int64_t)r * p.c_m + 32 * j);
+        } else {
+          __builtin_nontemporal_store(acc[i][j][v], c_g + (int64_t)r * p.c_m + 32 * j);
+        }
       }
 }
 
 GemmParams make_params(const GemmShape& g) {
   GemmParams p;
-  p.tiles_m = (int)(g.M / BM);
-  p.tiles_n = (int)(g.N / BN);
+  p.tiles_m = (int)((g.M + BM - 1) / BM);
+  p.tiles_n = (int)((g.N + BN - 1) / BN);
+  p.M = (int)g.M;
+  p.N = (int)g.N;
   p.k_tiles = (int)(g.K / BK);
   p.pad_ = 0;
-  p.a_m = g.a_m; p.b_k = g.b_k; p.c_m = g.c_m;
+  p.a_m = g.a_m; p.c_m = g.c_m;
+  p.b_k = (g.b_k == 1 && g.b_n != 1) ? g.b_n : g.b_k;   // row stride of B as stored: [n][k] (transposed) or [k][n]
   p.a_base = g.a_base; p.b_base = g.b_base; p.c_base = g.c_base;
   return p;
 }
@@ -654,7 +717,30 @@ GemmParams make_params(const GemmShape& g) {
 
 bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info) {
   if (in_dtype != STRIPE_BF16) return false;
-  if (g.a_k != 1 || g.b_n != 1 || g.c_n != 1) return false;
+  if (g.a_k != 1 || g.c_n != 1) return false;
+  // B row-major ([k][n], n contiguous) or transposed ([n][k], k contiguous); the LDS-direct kernel also takes
+  // M and N that are not multiples of the tile (row-major B then needs whole 8-column chunks)
+  const bool bt = g.b_k == 1 && g.b_n != 1;
+  if (!bt && g.b_n != 1) return false;
+  const int64_t b_row = bt ? g.b_n : g.b_k;
+  const bool dma_shape = g.K % (D_BK * D_STAGES) == 0 && g.K >= D_BK * D_STAGES && tune_int("gemm_dma", 1) != 0;
+  const bool ragged = (g.M % BM || g.N % BN);
+  if (bt || ragged) {
+    if (!dma_shape || g.M < 1 || g.N < 8 || (!bt && g.N % 8) || g.M > 0x7fffffff || g.N > 0x7fffffff) return false;
+    if (g.a_m % 8 || b_row % 8 || g.a_base % 8 || g.b_base % 8) return false;
+    const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    if (tiles_m > 32767 || tiles_n > 32767) return false;
+    l->variant = 30 + (bt ? D_BT : 0) + (ragged ? D_RAGGED : 0);
+    l->grid = tiles_m * tiles_n;
+    info->path = STRIPE_PATH_MFMA_GEMM;
+    info->tile_m = BM; info->tile_n = BN; info->tile_k = D_BK;
+    info->frag_m = 32; info->frag_n = 32; info->frag_k = 16;
+    info->lds_bytes = D_LDS;
+    info->workgroup_size = 256;
+    info->grid = l->grid;
+    snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_256x256x32_mfma32x32x16_w4_lds_direct%s%s", bt ? "_bt" : "", ragged ? "_ragged" : "");
+    return true;
+  }
   if (g.M % BM || g.N % BN || g.K % BK || g.K < BK) return false;
   if (g.a_m % 8 || g.b_k % 8 || g.a_base % 8 || g.b_base % 8) return false;  // 16-byte global loads
   if (g.M / BM > 32767 || g.N / BN > 32767 || g.K / BK > 0x7fffffff / BK) return false;
@@ -690,6 +776,9 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
     case 21: kernel = gemm_bf16_dma_kernel<8, 1>; break;
     case 22: kernel = gemm_bf16_dma_kernel<4, 0>; break;
     case 23: kernel = gemm_bf16_dma_kernel<4, 2>; break;
+    case 30 + D_BT: kernel = gemm_bf16_dma_kernel<4, 1, D_BT>; break;
+    case 30 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_RAGGED>; break;
+    case 30 + D_BT + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED>; break;
     case 10: kernel = gemm_bf16_w8_kernel<0>; break;
     case 11: kernel = gemm_bf16_w8_kernel<1>; break;
     default: kernel = gemm_bf16_w8_kernel<2>; break;

@@ -569,27 +569,46 @@ bool distinct(std::initializer_list<int> ids) {
 
 bool match_gemm(const FlatBlock& fb, GemmShape* g) {
   if (fb.empty || fb.n_refs != 3 || fb.intrinsic != STRIPE_INTR_MUL || fb.agg != STRIPE_AGG_ADD) return false;
-  if (fb.n_idx != 3 || !fb.cons.empty()) return false;
-  const Affine &A = fb.ref[0].addr, &B = fb.ref[1].addr, &C = fb.ref[2].addr;
+  if (fb.n_idx < 3 || !fb.cons.empty()) return false;
+  // Only the three address maps matter here.  Indexes that all of them use as outer*range + inner are one
+  // index as far as addresses go, even when they are separate buffer dimensions (the pixels n, y, x of a
+  // 1x1 convolution over dense tensors): merge such pairs until none is left.
+  std::vector<int64_t> rng(fb.range, fb.range + fb.n_idx);
+  std::vector<int64_t> ca(fb.ref[0].addr.c, fb.ref[0].addr.c + fb.n_idx), cb(fb.ref[1].addr.c, fb.ref[1].addr.c + fb.n_idx),
+      cc(fb.ref[2].addr.c, fb.ref[2].addr.c + fb.n_idx);
+  for (bool merged = true; merged && rng.size() > 3;) {
+    merged = false;
+    for (size_t o = 0; o < rng.size() && !merged; ++o)
+      for (size_t i = 0; i < rng.size() && !merged; ++i) {
+        if (o == i) continue;
+        auto nests = [&](const std::vector<int64_t>& x) { return (i128)x[o] == (i128)x[i] * rng[i]; };
+        if (nests(ca) && nests(cb) && nests(cc) && (i128)rng[i] * rng[o] < ((i128)1 << 62)) {
+          rng[i] *= rng[o];
+          for (auto* v : {&rng, &ca, &cb, &cc}) v->erase(v->begin() + o);
+          merged = true;
+        }
+      }
+  }
+  if (rng.size() != 3) return false;
   int m = -1, n = -1, k = -1;
   for (int j = 0; j < 3; ++j) {
-    if (C.c[j] == 0) {
+    if (cc[j] == 0) {
       if (k >= 0) return false;
       k = j;
-    } else if (A.c[j] && !B.c[j]) {
+    } else if (ca[j] && !cb[j]) {
       if (m >= 0) return false;
       m = j;
-    } else if (B.c[j] && !A.c[j]) {
+    } else if (cb[j] && !ca[j]) {
       if (n >= 0) return false;
       n = j;
     } else {
       return false;
     }
   }
-  if (m < 0 || n < 0 || k < 0 || !A.c[k] || !B.c[k]) return false;
-  g->M = fb.range[m]; g->N = fb.range[n]; g->K = fb.range[k];
-  g->a_m = A.c[m]; g->a_k = A.c[k]; g->b_k = B.c[k]; g->b_n = B.c[n]; g->c_m = C.c[m]; g->c_n = C.c[n];
-  g->a_base = A.k; g->b_base = B.k; g->c_base = C.k;
+  if (m < 0 || n < 0 || k < 0 || !ca[k] || !cb[k]) return false;
+  g->M = rng[m]; g->N = rng[n]; g->K = rng[k];
+  g->a_m = ca[m]; g->a_k = ca[k]; g->b_k = cb[k]; g->b_n = cb[n]; g->c_m = cc[m]; g->c_n = cc[n];
+  g->a_base = fb.ref[0].addr.k; g->b_base = fb.ref[1].addr.k; g->c_base = fb.ref[2].addr.k;
   return g->a_m > 0 && g->a_k > 0 && g->b_k > 0 && g->b_n > 0 && g->c_m > 0 && g->c_n > 0;
 }
 

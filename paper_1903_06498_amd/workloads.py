@@ -220,12 +220,14 @@ def conv2d_block(N, H, W, Ci, Co, R, S, stride, pad, in_dtype, out_dtype, filter
                       constraints=cons, intrinsic="mul")
 
 
-def matmul_block(M, N, K, in_dtype, out_dtype) -> Block:
-    """C[m,n] += A[m,k] * B[k,n], all row-major, no constraints."""
-    bufs = [Buffer("A", "in", in_dtype, (M, K)), Buffer("B", "in", in_dtype, (K, N)),
+def matmul_block(M, N, K, in_dtype, out_dtype, b_transposed=False) -> Block:
+    """C[m,n] += A[m,k] * B[k,n], all row-major, no constraints.  With b_transposed the second operand is
+    stored as [n][k] (C = A * B^T, the layout of a Linear layer's weights)."""
+    bufs = [Buffer("A", "in", in_dtype, (M, K)), Buffer("B", "in", in_dtype, (N, K) if b_transposed else (K, N)),
             Buffer("C", "out", out_dtype, (M, N))]
     return flat_block(bufs, dict(m=M, n=N, k=K),
-                      [(["m", "k"], "assign"), (["k", "n"], "assign"), (["m", "n"], "add")], intrinsic="mul")
+                      [(["m", "k"], "assign"), (["n", "k"] if b_transposed else ["k", "n"], "assign"), (["m", "n"], "add")],
+                      intrinsic="mul")
 
 
 def maxpool_block(N, H, W, C, R, stride, pad, dtype="f32") -> Block:

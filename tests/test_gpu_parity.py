@@ -268,6 +268,38 @@ def test_gemm_mfma_position_sensitive(tune, name, monkeypatch):
     parity(blk, ins, what=f"gemm {tune}")
 
 
+@pytest.mark.parametrize("M,N,K,bt", [(256, 256, 128, True), (512, 768, 384, True), (300, 520, 256, False), (2, 8, 128, False),
+                                      (257, 264, 128, False), (300, 333, 256, True), (70, 9, 128, True), (511, 8, 128, True)])
+def test_gemm_transposed_b_and_ragged_edges(M, N, K, bt):
+    """The LDS-direct kernel with B stored [n][k] and/or M, N that are not multiples of the 256 x 256 tile.
+    Position-sensitive operands first (every output is one specific A element, exactly), then seeded data."""
+    blk = W.matmul_block(M, N, K, "bf16", "f32", b_transposed=bt)
+    a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.bfloat16)
+    shift = 37
+    sel = (torch.arange(N) + shift) % K
+    b = torch.zeros((K, N), dtype=torch.bfloat16)
+    b[sel, torch.arange(N)] = 1.0
+    gpu, sb = run_gpu(blk, [a, b.t().contiguous() if bt else b], return_block=True)
+    ragged = M % 256 != 0 or N % 256 != 0
+    want_name = "lds_direct" + ("_bt" if bt else "") + ("_ragged" if ragged else "")
+    assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"].endswith(want_name), sb.info["kernel"]
+    assert np.array_equal(gpu.reshape(M, N), a.float()[:, sel].numpy())
+    ins = [W.seeded_tensor((M, K), "bf16", 0), W.seeded_tensor((N, K) if bt else (K, N), "bf16", 1)]
+    parity(blk, ins, what=f"gemm {M}x{N}x{K} bt={bt}")          # also checks that nothing outside C[0:M, 0:N] changed
+
+
+def test_pointwise_convolution_runs_on_the_gemm_kernel():
+    """A 1x1 convolution O[n,y,x,k] += I[n,y,x,c] * F[k,c] canonicalises to C = A * B^T (pixels merge into one index)."""
+    N, H, Wd, Ci, Co = 2, 12, 20, 128, 72
+    bufs = [W.Buffer("I", "in", "bf16", (N, H, Wd, Ci)), W.Buffer("F", "in", "bf16", (Co, Ci)),
+            W.Buffer("O", "out", "f32", (N, H, Wd, Co))]
+    blk = W.flat_block(bufs, dict(n=N, y=H, x=Wd, c=Ci, k=Co),
+                       [(["n", "y", "x", "c"], "assign"), (["k", "c"], "assign"), (["n", "y", "x", "k"], "add")], intrinsic="mul")
+    ins = [W.seeded_tensor((N, H, Wd, Ci), "bf16", 0), W.seeded_tensor((Co, Ci), "bf16", 1)]
+    info, _ = parity(blk, ins, what="1x1 conv")
+    assert info["path_name"] == "mfma_gemm" and info["kernel"].endswith("_bt_ragged"), info
+
+
 def test_gemm_config_full_size():
     """4096^3 in the benchmark's launch configuration: oracle slabs + identity property."""
     name = "gemm_bf16_4096"
