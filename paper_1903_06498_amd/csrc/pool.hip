@@ -225,11 +225,27 @@ __global__ __launch_bounds__(512) void pool_max_f32_roll_kernel(const PoolParams
 // Strip kernel with the same instruction diet as the rolling kernel (clamped
 // duplicates instead of selects, uniform row bases, three-operand maxima):
 // 128 lanes own 128 (column, channel-quad) items and TY output rows, and all
-// loads of the strip are issued before the first reduction.
-template <int TY>
-__global__ __launch_bounds__(128) void pool_max_f32_strip_kernel(const PoolParams p, const float* __restrict__ in,
-                                                                float* __restrict__ out) {
-  constexpr int ST = 2, S = 3, R = 3, NR = ST * (TY - 1) + R;
+// loads of the strip are issued before the first reduction.  Window R x S,
+// stride ST, max or min (both idempotent, which the clamped duplicates need).
+template <bool MIN>
+__device__ __forceinline__ float pick(float a, float b) { return MIN ? __builtin_fminf(a, b) : __builtin_fmaxf(a, b); }
+template <int N, bool MIN>
+__device__ __forceinline__ f32x4 fold(const f32x4* v) {
+  f32x4 r = v[0];
+#pragma unroll
+  for (int i = 1; i < N; ++i) {
+    r.x = pick<MIN>(r.x, v[i].x);
+    r.y = pick<MIN>(r.y, v[i].y);
+    r.z = pick<MIN>(r.z, v[i].z);
+    r.w = pick<MIN>(r.w, v[i].w);
+  }
+  return r;
+}
+
+template <int R, int S, int ST, int TY, bool MIN>
+__global__ __launch_bounds__(128) void pool_f32_strip_kernel(const PoolParams p, const float* __restrict__ in,
+                                                            float* __restrict__ out) {
+  constexpr int NR = ST * (TY - 1) + R;
   const unsigned b = blockIdx.x;
   const int bx = b % p.blocks_per_row;
   const int rest = b / p.blocks_per_row;
@@ -263,11 +279,11 @@ __global__ __launch_bounds__(128) void pool_max_f32_strip_kernel(const PoolParam
   }
   f32x4 hm[NR];
 #pragma unroll
-  for (int r = 0; r < NR; ++r) hm[r] = max3x4(v[r][0], v[r][1], v[r][2]);
+  for (int r = 0; r < NR; ++r) hm[r] = fold<S, MIN>(v[r]);
 #pragma unroll
   for (int ty = 0; ty < TY; ++ty) {
     const int yo = yo0 + ty;
-    if (yo < p.Ho) *(f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff) = max3x4(hm[ty * ST], hm[ty * ST + 1], hm[ty * ST + 2]);
+    if (yo < p.Ho) *(f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff) = fold<R, MIN>(hm + ty * ST);
   }
 }
 
@@ -290,7 +306,7 @@ constexpr int kTyChoices[] = {1, 2, 3, 4, 7};
 template <int TY, bool NT>
 hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st, bool lean) {
   if (lean && !NT) {
-    hipLaunchKernelGGL((pool_max_f32_strip_kernel<TY>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
+    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, false>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((pool_max_f32_kernel<3, 3, 2, TY, NT>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
@@ -301,10 +317,17 @@ hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* ou
 
 // variant = index into kTyChoices * 2 + nontemporal flag for the strip kernel, kRollVariant for the rolling kernel
 constexpr int kRollVariant = 100;
+// other windows and min pooling: lean strip kernel, 2 output rows per strip; variant = kShapeVariant + 2*shape + is_min
+constexpr int kShapeVariant = 200;
+struct PoolWindow { int r, s, stride; };
+constexpr PoolWindow kWindows[] = {{3, 3, 2}, {2, 2, 2}, {3, 3, 1}};
 
 bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_info_t* info) {
   if (dtype != STRIPE_F32) return false;
-  if (s.R != 3 || s.S != 3 || s.stride_y != 2 || s.stride_x != 2) return false;
+  int window = -1;
+  for (int w = 0; w < (int)(sizeof kWindows / sizeof kWindows[0]); ++w)
+    if (s.R == kWindows[w].r && s.S == kWindows[w].s && s.stride_y == kWindows[w].stride && s.stride_x == kWindows[w].stride) window = w;
+  if (window < 0) return false;
   if (s.i_c != 1 || s.o_c != 1 || s.C % 4) return false;
   // every window must hold at least one in-range tap, so every output is written
   if (s.pad_y >= s.R || s.pad_x >= s.S) return false;
@@ -315,6 +338,27 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   if (s.N > 0x7fffffff / 4 || s.H > 0x3fffffff || s.W > 0x3fffffff || s.Wo * (s.C / 4) > 0x3fffffff) return false;
   const bool row_offsets_fit = ((s.W - 1) * s.i_x + s.C) < ((int64_t)1 << 29) && ((s.Wo - 1) * s.o_x + s.C) < ((int64_t)1 << 29) &&
                               s.i_x >= 0 && s.o_x >= 0;
+  if (window != 0 || s.is_min) {
+    if (!row_offsets_fit) return false;
+    const PoolParams p = make_params(s, 2, 128);
+    const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
+    if (grid > 0x7fffffffLL) return false;
+    l->variant = kShapeVariant + 2 * window + (s.is_min ? 1 : 0);
+    l->rows = 2;
+    l->wg = 128;
+    l->grid = grid;
+    info->path = STRIPE_PATH_POOL;
+    info->tile_m = 2;
+    info->tile_n = 128;
+    info->tile_k = 0;
+    info->frag_m = info->frag_n = info->frag_k = 0;
+    info->lds_bytes = 0;
+    info->workgroup_size = 128;
+    info->grid = grid;
+    snprintf(info->kernel, sizeof info->kernel, "pool_%s_f32_%dx%ds%d_ty2", s.is_min ? "min" : "max", kWindows[window].r, kWindows[window].s,
+             kWindows[window].stride);
+    return true;
+  }
   if (tune_int("pool_roll", 0) && row_offsets_fit) {
     int rows = tune_int("pool_roll_rows", 7);
     if (rows < 1) rows = 1;
@@ -375,6 +419,21 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
 
 hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in, void* out, hipStream_t st) {
   if (((uintptr_t)in % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
+  if (l.variant >= kShapeVariant) {
+    const PoolParams p = make_params(s, 2, 128);
+    const dim3 g((unsigned)l.grid), b(128);
+    const float* i = (const float*)in;
+    float* o = (float*)out;
+    switch (l.variant - kShapeVariant) {
+      case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, 2, true>), g, b, 0, st, p, i, o); break;
+      case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, false>), g, b, 0, st, p, i, o); break;
+      case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, true>), g, b, 0, st, p, i, o); break;
+      case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, false>), g, b, 0, st, p, i, o); break;
+      case 5: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, true>), g, b, 0, st, p, i, o); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   if (l.variant == kRollVariant) {
     const PoolParams p = make_params(s, l.rows, l.wg);
     hipLaunchKernelGGL(pool_max_f32_roll_kernel, dim3((unsigned)l.grid), dim3(l.wg), 0, st, p, (const float*)in, (float*)out);

@@ -230,8 +230,8 @@ def matmul_block(M, N, K, in_dtype, out_dtype, b_transposed=False) -> Block:
                       intrinsic="mul")
 
 
-def maxpool_block(N, H, W, C, R, stride, pad, dtype="f32") -> Block:
-    """O[n,y,x,c] = max over in-bounds taps of I[n, s*y+i-p, s*x+j-p, c]; body load -> store."""
+def maxpool_block(N, H, W, C, R, stride, pad, dtype="f32", agg="max") -> Block:
+    """O[n,y,x,c] = max (or another aggregation) over in-bounds taps of I[n, s*y+i-p, s*x+j-p, c]; body load -> store."""
     Ho = (H + 2 * pad - R) // stride + 1
     Wo = (W + 2 * pad - R) // stride + 1
     bufs = [Buffer("I", "in", dtype, (N, H, W, C)), Buffer("O", "out", dtype, (N, Ho, Wo, C))]
@@ -240,7 +240,7 @@ def maxpool_block(N, H, W, C, R, stride, pad, dtype="f32") -> Block:
     xa = f"{s}*x + j - {p}"
     cons = [f"{ya} >= 0", f"{H - 1 + p} - {s}*y - i >= 0", f"{xa} >= 0", f"{W - 1 + p} - {s}*x - j >= 0"]
     return flat_block(bufs, dict(n=N, y=Ho, x=Wo, c=C, i=R, j=R),
-                      [(["n", ya, xa, "c"], "assign"), (["n", "y", "x", "c"], "max")],
+                      [(["n", ya, xa, "c"], "assign"), (["n", "y", "x", "c"], agg)],
                       constraints=cons, intrinsic="copy")
 
 

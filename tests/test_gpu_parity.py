@@ -219,6 +219,19 @@ def test_pool_rolling_chunks(rows, wg, monkeypatch):
     assert np.array_equal(run_gpu(blk, [x]).reshape(ref.shape), ref.numpy())
 
 
+@pytest.mark.parametrize("R,stride,pad,agg", [(2, 2, 0, "max"), (2, 2, 1, "min"), (3, 1, 1, "max"), (3, 1, 0, "min"), (3, 2, 1, "min"),
+                                              (3, 2, 0, "max"), (3, 1, 2, "max")])
+def test_pool_other_windows_and_min(R, stride, pad, agg):
+    """2x2/s2 and 3x3/s1 windows, several paddings, max and min on the pooling kernel: exact, and equal to the
+    generic kernel's result."""
+    N, H, Wd, C = 2, 21, 18, 12
+    blk = W.maxpool_block(N, H, Wd, C, R, stride, pad, agg=agg)
+    x = W.seeded_tensor((N, H, Wd, C), "f32", 5)
+    info, _ = parity(blk, [x], what=f"pool {R}x{R}s{stride}p{pad} {agg}")
+    assert info["path_name"] == "pool" and info["kernel"] == f"pool_{agg}_f32_{R}x{R}s{stride}_ty2", info
+    assert np.array_equal(run_gpu(blk, [x], "pool"), run_gpu(blk, [x], "generic"))
+
+
 def test_pool_all_negative_and_generic_agree():
     blk = W.maxpool_block(2, 21, 17, 8, 3, 2, 1)
     x = -torch.abs(W.seeded_tensor((2, 21, 17, 8), "f32", 1)) - 1
