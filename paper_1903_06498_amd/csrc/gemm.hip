@@ -416,7 +416,24 @@ struct DCtx {
 // have it); its tile then lies in LDS exactly like A's and a fragment is one 16-byte read.
 // MODE bit 1: M and N need not be multiples of 256: loads of rows (or column chunks) past the edge are redirected
 // to the last valid one -- they only feed accumulators that are never stored -- and the stores are predicated.
-constexpr int D_BT = 1, D_RAGGED = 2;
+// MODE bit 2: the operands are int8 with int32 accumulation (v_mfma_i32_32x32x32_i8).  Only the matrix instruction
+// changes: a tile row is 64 bytes either way (64 int8 or 32 bf16 values), a fragment chunk is 16 bytes either way,
+// and the 32 x 32 result layout is the same, so the host hands the int8 matrices over as 16-bit matrices of half
+// the width (strides and bases in 2-byte units) and the accumulators are kept as bit patterns in the same registers.
+// Needs D_BT: with k contiguous in both operands no transposition of bytes is required.
+constexpr int D_BT = 1, D_RAGGED = 2, D_I8 = 4;
+typedef __attribute__((ext_vector_type(4))) int d_i32x4;
+typedef __attribute__((ext_vector_type(16))) int d_i32x16;
+
+template <int MODE>
+__device__ __forceinline__ f32x16 d_mma(bf16x8 a, bf16x8 b, f32x16 acc) {
+  if constexpr (MODE & D_I8) {
+    return __builtin_bit_cast(f32x16, __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(d_i32x4, a), __builtin_bit_cast(d_i32x4, b),
+                                                                           __builtin_bit_cast(d_i32x16, acc), 0, 0, 0));
+  } else {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+  }
+}
 
 // The LDS-direct loads are written as assembly on purpose: the compiler cannot
 // tell that a load into one ring stage does not alias the fragment reads of
@@ -474,17 +491,17 @@ __device__ __forceinline__ void d_read_frags(const DCtx& c, const unsigned char*
   d_read_group<0, STAGE_N, S, 3, FN, MODE>(c, lds, af, bf);
 }
 
-template <int Q, int FN>
+template <int Q, int FN, int MODE = 0>
 __device__ __forceinline__ void d_mfma_row(const bf16x8 (&af)[4], const bf16x8 (&bf)[FN], f32x16 (&acc)[4][FN]) {
 #pragma unroll
-  for (int j = 0; j < FN; ++j) acc[Q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[Q], bf[j], acc[Q][j], 0, 0, 0);
+  for (int j = 0; j < FN; ++j) acc[Q][j] = d_mma<MODE>(af[Q], bf[j], acc[Q][j]);
 }
 
 // matrix instructions J0 .. J1-1 of accumulator row Q
-template <int Q, int J0, int J1, int FN>
+template <int Q, int J0, int J1, int FN, int MODE = 0>
 __device__ __forceinline__ void d_mfma_part(const bf16x8 (&af)[4], const bf16x8 (&bf)[FN], f32x16 (&acc)[4][FN]) {
 #pragma unroll
-  for (int j = J0; j < J1; ++j) acc[Q][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[Q], bf[j], acc[Q][j], 0, 0, 0);
+  for (int j = J0; j < J1; ++j) acc[Q][j] = d_mma<MODE>(af[Q], bf[j], acc[Q][j]);
 }
 
 #define D_FENCE() __builtin_amdgcn_sched_barrier(0)
@@ -535,31 +552,31 @@ __device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt
   const uint16_t* b = c.b_src + (size_t)(kt + 3) * c.b_kstep;
   const size_t a_koff = (size_t)(kt + 3) * D_BK, b_koff = (size_t)(kt + 3) * c.b_kstep;
   D_FENCE();
-  d_mfma_row<0, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 0, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<1, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 1, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
-  d_mfma_row<2, FN>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 2, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<0, FN, MODE>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 0, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<1, FN, MODE>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 1, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
+  d_mfma_row<2, FN, MODE>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 2, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
   // the barrier sits before the group's last matrix instruction, which then covers the barrier's latency
   constexpr int EARLY = SCHED == 2 ? FN - 1 : FN;   // matrix instructions of group 3 issued before the barrier
-  d_mfma_part<3, 0, EARLY, FN>(af[0], bf[0], acc);
+  d_mfma_part<3, 0, EARLY, FN, MODE>(af[0], bf[0], acc);
   if constexpr (SCHED == 0) d_read_group<SCHED, STAGE_N, 1, 3, FN, MODE>(c, lds, af[1], bf[1]);
   D_FENCE();
   d_wait_loads<PENDING>();
   __syncthreads();
   D_FENCE();
-  d_mfma_part<3, EARLY, FN, FN>(af[0], bf[0], acc);
-  d_mfma_row<0, FN>(af[1], bf[1], acc);
+  d_mfma_part<3, EARLY, FN, FN, MODE>(af[0], bf[0], acc);
+  d_mfma_row<0, FN, MODE>(af[1], bf[1], acc);
   if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 0, FN, MODE>(c, lds, af[0], bf[0]);
   if (ISSUE) d_issue_group<LD, WAVES, 0, MODE>(c, a, b, a_koff, b_koff);
   D_FENCE();
-  d_mfma_row<1, FN>(af[1], bf[1], acc);
+  d_mfma_row<1, FN, MODE>(af[1], bf[1], acc);
   if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 1, FN, MODE>(c, lds, af[0], bf[0]);
   if (ISSUE) d_issue_group<LD, WAVES, 1, MODE>(c, a, b, a_koff, b_koff);
   D_FENCE();
-  d_mfma_row<2, FN>(af[1], bf[1], acc);
+  d_mfma_row<2, FN, MODE>(af[1], bf[1], acc);
   if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 2, FN, MODE>(c, lds, af[0], bf[0]);
   if (ISSUE) d_issue_group<LD, WAVES, 2, MODE>(c, a, b, a_koff, b_koff);
   D_FENCE();
-  d_mfma_row<3, FN>(af[1], bf[1], acc);
+  d_mfma_row<3, FN, MODE>(af[1], bf[1], acc);
   if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 3, FN, MODE>(c, lds, af[0], bf[0]);
   if (ISSUE) d_issue_group<LD, WAVES, 3, MODE>(c, a, b, a_koff, b_koff);
   D_FENCE();
@@ -699,7 +716,7 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
       }
 }
 
-GemmParams make_params(const GemmShape& g) {
+GemmParams make_params(const GemmShape& g, bool i8 = false) {
   GemmParams p;
   p.tiles_m = (int)((g.M + BM - 1) / BM);
   p.tiles_n = (int)((g.N + BN - 1) / BN);
@@ -709,13 +726,38 @@ GemmParams make_params(const GemmShape& g) {
   p.pad_ = 0;
   p.a_m = g.a_m; p.c_m = g.c_m;
   p.b_k = (g.b_k == 1 && g.b_n != 1) ? g.b_n : g.b_k;   // row stride of B as stored: [n][k] (transposed) or [k][n]
-  p.a_base = g.a_base; p.b_base = g.b_base; p.c_base = g.c_base;
+  if (i8) {   // int8 operands seen as 16-bit matrices of half the width (see D_I8)
+    p.a_m /= 2;
+    p.b_k /= 2;
+  }
+  p.a_base = i8 ? g.a_base / 2 : g.a_base;
+  p.b_base = i8 ? g.b_base / 2 : g.b_base;
+  p.c_base = g.c_base;
   return p;
 }
 
 }  // namespace
 
 bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info) {
+  if (in_dtype == STRIPE_I8) {
+    // int8 x int8 -> int32 with both operands k-contiguous (C = A * B^T); K tiles of 64 bytes, four in flight
+    if (g.a_k != 1 || g.c_n != 1 || g.b_k != 1 || g.b_n == 1 || tune_int("gemm_dma", 1) == 0) return false;
+    if (g.K % 256 || g.K < 256 || g.M < 1 || g.N < 8 || g.M > 0x7fffffff || g.N > 0x7fffffff) return false;
+    if (g.a_m % 16 || g.b_n % 16 || g.a_base % 16 || g.b_base % 16) return false;   // 16-byte global loads
+    const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+    if (tiles_m > 32767 || tiles_n > 32767) return false;
+    const bool ragged = (g.M % BM || g.N % BN);
+    l->variant = 40 + (ragged ? D_RAGGED : 0);
+    l->grid = tiles_m * tiles_n;
+    info->path = STRIPE_PATH_MFMA_GEMM;
+    info->tile_m = BM; info->tile_n = BN; info->tile_k = 64;
+    info->frag_m = 32; info->frag_n = 32; info->frag_k = 32;
+    info->lds_bytes = D_LDS;
+    info->workgroup_size = 256;
+    info->grid = l->grid;
+    snprintf(info->kernel, sizeof info->kernel, "gemm_i8_256x256x64_mfma32x32x32_w4_lds_direct_bt%s", ragged ? "_ragged" : "");
+    return true;
+  }
   if (in_dtype != STRIPE_BF16) return false;
   if (g.a_k != 1 || g.c_n != 1) return false;
   // B row-major ([k][n], n contiguous) or transposed ([n][k], k contiguous); the LDS-direct kernel also takes
@@ -768,7 +810,8 @@ bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_i
 
 hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t st) {
   if (((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % 4)) return hipErrorInvalidValue;
-  const GemmParams p = make_params(g);
+  const bool i8 = l.variant >= 40;
+  const GemmParams p = make_params(g, i8);
   void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = nullptr;
   switch (l.variant) {
     case 0: case 1: case 2: kernel = gemm_bf16_w4_kernel; break;
@@ -779,6 +822,8 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
     case 30 + D_BT: kernel = gemm_bf16_dma_kernel<4, 1, D_BT>; break;
     case 30 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_RAGGED>; break;
     case 30 + D_BT + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED>; break;
+    case 40: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_I8>; break;
+    case 40 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED + D_I8>; break;
     case 10: kernel = gemm_bf16_w8_kernel<0>; break;
     case 11: kernel = gemm_bf16_w8_kernel<1>; break;
     default: kernel = gemm_bf16_w8_kernel<2>; break;
@@ -786,7 +831,7 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
   const int threads = (l.variant == 21 || (l.variant >= 10 && l.variant < 20)) ? THREADS : W4_THREADS;
   const int lds_bytes = l.variant >= 20 ? D_LDS : 2 * STAGE;
   GemmParams pk = p;
-  if (l.variant >= 20) pk.k_tiles = (int)(g.K / D_BK);
+  if (l.variant >= 20) pk.k_tiles = (int)(g.K / (i8 ? 64 : D_BK));
   // more than 64 KB of dynamic LDS has to be enabled once per device
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);

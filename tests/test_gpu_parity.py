@@ -301,6 +301,25 @@ def test_gemm_transposed_b_and_ragged_edges(M, N, K, bt):
     parity(blk, ins, what=f"gemm {M}x{N}x{K} bt={bt}")          # also checks that nothing outside C[0:M, 0:N] changed
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (512, 768, 512), (300, 333, 256), (70, 9, 512), (257, 8, 256)])
+def test_gemm_int8_transposed_b(M, N, K):
+    """int8 x int8 -> int32 on the matrix cores (C = A * B^T, both operands k-contiguous): bit-exact, including
+    extreme values (-128 * -128 summed over K) and edges that are not multiples of the tile."""
+    blk = W.matmul_block(M, N, K, "i8", "i32", b_transposed=True)
+    a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.int8)
+    sel = (torch.arange(N) + 37) % K
+    b = torch.zeros((N, K), dtype=torch.int8)
+    b[torch.arange(N), sel] = 1
+    gpu, sb = run_gpu(blk, [a, b], return_block=True)
+    ragged = M % 256 != 0 or N % 256 != 0
+    assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"] == "gemm_i8_256x256x64_mfma32x32x32_w4_lds_direct_bt" + ("_ragged" if ragged else "")
+    assert np.array_equal(gpu.reshape(M, N), a.to(torch.int32)[:, sel].numpy())
+    ins = [W.seeded_tensor((M, K), "i8", 0), W.seeded_tensor((N, K), "i8", 1)]
+    parity(blk, ins, what=f"int8 gemm {M}x{N}x{K}")
+    lows = [torch.full((M, K), -128, dtype=torch.int8), torch.full((N, K), -128, dtype=torch.int8)]
+    assert np.all(run_gpu(blk, lows) == 16384 * K)
+
+
 def test_pointwise_convolution_runs_on_the_gemm_kernel():
     """A 1x1 convolution O[n,y,x,k] += I[n,y,x,c] * F[k,c] canonicalises to C = A * B^T (pixels merge into one index)."""
     N, H, Wd, Ci, Co = 2, 12, 20, 128, 72
