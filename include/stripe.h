@@ -43,7 +43,10 @@ typedef enum { STRIPE_I8 = 0, STRIPE_I32 = 1, STRIPE_BF16 = 2, STRIPE_F32 = 3 } 
 
 /* Aggregation operations (Section 2.1 last sentence; Section 3.2: 'assign'
  * declares that no two iterations write the same element). */
-typedef enum { STRIPE_AGG_ASSIGN = 0, STRIPE_AGG_ADD = 1, STRIPE_AGG_MAX = 2, STRIPE_AGG_MIN = 3 } stripe_agg_t;
+typedef enum {
+  STRIPE_AGG_ASSIGN = 0, STRIPE_AGG_ADD = 1, STRIPE_AGG_MAX = 2, STRIPE_AGG_MIN = 3,
+  STRIPE_AGG_MUL = 4   /* product; integer products wrap in int32 like any int32 arithmetic here */
+} stripe_agg_t;
 
 /* Leaf statement lists (Section 3.2 "intrinsics"; Figure 5 lines 0-3 of the inner block):
  *   MUL : $a = load(in0); $b = load(in1); $o = mul($a,$b); out = store($o)

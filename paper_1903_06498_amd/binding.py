@@ -25,7 +25,7 @@ PATH_NAMES = {v: k for k, v in PATHS.items()}
 
 _DIR = {"in": 0, "out": 1}
 _DTYPE = {"i8": 0, "i32": 1, "bf16": 2, "f32": 3}
-_AGG = {"assign": 0, "add": 1, "max": 2, "min": 3}
+_AGG = {"assign": 0, "add": 1, "max": 2, "min": 3, "mul": 4}
 _INTR = {"mul": 0, "copy": 1, "add": 2}
 
 EXPORTS = ("stripe_block_create", "stripe_block_create_for_path", "stripe_block_run", "stripe_block_query",

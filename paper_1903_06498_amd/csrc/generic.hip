@@ -50,11 +50,11 @@ struct Elem<float> {
 // Identity of the aggregation: what an output element holds before the atomic combine pass.
 template <int AGG>
 __device__ __forceinline__ int32_t identity_of(int32_t) {
-  return AGG == STRIPE_AGG_MAX ? (int32_t)0x80000000 : AGG == STRIPE_AGG_MIN ? 0x7fffffff : 0;
+  return AGG == STRIPE_AGG_MAX ? (int32_t)0x80000000 : AGG == STRIPE_AGG_MIN ? 0x7fffffff : AGG == STRIPE_AGG_MUL ? 1 : 0;
 }
 template <int AGG>
 __device__ __forceinline__ float identity_of(float) {
-  return AGG == STRIPE_AGG_MAX ? -__builtin_huge_valf() : AGG == STRIPE_AGG_MIN ? __builtin_huge_valf() : 0.f;
+  return AGG == STRIPE_AGG_MAX ? -__builtin_huge_valf() : AGG == STRIPE_AGG_MIN ? __builtin_huge_valf() : AGG == STRIPE_AGG_MUL ? 1.f : 0.f;
 }
 
 // Atomic aggregation onto one output element.  Integer operations are exact in any order; float sums
@@ -62,7 +62,14 @@ __device__ __forceinline__ float identity_of(float) {
 // float max/min are exact and use a compare-and-swap loop.
 template <int AGG>
 __device__ __forceinline__ void atomic_combine(int32_t* p, int32_t v) {
-  if (AGG == STRIPE_AGG_MAX) atomicMax(p, v);
+  if (AGG == STRIPE_AGG_MUL) {
+    int32_t seen = __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (;;) {
+      const int32_t prev = atomicCAS(p, seen, (int32_t)((uint32_t)seen * (uint32_t)v));
+      if (prev == seen) break;
+      seen = prev;
+    }
+  } else if (AGG == STRIPE_AGG_MAX) atomicMax(p, v);
   else if (AGG == STRIPE_AGG_MIN) atomicMin(p, v);
   else atomicAdd(p, v);
 }
@@ -76,6 +83,14 @@ __device__ __forceinline__ void atomic_combine(float* p, float v) {
       if (prev == seen) break;
       seen = prev;
     }
+  } else if (AGG == STRIPE_AGG_MUL) {
+    unsigned* u = (unsigned*)p;
+    unsigned seen = __hip_atomic_load(u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (;;) {
+      const unsigned prev = atomicCAS(u, seen, __float_as_uint(__uint_as_float(seen) * v));
+      if (prev == seen) break;
+      seen = prev;
+    }
   } else {
     atomicAdd(p, v);
   }
@@ -85,6 +100,10 @@ template <int AGG, typename A>
 __device__ __forceinline__ A combine(A acc, A v) {
   if (AGG == STRIPE_AGG_MAX) return v > acc ? v : acc;
   if (AGG == STRIPE_AGG_MIN) return v < acc ? v : acc;
+  if (AGG == STRIPE_AGG_MUL) {
+    if constexpr (std::is_same<A, int32_t>::value) return (A)((uint32_t)acc * (uint32_t)v);   // wraps, like the atomic form
+    else return acc * v;
+  }
   return acc + v;
 }
 
@@ -252,6 +271,7 @@ hipError_t launch_agg(int agg, const GenericParams& p, const void* a, const void
   switch (agg) {
     case STRIPE_AGG_MAX: return launch_lanes<TIn, INTR, STRIPE_AGG_MAX>(p, a, b, o, s);
     case STRIPE_AGG_MIN: return launch_lanes<TIn, INTR, STRIPE_AGG_MIN>(p, a, b, o, s);
+    case STRIPE_AGG_MUL: return launch_lanes<TIn, INTR, STRIPE_AGG_MUL>(p, a, b, o, s);
     default: return launch_lanes<TIn, INTR, STRIPE_AGG_ADD>(p, a, b, o, s);  // assign: single writer, any op
   }
 }

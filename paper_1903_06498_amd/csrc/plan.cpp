@@ -248,7 +248,7 @@ stripe_status_t flatten(const stripe_block_desc_t* root, FlatBlock* fb, std::str
       }
     }
     const int a = b->refs[R - 1].agg;
-    if (a < STRIPE_AGG_ASSIGN || a > STRIPE_AGG_MIN) return bad(err, STRIPE_ERR_INVALID_DESC, "unknown aggregation");
+    if (a < STRIPE_AGG_ASSIGN || a > STRIPE_AGG_MUL) return bad(err, STRIPE_ERR_INVALID_DESC, "unknown aggregation");
     fb->level_agg[l] = a;
     if (a != STRIPE_AGG_ASSIGN) {
       if (fb->agg != STRIPE_AGG_ASSIGN && fb->agg != a)
