@@ -288,6 +288,7 @@ hipError_t launch_intr(int intr, int agg, const GenericParams& p, const void* a,
 }  // namespace
 
 hipError_t launch_generic(const Plan& plan, const void* in0, const void* in1, void* out, hipStream_t stream) {
+  if (plan.tiled.use) return launch_generic_tiled(plan, in0, in1, out, stream);
   const GenericParams& p = plan.gen;
   if (p.n_outputs <= 0) return hipErrorInvalidValue;
   const int64_t blocks = p.lanes == 64 ? (p.n_outputs + 3) / 4 : (p.n_outputs + 255) / 256;
@@ -304,6 +305,15 @@ hipError_t launch_generic(const Plan& plan, const void* in0, const void* in1, vo
 void generic_info(const Plan& plan, stripe_block_info_t* info) {
   const GenericParams& p = plan.gen;
   info->path = STRIPE_PATH_GENERIC;
+  if (plan.tiled.use) {
+    info->tile_m = 4; info->tile_n = 4; info->tile_k = plan.tiled.vec;
+    info->frag_m = info->frag_n = info->frag_k = 0;
+    info->lds_bytes = 0;
+    info->workgroup_size = 256;
+    info->grid = (plan.tiled.n_items + 255) / 256;
+    snprintf(info->kernel, sizeof info->kernel, "generic_tiled_4x4%s", plan.tiled.vec == 4 ? "_v4" : "");
+    return;
+  }
   info->tile_m = info->tile_n = info->tile_k = 0;
   info->frag_m = info->frag_n = info->frag_k = 0;
   info->lds_bytes = 0;

@@ -26,6 +26,7 @@ inline int tune_int(const char* key, int dflt) {
 // ---- generic affine-index contraction (any legal block) -------------------
 hipError_t launch_generic(const Plan& plan, const void* in0, const void* in1, void* out, hipStream_t stream);
 void generic_info(const Plan& plan, stripe_block_info_t* info);
+hipError_t launch_generic_tiled(const Plan& plan, const void* in0, const void* in1, void* out, hipStream_t stream);
 
 // ---- nested-tile dense contraction on matrix cores ------------------------
 struct GemmLaunch {

@@ -840,6 +840,77 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
     for (const Affine& c : fb.cons) narrow = narrow && reach(c) <= lim;
     g.narrow = narrow ? 1 : 0;
     g.atomic = injective ? 0 : 1;
+
+    // Register-tiled variant for sum-of-products blocks with enough parallelism (see TiledParams).
+    TiledParams& tp = plan->tiled;
+    std::memset(&tp, 0, sizeof tp);
+    if (narrow && injective && B && fb.intrinsic == STRIPE_INTR_MUL && fb.agg == STRIPE_AGG_ADD) {
+      auto absv = [](int64_t v) { return v < 0 ? -v : v; };
+      auto in_cons = [&](int j) {
+        for (const Affine& c : fb.cons)
+          if (c.c[j]) return true;
+        return false;
+      };
+      int pm = -1, pn = -1;
+      for (int j : out_idx) {   // out_idx is sorted by |output stride|: the first fit has the smallest
+        const bool inA = A.c[j] != 0, inB = B->c[j] != 0;
+        if (inA && !inB && pm < 0) pm = j;
+        if (!inA && inB && pn < 0 && !in_cons(j)) pn = j;
+      }
+      // innermost reduction index: free of constraints; unit stride in both operands is best (vector loads)
+      int r0 = -1;
+      for (int j : red_idx) {
+        if (in_cons(j)) continue;
+        const bool unit = absv(A.c[j]) == 1 && absv(B->c[j]) == 1;
+        if (r0 < 0 || (unit && !(absv(A.c[r0]) == 1 && absv(B->c[r0]) == 1))) r0 = j;
+      }
+      std::vector<int> reds;
+      if (r0 >= 0) reds.push_back(r0);
+      for (int j : red_idx)
+        if (j != r0) reds.push_back(j);
+      const int first_real = r0 >= 0 ? 0 : 1;   // without a constraint-free index level 0 stays a dummy of range 1
+      std::vector<int> outers;
+      for (int j : out_idx)
+        if (j != pm && j != pn) outers.push_back(j);
+      if (pm >= 0 && pn >= 0 && (int)reds.size() + first_real <= kTiledRed && (int)outers.size() <= kTiledOuter) {
+        tp.n_outer = (int)outers.size();
+        tp.n_cons = (int)fb.cons.size();
+        i128 items = 1;
+        for (int t = 0; t < kTiledOuter; ++t) tp.outer_range[t] = 1;
+        for (int t = 0; t < tp.n_outer; ++t) {
+          const int j = outers[t];
+          tp.outer_range[t] = (int32_t)fb.range[j];
+          tp.a_outer[t] = (int32_t)A.c[j]; tp.b_outer[t] = (int32_t)B->c[j]; tp.o_outer[t] = (int32_t)o.c[j];
+          for (int q = 0; q < tp.n_cons; ++q) tp.cons_outer[q][t] = (int32_t)fb.cons[q].c[j];
+          items *= fb.range[j];
+        }
+        tp.pm_range = (int32_t)fb.range[pm]; tp.pn_range = (int32_t)fb.range[pn];
+        tp.pm_blocks = (tp.pm_range + 3) / 4; tp.pn_blocks = (tp.pn_range + 3) / 4;
+        items *= (i128)tp.pm_blocks * tp.pn_blocks;
+        tp.a_pm = (int32_t)A.c[pm]; tp.o_pm = (int32_t)o.c[pm]; tp.b_pn = (int32_t)B->c[pn]; tp.o_pn = (int32_t)o.c[pn];
+        for (int q = 0; q < tp.n_cons; ++q) {
+          tp.cons_pm[q] = (int32_t)fb.cons[q].c[pm];
+          tp.cons_const[q] = (int32_t)fb.cons[q].k;
+        }
+        for (int t = 0; t < kTiledRed; ++t) tp.red_range[t] = 1;
+        for (size_t t = 0; t < reds.size(); ++t) {
+          const int j = reds[t], lvl = (int)t + first_real;
+          tp.red_range[lvl] = (int32_t)fb.range[j];
+          tp.a_red[lvl] = (int32_t)A.c[j]; tp.b_red[lvl] = (int32_t)B->c[j];
+          for (int q = 0; q < tp.n_cons; ++q) tp.cons_red[q][lvl] = (int32_t)fb.cons[q].c[j];
+        }
+        tp.a_base = (int32_t)A.k; tp.b_base = (int32_t)B->k; tp.o_base = (int32_t)o.k;
+        tp.n_items = (int64_t)items;
+        // four elements per load when the innermost reduction index is unit-stride in both operands and every
+        // other address term keeps 4-element alignment
+        bool vec = r0 >= 0 && A.c[r0] == 1 && B->c[r0] == 1 && fb.range[r0] % 4 == 0 && A.k % 4 == 0 && B->k % 4 == 0;
+        for (int j = 0; j < fb.n_idx && vec; ++j)
+          if (j != r0 && (A.c[j] % 4 || B->c[j] % 4)) vec = false;
+        tp.vec = vec ? 4 : 1;
+        // worth it only with enough lanes to fill the chip; small blocks stay on the wavefront-per-output mapping
+        tp.use = (items >= 16384 && items < ((i128)1 << 31)) ? 1 : 0;
+      }
+    }
   }
   if (path == STRIPE_PATH_GENERIC && !gen_ok) return bad(err, STRIPE_ERR_UNSUPPORTED, gen_why);
   if (!gen_ok) g.n_outputs = -1;  // marks "no generic fallback"

@@ -94,11 +94,34 @@ struct GenericParams {
   int32_t atomic, pad_;            // 1: output map not injective on the output indexes -> identity pass + atomic combine
 };
 
+// Parameters of the register-tiled generic contraction kernel: every lane owns a 4 x 4 patch of outputs
+// (4 values of one index that only the first operand and the output use, times 4 values of one index that only
+// the second operand and the output use) and walks the reduction indexes with up to four nested loops.
+constexpr int kTiledOuter = 6;
+constexpr int kTiledRed = 4;
+struct TiledParams {
+  int32_t use;                               // 0: this block runs on the plain generic kernel
+  int32_t vec;                               // 1 or 4: elements fetched per load along the innermost reduction index
+  int32_t n_outer, n_cons;
+  int32_t outer_range[kTiledOuter], a_outer[kTiledOuter], b_outer[kTiledOuter], o_outer[kTiledOuter];
+  int32_t cons_outer[kGenCons][kTiledOuter];
+  int32_t pm_range, pn_range, pm_blocks, pn_blocks;
+  int32_t a_pm, o_pm, b_pn, o_pn;
+  int32_t cons_pm[kGenCons];
+  int32_t red_range[kTiledRed], a_red[kTiledRed], b_red[kTiledRed];   // [0] innermost; no constraint depends on it
+  int32_t cons_red[kGenCons][kTiledRed];
+  int32_t cons_const[kGenCons];
+  int32_t a_base, b_base, o_base;
+  int32_t pad_;
+  int64_t n_items;                           // lanes: pn_blocks * pm_blocks * prod(outer_range)
+};
+
 struct Plan {
   FlatBlock flat;                  // canonical form
   stripe_block_info_t info = {};
   bool noop = false;               // empty iteration space: run() launches nothing
   GenericParams gen = {};
+  TiledParams tiled = {};
   GemmShape gemm = {};
   Conv2dShape conv = {};
   Pool2dShape pool = {};

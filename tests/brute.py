@@ -78,11 +78,14 @@ def evaluate(root, inputs, exact=lambda v: Fraction(v)):
 
 
 def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32", agg="add", intrinsic="mul",
-                 injective_out=False, max_range=4):
+                 injective_out=False, max_range=4, contraction_roles=False):
     """A random tiny block (every range <= 4, small integer coefficients).
 
     With injective_out every output dimension is moved by exactly one index
     (the shape the GPU library accepts without atomics).
+    With contraction_roles (needs injective_out and two inputs) every output index is given a role as in a
+    tensor contraction: it moves the first input only, the second input only, or both; the other indexes
+    are reduction indexes.  Coefficients, signs and constraints stay random.
     Accesses are made in-bounds by measuring, per buffer dimension, the
     extreme coordinates over the executed points and sizing/offsetting the
     root buffer to contain them.  Views of intermediate levels are sized the
@@ -106,10 +109,14 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
     if injective_out:
         cand = [(li, j) for li, (n_idx, _, _) in enumerate(shapes) for j in range(n_idx)]
         rng.shuffle(cand)
-        chosen = cand[:rng.randint(1, min(3, len(cand)))]
+        chosen = cand[:rng.randint(2 if (contraction_roles and len(cand) >= 2) else 1, min(3, len(cand)))]
         for d, key in enumerate(chosen):
             out_dim_of[key] = d
         ndims[n_in] = len(chosen)
+    role_of = {key: rng.choice(["first", "first", "second", "second", "both"]) for key in out_dim_of} if contraction_roles else {}
+    if contraction_roles and len(out_dim_of) >= 2:      # at least one index of each one-sided role
+        keys = list(out_dim_of)
+        role_of[keys[0]], role_of[keys[1]] = "first", "second"
 
     def rand_level(li, var_count):
         acc = [[[rng.randint(-1, 2) for _ in range(var_count)] for _ in range(nd)] for nd in ndims]
@@ -118,6 +125,11 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
             for (l2, j), d in out_dim_of.items():
                 if l2 == li:
                     acc[n_in][d][j] = rng.choice([1, 1, 2, -1])
+                    if contraction_roles and n_in == 2:
+                        silent = 1 if role_of[(l2, j)] == "first" else 0 if role_of[(l2, j)] == "second" else None
+                        if silent is not None:
+                            for row in acc[silent]:
+                                row[j] = 0
         return acc
 
     lv_specs = []
@@ -129,6 +141,11 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
         nv = n_idx + n_passed
         n_cons = rng.randint(0, 2)
         cons_coeff = [[rng.randint(-1, 1) for _ in range(nv)] for _ in range(n_cons)]
+        if contraction_roles:                           # keep the constraints off the second input's own indexes
+            for row in cons_coeff:
+                for (l2, j), role in role_of.items():
+                    if l2 == li and role == "second":
+                        row[j] = 0
         cons_const = [rng.randint(0, 3) for _ in range(n_cons)]
         lv_specs.append(dict(n_idx=n_idx, ranges=ranges, passed_coeff=passed_coeff, passed_const=passed_const,
                              cons_coeff=cons_coeff, cons_const=cons_const, acc=rand_level(li, nv)))
@@ -200,7 +217,7 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
                 in_lo[r][d] = inner if in_lo[r][d] is None else min(in_lo[r][d], inner)
                 in_hi[r][d] = inner if in_hi[r][d] is None else max(in_hi[r][d], inner)
     if not any_point:
-        return random_block(rng, nested, dtype_in, dtype_out, agg, intrinsic, injective_out, max_range)
+        return random_block(rng, nested, dtype_in, dtype_out, agg, intrinsic, injective_out, max_range, contraction_roles)
     if nested:
         # The inner level's constant places its coordinate at the start of the
         # outer level's view; the outer level's constant places the total

@@ -148,6 +148,71 @@ def test_generic_matmul_ragged(M, N, K, dtype):
     parity(blk, ins, "generic", what=f"generic matmul {dtype}")
 
 
+# ------------------------------------------------------------------ register-tiled generic contraction
+TILED_SEEN = []
+
+
+@pytest.mark.parametrize("seed", range(48))
+def test_tiled_generic_random_blocks(seed, monkeypatch):
+    """Random small (nested) integer sum-of-products blocks forced onto the 4 x 4 register-tiled kernel (it is
+    normally reserved for large blocks): ragged patches, negative strides, constraints on the blocked index,
+    untouched rows.  Bit-exact; blocks without the index roles the kernel needs stay on the plain kernel."""
+    monkeypatch.setenv("STRIPE_TUNE", "generic_tiled=2")
+    rng = random.Random(7000 + seed)
+    blk = brute.random_block(rng, seed % 4 == 3, "i32", "i32", "add", "mul", injective_out=True, max_range=9,
+                             contraction_roles=True)
+    nrng = np.random.default_rng(seed)
+    ins = [torch.from_numpy(nrng.integers(-3, 4, size=int(np.prod(r.sizes)), dtype=np.int32)) for r in blk.refs[:-1]]
+    try:
+        gpu, sb = run_gpu(blk, ins, "generic", return_block=True)
+    except B.StripeError as e:
+        assert e.status == 5, str(e)
+        pytest.skip(f"rejected at create: {e}")
+    TILED_SEEN.append(sb.info["kernel"].startswith("generic_tiled"))
+    res = O.evaluate(blk, [W.to_numpy(t) for t in ins], out=np.full(W.output_extent(blk), SENTINEL_I, np.int64))
+    assert np.array_equal(gpu.astype(np.int64), res.out), sb.info["kernel"]
+    say(f"seed {seed}: {sb.info['kernel']}")
+
+
+def test_tiled_generic_random_blocks_reached_the_tiled_kernel():
+    """Runs after the 48 cases above: a fair share of them must really have used the tiled kernel."""
+    assert len(TILED_SEEN) >= 40 and sum(TILED_SEEN) >= 15, (len(TILED_SEEN), sum(TILED_SEEN))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i8"])
+@pytest.mark.parametrize("shape", ["conv_ragged", "conv_vec", "matmul", "matmul_bt", "transposed_filter"])
+def test_tiled_generic_shapes(shape, dtype, monkeypatch):
+    """Convolutions (strided, asymmetric, padded), matmuls and a filter layout with k innermost on the tiled kernel,
+    with and without 4-element loads."""
+    monkeypatch.setenv("STRIPE_TUNE", "generic_tiled=2")
+    odt = "i32" if dtype == "i8" else "f32"
+    if shape == "conv_ragged":
+        N, H, Wd, Ci, Co, R, S, s, p = 2, 19, 13, 6, 10, 3, 5, 2, 2
+        blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, s, p, dtype, odt)
+        ins = [W.seeded_tensor((N, H, Wd, Ci), dtype, 0), W.seeded_tensor((R, S, Co, Ci), dtype, 1)]
+        want = "generic_tiled_4x4"
+    elif shape == "conv_vec":
+        N, H, Wd, Ci, Co, R, S, s, p = 1, 9, 11, 8, 7, 3, 3, 1, 1
+        blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, s, p, dtype, odt)
+        ins = [W.seeded_tensor((N, H, Wd, Ci), dtype, 0), W.seeded_tensor((R, S, Co, Ci), dtype, 1)]
+        want = "generic_tiled_4x4_v4"
+    elif shape == "matmul":
+        blk = W.matmul_block(70, 90, 52, dtype, odt)
+        ins = [W.seeded_tensor((70, 52), dtype, 0), W.seeded_tensor((52, 90), dtype, 1)]
+        want = "generic_tiled_4x4"
+    elif shape == "matmul_bt":
+        blk = W.matmul_block(33, 21, 64, dtype, odt, b_transposed=True)
+        ins = [W.seeded_tensor((33, 64), dtype, 0), W.seeded_tensor((21, 64), dtype, 1)]
+        want = "generic_tiled_4x4_v4"
+    else:
+        N, H, Wd, Ci, Co, R, S = 1, 9, 8, 5, 32, 3, 3
+        blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, 1, 1, dtype, odt, filter_layout="RSCK")
+        ins = [W.seeded_tensor((N, H, Wd, Ci), dtype, 0), W.seeded_tensor((R, S, Ci, Co), dtype, 1)]
+        want = "generic_tiled_4x4"
+    info, score = parity(blk, ins, "generic", what=f"tiled {shape} {dtype}")
+    assert info["kernel"] == want, info["kernel"]
+
+
 def test_product_aggregation_float():
     """O[a] = prod over r of (A[a, r] + B[r]) in fp32 against the fp64 oracle; and a shared-output form O[a + r]."""
     bufs = [W.Buffer("A", "in", "f32", (50, 9)), W.Buffer("B", "in", "f32", (9,)), W.Buffer("O", "out", "f32", (58,))]
@@ -453,6 +518,29 @@ def test_resnet_conv_config_full_size():
     cy = np.array([taps(y, 1, 1, 3, 56) for y in range(56)])
     want = 64.0 * cy[:, None] * cy[None, :]
     assert np.array_equal(gpu, np.broadcast_to(want[None, :, :, None], gpu.shape))
+
+
+def test_tiled_generic_at_full_size():
+    """The two convolution configurations on the register-tiled generic kernel (what a block gets when no
+    matrix-core family fits): all-ones closed form on every element, int8 bit-exact against the matrix-core result,
+    bf16 against an oracle window."""
+    name = "resnet_conv_bf16"
+    blk, ins = W.config_block(name), W.config_inputs(name)
+    ones = [torch.ones_like(ins[0]), torch.ones_like(ins[1])]
+    gpu, sb = run_gpu(blk, ones, "generic", return_block=True)
+    assert sb.info["kernel"] == "generic_tiled_4x4_v4", sb.info["kernel"]
+    cy = np.array([taps(y, 1, 1, 3, 56) for y in range(56)])
+    want = 64.0 * cy[:, None] * cy[None, :]
+    assert np.array_equal(gpu.reshape(32, 56, 56, 64), np.broadcast_to(want[None, :, :, None], (32, 56, 56, 64)))
+    gpu = run_gpu(blk, ins, "generic")
+    lo, hi = [13, 0, 50, 0, 0, 0, 0], [14, 56, 56, 3, 3, 64, 64]
+    res = O.evaluate(blk, [W.to_numpy(t).ravel() for t in ins], window=(lo, hi), threads=16, split_index=1)
+    compare(blk, ins, gpu, res, what="tiled generic resnet window")
+    name = "conv7x7_s2_int8"
+    blk, ins = W.config_block(name), W.config_inputs(name)
+    a, sb = run_gpu(blk, ins, "generic", return_block=True)
+    assert sb.info["kernel"] == "generic_tiled_4x4", sb.info["kernel"]
+    assert np.array_equal(a, run_gpu(blk, ins))
 
 
 def test_int8_conv_config_full_size():
