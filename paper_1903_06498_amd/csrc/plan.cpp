@@ -828,6 +828,10 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
       if (sa > 1 || sb > 1) lane_per_output_coalesces = false;
     }
     g.lanes = (!lane_per_output_coalesces && g.red_total >= 64) ? 64 : 1;
+    if (gen_ok && (g.lanes == 64 ? (outs + 3) / 4 : (outs + 255) / 256) > (i128)0x7fffffff) {
+      gen_ok = false;
+      gen_why = "more than 2^31 workgroups: split the block on an output index";
+    }
     // 32-bit index arithmetic when nothing the kernel computes can leave int32:
     // largest |offset| of each tensor, largest |value| of each constraint, the output count.
     auto reach = [&](const Affine& f) {

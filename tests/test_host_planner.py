@@ -123,6 +123,27 @@ def test_malformed_descriptors():
     assert B.stripe_status_string(4) == "access may leave its buffer or view"
 
 
+def test_very_large_blocks_plan_or_are_refused_cleanly():
+    """Sizes at and beyond the limits: no wrap-around in the planner's arithmetic, a status instead of a crash."""
+    big = W.matmul_block(65536, 65536, 65536, "bf16", "f32")          # 2^48 points, 8 GB operands: still a GEMM
+    info = B.StripeBlock(big).info
+    assert info["path_name"] == "mfma_gemm" and info["hull_points"] == 2 ** 48 and info["grid"] == 256 * 256
+    assert status_of(W.matmul_block(2 ** 21, 2 ** 21, 2 ** 21, "bf16", "f32")) == 3      # beyond 2^62 points
+    bufs = [W.Buffer("A", "in", "f32", (2 ** 17, 2 ** 16)), W.Buffer("O", "out", "f32", (2 ** 17, 2 ** 16))]
+    copy = W.flat_block(bufs, dict(a=2 ** 17, b=2 ** 16), [(["a", "b"], "assign"), (["a", "b"], "assign")], intrinsic="copy")
+    info = B.StripeBlock(copy).info                                    # offsets beyond 32 bits: the 64-bit kernel
+    assert info["kernel"] == "generic_affine_lane_per_output_i64" and info["grid"] == 2 ** 25
+    bufs = [W.Buffer("A", "in", "f32", (2 ** 20, 2 ** 20)), W.Buffer("O", "out", "f32", (2 ** 20, 2 ** 20))]
+    huge = W.flat_block(bufs, dict(a=2 ** 20, b=2 ** 20), [(["a", "b"], "assign"), (["a", "b"], "assign")], intrinsic="copy")
+    assert status_of(huge) == 3                                        # more workgroups than one launch can hold
+    one_index = W.flat_block([W.Buffer("A", "in", "f32", (2 ** 33,)), W.Buffer("O", "out", "f32", (2 ** 33,))], dict(x=2 ** 33),
+                             [(["x"], "assign"), (["x"], "assign")], intrinsic="copy")
+    assert status_of(one_index) == 2                                   # a single range is limited to 2^31 - 1
+    wide = W.maxpool_block(1, 3, 2 ** 30, 4, 3, 2, 1)                  # a row wider than the pooling kernels index
+    info = B.StripeBlock(wide).info
+    assert info["path_name"] == "generic" and info["work_points"] == -1    # too many points to count, reported as such
+
+
 def test_forcing_a_family_the_block_does_not_have_is_refused():
     assert status_of(W.config_block("maxpool_f32"), "mfma_gemm") == 3
     assert status_of(W.config_block("gemm_bf16_4096"), "pool") == 3
