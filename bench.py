@@ -25,7 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK = {"bf16_mfma_tflops": 2500.0, "int8_mfma_tops": 5000.0, "hbm_gbs": 8000.0}
+PEAK = {"bf16_mfma_tflops": 2500.0, "int8_mfma_tops": 5000.0, "hbm_gbs": 8000.0, "fp32_vector_tflops": 157.3}
 
 # Memory traffic per launch (bytes): FETCH_SIZE + WRITE_SIZE from the two rocprofv3 --pmc runs summarised under
 # profiles/<workload>.md, each scaled by what the same counter reads for the 64 MiB copy kernel (x2.0 and x1.0).
@@ -46,6 +46,12 @@ KIND = {
     "tiny_conv_f32": ("TFLOP/s", "hbm", "f32"),
     "device_copy": ("GB/s", "hbm", "u8"),     # the plain copy kernel: calibrates traffic counters and the HBM yardstick
     "library_gemm": ("TFLOP/s", "mfma", "bf16"),  # torch.mm (the vendor BLAS) on the GEMM workload's operands: a yardstick
+    # further shapes the kernel families cover (workloads.extra_block)
+    "gemm_bf16_4096_bt": ("TFLOP/s", "mfma", "bf16"),
+    "gemm_bf16_4000_ragged": ("TFLOP/s", "mfma", "bf16"),
+    "gemm_i8_4096_bt": ("TOP/s", "mfma", "int8"),
+    "pointwise_conv_bf16": ("TFLOP/s", "hbm", "bf16"),
+    "transposed_conv_f32": ("TFLOP/s", "alu", "f32"),
 }
 
 
@@ -174,8 +180,11 @@ def main():
         return bench_copy(args, torch, B)
     if name == "library_gemm":
         return bench_library_gemm(args, torch, W)
-    root = W.config_block(name)
-    inputs = W.config_inputs(name)
+    extra = name in W.EXTRA_NAMES
+    root = W.extra_block(name) if extra else W.config_block(name)
+    inputs = W.extra_inputs(name) if extra else W.config_inputs(name)
+    if extra:
+        args.cpu_baseline = 0        # the oracle is timed on the five configurations only
     blk = B.StripeBlock(root, args.path)
     info = blk.info
     ext = W.output_extent(root)
@@ -184,7 +193,7 @@ def main():
     set_bytes = sum(t.numel() * t.element_size() for t in inputs) + ext * 4
     n_sets = args.rotate
     if n_sets < 1:
-        n_sets = 1 if bound == "mfma" else max(2, int(640e6 // set_bytes) + 1)
+        n_sets = 1 if bound in ("mfma", "alu") else max(2, int(640e6 // set_bytes) + 1)
     sets = []
     for _ in range(n_sets):
         sets.append(([fill_like(t.to(dev), args.fill) for t in inputs], torch.zeros(ext, dtype=odt, device=dev)))
@@ -218,10 +227,10 @@ def main():
         value = nbytes / (ms_per_step * 1e-3) / 1e9
     else:
         value = flops / (ms_per_step * 1e-3) / 1e12
-    if bound == "mfma":
-        peak = PEAK["int8_mfma_tops"] if dtype == "int8" else PEAK["bf16_mfma_tflops"]
+    if bound in ("mfma", "alu"):
+        peak = PEAK["fp32_vector_tflops"] if bound == "alu" else PEAK["int8_mfma_tops"] if dtype == "int8" else PEAK["bf16_mfma_tflops"]
         achieved = flops / kernel_s / 1e12
-        roof = {"bound": "mfma", "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
+        roof = {"bound": bound, "achieved": round(achieved, 2), "peak": peak, "unit": "TFLOP/s",
                 "frac": round(achieved / peak, 4), "traffic": traffic}
     else:
         achieved = nbytes / kernel_s / 1e9

@@ -305,6 +305,36 @@ def config_block(name: str) -> Block:
     raise KeyError(name)
 
 
+# Further shapes the kernel families cover, for measurements beyond the five configurations (bench.py --workload).
+EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32")
+
+
+def extra_block(name: str) -> Block:
+    if name == "gemm_bf16_4096_bt":
+        return matmul_block(4096, 4096, 4096, "bf16", "f32", b_transposed=True)
+    if name == "gemm_bf16_4000_ragged":
+        return matmul_block(4000, 4000, 4096, "bf16", "f32")
+    if name == "gemm_i8_4096_bt":
+        return matmul_block(4096, 4096, 4096, "i8", "i32", b_transposed=True)
+    if name == "pointwise_conv_bf16":          # 1x1 convolution, 256 -> 64 channels on the ResNet block's 32 x 56 x 56 pixels
+        bufs = [Buffer("I", "in", "bf16", (32, 56, 56, 256)), Buffer("F", "in", "bf16", (64, 256)),
+                Buffer("O", "out", "f32", (32, 56, 56, 64))]
+        return flat_block(bufs, dict(n=32, y=56, x=56, c=256, k=64),
+                          [(["n", "y", "x", "c"], "assign"), (["k", "c"], "assign"), (["n", "y", "x", "k"], "add")], intrinsic="mul")
+    if name == "transposed_conv_f32":          # stride-2 transposed 3x3 convolution: output elements shared between index tuples
+        bufs = [Buffer("I", "in", "f32", (8, 28, 28, 32)), Buffer("F", "in", "f32", (3, 3, 32, 32)),
+                Buffer("O", "out", "f32", (8, 57, 57, 32))]
+        return flat_block(bufs, dict(n=8, y=28, x=28, i=3, j=3, c=32, k=32),
+                          [(["n", "y", "x", "c"], "assign"), (["i", "j", "c", "k"], "assign"),
+                           (["n", "2*y + i", "2*x + j", "k"], "add")], intrinsic="mul")
+    raise KeyError(name)
+
+
+def extra_inputs(name: str):
+    blk = extra_block(name)
+    return [seeded_tensor(r.sizes, r.dtype, seed) for seed, r in enumerate(blk.refs[:-1])]
+
+
 def config_inputs(name: str):
     """Seeded torch CPU tensors for a configuration: seed 0 for the first
     tensor, seed 1 for the second; bf16 by round-to-nearest-even of the fp32 draw."""
