@@ -166,9 +166,25 @@ constexpr int W4_ROWS = 7;
 // TEAMS: 1 = four wavefronts, each walks the three row groups; 2 = eight wavefronts, two per SIMD: team 0
 // computes rows 0-1 then 2-3, team 1 rows 4-6, so that one wavefront's store phase (LDS transposition, address
 // arithmetic, stores) runs while the other keeps the SIMD's matrix pipe busy.
-template <int TEAMS>
+// Source of the halo: lanes whose pixel lies outside the image fetch these 16 zero bytes instead.
+__device__ __attribute__((aligned(16))) unsigned char conv_zero_chunk[16];
+
+// LDS-direct 16-byte load: lane i of the wavefront lands at lds_off + 16*i (M0 carries the wave-uniform offset).
+// Written as assembly so that the compiler does not drain the load queue before unrelated LDS reads; the waits
+// are placed by hand (s_waitcnt vmcnt) where the data is first needed.
+__device__ __forceinline__ void c_load_lds16(const void* src, unsigned lds_off) {
+  const unsigned uniform_off = __builtin_amdgcn_readfirstlane(lds_off);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform_off) : "memory", "m0");
+}
+
+// DMA (needs TEAMS == 2): the strip's rows and the filter go global -> LDS with LDS-direct loads instead of
+// through registers, the filter in three slices ordered by filter column j.  The first row group of each team
+// starts as soon as the rows and the first slice have landed and meets the other two slices on the way, so the
+// first stores leave earlier; no LDS-store instructions and no staging registers are spent.
+template <int TEAMS, bool DMA = false>
 __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const ConvParams p, const uint16_t* __restrict__ I,
                                                                         const uint16_t* __restrict__ F, float* __restrict__ O) {
+  static_assert(!DMA || TEAMS == 2, "the LDS-direct staging is written for eight wavefronts");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   unsigned char* lf = lds;
   unsigned char* lp = lds + C_FILTER_BYTES;
@@ -177,6 +193,39 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   const int y0 = (blockIdx.x - n * p.strips_per_image) * W4_ROWS;
   const int PW = p.W + 2;
   constexpr int PR = W4_ROWS + 2;
+  // bytes of the patch image rounded up to whole 1 KB load blocks (DMA); the output transposition buffers follow
+  const int patch_bytes = DMA ? ((PR * PW * 128 + 1023) & ~1023) : PR * PW * 128;
+  if constexpr (DMA) {
+    // ---- staging by LDS-direct loads: 9 patch blocks, then 3 filter blocks per slice, per wavefront (18 loads)
+    const int sub = lane >> 3, slot = lane & 7;
+    const char* ig = (const char*)(I + p.i_base + (int64_t)n * p.i_n);
+    const int n_blocks = patch_bytes >> 10;
+#pragma unroll
+    for (int e = 0; e < 9; ++e) {
+      const int b = wave + 8 * e;                     // block b = LDS pixels 8b .. 8b+7
+      const int pix = b * 8 + sub;
+      const int r = (int)__umulhi((unsigned)pix, (unsigned)p.pad_), col = pix - r * PW;   // pad_ carries ceil(2^32 / PW)
+      const int y = y0 - 1 + r, x = col - 1;
+      const int c = slot ^ ((pix >> 1) & 7);
+      const bool inside = r < PR && y >= 0 && y < p.H && x >= 0 && x < p.W;
+      const void* src = inside ? (const void*)(ig + (uint32_t)(y * (int)p.i_y + x * (int)p.i_x + c * 8) * 2u) : (const void*)conv_zero_chunk;
+      // blocks past the patch (a wavefront issues 9 loads whatever the width, so that the wait counts are the same
+      // for all) land in the output transposition area, which nothing reads before it is rewritten
+      const unsigned dst = C_FILTER_BYTES + (b < n_blocks ? b * 1024 : patch_bytes + wave * 1024);
+      c_load_lds16(b < n_blocks ? src : (const void*)conv_zero_chunk, dst);
+    }
+    const char* fgb = (const char*)(F + p.f_base);
+#pragma unroll
+    for (int tj = 0; tj < 3; ++tj)
+#pragma unroll
+      for (int ti = 0; ti < 3; ++ti) {
+        const int row = (ti * 3 + tj) * C_CO + wave * 8 + sub;     // filter row (tap, k)
+        const int c = slot ^ ((row >> 1) & 7);
+        c_load_lds16(fgb + (row * C_CI + c * 8) * 2, ((ti * 3 + tj) * C_CO + wave * 8) * 128);
+      }
+    asm volatile("s_waitcnt vmcnt(6)" ::: "memory");   // the wavefront's patch blocks and its share of slice 0
+    __syncthreads();
+  } else {
 
   // ---- staging.  Every global load of the lane is in flight before the first LDS store.
   // A lane keeps its 16-byte chunk index c = t&7 and walks pixels: filter rows (t>>3) + 32u (its LDS swizzle
@@ -228,6 +277,7 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
     }
   }
   __syncthreads();
+  }
 
   // ---- compute: wavefront = (pixel half mh, channel half nh), 7 rows
   const int team = wave >> 2, mh = (wave >> 1) & 1, nh = wave & 1;
@@ -241,7 +291,7 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   // ([pixel][32 channels], behind the patch) and leaves as 16-byte stores: 8 lanes write the 128 contiguous
   // bytes of a pixel's channel half.
   constexpr int OT_BYTES = 4096 / TEAMS, OT_PIXELS = 32 / TEAMS;    // a fragment leaves in TEAMS rounds of OT_PIXELS pixels
-  unsigned char* ot = lp + PR * PW * 128 + wave * OT_BYTES;
+  unsigned char* ot = lp + patch_bytes + wave * OT_BYTES;
   const int sp = lane >> 3, sc = lane & 7;          // store phase: pixel sp (+8j) of the fragment, channel quad sc
   char* og = (char*)(O + p.o_base + (int64_t)n * p.o_n) + (nh * 32 + sc * 4) * 4;
   unsigned char* wbase[4];     // write address of accumulator elements v = 0..3 (pixel 4*fh + v); + 1 KB per further 8 pixels
@@ -264,8 +314,9 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   // column j and one 16-channel K step need the n+2 pixel fragments of the group's input rows (read once, used
   // by the three filter rows i: output row r takes input row r+i) and 3 filter fragments for 3n matrix
   // instructions; the fragments of the next (j, K step) are requested before the current ones are consumed.
-  auto row_group = [&](auto r0_tag, auto n_tag) {
+  auto row_group = [&](auto r0_tag, auto n_tag, auto first_tag) {
     constexpr int R0 = decltype(r0_tag)::value, NR = decltype(n_tag)::value;
+    constexpr bool MEET_SLICES = DMA && decltype(first_tag)::value;   // first group of a team under DMA staging
     f32x16 acc[NR];
 #pragma unroll
     for (int r = 0; r < NR; ++r)
@@ -294,7 +345,14 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
       const int cur = it & 1;
       __builtin_amdgcn_sched_barrier(0);
       if (it + 1 < 12) {
-        if (((it + 1) & 3) == 0) set_bases((it + 1) >> 2);
+        if (((it + 1) & 3) == 0) {
+          if constexpr (MEET_SLICES) {   // the next filter column's slice: this wavefront's share, then everybody's
+            if (it + 1 == 4) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+          }
+          set_bases((it + 1) >> 2);
+        }
         read_frags(cur ^ 1, (it + 1) >> 2, (it + 1) & 3);
       }
 #pragma unroll
@@ -326,16 +384,18 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
       }
     }
   };
+  constexpr std::true_type first{};
+  constexpr std::false_type later{};
   if constexpr (TEAMS == 1) {
-    row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{});
-    row_group(std::integral_constant<int, 3>{}, std::integral_constant<int, 2>{});
-    row_group(std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{});
+    row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 3>{}, first);
+    row_group(std::integral_constant<int, 3>{}, std::integral_constant<int, 2>{}, later);
+    row_group(std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{}, later);
   } else if (team == 0) {   // a single row first: the sooner the first stores leave, the sooner the write stream starts
-    row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{});
-    row_group(std::integral_constant<int, 1>{}, std::integral_constant<int, 3>{});
+    row_group(std::integral_constant<int, 0>{}, std::integral_constant<int, 1>{}, first);
+    row_group(std::integral_constant<int, 1>{}, std::integral_constant<int, 3>{}, later);
   } else {
-    row_group(std::integral_constant<int, 4>{}, std::integral_constant<int, 1>{});
-    row_group(std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{});
+    row_group(std::integral_constant<int, 4>{}, std::integral_constant<int, 1>{}, first);
+    row_group(std::integral_constant<int, 5>{}, std::integral_constant<int, 2>{}, later);
   }
 }
 
@@ -379,12 +439,14 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
   // four-wavefront kernel: strips of 7 rows, 32-bit element offsets inside an image
   const bool offsets_fit = c.i_y >= 0 && c.i_x >= 0 && c.o_x >= 0 && (c.H * c.i_y + c.W * c.i_x + 64) < ((int64_t)1 << 30) &&
                            (c.W * c.o_x + 64) < ((int64_t)1 << 30);
-  const int w4_lds = C_FILTER_BYTES + (W4_ROWS + 2) * ((int)c.W + 2) * 128 + W4_LDS_EXTRA;
+  int w4_lds = C_FILTER_BYTES + (W4_ROWS + 2) * ((int)c.W + 2) * 128 + W4_LDS_EXTRA;
   const int w4_teams = tune_int("conv_w4_teams", 2) == 1 ? 1 : 2;
+  const bool w4_dma = w4_teams == 2 && tune_int("conv_dma", 1) != 0;
+  if (w4_dma) w4_lds = C_FILTER_BYTES + (((W4_ROWS + 2) * ((int)c.W + 2) * 128 + 1023) & ~1023) + W4_LDS_EXTRA;
   if (tune_int("conv_w4", 1) && offsets_fit && w4_lds <= 160 * 1024 && (c.W + 2) * 8 <= 512) {
     const int64_t grid = c.N * ((c.Ho + W4_ROWS - 1) / W4_ROWS);
     if (grid > 0x7fffffffLL) return false;
-    l->variant = kConvW4Variant + w4_teams;
+    l->variant = kConvW4Variant + (w4_dma ? 3 : w4_teams);
     l->grid = grid;
     info->path = STRIPE_PATH_MFMA_CONV;
     info->tile_m = W4_ROWS * (int)c.W;
@@ -394,7 +456,7 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
     info->lds_bytes = w4_lds;
     info->workgroup_size = 256 * w4_teams;
     info->grid = grid;
-    snprintf(info->kernel, sizeof info->kernel, "conv3x3_bf16_c64k64_strip7_w%d_mfma32x32x16", 4 * w4_teams);
+    snprintf(info->kernel, sizeof info->kernel, "conv3x3_bf16_c64k64_strip7_w%d%s_mfma32x32x16", 4 * w4_teams, w4_dma ? "_dma" : "");
     return true;
   }
   const int rows = rows_per_strip(c);
@@ -421,24 +483,25 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
   if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
   if (l.variant > kConvW4Variant) {
-    const bool two = l.variant == kConvW4Variant + 2;
-    const ConvParams pp = make_params(c, W4_ROWS);
-    const int lds_w4 = C_FILTER_BYTES + (W4_ROWS + 2) * ((int)c.W + 2) * 128 + W4_LDS_EXTRA;
-    const void* fn = two ? (const void*)conv3x3_bf16_w4_kernel<2> : (const void*)conv3x3_bf16_w4_kernel<1>;
+    const int mode = l.variant - kConvW4Variant;   // 1: four wavefronts, 2: eight, 3: eight with LDS-direct staging
+    ConvParams pp = make_params(c, W4_ROWS);
+    const uint32_t pw = (uint32_t)c.W + 2;
+    pp.pad_ = (int32_t)(uint32_t)((((uint64_t)1 << 32) + pw - 1) / pw);   // reciprocal of the patch width, for the LDS-direct staging
+    const int patch = (W4_ROWS + 2) * ((int)c.W + 2) * 128;
+    const int lds_w4 = C_FILTER_BYTES + (mode == 3 ? ((patch + 1023) & ~1023) : patch) + W4_LDS_EXTRA;
+    typedef void (*kern_t)(const ConvParams, const uint16_t*, const uint16_t*, float*);
+    const kern_t fn = mode == 3 ? (kern_t)conv3x3_bf16_w4_kernel<2, true> : mode == 2 ? (kern_t)conv3x3_bf16_w4_kernel<2, false>
+                                                                                      : (kern_t)conv3x3_bf16_w4_kernel<1, false>;
     int dev4 = -1;
     hipError_t e4 = hipGetDevice(&dev4);
     if (e4 != hipSuccess) return e4;
     if (dev4 != l.lds_enabled_on) {
-      e4 = hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+      e4 = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
       if (e4 != hipSuccess) return e4;
       l.lds_enabled_on = dev4;
     }
-    if (two)
-      hipLaunchKernelGGL(conv3x3_bf16_w4_kernel<2>, dim3((unsigned)l.grid), dim3(512), lds_w4, st, pp, (const uint16_t*)in,
-                         (const uint16_t*)flt, (float*)out);
-    else
-      hipLaunchKernelGGL(conv3x3_bf16_w4_kernel<1>, dim3((unsigned)l.grid), dim3(256), lds_w4, st, pp, (const uint16_t*)in,
-                         (const uint16_t*)flt, (float*)out);
+    hipLaunchKernelGGL(fn, dim3((unsigned)l.grid), dim3(mode == 1 ? 256 : 512), lds_w4, st, pp, (const uint16_t*)in,
+                       (const uint16_t*)flt, (float*)out);
     return hipGetLastError();
   }
   const int rows = l.variant;

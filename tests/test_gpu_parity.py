@@ -439,25 +439,29 @@ def test_gemm_config_full_size():
 
 
 # ------------------------------------------------------------------ convolution path (matrix cores)
-@pytest.mark.parametrize("w4", [2, 1, 0])
-@pytest.mark.parametrize("N,H,Wd", [(2, 10, 13), (1, 7, 56), (3, 20, 64), (1, 2, 2), (2, 9, 33), (1, 15, 31), (2, 11, 58)])
+@pytest.mark.parametrize("w4", [3, 2, 1, 0])
+@pytest.mark.parametrize("N,H,Wd", [(2, 10, 13), (1, 7, 56), (3, 20, 64), (1, 2, 2), (2, 9, 33), (1, 15, 31), (2, 11, 58), (1, 8, 62)])
 def test_conv_mfma_bf16_small(N, H, Wd, w4, monkeypatch):
     """3x3, 64 -> 64 channels, 'same' padding: ragged strips, both pixel fragments, halo on all four sides;
-    the row-group kernel with two teams of wavefronts (default) and with one, and the wavefront-per-row kernel."""
-    monkeypatch.setenv("STRIPE_TUNE", f"conv_w4={min(w4, 1)},conv_w4_teams={max(w4, 1)}")
+    the row-group kernel with LDS-direct staging (3, the default), with register staging and two teams of wavefronts
+    (2) or one (1), and the wavefront-per-row kernel (0)."""
+    monkeypatch.setenv("STRIPE_TUNE", f"conv_w4={min(w4, 1)},conv_w4_teams={min(max(w4, 1), 2)},conv_dma={int(w4 == 3)}")
     blk = W.conv2d_block(N, H, Wd, 64, 64, 3, 3, 1, 1, "bf16", "f32")
     ins = [W.seeded_tensor((N, H, Wd, 64), "bf16", 0), W.seeded_tensor((3, 3, 64, 64), "bf16", 1)]
     info, score = parity(blk, ins, what=f"conv mfma {N}x{H}x{Wd}")
     say(f"conv mfma {N}x{H}x{Wd}: {info['kernel']} err/bound {score:.3f}")
-    fits = 73728 + 9 * (Wd + 2) * 128 + 16384 <= 160 * 1024      # filter + haloed strip + store buffers in LDS
-    want = f"_w{4 * w4}_" if (w4 and fits) else "_strip7_mfma"
+    patch = 9 * (Wd + 2) * 128
+    if w4 == 3:
+        patch = (patch + 1023) // 1024 * 1024                    # whole 1 KB load blocks
+    fits = 73728 + patch + 16384 <= 160 * 1024                   # filter + haloed strip + store buffers in LDS
+    want = (f"_w{4 * min(w4, 2)}_" + ("dma_" if w4 == 3 else "mfma")) if (w4 and fits) else "_strip7_mfma"
     assert info["path_name"] == "mfma_conv" and want in info["kernel"], info
 
 
-@pytest.mark.parametrize("w4", [2, 1, 0])
+@pytest.mark.parametrize("w4", [3, 2, 1, 0])
 def test_conv_mfma_position_sensitive(w4, monkeypatch):
     """Delta input: the output is the (flipped) filter patch, exactly -- catches any mix-up of taps, pixels or channels."""
-    monkeypatch.setenv("STRIPE_TUNE", f"conv_w4={min(w4, 1)},conv_w4_teams={max(w4, 1)}")
+    monkeypatch.setenv("STRIPE_TUNE", f"conv_w4={min(w4, 1)},conv_w4_teams={min(max(w4, 1), 2)},conv_dma={int(w4 == 3)}")
     N, H, Wd = 1, 9, 40
     blk = W.conv2d_block(N, H, Wd, 64, 64, 3, 3, 1, 1, "bf16", "f32")
     f = W.seeded_tensor((3, 3, 64, 64), "bf16", 1)
