@@ -9,14 +9,22 @@
 // (Section 2.3, "Separating Interior and Boundary Tiles").
 //
 // Nesting (Section 3.1.3), mapped by hand:
-//   outer block  -> one workgroup per strip of ROWS output rows of one image,
-//   middle block -> the strip's ROWS+2 input rows (with halo) and the whole
-//                   3x3x64x64 filter, staged once in LDS (about 139 KB of 160 KB),
-//   inner block  -> one wavefront per output row: 2 pixel fragments x 2 channel
-//                   fragments of v_mfma_f32_32x32x16_bf16, 36 K steps (9 taps x 64 channels).
+//   outer block  -> one workgroup per strip of 7 output rows of one image,
+//   middle block -> the strip's 9 input rows (with halo) and the whole
+//                   3x3x64x64 filter in LDS (about 139 KB of 160 KB),
+//   inner block  -> 32 x 32 fragments of v_mfma_f32_32x32x16_bf16, 36 K steps
+//                   (9 taps x 64 channels) per fragment.
 // Both LDS arrays hold 128-byte rows (one pixel or one filter row = 64 channels)
 // with the 16-byte chunks XOR-swizzled by (row>>1)&7, so the 16-byte fragment
 // reads of 32 consecutive pixels / filter rows are bank-conflict free.
+//
+// Two kernels, in this order in the file:
+//   conv3x3_bf16_kernel     one wavefront per output row (2 x 2 fragments), staged through registers;
+//                           the fallback for widths whose buffers leave no room for the second kernel's;
+//   conv3x3_bf16_w4_kernel  the default: wavefront = (pixel half, channel half), rows taken in groups so that
+//                           pixel fragments are shared between filter rows and finished rows are stored while
+//                           others are computed; one or two teams of four wavefronts; staging through registers
+//                           or by LDS-direct loads that the first row group meets on the way.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -148,24 +156,25 @@ __global__ __launch_bounds__(C_MAX_ROWS * 64) void conv3x3_bf16_kernel(const Con
 }
 
 // ---------------------------------------------------------------------------
-// Four-wavefront variant: the same LDS images (filter + haloed strip of 7
-// output rows), but the strip's 7 x 2 x 2 output fragments are divided so that
-// every SIMD carries the same number of matrix instructions: wavefront w owns
-// pixel half w>>1 and channel half w&1 of all 7 rows (7 accumulator
-// fragments).  For one filter column j and one 16-channel K step the 9 pixel
-// fragments of the strip's 9 input rows are read once and serve the three
-// filter rows i (output row r uses input row r+i), so a wavefront issues 12
-// LDS fragment reads per 21 matrix instructions instead of 21 + 21.  Reads of
-// the next (j, K step) are issued before the matrix instructions of the
+// Row-group kernel: the same LDS images (filter + haloed strip of 7 output
+// rows), but the strip's 7 x 2 x 2 output fragments are divided so that every
+// SIMD carries the same number of matrix instructions: a wavefront owns one
+// pixel half and one channel half (one 32 x 32 fragment per output row).
+// Rows are taken in groups; within a group of n rows, one filter column j and
+// one 16-channel K step need the n+2 pixel fragments of the group's input
+// rows, read once and used by the three filter rows i (output row r uses
+// input row r+i), plus 3 filter fragments, for 3n matrix instructions.  Reads
+// of the next (j, K step) are issued before the matrix instructions of the
 // current one.  Staging index arithmetic is 32-bit with a reciprocal multiply
 // for the division by the patch width: at ~13 us per launch the integer work
-// of 35 staged chunks per lane is not free.
+// of the staged chunks is not free.
 // ---------------------------------------------------------------------------
 constexpr int W4_ROWS = 7;
 
-// TEAMS: 1 = four wavefronts, each walks the three row groups; 2 = eight wavefronts, two per SIMD: team 0
-// computes rows 0-1 then 2-3, team 1 rows 4-6, so that one wavefront's store phase (LDS transposition, address
-// arithmetic, stores) runs while the other keeps the SIMD's matrix pipe busy.
+// TEAMS: 1 = four wavefronts, each walks three row groups (3 + 2 + 2 rows); 2 = eight wavefronts, two per SIMD:
+// team 0 computes row 0, then rows 1-3, team 1 row 4, then rows 5-6, so that one wavefront's store phase (LDS
+// transposition, address arithmetic, stores) runs while the other keeps the SIMD's matrix pipe busy, and the
+// first stores leave after a single row's worth of matrix work.
 // Source of the halo: lanes whose pixel lies outside the image fetch these 16 zero bytes instead.
 __device__ __attribute__((aligned(16))) unsigned char conv_zero_chunk[16];
 

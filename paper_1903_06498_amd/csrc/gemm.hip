@@ -3,14 +3,17 @@
 //
 // The three nesting levels of the Stripe block (paper Section 3.1.3; Figure 3's
 // columns) are mapped by hand:
-//   outer block  -> one workgroup per BM x BN tile of C (XCD-aware tile order),
-//   middle block -> K tiles of BK staged in LDS, double-buffered,
-//   inner block  -> v_mfma_f32_32x32x16_bf16 fragments, 4 x 2 per wavefront.
-// The "microarchitectural transposition" the matrix core needs (Section 2.3) is
-// done on the way into LDS: both operands are stored K-contiguous per row
-// (A as [m][k], B transposed to [n][k]) in 128-byte rows whose 16-byte chunks
-// are XOR-swizzled with the row number, so fragment reads (16 bytes per lane)
-// spread over all banks.
+//   outer block  -> one workgroup per 256 x 256 tile of C (XCD-aware tile order),
+//   middle block -> K tiles staged in LDS (ring of 2 or 4 stages),
+//   inner block  -> v_mfma_f32_32x32x16_bf16 fragments (v_mfma_i32_32x32x32_i8 in the int8 mode).
+// Three kernels, in this order in the file:
+//   gemm_bf16_w8_kernel   8 wavefronts, operands staged through registers, B transposed on the way into LDS
+//                         (the "microarchitectural transposition" of Section 2.3), K tiles of 64;
+//   gemm_bf16_w4_kernel   4 wavefronts of 128 x 128, same staging, deeper software pipeline;
+//   gemm_bf16_dma_kernel  the default: LDS-direct loads into a four-stage ring, B kept [k][n] and read with the
+//                         transposing LDS read; template modes for a transposed B, ragged M/N and int8.
+// All LDS tiles hold K-contiguous rows whose 16-byte chunks are XOR-swizzled with the row number, so fragment
+// reads (16 bytes per lane) spread over all banks.
 #include <hip/hip_runtime.h>
 
 #include "kernels.hpp"

@@ -659,7 +659,7 @@ bool match_conv2d(const FlatBlock& fb, Conv2dShape* c) {
 
 bool match_pool2d(const FlatBlock& fb, Pool2dShape* p) {
   if (fb.empty || fb.n_refs != 2 || fb.intrinsic != STRIPE_INTR_COPY) return false;
-  if (fb.agg != STRIPE_AGG_MAX && fb.agg != STRIPE_AGG_MIN) return false;
+  if (fb.agg != STRIPE_AGG_MAX && fb.agg != STRIPE_AGG_MIN && fb.agg != STRIPE_AGG_ADD) return false;
   const FlatRef &I = fb.ref[0], &O = fb.ref[1];
   Window2d w;
   if (!match_window(fb, I, O.addr, &w)) return false;
@@ -678,7 +678,7 @@ bool match_pool2d(const FlatBlock& fb, Pool2dShape* p) {
   p->o_n = w.n >= 0 ? O.addr.c[w.n] : 0; p->o_y = O.addr.c[w.y]; p->o_x = O.addr.c[w.x]; p->o_c = O.addr.c[w.c];
   p->i_base = I.addr.k + w.py * w.st_y + w.px * w.st_x;
   p->o_base = O.addr.k;
-  p->is_min = fb.agg == STRIPE_AGG_MIN;
+  p->agg = fb.agg;
   return true;
 }
 

@@ -74,7 +74,7 @@ struct Pool2dShape {     // O[n,y,x,c] = agg over in-bounds taps of I[n, s*y+i-p
   int64_t stride_y, stride_x, pad_y, pad_x;
   int64_t i_n, i_y, i_x, i_c, o_n, o_y, o_x, o_c;
   int64_t i_base, o_base;
-  int is_min;              // aggregation is min instead of max
+  int agg;                 // STRIPE_AGG_MAX, _MIN or _ADD (sum pooling)
 };
 
 // Parameters of the generic affine-index kernel (passed by value as kernel argument).

@@ -227,22 +227,26 @@ __global__ __launch_bounds__(512) void pool_max_f32_roll_kernel(const PoolParams
 // 128 lanes own 128 (column, channel-quad) items and TY output rows, and all
 // loads of the strip are issued before the first reduction.  Window R x S,
 // stride ST, max or min (both idempotent, which the clamped duplicates need).
-template <bool MIN>
-__device__ __forceinline__ float pick(float a, float b) { return MIN ? __builtin_fminf(a, b) : __builtin_fmaxf(a, b); }
-template <int N, bool MIN>
+// MODE: 0 max, 1 min, 2 sum.  A sum is not idempotent, so there the taps outside the image are replaced by zeros
+// (exact for a sum) instead of being left as clamped duplicates.
+template <int MODE>
+__device__ __forceinline__ float pick(float a, float b) {
+  return MODE == 2 ? a + b : MODE == 1 ? __builtin_fminf(a, b) : __builtin_fmaxf(a, b);
+}
+template <int N, int MODE>
 __device__ __forceinline__ f32x4 fold(const f32x4* v) {
   f32x4 r = v[0];
 #pragma unroll
   for (int i = 1; i < N; ++i) {
-    r.x = pick<MIN>(r.x, v[i].x);
-    r.y = pick<MIN>(r.y, v[i].y);
-    r.z = pick<MIN>(r.z, v[i].z);
-    r.w = pick<MIN>(r.w, v[i].w);
+    r.x = pick<MODE>(r.x, v[i].x);
+    r.y = pick<MODE>(r.y, v[i].y);
+    r.z = pick<MODE>(r.z, v[i].z);
+    r.w = pick<MODE>(r.w, v[i].w);
   }
   return r;
 }
 
-template <int R, int S, int ST, int TY, bool MIN>
+template <int R, int S, int ST, int TY, int MODE>
 __global__ __launch_bounds__(128) void pool_f32_strip_kernel(const PoolParams p, const float* __restrict__ in,
                                                             float* __restrict__ out) {
   constexpr int NR = ST * (TY - 1) + R;
@@ -256,10 +260,12 @@ __global__ __launch_bounds__(128) void pool_f32_strip_kernel(const PoolParams p,
   const int c4 = item % p.C4;
   const int xo = item / p.C4;
   uint32_t voff[S];
+  bool xv[S];
 #pragma unroll
   for (int j = 0; j < S; ++j) {
     const int xc = xo * ST - p.pad_x + j;
     const int xcl = xc < 0 ? 0 : (xc >= p.W ? p.W - 1 : xc);
+    xv[j] = xc == xcl;
     voff[j] = ((uint32_t)xcl * (uint32_t)p.i_x + (uint32_t)c4 * 4u) * 4u;
   }
   const uint32_t ooff = ((uint32_t)xo * (uint32_t)p.o_x + (uint32_t)c4 * 4u) * 4u;
@@ -279,11 +285,20 @@ __global__ __launch_bounds__(128) void pool_f32_strip_kernel(const PoolParams p,
   }
   f32x4 hm[NR];
 #pragma unroll
-  for (int r = 0; r < NR; ++r) hm[r] = fold<S, MIN>(v[r]);
+  for (int r = 0; r < NR; ++r) {
+    if constexpr (MODE == 2) {
+      const int y = y0 + r;
+      const bool yv = y >= 0 && y < p.H;
+      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < S; ++j) v[r][j] = (yv && xv[j]) ? v[r][j] : zero;
+    }
+    hm[r] = fold<S, MODE>(v[r]);
+  }
 #pragma unroll
   for (int ty = 0; ty < TY; ++ty) {
     const int yo = yo0 + ty;
-    if (yo < p.Ho) *(f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff) = fold<R, MIN>(hm + ty * ST);
+    if (yo < p.Ho) *(f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff) = fold<R, MODE>(hm + ty * ST);
   }
 }
 
@@ -306,7 +321,7 @@ constexpr int kTyChoices[] = {1, 2, 3, 4, 7};
 template <int TY, bool NT>
 hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st, bool lean) {
   if (lean && !NT) {
-    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, false>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
+    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, 0>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((pool_max_f32_kernel<3, 3, 2, TY, NT>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
@@ -317,7 +332,7 @@ hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* ou
 
 // variant = index into kTyChoices * 2 + nontemporal flag for the strip kernel, kRollVariant for the rolling kernel
 constexpr int kRollVariant = 100;
-// other windows and min pooling: lean strip kernel, 2 output rows per strip; variant = kShapeVariant + 2*shape + is_min
+// other windows, min and sum pooling: lean strip kernel, 2 output rows per strip; variant = kShapeVariant + 3*shape + mode
 constexpr int kShapeVariant = 200;
 struct PoolWindow { int r, s, stride; };
 constexpr PoolWindow kWindows[] = {{3, 3, 2}, {2, 2, 2}, {3, 3, 1}};
@@ -338,12 +353,13 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   if (s.N > 0x7fffffff / 4 || s.H > 0x3fffffff || s.W > 0x3fffffff || s.Wo * (s.C / 4) > 0x3fffffff) return false;
   const bool row_offsets_fit = ((s.W - 1) * s.i_x + s.C) < ((int64_t)1 << 29) && ((s.Wo - 1) * s.o_x + s.C) < ((int64_t)1 << 29) &&
                               s.i_x >= 0 && s.o_x >= 0;
-  if (window != 0 || s.is_min) {
+  const int mode = s.agg == STRIPE_AGG_ADD ? 2 : s.agg == STRIPE_AGG_MIN ? 1 : 0;
+  if (window != 0 || mode != 0) {
     if (!row_offsets_fit) return false;
     const PoolParams p = make_params(s, 2, 128);
     const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
     if (grid > 0x7fffffffLL) return false;
-    l->variant = kShapeVariant + 2 * window + (s.is_min ? 1 : 0);
+    l->variant = kShapeVariant + 3 * window + mode;
     l->rows = 2;
     l->wg = 128;
     l->grid = grid;
@@ -355,8 +371,8 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     info->lds_bytes = 0;
     info->workgroup_size = 128;
     info->grid = grid;
-    snprintf(info->kernel, sizeof info->kernel, "pool_%s_f32_%dx%ds%d_ty2", s.is_min ? "min" : "max", kWindows[window].r, kWindows[window].s,
-             kWindows[window].stride);
+    snprintf(info->kernel, sizeof info->kernel, "pool_%s_f32_%dx%ds%d_ty2", mode == 2 ? "sum" : mode == 1 ? "min" : "max", kWindows[window].r,
+             kWindows[window].s, kWindows[window].stride);
     return true;
   }
   if (tune_int("pool_roll", 0) && row_offsets_fit) {
@@ -425,11 +441,14 @@ hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in
     const float* i = (const float*)in;
     float* o = (float*)out;
     switch (l.variant - kShapeVariant) {
-      case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, 2, true>), g, b, 0, st, p, i, o); break;
-      case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, false>), g, b, 0, st, p, i, o); break;
-      case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, true>), g, b, 0, st, p, i, o); break;
-      case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, false>), g, b, 0, st, p, i, o); break;
-      case 5: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, true>), g, b, 0, st, p, i, o); break;
+      case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, 2, 1>), g, b, 0, st, p, i, o); break;
+      case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, 2, 2>), g, b, 0, st, p, i, o); break;
+      case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, 0>), g, b, 0, st, p, i, o); break;
+      case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, 1>), g, b, 0, st, p, i, o); break;
+      case 5: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, 2>), g, b, 0, st, p, i, o); break;
+      case 6: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, 0>), g, b, 0, st, p, i, o); break;
+      case 7: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, 1>), g, b, 0, st, p, i, o); break;
+      case 8: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, 2>), g, b, 0, st, p, i, o); break;
       default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -306,16 +306,24 @@ def test_pool_rolling_chunks(rows, wg, monkeypatch):
 
 
 @pytest.mark.parametrize("R,stride,pad,agg", [(2, 2, 0, "max"), (2, 2, 1, "min"), (3, 1, 1, "max"), (3, 1, 0, "min"), (3, 2, 1, "min"),
-                                              (3, 2, 0, "max"), (3, 1, 2, "max")])
+                                              (3, 2, 0, "max"), (3, 1, 2, "max"), (3, 2, 1, "add"), (2, 2, 1, "add"), (3, 1, 2, "add")])
 def test_pool_other_windows_and_min(R, stride, pad, agg):
-    """2x2/s2 and 3x3/s1 windows, several paddings, max and min on the pooling kernel: exact, and equal to the
-    generic kernel's result."""
+    """2x2/s2 and 3x3/s1 windows, several paddings, max, min and sum on the pooling kernel: max/min exact and equal
+    to the generic kernel's result; sums (taps outside the image contribute nothing) within the fp32 tolerance."""
     N, H, Wd, C = 2, 21, 18, 12
     blk = W.maxpool_block(N, H, Wd, C, R, stride, pad, agg=agg)
     x = W.seeded_tensor((N, H, Wd, C), "f32", 5)
     info, _ = parity(blk, [x], what=f"pool {R}x{R}s{stride}p{pad} {agg}")
-    assert info["path_name"] == "pool" and info["kernel"] == f"pool_{agg}_f32_{R}x{R}s{stride}_ty2", info
-    assert np.array_equal(run_gpu(blk, [x], "pool"), run_gpu(blk, [x], "generic"))
+    name = "sum" if agg == "add" else agg
+    assert info["path_name"] == "pool" and info["kernel"] == f"pool_{name}_f32_{R}x{R}s{stride}_ty2", info
+    if agg != "add":
+        assert np.array_equal(run_gpu(blk, [x], "pool"), run_gpu(blk, [x], "generic"))
+    else:                    # all-ones: the sum is the number of in-range taps, exactly
+        ones = torch.ones_like(x)
+        got = run_gpu(blk, [ones], "pool").reshape(N, -1, info["output_elements"] // (N * C * ((H + 2 * pad - R) // stride + 1)), C)
+        cy = np.array([taps(y, stride, pad, R, H) for y in range(got.shape[1])])
+        cx = np.array([taps(xx, stride, pad, R, Wd) for xx in range(got.shape[2])])
+        assert np.array_equal(got, np.broadcast_to((cy[:, None] * cx[None, :])[None, :, :, None], got.shape))
 
 
 def test_pool_all_negative_and_generic_agree():
