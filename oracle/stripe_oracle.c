@@ -117,6 +117,7 @@ static int leaf_statements(ctx_t* c, int L) {
     } else {
       const int64_t b = load_int(c->inputs[1], c->lvl[0]->refs[1].dtype, addr[1]);
       v = (leaf->intrinsic == SO_INTR_MUL) ? a * b : a + b;
+      if (leaf->intrinsic == SO_INTR_ADD_RELU && v < 0) v = 0;
     }
     if (!fits_i32(v)) return fail(c, SO_ERR_INT_OVERFLOW, "value %lld at element %lld exceeds int32", (long long)(v), (long long)(e));
     if (!c->touched[e]) {
@@ -142,6 +143,7 @@ static int leaf_statements(ctx_t* c, int L) {
     } else {
       const double b = load_float(c->inputs[1], c->lvl[0]->refs[1].dtype, addr[1]);
       v = (leaf->intrinsic == SO_INTR_MUL) ? a * b : a + b;
+      if (leaf->intrinsic == SO_INTR_ADD_RELU && v < 0) v = 0;
     }
     if (!c->touched[e]) {
       c->touched[e] = 1;
@@ -258,7 +260,9 @@ static int collect(ctx_t* c, const so_block_t* root) {
   const int n_in = c->n_refs - 1;
   if (leaf->intrinsic == SO_INTR_COPY ? n_in != 1 : n_in != 2) return fail(c, SO_ERR_BAD_BLOCK, "intrinsic %lld does not take %lld inputs", (long long)(leaf->intrinsic), (long long)(n_in));
   const int odt = root->refs[c->out_ref].dtype;
-  if (odt != SO_I32 && odt != SO_F32) return fail(c, SO_ERR_BAD_BLOCK, "output type must be i32 or f32");
+  /* a bf16 output buffer is a float block too: the result is returned in fp64, rounding it to the buffer's type is
+     left to whoever compares */
+  if (odt != SO_I32 && odt != SO_F32 && odt != SO_BF16) return fail(c, SO_ERR_BAD_BLOCK, "output type must be i32, f32 or bf16");
   c->int_mode = (odt == SO_I32);
   for (int r = 0; r < n_in; ++r) {
     const int dt = root->refs[r].dtype;

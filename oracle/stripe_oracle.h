@@ -40,7 +40,7 @@ extern "C" {
 enum { SO_DIR_IN = 0, SO_DIR_OUT = 1 };
 enum { SO_I8 = 0, SO_I32 = 1, SO_BF16 = 2, SO_F32 = 3 };
 enum { SO_AGG_ASSIGN = 0, SO_AGG_ADD = 1, SO_AGG_MAX = 2, SO_AGG_MIN = 3, SO_AGG_MUL = 4 };
-enum { SO_INTR_MUL = 0, SO_INTR_COPY = 1, SO_INTR_ADD = 2 };
+enum { SO_INTR_MUL = 0, SO_INTR_COPY = 1, SO_INTR_ADD = 2, SO_INTR_ADD_RELU = 3 /* load, load, add, relu (max with 0), store */ };
 
 enum {
   SO_OK = 0,

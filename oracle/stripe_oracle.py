@@ -30,7 +30,7 @@ _DIR = {"in": 0, "out": 1}
 _DTYPE = {"i8": 0, "i32": 1, "bf16": 2, "f32": 3}
 _NP_DTYPE = {"i8": np.int8, "i32": np.int32, "bf16": np.uint16, "f32": np.float32}
 _AGG = {"assign": 0, "add": 1, "max": 2, "min": 3, "mul": 4}
-_INTR = {"mul": 0, "copy": 1, "add": 2}
+_INTR = {"mul": 0, "copy": 1, "add": 2, "add_relu": 3}
 
 ERR_NAMES = {1: "bad block", 2: "out of bounds", 3: "assign conflict", 4: "int32 overflow"}
 
@@ -160,6 +160,63 @@ def _eval_once(cb, in_ptrs, is_int, out, touched, win):
                      out.ctypes.data_as(C.POINTER(C.c_int64)) if is_int else None,
                      touched.ctypes.data_as(C.POINTER(C.c_uint8)), lo, hi, C.byref(npts), err, 256)
     return rc, err.value.decode(), int(npts.value)
+
+
+def statements(root) -> list:
+    """The statement list of the root block (Section 3.2: a block's statements execute as if in serial)."""
+    out, s = [], root.child
+    while s is not None:
+        out.append(s)
+        s = getattr(s, "next", None)
+    return out
+
+
+def evaluate_program(root, inputs: Sequence[np.ndarray], out: Optional[np.ndarray] = None, threads: int = 1) -> Result:
+    """A root block with several statements and temporaries ('temp' refinements of the root).
+
+    The statements run one after the other, each evaluated exactly like a single block.  A statement names the
+    root buffers it uses through `parent_refs`.  What a statement writes is stored in the buffer's declared
+    element type (a temporary declared f32 holds the fp64 result rounded to fp32; integers stay exact), and later
+    statements read that.  The result returned is the last statement's: the program's output, in fp64 / int64,
+    not yet rounded to the output buffer's type."""
+    import copy
+    stmts = statements(root)
+    held = {}                      # root refinement number -> array in its declared element type
+    it = iter(inputs)
+    for j, r in enumerate(root.refs):
+        if r.dir == "in":
+            held[j] = np.ascontiguousarray(next(it))
+    res = None
+    for si, st in enumerate(stmts):
+        uses = list(st.parent_refs) if getattr(st, "parent_refs", None) is not None else list(range(len(st.refs)))
+        sub_refs = []
+        for lr, j in zip(st.refs, uses):
+            rr = copy.copy(root.refs[j])
+            rr.dir = lr.dir                    # a temporary is 'out' for the statement that writes it, 'in' later
+            sub_refs.append(rr)
+        single = copy.copy(st)
+        single.next = None
+        single.parent_refs = None
+        sub_root = type(root)(idx_names=[], ranges=[], refs=sub_refs, child=single)
+        ins = []
+        for lr, j in zip(st.refs[:-1], uses[:-1]):
+            if j not in held:
+                raise OracleError(1, f"statement {si} reads root buffer {j} before anything wrote it")
+            ins.append(held[j])
+        last = si == len(stmts) - 1
+        res = evaluate(sub_root, ins, out=out if last else None, threads=threads)
+        jo = uses[-1]
+        odt = root.refs[jo].dtype
+        if not last:
+            if not res.touched.all():
+                raise OracleError(1, f"statement {si} leaves elements of temporary {jo} unwritten")
+            if odt == "f32":
+                held[jo] = res.out.astype(np.float32)
+            elif odt == "i32":
+                held[jo] = res.out.astype(np.int32)
+            else:
+                raise OracleError(1, "temporaries are f32 or i32")
+    return res
 
 
 def evaluate(root, inputs: Sequence[np.ndarray], out: Optional[np.ndarray] = None,

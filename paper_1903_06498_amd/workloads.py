@@ -18,7 +18,7 @@ import numpy as np
 
 DTYPES = ("i8", "i32", "bf16", "f32")
 AGGS = ("assign", "add", "max", "min", "mul")
-INTRINSICS = ("mul", "copy", "add")
+INTRINSICS = ("mul", "copy", "add", "add_relu")
 
 
 @dataclass
@@ -47,6 +47,8 @@ class Block:
     refs: List[Refinement] = field(default_factory=list)
     intrinsic: Optional[str] = None   # leaf only
     child: Optional["Block"] = None
+    next: Optional["Block"] = None    # next statement of the parent's statement list (statements run in order)
+    parent_refs: Optional[List[int]] = None   # which parent refinement each of `refs` refines; None: same positions
 
     @property
     def var_names(self) -> List[str]:
@@ -303,6 +305,38 @@ def config_block(name: str) -> Block:
     if name == "maxpool_f32":
         return maxpool_block(32, 112, 112, 64, 3, 2, 1, "f32")
     raise KeyError(name)
+
+
+def conv_bias_relu_program(N, H, W, Ci, Co, R, S, stride, pad, in_dtype="bf16", out_dtype="bf16") -> Block:
+    """Two statements under one root (Section 3.2: statements run as if in serial; Section 2.3: fusion and
+    scalarisation are what an implementation may do with them):
+        0:  T[n,y,x,k] += I[n, s*y+i-p, s*x+j-p, c] * F[i,j,k,c]      (T: an f32 temporary of the root)
+        1:  O[n,y,x,k]  = relu(T[n,y,x,k] + B[k])
+    Root buffers, in order: I, F, B (inputs), T (temporary), O (output).  Integer inputs give an i32 temporary,
+    bias and output."""
+    acc = "i32" if in_dtype in ("i8", "i32") else "f32"
+    if acc == "i32":
+        out_dtype = "i32"
+    Ho = (H + 2 * pad - R) // stride + 1
+    Wo = (W + 2 * pad - S) // stride + 1
+    bufs = [Buffer("I", "in", in_dtype, (N, H, W, Ci)), Buffer("F", "in", in_dtype, (R, S, Co, Ci)),
+            Buffer("B", "in", acc, (Co,)), Buffer("T", "temp", acc, (N, Ho, Wo, Co)),
+            Buffer("O", "out", out_dtype, (N, Ho, Wo, Co))]
+    s_, p_ = stride, pad
+    ya, xa = f"{s_}*y + i - {p_}", f"{s_}*x + j - {p_}"
+    cons = [f"{ya} >= 0", f"{H - 1 + p_} - {s_}*y - i >= 0", f"{xa} >= 0", f"{W - 1 + p_} - {s_}*x - j >= 0"] if pad else []
+    conv_bufs = [bufs[0], bufs[1], Buffer("T", "out", acc, (N, Ho, Wo, Co))]
+    s0 = make_level(dict(n=N, y=Ho, x=Wo, i=R, j=S, c=Ci, k=Co),
+                    [(["n", ya, xa, "c"], "assign"), (["i", "j", "k", "c"], "assign"), (["n", "y", "x", "k"], "add")],
+                    buffers=conv_bufs, constraints=cons, intrinsic="mul")
+    s0.parent_refs = [0, 1, 3]
+    ew_bufs = [Buffer("T", "in", acc, (N, Ho, Wo, Co)), bufs[2], bufs[4]]
+    s1 = make_level(dict(n=N, y=Ho, x=Wo, k=Co),
+                    [(["n", "y", "x", "k"], "assign"), (["k"], "assign"), (["n", "y", "x", "k"], "assign")],
+                    buffers=ew_bufs, intrinsic="add_relu")
+    s1.parent_refs = [3, 2, 4]
+    s0.next = s1
+    return make_root(bufs, s0)
 
 
 # Further shapes the kernel families cover, for measurements beyond the five configurations (bench.py --workload).
