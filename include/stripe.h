@@ -48,13 +48,16 @@ typedef enum {
   STRIPE_AGG_MUL = 4   /* product; integer products wrap in int32 like any int32 arithmetic here */
 } stripe_agg_t;
 
-/* Leaf statement lists (Section 3.2 "intrinsics"; Figure 5 lines 0-3 of the inner block):
+/* Leaf statement lists (Section 3.2 "intrinsics"; Figure 5, the four statements of the inner block):
  *   MUL : $a = load(in0); $b = load(in1); $o = mul($a,$b); out = store($o)
  *   ADD : the same with add
- *   COPY: $a = load(in0); out = store($a)                                   */
-typedef enum { STRIPE_INTR_MUL = 0, STRIPE_INTR_COPY = 1, STRIPE_INTR_ADD = 2 } stripe_intrinsic_t;
+ *   COPY: $a = load(in0); out = store($a)
+ *   ADD_RELU: $a = load(in0); $b = load(in1); $o = relu(add($a,$b)); out = store($o)   (relu(v) = max(v, 0)) */
+typedef enum { STRIPE_INTR_MUL = 0, STRIPE_INTR_COPY = 1, STRIPE_INTR_ADD = 2, STRIPE_INTR_ADD_RELU = 3 } stripe_intrinsic_t;
 
-typedef enum { STRIPE_IN = 0, STRIPE_OUT = 1 } stripe_dir_t;
+/* TEMP: only at the root of a block with several statements: a buffer the library owns, written by one statement
+ * and read by later ones.  The caller passes no pointer for it. */
+typedef enum { STRIPE_IN = 0, STRIPE_OUT = 1, STRIPE_TEMP = 2 } stripe_dir_t;
 
 /* Which kernel family runs the block (reported by stripe_block_query). */
 typedef enum {
@@ -102,7 +105,7 @@ typedef struct {
  * Every level lists the same buffers in the same order: inputs first (one for
  * COPY, two for MUL/ADD), the single output last.
  * Element types: inputs i8/i32 with an i32 output, or bf16/f32 with an f32
- * output.  Integer arithmetic is exact two's-complement int32 (operands
+ * or bf16 output (rounded to nearest even on store).  Integer arithmetic is exact two's-complement int32 (operands
  * sign-extended before the multiply); float blocks accumulate in fp32.
  */
 typedef struct stripe_block_desc {
@@ -118,6 +121,13 @@ typedef struct stripe_block_desc {
   const stripe_refinement_t* refs;
   stripe_intrinsic_t intrinsic; /* leaf only */
   const struct stripe_block_desc* child;
+  /* Statement lists (Section 3.2: a block may hold several statements, executed as if in serial).  Supported
+   * at the root only: root->child is the first statement, ->next the following ones (NULL ends the list).
+   * A statement of a list names the root refinements it uses, inputs first and its output last, in
+   * parent_refs[n_refs]; with a single statement parent_refs may be NULL (same positions).  Root refinements
+   * then come in the order: the caller's inputs, temporaries (STRIPE_TEMP), the single output last. */
+  const struct stripe_block_desc* next;
+  const int32_t* parent_refs;
 } stripe_block_desc_t;          /* n_vars of a level = n_idx + n_passed */
 
 typedef struct stripe_block stripe_block_t; /* opaque handle */

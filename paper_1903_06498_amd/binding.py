@@ -23,10 +23,10 @@ STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_INVALID_DESC", 3: "ERR_UNSUPPORT
 PATHS = {"auto": 0, "generic": 1, "mfma_gemm": 2, "mfma_conv": 3, "pool": 4}
 PATH_NAMES = {v: k for k, v in PATHS.items()}
 
-_DIR = {"in": 0, "out": 1}
+_DIR = {"in": 0, "out": 1, "temp": 2}
 _DTYPE = {"i8": 0, "i32": 1, "bf16": 2, "f32": 3}
 _AGG = {"assign": 0, "add": 1, "max": 2, "min": 3, "mul": 4}
-_INTR = {"mul": 0, "copy": 1, "add": 2}
+_INTR = {"mul": 0, "copy": 1, "add": 2, "add_relu": 3}
 
 EXPORTS = ("stripe_block_create", "stripe_block_create_for_path", "stripe_block_run", "stripe_block_query",
            "stripe_block_destroy", "stripe_status_string", "stripe_last_error", "stripe_device_copy",
@@ -48,7 +48,8 @@ stripe_block_desc_t._fields_ = [
     ("n_passed", C.c_int32), ("passed_coeff", C.POINTER(C.c_int64)), ("passed_const", C.POINTER(C.c_int64)),
     ("n_constraints", C.c_int32), ("cons_coeff", C.POINTER(C.c_int64)), ("cons_const", C.POINTER(C.c_int64)),
     ("n_refs", C.c_int32), ("refs", C.POINTER(stripe_refinement_t)),
-    ("intrinsic", C.c_int), ("child", C.POINTER(stripe_block_desc_t))]
+    ("intrinsic", C.c_int), ("child", C.POINTER(stripe_block_desc_t)),
+    ("next", C.POINTER(stripe_block_desc_t)), ("parent_refs", C.POINTER(C.c_int32))]
 
 
 class stripe_block_info_t(C.Structure):
@@ -160,6 +161,16 @@ def marshal(block, keep: list) -> stripe_block_desc_t:
         child = marshal(block.child, keep)
         keep.append(child)
         d.child = C.pointer(child)
+    nxt = getattr(block, "next", None)
+    if nxt is not None:
+        sibling = marshal(nxt, keep)
+        keep.append(sibling)
+        d.next = C.pointer(sibling)
+    uses = getattr(block, "parent_refs", None)
+    if uses is not None:
+        arr = (C.c_int32 * len(uses))(*[int(v) for v in uses])
+        keep.append(arr)
+        d.parent_refs = C.cast(arr, C.POINTER(C.c_int32))
     return d
 
 
@@ -301,7 +312,7 @@ class StripeBlock:
     def __init__(self, block, path: str = "auto"):
         self.handle = stripe_block_create(block, path)
         self.info = stripe_block_query(self.handle)
-        self._n_in = len(block.refs) - 1
+        self._n_in = sum(1 for r in block.refs if r.dir == "in")
         self._in_arr = (C.c_void_p * self._n_in)()      # reused on every run: marshalling cost matters for tiny blocks
 
     def run(self, inputs, output, stream: Optional[int] = None) -> None:

@@ -5,11 +5,21 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 #include "kernels.hpp"
 #include "plan.hpp"
 
 using namespace stripe;
+
+// One statement of a root block's statement list, planned like a block of its own, with the root refinements it
+// reads and writes.
+struct Stage {
+  stripe_block* blk = nullptr;
+  int n_in = 0;
+  int src[2] = {-1, -1};
+  int dst = -1;
+};
 
 struct stripe_block {
   Plan plan;
@@ -17,6 +27,18 @@ struct stripe_block {
   ConvLaunch conv;
   PoolLaunch pool;
   int n_inputs = 0;
+  // statement lists (empty for a single block): stages in order, and per root refinement either the caller's
+  // input number, or the size of a temporary the handle owns (allocated on the first run, per device)
+  std::vector<Stage> stages;
+  std::vector<int> input_slot;       // root refinement -> index into run()'s inputs, -1 otherwise
+  std::vector<int64_t> temp_bytes;   // root refinement -> bytes of the temporary, 0 otherwise
+  std::vector<void*> temp_ptr;
+  int temp_dev = -1;
+  ~stripe_block() {
+    for (Stage& st : stages) delete st.blk;
+    for (void* t : temp_ptr)
+      if (t) (void)hipFree(t);
+  }
 };
 
 namespace {
@@ -34,12 +56,144 @@ namespace stripe {
 stripe_status_t api_fail(stripe_status_t st, const std::string& msg) { return fail(st, msg); }
 }  // namespace stripe
 
-extern "C" {
+namespace {
 
-stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, stripe_path_t path, stripe_block_t** out) {
-  if (!desc || !out) return fail(STRIPE_ERR_NULL, "desc or out is NULL");
-  *out = nullptr;
-  if (path < STRIPE_PATH_AUTO || path > STRIPE_PATH_POOL) return fail(STRIPE_ERR_INVALID_DESC, "unknown path");
+stripe_status_t create_single(const stripe_block_desc_t* desc, stripe_path_t path, stripe_block_t** out);
+
+// A root block with a statement list (Section 3.2: statements execute as if in serial): every statement is planned
+// as a block of its own over the root buffers it names; temporaries of the root live in memory the handle owns.
+stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t path, stripe_block_t** out) {
+  if (root->n_idx != 0 || root->n_passed != 0 || root->n_constraints != 0 || !root->refs || root->n_refs < 2 || root->n_refs > 16)
+    return fail(STRIPE_ERR_INVALID_DESC, "a statement list needs a declaring root block with 2..16 buffers");
+  if (path != STRIPE_PATH_AUTO && path != STRIPE_PATH_GENERIC)
+    return fail(STRIPE_ERR_UNSUPPORTED, "a kernel family can be forced for single blocks only");
+  const int R = root->n_refs;
+  stripe_block* prog = new (std::nothrow) stripe_block();
+  if (!prog) return fail(STRIPE_ERR_NOMEM, "out of host memory");
+  prog->input_slot.assign(R, -1);
+  prog->temp_bytes.assign(R, 0);
+  prog->temp_ptr.assign(R, nullptr);
+  std::vector<char> written(R, 0);
+  int n_inputs = 0, phase = 0;
+  for (int r = 0; r < R; ++r) {
+    const stripe_refinement_t& t = root->refs[r];
+    const int want = t.dir == STRIPE_IN ? 0 : t.dir == STRIPE_TEMP ? 1 : 2;
+    if (want < phase || (r == R - 1) != (t.dir == STRIPE_OUT) || t.ndim < 1 || t.ndim > 8 || !t.sizes || !t.strides || !t.access_const) {
+      delete prog;
+      return fail(STRIPE_ERR_INVALID_DESC, "root buffers come as inputs, then temporaries, then the single output");
+    }
+    phase = want;
+    if (t.dir == STRIPE_IN) {
+      prog->input_slot[r] = n_inputs++;
+      written[r] = 1;
+    } else if (t.dir == STRIPE_TEMP) {
+      if (t.dtype != STRIPE_F32 && t.dtype != STRIPE_I32) {
+        delete prog;
+        return fail(STRIPE_ERR_UNSUPPORTED, "temporaries hold f32 or i32");
+      }
+      int64_t extent = 1;
+      for (int d = 0; d < t.ndim; ++d) {
+        if (t.sizes[d] < 1 || t.strides[d] < 0 || t.access_const[d] < 0 || t.sizes[d] > ((int64_t)1 << 40) || t.strides[d] > ((int64_t)1 << 40)) {
+          delete prog;
+          return fail(STRIPE_ERR_INVALID_DESC, "bad temporary declaration");
+        }
+        extent += (t.access_const[d] + t.sizes[d] - 1) * t.strides[d];
+      }
+      if (extent > ((int64_t)1 << 40)) {
+        delete prog;
+        return fail(STRIPE_ERR_INVALID_DESC, "temporary too large");
+      }
+      prog->temp_bytes[r] = extent * 4;
+    }
+  }
+  prog->n_inputs = n_inputs;
+  int n_stmt = 0;
+  for (const stripe_block_desc_t* st = root->child; st; st = st->next) {
+    ++n_stmt;
+    if (n_stmt > 8 || st->n_refs < 2 || st->n_refs > 3 || !st->parent_refs || !st->refs) {
+      delete prog;
+      return fail(STRIPE_ERR_INVALID_DESC, "a statement of a list has 2 or 3 refinements and names their root buffers in parent_refs");
+    }
+    stripe_refinement_t refs[3];
+    Stage stage;
+    stage.n_in = st->n_refs - 1;
+    for (int i = 0; i < st->n_refs; ++i) {
+      const int j = st->parent_refs[i];
+      const bool is_out = i == st->n_refs - 1;
+      if (j < 0 || j >= R || (is_out ? root->refs[j].dir == STRIPE_IN : !written[j]) || (is_out && st->next == nullptr) != (is_out && j == R - 1)) {
+        delete prog;
+        return fail(STRIPE_ERR_INVALID_DESC, "a statement reads a buffer nothing wrote yet, writes a caller's input, or the list does not end with the output");
+      }
+      refs[i] = root->refs[j];
+      refs[i].dir = is_out ? STRIPE_OUT : STRIPE_IN;
+      if (is_out) stage.dst = j; else stage.src[i] = j;
+    }
+    written[stage.dst] = 1;
+    stripe_block_desc_t stmt = *st;
+    stmt.next = nullptr;
+    stmt.parent_refs = nullptr;
+    stripe_block_desc_t sub = {};
+    sub.n_refs = st->n_refs;
+    sub.refs = refs;
+    sub.child = &stmt;
+    const stripe_status_t rc = create_single(&sub, path, &stage.blk);
+    if (rc != STRIPE_OK) {
+      delete prog;
+      return rc;   // detail already recorded
+    }
+    prog->stages.push_back(stage);
+  }
+  // what the program as a whole looks like from outside
+  stripe_block_info_t& info = prog->plan.info;
+  info = prog->stages[0].blk->plan.info;
+  info.hull_points = info.work_points = 0;
+  info.algorithmic_bytes = 0;
+  std::string names;
+  for (const Stage& stg : prog->stages) {
+    const stripe_block_info_t& si = stg.blk->plan.info;
+    info.hull_points += si.hull_points;
+    info.work_points = (info.work_points < 0 || si.work_points < 0) ? -1 : info.work_points + si.work_points;
+    names += (names.empty() ? "" : " ; ") + std::string(si.kernel);
+  }
+  info.output_elements = prog->stages.back().blk->plan.info.output_elements;
+  for (int r = 0; r < R; ++r)   // every caller-visible buffer once; temporaries are the library's business
+    if (root->refs[r].dir != STRIPE_TEMP) {
+      int64_t n = 1;
+      for (int d = 0; d < root->refs[r].ndim; ++d) n *= root->refs[r].sizes[d];
+      info.algorithmic_bytes += n * (root->refs[r].dtype == STRIPE_I8 ? 1 : root->refs[r].dtype == STRIPE_BF16 ? 2 : 4);
+    }
+  std::snprintf(info.kernel, sizeof info.kernel, "%s", names.c_str());
+  *out = prog;
+  return STRIPE_OK;
+}
+
+stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void* output, void* hip_stream) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail(STRIPE_ERR_HIP, hipGetErrorString(e));
+  if (dev != prog->temp_dev) {   // first run (on this device): the temporaries
+    for (size_t r = 0; r < prog->temp_ptr.size(); ++r) {
+      if (prog->temp_ptr[r]) (void)hipFree(prog->temp_ptr[r]);
+      prog->temp_ptr[r] = nullptr;
+      if (prog->temp_bytes[r] && hipMalloc(&prog->temp_ptr[r], (size_t)prog->temp_bytes[r]) != hipSuccess)
+        return fail(STRIPE_ERR_NOMEM, "out of device memory for a temporary");
+    }
+    prog->temp_dev = dev;
+  }
+  const int R = (int)prog->input_slot.size();
+  auto where = [&](int r) -> const void* {
+    if (r == R - 1) return output;
+    return prog->input_slot[r] >= 0 ? inputs[prog->input_slot[r]] : prog->temp_ptr[r];
+  };
+  for (const Stage& st : prog->stages) {
+    const void* ins[2] = {where(st.src[0]), st.n_in > 1 ? where(st.src[1]) : nullptr};
+    const stripe_status_t rc = stripe_block_run(st.blk, ins, const_cast<void*>(where(st.dst)), hip_stream);
+    if (rc != STRIPE_OK) return rc;
+  }
+  return STRIPE_OK;
+}
+
+stripe_status_t create_single(const stripe_block_desc_t* desc, stripe_path_t path, stripe_block_t** out) {
   std::string err;
   FlatBlock fb;
   stripe_status_t st = flatten(desc, &fb, &err);
@@ -84,6 +238,20 @@ stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, st
   return STRIPE_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, stripe_path_t path, stripe_block_t** out) {
+  if (!desc || !out) return fail(STRIPE_ERR_NULL, "desc or out is NULL");
+  *out = nullptr;
+  if (path < STRIPE_PATH_AUTO || path > STRIPE_PATH_POOL) return fail(STRIPE_ERR_INVALID_DESC, "unknown path");
+  if (desc->child && (desc->child->next || desc->child->parent_refs)) return create_program(desc, path, out);
+  for (int r = 0; desc->refs && r < desc->n_refs; ++r)
+    if (desc->refs[r].dir == STRIPE_TEMP) return fail(STRIPE_ERR_INVALID_DESC, "a temporary needs a statement list that writes and reads it");
+  return create_single(desc, path, out);
+}
+
 stripe_status_t stripe_block_create(const stripe_block_desc_t* desc, stripe_block_t** out) {
   return stripe_block_create_for_path(desc, STRIPE_PATH_AUTO, out);
 }
@@ -92,6 +260,7 @@ stripe_status_t stripe_block_run(stripe_block_t* blk, const void* const* inputs,
   if (!blk || !inputs || !output) return fail(STRIPE_ERR_NULL, "blk, inputs or output is NULL");
   for (int i = 0; i < blk->n_inputs; ++i)
     if (!inputs[i]) return fail(STRIPE_ERR_NULL, "an input pointer is NULL");
+  if (!blk->stages.empty()) return run_program(blk, inputs, output, hip_stream);
   const Plan& p = blk->plan;
   if (p.noop) return STRIPE_OK;
   hipStream_t s = (hipStream_t)hip_stream;

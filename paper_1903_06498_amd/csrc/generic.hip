@@ -166,12 +166,19 @@ __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, con
     if (INTR != STRIPE_INTR_COPY) {
       const Acc b = Elem<TIn>::load(in1, ob);
       v = (INTR == STRIPE_INTR_MUL) ? a * b : a + b;
+      if (INTR == STRIPE_INTR_ADD_RELU) v = v > (Acc)0 ? v : (Acc)0;
     }
     acc = touched ? combine<AGG, Acc>(acc, v) : v;
     touched = true;
   };
 
   auto finish = [&](I off) {
+    if (std::is_same<Acc, float>::value && p.out_bf16) {   // bf16 output buffer: round to nearest even (never atomic)
+      const uint32_t u = __float_as_uint((float)acc);
+      ((uint16_t*)out)[off] = (u & 0x7fffffffu) > 0x7f800000u ? (uint16_t)((u >> 16) | 0x40u)       // NaN stays NaN
+                                                              : (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+      return;
+    }
     Acc* dst = (Acc*)out + off;
     if (pass == 0) *dst = acc;
     else if (pass == 1) *dst = identity_of<AGG>(Acc());
@@ -281,6 +288,7 @@ hipError_t launch_intr(int intr, int agg, const GenericParams& p, const void* a,
   switch (intr) {
     case STRIPE_INTR_COPY: return launch_agg<TIn, STRIPE_INTR_COPY>(agg, p, a, b, o, s);
     case STRIPE_INTR_ADD: return launch_agg<TIn, STRIPE_INTR_ADD>(agg, p, a, b, o, s);
+    case STRIPE_INTR_ADD_RELU: return launch_agg<TIn, STRIPE_INTR_ADD_RELU>(agg, p, a, b, o, s);
     default: return launch_agg<TIn, STRIPE_INTR_MUL>(agg, p, a, b, o, s);
   }
 }

@@ -139,7 +139,8 @@ stripe_status_t flatten(const stripe_block_desc_t* root, FlatBlock* fb, std::str
   fb->n_levels = L;
   const stripe_block_desc_t* leaf = lvl[L - 1];
   fb->intrinsic = leaf->intrinsic;
-  if (leaf->intrinsic != STRIPE_INTR_MUL && leaf->intrinsic != STRIPE_INTR_COPY && leaf->intrinsic != STRIPE_INTR_ADD)
+  if (leaf->intrinsic != STRIPE_INTR_MUL && leaf->intrinsic != STRIPE_INTR_COPY && leaf->intrinsic != STRIPE_INTR_ADD &&
+      leaf->intrinsic != STRIPE_INTR_ADD_RELU)
     return bad(err, STRIPE_ERR_INVALID_DESC, "unknown intrinsic");
   if ((leaf->intrinsic == STRIPE_INTR_COPY ? 1 : 2) != R - 1)
     return bad(err, STRIPE_ERR_INVALID_DESC, "COPY takes one input, MUL and ADD take two");
@@ -171,11 +172,12 @@ stripe_status_t flatten(const stripe_block_desc_t* root, FlatBlock* fb, std::str
     }
   }
   const int odt = fb->ref[R - 1].dtype;
-  if (odt != STRIPE_I32 && odt != STRIPE_F32) return bad(err, STRIPE_ERR_INVALID_DESC, "the output is i32 or f32");
+  if (odt != STRIPE_I32 && odt != STRIPE_F32 && odt != STRIPE_BF16) return bad(err, STRIPE_ERR_INVALID_DESC, "the output is i32, f32 or bf16");
   fb->int_mode = (odt == STRIPE_I32);
+  fb->out_bf16 = (odt == STRIPE_BF16);
   for (int r = 0; r + 1 < R; ++r) {
     if (is_int_type(fb->ref[r].dtype) != fb->int_mode)
-      return bad(err, STRIPE_ERR_INVALID_DESC, "integer inputs need an i32 output, float inputs an f32 output");
+      return bad(err, STRIPE_ERR_INVALID_DESC, "integer inputs need an i32 output, float inputs an f32 or bf16 output");
     if (fb->ref[r].dtype != fb->ref[0].dtype)
       return bad(err, STRIPE_ERR_UNSUPPORTED, "both inputs must have the same element type");
   }
@@ -745,9 +747,13 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
   if (fb.agg == STRIPE_AGG_ASSIGN && !red_idx.empty())
     return bad(err, STRIPE_ERR_ASSIGN_CONFLICT, "'assign' output with an index that does not move the output address");
 
-  const bool is_gemm = injective && match_gemm(fb, &plan->gemm);
-  const bool is_conv = injective && match_conv2d(fb, &plan->conv);
-  const bool is_pool = injective && match_pool2d(fb, &plan->pool);
+  // the specialised families store fp32 / int32; a bf16 output buffer runs on the generic kernel
+  if (fb.out_bf16 && !injective)
+    return bad(err, STRIPE_ERR_UNSUPPORTED, "a bf16 output shared between index tuples (no 16-bit atomic aggregation)");
+  const bool plain_out = injective && !fb.out_bf16;
+  const bool is_gemm = plain_out && match_gemm(fb, &plan->gemm);
+  const bool is_conv = plain_out && match_conv2d(fb, &plan->conv);
+  const bool is_pool = plain_out && match_pool2d(fb, &plan->pool);
   stripe_path_t path = forced;
   if (path == STRIPE_PATH_AUTO) {
     path = is_gemm ? STRIPE_PATH_MFMA_GEMM : is_conv ? STRIPE_PATH_MFMA_CONV : is_pool ? STRIPE_PATH_POOL : STRIPE_PATH_GENERIC;
@@ -844,11 +850,12 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
     for (const Affine& c : fb.cons) narrow = narrow && reach(c) <= lim;
     g.narrow = narrow ? 1 : 0;
     g.atomic = injective ? 0 : 1;
+    g.out_bf16 = fb.out_bf16 ? 1 : 0;
 
     // Register-tiled variant for sum-of-products blocks with enough parallelism (see TiledParams).
     TiledParams& tp = plan->tiled;
     std::memset(&tp, 0, sizeof tp);
-    if (narrow && injective && B && fb.intrinsic == STRIPE_INTR_MUL && fb.agg == STRIPE_AGG_ADD) {
+    if (narrow && injective && B && fb.intrinsic == STRIPE_INTR_MUL && fb.agg == STRIPE_AGG_ADD && !fb.out_bf16) {
       auto absv = [](int64_t v) { return v < 0 ? -v : v; };
       auto in_cons = [&](int j) {
         for (const Affine& c : fb.cons)

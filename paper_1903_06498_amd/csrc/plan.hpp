@@ -51,6 +51,7 @@ struct FlatBlock {
   int n_levels = 0;
   int intrinsic = STRIPE_INTR_MUL;
   bool int_mode = false;
+  bool out_bf16 = false;            // float block whose output buffer holds bf16 (rounded on store)
   bool empty = false;               // some range is 0 or the constraints exclude every point
 };
 
@@ -91,7 +92,7 @@ struct GenericParams {
   int64_t cons_const[kGenCons];
   int64_t n_outputs;
   uint32_t red_total, inner_range;
-  int32_t atomic, pad_;            // 1: output map not injective on the output indexes -> identity pass + atomic combine
+  int32_t atomic, out_bf16;        // atomic 1: output map not injective on the output indexes -> identity pass + atomic combine
 };
 
 // Parameters of the register-tiled generic contraction kernel: every lane owns a 4 x 4 patch of outputs

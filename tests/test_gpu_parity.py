@@ -6,6 +6,7 @@ element; the benchmark-size cases run in the launch configuration bench.py
 times and are compared on oracle-computed slabs plus size-independent
 properties (identity operand, all-ones tap counts).
 """
+import math
 import random
 import sys
 
@@ -242,6 +243,40 @@ def test_empty_block_launches_nothing():
     blk.refs[2].sizes = [3, 1]
     gpu = run_gpu(blk, [torch.zeros(15), torch.zeros(5)])
     assert np.all(gpu == np.float32(SENTINEL_F))
+
+
+# ------------------------------------------------------------------ statement lists (two statements and a temporary)
+def program_parity(N, H, Wd, Ci, Co, R, stride, pad, in_dt, out_dt, path="auto"):
+    prog = W.conv_bias_relu_program(N, H, Wd, Ci, Co, R, R, stride, pad, in_dt, out_dt)
+    acc = "i32" if in_dt == "i8" else "f32"
+    ins = [W.seeded_tensor((N, H, Wd, Ci), in_dt, 0), W.seeded_tensor((R, R, Co, Ci), in_dt, 1)]
+    bias = (W.seeded_tensor((Co,), "i32", 2) * 30) if acc == "i32" else W.seeded_tensor((Co,), "f32", 2)
+    if acc == "f32" and in_dt == "bf16":
+        ins[1] = (ins[1].float() * (2.0 / (R * R * Ci)) ** 0.5).to(torch.bfloat16)     # keep sums O(1), like the bias
+    gpu, sb = run_gpu(prog, ins + [bias], path, return_block=True)
+    res = O.evaluate_program(prog, [W.to_numpy(t).ravel() for t in ins] + [bias.numpy()], threads=8)
+    assert res.touched.all()
+    if acc == "i32":
+        assert np.array_equal(gpu.astype(np.int64), res.out)
+    else:
+        err = np.abs(gpu.astype(np.float64) - res.out)
+        K = R * R * Ci
+        amax, bmax = float(ins[0].float().abs().max()), float(ins[1].float().abs().max())
+        tol = (4e-3 * math.sqrt(K) * amax * bmax) if in_dt == "bf16" else 1e-4 * max(1.0, float(np.sqrt(np.mean(res.out ** 2))))
+        if out_dt == "bf16":
+            tol = tol + 2.0 ** -8 * np.abs(res.out)          # the store rounds to bf16: half an ulp, and a little
+        assert np.all(err <= tol), float(np.max(err - tol))
+        assert (gpu == 0).any() and (gpu > 0).any()          # the relu cut is exercised on both sides
+    return sb.info
+
+
+@pytest.mark.parametrize("in_dt,out_dt", [("f32", "f32"), ("bf16", "f32"), ("bf16", "bf16"), ("i8", "i32"), ("f32", "bf16")])
+@pytest.mark.parametrize("shape", [(2, 9, 7, 5, 6, 3, 1, 1), (1, 12, 11, 8, 16, 3, 2, 0)])
+def test_two_statement_program_small(shape, in_dt, out_dt):
+    """convolution into an f32 (i32) temporary, then relu(T + bias) into the output, on general shapes (generic
+    kernels): the statements run in order through a temporary the handle owns."""
+    info = program_parity(*shape, in_dt, out_dt)
+    assert " ; " in info["kernel"], info["kernel"]
 
 
 # ------------------------------------------------------------------ blocks produced by the tiling rewrite

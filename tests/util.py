@@ -37,7 +37,7 @@ def run_gpu(root, inputs, path="auto", return_block=False):
         dins.append(t.contiguous().to(dev))
     blk.run(dins, out)
     torch.cuda.synchronize()
-    res = out.cpu().numpy()
+    res = (out.float() if odt == "bf16" else out).cpu().numpy()
     if return_block:
         return res, blk
     blk.close()
