@@ -52,6 +52,8 @@ KIND = {
     "gemm_i8_4096_bt": ("TOP/s", "mfma", "int8"),
     "pointwise_conv_bf16": ("TFLOP/s", "hbm", "bf16"),
     "transposed_conv_f32": ("TFLOP/s", "alu", "f32"),
+    "resnet_conv_bias_relu_bf16": ("TFLOP/s", "hbm", "bf16"),   # two statements fused into one kernel, bf16 output
+    "resnet_conv_bias_relu_f32": ("TFLOP/s", "hbm", "bf16"),
 }
 
 
@@ -188,9 +190,9 @@ def main():
     blk = B.StripeBlock(root, args.path)
     info = blk.info
     ext = W.output_extent(root)
-    odt = torch.int32 if root.refs[-1].dtype == "i32" else torch.float32
+    odt = {"i32": torch.int32, "bf16": torch.bfloat16}.get(root.refs[-1].dtype, torch.float32)
 
-    set_bytes = sum(t.numel() * t.element_size() for t in inputs) + ext * 4
+    set_bytes = sum(t.numel() * t.element_size() for t in inputs) + ext * (2 if odt == torch.bfloat16 else 4)
     n_sets = args.rotate
     if n_sets < 1:
         n_sets = 1 if bound in ("mfma", "alu") else max(2, int(640e6 // set_bytes) + 1)

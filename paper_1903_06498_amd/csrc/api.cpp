@@ -34,6 +34,7 @@ struct stripe_block {
   std::vector<int64_t> temp_bytes;   // root refinement -> bytes of the temporary, 0 otherwise
   std::vector<void*> temp_ptr;
   int temp_dev = -1;
+  int fused = 0;                     // 1, 2: the two statements run as one convolution kernel with a bias+relu epilogue (fp32 / bf16 output)
   ~stripe_block() {
     for (Stage& st : stages) delete st.blk;
     for (void* t : temp_ptr)
@@ -143,6 +144,35 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
     }
     prog->stages.push_back(stage);
   }
+  // Fusion and scalarisation (Section 2.3): a convolution into a temporary followed by O = relu(T + bias[k]) over
+  // the same dense image runs as one kernel whose accumulators are the temporary, which then needs no memory.
+  if (prog->stages.size() == 2 && tune_int("fuse", 1)) {
+    const Stage &s0 = prog->stages[0], &s1 = prog->stages[1];
+    const Plan& c = s0.blk->plan;
+    const FlatBlock& e = s1.blk->plan.flat;
+    bool ok = c.info.path == STRIPE_PATH_MFMA_CONV && c.in_dtype == STRIPE_BF16 && conv_can_fuse_bias_relu(c.conv, s0.blk->conv) &&
+              root->refs[s0.dst].dir == STRIPE_TEMP && s1.n_in == 2 && s1.src[0] == s0.dst && !e.empty && e.intrinsic == STRIPE_INTR_ADD_RELU &&
+              e.cons.empty() && e.n_refs == 3 && e.n_idx >= 2 && e.ref[0].dtype == STRIPE_F32 && e.ref[1].dtype == STRIPE_F32;
+    if (ok) {
+      // the second statement as its address maps see it: one merged pixel index and the channel index
+      std::vector<int64_t> rng, ct, cbias, co;
+      address_form(e, 2, &rng, &ct, &cbias, &co);
+      const int64_t pixels = c.conv.N * c.conv.H * c.conv.W;
+      ok = rng.size() == 2;
+      if (ok) {
+        const int k = (rng[0] == c.conv.Co && cbias[0] == 1) ? 0 : 1, px = 1 - k;
+        ok = rng[k] == c.conv.Co && rng[px] == pixels && ct[k] == 1 && cbias[k] == 1 && co[k] == 1 && ct[px] == c.conv.Co && cbias[px] == 0 &&
+             co[px] == c.conv.Co && e.ref[0].addr.k == 0 && e.ref[1].addr.k % 4 == 0 && e.ref[2].addr.k == 0;
+      }
+      if (ok) {
+        prog->fused = e.out_bf16 ? 2 : 1;
+        prog->plan.conv = c.conv;
+        prog->conv = s0.blk->conv;
+        prog->plan.gemm.b_base = e.ref[1].addr.k;   // element offset of the bias inside its buffer
+        prog->temp_bytes[s0.dst] = 0;               // scalarised away
+      }
+    }
+  }
   // what the program as a whole looks like from outside
   stripe_block_info_t& info = prog->plan.info;
   info = prog->stages[0].blk->plan.info;
@@ -162,6 +192,7 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
       for (int d = 0; d < root->refs[r].ndim; ++d) n *= root->refs[r].sizes[d];
       info.algorithmic_bytes += n * (root->refs[r].dtype == STRIPE_I8 ? 1 : root->refs[r].dtype == STRIPE_BF16 ? 2 : 4);
     }
+  if (prog->fused) names = std::string(prog->stages[0].blk->plan.info.kernel) + (prog->fused == 2 ? "+bias_relu_bf16" : "+bias_relu");
   std::snprintf(info.kernel, sizeof info.kernel, "%s", names.c_str());
   *out = prog;
   return STRIPE_OK;
@@ -181,6 +212,14 @@ stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void*
     prog->temp_dev = dev;
   }
   const int R = (int)prog->input_slot.size();
+  if (prog->fused) {
+    const Stage &s0 = prog->stages[0], &s1 = prog->stages[1];
+    const float* bias = (const float*)inputs[prog->input_slot[s1.src[1]]] + prog->plan.gemm.b_base;
+    e = launch_conv_bias_relu(prog->plan.conv, prog->conv, inputs[prog->input_slot[s0.src[0]]], inputs[prog->input_slot[s0.src[1]]], bias,
+                              output, prog->fused == 2, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(STRIPE_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+    return STRIPE_OK;
+  }
   auto where = [&](int r) -> const void* {
     if (r == R - 1) return output;
     return prog->input_slot[r] >= 0 ? inputs[prog->input_slot[r]] : prog->temp_ptr[r];

@@ -38,6 +38,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 typedef __attribute__((ext_vector_type(4))) float f32x4s;
+typedef __attribute__((ext_vector_type(2))) unsigned u32x2s;
 
 struct ConvParams {
   int32_t N, H, W, strips_per_image, rows, pad_;
@@ -190,9 +191,15 @@ __device__ __forceinline__ void c_load_lds16(const void* src, unsigned lds_off) 
 // through registers, the filter in three slices ordered by filter column j.  The first row group of each team
 // starts as soon as the rows and the first slice have landed and meets the other two slices on the way, so the
 // first stores leave earlier; no LDS-store instructions and no staging registers are spent.
-template <int TEAMS, bool DMA = false>
+//
+// EPI: what happens to a finished accumulator on its way out.  0: stored as it is.  1 and 2: the fused form of
+// a following statement O = relu(T + bias[k]) whose temporary T is this block's output (Section 2.3, fusion and
+// scalarisation: T never exists in memory, it lives in the accumulators): bias added, relu applied, stored as
+// fp32 (1) or rounded to bf16 (2).  `O` then points at that statement's output buffer.
+template <int TEAMS, bool DMA = false, int EPI = 0>
 __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const ConvParams p, const uint16_t* __restrict__ I,
-                                                                        const uint16_t* __restrict__ F, float* __restrict__ O) {
+                                                                        const uint16_t* __restrict__ F, void* __restrict__ O,
+                                                                        const float* __restrict__ bias) {
   static_assert(!DMA || TEAMS == 2, "the LDS-direct staging is written for eight wavefronts");
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   unsigned char* lf = lds;
@@ -302,7 +309,10 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   constexpr int OT_BYTES = 4096 / TEAMS, OT_PIXELS = 32 / TEAMS;    // a fragment leaves in TEAMS rounds of OT_PIXELS pixels
   unsigned char* ot = lp + patch_bytes + wave * OT_BYTES;
   const int sp = lane >> 3, sc = lane & 7;          // store phase: pixel sp (+8j) of the fragment, channel quad sc
-  char* og = (char*)(O + p.o_base + (int64_t)n * p.o_n) + (nh * 32 + sc * 4) * 4;
+  constexpr int OB = EPI == 2 ? 2 : 4;               // bytes per output element
+  char* og = (char*)O + (p.o_base + (int64_t)n * p.o_n + nh * 32 + sc * 4) * OB;
+  f32x4s bias4 = {0.f, 0.f, 0.f, 0.f};               // the lane's four channels in the store phase
+  if constexpr (EPI != 0) bias4 = *(const f32x4s*)(bias + nh * 32 + sc * 4);
   unsigned char* wbase[4];     // write address of accumulator elements v = 0..3 (pixel 4*fh + v); + 1 KB per further 8 pixels
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
@@ -315,7 +325,7 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   for (int j = 0; j < 4; ++j) {
     const int x = mh * 32 + sp + 8 * j;
     ovalid[j] = x < p.W;
-    ooff[j] = (uint32_t)((x < p.W ? x : 0) * (int)p.o_x) * 4u;
+    ooff[j] = (uint32_t)((x < p.W ? x : 0) * (int)p.o_x) * (unsigned)OB;
   }
 
   // Output rows are finished in three groups (3 + 2 + 2 rows) rather than all at the end, so that the stores
@@ -375,7 +385,7 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
     for (int r = 0; r < NR; ++r) {
       const int y = y0 + R0 + r;
       if (y < p.H) {                                   // uniform
-        char* orow = og + (int64_t)y * p.o_y * 4;
+        char* orow = og + (int64_t)y * p.o_y * OB;
 #pragma unroll
         for (int h = 0; h < TEAMS; ++h) {
           constexpr int G = 4 / TEAMS;               // groups of 8 pixels per round
@@ -385,8 +395,25 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
 #pragma unroll
           for (int j = 0; j < G; ++j) {
             const int pixel = sp + 8 * j;            // within the round; (pixel & 7) == sp either way
-            const f32x4s v = *(const f32x4s*)(ot + pixel * 128 + ((sc ^ (pixel & 7)) << 4));
-            if (ovalid[h * G + j]) __builtin_nontemporal_store(v, (f32x4s*)(orow + ooff[h * G + j]));
+            f32x4s v = *(const f32x4s*)(ot + pixel * 128 + ((sc ^ (pixel & 7)) << 4));
+            if constexpr (EPI != 0) {
+              v.x = __builtin_fmaxf(v.x + bias4.x, 0.f);   // relu; a NaN becomes 0
+              v.y = __builtin_fmaxf(v.y + bias4.y, 0.f);
+              v.z = __builtin_fmaxf(v.z + bias4.z, 0.f);
+              v.w = __builtin_fmaxf(v.w + bias4.w, 0.f);
+            }
+            if constexpr (EPI == 2) {
+              // fp32 -> bf16, round to nearest even, two values per conversion instruction
+              typedef float f32x2c __attribute__((ext_vector_type(2)));
+              typedef __bf16 bf16x2c __attribute__((ext_vector_type(2)));
+              const bf16x2c lo = __builtin_convertvector((f32x2c){v.x, v.y}, bf16x2c), hi = __builtin_convertvector((f32x2c){v.z, v.w}, bf16x2c);
+              u32x2s packed = {__builtin_bit_cast(unsigned, lo), __builtin_bit_cast(unsigned, hi)};
+              // (a wavefront holds 32 of a pixel's 64 channels, i.e. half a 128-byte line of bf16; plain stores that
+              // leave the merging of the halves to L2 were measured slower than these streaming half-line stores)
+              if (ovalid[h * G + j]) __builtin_nontemporal_store(packed, (u32x2s*)(orow + ooff[h * G + j]));
+            } else {
+              if (ovalid[h * G + j]) __builtin_nontemporal_store(v, (f32x4s*)(orow + ooff[h * G + j]));
+            }
           }
           __builtin_amdgcn_wave_barrier();
         }
@@ -488,7 +515,27 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
   return true;
 }
 
+bool conv_can_fuse_bias_relu(const Conv2dShape& c, const ConvLaunch& l) {
+  // the LDS-direct row-group kernel, writing a dense [n][y][x][k] image (the fused statement's output shares its layout)
+  return l.variant == kConvW4Variant + 3 && c.o_x == C_CO && (c.H == 1 || c.o_y == c.W * C_CO) && (c.N == 1 || c.o_n == c.H * c.W * C_CO) &&
+         c.o_base == 0;
+}
+
+static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias,
+                                  int epi, hipStream_t st);
+
+hipError_t launch_conv_bias_relu(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, const void* bias, void* out,
+                                 bool out_bf16, hipStream_t st) {
+  if (!conv_can_fuse_bias_relu(c, l) || ((uintptr_t)bias % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
+  return launch_conv_epi(c, l, in, flt, out, bias, out_bf16 ? 2 : 1, st);
+}
+
 hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
+  return launch_conv_epi(c, l, in, flt, out, nullptr, 0, st);
+}
+
+static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias,
+                                  int epi, hipStream_t st) {
   if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
   if (l.variant > kConvW4Variant) {
@@ -498,8 +545,10 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
     pp.pad_ = (int32_t)(uint32_t)((((uint64_t)1 << 32) + pw - 1) / pw);   // reciprocal of the patch width, for the LDS-direct staging
     const int patch = (W4_ROWS + 2) * ((int)c.W + 2) * 128;
     const int lds_w4 = C_FILTER_BYTES + (mode == 3 ? ((patch + 1023) & ~1023) : patch) + W4_LDS_EXTRA;
-    typedef void (*kern_t)(const ConvParams, const uint16_t*, const uint16_t*, float*);
-    const kern_t fn = mode == 3 ? (kern_t)conv3x3_bf16_w4_kernel<2, true> : mode == 2 ? (kern_t)conv3x3_bf16_w4_kernel<2, false>
+    typedef void (*kern_t)(const ConvParams, const uint16_t*, const uint16_t*, void*, const float*);
+    const kern_t fn = (mode == 3 && epi == 1) ? (kern_t)conv3x3_bf16_w4_kernel<2, true, 1>
+                    : (mode == 3 && epi == 2) ? (kern_t)conv3x3_bf16_w4_kernel<2, true, 2>
+                    : mode == 3 ? (kern_t)conv3x3_bf16_w4_kernel<2, true> : mode == 2 ? (kern_t)conv3x3_bf16_w4_kernel<2, false>
                                                                                       : (kern_t)conv3x3_bf16_w4_kernel<1, false>;
     int dev4 = -1;
     hipError_t e4 = hipGetDevice(&dev4);
@@ -510,7 +559,7 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
       l.lds_enabled_on = dev4;
     }
     hipLaunchKernelGGL(fn, dim3((unsigned)l.grid), dim3(mode == 1 ? 256 : 512), lds_w4, st, pp, (const uint16_t*)in,
-                       (const uint16_t*)flt, (float*)out);
+                       (const uint16_t*)flt, out, (const float*)bias);
     return hipGetLastError();
   }
   const int rows = l.variant;

@@ -45,6 +45,11 @@ struct ConvLaunch {
 };
 bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
 hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);
+// The 3x3 bf16 kernel fused with a following statement O = relu(T + bias[k]) (T = the convolution's output):
+// bias fp32 [64], out fp32 or bf16 in the convolution output's dense layout.
+bool conv_can_fuse_bias_relu(const Conv2dShape& c, const ConvLaunch& l);
+hipError_t launch_conv_bias_relu(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, const void* bias, void* out,
+                                 bool out_bf16, hipStream_t stream);
 // strided 7x7 int8 variant (dispatched to by conv_select / launch_conv)
 bool conv_i8_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
 hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);

@@ -569,28 +569,35 @@ bool distinct(std::initializer_list<int> ids) {
 
 }  // namespace
 
-bool match_gemm(const FlatBlock& fb, GemmShape* g) {
-  if (fb.empty || fb.n_refs != 3 || fb.intrinsic != STRIPE_INTR_MUL || fb.agg != STRIPE_AGG_ADD) return false;
-  if (fb.n_idx < 3 || !fb.cons.empty()) return false;
-  // Only the three address maps matter here.  Indexes that all of them use as outer*range + inner are one
-  // index as far as addresses go, even when they are separate buffer dimensions (the pixels n, y, x of a
-  // 1x1 convolution over dense tensors): merge such pairs until none is left.
-  std::vector<int64_t> rng(fb.range, fb.range + fb.n_idx);
-  std::vector<int64_t> ca(fb.ref[0].addr.c, fb.ref[0].addr.c + fb.n_idx), cb(fb.ref[1].addr.c, fb.ref[1].addr.c + fb.n_idx),
-      cc(fb.ref[2].addr.c, fb.ref[2].addr.c + fb.n_idx);
-  for (bool merged = true; merged && rng.size() > 3;) {
+// The block as its three address maps see it.  Indexes that all of them use as outer*range + inner are one index
+// as far as addresses go, even when they are separate buffer dimensions (the pixels n, y, x of dense NHWC
+// tensors): such pairs are merged until none is left or `target` indexes remain.  Constraint-free blocks only.
+void address_form(const FlatBlock& fb, size_t target, std::vector<int64_t>* rng, std::vector<int64_t>* ca, std::vector<int64_t>* cb,
+                  std::vector<int64_t>* cc) {
+  rng->assign(fb.range, fb.range + fb.n_idx);
+  ca->assign(fb.ref[0].addr.c, fb.ref[0].addr.c + fb.n_idx);
+  cb->assign(fb.ref[1].addr.c, fb.ref[1].addr.c + fb.n_idx);
+  cc->assign(fb.ref[2].addr.c, fb.ref[2].addr.c + fb.n_idx);
+  for (bool merged = true; merged && rng->size() > target;) {
     merged = false;
-    for (size_t o = 0; o < rng.size() && !merged; ++o)
-      for (size_t i = 0; i < rng.size() && !merged; ++i) {
+    for (size_t o = 0; o < rng->size() && !merged; ++o)
+      for (size_t i = 0; i < rng->size() && !merged; ++i) {
         if (o == i) continue;
-        auto nests = [&](const std::vector<int64_t>& x) { return (i128)x[o] == (i128)x[i] * rng[i]; };
-        if (nests(ca) && nests(cb) && nests(cc) && (i128)rng[i] * rng[o] < ((i128)1 << 62)) {
-          rng[i] *= rng[o];
-          for (auto* v : {&rng, &ca, &cb, &cc}) v->erase(v->begin() + o);
+        auto nests = [&](const std::vector<int64_t>& x) { return (i128)x[o] == (i128)x[i] * (*rng)[i]; };
+        if (nests(*ca) && nests(*cb) && nests(*cc) && (i128)(*rng)[i] * (*rng)[o] < ((i128)1 << 62)) {
+          (*rng)[i] *= (*rng)[o];
+          for (auto* v : {rng, ca, cb, cc}) v->erase(v->begin() + o);
           merged = true;
         }
       }
   }
+}
+
+bool match_gemm(const FlatBlock& fb, GemmShape* g) {
+  if (fb.empty || fb.n_refs != 3 || fb.intrinsic != STRIPE_INTR_MUL || fb.agg != STRIPE_AGG_ADD) return false;
+  if (fb.n_idx < 3 || !fb.cons.empty()) return false;
+  std::vector<int64_t> rng, ca, cb, cc;
+  address_form(fb, 3, &rng, &ca, &cb, &cc);
   if (rng.size() != 3) return false;
   int m = -1, n = -1, k = -1;
   for (int j = 0; j < 3; ++j) {

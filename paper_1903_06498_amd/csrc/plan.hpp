@@ -141,6 +141,8 @@ bool match_conv2d(const FlatBlock& fb, Conv2dShape* c);
 bool match_pool2d(const FlatBlock& fb, Pool2dShape* p);
 
 int64_t count_points(const FlatBlock& fb, int64_t enumeration_cap);
+void address_form(const FlatBlock& fb, size_t target, std::vector<int64_t>* rng, std::vector<int64_t>* ca, std::vector<int64_t>* cb,
+                  std::vector<int64_t>* cc);
 
 // Records the calling thread's error detail (what stripe_last_error() returns) and passes the status through.
 stripe_status_t api_fail(stripe_status_t st, const std::string& msg);

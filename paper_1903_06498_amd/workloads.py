@@ -340,7 +340,8 @@ def conv_bias_relu_program(N, H, W, Ci, Co, R, S, stride, pad, in_dtype="bf16", 
 
 
 # Further shapes the kernel families cover, for measurements beyond the five configurations (bench.py --workload).
-EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32")
+EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32",
+               "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32")
 
 
 def extra_block(name: str) -> Block:
@@ -350,6 +351,10 @@ def extra_block(name: str) -> Block:
         return matmul_block(4000, 4000, 4096, "bf16", "f32")
     if name == "gemm_i8_4096_bt":
         return matmul_block(4096, 4096, 4096, "i8", "i32", b_transposed=True)
+    if name == "resnet_conv_bias_relu_bf16":   # the ResNet block followed by O = relu(T + bias), bf16 output: two statements
+        return conv_bias_relu_program(32, 56, 56, 64, 64, 3, 3, 1, 1, "bf16", "bf16")
+    if name == "resnet_conv_bias_relu_f32":    # the same with an fp32 output
+        return conv_bias_relu_program(32, 56, 56, 64, 64, 3, 3, 1, 1, "bf16", "f32")
     if name == "pointwise_conv_bf16":          # 1x1 convolution, 256 -> 64 channels on the ResNet block's 32 x 56 x 56 pixels
         bufs = [Buffer("I", "in", "bf16", (32, 56, 56, 256)), Buffer("F", "in", "bf16", (64, 256)),
                 Buffer("O", "out", "f32", (32, 56, 56, 64))]
@@ -365,6 +370,8 @@ def extra_block(name: str) -> Block:
 
 
 def extra_inputs(name: str):
+    if name in ("resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32"):
+        return config_inputs("resnet_conv_bf16") + [seeded_tensor((64,), "f32", 2)]
     blk = extra_block(name)
     return [seeded_tensor(r.sizes, r.dtype, seed) for seed, r in enumerate(blk.refs[:-1])]
 

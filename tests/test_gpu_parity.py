@@ -279,6 +279,44 @@ def test_two_statement_program_small(shape, in_dt, out_dt):
     assert " ; " in info["kernel"], info["kernel"]
 
 
+@pytest.mark.parametrize("fuse", [1, 0])
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+@pytest.mark.parametrize("N,H,Wd", [(2, 10, 13), (1, 7, 56), (2, 15, 31)])
+def test_fused_convolution_bias_relu(N, H, Wd, out_dt, fuse, monkeypatch):
+    """3x3, 64 -> 64 channels: the planner fuses the two statements into the matrix-core convolution kernel with a
+    bias + relu epilogue (the temporary stays in the accumulators); with fuse=0 the same program runs as two
+    launches through a real temporary.  Both against the oracle's serial evaluation."""
+    monkeypatch.setenv("STRIPE_TUNE", f"fuse={fuse}")
+    info = program_parity(N, H, Wd, 64, 64, 3, 1, 1, "bf16", out_dt)
+    if fuse:
+        assert info["kernel"].endswith("+bias_relu" + ("_bf16" if out_dt == "bf16" else "")) and info["path_name"] == "mfma_conv", info["kernel"]
+    else:
+        assert " ; " in info["kernel"], info["kernel"]
+
+
+def test_fused_convolution_bias_relu_full_size():
+    """The ResNet-shaped block with a bf16 output, fused: all-ones closed form on every element, and the seeded
+    inputs against the unfused two-launch execution of the same program (which the small cases pin to the oracle)."""
+    prog = W.extra_block("resnet_conv_bias_relu_bf16")
+    ins = W.extra_inputs("resnet_conv_bias_relu_bf16")
+    ones = [torch.ones_like(ins[0]), torch.ones_like(ins[1]), -40.0 * torch.arange(64, dtype=torch.float32)]
+    gpu, sb = run_gpu(prog, ones, return_block=True)
+    assert sb.info["kernel"].endswith("+bias_relu_bf16"), sb.info["kernel"]
+    cy = np.array([taps(y, 1, 1, 3, 56) for y in range(56)])
+    t = 64.0 * cy[:, None] * cy[None, :]
+    want = np.maximum(t[:, :, None] - 40.0 * np.arange(64)[None, None, :], 0.0)          # all exactly representable in bf16
+    assert np.array_equal(gpu.reshape(32, 56, 56, 64), np.broadcast_to(want[None], (32, 56, 56, 64)))
+    fused = run_gpu(prog, ins)
+    import os
+    os.environ["STRIPE_TUNE"] = "fuse=0"
+    try:
+        unfused = run_gpu(prog, ins)
+    finally:
+        del os.environ["STRIPE_TUNE"]
+    # same fp32 sums up to summation order, then one rounding to bf16: at most one bf16 step apart
+    assert np.all(np.abs(fused - unfused) <= 2.0 ** -7 * np.maximum(np.abs(unfused), 2.0 ** -10))
+
+
 # ------------------------------------------------------------------ blocks produced by the tiling rewrite
 @pytest.mark.parametrize("case", ["pool_ragged", "conv_bf16", "matmul_f32", "fig5_ragged"])
 def test_rewritten_nests_run_like_their_flat_forms(case):
