@@ -250,6 +250,7 @@ stripe_status_t create_single(const stripe_block_desc_t* desc, stripe_path_t pat
   blk->n_inputs = fb.n_refs - 1;
   Plan& p = blk->plan;
   if (tune_int("generic_i64", 0)) p.gen.narrow = 0;   // test hook: 64-bit index arithmetic in the generic kernel
+  if (tune_int("generic_i64", 0) || !tune_int("generic_point4", 1)) p.gen.point4 = 0;
   if (tune_int("generic_i64", 0) || !tune_int("generic_tiled", 1)) p.tiled.use = 0;
   else if (tune_int("generic_tiled", 1) == 2 && p.tiled.n_items > 0) p.tiled.use = 1;   // test hook: tiled kernel also for small blocks
   if (!p.noop) {

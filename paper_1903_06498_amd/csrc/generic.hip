@@ -258,6 +258,69 @@ __global__ __launch_bounds__(256) void generic_kernel(const GenericParams p, con
   }
 }
 
+// Pointwise blocks: no reduction, no constraints, every lane computes four consecutive outputs along the fastest
+// output index (vector loads where an input follows that index, a broadcast where it does not; one vector store).
+template <typename TIn, int INTR>
+__global__ __launch_bounds__(256) void generic_point4_kernel(const GenericParams p, const void* __restrict__ in0,
+                                                             const void* __restrict__ in1, void* __restrict__ out) {
+  using Acc = typename Elem<TIn>::Acc;
+  typedef TIn in4 __attribute__((ext_vector_type(4)));
+  typedef Acc acc4 __attribute__((ext_vector_type(4)));
+  uint32_t t = blockIdx.x * 256u + threadIdx.x;
+  if ((int64_t)t >= p.n_outputs / 4) return;
+  const uint32_t q0 = (uint32_t)p.out_range[0] / 4u;
+  const int o0 = (int)(t % q0) * 4;
+  t /= q0;
+  int offA = (int)p.a_base + (int)p.a_out[0] * o0, offB = (int)p.b_base + (int)p.b_out[0] * o0, offO = (int)p.o_base + o0;
+  for (int j = 1; j < p.n_out; ++j) {
+    const uint32_t rng = (uint32_t)p.out_range[j];
+    const int o = (int)(t % rng);
+    t /= rng;
+    offA += (int)p.a_out[j] * o;
+    offB += (int)p.b_out[j] * o;
+    offO += (int)p.o_out[j] * o;
+  }
+  auto fetch = [](const void* base, int off, bool follows) {
+    in4 r;
+    if (follows) {
+      r = *(const in4*)((const TIn*)base + off);
+    } else {
+      const TIn s = ((const TIn*)base)[off];
+      r = (in4){s, s, s, s};
+    }
+    return r;
+  };
+  auto widen = [](TIn x) -> Acc {
+    if constexpr (std::is_same<TIn, uint16_t>::value) return __uint_as_float((uint32_t)x << 16);
+    else return (Acc)x;
+  };
+  const in4 a = fetch(in0, offA, p.a_out[0] == 1);
+  in4 b = a;
+  if (INTR != STRIPE_INTR_COPY) b = fetch(in1, offB, p.b_out[0] == 1);
+  acc4 v;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const Acc x = widen(a[e]), y = widen(b[e]);
+    Acc r = INTR == STRIPE_INTR_COPY ? x : INTR == STRIPE_INTR_MUL ? x * y : x + y;
+    if (INTR == STRIPE_INTR_ADD_RELU) r = r > (Acc)0 ? r : (Acc)0;
+    v[e] = r;
+  }
+  if (std::is_same<Acc, float>::value && p.out_bf16) {
+    typedef __bf16 bf4 __attribute__((ext_vector_type(4)));
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    *(bf4*)((uint16_t*)out + offO) = __builtin_convertvector((f4){(float)v[0], (float)v[1], (float)v[2], (float)v[3]}, bf4);   // round to nearest even
+  } else {
+    *(acc4*)((Acc*)out + offO) = v;
+  }
+}
+
+template <typename TIn, int INTR>
+hipError_t launch_point4(const GenericParams& p, const void* a, const void* b, void* o, hipStream_t s) {
+  const int64_t grid = (p.n_outputs / 4 + 255) / 256;
+  hipLaunchKernelGGL((generic_point4_kernel<TIn, INTR>), dim3((unsigned)grid), dim3(256), 0, s, p, a, b, o);
+  return hipGetLastError();
+}
+
 template <typename TIn, int INTR, int AGG>
 hipError_t launch_lanes(const GenericParams& p, const void* a, const void* b, void* o, hipStream_t s) {
   const int64_t grid = p.lanes == 64 ? (p.n_outputs + 3) / 4 : (p.n_outputs + 255) / 256;
@@ -285,6 +348,15 @@ hipError_t launch_agg(int agg, const GenericParams& p, const void* a, const void
 
 template <typename TIn>
 hipError_t launch_intr(int intr, int agg, const GenericParams& p, const void* a, const void* b, void* o, hipStream_t s) {
+  // the four-outputs-per-lane form needs the buffers themselves 16-byte aligned
+  if (p.point4 && !((uintptr_t)a % 16) && !((uintptr_t)o % 16) && (intr == STRIPE_INTR_COPY || !((uintptr_t)b % 16))) {
+    switch (intr) {
+      case STRIPE_INTR_COPY: return launch_point4<TIn, STRIPE_INTR_COPY>(p, a, b, o, s);
+      case STRIPE_INTR_ADD: return launch_point4<TIn, STRIPE_INTR_ADD>(p, a, b, o, s);
+      case STRIPE_INTR_ADD_RELU: return launch_point4<TIn, STRIPE_INTR_ADD_RELU>(p, a, b, o, s);
+      default: return launch_point4<TIn, STRIPE_INTR_MUL>(p, a, b, o, s);
+    }
+  }
   switch (intr) {
     case STRIPE_INTR_COPY: return launch_agg<TIn, STRIPE_INTR_COPY>(agg, p, a, b, o, s);
     case STRIPE_INTR_ADD: return launch_agg<TIn, STRIPE_INTR_ADD>(agg, p, a, b, o, s);
@@ -327,6 +399,11 @@ void generic_info(const Plan& plan, stripe_block_info_t* info) {
   info->lds_bytes = 0;
   info->workgroup_size = 256;
   info->grid = p.lanes == 64 ? (p.n_outputs + 3) / 4 : (p.n_outputs + 255) / 256;
+  if (p.point4) {
+    info->grid = (p.n_outputs / 4 + 255) / 256;
+    snprintf(info->kernel, sizeof info->kernel, "generic_pointwise_x4");
+    return;
+  }
   snprintf(info->kernel, sizeof info->kernel, "generic_affine_%s%s%s", p.lanes == 64 ? "wave_per_output" : "lane_per_output",
            p.narrow ? "" : "_i64", p.atomic ? "_atomic" : "");
 }

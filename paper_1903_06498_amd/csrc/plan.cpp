@@ -858,6 +858,17 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
     g.narrow = narrow ? 1 : 0;
     g.atomic = injective ? 0 : 1;
     g.out_bf16 = fb.out_bf16 ? 1 : 0;
+    // Pointwise blocks (every index moves the output, no constraints): four consecutive outputs per lane when the
+    // fastest output index has unit stride in the output, stride 0 or 1 in the inputs, and everything else keeps
+    // 4-element alignment.
+    {
+      bool p4 = narrow && injective && g.n_red == 0 && fb.cons.empty() && g.n_out >= 1 && g.out_range[0] % 4 == 0 && g.o_out[0] == 1 &&
+                (g.a_out[0] == 0 || g.a_out[0] == 1) && (!B || g.b_out[0] == 0 || g.b_out[0] == 1) && g.o_base % 4 == 0 &&
+                (g.a_out[0] == 0 || g.a_base % 4 == 0) && (!B || g.b_out[0] == 0 || g.b_base % 4 == 0);
+      for (int t = 1; t < g.n_out && p4; ++t)
+        p4 = g.o_out[t] % 4 == 0 && (g.a_out[0] == 0 || g.a_out[t] % 4 == 0) && (!B || g.b_out[0] == 0 || g.b_out[t] % 4 == 0);
+      g.point4 = p4 ? 1 : 0;
+    }
 
     // Register-tiled variant for sum-of-products blocks with enough parallelism (see TiledParams).
     TiledParams& tp = plan->tiled;

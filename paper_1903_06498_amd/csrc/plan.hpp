@@ -92,6 +92,7 @@ struct GenericParams {
   int64_t cons_const[kGenCons];
   int64_t n_outputs;
   uint32_t red_total, inner_range;
+  int32_t point4, pad_;            // point4 1: no reduction, no constraints, four consecutive outputs per lane (vector loads and stores)
   int32_t atomic, out_bf16;        // atomic 1: output map not injective on the output indexes -> identity pass + atomic combine
 };
 

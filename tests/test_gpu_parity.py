@@ -214,6 +214,29 @@ def test_tiled_generic_shapes(shape, dtype, monkeypatch):
     assert info["kernel"] == want, info["kernel"]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "i8", "i32"])
+@pytest.mark.parametrize("intrinsic", ["copy", "add", "mul", "add_relu"])
+@pytest.mark.parametrize("broadcast", ["none", "second_over_rows", "second_scalar_per_row"])
+def test_pointwise_blocks_four_per_lane(intrinsic, dtype, broadcast):
+    """O[a,b,c] = f(A[a,b,c], B[...]) without reduction: the four-outputs-per-lane kernel with a full second operand,
+    one broadcast over the outer indexes (B[c]) and one broadcast along the fastest index (B[a,b]); and the plain
+    kernel when the fastest range is not a multiple of 4.  Exact for integers, copy and add of exact values."""
+    odt = "i32" if dtype in ("i8", "i32") else "f32"
+    for shape in ((5, 7, 24), (3, 4, 10)):
+        a_, b_, c_ = shape
+        bshape, bacc = {"none": (shape, ["a", "b", "c"]), "second_over_rows": ((c_,), ["c"]),
+                        "second_scalar_per_row": ((a_, b_), ["a", "b"])}[broadcast]
+        bufs = [W.Buffer("A", "in", dtype, shape)] + ([] if intrinsic == "copy" else [W.Buffer("B", "in", dtype, bshape)]) + \
+               [W.Buffer("O", "out", odt, shape)]
+        refs = [(["a", "b", "c"], "assign")] + ([] if intrinsic == "copy" else [(bacc, "assign")]) + [(["a", "b", "c"], "assign")]
+        blk = W.flat_block(bufs, dict(a=a_, b=b_, c=c_), refs, intrinsic=intrinsic)
+        ins = [W.seeded_tensor(shape, dtype, 0)] + ([] if intrinsic == "copy" else [W.seeded_tensor(bshape, dtype, 1)])
+        if dtype == "i32":
+            ins = [t // 40 for t in ins]                      # keep products inside int32
+        info, _ = parity(blk, ins, "generic", what=f"pointwise {intrinsic} {dtype} {broadcast} {shape}")
+        assert (info["kernel"] == "generic_pointwise_x4") == (c_ % 4 == 0), info["kernel"]
+
+
 def test_product_aggregation_float():
     """O[a] = prod over r of (A[a, r] + B[r]) in fp32 against the fp64 oracle; and a shared-output form O[a + r]."""
     bufs = [W.Buffer("A", "in", "f32", (50, 9)), W.Buffer("B", "in", "f32", (9,)), W.Buffer("O", "out", "f32", (58,))]
