@@ -14,6 +14,10 @@ What is counted, for one tile of a flat block:
     into a set;
   * tiles = product over indexes of ceil(range / tile); work = product of the ranges of the tiled indexes;
   * cost = tiles * lines / work.
+
+Pinned by the two costs Figure 4 prints for admissible tiles (4.5 and 4.666) and by the tile it shows as excluded.
+The figure's fourth cost, 5.625, is not reproduced by any tile under this reading of the caption: parity unpinned
+for that one number.
 """
 from itertools import product
 
