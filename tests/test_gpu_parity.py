@@ -248,6 +248,30 @@ def test_product_aggregation_float():
         assert info["kernel"].endswith("_atomic") == (out_access != "a")
 
 
+def test_misaligned_buffers_are_refused_not_launched():
+    """The matrix-core and pooling kernels load 16 bytes at a time: a buffer that is not 16-byte aligned must come
+    back as an error from run (nothing is launched), while the generic path takes any element-aligned pointer."""
+    dev = torch.device("cuda:0")
+    blk = W.matmul_block(256, 256, 128, "bf16", "f32")
+    sb = B.StripeBlock(blk)
+    a = torch.zeros(256 * 128 + 8, dtype=torch.bfloat16, device=dev)
+    b = torch.zeros(128 * 256, dtype=torch.bfloat16, device=dev)
+    out = torch.zeros(256 * 256, dtype=torch.float32, device=dev)
+    with pytest.raises(B.StripeError) as e:
+        sb.run([a.data_ptr() + 2, b], out)
+    assert e.value.status == 6
+    sb.run([a, b], out)                                   # the handle is still usable
+    torch.cuda.synchronize()
+    gen = B.StripeBlock(blk, "generic")
+    ones = torch.ones(256 * 128 + 8, dtype=torch.bfloat16, device=dev)
+    gen.run([ones.data_ptr() + 2, torch.ones(128 * 256, dtype=torch.bfloat16, device=dev)], out)
+    torch.cuda.synchronize()
+    assert torch.all(out == 128.0)
+    with pytest.raises(B.StripeError) as e:
+        sb.run([0, b], out)                               # NULL input
+    assert e.value.status == 1
+
+
 def test_unwritten_elements_keep_their_contents():
     bufs = [W.Buffer("A", "in", "i32", (70,)), W.Buffer("O", "out", "i32", (70,))]
     blk = W.flat_block(bufs, dict(x=70, r=3), [(["x"], "assign"), (["x"], "add")],
