@@ -31,6 +31,7 @@ struct GemmParams {
   int32_t M, N;               // used by the variants that accept M, N that are not multiples of the tile
   int64_t a_m, b_k, c_m;      // row strides in elements (a_k = b_n = c_n = 1); for a transposed B ([n][k], k contiguous) b_k holds its row stride
   int64_t a_base, b_base, c_base;
+  int64_t a_b, b_b, c_b;      // element distance between two products of a batch (LDS-direct kernel only)
 };
 
 constexpr int BM = 256, BN = 256, BK = 64;
@@ -595,7 +596,12 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave / WN_WAVES, wn = wave % WN_WAVES;
   int tm, tn;
-  tile_of(blockIdx.x, gridDim.x, p.tiles_m, p.tiles_n, &tm, &tn);
+  // a batch of products: consecutive groups of tiles_m * tiles_n workgroups take consecutive batch entries
+  const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n), batch = blockIdx.x / tiles;
+  A += (int64_t)batch * p.a_b;
+  B += (int64_t)batch * p.b_b;
+  C += (int64_t)batch * p.c_b;
+  tile_of(blockIdx.x - batch * tiles, tiles, p.tiles_m, p.tiles_n, &tm, &tn);
 
   DCtx c;
   // A loads: load u of wavefront w fills LDS rows 16*(WAVES*u+w) .. +15 of the stage (1 KB): lane -> row + lane/4, slot lane&3
@@ -736,12 +742,31 @@ GemmParams make_params(const GemmShape& g, bool i8 = false) {
   p.a_base = i8 ? g.a_base / 2 : g.a_base;
   p.b_base = i8 ? g.b_base / 2 : g.b_base;
   p.c_base = g.c_base;
+  p.a_b = i8 ? g.a_b / 2 : g.a_b;
+  p.b_b = i8 ? g.b_b / 2 : g.b_b;
+  p.c_b = g.c_b;
   return p;
 }
 
 }  // namespace
 
+static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info);
+
 bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info) {
+  if (!gemm_select_one(g, in_dtype, l, info)) return false;
+  if (g.batch > 1) {
+    // a batch of products: only the LDS-direct kernel walks the batch index; batch strides keep the 16-byte alignment
+    const int64_t align = in_dtype == STRIPE_I8 ? 16 : 8;
+    if (l->variant < 20 || g.a_b % align || g.b_b % align || g.batch > 0x7fffffffLL / l->grid) return false;
+    l->grid *= g.batch;
+    info->grid = l->grid;
+    const size_t n = strlen(info->kernel);
+    snprintf(info->kernel + n, sizeof info->kernel - n, "_batch");
+  }
+  return true;
+}
+
+static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info) {
   if (in_dtype == STRIPE_I8) {
     // int8 x int8 -> int32 with both operands k-contiguous (C = A * B^T); K tiles of 64 bytes, four in flight
     if (g.a_k != 1 || g.c_n != 1 || g.b_k != 1 || g.b_n == 1 || tune_int("gemm_dma", 1) == 0) return false;

@@ -598,6 +598,17 @@ bool match_gemm(const FlatBlock& fb, GemmShape* g) {
   if (fb.n_idx < 3 || !fb.cons.empty()) return false;
   std::vector<int64_t> rng, ca, cb, cc;
   address_form(fb, 3, &rng, &ca, &cb, &cc);
+  g->batch = 1;
+  g->a_b = g->b_b = g->c_b = 0;
+  if (rng.size() == 4) {   // one more index that moves all three operands: a batch of independent products
+    int bi = -1;
+    for (int j = 0; j < 4; ++j)
+      if (ca[j] && cb[j] && cc[j]) bi = bi < 0 ? j : 4;
+    if (bi < 0 || bi > 3 || ca[bi] < 0 || cb[bi] < 0 || cc[bi] < 0) return false;
+    g->batch = rng[bi];
+    g->a_b = ca[bi]; g->b_b = cb[bi]; g->c_b = cc[bi];
+    for (auto* v : {&rng, &ca, &cb, &cc}) v->erase(v->begin() + bi);
+  }
   if (rng.size() != 3) return false;
   int m = -1, n = -1, k = -1;
   for (int j = 0; j < 3; ++j) {

@@ -55,10 +55,11 @@ struct FlatBlock {
   bool empty = false;               // some range is 0 or the constraints exclude every point
 };
 
-struct GemmShape {       // C[m,n] (+)= A[m,k] * B[k,n]
+struct GemmShape {       // C[b,m,n] (+)= A[b,m,k] * B[b,k,n]   (batch = 1: no batch index)
   int64_t M, N, K;
   int64_t a_m, a_k, b_k, b_n, c_m, c_n;   // element strides
   int64_t a_base, b_base, c_base;
+  int64_t batch, a_b, b_b, c_b;           // batch count and element strides of the batch index (every operand moves with it)
 };
 
 struct Conv2dShape {     // O[n,y,x,k] (+)= I[n, s*y+i-p, s*x+j-q, c] * F[i,j,k,c]  (any strides)

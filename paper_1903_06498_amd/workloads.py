@@ -232,6 +232,17 @@ def matmul_block(M, N, K, in_dtype, out_dtype, b_transposed=False) -> Block:
                       intrinsic="mul")
 
 
+def batched_matmul_block(batch, M, N, K, in_dtype, out_dtype, b_transposed=False, shared_b=False) -> Block:
+    """C[b,m,n] += A[b,m,k] * B[b,k,n]: a batch of independent products (with shared_b every product uses one B)."""
+    bshape = (N, K) if b_transposed else (K, N)
+    bacc = ["n", "k"] if b_transposed else ["k", "n"]
+    bufs = [Buffer("A", "in", in_dtype, (batch, M, K)), Buffer("B", "in", in_dtype, bshape if shared_b else (batch,) + bshape),
+            Buffer("C", "out", out_dtype, (batch, M, N))]
+    return flat_block(bufs, dict(b=batch, m=M, n=N, k=K),
+                      [(["b", "m", "k"], "assign"), (bacc if shared_b else ["b"] + bacc, "assign"), (["b", "m", "n"], "add")],
+                      intrinsic="mul")
+
+
 def maxpool_block(N, H, W, C, R, stride, pad, dtype="f32", agg="max") -> Block:
     """O[n,y,x,c] = max (or another aggregation) over in-bounds taps of I[n, s*y+i-p, s*x+j-p, c]; body load -> store."""
     Ho = (H + 2 * pad - R) // stride + 1

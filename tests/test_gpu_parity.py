@@ -534,6 +534,31 @@ def test_gemm_int8_transposed_b(M, N, K):
     assert np.all(run_gpu(blk, lows) == 16384 * K)
 
 
+@pytest.mark.parametrize("batch,M,N,K,dtype,bt,shared", [(3, 256, 256, 128, "bf16", False, False), (2, 300, 200, 128, "bf16", True, False),
+                                                         (5, 70, 264, 256, "bf16", False, False), (2, 256, 256, 256, "i8", True, False),
+                                                         (3, 130, 9, 512, "i8", True, False), (4, 64, 256, 128, "bf16", False, True)])
+def test_batched_gemm(batch, M, N, K, dtype, bt, shared):
+    """C[b] = A[b] * B[b] on the matrix cores: the batch index becomes the slowest part of the grid.  With a B shared
+    by all products the batch merges into M and the block is a plain GEMM.  Position-sensitive operands per batch
+    entry (different shifts), then seeded data against the oracle."""
+    odt = "i32" if dtype == "i8" else "f32"
+    tdt = torch.int8 if dtype == "i8" else torch.bfloat16
+    blk = W.batched_matmul_block(batch, M, N, K, dtype, odt, b_transposed=bt, shared_b=shared)
+    a = ((torch.arange(batch)[:, None, None] * 11 + torch.arange(M)[None, :, None] * 7 + torch.arange(K)[None, None, :] * 3) % 251 - 125).to(tdt)
+    nb = 1 if shared else batch
+    sel = (torch.arange(N)[None, :] + 37 + 5 * torch.arange(nb)[:, None]) % K
+    b = torch.zeros((nb, K, N), dtype=tdt)
+    for i in range(nb):
+        b[i, sel[i], torch.arange(N)] = 1
+    bb = (b.transpose(1, 2) if bt else b).contiguous()
+    gpu, sb = run_gpu(blk, [a, bb[0] if shared else bb], return_block=True)
+    assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"].endswith("_batch") == (not shared), sb.info["kernel"]
+    want = torch.stack([a[i].float()[:, sel[0 if shared else i]] for i in range(batch)]).numpy()
+    assert np.array_equal(gpu.reshape(batch, M, N), want)
+    ins = [W.seeded_tensor(r.sizes, dtype, s_) for s_, r in enumerate(blk.refs[:-1])]
+    parity(blk, ins, what=f"batched gemm {batch}x{M}x{N}x{K} {dtype}")
+
+
 def test_pointwise_convolution_runs_on_the_gemm_kernel():
     """A 1x1 convolution O[n,y,x,k] += I[n,y,x,c] * F[k,c] canonicalises to C = A * B^T (pixels merge into one index)."""
     N, H, Wd, Ci, Co = 2, 12, 20, 128, 72
