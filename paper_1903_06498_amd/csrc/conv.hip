@@ -306,7 +306,7 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   // fragment, channel l&31 of the wavefront's 32.  Each fragment goes through a 4 KB buffer of the wavefront
   // ([pixel][32 channels], behind the patch) and leaves as 16-byte stores: 8 lanes write the 128 contiguous
   // bytes of a pixel's channel half.
-  constexpr int OT_BYTES = 4096 / TEAMS, OT_PIXELS = 32 / TEAMS;    // a fragment leaves in TEAMS rounds of OT_PIXELS pixels
+  constexpr int OT_BYTES = 4096 / TEAMS;             // a fragment leaves in TEAMS rounds of 32 / TEAMS pixels
   unsigned char* ot = lp + patch_bytes + wave * OT_BYTES;
   const int sp = lane >> 3, sc = lane & 7;          // store phase: pixel sp (+8j) of the fragment, channel quad sc
   constexpr int OB = EPI == 2 ? 2 : 4;               // bytes per output element
