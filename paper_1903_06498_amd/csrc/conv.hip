@@ -182,6 +182,8 @@ __device__ __attribute__((aligned(16))) unsigned char conv_zero_chunk[16];
 // LDS-direct 16-byte load: lane i of the wavefront lands at lds_off + 16*i (M0 carries the wave-uniform offset).
 // Written as assembly so that the compiler does not drain the load queue before unrelated LDS reads; the waits
 // are placed by hand (s_waitcnt vmcnt) where the data is first needed.
+// M0 is written here and nowhere else: these kernels index no register array dynamically and use no other
+// instruction that reads M0, so the compiler (which treats M0 as reserved and ignores the clobber) keeps no value in it.
 __device__ __forceinline__ void c_load_lds16(const void* src, unsigned lds_off) {
   const unsigned uniform_off = __builtin_amdgcn_readfirstlane(lds_off);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform_off) : "memory", "m0");

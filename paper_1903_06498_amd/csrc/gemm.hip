@@ -444,6 +444,8 @@ __device__ __forceinline__ f32x16 d_mma(bf16x8 a, bf16x8 b, f32x16 acc) {
 // another and would drain the whole load queue before every LDS read.  Here the
 // queue depth is managed by hand with the s_waitcnt in d_tile().  M0 carries
 // the wave-uniform LDS destination (lane i lands at +16*i).
+// M0 is written here and nowhere else: these kernels index no register array dynamically and use no other
+// instruction that reads M0, so the compiler (which treats M0 as reserved and ignores the clobber) keeps no value in it.
 __device__ __forceinline__ void d_load_lds16(const uint16_t* src, unsigned lds_off) {
   const unsigned uniform_off = __builtin_amdgcn_readfirstlane(lds_off);
   asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform_off) : "memory", "m0");
