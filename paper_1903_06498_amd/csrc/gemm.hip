@@ -727,6 +727,116 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
       }
 }
 
+// ---------------------------------------------------------------------------
+// 128 x 128 tiles for products with fewer 256 x 256 tiles than the chip has
+// CUs (a 2048^3 product has 64): four times as many workgroups, each four
+// wavefronts side by side along n (128 rows x 32 columns per wavefront: four A
+// fragments, one B fragment, four matrix instructions per 16-deep K step).
+// Same staging as the large-tile kernel -- LDS-direct loads into a four-stage
+// ring of 32-deep K tiles, A rows swizzled by (row>>2)&3, B kept [k][n] in
+// 256-byte rows swizzled by 4*(k&3) and read with the transposing LDS read --
+// at half the bytes per tile (8 KB + 8 KB), so two workgroups fit on a CU.
+// Row-major operands, M and N multiples of 128, K a multiple of 128.
+// ---------------------------------------------------------------------------
+constexpr int T_BM = 128, T_BN = 128, T_A_STAGE = T_BM * 64, T_B_STAGE = D_BK * T_BN * 2, T_B0 = D_STAGES * T_A_STAGE;
+constexpr int T_LDS = D_STAGES * (T_A_STAGE + T_B_STAGE);   // 64 KB
+
+__global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams p, const uint16_t* __restrict__ A,
+                                                                const uint16_t* __restrict__ B, float* __restrict__ C) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  typedef __attribute__((address_space(3))) s16x4* lptr;
+  const int t = threadIdx.x, lane = t & 63, wn = t >> 6;
+  const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n), batch = blockIdx.x / tiles;
+  A += (int64_t)batch * p.a_b;
+  B += (int64_t)batch * p.b_b;
+  C += (int64_t)batch * p.c_b;
+  const unsigned tile = blockIdx.x - batch * tiles;
+  const int tm = (int)(tile / (unsigned)p.tiles_n), tn = (int)(tile % (unsigned)p.tiles_n);
+
+  // loads: two A blocks and two B blocks of 1 KB per wavefront and K tile
+  const uint16_t* a_src;
+  const uint16_t* b_src;
+  {
+    const int row = 16 * wn + (lane >> 2);              // + 64*u
+    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    a_src = A + p.a_base + ((int64_t)tm * T_BM + row) * p.a_m + chunk * 8;
+    const int k = 4 * wn + (lane >> 4);                 // + 16*u ; k&3 == lane>>4
+    const int bchunk = (lane & 15) ^ (4 * (k & 3));
+    b_src = B + p.b_base + (int64_t)k * p.b_k + (int64_t)tn * T_BN + bchunk * 8;
+  }
+  const size_t a_step = (size_t)64 * p.a_m, b_step = (size_t)16 * p.b_k, b_kstep = (size_t)D_BK * p.b_k;
+  const unsigned wave_lds = wn * 1024;
+  auto issue = [&](int stage, int kt) {
+    const uint16_t* a = a_src + (size_t)kt * D_BK;
+    const uint16_t* b = b_src + (size_t)kt * b_kstep;
+    d_load_lds16(a, stage * T_A_STAGE + wave_lds);
+    d_load_lds16(a + a_step, stage * T_A_STAGE + 4096 + wave_lds);
+    d_load_lds16(b, T_B0 + stage * T_B_STAGE + wave_lds);
+    d_load_lds16(b + b_step, T_B0 + stage * T_B_STAGE + 4096 + wave_lds);
+  };
+  // fragment addresses
+  const int fr = lane & 31, fh = lane >> 5;
+  const unsigned a_fr = (unsigned)(fr * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
+  unsigned b_fr;
+  {
+    const int g = lane >> 4, pl = lane & 15;
+    const int k = 8 * (g >> 1) + (pl >> 2);
+    const int low2 = 2 * (g & 1) + ((pl & 3) >> 1);
+    b_fr = (unsigned)(T_B0 + k * 256 + (((wn * 4 + low2) ^ (4 * (k & 3))) << 4) + (pl & 1) * 8);
+  }
+  auto read_frags = [&](int stage, int s, bf16x8 (&af)[4], bf16x8& bf) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) af[q] = *(const bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * T_A_STAGE + q * 32 * 64);
+    const unsigned char* pb = lds + b_fr + stage * T_B_STAGE + s * 16 * 256;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)pb);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(pb + 4 * 256));
+    bf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+  };
+
+  f32x16 acc[4];
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+
+  const int k_tiles = p.k_tiles;   // a multiple of 4, at least 4 (host)
+  issue(0, 0);
+  issue(1, 1);
+  issue(2, 2);
+  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  __syncthreads();
+  bf16x8 af[2][4], bf[2];
+  read_frags(0, 0, af[0], bf[0]);
+  for (int kt = 0; kt < k_tiles; ++kt) {
+    const int stage = kt & 3;
+    // K step 0 of this tile, while its K step 1 is read
+    D_FENCE();
+    read_frags(stage, 1, af[1], bf[1]);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][q], bf[0], acc[q], 0, 0, 0);
+    D_FENCE();
+    // tile kt+1 must have landed (its loads were issued two tiles ago); then the ring slot of tile kt-1 is free for kt+3
+    if (kt + 2 < k_tiles) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (kt + 3 < k_tiles) issue((kt + 3) & 3, kt + 3);
+    D_FENCE();
+    if (kt + 1 < k_tiles) read_frags((kt + 1) & 3, 0, af[0], bf[0]);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][q], bf[1], acc[q], 0, 0, 0);
+    D_FENCE();
+  }
+
+  float* c_g = C + p.c_base + ((int64_t)tm * T_BM + 4 * fh) * p.c_m + (int64_t)tn * T_BN + wn * 32 + fr;
+#pragma unroll
+  for (int q = 0; q < 4; ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int r = 32 * q + 8 * (v / 4) + (v % 4);
+      __builtin_nontemporal_store(acc[q][v], c_g + (int64_t)r * p.c_m);
+    }
+}
+
 GemmParams make_params(const GemmShape& g, bool i8 = false) {
   GemmParams p;
   p.tiles_m = (int)((g.M + BM - 1) / BM);
@@ -797,6 +907,21 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
   const int64_t b_row = bt ? g.b_n : g.b_k;
   const bool dma_shape = g.K % (D_BK * D_STAGES) == 0 && g.K >= D_BK * D_STAGES && tune_int("gemm_dma", 1) != 0;
   const bool ragged = (g.M % BM || g.N % BN);
+  // few large tiles: 128 x 128 tiles put four times as many workgroups on the chip
+  const int64_t big_tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * (g.batch > 1 ? g.batch : 1);
+  if (!bt && dma_shape && big_tiles <= 128 && g.M % T_BM == 0 && g.N % T_BN == 0 && tune_int("gemm_t128", 1) != 0 &&
+      g.a_m % 8 == 0 && g.b_k % 8 == 0 && g.a_base % 8 == 0 && g.b_base % 8 == 0 && g.M / T_BM <= 32767 && g.N / T_BN <= 32767) {
+    l->variant = 50;
+    l->grid = (g.M / T_BM) * (g.N / T_BN);
+    info->path = STRIPE_PATH_MFMA_GEMM;
+    info->tile_m = T_BM; info->tile_n = T_BN; info->tile_k = D_BK;
+    info->frag_m = 32; info->frag_n = 32; info->frag_k = 16;
+    info->lds_bytes = T_LDS;
+    info->workgroup_size = 256;
+    info->grid = l->grid;
+    snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_128x128x32_mfma32x32x16_w4_lds_direct");
+    return true;
+  }
   if (bt || ragged) {
     if (!dma_shape || g.M < 1 || g.N < 8 || (!bt && g.N % 8) || g.M > 0x7fffffff || g.N > 0x7fffffff) return false;
     if (g.a_m % 8 || b_row % 8 || g.a_base % 8 || g.b_base % 8) return false;
@@ -840,7 +965,7 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
 
 hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t st) {
   if (((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % 4)) return hipErrorInvalidValue;
-  const bool i8 = l.variant >= 40;
+  const bool i8 = l.variant >= 40 && l.variant < 50;
   const GemmParams p = make_params(g, i8);
   void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = nullptr;
   switch (l.variant) {
@@ -852,6 +977,7 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
     case 30 + D_BT: kernel = gemm_bf16_dma_kernel<4, 1, D_BT>; break;
     case 30 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_RAGGED>; break;
     case 30 + D_BT + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED>; break;
+    case 50: kernel = gemm_bf16_t128_kernel; break;
     case 40: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_I8>; break;
     case 40 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED + D_I8>; break;
     case 10: kernel = gemm_bf16_w8_kernel<0>; break;
@@ -859,9 +985,13 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
     default: kernel = gemm_bf16_w8_kernel<2>; break;
   }
   const int threads = (l.variant == 21 || (l.variant >= 10 && l.variant < 20)) ? THREADS : W4_THREADS;
-  const int lds_bytes = l.variant >= 20 ? D_LDS : 2 * STAGE;
+  const int lds_bytes = l.variant == 50 ? T_LDS : l.variant >= 20 ? D_LDS : 2 * STAGE;
   GemmParams pk = p;
   if (l.variant >= 20) pk.k_tiles = (int)(g.K / (i8 ? 64 : D_BK));
+  if (l.variant == 50) {
+    pk.tiles_m = (int)(g.M / T_BM);
+    pk.tiles_n = (int)(g.N / T_BN);
+  }
   // more than 64 KB of dynamic LDS has to be enabled once per device
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);

@@ -463,7 +463,7 @@ def test_maxpool_config_full_size():
 
 
 # ------------------------------------------------------------------ dense contraction path
-@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 768, 320), (1024, 512, 128)])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 768, 320), (1024, 512, 128), (128, 128, 128), (384, 640, 256), (1152, 128, 512)])
 def test_gemm_mfma_small(M, N, K):
     blk = W.matmul_block(M, N, K, "bf16", "f32")
     ins = [W.seeded_tensor((M, K), "bf16", 0), W.seeded_tensor((K, N), "bf16", 1)]
@@ -472,7 +472,10 @@ def test_gemm_mfma_small(M, N, K):
     assert info["path_name"] == "mfma_gemm"
 
 
-@pytest.mark.parametrize("tune,name", [("gemm_dma_waves=4", "w4_lds_direct"), ("gemm_dma_waves=8", "w8_lds_direct"),
+@pytest.mark.parametrize("tune,name", [("gemm_t128=0,gemm_dma_waves=4", "256x256x32_mfma32x32x16_w4_lds_direct"),
+                                       ("gemm_t128=0,gemm_dma_waves=8", "w8_lds_direct"),
+                                       ("gemm_t128=0,gemm_sched=0", "w4_lds_direct_s0"), ("gemm_t128=0,gemm_sched=2", "w4_lds_direct_s2"),
+                                       ("gemm_t128=1", "128x128x32_mfma32x32x16_w4_lds_direct"),
                                        ("gemm_dma=0,gemm_waves=4", "w4_swz2"), ("gemm_dma=0,gemm_waves=8,gemm_swz=1", "w8_swz1"),
                                        ("gemm_dma=0,gemm_waves=8,gemm_swz=0", "w8_swz0")])
 def test_gemm_mfma_position_sensitive(tune, name, monkeypatch):
