@@ -736,11 +736,13 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
 // ring of 32-deep K tiles, A rows swizzled by (row>>2)&3, B kept [k][n] in
 // 256-byte rows swizzled by 4*(k&3) and read with the transposing LDS read --
 // at half the bytes per tile (8 KB + 8 KB), so two workgroups fit on a CU.
-// Row-major operands, M and N multiples of 128, K a multiple of 128.
+// M and N multiples of 128, K a multiple of 128 (256 for int8).  MODE as in the large-tile kernel: D_BT for a
+// transposed B (its tile then lies in LDS like A's), D_I8 for int8 operands with int32 accumulation.
 // ---------------------------------------------------------------------------
 constexpr int T_BM = 128, T_BN = 128, T_A_STAGE = T_BM * 64, T_B_STAGE = D_BK * T_BN * 2, T_B0 = D_STAGES * T_A_STAGE;
 constexpr int T_LDS = D_STAGES * (T_A_STAGE + T_B_STAGE);   // 64 KB
 
+template <int MODE>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams p, const uint16_t* __restrict__ A,
                                                                 const uint16_t* __restrict__ B, float* __restrict__ C) {
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -760,11 +762,16 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
     const int row = 16 * wn + (lane >> 2);              // + 64*u
     const int chunk = (lane & 3) ^ ((row >> 2) & 3);
     a_src = A + p.a_base + ((int64_t)tm * T_BM + row) * p.a_m + chunk * 8;
-    const int k = 4 * wn + (lane >> 4);                 // + 16*u ; k&3 == lane>>4
-    const int bchunk = (lane & 15) ^ (4 * (k & 3));
-    b_src = B + p.b_base + (int64_t)k * p.b_k + (int64_t)tn * T_BN + bchunk * 8;
+    if constexpr (MODE & D_BT) {
+      b_src = B + p.b_base + ((int64_t)tn * T_BN + row) * p.b_k + chunk * 8;
+    } else {
+      const int k = 4 * wn + (lane >> 4);                 // + 16*u ; k&3 == lane>>4
+      const int bchunk = (lane & 15) ^ (4 * (k & 3));
+      b_src = B + p.b_base + (int64_t)k * p.b_k + (int64_t)tn * T_BN + bchunk * 8;
+    }
   }
-  const size_t a_step = (size_t)64 * p.a_m, b_step = (size_t)16 * p.b_k, b_kstep = (size_t)D_BK * p.b_k;
+  const size_t a_step = (size_t)64 * p.a_m, b_step = (MODE & D_BT) ? (size_t)64 * p.b_k : (size_t)16 * p.b_k,
+               b_kstep = (MODE & D_BT) ? (size_t)D_BK : (size_t)D_BK * p.b_k;
   const unsigned wave_lds = wn * 1024;
   auto issue = [&](int stage, int kt) {
     const uint16_t* a = a_src + (size_t)kt * D_BK;
@@ -783,14 +790,19 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
     const int k = 8 * (g >> 1) + (pl >> 2);
     const int low2 = 2 * (g & 1) + ((pl & 3) >> 1);
     b_fr = (unsigned)(T_B0 + k * 256 + (((wn * 4 + low2) ^ (4 * (k & 3))) << 4) + (pl & 1) * 8);
+    if constexpr (MODE & D_BT) b_fr = (unsigned)(T_B0 + (wn * 32 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
   }
   auto read_frags = [&](int stage, int s, bf16x8 (&af)[4], bf16x8& bf) {
 #pragma unroll
     for (int q = 0; q < 4; ++q) af[q] = *(const bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * T_A_STAGE + q * 32 * 64);
-    const unsigned char* pb = lds + b_fr + stage * T_B_STAGE + s * 16 * 256;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)pb);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(pb + 4 * 256));
-    bf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    if constexpr (MODE & D_BT) {
+      bf = *(const bf16x8*)(lds + (b_fr ^ (unsigned)(s << 5)) + stage * T_B_STAGE);
+    } else {
+      const unsigned char* pb = lds + b_fr + stage * T_B_STAGE + s * 16 * 256;
+      const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)pb);
+      const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lptr)(pb + 4 * 256));
+      bf = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+    }
   };
 
   f32x16 acc[4];
@@ -813,7 +825,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
     D_FENCE();
     read_frags(stage, 1, af[1], bf[1]);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[0][q], bf[0], acc[q], 0, 0, 0);
+    for (int q = 0; q < 4; ++q) acc[q] = d_mma<MODE>(af[0][q], bf[0], acc[q]);
     D_FENCE();
     // tile kt+1 must have landed (its loads were issued two tiles ago); then the ring slot of tile kt-1 is free for kt+3
     if (kt + 2 < k_tiles) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
@@ -823,7 +835,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
     D_FENCE();
     if (kt + 1 < k_tiles) read_frags((kt + 1) & 3, 0, af[0], bf[0]);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[1][q], bf[1], acc[q], 0, 0, 0);
+    for (int q = 0; q < 4; ++q) acc[q] = d_mma<MODE>(af[1][q], bf[1], acc[q]);
     D_FENCE();
   }
 
@@ -887,6 +899,19 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
     const int64_t tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
     if (tiles_m > 32767 || tiles_n > 32767) return false;
     const bool ragged = (g.M % BM || g.N % BN);
+    if (tiles_m * tiles_n * (g.batch > 1 ? g.batch : 1) <= 128 && g.M % T_BM == 0 && g.N % T_BN == 0 && tune_int("gemm_t128", 1) != 0 &&
+        g.M / T_BM <= 32767 && g.N / T_BN <= 32767) {
+      l->variant = 52;
+      l->grid = (g.M / T_BM) * (g.N / T_BN);
+      info->path = STRIPE_PATH_MFMA_GEMM;
+      info->tile_m = T_BM; info->tile_n = T_BN; info->tile_k = 64;
+      info->frag_m = 32; info->frag_n = 32; info->frag_k = 32;
+      info->lds_bytes = T_LDS;
+      info->workgroup_size = 256;
+      info->grid = l->grid;
+      snprintf(info->kernel, sizeof info->kernel, "gemm_i8_128x128x64_mfma32x32x32_w4_lds_direct_bt");
+      return true;
+    }
     l->variant = 40 + (ragged ? D_RAGGED : 0);
     l->grid = tiles_m * tiles_n;
     info->path = STRIPE_PATH_MFMA_GEMM;
@@ -909,9 +934,9 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
   const bool ragged = (g.M % BM || g.N % BN);
   // few large tiles: 128 x 128 tiles put four times as many workgroups on the chip
   const int64_t big_tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN) * (g.batch > 1 ? g.batch : 1);
-  if (!bt && dma_shape && big_tiles <= 128 && g.M % T_BM == 0 && g.N % T_BN == 0 && tune_int("gemm_t128", 1) != 0 &&
-      g.a_m % 8 == 0 && g.b_k % 8 == 0 && g.a_base % 8 == 0 && g.b_base % 8 == 0 && g.M / T_BM <= 32767 && g.N / T_BN <= 32767) {
-    l->variant = 50;
+  if (dma_shape && big_tiles <= 128 && g.M % T_BM == 0 && g.N % T_BN == 0 && tune_int("gemm_t128", 1) != 0 &&
+      g.a_m % 8 == 0 && b_row % 8 == 0 && g.a_base % 8 == 0 && g.b_base % 8 == 0 && g.M / T_BM <= 32767 && g.N / T_BN <= 32767) {
+    l->variant = bt ? 51 : 50;
     l->grid = (g.M / T_BM) * (g.N / T_BN);
     info->path = STRIPE_PATH_MFMA_GEMM;
     info->tile_m = T_BM; info->tile_n = T_BN; info->tile_k = D_BK;
@@ -919,7 +944,7 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
     info->lds_bytes = T_LDS;
     info->workgroup_size = 256;
     info->grid = l->grid;
-    snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_128x128x32_mfma32x32x16_w4_lds_direct");
+    snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_128x128x32_mfma32x32x16_w4_lds_direct%s", bt ? "_bt" : "");
     return true;
   }
   if (bt || ragged) {
@@ -965,7 +990,7 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
 
 hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t st) {
   if (((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % 4)) return hipErrorInvalidValue;
-  const bool i8 = l.variant >= 40 && l.variant < 50;
+  const bool i8 = (l.variant >= 40 && l.variant < 50) || l.variant == 52;
   const GemmParams p = make_params(g, i8);
   void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = nullptr;
   switch (l.variant) {
@@ -977,7 +1002,9 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
     case 30 + D_BT: kernel = gemm_bf16_dma_kernel<4, 1, D_BT>; break;
     case 30 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_RAGGED>; break;
     case 30 + D_BT + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED>; break;
-    case 50: kernel = gemm_bf16_t128_kernel; break;
+    case 50: kernel = gemm_bf16_t128_kernel<0>; break;
+    case 51: kernel = gemm_bf16_t128_kernel<D_BT>; break;
+    case 52: kernel = gemm_bf16_t128_kernel<D_BT + D_I8>; break;
     case 40: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_I8>; break;
     case 40 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED + D_I8>; break;
     case 10: kernel = gemm_bf16_w8_kernel<0>; break;
@@ -985,10 +1012,10 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
     default: kernel = gemm_bf16_w8_kernel<2>; break;
   }
   const int threads = (l.variant == 21 || (l.variant >= 10 && l.variant < 20)) ? THREADS : W4_THREADS;
-  const int lds_bytes = l.variant == 50 ? T_LDS : l.variant >= 20 ? D_LDS : 2 * STAGE;
+  const int lds_bytes = l.variant >= 50 ? T_LDS : l.variant >= 20 ? D_LDS : 2 * STAGE;
   GemmParams pk = p;
   if (l.variant >= 20) pk.k_tiles = (int)(g.K / (i8 ? 64 : D_BK));
-  if (l.variant == 50) {
+  if (l.variant >= 50) {
     pk.tiles_m = (int)(g.M / T_BM);
     pk.tiles_n = (int)(g.N / T_BN);
   }

@@ -500,9 +500,10 @@ def test_gemm_mfma_position_sensitive(tune, name, monkeypatch):
 
 @pytest.mark.parametrize("M,N,K,bt", [(256, 256, 128, True), (512, 768, 384, True), (300, 520, 256, False), (2, 8, 128, False),
                                       (257, 264, 128, False), (300, 333, 256, True), (70, 9, 128, True), (511, 8, 128, True)])
-def test_gemm_transposed_b_and_ragged_edges(M, N, K, bt):
+def test_gemm_transposed_b_and_ragged_edges(M, N, K, bt, monkeypatch):
     """The LDS-direct kernel with B stored [n][k] and/or M, N that are not multiples of the 256 x 256 tile.
     Position-sensitive operands first (every output is one specific A element, exactly), then seeded data."""
+    monkeypatch.setenv("STRIPE_TUNE", "gemm_t128=0")       # the 256 x 256 kernel's modes; the small-tile kernel is covered below
     blk = W.matmul_block(M, N, K, "bf16", "f32", b_transposed=bt)
     a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.bfloat16)
     shift = 37
@@ -518,10 +519,13 @@ def test_gemm_transposed_b_and_ragged_edges(M, N, K, bt):
     parity(blk, ins, what=f"gemm {M}x{N}x{K} bt={bt}")          # also checks that nothing outside C[0:M, 0:N] changed
 
 
-@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (512, 768, 512), (300, 333, 256), (70, 9, 512), (257, 8, 256)])
-def test_gemm_int8_transposed_b(M, N, K):
+@pytest.mark.parametrize("t128", [1, 0])
+@pytest.mark.parametrize("M,N,K", [(256, 256, 256), (512, 768, 512), (300, 333, 256), (70, 9, 512), (257, 8, 256), (128, 384, 256)])
+def test_gemm_int8_transposed_b(M, N, K, t128, monkeypatch):
     """int8 x int8 -> int32 on the matrix cores (C = A * B^T, both operands k-contiguous): bit-exact, including
-    extreme values (-128 * -128 summed over K) and edges that are not multiples of the tile."""
+    extreme values (-128 * -128 summed over K) and edges that are not multiples of the tile; small aligned
+    products on the 128 x 128-tile kernel (t128=1) and on the 256 x 256 one."""
+    monkeypatch.setenv("STRIPE_TUNE", f"gemm_t128={t128}")
     blk = W.matmul_block(M, N, K, "i8", "i32", b_transposed=True)
     a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.int8)
     sel = (torch.arange(N) + 37) % K
@@ -529,7 +533,9 @@ def test_gemm_int8_transposed_b(M, N, K):
     b[torch.arange(N), sel] = 1
     gpu, sb = run_gpu(blk, [a, b], return_block=True)
     ragged = M % 256 != 0 or N % 256 != 0
-    assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"] == "gemm_i8_256x256x64_mfma32x32x32_w4_lds_direct_bt" + ("_ragged" if ragged else "")
+    small = bool(t128) and M % 128 == 0 and N % 128 == 0
+    want = "gemm_i8_128x128x64_mfma32x32x32_w4_lds_direct_bt" if small else "gemm_i8_256x256x64_mfma32x32x32_w4_lds_direct_bt" + ("_ragged" if ragged else "")
+    assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"] == want, sb.info["kernel"]
     assert np.array_equal(gpu.reshape(M, N), a.to(torch.int32)[:, sel].numpy())
     ins = [W.seeded_tensor((M, K), "i8", 0), W.seeded_tensor((N, K), "i8", 1)]
     parity(blk, ins, what=f"int8 gemm {M}x{N}x{K}")
@@ -560,6 +566,22 @@ def test_batched_gemm(batch, M, N, K, dtype, bt, shared):
     assert np.array_equal(gpu.reshape(batch, M, N), want)
     ins = [W.seeded_tensor(r.sizes, dtype, s_) for s_, r in enumerate(blk.refs[:-1])]
     parity(blk, ins, what=f"batched gemm {batch}x{M}x{N}x{K} {dtype}")
+
+
+@pytest.mark.parametrize("M,N,K,bt", [(128, 128, 128, False), (384, 640, 256, True), (1024, 256, 384, False), (256, 1152, 128, True)])
+def test_gemm_small_tile_kernel(M, N, K, bt):
+    """Products with few 256 x 256 tiles run on the 128 x 128-tile kernel (row-major and transposed B): position-sensitive
+    operands exactly, then seeded data."""
+    blk = W.matmul_block(M, N, K, "bf16", "f32", b_transposed=bt)
+    a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.bfloat16)
+    sel = (torch.arange(N) + 37) % K
+    b = torch.zeros((K, N), dtype=torch.bfloat16)
+    b[sel, torch.arange(N)] = 1.0
+    gpu, sb = run_gpu(blk, [a, b.t().contiguous() if bt else b], return_block=True)
+    assert sb.info["kernel"] == "gemm_bf16_128x128x32_mfma32x32x16_w4_lds_direct" + ("_bt" if bt else ""), sb.info["kernel"]
+    assert np.array_equal(gpu.reshape(M, N), a.float()[:, sel].numpy())
+    ins = [W.seeded_tensor((M, K), "bf16", 0), W.seeded_tensor((N, K) if bt else (K, N), "bf16", 1)]
+    parity(blk, ins, what=f"small-tile gemm {M}x{N}x{K} bt={bt}")
 
 
 def test_pointwise_convolution_runs_on_the_gemm_kernel():
