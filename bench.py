@@ -50,6 +50,8 @@ KIND = {
     "gemm_bf16_4096_bt": ("TFLOP/s", "mfma", "bf16"),
     "gemm_bf16_4000_ragged": ("TFLOP/s", "mfma", "bf16"),
     "gemm_i8_4096_bt": ("TOP/s", "mfma", "int8"),
+    "gemm_bf16_1024": ("TFLOP/s", "mfma", "bf16"),
+    "gemm_bf16_2048": ("TFLOP/s", "mfma", "bf16"),
     "pointwise_conv_bf16": ("TFLOP/s", "hbm", "bf16"),
     "transposed_conv_f32": ("TFLOP/s", "alu", "f32"),
     "resnet_conv_bias_relu_bf16": ("TFLOP/s", "hbm", "bf16"),   # two statements fused into one kernel, bf16 output

@@ -352,12 +352,15 @@ def conv_bias_relu_program(N, H, W, Ci, Co, R, S, stride, pad, in_dtype="bf16", 
 
 # Further shapes the kernel families cover, for measurements beyond the five configurations (bench.py --workload).
 EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32",
-               "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32")
+               "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "gemm_bf16_1024", "gemm_bf16_2048")
 
 
 def extra_block(name: str) -> Block:
     if name == "gemm_bf16_4096_bt":
         return matmul_block(4096, 4096, 4096, "bf16", "f32", b_transposed=True)
+    if name in ("gemm_bf16_1024", "gemm_bf16_2048"):      # fewer 256 x 256 tiles than CUs: the 128 x 128-tile kernel
+        n = int(name.rsplit("_", 1)[1])
+        return matmul_block(n, n, n, "bf16", "f32")
     if name == "gemm_bf16_4000_ragged":
         return matmul_block(4000, 4000, 4096, "bf16", "f32")
     if name == "gemm_i8_4096_bt":
