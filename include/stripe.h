@@ -175,7 +175,11 @@ stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, st
  * not enter the aggregation).  A block whose output elements are shared
  * between index tuples through different output indexes (O[x + i]) is run as
  * two launches: the aggregation's identity to every reached element, then an
- * atomic combine.  Asynchronous: returns after enqueueing; only
+ * atomic combine.  A statement list runs its statements in order on the
+ * stream; temporaries that are not fused away live in device memory the
+ * handle allocates on its first run on a device (the only allocation run()
+ * ever makes) and frees on destroy, so two overlapping runs of such a handle
+ * race on them.  Asynchronous: returns after enqueueing; only
  * launch errors are reported.  Calls on different handles may overlap; two
  * overlapping calls that write the same output buffer race.
  */
