@@ -742,12 +742,17 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
 constexpr int T_BM = 128, T_BN = 128, T_A_STAGE = T_BM * 64, T_B_STAGE = D_BK * T_BN * 2, T_B0 = D_STAGES * T_A_STAGE;
 constexpr int T_LDS = D_STAGES * (T_A_STAGE + T_B_STAGE);   // 64 KB
 
-template <int MODE>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams p, const uint16_t* __restrict__ A,
-                                                                const uint16_t* __restrict__ B, float* __restrict__ C) {
+// W8: eight wavefronts (2 along m x 4 along n, 64 x 32 each) instead of four (128 x 32 each): two wavefronts per
+// SIMD, so that one's waits (LDS latency, barrier) are covered by the other's matrix instructions.
+template <int MODE, int W8 = 0>
+__global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const GemmParams p, const uint16_t* __restrict__ A,
+                                                                         const uint16_t* __restrict__ B, float* __restrict__ C) {
+  constexpr int NW = 4 * (1 + W8);          // wavefronts
+  constexpr int NF = 4 / (1 + W8);          // A fragments (32 rows each) per wavefront
+  constexpr int LPW = 2 / (1 + W8);         // 1 KB load blocks per wavefront, per operand and K tile
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   typedef __attribute__((address_space(3))) s16x4* lptr;
-  const int t = threadIdx.x, lane = t & 63, wn = t >> 6;
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6, wn = wv & 3, wm = wv >> 2;
   const unsigned tiles = (unsigned)(p.tiles_m * p.tiles_n), batch = blockIdx.x / tiles;
   A += (int64_t)batch * p.a_b;
   B += (int64_t)batch * p.b_b;
@@ -755,35 +760,35 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
   const unsigned tile = blockIdx.x - batch * tiles;
   const int tm = (int)(tile / (unsigned)p.tiles_n), tn = (int)(tile % (unsigned)p.tiles_n);
 
-  // loads: two A blocks and two B blocks of 1 KB per wavefront and K tile
+  // loads: block wv (+ NW*u) of each operand's 8 blocks of 1 KB per K tile
   const uint16_t* a_src;
   const uint16_t* b_src;
   {
-    const int row = 16 * wn + (lane >> 2);              // + 64*u
+    const int row = 16 * wv + (lane >> 2);              // + 16*NW*u
     const int chunk = (lane & 3) ^ ((row >> 2) & 3);
     a_src = A + p.a_base + ((int64_t)tm * T_BM + row) * p.a_m + chunk * 8;
     if constexpr (MODE & D_BT) {
       b_src = B + p.b_base + ((int64_t)tn * T_BN + row) * p.b_k + chunk * 8;
     } else {
-      const int k = 4 * wn + (lane >> 4);                 // + 16*u ; k&3 == lane>>4
+      const int k = 4 * wv + (lane >> 4);                 // + 4*NW*u ; k&3 == lane>>4
       const int bchunk = (lane & 15) ^ (4 * (k & 3));
       b_src = B + p.b_base + (int64_t)k * p.b_k + (int64_t)tn * T_BN + bchunk * 8;
     }
   }
-  const size_t a_step = (size_t)64 * p.a_m, b_step = (MODE & D_BT) ? (size_t)64 * p.b_k : (size_t)16 * p.b_k,
+  const size_t a_step = (size_t)(16 * NW) * p.a_m, b_step = (MODE & D_BT) ? (size_t)(16 * NW) * p.b_k : (size_t)(4 * NW) * p.b_k,
                b_kstep = (MODE & D_BT) ? (size_t)D_BK : (size_t)D_BK * p.b_k;
-  const unsigned wave_lds = wn * 1024;
+  const unsigned wave_lds = wv * 1024;
   auto issue = [&](int stage, int kt) {
     const uint16_t* a = a_src + (size_t)kt * D_BK;
     const uint16_t* b = b_src + (size_t)kt * b_kstep;
-    d_load_lds16(a, stage * T_A_STAGE + wave_lds);
-    d_load_lds16(a + a_step, stage * T_A_STAGE + 4096 + wave_lds);
-    d_load_lds16(b, T_B0 + stage * T_B_STAGE + wave_lds);
-    d_load_lds16(b + b_step, T_B0 + stage * T_B_STAGE + 4096 + wave_lds);
+#pragma unroll
+    for (int u = 0; u < LPW; ++u) d_load_lds16(a + u * a_step, stage * T_A_STAGE + u * (NW * 1024) + wave_lds);
+#pragma unroll
+    for (int u = 0; u < LPW; ++u) d_load_lds16(b + u * b_step, T_B0 + stage * T_B_STAGE + u * (NW * 1024) + wave_lds);
   };
   // fragment addresses
   const int fr = lane & 31, fh = lane >> 5;
-  const unsigned a_fr = (unsigned)(fr * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
+  const unsigned a_fr = (unsigned)((wm * 64 * W8 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
   unsigned b_fr;
   {
     const int g = lane >> 4, pl = lane & 15;
@@ -792,9 +797,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
     b_fr = (unsigned)(T_B0 + k * 256 + (((wn * 4 + low2) ^ (4 * (k & 3))) << 4) + (pl & 1) * 8);
     if constexpr (MODE & D_BT) b_fr = (unsigned)(T_B0 + (wn * 32 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
   }
-  auto read_frags = [&](int stage, int s, bf16x8 (&af)[4], bf16x8& bf) {
+  auto read_frags = [&](int stage, int s, bf16x8 (&af)[NF], bf16x8& bf) {
 #pragma unroll
-    for (int q = 0; q < 4; ++q) af[q] = *(const bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * T_A_STAGE + q * 32 * 64);
+    for (int q = 0; q < NF; ++q) af[q] = *(const bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * T_A_STAGE + q * 32 * 64);
     if constexpr (MODE & D_BT) {
       bf = *(const bf16x8*)(lds + (b_fr ^ (unsigned)(s << 5)) + stage * T_B_STAGE);
     } else {
@@ -805,9 +810,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
     }
   };
 
-  f32x16 acc[4];
+  f32x16 acc[NF];
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
+  for (int q = 0; q < NF; ++q)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
 
@@ -815,9 +820,10 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
   issue(0, 0);
   issue(1, 1);
   issue(2, 2);
-  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  if (LPW == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
   __syncthreads();
-  bf16x8 af[2][4], bf[2];
+  bf16x8 af[2][NF], bf[2];
   read_frags(0, 0, af[0], bf[0]);
   for (int kt = 0; kt < k_tiles; ++kt) {
     const int stage = kt & 3;
@@ -825,23 +831,24 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_t128_kernel(const GemmParams
     D_FENCE();
     read_frags(stage, 1, af[1], bf[1]);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = d_mma<MODE>(af[0][q], bf[0], acc[q]);
+    for (int q = 0; q < NF; ++q) acc[q] = d_mma<MODE>(af[0][q], bf[0], acc[q]);
     D_FENCE();
     // tile kt+1 must have landed (its loads were issued two tiles ago); then the ring slot of tile kt-1 is free for kt+3
-    if (kt + 2 < k_tiles) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (kt + 2 >= k_tiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    else if (LPW == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
     __syncthreads();
     if (kt + 3 < k_tiles) issue((kt + 3) & 3, kt + 3);
     D_FENCE();
     if (kt + 1 < k_tiles) read_frags((kt + 1) & 3, 0, af[0], bf[0]);
 #pragma unroll
-    for (int q = 0; q < 4; ++q) acc[q] = d_mma<MODE>(af[1][q], bf[1], acc[q]);
+    for (int q = 0; q < NF; ++q) acc[q] = d_mma<MODE>(af[1][q], bf[1], acc[q]);
     D_FENCE();
   }
 
-  float* c_g = C + p.c_base + ((int64_t)tm * T_BM + 4 * fh) * p.c_m + (int64_t)tn * T_BN + wn * 32 + fr;
+  float* c_g = C + p.c_base + ((int64_t)tm * T_BM + wm * 64 * W8 + 4 * fh) * p.c_m + (int64_t)tn * T_BN + wn * 32 + fr;
 #pragma unroll
-  for (int q = 0; q < 4; ++q)
+  for (int q = 0; q < NF; ++q)
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int r = 32 * q + 8 * (v / 4) + (v % 4);
@@ -902,14 +909,15 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
     if (tiles_m * tiles_n * (g.batch > 1 ? g.batch : 1) <= 128 && g.M % T_BM == 0 && g.N % T_BN == 0 && tune_int("gemm_t128", 1) != 0 &&
         g.M / T_BM <= 32767 && g.N / T_BN <= 32767) {
       l->variant = 52;
+      l->t128_waves = tune_int("gemm_t128_waves", 8) == 4 ? 4 : 8;
       l->grid = (g.M / T_BM) * (g.N / T_BN);
       info->path = STRIPE_PATH_MFMA_GEMM;
       info->tile_m = T_BM; info->tile_n = T_BN; info->tile_k = 64;
       info->frag_m = 32; info->frag_n = 32; info->frag_k = 32;
       info->lds_bytes = T_LDS;
-      info->workgroup_size = 256;
+      info->workgroup_size = 64 * l->t128_waves;
       info->grid = l->grid;
-      snprintf(info->kernel, sizeof info->kernel, "gemm_i8_128x128x64_mfma32x32x32_w4_lds_direct_bt");
+      snprintf(info->kernel, sizeof info->kernel, "gemm_i8_128x128x64_mfma32x32x32_w%d_lds_direct_bt", l->t128_waves);
       return true;
     }
     l->variant = 40 + (ragged ? D_RAGGED : 0);
@@ -937,14 +945,15 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
   if (dma_shape && big_tiles <= 128 && g.M % T_BM == 0 && g.N % T_BN == 0 && tune_int("gemm_t128", 1) != 0 &&
       g.a_m % 8 == 0 && b_row % 8 == 0 && g.a_base % 8 == 0 && g.b_base % 8 == 0 && g.M / T_BM <= 32767 && g.N / T_BN <= 32767) {
     l->variant = bt ? 51 : 50;
+    l->t128_waves = tune_int("gemm_t128_waves", 8) == 4 ? 4 : 8;
     l->grid = (g.M / T_BM) * (g.N / T_BN);
     info->path = STRIPE_PATH_MFMA_GEMM;
     info->tile_m = T_BM; info->tile_n = T_BN; info->tile_k = D_BK;
     info->frag_m = 32; info->frag_n = 32; info->frag_k = 16;
     info->lds_bytes = T_LDS;
-    info->workgroup_size = 256;
+    info->workgroup_size = 64 * l->t128_waves;
     info->grid = l->grid;
-    snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_128x128x32_mfma32x32x16_w4_lds_direct%s", bt ? "_bt" : "");
+    snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_128x128x32_mfma32x32x16_w%d_lds_direct%s", l->t128_waves, bt ? "_bt" : "");
     return true;
   }
   if (bt || ragged) {
@@ -992,6 +1001,7 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
   if (((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % 4)) return hipErrorInvalidValue;
   const bool i8 = (l.variant >= 40 && l.variant < 50) || l.variant == 52;
   const GemmParams p = make_params(g, i8);
+  const bool t128_w8 = l.variant >= 50 && l.t128_waves == 8;
   void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = nullptr;
   switch (l.variant) {
     case 0: case 1: case 2: kernel = gemm_bf16_w4_kernel; break;
@@ -1002,16 +1012,16 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
     case 30 + D_BT: kernel = gemm_bf16_dma_kernel<4, 1, D_BT>; break;
     case 30 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_RAGGED>; break;
     case 30 + D_BT + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED>; break;
-    case 50: kernel = gemm_bf16_t128_kernel<0>; break;
-    case 51: kernel = gemm_bf16_t128_kernel<D_BT>; break;
-    case 52: kernel = gemm_bf16_t128_kernel<D_BT + D_I8>; break;
+    case 50: kernel = t128_w8 ? gemm_bf16_t128_kernel<0, 1> : gemm_bf16_t128_kernel<0, 0>; break;
+    case 51: kernel = t128_w8 ? gemm_bf16_t128_kernel<D_BT, 1> : gemm_bf16_t128_kernel<D_BT, 0>; break;
+    case 52: kernel = t128_w8 ? gemm_bf16_t128_kernel<D_BT + D_I8, 1> : gemm_bf16_t128_kernel<D_BT + D_I8, 0>; break;
     case 40: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_I8>; break;
     case 40 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED + D_I8>; break;
     case 10: kernel = gemm_bf16_w8_kernel<0>; break;
     case 11: kernel = gemm_bf16_w8_kernel<1>; break;
     default: kernel = gemm_bf16_w8_kernel<2>; break;
   }
-  const int threads = (l.variant == 21 || (l.variant >= 10 && l.variant < 20)) ? THREADS : W4_THREADS;
+  const int threads = (l.variant == 21 || (l.variant >= 10 && l.variant < 20) || t128_w8) ? THREADS : W4_THREADS;
   const int lds_bytes = l.variant >= 50 ? T_LDS : l.variant >= 20 ? D_LDS : 2 * STAGE;
   GemmParams pk = p;
   if (l.variant >= 20) pk.k_tiles = (int)(g.K / (i8 ? 64 : D_BK));

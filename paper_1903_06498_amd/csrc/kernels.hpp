@@ -31,6 +31,7 @@ hipError_t launch_generic_tiled(const Plan& plan, const void* in0, const void* i
 // ---- nested-tile dense contraction on matrix cores ------------------------
 struct GemmLaunch {
   int variant = -1;
+  int t128_waves = 4;   // wavefronts of the 128 x 128-tile kernel: 4 or 8
   int64_t grid = 0;
   mutable int lds_enabled_on = -1;  // device on which the kernel's large LDS size has been enabled
 };

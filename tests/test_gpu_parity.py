@@ -475,7 +475,8 @@ def test_gemm_mfma_small(M, N, K):
 @pytest.mark.parametrize("tune,name", [("gemm_t128=0,gemm_dma_waves=4", "256x256x32_mfma32x32x16_w4_lds_direct"),
                                        ("gemm_t128=0,gemm_dma_waves=8", "w8_lds_direct"),
                                        ("gemm_t128=0,gemm_sched=0", "w4_lds_direct_s0"), ("gemm_t128=0,gemm_sched=2", "w4_lds_direct_s2"),
-                                       ("gemm_t128=1", "128x128x32_mfma32x32x16_w4_lds_direct"),
+                                       ("gemm_t128=1", "128x128x32_mfma32x32x16_w8_lds_direct"),
+                                       ("gemm_t128=1,gemm_t128_waves=4", "128x128x32_mfma32x32x16_w4_lds_direct"),
                                        ("gemm_dma=0,gemm_waves=4", "w4_swz2"), ("gemm_dma=0,gemm_waves=8,gemm_swz=1", "w8_swz1"),
                                        ("gemm_dma=0,gemm_waves=8,gemm_swz=0", "w8_swz0")])
 def test_gemm_mfma_position_sensitive(tune, name, monkeypatch):
@@ -534,7 +535,7 @@ def test_gemm_int8_transposed_b(M, N, K, t128, monkeypatch):
     gpu, sb = run_gpu(blk, [a, b], return_block=True)
     ragged = M % 256 != 0 or N % 256 != 0
     small = bool(t128) and M % 128 == 0 and N % 128 == 0
-    want = "gemm_i8_128x128x64_mfma32x32x32_w4_lds_direct_bt" if small else "gemm_i8_256x256x64_mfma32x32x32_w4_lds_direct_bt" + ("_ragged" if ragged else "")
+    want = "gemm_i8_128x128x64_mfma32x32x32_w8_lds_direct_bt" if small else "gemm_i8_256x256x64_mfma32x32x32_w4_lds_direct_bt" + ("_ragged" if ragged else "")
     assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"] == want, sb.info["kernel"]
     assert np.array_equal(gpu.reshape(M, N), a.to(torch.int32)[:, sel].numpy())
     ins = [W.seeded_tensor((M, K), "i8", 0), W.seeded_tensor((N, K), "i8", 1)]
@@ -568,17 +569,19 @@ def test_batched_gemm(batch, M, N, K, dtype, bt, shared):
     parity(blk, ins, what=f"batched gemm {batch}x{M}x{N}x{K} {dtype}")
 
 
+@pytest.mark.parametrize("waves", [8, 4])
 @pytest.mark.parametrize("M,N,K,bt", [(128, 128, 128, False), (384, 640, 256, True), (1024, 256, 384, False), (256, 1152, 128, True)])
-def test_gemm_small_tile_kernel(M, N, K, bt):
-    """Products with few 256 x 256 tiles run on the 128 x 128-tile kernel (row-major and transposed B): position-sensitive
-    operands exactly, then seeded data."""
+def test_gemm_small_tile_kernel(M, N, K, bt, waves, monkeypatch):
+    """Products with few 256 x 256 tiles run on the 128 x 128-tile kernel (row-major and transposed B, eight or four
+    wavefronts): position-sensitive operands exactly, then seeded data."""
+    monkeypatch.setenv("STRIPE_TUNE", f"gemm_t128_waves={waves}")
     blk = W.matmul_block(M, N, K, "bf16", "f32", b_transposed=bt)
     a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.bfloat16)
     sel = (torch.arange(N) + 37) % K
     b = torch.zeros((K, N), dtype=torch.bfloat16)
     b[sel, torch.arange(N)] = 1.0
     gpu, sb = run_gpu(blk, [a, b.t().contiguous() if bt else b], return_block=True)
-    assert sb.info["kernel"] == "gemm_bf16_128x128x32_mfma32x32x16_w4_lds_direct" + ("_bt" if bt else ""), sb.info["kernel"]
+    assert sb.info["kernel"] == f"gemm_bf16_128x128x32_mfma32x32x16_w{waves}_lds_direct" + ("_bt" if bt else ""), sb.info["kernel"]
     assert np.array_equal(gpu.reshape(M, N), a.float()[:, sel].numpy())
     ins = [W.seeded_tensor((M, K), "bf16", 0), W.seeded_tensor((N, K) if bt else (K, N), "bf16", 1)]
     parity(blk, ins, what=f"small-tile gemm {M}x{N}x{K} bt={bt}")
