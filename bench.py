@@ -52,6 +52,7 @@ KIND = {
     "gemm_i8_4096_bt": ("TOP/s", "mfma", "int8"),
     "gemm_bf16_1024": ("TFLOP/s", "mfma", "bf16"),
     "gemm_bf16_2048": ("TFLOP/s", "mfma", "bf16"),
+    "linear_bias_relu_4096": ("TFLOP/s", "mfma", "bf16"),
     "pointwise_conv_bf16": ("TFLOP/s", "hbm", "bf16"),
     "transposed_conv_f32": ("TFLOP/s", "alu", "f32"),
     "resnet_conv_bias_relu_bf16": ("TFLOP/s", "hbm", "bf16"),   # two statements fused into one kernel, bf16 output

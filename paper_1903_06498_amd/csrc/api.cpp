@@ -34,7 +34,10 @@ struct stripe_block {
   std::vector<int64_t> temp_bytes;   // root refinement -> bytes of the temporary, 0 otherwise
   std::vector<void*> temp_ptr;
   int temp_dev = -1;
-  int fused = 0;                     // 1, 2: the two statements run as one convolution kernel with a bias+relu epilogue (fp32 / bf16 output)
+  // 1, 2: the two statements run as one convolution kernel with a bias+relu epilogue (fp32 / bf16 output);
+  // 3, 4: the same with the dense-contraction kernel
+  int fused = 0;
+  int64_t fuse_bias_off = 0, fuse_o_m = 0, fuse_o_base = 0;
   ~stripe_block() {
     for (Stage& st : stages) delete st.blk;
     for (void* t : temp_ptr)
@@ -168,8 +171,36 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
         prog->fused = e.out_bf16 ? 2 : 1;
         prog->plan.conv = c.conv;
         prog->conv = s0.blk->conv;
-        prog->plan.gemm.b_base = e.ref[1].addr.k;   // element offset of the bias inside its buffer
+        prog->fuse_bias_off = e.ref[1].addr.k;      // element offset of the bias inside its buffer
         prog->temp_bytes[s0.dst] = 0;               // scalarised away
+      }
+    }
+  }
+  // The same for a dense contraction C = A * B (or A * B^T) followed by O[m,n] = relu(C[m,n] + bias[n]).
+  if (!prog->fused && prog->stages.size() == 2 && tune_int("fuse", 1)) {
+    const Stage &s0 = prog->stages[0], &s1 = prog->stages[1];
+    const Plan& c = s0.blk->plan;
+    const FlatBlock& e = s1.blk->plan.flat;
+    bool ok = c.info.path == STRIPE_PATH_MFMA_GEMM && c.in_dtype == STRIPE_BF16 && gemm_can_fuse_bias_relu(c.gemm, s0.blk->gemm) &&
+              root->refs[s0.dst].dir == STRIPE_TEMP && s1.n_in == 2 && s1.src[0] == s0.dst && !e.empty && e.intrinsic == STRIPE_INTR_ADD_RELU &&
+              e.cons.empty() && e.n_refs == 3 && e.n_idx >= 2 && e.ref[0].dtype == STRIPE_F32 && e.ref[1].dtype == STRIPE_F32;
+    if (ok) {
+      std::vector<int64_t> rng, ct, cbias, co;
+      address_form(e, 2, &rng, &ct, &cbias, &co);
+      ok = rng.size() == 2;
+      if (ok) {
+        const int n = (rng[0] == c.gemm.N && cbias[0] == 1 && ct[0] == 1) ? 0 : 1, m = 1 - n;
+        ok = rng[n] == c.gemm.N && rng[m] == c.gemm.M && ct[n] == 1 && cbias[n] == 1 && co[n] == 1 && ct[m] == c.gemm.c_m && cbias[m] == 0 &&
+             co[m] >= c.gemm.N && e.ref[0].addr.k == c.gemm.c_base;
+        if (ok) {
+          prog->fused = e.out_bf16 ? 4 : 3;
+          prog->plan.gemm = c.gemm;
+          prog->gemm = s0.blk->gemm;
+          prog->fuse_bias_off = e.ref[1].addr.k;
+          prog->fuse_o_m = co[m];
+          prog->fuse_o_base = e.ref[2].addr.k;
+          prog->temp_bytes[s0.dst] = 0;
+        }
       }
     }
   }
@@ -214,7 +245,11 @@ stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void*
   const int R = (int)prog->input_slot.size();
   if (prog->fused) {
     const Stage &s0 = prog->stages[0], &s1 = prog->stages[1];
-    const float* bias = (const float*)inputs[prog->input_slot[s1.src[1]]] + prog->plan.gemm.b_base;
+    const float* bias = (const float*)inputs[prog->input_slot[s1.src[1]]] + prog->fuse_bias_off;
+    if (prog->fused >= 3)
+      e = launch_gemm_bias_relu(prog->plan.gemm, prog->gemm, inputs[prog->input_slot[s0.src[0]]], inputs[prog->input_slot[s0.src[1]]], bias,
+                                output, prog->fuse_o_m, prog->fuse_o_base, prog->fused == 4, (hipStream_t)hip_stream);
+    else
     e = launch_conv_bias_relu(prog->plan.conv, prog->conv, inputs[prog->input_slot[s0.src[0]]], inputs[prog->input_slot[s0.src[1]]], bias,
                               output, prog->fused == 2, (hipStream_t)hip_stream);
     if (e != hipSuccess) return fail(STRIPE_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));

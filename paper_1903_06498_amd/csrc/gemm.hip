@@ -32,7 +32,22 @@ struct GemmParams {
   int64_t a_m, b_k, c_m;      // row strides in elements (a_k = b_n = c_n = 1); for a transposed B ([n][k], k contiguous) b_k holds its row stride
   int64_t a_base, b_base, c_base;
   int64_t a_b, b_b, c_b;      // element distance between two products of a batch (LDS-direct kernel only)
+  // Fused following statement O = relu(C + bias[n]) (LDS-direct kernels, float modes): epi 0 = none, 1 = fp32
+  // output, 2 = bf16 output; the C pointer and c_m / c_base then describe O.
+  const float* bias;
+  int32_t epi, pad2_;
 };
+
+// Fused epilogue of one accumulator value: bias, relu, store as fp32 or bf16 (round to nearest even).
+__device__ __forceinline__ void epi_store(const GemmParams& p, float* C, int64_t off, float v, float bias) {
+  v = __builtin_fmaxf(v + bias, 0.f);
+  if (p.epi == 1) {
+    __builtin_nontemporal_store(v, C + off);
+  } else {
+    const uint32_t u = __float_as_uint(v);
+    ((uint16_t*)C)[off] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);
+  }
+}
 
 constexpr int BM = 256, BN = 256, BK = 64;
 constexpr int WAVES_M = 2, WAVES_N = 4;            // 8 wavefronts, 512 lanes
@@ -710,6 +725,26 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
   d_tile<WAVES, SCHED, 3, false, 0, false, MODE>(c, lds, last4 + 3, af, bf, acc);
 
   const int fr = lane & 31, fh = lane >> 5;
+  if (!(MODE & D_I8) && p.epi) {   // the fused form of a following relu(C + bias) statement; uniform branch
+    const int64_t off0 = p.c_base + ((int64_t)tm * BM + wm * 128 + 4 * fh) * p.c_m + (int64_t)tn * BN + wn * 32 * FN + fr;
+    float bj[FN];
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+      const int64_t gn = (int64_t)tn * BN + wn * 32 * FN + fr + 32 * j;
+      bj[j] = p.bias[(MODE & D_RAGGED) ? (gn < p.N ? gn : p.N - 1) : gn];
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < FN; ++j)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int r = 32 * i + 8 * (v / 4) + (v % 4);
+          const int64_t gm = (int64_t)tm * BM + wm * 128 + 4 * fh + r, gn = (int64_t)tn * BN + wn * 32 * FN + fr + 32 * j;
+          if (!(MODE & D_RAGGED) || (gm < p.M && gn < p.N)) epi_store(p, C, off0 + (int64_t)r * p.c_m + 32 * j, acc[i][j][v], bj[j]);
+        }
+    return;
+  }
   float* c_g = C + p.c_base + ((int64_t)tm * BM + wm * 128 + 4 * fh) * p.c_m + (int64_t)tn * BN + wn * 32 * FN + fr;
 #pragma unroll
   for (int i = 0; i < 4; ++i)
@@ -846,6 +881,15 @@ __global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const
     D_FENCE();
   }
 
+  if (!(MODE & D_I8) && p.epi) {   // fused relu(C + bias)
+    const int64_t off0 = p.c_base + ((int64_t)tm * T_BM + wm * 64 * W8 + 4 * fh) * p.c_m + (int64_t)tn * T_BN + wn * 32 + fr;
+    const float bn = p.bias[(int64_t)tn * T_BN + wn * 32 + fr];
+#pragma unroll
+    for (int q = 0; q < NF; ++q)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) epi_store(p, C, off0 + (int64_t)(32 * q + 8 * (v / 4) + (v % 4)) * p.c_m, acc[q][v], bn);
+    return;
+  }
   float* c_g = C + p.c_base + ((int64_t)tm * T_BM + wm * 64 * W8 + 4 * fh) * p.c_m + (int64_t)tn * T_BN + wn * 32 + fr;
 #pragma unroll
   for (int q = 0; q < NF; ++q)
@@ -876,6 +920,9 @@ GemmParams make_params(const GemmShape& g, bool i8 = false) {
   p.a_b = i8 ? g.a_b / 2 : g.a_b;
   p.b_b = i8 ? g.b_b / 2 : g.b_b;
   p.c_b = g.c_b;
+  p.bias = nullptr;
+  p.epi = 0;
+  p.pad2_ = 0;
   return p;
 }
 
@@ -997,8 +1044,27 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
   return true;
 }
 
+static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, const float* bias, int epi,
+                                  int64_t o_m, int64_t o_base, hipStream_t st);
+
+bool gemm_can_fuse_bias_relu(const GemmShape& g, const GemmLaunch& l) {
+  // the LDS-direct kernels in their float modes, one product (no batch)
+  return g.batch <= 1 && ((l.variant >= 20 && l.variant < 40) || l.variant == 50 || l.variant == 51);
+}
+
+hipError_t launch_gemm_bias_relu(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, const void* bias, void* out,
+                                 int64_t o_m, int64_t o_base, bool out_bf16, hipStream_t st) {
+  if (!gemm_can_fuse_bias_relu(g, l) || !bias || ((uintptr_t)bias % 4) || ((uintptr_t)out % (out_bf16 ? 2 : 4))) return hipErrorInvalidValue;
+  return launch_gemm_epi(g, l, a, b, out, (const float*)bias, out_bf16 ? 2 : 1, o_m, o_base, st);
+}
+
 hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t st) {
-  if (((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % 4)) return hipErrorInvalidValue;
+  return launch_gemm_epi(g, l, a, b, c, nullptr, 0, g.c_m, g.c_base, st);
+}
+
+static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, const float* bias, int epi,
+                                  int64_t o_m, int64_t o_base, hipStream_t st) {
+  if (((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % (epi == 2 ? 2 : 4))) return hipErrorInvalidValue;
   const bool i8 = (l.variant >= 40 && l.variant < 50) || l.variant == 52;
   const GemmParams p = make_params(g, i8);
   const bool t128_w8 = l.variant >= 50 && l.t128_waves == 8;
@@ -1025,6 +1091,10 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
   const int lds_bytes = l.variant >= 50 ? T_LDS : l.variant >= 20 ? D_LDS : 2 * STAGE;
   GemmParams pk = p;
   if (l.variant >= 20) pk.k_tiles = (int)(g.K / (i8 ? 64 : D_BK));
+  pk.bias = bias;
+  pk.epi = epi;
+  pk.c_m = o_m;
+  pk.c_base = o_base;
   if (l.variant >= 50) {
     pk.tiles_m = (int)(g.M / T_BM);
     pk.tiles_n = (int)(g.N / T_BN);

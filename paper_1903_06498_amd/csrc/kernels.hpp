@@ -37,6 +37,11 @@ struct GemmLaunch {
 };
 bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info);
 hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t stream);
+// The product fused with a following statement O[m,n] = relu(C[m,n] + bias[n]) (C = the product's output, which then
+// never reaches memory): O fp32 or bf16 with row stride o_m and element offset o_base.
+bool gemm_can_fuse_bias_relu(const GemmShape& g, const GemmLaunch& l);
+hipError_t launch_gemm_bias_relu(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, const void* bias, void* out,
+                                 int64_t o_m, int64_t o_base, bool out_bf16, hipStream_t stream);
 
 // ---- nested-tile convolution-shaped contraction on matrix cores -----------
 struct ConvLaunch {

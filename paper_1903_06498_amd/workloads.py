@@ -350,9 +350,27 @@ def conv_bias_relu_program(N, H, W, Ci, Co, R, S, stride, pad, in_dtype="bf16", 
     return make_root(bufs, s0)
 
 
+def linear_bias_relu_program(M, N, K, out_dtype="bf16", b_transposed=True) -> Block:
+    """A Linear layer with activation as two statements:  T[m,n] += X[m,k] * W[n,k]  (W as stored by a Linear layer;
+    row-major [k][n] with b_transposed=False), then  O[m,n] = relu(T[m,n] + B[n]).  Root buffers: X, W, B, T (f32
+    temporary), O."""
+    wshape, wacc = ((N, K), ["n", "k"]) if b_transposed else ((K, N), ["k", "n"])
+    bufs = [Buffer("X", "in", "bf16", (M, K)), Buffer("W", "in", "bf16", wshape), Buffer("B", "in", "f32", (N,)),
+            Buffer("T", "temp", "f32", (M, N)), Buffer("O", "out", out_dtype, (M, N))]
+    s0 = make_level(dict(m=M, n=N, k=K), [(["m", "k"], "assign"), (wacc, "assign"), (["m", "n"], "add")],
+                    buffers=[bufs[0], bufs[1], Buffer("T", "out", "f32", (M, N))], intrinsic="mul")
+    s0.parent_refs = [0, 1, 3]
+    s1 = make_level(dict(m=M, n=N), [(["m", "n"], "assign"), (["n"], "assign"), (["m", "n"], "assign")],
+                    buffers=[Buffer("T", "in", "f32", (M, N)), bufs[2], bufs[4]], intrinsic="add_relu")
+    s1.parent_refs = [3, 2, 4]
+    s0.next = s1
+    return make_root(bufs, s0)
+
+
 # Further shapes the kernel families cover, for measurements beyond the five configurations (bench.py --workload).
 EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32",
-               "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "gemm_bf16_1024", "gemm_bf16_2048")
+               "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "gemm_bf16_1024", "gemm_bf16_2048",
+               "linear_bias_relu_4096")
 
 
 def extra_block(name: str) -> Block:
@@ -367,6 +385,8 @@ def extra_block(name: str) -> Block:
         return matmul_block(4096, 4096, 4096, "i8", "i32", b_transposed=True)
     if name == "resnet_conv_bias_relu_bf16":   # the ResNet block followed by O = relu(T + bias), bf16 output: two statements
         return conv_bias_relu_program(32, 56, 56, 64, 64, 3, 3, 1, 1, "bf16", "bf16")
+    if name == "linear_bias_relu_4096":        # relu(X * W^T + b), 4096^3, bf16 output: two statements fused into the GEMM
+        return linear_bias_relu_program(4096, 4096, 4096, "bf16", b_transposed=True)
     if name == "resnet_conv_bias_relu_f32":    # the same with an fp32 output
         return conv_bias_relu_program(32, 56, 56, 64, 64, 3, 3, 1, 1, "bf16", "f32")
     if name == "pointwise_conv_bf16":          # 1x1 convolution, 256 -> 64 channels on the ResNet block's 32 x 56 x 56 pixels
@@ -387,7 +407,7 @@ def extra_inputs(name: str):
     if name in ("resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32"):
         return config_inputs("resnet_conv_bf16") + [seeded_tensor((64,), "f32", 2)]
     blk = extra_block(name)
-    return [seeded_tensor(r.sizes, r.dtype, seed) for seed, r in enumerate(blk.refs[:-1])]
+    return [seeded_tensor(r.sizes, r.dtype, seed) for seed, r in enumerate(blk.refs) if r.dir == "in"]
 
 
 def config_inputs(name: str):

@@ -341,6 +341,28 @@ def test_fused_convolution_bias_relu(N, H, Wd, out_dt, fuse, monkeypatch):
         assert " ; " in info["kernel"], info["kernel"]
 
 
+@pytest.mark.parametrize("fuse", [1, 0])
+@pytest.mark.parametrize("M,N,K,bt,out_dt", [(256, 256, 128, True, "bf16"), (300, 520, 256, True, "f32"), (512, 256, 128, False, "bf16"),
+                                             (384, 640, 256, True, "f32"), (70, 264, 128, False, "f32"), (1024, 1024, 256, True, "bf16")])
+def test_fused_linear_bias_relu(M, N, K, bt, out_dt, fuse, monkeypatch):
+    """O = relu(X * W^T + b) as two statements: fused into the dense-contraction kernels' epilogue (all their float
+    modes: 256 and 128 tiles, transposed / row-major W, ragged edges), or unfused through a temporary."""
+    monkeypatch.setenv("STRIPE_TUNE", f"fuse={fuse}")
+    prog = W.linear_bias_relu_program(M, N, K, out_dt, b_transposed=bt)
+    x = W.seeded_tensor((M, K), "bf16", 0)
+    w = (W.seeded_tensor((N, K) if bt else (K, N), "bf16", 1).float() * (1.0 / K) ** 0.5).to(torch.bfloat16)
+    b = W.seeded_tensor((N,), "f32", 2)
+    gpu, sb = run_gpu(prog, [x, w, b], return_block=True)
+    assert ("+bias" in sb.info["kernel"]) == bool(fuse) and sb.info["path_name"] == "mfma_gemm", sb.info["kernel"]
+    res = O.evaluate_program(prog, [W.to_numpy(x).ravel(), W.to_numpy(w).ravel(), b.numpy()], threads=8)
+    err = np.abs(gpu.astype(np.float64) - res.out)
+    tol = 4e-3 * math.sqrt(K) * float(x.float().abs().max()) * float(w.float().abs().max())
+    if out_dt == "bf16":
+        tol = tol + 2.0 ** -8 * np.abs(res.out)
+    assert res.touched.all() and np.all(err <= tol), float(np.max(err - tol))
+    assert (gpu == 0).any() and (gpu > 0).any()
+
+
 def test_fused_convolution_bias_relu_full_size():
     """The ResNet-shaped block with a bf16 output, fused: all-ones closed form on every element, and the seeded
     inputs against the unfused two-launch execution of the same program (which the small cases pin to the oracle)."""
