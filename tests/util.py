@@ -5,6 +5,7 @@ Tolerances (stated once, used everywhere):
   max / min blocks    exact equality of values (order-independent operation)
   fp32-input blocks   max |g - r| / max(|r|, rms(r)) <= 1e-4 against the fp64 oracle
   bf16-input blocks   |g - r| <= 4e-3 * sqrt(K) * max|a| * max|b|, K = reduction points per output
+  bf16 output buffers the above plus 2^-8 * |r| (one rounding to bf16 on store; the oracle returns the unrounded value)
 Elements no iteration writes must keep the sentinel the output was filled with.
 """
 from __future__ import annotations
