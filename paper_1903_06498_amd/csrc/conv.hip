@@ -474,6 +474,8 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
   if (c.f_k != C_CI || c.f_s != C_CO * C_CI || c.f_r != 3 * C_CO * C_CI) return false;
   for (int64_t v : {c.i_n, c.i_y, c.i_x, c.i_base, c.f_base})
     if (v % 8) return false;
+  for (int64_t v : {c.o_n, c.o_y, c.o_x, c.o_base})   // 16-byte stores
+    if (v % 4) return false;
   // four-wavefront kernel: strips of 7 rows, 32-bit element offsets inside an image
   const bool offsets_fit = c.i_y >= 0 && c.i_x >= 0 && c.o_x >= 0 && (c.H * c.i_y + c.W * c.i_x + 64) < ((int64_t)1 << 30) &&
                            (c.W * c.o_x + 64) < ((int64_t)1 << 30);
@@ -539,7 +541,7 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
 static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias,
                                   int epi, hipStream_t st) {
   if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
-  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
+  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
   if (l.variant > kConvW4Variant) {
     const int mode = l.variant - kConvW4Variant;   // 1: four wavefronts, 2: eight, 3: eight with LDS-direct staging
     ConvParams pp = make_params(c, W4_ROWS);

@@ -189,6 +189,24 @@ def make_root(buffers: Sequence[Buffer], child: Block) -> Block:
     return root
 
 
+def embed(root: Block, origins: Sequence[Sequence[int]], parent_sizes: Sequence[Sequence[int]]) -> Block:
+    """Declare every buffer of `root` as a window of a larger, contiguous tensor: buffer r starts at coordinate
+    origins[r] of a tensor of extents parent_sizes[r].  The root refinement then carries that origin as its
+    constant (Figure 5 writes it 'in I[0, 0, 0]' for a window at the tensor's own origin) and every level the parent
+    tensor's strides; the declared sizes stay the window's.  The arrays handed to an evaluator are the parents."""
+    for r, (org, psz) in enumerate(zip(origins, parent_sizes)):
+        top = root.refs[r]
+        if len(org) != len(top.sizes) or len(psz) != len(top.sizes):
+            raise ValueError(f"{top.name}: one origin and one parent extent per dimension")
+        if any(o < 0 or o + n > p for o, n, p in zip(org, top.sizes, psz)):
+            raise ValueError(f"{top.name}: the window leaves its parent tensor")
+        strides = contiguous_strides(psz)
+        for lv in root.levels():
+            lv.refs[r].strides = list(strides)
+        top.access_const = [int(o) for o in org]
+    return root
+
+
 def flat_block(buffers: Sequence[Buffer], idx: Dict[str, int], refs: Sequence[Tuple],
                constraints: Sequence[str] = (), intrinsic: str = "mul") -> Block:
     """A root declaration with one un-nested block below it (Figure 5a's shape)."""
@@ -464,7 +482,11 @@ def to_numpy(t) -> np.ndarray:
     return t.numpy()
 
 
+def buffer_extent(ref: Refinement) -> int:
+    """Elements a root buffer must hold: largest declared address + 1 (the root constant is the window's origin)."""
+    return sum((c + n - 1) * s for c, n, s in zip(ref.access_const, ref.sizes, ref.strides)) + 1
+
+
 def output_extent(root: Block) -> int:
-    """Elements the output buffer must hold: largest declared address + 1."""
-    o = root.refs[-1]
-    return sum((c + n - 1) * s for c, n, s in zip(o.access_const, o.sizes, o.strides)) + 1
+    """Elements the output buffer must hold."""
+    return buffer_extent(root.refs[-1])

@@ -78,7 +78,7 @@ def evaluate(root, inputs, exact=lambda v: Fraction(v)):
 
 
 def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32", agg="add", intrinsic="mul",
-                 injective_out=False, max_range=4, contraction_roles=False):
+                 injective_out=False, max_range=4, contraction_roles=False, root_origin=0):
     """A random tiny block (every range <= 4, small integer coefficients).
 
     With injective_out every output dimension is moved by exactly one index
@@ -86,6 +86,9 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
     With contraction_roles (needs injective_out and two inputs) every output index is given a role as in a
     tensor contraction: it moves the first input only, the second input only, or both; the other indexes
     are reduction indexes.  Coefficients, signs and constraints stay random.
+    With root_origin > 0 every buffer is declared as a window of a larger tensor: the root refinement gets a
+    random origin in 0..root_origin per dimension and the strides are those of a parent tensor that holds the
+    window at that origin (plus a little slack).
     Accesses are made in-bounds by measuring, per buffer dimension, the
     extreme coordinates over the executed points and sizing/offsetting the
     root buffer to contain them.  Views of intermediate levels are sized the
@@ -151,8 +154,12 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
                              cons_coeff=cons_coeff, cons_const=cons_const, acc=rand_level(li, nv)))
         parent_nv = nv
 
+    origin = [[rng.randint(0, root_origin) for _ in range(nd)] for nd in ndims]
+    slack = [[rng.randint(0, 1) if root_origin else 0 for _ in range(nd)] for nd in ndims]
+
     # Build with provisional sizes, measure extremes, then fix sizes and offsets.
     def build(root_sizes, root_off, mid_sizes, mid_off):
+        parent = [[n + o + s for n, o, s in zip(root_sizes[r], origin[r], slack[r])] for r in range(n_in + 1)]
         levels = []
         for li, sp in enumerate(lv_specs):
             refs = []
@@ -166,7 +173,7 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
                 sizes = [1] * nd if li == n_levels - 1 else mid_sizes[r]
                 lv_agg = agg if r == n_in else "assign"
                 refs.append(W.Refinement(names[r], dirs[r], dts[r], lv_agg, sp["acc"][r], const, list(sizes),
-                                         W.contiguous_strides(root_sizes[r])))
+                                         W.contiguous_strides(parent[r])))
             b = W.Block(idx_names=[f"i{li}_{j}" for j in range(sp["n_idx"])], ranges=sp["ranges"],
                         passed_names=[f"p{li}_{j}" for j in range(len(sp["passed_coeff"]))],
                         passed_coeff=sp["passed_coeff"], passed_const=sp["passed_const"],
@@ -178,8 +185,8 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
         root = W.Block(idx_names=[], ranges=[])
         for r in range(n_in + 1):
             nd = ndims[r]
-            root.refs.append(W.Refinement(names[r], dirs[r], dts[r], "assign", [[] for _ in range(nd)], [0] * nd,
-                                          list(root_sizes[r]), W.contiguous_strides(root_sizes[r])))
+            root.refs.append(W.Refinement(names[r], dirs[r], dts[r], "assign", [[] for _ in range(nd)], list(origin[r]),
+                                          list(root_sizes[r]), W.contiguous_strides(parent[r])))
         root.child = levels[0]
         return root
 
@@ -217,7 +224,7 @@ def random_block(rng: random.Random, nested: bool, dtype_in="i8", dtype_out="i32
                 in_lo[r][d] = inner if in_lo[r][d] is None else min(in_lo[r][d], inner)
                 in_hi[r][d] = inner if in_hi[r][d] is None else max(in_hi[r][d], inner)
     if not any_point:
-        return random_block(rng, nested, dtype_in, dtype_out, agg, intrinsic, injective_out, max_range, contraction_roles)
+        return random_block(rng, nested, dtype_in, dtype_out, agg, intrinsic, injective_out, max_range, contraction_roles, root_origin)
     if nested:
         # The inner level's constant places its coordinate at the start of the
         # outer level's view; the outer level's constant places the total

@@ -356,3 +356,89 @@ def test_random_tiny_float_blocks_against_exact_fractions(seed):
     res = O.evaluate(blk, ins)
     for e, v in want.items():
         assert abs(res.out[e] - float(v)) <= 1e-13 * max(1.0, abs(float(v)))
+
+
+# ------------------------------------------------- root refinements with an origin (windows of larger tensors)
+def test_root_origin_matmul_windows_match_library_slices():
+    """Every buffer declared as a window of a larger tensor (the root refinement's constant is the window's origin):
+    the result is the library product of the slices, written into the slice of the output tensor, nothing else."""
+    M, N, K = 9, 7, 11
+    pa, pb, pc = (M + 5, K + 4), (K + 3, N + 6), (M + 4, N + 3)
+    oa, ob, oc = (2, 3), (1, 5), (3, 1)
+    blk = W.embed(W.matmul_block(M, N, K, "f32", "f32"), [oa, ob, oc], [pa, pb, pc])
+    a, b = W.seeded_tensor(pa, "f32", 0), W.seeded_tensor(pb, "f32", 1)
+    ext = W.output_extent(blk)
+    assert ext == (oc[0] + M - 1) * pc[1] + oc[1] + N
+    res = O.evaluate(blk, [W.to_numpy(a).ravel(), W.to_numpy(b).ravel()], out=np.full(ext, 777.0))
+    ref = (a.double()[oa[0]:oa[0] + M, oa[1]:oa[1] + K] @ b.double()[ob[0]:ob[0] + K, ob[1]:ob[1] + N]).numpy()
+    img = np.full(pc[0] * pc[1], 777.0)
+    img[:ext] = res.out
+    img = img.reshape(pc)
+    win = img[oc[0]:oc[0] + M, oc[1]:oc[1] + N]
+    assert np.max(np.abs(win - ref)) <= 1e-12 * np.max(np.abs(ref))
+    img[oc[0]:oc[0] + M, oc[1]:oc[1] + N] = 777.0
+    assert np.all(img == 777.0)                       # nothing outside the window was written
+    assert res.touched.sum() == M * N and res.n_points == M * N * K
+
+
+def test_root_origin_conv_and_pool_windows_match_library_slices():
+    """A strided convolution and a max pooling over a crop of a larger image, into a crop of a larger output."""
+    N, H, Wd, Ci, Co, R, S, s, p = 2, 11, 9, 3, 4, 3, 5, 2, 1
+    Ho, Wo = (H + 2 * p - R) // s + 1, (Wd + 2 * p - S) // s + 1
+    pi, pf, po = (N + 1, H + 3, Wd + 4, Ci + 2), (R + 1, S, Co + 2, Ci + 1), (N + 2, Ho + 1, Wo + 2, Co + 3)
+    oi, of, oo = (1, 2, 3, 1), (1, 0, 2, 1), (2, 0, 1, 3)
+    blk = W.embed(W.conv2d_block(N, H, Wd, Ci, Co, R, S, s, p, "i8", "i32"), [oi, of, oo], [pi, pf, po])
+    i, f = W.seeded_tensor(pi, "i8", 0), W.seeded_tensor(pf, "i8", 1)
+    res = O.evaluate(blk, [W.to_numpy(i).ravel(), W.to_numpy(f).ravel()])
+    ic = i[oi[0]:oi[0] + N, oi[1]:oi[1] + H, oi[2]:oi[2] + Wd, oi[3]:oi[3] + Ci]
+    fc = f[of[0]:of[0] + R, of[1]:of[1] + S, of[2]:of[2] + Co, of[3]:of[3] + Ci]
+    ref = torch.nn.functional.conv2d(ic.long().permute(0, 3, 1, 2), fc.long().permute(2, 3, 0, 1), stride=s,
+                                     padding=p).permute(0, 2, 3, 1).numpy()
+    img = np.zeros(int(np.prod(po)), np.int64)
+    img[:res.out.size] = res.out
+    img = img.reshape(po)
+    assert np.array_equal(img[oo[0]:oo[0] + N, oo[1]:oo[1] + Ho, oo[2]:oo[2] + Wo, oo[3]:oo[3] + Co], ref)
+    assert res.touched.sum() == ref.size
+
+    N, H, Wd, Cc = 1, 13, 10, 3
+    Ho, Wo = (H + 2 - 3) // 2 + 1, (Wd + 2 - 3) // 2 + 1
+    pi, po = (N + 1, H + 2, Wd + 1, Cc + 2), (N, Ho + 3, Wo + 1, Cc + 1)
+    oi, oo = (1, 1, 0, 2), (0, 2, 1, 0)
+    blk = W.embed(W.maxpool_block(N, H, Wd, Cc, 3, 2, 1), [oi, oo], [pi, po])
+    x = W.seeded_tensor(pi, "f32", 0)
+    res = O.evaluate(blk, [W.to_numpy(x).ravel()])
+    xc = x[oi[0]:oi[0] + N, oi[1]:oi[1] + H, oi[2]:oi[2] + Wd, oi[3]:oi[3] + Cc]
+    ref = torch.nn.functional.max_pool2d(xc.permute(0, 3, 1, 2), 3, 2, 1).permute(0, 2, 3, 1).numpy()
+    img = np.zeros(int(np.prod(po)))
+    img[:res.out.size] = res.out
+    img = img.reshape(po)
+    assert np.array_equal(img[oo[0]:oo[0] + N, oo[1]:oo[1] + Ho, oo[2]:oo[2] + Wo, oo[3]:oo[3] + Cc], ref.astype(np.float64))
+
+
+def test_root_origin_moves_the_view_not_the_bounds():
+    """Bounds are those of the window: an access that leaves the declared window is an error even where the parent
+    tensor still has elements there."""
+    blk = W.embed(W.matmul_block(3, 4, 5, "f32", "f32"), [(1, 1), (1, 1), (1, 1)], [(6, 8), (8, 7), (6, 7)])
+    blk.child.ranges[2] = 6                          # k runs one past the 5-long window of A and B
+    with pytest.raises(O.OracleError) as e:
+        O.evaluate(blk, [np.zeros(48, np.float32), np.zeros(56, np.float32)])
+    assert e.value.code == 2
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_tiny_blocks_with_root_origins_against_dictionary_evaluator(seed):
+    rng = random.Random(500 + seed)
+    agg = ["add", "max", "min", "mul"][seed % 4]
+    intrinsic = ["mul", "copy", "add"][seed % 3]
+    blk = brute.random_block(rng, seed % 2 == 1, "i32", "i32", agg, intrinsic, root_origin=3)
+    nrng = np.random.default_rng(seed)
+    ins = [nrng.integers(-3, 4, size=W.buffer_extent(r), dtype=np.int32) for r in blk.refs[:-1]]
+    want = brute.evaluate(blk, ins, exact=int)
+    ext = W.output_extent(blk)
+    res = O.evaluate(blk, ins, out=np.full(ext, 12345, np.int64))
+    assert res.n_points == sum(1 for _ in brute.enumerate_points(blk))
+    for e in range(ext):
+        if e in want:
+            assert res.touched[e] == 1 and res.out[e] == want[e], (e, res.out[e], want[e])
+        else:
+            assert res.touched[e] == 0 and res.out[e] == 12345
