@@ -186,6 +186,23 @@ stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, st
 stripe_status_t stripe_block_run(stripe_block_t* blk, const void* const* inputs, void* output,
                                  void* hip_stream);
 
+/*
+ * stripe_block_run for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the same launches, but the temporaries of a statement list live in a
+ * fixed array of STRIPE_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU the library
+ * runs on holds its own copy until the process ends) instead of memory the handle allocates on its first run.
+ * The call makes no hipMalloc / hipFree and calls no allocating library routine; the caller still passes inputs
+ * and output.  Temporaries are placed one after the other, each rounded up to 256 bytes; if their sum exceeds
+ * STRIPE_STATIC_SCRATCH_BYTES the call returns STRIPE_ERR_NOMEM and launches nothing (use stripe_block_run
+ * then).  Handles without temporaries (single blocks, fused statement lists) use no scratch at all.
+ * Every call on a GPU shares that GPU's array, which keeps the previous call's contents; nothing in it needs to
+ * start at zero (a statement writes every element of a temporary before a later one reads it).  Two calls that
+ * overlap on one GPU (different streams, or different host threads) and both use temporaries RACE on the array:
+ * serialise them on one stream.  The array's device address is looked up on the first call on each device.
+ */
+#define STRIPE_STATIC_SCRATCH_BYTES (8u << 20)
+stripe_status_t stripe_block_run_static(stripe_block_t* blk, const void* const* inputs, void* output, void* hip_stream);
+
 stripe_status_t stripe_block_query(const stripe_block_t* blk, stripe_block_info_t* info);
 
 void stripe_block_destroy(stripe_block_t* blk);

@@ -28,7 +28,7 @@ _DTYPE = {"i8": 0, "i32": 1, "bf16": 2, "f32": 3}
 _AGG = {"assign": 0, "add": 1, "max": 2, "min": 3, "mul": 4}
 _INTR = {"mul": 0, "copy": 1, "add": 2, "add_relu": 3}
 
-EXPORTS = ("stripe_block_create", "stripe_block_create_for_path", "stripe_block_run", "stripe_block_query",
+EXPORTS = ("stripe_block_create", "stripe_block_create_for_path", "stripe_block_run", "stripe_block_run_static", "stripe_block_query",
            "stripe_block_destroy", "stripe_status_string", "stripe_last_error", "stripe_device_copy",
            "stripe_tile_cost", "stripe_tile_search", "stripe_block_tile", "stripe_desc_free")
 
@@ -98,6 +98,8 @@ def _load():
     lib.stripe_block_create_for_path.argtypes = [C.POINTER(stripe_block_desc_t), C.c_int, C.POINTER(handle)]
     lib.stripe_block_run.restype = C.c_int
     lib.stripe_block_run.argtypes = [handle, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]
+    lib.stripe_block_run_static.restype = C.c_int
+    lib.stripe_block_run_static.argtypes = [handle, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]
     lib.stripe_block_query.restype = C.c_int
     lib.stripe_block_query.argtypes = [handle, C.POINTER(stripe_block_info_t)]
     lib.stripe_block_destroy.restype = None
@@ -201,6 +203,11 @@ def stripe_block_create(block, path: str = "auto") -> C.c_void_p:
 def stripe_block_run(handle, input_ptrs: Sequence[int], output_ptr: int, stream: int = 0) -> None:
     arr = (C.c_void_p * len(input_ptrs))(*[C.c_void_p(int(p)) for p in input_ptrs])
     _check(lib.stripe_block_run(handle, arr, C.c_void_p(int(output_ptr)), C.c_void_p(int(stream))))
+
+
+def stripe_block_run_static(handle, input_ptrs: Sequence[int], output_ptr: int, stream: int = 0) -> None:
+    arr = (C.c_void_p * len(input_ptrs))(*[C.c_void_p(int(p)) for p in input_ptrs])
+    _check(lib.stripe_block_run_static(handle, arr, C.c_void_p(int(output_ptr)), C.c_void_p(int(stream))))
 
 
 def stripe_block_query(handle) -> dict:
@@ -326,6 +333,21 @@ class StripeBlock:
             arr[i] = t if isinstance(t, int) else t.data_ptr()
         out = output if isinstance(output, int) else output.data_ptr()
         st = lib.stripe_block_run(self.handle, arr, out, stream)
+        if st != STRIPE_OK:
+            raise StripeError(st, stripe_last_error())
+
+    def run_static(self, inputs, output, stream: Optional[int] = None) -> None:
+        """As run(), through stripe_block_run_static: temporaries in the library's static scratch array."""
+        if stream is None:
+            import torch
+            stream = torch.cuda.current_stream().cuda_stream
+        if len(inputs) != self._n_in:
+            raise ValueError(f"expected {self._n_in} inputs")
+        arr = self._in_arr
+        for i, t in enumerate(inputs):
+            arr[i] = t if isinstance(t, int) else t.data_ptr()
+        out = output if isinstance(output, int) else output.data_ptr()
+        st = lib.stripe_block_run_static(self.handle, arr, out, stream)
         if st != STRIPE_OK:
             raise StripeError(st, stripe_last_error())
 

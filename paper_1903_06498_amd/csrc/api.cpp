@@ -1,8 +1,10 @@
 // C ABI of the Stripe block executor: see include/stripe.h.
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -44,6 +46,11 @@ struct stripe_block {
       if (t) (void)hipFree(t);
   }
 };
+
+// Scratch memory of stripe_block_run_static(): one array per GPU, part of the code object, never allocated or
+// freed.  In host code the name is only a stand-in for the symbol; the device address of each GPU's copy is
+// looked up once per device (static_scratch_of) and only that pointer is ever handed to a kernel.
+static __device__ __align__(256) unsigned char scratch[STRIPE_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -229,11 +236,64 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
   return STRIPE_OK;
 }
 
-stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void* output, void* hip_stream) {
+bool need_scratch(const stripe_block* prog) {
+  for (int64_t b : prog->temp_bytes)
+    if (b) return true;
+  return false;
+}
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+std::atomic<unsigned char*> g_scratch_ptr[kMaxDevices];
+
+// Device address of the current GPU's copy of `scratch` (looked up on the first call on that GPU).
+stripe_status_t static_scratch_of(int dev, unsigned char** out) {
+  if (dev < 0 || dev >= kMaxDevices) return fail(STRIPE_ERR_UNSUPPORTED, "device ordinal beyond the 64 this call keeps scratch pointers for");
+  unsigned char* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (!p) {
+      void* sym = nullptr;
+      const hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+      if (e != hipSuccess || !sym) return fail(STRIPE_ERR_HIP, std::string("hipGetSymbolAddress(scratch) failed: ") + hipGetErrorString(e));
+      p = (unsigned char*)sym;
+      g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return STRIPE_OK;
+}
+
+int64_t round_up_256(int64_t v) { return (v + 255) / 256 * 256; }
+
+// use_static: temporaries are carved out of the GPU's static scratch array instead of memory the handle allocates.
+stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void* output, void* hip_stream, bool use_static) {
   int dev = -1;
-  hipError_t e = hipGetDevice(&dev);
+  hipError_t e = hipSuccess;
+  void* static_temp[16] = {};   // a statement list declares at most 16 root buffers
+  if (use_static) {
+    int64_t need = 0;
+    for (int64_t b : prog->temp_bytes) need += round_up_256(b);
+    if (need > (int64_t)STRIPE_STATIC_SCRATCH_BYTES)
+      return fail(STRIPE_ERR_NOMEM, "the block's temporaries need " + std::to_string(need) + " bytes, the static scratch holds " +
+                                        std::to_string((long long)STRIPE_STATIC_SCRATCH_BYTES));
+  }
+  e = hipGetDevice(&dev);
   if (e != hipSuccess) return fail(STRIPE_ERR_HIP, hipGetErrorString(e));
-  if (dev != prog->temp_dev) {   // first run (on this device): the temporaries
+  if (use_static) {
+    unsigned char* base = nullptr;
+    if (need_scratch(prog)) {
+      const stripe_status_t rc = static_scratch_of(dev, &base);
+      if (rc != STRIPE_OK) return rc;
+    }
+    int64_t off = 0;
+    for (size_t r = 0; r < prog->temp_bytes.size(); ++r)
+      if (prog->temp_bytes[r]) {
+        static_temp[r] = base + off;
+        off += round_up_256(prog->temp_bytes[r]);
+      }
+  } else if (dev != prog->temp_dev) {   // first run (on this device): the temporaries
     for (size_t r = 0; r < prog->temp_ptr.size(); ++r) {
       if (prog->temp_ptr[r]) (void)hipFree(prog->temp_ptr[r]);
       prog->temp_ptr[r] = nullptr;
@@ -257,7 +317,8 @@ stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void*
   }
   auto where = [&](int r) -> const void* {
     if (r == R - 1) return output;
-    return prog->input_slot[r] >= 0 ? inputs[prog->input_slot[r]] : prog->temp_ptr[r];
+    if (prog->input_slot[r] >= 0) return inputs[prog->input_slot[r]];
+    return use_static ? static_temp[r] : prog->temp_ptr[r];
   };
   for (const Stage& st : prog->stages) {
     const void* ins[2] = {where(st.src[0]), st.n_in > 1 ? where(st.src[1]) : nullptr};
@@ -331,11 +392,19 @@ stripe_status_t stripe_block_create(const stripe_block_desc_t* desc, stripe_bloc
   return stripe_block_create_for_path(desc, STRIPE_PATH_AUTO, out);
 }
 
+stripe_status_t stripe_block_run_static(stripe_block_t* blk, const void* const* inputs, void* output, void* hip_stream) {
+  if (!blk || !inputs || !output) return fail(STRIPE_ERR_NULL, "blk, inputs or output is NULL");
+  for (int i = 0; i < blk->n_inputs; ++i)
+    if (!inputs[i]) return fail(STRIPE_ERR_NULL, "an input pointer is NULL");
+  if (!blk->stages.empty()) return run_program(blk, inputs, output, hip_stream, /*use_static=*/true);
+  return stripe_block_run(blk, inputs, output, hip_stream);   // a single block has no temporaries: nothing is ever allocated
+}
+
 stripe_status_t stripe_block_run(stripe_block_t* blk, const void* const* inputs, void* output, void* hip_stream) {
   if (!blk || !inputs || !output) return fail(STRIPE_ERR_NULL, "blk, inputs or output is NULL");
   for (int i = 0; i < blk->n_inputs; ++i)
     if (!inputs[i]) return fail(STRIPE_ERR_NULL, "an input pointer is NULL");
-  if (!blk->stages.empty()) return run_program(blk, inputs, output, hip_stream);
+  if (!blk->stages.empty()) return run_program(blk, inputs, output, hip_stream, /*use_static=*/false);
   const Plan& p = blk->plan;
   if (p.noop) return STRIPE_OK;
   hipStream_t s = (hipStream_t)hip_stream;
