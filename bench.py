@@ -52,6 +52,9 @@ KIND = {
     "gemm_i8_4096_bt": ("TOP/s", "mfma", "int8"),
     "gemm_bf16_1024": ("TFLOP/s", "mfma", "bf16"),
     "gemm_bf16_2048": ("TFLOP/s", "mfma", "bf16"),
+    "gemm_bf16_256x256x65536": ("TFLOP/s", "mfma", "bf16"),    # split reduction (STRIPE_TUNE=gemm_splitk=0 times it unsplit)
+    "gemm_i8_256x256x65536_bt": ("TOP/s", "mfma", "int8"),
+    "gemm_bf16_1024x1024x8192": ("TFLOP/s", "mfma", "bf16"),
     "linear_bias_relu_4096": ("TFLOP/s", "mfma", "bf16"),
     "pointwise_conv_bf16": ("TFLOP/s", "hbm", "bf16"),
     "transposed_conv_f32": ("TFLOP/s", "alu", "f32"),

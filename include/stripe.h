@@ -36,7 +36,8 @@ typedef enum {
   STRIPE_ERR_OUT_OF_BOUNDS = 4,   /* an access inside the polyhedron may leave its buffer or view */
   STRIPE_ERR_ASSIGN_CONFLICT = 5, /* 'assign' level whose iterations are not provably disjoint */
   STRIPE_ERR_HIP = 6,             /* a HIP runtime call failed */
-  STRIPE_ERR_NOMEM = 7
+  STRIPE_ERR_NOMEM = 7,           /* out of host or device memory, or a workspace / the static scratch is too small */
+  STRIPE_ERR_MISALIGNED = 8       /* a buffer pointer lacks the 16-byte alignment the planned kernel family needs */
 } stripe_status_t;
 
 typedef enum { STRIPE_I8 = 0, STRIPE_I32 = 1, STRIPE_BF16 = 2, STRIPE_F32 = 3 } stripe_dtype_t;
@@ -147,7 +148,8 @@ typedef struct {
   int32_t lds_bytes;
   int32_t workgroup_size;
   int64_t grid;               /* workgroups per launch */
-  char kernel[64];            /* name of the kernel variant */
+  char kernel[96];            /* name of the kernel variant */
+  int64_t workspace_bytes;    /* device workspace the handle's launches use (see stripe_block_set_workspace); 0 = none */
 } stripe_block_info_t;
 
 /*
@@ -176,32 +178,66 @@ stripe_status_t stripe_block_create_for_path(const stripe_block_desc_t* desc, st
  * between index tuples through different output indexes (O[x + i]) is run as
  * two launches: the aggregation's identity to every reached element, then an
  * atomic combine.  A statement list runs its statements in order on the
- * stream; temporaries that are not fused away live in device memory the
- * handle allocates on its first run on a device (the only allocation run()
- * ever makes) and frees on destroy, so two overlapping runs of such a handle
- * race on them.  Asynchronous: returns after enqueueing; only
- * launch errors are reported.  Calls on different handles may overlap; two
- * overlapping calls that write the same output buffer race.
+ * stream.
+ * Workspace: temporaries of a statement list that are not fused away, and
+ * the partial sums of a dense contraction whose reduction index is split
+ * over workgroups (Section 2.1: aggregations are associative and commutative,
+ * so a reduction may be regrouped; chosen at create for products with few
+ * output tiles and a long reduction), live in a device workspace of
+ * stripe_block_workspace_size() bytes.  If the caller has handed one over
+ * with stripe_block_set_workspace(), run() uses it and never allocates;
+ * otherwise the handle allocates it on its first run on a device (the only
+ * allocation run() ever makes; that first call then is not purely
+ * asynchronous) and frees it on destroy.  Either way two overlapping runs of
+ * one handle race on the workspace.  Handles that report 0 bytes never
+ * allocate.
+ * Alignment: the specialised kernel families move 16 bytes per lane.
+ * Whether a block's strides and origins keep that alignment is decided at
+ * create (a block that does not runs on the generic kernels, which take
+ * any element-aligned pointer); the buffer POINTERS are only seen here, and a
+ * pointer that is not 16-byte aligned, handed to a handle planned for a
+ * specialised family (path != STRIPE_PATH_GENERIC in stripe_block_query),
+ * is refused with STRIPE_ERR_MISALIGNED before anything is launched.
+ * Non-finite inputs are outside the contract of the specialised families:
+ * they realise constraints by feeding zeros for removed points (0 * Inf is
+ * NaN where the definition skips the point) and use IEEE maxNum/minNum for
+ * max/min (a NaN operand is ignored).
+ * Asynchronous: returns after enqueueing; only launch errors are reported.
+ * Calls on different handles may overlap; two overlapping calls that write
+ * the same output buffer race.
  */
 stripe_status_t stripe_block_run(stripe_block_t* blk, const void* const* inputs, void* output,
                                  void* hip_stream);
 
 /*
  * stripe_block_run for callers that cannot allocate device memory (code under HIP graph capture, tight serving
- * loops, harnesses that forbid hipMalloc): the same launches, but the temporaries of a statement list live in a
- * fixed array of STRIPE_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU the library
- * runs on holds its own copy until the process ends) instead of memory the handle allocates on its first run.
+ * loops, harnesses that forbid hipMalloc): the same launches, but the handle's workspace (temporaries of a
+ * statement list, partial sums of a split reduction) lives in a fixed array of STRIPE_STATIC_SCRATCH_BYTES that
+ * is part of the library's code object (each GPU the library runs on holds its own copy until the process
+ * ends) instead of memory the handle allocates on its first run; a workspace set with
+ * stripe_block_set_workspace is not used by this call.
  * The call makes no hipMalloc / hipFree and calls no allocating library routine; the caller still passes inputs
- * and output.  Temporaries are placed one after the other, each rounded up to 256 bytes; if their sum exceeds
- * STRIPE_STATIC_SCRATCH_BYTES the call returns STRIPE_ERR_NOMEM and launches nothing (use stripe_block_run
- * then).  Handles without temporaries (single blocks, fused statement lists) use no scratch at all.
+ * and output.  If stripe_block_workspace_size() exceeds STRIPE_STATIC_SCRATCH_BYTES the call returns
+ * STRIPE_ERR_NOMEM and launches nothing (use stripe_block_run then).  Handles that need no workspace use no
+ * scratch at all.
  * Every call on a GPU shares that GPU's array, which keeps the previous call's contents; nothing in it needs to
- * start at zero (a statement writes every element of a temporary before a later one reads it).  Two calls that
- * overlap on one GPU (different streams, or different host threads) and both use temporaries RACE on the array:
- * serialise them on one stream.  The array's device address is looked up on the first call on each device.
+ * start at zero (every element of a temporary or of a partial-sum image is written before it is read).  Two
+ * calls that overlap on one GPU (different streams, or different host threads) and both need a workspace RACE
+ * on the array: serialise them on one stream.  The array's device address is looked up on the first call on
+ * each device.
  */
 #define STRIPE_STATIC_SCRATCH_BYTES (8u << 20)
 stripe_status_t stripe_block_run_static(stripe_block_t* blk, const void* const* inputs, void* output, void* hip_stream);
+
+/*
+ * The device workspace of a handle (see stripe_block_run).  workspace_size: bytes the handle's launches need, 0
+ * if none.  set_workspace: `device_ptr` (256-byte aligned DEVICE memory of at least that many bytes, owned by
+ * the caller, valid until replaced or the handle is destroyed) becomes the workspace of every later
+ * stripe_block_run, which then never allocates; NULL returns to handle-owned memory.  STRIPE_ERR_NOMEM if
+ * `bytes` is too small, STRIPE_ERR_INVALID_DESC if misaligned.  Host only.
+ */
+stripe_status_t stripe_block_workspace_size(const stripe_block_t* blk, size_t* bytes);
+stripe_status_t stripe_block_set_workspace(stripe_block_t* blk, void* device_ptr, size_t bytes);
 
 stripe_status_t stripe_block_query(const stripe_block_t* blk, stripe_block_info_t* info);
 

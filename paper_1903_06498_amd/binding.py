@@ -19,7 +19,7 @@ LIB_PATH = os.path.join(_HERE, "libstripe_hip.so")
 
 STRIPE_OK = 0
 STATUS_NAMES = {0: "OK", 1: "ERR_NULL", 2: "ERR_INVALID_DESC", 3: "ERR_UNSUPPORTED", 4: "ERR_OUT_OF_BOUNDS",
-                5: "ERR_ASSIGN_CONFLICT", 6: "ERR_HIP", 7: "ERR_NOMEM"}
+                5: "ERR_ASSIGN_CONFLICT", 6: "ERR_HIP", 7: "ERR_NOMEM", 8: "ERR_MISALIGNED"}
 PATHS = {"auto": 0, "generic": 1, "mfma_gemm": 2, "mfma_conv": 3, "pool": 4}
 PATH_NAMES = {v: k for k, v in PATHS.items()}
 
@@ -29,6 +29,7 @@ _AGG = {"assign": 0, "add": 1, "max": 2, "min": 3, "mul": 4}
 _INTR = {"mul": 0, "copy": 1, "add": 2, "add_relu": 3}
 
 EXPORTS = ("stripe_block_create", "stripe_block_create_for_path", "stripe_block_run", "stripe_block_run_static", "stripe_block_query",
+           "stripe_block_workspace_size", "stripe_block_set_workspace",
            "stripe_block_destroy", "stripe_status_string", "stripe_last_error", "stripe_device_copy",
            "stripe_tile_cost", "stripe_tile_search", "stripe_block_tile", "stripe_desc_free")
 
@@ -59,7 +60,7 @@ class stripe_block_info_t(C.Structure):
                 ("tile_m", C.c_int32), ("tile_n", C.c_int32), ("tile_k", C.c_int32),
                 ("frag_m", C.c_int32), ("frag_n", C.c_int32), ("frag_k", C.c_int32),
                 ("lds_bytes", C.c_int32), ("workgroup_size", C.c_int32), ("grid", C.c_int64),
-                ("kernel", C.c_char * 64)]
+                ("kernel", C.c_char * 96), ("workspace_bytes", C.c_int64)]
 
 
 class stripe_tile_model_t(C.Structure):
@@ -102,6 +103,10 @@ def _load():
     lib.stripe_block_run_static.argtypes = [handle, C.POINTER(C.c_void_p), C.c_void_p, C.c_void_p]
     lib.stripe_block_query.restype = C.c_int
     lib.stripe_block_query.argtypes = [handle, C.POINTER(stripe_block_info_t)]
+    lib.stripe_block_workspace_size.restype = C.c_int
+    lib.stripe_block_workspace_size.argtypes = [handle, C.POINTER(C.c_size_t)]
+    lib.stripe_block_set_workspace.restype = C.c_int
+    lib.stripe_block_set_workspace.argtypes = [handle, C.c_void_p, C.c_size_t]
     lib.stripe_block_destroy.restype = None
     lib.stripe_block_destroy.argtypes = [handle]
     lib.stripe_status_string.restype = C.c_char_p
@@ -208,6 +213,16 @@ def stripe_block_run(handle, input_ptrs: Sequence[int], output_ptr: int, stream:
 def stripe_block_run_static(handle, input_ptrs: Sequence[int], output_ptr: int, stream: int = 0) -> None:
     arr = (C.c_void_p * len(input_ptrs))(*[C.c_void_p(int(p)) for p in input_ptrs])
     _check(lib.stripe_block_run_static(handle, arr, C.c_void_p(int(output_ptr)), C.c_void_p(int(stream))))
+
+
+def stripe_block_workspace_size(handle) -> int:
+    n = C.c_size_t(0)
+    _check(lib.stripe_block_workspace_size(handle, C.byref(n)))
+    return int(n.value)
+
+
+def stripe_block_set_workspace(handle, device_ptr: int, n_bytes: int) -> None:
+    _check(lib.stripe_block_set_workspace(handle, C.c_void_p(int(device_ptr)), C.c_size_t(int(n_bytes))))
 
 
 def stripe_block_query(handle) -> dict:
@@ -350,6 +365,14 @@ class StripeBlock:
         st = lib.stripe_block_run_static(self.handle, arr, out, stream)
         if st != STRIPE_OK:
             raise StripeError(st, stripe_last_error())
+
+    def set_workspace(self, tensor) -> None:
+        """Hand the handle a caller-owned device workspace (a torch CUDA tensor, kept alive here), or None."""
+        self._ws = tensor
+        if tensor is None:
+            stripe_block_set_workspace(self.handle, 0, 0)
+        else:
+            stripe_block_set_workspace(self.handle, tensor.data_ptr(), tensor.numel() * tensor.element_size())
 
     def close(self) -> None:
         if self.handle is not None:

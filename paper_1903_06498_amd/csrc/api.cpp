@@ -34,16 +34,23 @@ struct stripe_block {
   std::vector<Stage> stages;
   std::vector<int> input_slot;       // root refinement -> index into run()'s inputs, -1 otherwise
   std::vector<int64_t> temp_bytes;   // root refinement -> bytes of the temporary, 0 otherwise
-  std::vector<void*> temp_ptr;
-  int temp_dev = -1;
+  // Device workspace of the handle's launches: temporaries of a statement list (temp_off), then each stage's own
+  // workspace (stage_ws_off); for a single block the partial sums of a split reduction.  Every part starts on a
+  // 256-byte boundary.  The memory is the caller's (set_workspace), else the handle's (allocated on the first
+  // run on a device), else the library's static scratch array (run_static).
+  std::vector<int64_t> temp_off, stage_ws_off;
+  int64_t ws_bytes = 0;
+  void* caller_ws = nullptr;
+  size_t caller_ws_bytes = 0;
+  void* owned_ws = nullptr;
+  int owned_ws_dev = -1;
   // 1, 2: the two statements run as one convolution kernel with a bias+relu epilogue (fp32 / bf16 output);
   // 3, 4: the same with the dense-contraction kernel
   int fused = 0;
   int64_t fuse_bias_off = 0, fuse_o_m = 0, fuse_o_base = 0;
   ~stripe_block() {
     for (Stage& st : stages) delete st.blk;
-    for (void* t : temp_ptr)
-      if (t) (void)hipFree(t);
+    if (owned_ws) (void)hipFree(owned_ws);
   }
 };
 
@@ -69,6 +76,8 @@ stripe_status_t api_fail(stripe_status_t st, const std::string& msg) { return fa
 
 namespace {
 
+int64_t round_up_256(int64_t v) { return (v + 255) / 256 * 256; }
+
 stripe_status_t create_single(const stripe_block_desc_t* desc, stripe_path_t path, stripe_block_t** out);
 
 // A root block with a statement list (Section 3.2: statements execute as if in serial): every statement is planned
@@ -83,7 +92,6 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
   if (!prog) return fail(STRIPE_ERR_NOMEM, "out of host memory");
   prog->input_slot.assign(R, -1);
   prog->temp_bytes.assign(R, 0);
-  prog->temp_ptr.assign(R, nullptr);
   std::vector<char> written(R, 0);
   int n_inputs = 0, phase = 0;
   for (int r = 0; r < R; ++r) {
@@ -232,14 +240,23 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
     }
   if (prog->fused) names = std::string(prog->stages[0].blk->plan.info.kernel) + (prog->fused == 2 ? "+bias_relu_bf16" : "+bias_relu");
   std::snprintf(info.kernel, sizeof info.kernel, "%s", names.c_str());
+  // workspace layout: temporaries that were not scalarised away, then what each stage's own launches need
+  prog->temp_off.assign(R, 0);
+  prog->ws_bytes = 0;
+  for (int r = 0; r < R; ++r)
+    if (prog->temp_bytes[r]) {
+      prog->temp_off[r] = prog->ws_bytes;
+      prog->ws_bytes += round_up_256(prog->temp_bytes[r]);
+    }
+  prog->stage_ws_off.assign(prog->stages.size(), 0);
+  if (!prog->fused)
+    for (size_t i = 0; i < prog->stages.size(); ++i) {
+      prog->stage_ws_off[i] = prog->ws_bytes;
+      prog->ws_bytes += round_up_256(prog->stages[i].blk->ws_bytes);
+    }
+  info.workspace_bytes = prog->ws_bytes;
   *out = prog;
   return STRIPE_OK;
-}
-
-bool need_scratch(const stripe_block* prog) {
-  for (int64_t b : prog->temp_bytes)
-    if (b) return true;
-  return false;
 }
 
 constexpr int kMaxDevices = 64;
@@ -265,47 +282,49 @@ stripe_status_t static_scratch_of(int dev, unsigned char** out) {
   return STRIPE_OK;
 }
 
-int64_t round_up_256(int64_t v) { return (v + 255) / 256 * 256; }
-
-// use_static: temporaries are carved out of the GPU's static scratch array instead of memory the handle allocates.
-stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void* output, void* hip_stream, bool use_static) {
+// Where the handle's workspace lives for this run.  use_static: the GPU's static scratch array (no allocation
+// ever); otherwise the caller's workspace if one was set, else memory the handle allocates on its first run on a
+// device.  A handle that needs no workspace gets NULL.
+stripe_status_t resolve_workspace(stripe_block* blk, bool use_static, unsigned char** ws) {
+  *ws = nullptr;
+  if (blk->ws_bytes == 0) return STRIPE_OK;
+  if (use_static && blk->ws_bytes > (int64_t)STRIPE_STATIC_SCRATCH_BYTES)
+    return fail(STRIPE_ERR_NOMEM, "the block's workspace needs " + std::to_string((long long)blk->ws_bytes) + " bytes, the static scratch holds " +
+                                      std::to_string((long long)STRIPE_STATIC_SCRATCH_BYTES));
+  if (!use_static && blk->caller_ws) {
+    *ws = (unsigned char*)blk->caller_ws;
+    return STRIPE_OK;
+  }
   int dev = -1;
-  hipError_t e = hipSuccess;
-  void* static_temp[16] = {};   // a statement list declares at most 16 root buffers
-  if (use_static) {
-    int64_t need = 0;
-    for (int64_t b : prog->temp_bytes) need += round_up_256(b);
-    if (need > (int64_t)STRIPE_STATIC_SCRATCH_BYTES)
-      return fail(STRIPE_ERR_NOMEM, "the block's temporaries need " + std::to_string(need) + " bytes, the static scratch holds " +
-                                        std::to_string((long long)STRIPE_STATIC_SCRATCH_BYTES));
-  }
-  e = hipGetDevice(&dev);
+  const hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return fail(STRIPE_ERR_HIP, hipGetErrorString(e));
-  if (use_static) {
-    unsigned char* base = nullptr;
-    if (need_scratch(prog)) {
-      const stripe_status_t rc = static_scratch_of(dev, &base);
-      if (rc != STRIPE_OK) return rc;
+  if (use_static) return static_scratch_of(dev, ws);
+  if (dev != blk->owned_ws_dev) {   // first run (on this device)
+    if (blk->owned_ws) (void)hipFree(blk->owned_ws);
+    blk->owned_ws = nullptr;
+    blk->owned_ws_dev = -1;
+    if (hipMalloc(&blk->owned_ws, (size_t)blk->ws_bytes) != hipSuccess) {
+      blk->owned_ws = nullptr;
+      return fail(STRIPE_ERR_NOMEM, "out of device memory for the handle's workspace");
     }
-    int64_t off = 0;
-    for (size_t r = 0; r < prog->temp_bytes.size(); ++r)
-      if (prog->temp_bytes[r]) {
-        static_temp[r] = base + off;
-        off += round_up_256(prog->temp_bytes[r]);
-      }
-  } else if (dev != prog->temp_dev) {   // first run (on this device): the temporaries
-    for (size_t r = 0; r < prog->temp_ptr.size(); ++r) {
-      if (prog->temp_ptr[r]) (void)hipFree(prog->temp_ptr[r]);
-      prog->temp_ptr[r] = nullptr;
-      if (prog->temp_bytes[r] && hipMalloc(&prog->temp_ptr[r], (size_t)prog->temp_bytes[r]) != hipSuccess)
-        return fail(STRIPE_ERR_NOMEM, "out of device memory for a temporary");
-    }
-    prog->temp_dev = dev;
+    blk->owned_ws_dev = dev;
   }
+  *ws = (unsigned char*)blk->owned_ws;
+  return STRIPE_OK;
+}
+
+stripe_status_t run_single(stripe_block* blk, const void* const* inputs, void* output, void* hip_stream, unsigned char* ws);
+
+stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void* output, void* hip_stream, unsigned char* ws) {
+  hipError_t e = hipSuccess;
   const int R = (int)prog->input_slot.size();
   if (prog->fused) {
     const Stage &s0 = prog->stages[0], &s1 = prog->stages[1];
     const float* bias = (const float*)inputs[prog->input_slot[s1.src[1]]] + prog->fuse_bias_off;
+    const bool conv = prog->fused < 3, out_bf16 = prog->fused == 2 || prog->fused == 4;
+    if (((uintptr_t)inputs[prog->input_slot[s0.src[0]]] % 16) || ((uintptr_t)inputs[prog->input_slot[s0.src[1]]] % 16) ||
+        ((uintptr_t)bias % (conv ? 16 : 4)) || ((uintptr_t)output % (conv ? 16 : out_bf16 ? 2 : 4)))
+      return fail(STRIPE_ERR_MISALIGNED, "the fused matrix-core kernel needs 16-byte aligned operands (convolution: also bias and output)");
     if (prog->fused >= 3)
       e = launch_gemm_bias_relu(prog->plan.gemm, prog->gemm, inputs[prog->input_slot[s0.src[0]]], inputs[prog->input_slot[s0.src[1]]], bias,
                                 output, prog->fuse_o_m, prog->fuse_o_base, prog->fused == 4, (hipStream_t)hip_stream);
@@ -318,14 +337,47 @@ stripe_status_t run_program(stripe_block* prog, const void* const* inputs, void*
   auto where = [&](int r) -> const void* {
     if (r == R - 1) return output;
     if (prog->input_slot[r] >= 0) return inputs[prog->input_slot[r]];
-    return use_static ? static_temp[r] : prog->temp_ptr[r];
+    return ws + prog->temp_off[r];
   };
-  for (const Stage& st : prog->stages) {
+  for (size_t i = 0; i < prog->stages.size(); ++i) {
+    const Stage& st = prog->stages[i];
     const void* ins[2] = {where(st.src[0]), st.n_in > 1 ? where(st.src[1]) : nullptr};
-    const stripe_status_t rc = stripe_block_run(st.blk, ins, const_cast<void*>(where(st.dst)), hip_stream);
+    const stripe_status_t rc = run_single(st.blk, ins, const_cast<void*>(where(st.dst)), hip_stream, ws ? ws + prog->stage_ws_off[i] : nullptr);
     if (rc != STRIPE_OK) return rc;
   }
   return STRIPE_OK;
+}
+
+stripe_status_t run_single(stripe_block* blk, const void* const* inputs, void* output, void* hip_stream, unsigned char* ws) {
+  const Plan& p = blk->plan;
+  if (p.noop) return STRIPE_OK;
+  hipStream_t s = (hipStream_t)hip_stream;
+  const void* in0 = inputs[0];
+  const void* in1 = blk->n_inputs > 1 ? inputs[1] : nullptr;
+  hipError_t e = hipSuccess;
+  if (p.info.path != STRIPE_PATH_GENERIC &&
+      (((uintptr_t)in0 % 16) || (in1 && ((uintptr_t)in1 % 16)) || ((uintptr_t)output % (p.info.path == STRIPE_PATH_MFMA_GEMM ? 4 : 16))))
+    return fail(STRIPE_ERR_MISALIGNED, "this handle was planned for a kernel family that moves 16 bytes per lane: input pointers (and, except for "
+                                       "dense contractions, the output pointer) must be 16-byte aligned");
+  switch (p.info.path) {
+    case STRIPE_PATH_MFMA_GEMM: e = launch_gemm(p.gemm, blk->gemm, in0, in1, output, ws, s); break;
+    case STRIPE_PATH_MFMA_CONV: e = launch_conv(p.conv, blk->conv, in0, in1, output, s); break;
+    case STRIPE_PATH_POOL: e = launch_pool(p.pool, blk->pool, in0, output, s); break;
+    default: e = launch_generic(p, in0, in1, output, s); break;
+  }
+  if (e != hipSuccess) return fail(STRIPE_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+  return STRIPE_OK;
+}
+
+stripe_status_t run_any(stripe_block* blk, const void* const* inputs, void* output, void* hip_stream, bool use_static) {
+  if (!blk || !inputs || !output) return fail(STRIPE_ERR_NULL, "blk, inputs or output is NULL");
+  for (int i = 0; i < blk->n_inputs; ++i)
+    if (!inputs[i]) return fail(STRIPE_ERR_NULL, "an input pointer is NULL");
+  unsigned char* ws = nullptr;
+  const stripe_status_t rc = resolve_workspace(blk, use_static, &ws);
+  if (rc != STRIPE_OK) return rc;
+  if (!blk->stages.empty()) return run_program(blk, inputs, output, hip_stream, ws);
+  return run_single(blk, inputs, output, hip_stream, ws);
 }
 
 stripe_status_t create_single(const stripe_block_desc_t* desc, stripe_path_t path, stripe_block_t** out) {
@@ -369,7 +421,9 @@ stripe_status_t create_single(const stripe_block_desc_t* desc, stripe_path_t pat
       }
       generic_info(p, &p.info);
     }
+    if (p.info.path == STRIPE_PATH_MFMA_GEMM && picked) blk->ws_bytes = blk->gemm.ws_bytes;
   }
+  p.info.workspace_bytes = blk->ws_bytes;
   *out = blk;
   return STRIPE_OK;
 }
@@ -393,31 +447,31 @@ stripe_status_t stripe_block_create(const stripe_block_desc_t* desc, stripe_bloc
 }
 
 stripe_status_t stripe_block_run_static(stripe_block_t* blk, const void* const* inputs, void* output, void* hip_stream) {
-  if (!blk || !inputs || !output) return fail(STRIPE_ERR_NULL, "blk, inputs or output is NULL");
-  for (int i = 0; i < blk->n_inputs; ++i)
-    if (!inputs[i]) return fail(STRIPE_ERR_NULL, "an input pointer is NULL");
-  if (!blk->stages.empty()) return run_program(blk, inputs, output, hip_stream, /*use_static=*/true);
-  return stripe_block_run(blk, inputs, output, hip_stream);   // a single block has no temporaries: nothing is ever allocated
+  return run_any(blk, inputs, output, hip_stream, /*use_static=*/true);
 }
 
 stripe_status_t stripe_block_run(stripe_block_t* blk, const void* const* inputs, void* output, void* hip_stream) {
-  if (!blk || !inputs || !output) return fail(STRIPE_ERR_NULL, "blk, inputs or output is NULL");
-  for (int i = 0; i < blk->n_inputs; ++i)
-    if (!inputs[i]) return fail(STRIPE_ERR_NULL, "an input pointer is NULL");
-  if (!blk->stages.empty()) return run_program(blk, inputs, output, hip_stream, /*use_static=*/false);
-  const Plan& p = blk->plan;
-  if (p.noop) return STRIPE_OK;
-  hipStream_t s = (hipStream_t)hip_stream;
-  const void* in0 = inputs[0];
-  const void* in1 = blk->n_inputs > 1 ? inputs[1] : nullptr;
-  hipError_t e = hipSuccess;
-  switch (p.info.path) {
-    case STRIPE_PATH_MFMA_GEMM: e = launch_gemm(p.gemm, blk->gemm, in0, in1, output, s); break;
-    case STRIPE_PATH_MFMA_CONV: e = launch_conv(p.conv, blk->conv, in0, in1, output, s); break;
-    case STRIPE_PATH_POOL: e = launch_pool(p.pool, blk->pool, in0, output, s); break;
-    default: e = launch_generic(p, in0, in1, output, s); break;
+  return run_any(blk, inputs, output, hip_stream, /*use_static=*/false);
+}
+
+stripe_status_t stripe_block_workspace_size(const stripe_block_t* blk, size_t* bytes) {
+  if (!blk || !bytes) return fail(STRIPE_ERR_NULL, "blk or bytes is NULL");
+  *bytes = (size_t)blk->ws_bytes;
+  return STRIPE_OK;
+}
+
+stripe_status_t stripe_block_set_workspace(stripe_block_t* blk, void* device_ptr, size_t bytes) {
+  if (!blk) return fail(STRIPE_ERR_NULL, "blk is NULL");
+  if (!device_ptr) {
+    blk->caller_ws = nullptr;
+    blk->caller_ws_bytes = 0;
+    return STRIPE_OK;
   }
-  if (e != hipSuccess) return fail(STRIPE_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+  if ((uintptr_t)device_ptr % 256) return fail(STRIPE_ERR_INVALID_DESC, "the workspace must be 256-byte aligned");
+  if ((int64_t)bytes < blk->ws_bytes)
+    return fail(STRIPE_ERR_NOMEM, "the workspace holds " + std::to_string(bytes) + " bytes, the handle needs " + std::to_string((long long)blk->ws_bytes));
+  blk->caller_ws = device_ptr;
+  blk->caller_ws_bytes = bytes;
   return STRIPE_OK;
 }
 
@@ -439,6 +493,7 @@ const char* stripe_status_string(stripe_status_t status) {
     case STRIPE_ERR_ASSIGN_CONFLICT: return "assign aggregation with several writers";
     case STRIPE_ERR_HIP: return "HIP runtime error";
     case STRIPE_ERR_NOMEM: return "out of memory";
+    case STRIPE_ERR_MISALIGNED: return "buffer pointer not aligned for the planned kernel family";
   }
   return "unknown status";
 }

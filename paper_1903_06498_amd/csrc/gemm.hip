@@ -900,6 +900,35 @@ __global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const
     }
 }
 
+// ---------------------------------------------------------------------------
+// Split reduction (Section 2.1, last paragraph; Definition 2 rule 3: an aggregation may be regrouped because the
+// operation is associative and commutative).  A product with few output tiles and a long reduction index is run
+// as S products over K / S each -- the batch mechanism of the kernels above, every slice writing its own M x N
+// image of partial sums into a workspace -- and this kernel adds the S images in slice order, so the result does
+// not depend on scheduling: integer sums are exact, float sums are reproducible from run to run.
+// ---------------------------------------------------------------------------
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const T* __restrict__ part, T* __restrict__ C, int64_t M, int64_t N, int64_t c_m,
+                                                            int64_t c_base, int S) {
+  typedef T vec_t __attribute__((ext_vector_type(VEC)));
+  const int64_t per_row = N / VEC, total = M * per_row, image = M * N;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int64_t m = e / per_row, n = (e - m * per_row) * VEC;
+    const T* src = part + m * N + n;
+    vec_t acc = *(const vec_t*)src;
+    int sl = 1;
+    for (; sl + 8 <= S; sl += 8) {   // eight loads in flight, added in slice order
+      vec_t v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load((const vec_t*)(src + (int64_t)(sl + u) * image));
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+    for (; sl < S; ++sl) acc += __builtin_nontemporal_load((const vec_t*)(src + (int64_t)sl * image));
+    *(vec_t*)(C + c_base + m * c_m + n) = acc;
+  }
+}
+
 GemmParams make_params(const GemmShape& g, bool i8 = false) {
   GemmParams p;
   p.tiles_m = (int)((g.M + BM - 1) / BM);
@@ -930,8 +959,52 @@ GemmParams make_params(const GemmShape& g, bool i8 = false) {
 
 static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info);
 
+// How many slices of the reduction index a single product is cut into (1 = not split).  Only the LDS-direct
+// kernels walk a batch; a slice must be whole passes through their four-stage ring.  The choice minimises a small
+// time model calibrated on this chip: workgroups run in rounds of one per CU, a round costs the slice's K tiles
+// times the measured time per tile, and splitting adds a second launch plus writing and re-reading S images of
+// partial sums.  A split has to beat the unsplit launch by a fifth to be taken.
+// STRIPE_TUNE gemm_splitk: 0 or 1 = never, n > 1 = n slices if legal.
+static int choose_split_k(const GemmShape& g, int in_dtype, const GemmLaunch& l) {
+  if (g.batch > 1 || l.variant < 20) return 1;
+  const bool i8 = in_dtype == STRIPE_I8;
+  const int64_t ring = i8 ? 256 : D_BK * D_STAGES;
+  const int forced = tune_int("gemm_splitk", -1);
+  if (forced == 0 || forced == 1) return 1;
+  auto legal = [&](int64_t s) {
+    return s >= 2 && g.K % (s * ring) == 0 && s * l.grid <= 0x7fffffffLL && s * g.M * g.N * 4 <= ((int64_t)1 << 31);
+  };
+  if (forced > 1) return legal(forced) ? forced : 1;
+  if (g.K < 16 * ring) return 1;   // short reductions: a second launch costs more than the idle CUs
+  const double us_per_tile = l.variant >= 50 ? 0.30 : 0.85;   // one K tile (32 deep; int8: 64) of a 128- / 256-wide workgroup tile
+  const double k_tile = i8 ? 64.0 : (double)D_BK;
+  auto model_us = [&](int64_t s) {
+    const double rounds = (double)((l.grid * s + 255) / 256);
+    double t = 3.0 + rounds * ((double)g.K / (double)s / k_tile) * us_per_tile;
+    if (s > 1) t += 2.5 + (double)s * (double)g.M * (double)g.N * 8.0 / 2.0e6;   // second launch; partial sums out and back at an effective 2 TB/s
+    return t;
+  };
+  int64_t best = 1;
+  double best_t = model_us(1) * 0.8;
+  for (int64_t s = 2; s <= g.K / ring && s <= 1024; ++s)
+    if (legal(s) && model_us(s) < best_t) {
+      best = s;
+      best_t = model_us(s);
+    }
+  return (int)best;
+}
+
 bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info) {
   if (!gemm_select_one(g, in_dtype, l, info)) return false;
+  l->split_k = choose_split_k(g, in_dtype, *l);
+  l->ws_bytes = 0;
+  if (l->split_k > 1) {
+    l->ws_bytes = (int64_t)l->split_k * g.M * g.N * 4;
+    l->grid *= l->split_k;
+    info->grid = l->grid;
+    const size_t n = strlen(info->kernel);
+    snprintf(info->kernel + n, sizeof info->kernel - n, "_splitk%d", l->split_k);
+  }
   if (g.batch > 1) {
     // a batch of products: only the LDS-direct kernel walks the batch index; batch strides keep the 16-byte alignment
     const int64_t align = in_dtype == STRIPE_I8 ? 16 : 8;
@@ -1048,8 +1121,8 @@ static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const
                                   int64_t o_m, int64_t o_base, hipStream_t st);
 
 bool gemm_can_fuse_bias_relu(const GemmShape& g, const GemmLaunch& l) {
-  // the LDS-direct kernels in their float modes, one product (no batch)
-  return g.batch <= 1 && ((l.variant >= 20 && l.variant < 40) || l.variant == 50 || l.variant == 51);
+  // the LDS-direct kernels in their float modes, one product (no batch, reduction not split)
+  return g.batch <= 1 && l.split_k <= 1 && ((l.variant >= 20 && l.variant < 40) || l.variant == 50 || l.variant == 51);
 }
 
 hipError_t launch_gemm_bias_relu(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, const void* bias, void* out,
@@ -1058,8 +1131,31 @@ hipError_t launch_gemm_bias_relu(const GemmShape& g, const GemmLaunch& l, const 
   return launch_gemm_epi(g, l, a, b, out, (const float*)bias, out_bf16 ? 2 : 1, o_m, o_base, st);
 }
 
-hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t st) {
-  return launch_gemm_epi(g, l, a, b, c, nullptr, 0, g.c_m, g.c_base, st);
+hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, void* workspace, hipStream_t st) {
+  if (l.split_k <= 1) return launch_gemm_epi(g, l, a, b, c, nullptr, 0, g.c_m, g.c_base, st);
+  // S slices of the reduction index as a batch of S products into the workspace, then their sum into C
+  if (!workspace || ((uintptr_t)workspace % 16) || ((uintptr_t)c % 4)) return hipErrorInvalidValue;
+  const bool bt = g.b_k == 1 && g.b_n != 1;
+  GemmShape slice = g;
+  slice.K = g.K / l.split_k;
+  slice.batch = l.split_k;
+  slice.a_b = slice.K;                                  // A is k-contiguous
+  slice.b_b = bt ? slice.K : slice.K * g.b_k;
+  slice.c_b = g.M * g.N;
+  const hipError_t e = launch_gemm_epi(slice, l, a, b, workspace, nullptr, 0, g.N, 0, st);
+  if (e != hipSuccess) return e;
+  const bool i8 = (l.variant >= 40 && l.variant < 50) || l.variant == 52;
+  const bool vec4 = g.N % 4 == 0 && g.c_m % 4 == 0 && g.c_base % 4 == 0 && ((uintptr_t)c % 16) == 0;
+  const int64_t items = g.M * (vec4 ? g.N / 4 : g.N);
+  const unsigned blocks = (unsigned)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
+  if (i8) {
+    if (vec4) hipLaunchKernelGGL((splitk_reduce_kernel<int, 4>), dim3(blocks), dim3(256), 0, st, (const int*)workspace, (int*)c, g.M, g.N, g.c_m, g.c_base, l.split_k);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<int, 1>), dim3(blocks), dim3(256), 0, st, (const int*)workspace, (int*)c, g.M, g.N, g.c_m, g.c_base, l.split_k);
+  } else {
+    if (vec4) hipLaunchKernelGGL((splitk_reduce_kernel<float, 4>), dim3(blocks), dim3(256), 0, st, (const float*)workspace, (float*)c, g.M, g.N, g.c_m, g.c_base, l.split_k);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<float, 1>), dim3(blocks), dim3(256), 0, st, (const float*)workspace, (float*)c, g.M, g.N, g.c_m, g.c_base, l.split_k);
+  }
+  return hipGetLastError();
 }
 
 static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, const float* bias, int epi,

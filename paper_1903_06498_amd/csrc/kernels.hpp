@@ -33,10 +33,13 @@ struct GemmLaunch {
   int variant = -1;
   int t128_waves = 4;   // wavefronts of the 128 x 128-tile kernel: 4 or 8
   int64_t grid = 0;
+  int split_k = 1;       // slices of the reduction index, each run as one product of a batch into the workspace
+  int64_t ws_bytes = 0;  // workspace launch_gemm needs: split_k images of M x N partial sums
   mutable int lds_enabled_on = -1;  // device on which the kernel's large LDS size has been enabled
 };
 bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_info_t* info);
-hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, hipStream_t stream);
+// workspace: device memory of l.ws_bytes (16-byte aligned), may be NULL when that is 0
+hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, const void* b, void* c, void* workspace, hipStream_t stream);
 // The product fused with a following statement O[m,n] = relu(C[m,n] + bias[n]) (C = the product's output, which then
 // never reaches memory): O fp32 or bf16 with row stride o_m and element offset o_base.
 bool gemm_can_fuse_bias_relu(const GemmShape& g, const GemmLaunch& l);

@@ -388,7 +388,7 @@ def linear_bias_relu_program(M, N, K, out_dtype="bf16", b_transposed=True) -> Bl
 # Further shapes the kernel families cover, for measurements beyond the five configurations (bench.py --workload).
 EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32",
                "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "gemm_bf16_1024", "gemm_bf16_2048",
-               "linear_bias_relu_4096")
+               "linear_bias_relu_4096", "gemm_bf16_256x256x65536", "gemm_i8_256x256x65536_bt", "gemm_bf16_1024x1024x8192")
 
 
 def extra_block(name: str) -> Block:
@@ -397,6 +397,12 @@ def extra_block(name: str) -> Block:
     if name in ("gemm_bf16_1024", "gemm_bf16_2048"):      # fewer 256 x 256 tiles than CUs: the 128 x 128-tile kernel
         n = int(name.rsplit("_", 1)[1])
         return matmul_block(n, n, n, "bf16", "f32")
+    if name == "gemm_bf16_256x256x65536":      # few output tiles, long reduction index: the reduction is split over workgroups
+        return matmul_block(256, 256, 65536, "bf16", "f32")
+    if name == "gemm_i8_256x256x65536_bt":
+        return matmul_block(256, 256, 65536, "i8", "i32", b_transposed=True)
+    if name == "gemm_bf16_1024x1024x8192":
+        return matmul_block(1024, 1024, 8192, "bf16", "f32")
     if name == "gemm_bf16_4000_ragged":
         return matmul_block(4000, 4000, 4096, "bf16", "f32")
     if name == "gemm_i8_4096_bt":

@@ -250,7 +250,8 @@ def test_product_aggregation_float():
 
 def test_misaligned_buffers_are_refused_not_launched():
     """The matrix-core and pooling kernels load 16 bytes at a time: a buffer that is not 16-byte aligned must come
-    back as an error from run (nothing is launched), while the generic path takes any element-aligned pointer."""
+    back as the misalignment status from run (nothing is launched), while the generic path takes any element-aligned
+    pointer."""
     dev = torch.device("cuda:0")
     blk = W.matmul_block(256, 256, 128, "bf16", "f32")
     sb = B.StripeBlock(blk)
@@ -259,7 +260,7 @@ def test_misaligned_buffers_are_refused_not_launched():
     out = torch.zeros(256 * 256, dtype=torch.float32, device=dev)
     with pytest.raises(B.StripeError) as e:
         sb.run([a.data_ptr() + 2, b], out)
-    assert e.value.status == 6
+    assert e.value.status == 8
     sb.run([a, b], out)                                   # the handle is still usable
     torch.cuda.synchronize()
     gen = B.StripeBlock(blk, "generic")
@@ -657,6 +658,66 @@ def test_gemm_small_tile_kernel(M, N, K, bt, waves, monkeypatch):
     assert np.array_equal(gpu.reshape(M, N), a.float()[:, sel].numpy())
     ins = [W.seeded_tensor((M, K), "bf16", 0), W.seeded_tensor((N, K) if bt else (K, N), "bf16", 1)]
     parity(blk, ins, what=f"small-tile gemm {M}x{N}x{K} bt={bt}")
+
+
+@pytest.mark.parametrize("M,N,K,dt,bt,tune", [(256, 256, 16384, "bf16", False, ""), (256, 256, 8192, "bf16", True, ""),
+                                              (128, 256, 16384, "i8", True, ""), (200, 136, 8192, "bf16", False, ""),
+                                              (300, 264, 4096, "i8", True, ""), (256, 384, 1536, "bf16", False, "gemm_splitk=3"),
+                                              (512, 512, 2048, "bf16", True, "gemm_splitk=2,gemm_t128=0"),
+                                              (256, 256, 1024, "i8", True, "gemm_splitk=4")])
+def test_split_reduction(M, N, K, dt, bt, tune, monkeypatch):
+    """A product with few output tiles and a long reduction index: the reduction is cut into slices that run as
+    separate workgroups, partial sums go through the handle's workspace and are added in slice order.  int8
+    bit-exact, bf16 within tolerance; a shifted-identity operand that takes each output column from a different
+    k (hence from different slices) must pass the first operand through exactly.  The caller-provided workspace and
+    the static-scratch entry point give the same bits as the handle-owned workspace."""
+    if tune:
+        monkeypatch.setenv("STRIPE_TUNE", tune)
+    odt = "i32" if dt == "i8" else "f32"
+    blk = W.matmul_block(M, N, K, dt, odt, b_transposed=bt)
+    tdt = torch.int8 if dt == "i8" else torch.bfloat16
+    a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(tdt)
+    sel = (torch.arange(N) * 613 + 37) % K
+    b = torch.zeros((K, N), dtype=tdt)
+    b[sel, torch.arange(N)] = 1
+    gpu, sb = run_gpu(blk, [a, b.t().contiguous() if bt else b], return_block=True)
+    assert "_splitk" in sb.info["kernel"] and sb.info["path_name"] == "mfma_gemm", sb.info["kernel"]
+    S = int(sb.info["kernel"].rsplit("_splitk", 1)[1])
+    assert sb.info["workspace_bytes"] == S * M * N * 4 == B.stripe_block_workspace_size(sb.handle)
+    say(f"split reduction {M}x{N}x{K} {dt}: {sb.info['kernel']} grid {sb.info['grid']}")
+    assert np.array_equal(gpu.reshape(M, N), a.float()[:, sel].numpy())
+    ins = [W.seeded_tensor((M, K), dt, 0), W.seeded_tensor((N, K) if bt else (K, N), dt, 1)]
+    parity(blk, ins, threads=16, what=f"split reduction {M}x{N}x{K} {dt}")
+    # the three homes of the workspace give identical bits
+    dev = torch.device("cuda:0")
+    dins = [t.to(dev) for t in ins]
+    outs = []
+    for mode in ("owned", "caller", "static"):
+        out = torch.zeros(M * N, dtype=torch.int32 if dt == "i8" else torch.float32, device=dev)
+        if mode == "caller":
+            sb.set_workspace(torch.empty(sb.info["workspace_bytes"] + 256, dtype=torch.uint8, device=dev))
+        if mode == "static":
+            if sb.info["workspace_bytes"] > 8 << 20:
+                continue
+            sb.run_static(dins, out)
+        else:
+            sb.run(dins, out)
+        torch.cuda.synchronize()
+        outs.append(out.cpu())
+    assert all(torch.equal(outs[0], o) for o in outs[1:])
+    sb.close()
+
+
+def test_split_reduction_off_matches(monkeypatch):
+    """gemm_splitk=0 runs the same block unsplit; both match the oracle (checked above) and each other closely."""
+    blk = W.matmul_block(256, 256, 8192, "i8", "i32", b_transposed=True)
+    ins = [W.seeded_tensor((256, 8192), "i8", 0), W.seeded_tensor((256, 8192), "i8", 1)]
+    split, sb = run_gpu(blk, ins, return_block=True)
+    assert "_splitk" in sb.info["kernel"]
+    monkeypatch.setenv("STRIPE_TUNE", "gemm_splitk=0")
+    whole, sb2 = run_gpu(blk, ins, return_block=True)
+    assert "_splitk" not in sb2.info["kernel"] and sb2.info["workspace_bytes"] == 0
+    assert np.array_equal(split, whole)
 
 
 def test_pointwise_convolution_runs_on_the_gemm_kernel():

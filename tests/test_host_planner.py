@@ -156,3 +156,40 @@ def test_tune_override_selects_variants(monkeypatch):
     assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty4_nt"
     monkeypatch.delenv("STRIPE_TUNE")
     assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty2"
+
+
+def test_split_reduction_is_planned_for_few_tiles_and_long_k(monkeypatch):
+    """Section 2.1: an aggregation may be regrouped.  Few output tiles + long reduction index => slices over
+    workgroups, with a workspace of one partial-sum image per slice; large products and short reductions stay whole."""
+    sb = B.StripeBlock(W.matmul_block(256, 256, 65536, "bf16", "f32"))
+    assert "_splitk" in sb.info["kernel"]
+    S = int(sb.info["kernel"].rsplit("_splitk", 1)[1])
+    assert S >= 2 and 65536 % (S * 128) == 0
+    assert sb.info["workspace_bytes"] == S * 256 * 256 * 4 == B.stripe_block_workspace_size(sb.handle)
+    assert sb.info["grid"] == 4 * S                       # four 128 x 128 tiles, S slices each
+    with pytest.raises(B.StripeError) as e:
+        B.stripe_block_set_workspace(sb.handle, 256, 1024)            # too small
+    assert e.value.status == 7
+    with pytest.raises(B.StripeError) as e:
+        B.stripe_block_set_workspace(sb.handle, 257, 1 << 30)         # misaligned
+    assert e.value.status == 2
+    B.stripe_block_set_workspace(sb.handle, 0, 0)                     # back to handle-owned memory
+    sb.close()
+    for shape in [(4096, 4096, 4096), (512, 512, 512), (2048, 2048, 2048)]:
+        sb = B.StripeBlock(W.matmul_block(*shape, "bf16", "f32"))
+        assert "_splitk" not in sb.info["kernel"] and sb.info["workspace_bytes"] == 0, sb.info["kernel"]
+        sb.close()
+    monkeypatch.setenv("STRIPE_TUNE", "gemm_splitk=0")
+    sb = B.StripeBlock(W.matmul_block(256, 256, 65536, "bf16", "f32"))
+    assert "_splitk" not in sb.info["kernel"] and sb.info["workspace_bytes"] == 0
+    sb.close()
+
+
+def test_statement_list_reports_its_workspace():
+    prog = W.conv_bias_relu_program(2, 9, 7, 5, 6, 3, 3, 1, 1, "f32", "f32")
+    sb = B.StripeBlock(prog)
+    assert sb.info["workspace_bytes"] == (2 * 9 * 7 * 6 * 4 + 255) // 256 * 256
+    sb.close()
+    fused = B.StripeBlock(W.conv_bias_relu_program(1, 7, 20, 64, 64, 3, 3, 1, 1, "bf16", "f32"))
+    assert "+bias_relu" in fused.info["kernel"] and fused.info["workspace_bytes"] == 0     # the temporary was scalarised away
+    fused.close()
