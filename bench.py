@@ -56,6 +56,13 @@ KIND = {
     "gemm_i8_256x256x65536_bt": ("TOP/s", "mfma", "int8"),
     "gemm_bf16_1024x1024x8192": ("TFLOP/s", "mfma", "bf16"),
     "linear_bias_relu_4096": ("TFLOP/s", "mfma", "bf16"),
+    # convolution shapes beyond the two tuned ones: the general matrix-core convolution kernel (--path generic: the fallback it replaces)
+    "conv3x3_bf16_128to128": ("TFLOP/s", "mfma", "bf16"),
+    "conv3x3_s2_bf16_64to128": ("TFLOP/s", "mfma", "bf16"),
+    "conv1x7_bf16_64to64": ("TFLOP/s", "hbm", "bf16"),
+    "conv3x3_bf16_w112": ("TFLOP/s", "hbm", "bf16"),
+    "conv5x5_bf16_32to32": ("TFLOP/s", "hbm", "bf16"),
+    "conv3x3_i8_64to64": ("TOP/s", "hbm", "int8"),
     "pointwise_conv_bf16": ("TFLOP/s", "hbm", "bf16"),
     "transposed_conv_f32": ("TFLOP/s", "alu", "f32"),
     "resnet_conv_bias_relu_bf16": ("TFLOP/s", "hbm", "bf16"),   # two statements fused into one kernel, bf16 output

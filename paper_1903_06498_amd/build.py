@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstripe_hip.so")
-SOURCES = ["api.cpp", "plan.cpp", "tiling.cpp", "generic.hip", "generic_tiled.hip", "pool.hip", "gemm.hip", "conv.hip", "conv_i8.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "tiling.cpp", "generic.hip", "generic_tiled.hip", "pool.hip", "gemm.hip", "conv.hip", "conv_i8.hip", "conv_igemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -410,6 +410,11 @@ stripe_status_t create_single(const stripe_block_desc_t* desc, stripe_path_t pat
       case STRIPE_PATH_POOL: picked = pool_select(p.pool, p.in_dtype, &blk->pool, &p.info); break;
       default: break;
     }
+    // a block both matchers accept (a 1x1 convolution) whose shape the contraction kernels do not cover
+    if (!picked && !forced && p.info.path == STRIPE_PATH_MFMA_GEMM && p.is_conv) {
+      picked = conv_select(p.conv, p.in_dtype, &blk->conv, &p.info);
+      if (!picked) p.info.path = STRIPE_PATH_MFMA_GEMM;
+    }
     if (!picked) {
       if (forced && p.info.path != STRIPE_PATH_GENERIC) {
         delete blk;

@@ -462,10 +462,21 @@ ConvParams make_params(const Conv2dShape& c, int rows) {
 
 }  // namespace
 
+static bool conv3x3_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
+
+// The tuned kernels for their shapes (3x3 over 64 channels, 7x7 stride 2 over 3 channels), the general kernel otherwise.
 bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info) {
   if (tune_int("conv_mfma", 1) == 0) return false;
-  if (in_dtype == STRIPE_I8) return conv_i8_select(c, in_dtype, l, info);
+  l->in_dtype = in_dtype;
+  const bool tuned = tune_int("conv_tuned", 1) != 0;   // 0: measure the general kernel on the tuned kernels' shapes
+  if (tuned && in_dtype == STRIPE_I8 && conv_i8_select(c, in_dtype, l, info)) return true;
+  if (tuned && in_dtype == STRIPE_BF16 && conv3x3_select(c, in_dtype, l, info)) return true;
+  return conv_igemm_select(c, in_dtype, false, l, info);
+}
+
+static bool conv3x3_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info) {
   if (in_dtype != STRIPE_BF16) return false;
+  if (c.dil_y != 1 || c.dil_x != 1) return false;
   if (c.R != 3 || c.S != 3 || c.stride_y != 1 || c.stride_x != 1 || c.pad_y != 1 || c.pad_x != 1) return false;
   if (c.Ci != C_CI || c.Co != C_CO || c.Ho != c.H || c.Wo != c.W) return false;
   if (c.W > 64 || c.W < 1) return false;
@@ -540,6 +551,7 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
 
 static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias,
                                   int epi, hipStream_t st) {
+  if (l.variant >= kConvIgemmVariant) return launch_conv_igemm(c, l, l.in_dtype, false, in, flt, out, st);
   if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
   if (l.variant > kConvW4Variant) {

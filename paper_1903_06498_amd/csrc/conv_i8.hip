@@ -242,6 +242,7 @@ constexpr int kStripChoices[] = {2, 4, 7, 8};
 }  // namespace
 
 bool conv_i8_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info) {
+  if (c.dil_y != 1 || c.dil_x != 1) return false;
   if (in_dtype != STRIPE_I8) return false;
   if (c.R != Q_R || c.S != Q_S || c.stride_y != 2 || c.stride_x != 2 || c.pad_y != 3 || c.pad_x != 3) return false;
   if (c.Ci != Q_CI || c.Co != Q_CO) return false;

@@ -1,0 +1,308 @@
+// Nested-tile convolution on the gfx950 matrix cores for the whole family of dense convolution-shaped blocks
+//   O[n,y,x,k] = sum_{i,j,c} I[n, sy*y + dy*i - py, sx*x + dx*j - px, c] * F[i,j,k,c]
+// (any filter extent R x S up to 32 x 32, any stride, dilation and padding, any image width, channels contiguous in
+// all three tensors; bf16 with Ci a multiple of 32, or int8 with Ci a multiple of 64; any Co).
+//
+// The nesting of paper Section 3.1.3 (Figure 3's three columns), mapped by hand:
+//   outer block  -> one workgroup per tile of TM output pixels x TN output channels; the pixels of a tile are
+//                   consecutive in the flattened (n, y, x) order, so a tile may span rows and images;
+//   middle block -> the reduction (i, j, c) walked as K tiles of one filter tap x 64 bytes of channels, staged in a
+//                   four-stage LDS ring by LDS-direct loads: the A side gathers each pixel's channels for that tap
+//                   straight from the image (the view of Figure 5b, built by address arithmetic instead of a copy),
+//                   the B side takes the tap's [k][c] slice of the filter;
+//   inner block  -> v_mfma_f32_32x32x16_bf16 / v_mfma_i32_32x32x32_i8 fragments, 64 pixels x 32 channels per wavefront.
+// Constraints (padding) are realised per pixel and tap: a lane whose tap falls outside the image fetches 16 zero
+// bytes instead (adding zero is the identity of the sum), so interior and boundary tiles run the same code and no
+// per-point test reaches the matrix instructions (Section 2.3: keep the hot loop rectilinear).
+// The two tuned kernels (3x3 / 64 channels in conv.hip, 7x7 / 3 channels in conv_i8.hip) stay the fast cases; this
+// kernel re-reads each input element once per tap from L2, which they avoid.
+#include <hip/hip_runtime.h>
+
+#include "kernels.hpp"
+
+namespace stripe {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 g_bf16x8;
+typedef __attribute__((ext_vector_type(16))) float g_f32x16;
+typedef __attribute__((ext_vector_type(4))) int g_i32x4;
+typedef __attribute__((ext_vector_type(16))) int g_i32x16;
+
+struct IgemmParams {
+  int64_t i_n, i_y, i_x;          // element strides; the channel stride is 1 in all three tensors
+  int64_t f_r, f_s, f_k;
+  int64_t o_n, o_y, o_x;
+  int64_t i_base, f_base, o_base;
+  int32_t Ho, Wo, H, W, Co;
+  int32_t R, S, stride_y, stride_x, pad_y, pad_x, dil_y, dil_x;
+  int32_t m_total;                // output pixels N * Ho * Wo
+  int32_t tiles_n;                // workgroup tiles along the output channels
+  int32_t chunks;                 // 64-byte channel chunks per tap
+  int32_t k_tiles;                // R * S * chunks
+  int32_t out_bf16;               // float blocks: round the result to bf16 on store
+};
+
+// Lanes whose tap lies outside the image fetch these 16 zero bytes instead.
+__device__ __attribute__((aligned(16))) unsigned char igemm_zero_chunk[16];
+
+// LDS-direct 16-byte load: lane i of the wavefront lands at lds_off + 16 * i.  Written as assembly because the
+// compiler cannot know that a load into one ring stage does not alias the fragment reads of another; the load
+// queue depth is managed by hand with s_waitcnt below.  M0 (the wave-uniform LDS destination) is written here and
+// nowhere else in this kernel.
+__device__ __forceinline__ void g_load_lds16(const void* src, unsigned lds_off) {
+  const unsigned uniform_off = __builtin_amdgcn_readfirstlane(lds_off);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform_off) : "memory", "m0");
+}
+
+template <bool I8>
+__device__ __forceinline__ g_f32x16 g_mma(g_bf16x8 a, g_bf16x8 b, g_f32x16 acc) {
+  if constexpr (I8) {
+    return __builtin_bit_cast(g_f32x16, __builtin_amdgcn_mfma_i32_32x32x32_i8(__builtin_bit_cast(g_i32x4, a), __builtin_bit_cast(g_i32x4, b),
+                                                                            __builtin_bit_cast(g_i32x16, acc), 0, 0, 0));
+  } else {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc, 0, 0, 0);
+  }
+}
+
+#define G_FENCE() __builtin_amdgcn_sched_barrier(0)
+
+template <int N>
+__device__ __forceinline__ void g_wait_loads() {
+  static_assert(N == 0 || N == 2 || N == 3 || N == 4 || N == 6, "load queue depths used below");
+  if (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+  else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  else if (N == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+  else if (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+}
+
+// TN = 128: tiles of 128 pixels x 128 channels, wavefronts 2 (pixels) x 4 (channels);
+// TN = 64 : tiles of 256 pixels x  64 channels, wavefronts 4 x 2.
+// LDS: A stages at 0 (TM rows of 64 bytes, 16-byte chunk c of row r in slot c ^ ((r >> 2) & 3)), B stages behind
+// them (TN rows, same layout); an LDS-direct load fills one 1 KB block = 16 rows.
+template <int TN, bool I8>
+__global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p, const unsigned char* __restrict__ I,
+                                                            const unsigned char* __restrict__ F, void* __restrict__ O) {
+  constexpr int TM = TN == 128 ? 128 : 256;
+  constexpr int WN = TN / 32;                 // wavefronts side by side along the channels
+  constexpr int LA = TM / 128;                // 1 KB A blocks per wavefront and K tile
+  constexpr int LPT = LA + 1;                 // loads per wavefront and K tile (one B block each)
+  constexpr int A_STAGE = TM * 64, B_STAGE = TN * 64, B0 = 4 * A_STAGE;
+  constexpr int ES = I8 ? 1 : 2;              // bytes per input element
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  const int t = threadIdx.x, lane = t & 63, wv = t >> 6, wn = wv % WN, wm = wv / WN;
+  // consecutive hardware workgroup ids go round the 8 XCDs: give each XCD a contiguous run of tiles, channel tiles
+  // of one pixel tile next to each other, so the L2 that fetched a pixel tile serves all its channel tiles
+  const unsigned grid = gridDim.x, b = blockIdx.x;
+  const unsigned logical = (grid % 8u) ? b : (b % 8u) * (grid / 8u) + b / 8u;
+  const int tn = (int)(logical % (unsigned)p.tiles_n), tm = (int)(logical / (unsigned)p.tiles_n);
+
+  // ---- A side: the lane's pixel(s), its first byte in the image for tap (0,0), and which taps are inside the image
+  const unsigned char* a_base[LA];
+  unsigned rmask[LA], cmask[LA];
+#pragma unroll
+  for (int u = 0; u < LA; ++u) {
+    const int row = 16 * (wv + 8 * u) + (lane >> 2);
+    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    int m = tm * TM + row;
+    if (m >= p.m_total) m = p.m_total - 1;    // rows past the end repeat the last pixel; they are never stored
+    const int x = m % p.Wo, q = m / p.Wo, y = q % p.Ho, n = q / p.Ho;
+    const int iy0 = y * p.stride_y - p.pad_y, ix0 = x * p.stride_x - p.pad_x;
+    a_base[u] = I + (p.i_base + (int64_t)n * p.i_n + (int64_t)iy0 * p.i_y + (int64_t)ix0 * p.i_x) * ES + chunk * 16;
+    unsigned rm = 0, cm = 0;
+    for (int i = 0; i < p.R; ++i) {
+      const int yy = iy0 + i * p.dil_y;
+      if (yy >= 0 && yy < p.H) rm |= 1u << i;
+    }
+    for (int j = 0; j < p.S; ++j) {
+      const int xx = ix0 + j * p.dil_x;
+      if (xx >= 0 && xx < p.W) cm |= 1u << j;
+    }
+    rmask[u] = rm;
+    cmask[u] = cm;
+  }
+  // ---- B side: the lane's filter row (an output channel; rows past Co repeat the last one, never stored)
+  const int bb = wv % (TN / 16);              // with TN = 64 wavefronts 4..7 repeat the loads of 0..3 (same bytes, same place)
+  const unsigned char* b_base;
+  {
+    const int row = 16 * bb + (lane >> 2);
+    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    int gn = tn * TN + row;
+    if (gn >= p.Co) gn = p.Co - 1;
+    b_base = F + (p.f_base + (int64_t)gn * p.f_k) * ES + chunk * 16;
+  }
+  // the K tile the next issue() fetches: filter tap (ti, tj), channel chunk tc; all wave-uniform
+  int ti = 0, tj = 0, tc = 0;
+  auto issue = [&](int stage) {
+    const int64_t a_off = ((int64_t)(ti * p.dil_y) * p.i_y + (int64_t)(tj * p.dil_x) * p.i_x) * ES + tc * 64;
+    const int64_t b_off = ((int64_t)ti * p.f_r + (int64_t)tj * p.f_s) * ES + tc * 64;
+#pragma unroll
+    for (int u = 0; u < LA; ++u) {
+      const bool inside = ((rmask[u] >> ti) & (cmask[u] >> tj) & 1u) != 0;
+      const void* src = inside ? (const void*)(a_base[u] + a_off) : (const void*)igemm_zero_chunk;
+      g_load_lds16(src, stage * A_STAGE + (wv + 8 * u) * 1024);
+    }
+    g_load_lds16(b_base + b_off, B0 + stage * B_STAGE + bb * 1024);
+    if (++tc == p.chunks) {
+      tc = 0;
+      if (++tj == p.S) {
+        tj = 0;
+        ++ti;
+      }
+    }
+  };
+
+  // ---- fragments: lane supplies row (lane & 31) and 16-byte chunk 2 * s + (lane >> 5) of K step s
+  const int fr = lane & 31, fh = lane >> 5;
+  const unsigned a_fr = (unsigned)((wm * 64 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
+  const unsigned b_fr = (unsigned)(B0 + (wn * 32 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
+  auto read_frags = [&](int stage, int s, g_bf16x8 (&af)[2], g_bf16x8& bf) {
+#pragma unroll
+    for (int q = 0; q < 2; ++q) af[q] = *(const g_bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * A_STAGE + q * 32 * 64);
+    bf = *(const g_bf16x8*)(lds + (b_fr ^ (unsigned)(s << 5)) + stage * B_STAGE);
+  };
+
+  g_f32x16 acc[2];
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+
+  const int k_tiles = p.k_tiles;   // >= 1
+  issue(0);
+  if (k_tiles > 1) issue(1);
+  if (k_tiles > 2) issue(2);
+  if (k_tiles > 2) g_wait_loads<2 * LPT>();
+  else if (k_tiles > 1) g_wait_loads<LPT>();
+  else g_wait_loads<0>();
+  __syncthreads();
+  g_bf16x8 af[2][2], bf[2];
+  read_frags(0, 0, af[0], bf[0]);
+  for (int kt = 0; kt < k_tiles; ++kt) {
+    const int stage = kt & 3;
+    G_FENCE();
+    read_frags(stage, 1, af[1], bf[1]);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) acc[q] = g_mma<I8>(af[0][q], bf[0], acc[q]);
+    G_FENCE();
+    // tile kt+1 must have landed (its loads were issued two tiles ago); after the barrier every wavefront is done
+    // with tile kt-1, whose ring slot then takes tile kt+3
+    if (kt + 2 >= k_tiles) g_wait_loads<0>();
+    else g_wait_loads<LPT>();
+    __syncthreads();
+    if (kt + 3 < k_tiles) issue((kt + 3) & 3);
+    G_FENCE();
+    if (kt + 1 < k_tiles) read_frags((kt + 1) & 3, 0, af[0], bf[0]);
+#pragma unroll
+    for (int q = 0; q < 2; ++q) acc[q] = g_mma<I8>(af[1][q], bf[1], acc[q]);
+    G_FENCE();
+  }
+
+  // ---- store.  The ring is no longer needed: its first bytes take the output offset of each of the tile's pixels
+  // (-1 for rows past the last pixel and for pixels no iteration writes), computed once per pixel instead of once per accumulator element.
+  __syncthreads();
+  int64_t* out_off = (int64_t*)lds;
+  if (t < TM) {
+    const int m = tm * TM + t;
+    int64_t off = -1;
+    if (m < p.m_total) {
+      const int x = m % p.Wo, q = m / p.Wo, y = q % p.Ho, n = q / p.Ho;
+      // a pixel none of whose taps lies inside the image is written by no iteration: it keeps its contents
+      const int iy0 = y * p.stride_y - p.pad_y, ix0 = x * p.stride_x - p.pad_x;
+      bool any_row = false, any_col = false;
+      for (int i = 0; i < p.R; ++i) any_row |= (iy0 + i * p.dil_y >= 0 && iy0 + i * p.dil_y < p.H);
+      for (int j = 0; j < p.S; ++j) any_col |= (ix0 + j * p.dil_x >= 0 && ix0 + j * p.dil_x < p.W);
+      if (any_row && any_col) off = p.o_base + (int64_t)n * p.o_n + (int64_t)y * p.o_y + (int64_t)x * p.o_x;
+    }
+    out_off[t] = off;
+  }
+  __syncthreads();
+  const int k = tn * TN + wn * 32 + fr;       // the lane's output channel
+  if (k >= p.Co) return;
+#pragma unroll
+  for (int q = 0; q < 2; ++q)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int row = wm * 64 + 32 * q + 8 * (v / 4) + (v % 4) + 4 * fh;
+      const int64_t off = out_off[row];
+      if (off < 0) continue;
+      if (!I8 && p.out_bf16) {
+        const uint32_t u = __float_as_uint(acc[q][v]);
+        ((uint16_t*)O)[off + k] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);   // round to nearest even
+      } else {
+        __builtin_nontemporal_store(acc[q][v], (float*)O + off + k);   // int32 results travel as bit patterns
+      }
+    }
+}
+
+}  // namespace
+
+bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLaunch* l, stripe_block_info_t* info) {
+  if (tune_int("conv_igemm", 1) == 0) return false;
+  const bool i8 = in_dtype == STRIPE_I8;
+  if (!i8 && in_dtype != STRIPE_BF16) return false;
+  const int64_t ck = i8 ? 64 : 32;            // channels per 64-byte K tile row
+  const int64_t al = i8 ? 16 : 8;             // elements per 16 bytes
+  if (c.i_c != 1 || c.f_c != 1 || c.o_k != 1) return false;
+  if (c.Ci < ck || c.Ci % ck || c.Co < 1 || c.R < 1 || c.S < 1 || c.R > 32 || c.S > 32) return false;
+  if (c.stride_y < 1 || c.stride_x < 1 || c.dil_y < 1 || c.dil_x < 1 || c.pad_y < 0 || c.pad_x < 0) return false;
+  for (int64_t v : {c.i_n, c.i_y, c.i_x, c.i_base, c.f_r, c.f_s, c.f_k, c.f_base})
+    if (v % al) return false;                 // 16-byte loads
+  for (int64_t v : {c.N, c.Ho, c.Wo, c.H, c.W, c.Co, c.stride_y, c.stride_x, c.pad_y, c.pad_x, c.dil_y, c.dil_x})
+    if (v > 0x3fffffff) return false;
+  const int64_t m_total = c.N * c.Ho * c.Wo;
+  if (m_total < 1 || m_total > 0x7fffffffLL - 512) return false;
+  if (c.R * c.S * (c.Ci / ck) > 0x7fffffffLL) return false;
+  // narrow outputs take the 256-pixel x 64-channel tile, wide ones 128 x 128
+  const int tn = c.Co <= 64 ? 64 : 128, tm = tn == 128 ? 128 : 256;
+  const int64_t tiles_m = (m_total + tm - 1) / tm, tiles_n = (c.Co + tn - 1) / tn;
+  if (tiles_m * tiles_n > 0x7fffffffLL) return false;
+  l->variant = tn == 128 ? kConvIgemmVariant : kConvIgemmVariant + 1;
+  l->grid = tiles_m * tiles_n;
+  info->path = STRIPE_PATH_MFMA_CONV;
+  info->tile_m = tm; info->tile_n = tn; info->tile_k = (int)ck;
+  info->frag_m = 32; info->frag_n = 32; info->frag_k = i8 ? 32 : 16;
+  info->lds_bytes = 4 * (tm + tn) * 64;
+  info->workgroup_size = 512;
+  info->grid = l->grid;
+  snprintf(info->kernel, sizeof info->kernel, "conv_igemm_%s_%dx%dx%d_mfma32x32x%d_w8_lds_direct%s", i8 ? "i8" : "bf16", tm, tn, (int)ck,
+           i8 ? 32 : 16, (!i8 && out_bf16) ? "_obf16" : "");
+  return true;
+}
+
+hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_dtype, bool out_bf16, const void* in, const void* flt, void* out,
+                             hipStream_t st) {
+  const bool i8 = in_dtype == STRIPE_I8;
+  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
+  IgemmParams p;
+  p.i_n = c.i_n; p.i_y = c.i_y; p.i_x = c.i_x;
+  p.f_r = c.f_r; p.f_s = c.f_s; p.f_k = c.f_k;
+  p.o_n = c.o_n; p.o_y = c.o_y; p.o_x = c.o_x;
+  p.i_base = c.i_base; p.f_base = c.f_base; p.o_base = c.o_base;
+  p.Ho = (int)c.Ho; p.Wo = (int)c.Wo; p.H = (int)c.H; p.W = (int)c.W; p.Co = (int)c.Co;
+  p.R = (int)c.R; p.S = (int)c.S;
+  p.stride_y = (int)c.stride_y; p.stride_x = (int)c.stride_x; p.pad_y = (int)c.pad_y; p.pad_x = (int)c.pad_x;
+  p.dil_y = (int)c.dil_y; p.dil_x = (int)c.dil_x;
+  p.m_total = (int)(c.N * c.Ho * c.Wo);
+  const int tn = l.variant == kConvIgemmVariant ? 128 : 64, tm = tn == 128 ? 128 : 256;
+  p.tiles_n = (int)((c.Co + tn - 1) / tn);
+  p.chunks = (int)(c.Ci / (i8 ? 64 : 32));
+  p.k_tiles = (int)(c.R * c.S) * p.chunks;
+  p.out_bf16 = out_bf16 ? 1 : 0;
+  typedef void (*kern_t)(const IgemmParams, const unsigned char*, const unsigned char*, void*);
+  const kern_t fn = tn == 128 ? (i8 ? (kern_t)conv_igemm_kernel<128, true> : (kern_t)conv_igemm_kernel<128, false>)
+                              : (i8 ? (kern_t)conv_igemm_kernel<64, true> : (kern_t)conv_igemm_kernel<64, false>);
+  const int lds_bytes = 4 * (tm + tn) * 64;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev != l.lds_enabled_on) {   // more than 64 KB of dynamic LDS has to be enabled once per device
+    e = hipFuncSetAttribute((const void*)fn, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+    if (e != hipSuccess) return e;
+    l.lds_enabled_on = dev;
+  }
+  hipLaunchKernelGGL(fn, dim3((unsigned)l.grid), dim3(512), lds_bytes, st, p, (const unsigned char*)in, (const unsigned char*)flt, out);
+  return hipGetLastError();
+}
+
+}  // namespace stripe

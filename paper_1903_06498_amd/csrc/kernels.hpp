@@ -47,9 +47,11 @@ hipError_t launch_gemm_bias_relu(const GemmShape& g, const GemmLaunch& l, const 
                                  int64_t o_m, int64_t o_base, bool out_bf16, hipStream_t stream);
 
 // ---- nested-tile convolution-shaped contraction on matrix cores -----------
+constexpr int kConvIgemmVariant = 300;   // 300: 128 x 128 tiles, 301: 256 x 64 tiles of the general convolution kernel
 struct ConvLaunch {
   int variant = -1;
   int64_t grid = 0;
+  int in_dtype = 0;       // element type of the operands (general kernel: bf16 or int8)
   mutable int lds_enabled_on = -1;
 };
 bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
@@ -59,6 +61,11 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
 bool conv_can_fuse_bias_relu(const Conv2dShape& c, const ConvLaunch& l);
 hipError_t launch_conv_bias_relu(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, const void* bias, void* out,
                                  bool out_bf16, hipStream_t stream);
+// general convolution kernel (implicit contraction: any filter extent, stride, dilation, padding, image width;
+// bf16 with Ci % 32 == 0 or int8 with Ci % 64 == 0; channels contiguous); conv_select falls back to it
+bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLaunch* l, stripe_block_info_t* info);
+hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_dtype, bool out_bf16, const void* in, const void* flt, void* out,
+                             hipStream_t stream);
 // strided 7x7 int8 variant (dispatched to by conv_select / launch_conv)
 bool conv_i8_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
 hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);

@@ -494,9 +494,9 @@ int single_term(const Affine& a, int n, int64_t* coef) {  // index of the only n
   return j;
 }
 
-struct Window2d {  // roles of the indexes of  X[n, sy*y + i - py, sx*x + j - px, c]
+struct Window2d {  // roles of the indexes of  X[n, sy*y + dy*i - py, sx*x + dx*j - px, c]
   int n = -1, y = -1, x = -1, c = -1, i = -1, j = -1;
-  int64_t sy = 1, sx = 1, py = 0, px = 0;
+  int64_t sy = 1, sx = 1, py = 0, px = 0, dy = 1, dx = 1;
   int64_t H = 1, W = 1, st_n = 0, st_y = 0, st_x = 0, st_c = 0;
 };
 
@@ -523,23 +523,24 @@ bool match_window(const FlatBlock& fb, const FlatRef& in, const Affine& out_addr
     const int d = pass ? dx : dy;
     const Affine& a = in.coord[d];
     int o = -1, r = -1;
-    int64_t s = 1;
+    int64_t s = 1, dil = 1;
     for (int t = 0; t < fb.n_idx; ++t) {
       if (!a.c[t]) continue;
       if (out_addr.c[t]) {  // an output index: the window's position
         if (o >= 0 || a.c[t] < 1) return false;
         o = t;
         s = a.c[t];
-      } else {              // a reduction index: the tap
-        if (r >= 0 || a.c[t] != 1) return false;
+      } else {              // a reduction index: the tap (coefficient = dilation)
+        if (r >= 0 || a.c[t] < 1) return false;
         r = t;
+        dil = a.c[t];
       }
     }
     if (a.k > 0) return false;
     if (pass) {
-      w->x = o; w->j = r; w->sx = s; w->px = -a.k; w->W = in.sizes[d]; w->st_x = in.strides[d];
+      w->x = o; w->j = r; w->sx = s; w->dx = dil; w->px = -a.k; w->W = in.sizes[d]; w->st_x = in.strides[d];
     } else {
-      w->y = o; w->i = r; w->sy = s; w->py = -a.k; w->H = in.sizes[d]; w->st_y = in.strides[d];
+      w->y = o; w->i = r; w->sy = s; w->dy = dil; w->py = -a.k; w->H = in.sizes[d]; w->st_y = in.strides[d];
     }
   }
   // Constraints may only be the window's own bounds: coord >= 0 or size-1-coord >= 0.
@@ -668,6 +669,7 @@ bool match_conv2d(const FlatBlock& fb, Conv2dShape* c) {
   c->R = range_or_1(fb, w.i); c->S = range_or_1(fb, w.j); c->Ci = fb.range[w.c];
   c->H = w.H; c->W = w.W;
   c->stride_y = w.sy; c->stride_x = w.sx; c->pad_y = w.py; c->pad_x = w.px;
+  c->dil_y = w.dy; c->dil_x = w.dx;
   c->i_n = w.st_n; c->i_y = w.st_y; c->i_x = w.st_x; c->i_c = w.st_c;
   c->f_r = f_r; c->f_s = f_s; c->f_k = f_k; c->f_c = f_c;
   c->o_n = w.n >= 0 ? O.addr.c[w.n] : 0; c->o_y = O.addr.c[w.y]; c->o_x = O.addr.c[w.x]; c->o_k = O.addr.c[k];
@@ -694,6 +696,7 @@ bool match_pool2d(const FlatBlock& fb, Pool2dShape* p) {
   p->N = range_or_1(fb, w.n); p->Ho = fb.range[w.y]; p->Wo = fb.range[w.x]; p->C = fb.range[w.c];
   p->R = range_or_1(fb, w.i); p->S = range_or_1(fb, w.j); p->H = w.H; p->W = w.W;
   p->stride_y = w.sy; p->stride_x = w.sx; p->pad_y = w.py; p->pad_x = w.px;
+  p->dil_y = w.dy; p->dil_x = w.dx;
   p->i_n = w.st_n; p->i_y = w.st_y; p->i_x = w.st_x; p->i_c = w.st_c;
   p->o_n = w.n >= 0 ? O.addr.c[w.n] : 0; p->o_y = O.addr.c[w.y]; p->o_x = O.addr.c[w.x]; p->o_c = O.addr.c[w.c];
   p->i_base = I.addr.k + w.py * w.st_y + w.px * w.st_x;
@@ -772,6 +775,9 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
   const bool is_gemm = plain_out && match_gemm(fb, &plan->gemm);
   const bool is_conv = plain_out && match_conv2d(fb, &plan->conv);
   const bool is_pool = plain_out && match_pool2d(fb, &plan->pool);
+  plan->is_gemm = is_gemm;
+  plan->is_conv = is_conv;
+  plan->is_pool = is_pool;
   stripe_path_t path = forced;
   if (path == STRIPE_PATH_AUTO) {
     path = is_gemm ? STRIPE_PATH_MFMA_GEMM : is_conv ? STRIPE_PATH_MFMA_CONV : is_pool ? STRIPE_PATH_POOL : STRIPE_PATH_GENERIC;

@@ -62,18 +62,20 @@ struct GemmShape {       // C[b,m,n] (+)= A[b,m,k] * B[b,k,n]   (batch = 1: no b
   int64_t batch, a_b, b_b, c_b;           // batch count and element strides of the batch index (every operand moves with it)
 };
 
-struct Conv2dShape {     // O[n,y,x,k] (+)= I[n, s*y+i-p, s*x+j-q, c] * F[i,j,k,c]  (any strides)
+struct Conv2dShape {     // O[n,y,x,k] (+)= I[n, s*y+d*i-p, s*x+d*j-q, c] * F[i,j,k,c]  (any strides)
   int64_t N, Ho, Wo, Co, R, S, Ci, H, W;
   int64_t stride_y, stride_x, pad_y, pad_x;
+  int64_t dil_y, dil_x;                   // dilation: coefficient of the tap indexes i, j in the input access
   int64_t i_n, i_y, i_x, i_c;             // input element strides
   int64_t f_r, f_s, f_k, f_c;             // filter element strides
   int64_t o_n, o_y, o_x, o_k;             // output element strides
   int64_t i_base, f_base, o_base;
 };
 
-struct Pool2dShape {     // O[n,y,x,c] = agg over in-bounds taps of I[n, s*y+i-p, s*x+j-q, c]
+struct Pool2dShape {     // O[n,y,x,c] = agg over in-bounds taps of I[n, s*y+d*i-p, s*x+d*j-q, c]
   int64_t N, Ho, Wo, C, R, S, H, W;
   int64_t stride_y, stride_x, pad_y, pad_x;
+  int64_t dil_y, dil_x;
   int64_t i_n, i_y, i_x, i_c, o_n, o_y, o_x, o_c;
   int64_t i_base, o_base;
   int agg;                 // STRIPE_AGG_MAX, _MIN or _ADD (sum pooling)
@@ -129,6 +131,7 @@ struct Plan {
   Conv2dShape conv = {};
   Pool2dShape pool = {};
   int in_dtype = 0;
+  bool is_gemm = false, is_conv = false, is_pool = false;   // which shape matchers accept the block (gemm / conv / pool filled accordingly)
 };
 
 // Each returns STRIPE_OK or an error with `err` filled.

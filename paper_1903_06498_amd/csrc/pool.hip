@@ -338,6 +338,7 @@ struct PoolWindow { int r, s, stride; };
 constexpr PoolWindow kWindows[] = {{3, 3, 2}, {2, 2, 2}, {3, 3, 1}};
 
 bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_info_t* info) {
+  if (s.dil_y != 1 || s.dil_x != 1) return false;   // dilated windows run on the generic kernel
   if (dtype != STRIPE_F32) return false;
   int window = -1;
   for (int w = 0; w < (int)(sizeof kWindows / sizeof kWindows[0]); ++w)

@@ -388,7 +388,8 @@ def linear_bias_relu_program(M, N, K, out_dtype="bf16", b_transposed=True) -> Bl
 # Further shapes the kernel families cover, for measurements beyond the five configurations (bench.py --workload).
 EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32",
                "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "gemm_bf16_1024", "gemm_bf16_2048",
-               "linear_bias_relu_4096", "gemm_bf16_256x256x65536", "gemm_i8_256x256x65536_bt", "gemm_bf16_1024x1024x8192")
+               "linear_bias_relu_4096", "gemm_bf16_256x256x65536", "gemm_i8_256x256x65536_bt", "gemm_bf16_1024x1024x8192", "conv3x3_bf16_128to128", "conv3x3_s2_bf16_64to128", "conv1x7_bf16_64to64",
+               "conv3x3_bf16_w112", "conv5x5_bf16_32to32", "conv3x3_i8_64to64")
 
 
 def extra_block(name: str) -> Block:
@@ -397,6 +398,17 @@ def extra_block(name: str) -> Block:
     if name in ("gemm_bf16_1024", "gemm_bf16_2048"):      # fewer 256 x 256 tiles than CUs: the 128 x 128-tile kernel
         n = int(name.rsplit("_", 1)[1])
         return matmul_block(n, n, n, "bf16", "f32")
+    family = {   # convolution shapes beyond the two tuned ones (the general matrix-core convolution kernel)
+        "conv3x3_bf16_128to128": (32, 28, 28, 128, 128, 3, 3, 1, 1, "bf16"),
+        "conv3x3_s2_bf16_64to128": (32, 56, 56, 64, 128, 3, 3, 2, 1, "bf16"),
+        "conv1x7_bf16_64to64": (32, 56, 56, 64, 64, 1, 7, 1, 3, "bf16"),
+        "conv3x3_bf16_w112": (8, 112, 112, 64, 64, 3, 3, 1, 1, "bf16"),
+        "conv5x5_bf16_32to32": (32, 56, 56, 32, 32, 5, 5, 1, 2, "bf16"),
+        "conv3x3_i8_64to64": (32, 56, 56, 64, 64, 3, 3, 1, 1, "i8"),
+    }
+    if name in family:
+        N, H, Wd, Ci, Co, R, S, st, pad, dt = family[name]
+        return conv2d_block(N, H, Wd, Ci, Co, R, S, st, pad, dt, "i32" if dt == "i8" else "f32")
     if name == "gemm_bf16_256x256x65536":      # few output tiles, long reduction index: the reduction is split over workgroups
         return matmul_block(256, 256, 65536, "bf16", "f32")
     if name == "gemm_i8_256x256x65536_bt":

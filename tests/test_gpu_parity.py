@@ -823,6 +823,88 @@ def test_conv_mfma_int8_extreme_values():
     assert np.array_equal(gpu, np.broadcast_to(want[None, :, :, None], gpu.shape))
 
 
+# ------------------------------------------------------------------ the general matrix-core convolution kernel
+IGEMM_CASES = {
+    # name: (N, H, W, Ci, Co, R, S, stride, pad, dtype)
+    "3x3_128to128": (2, 28, 28, 128, 128, 3, 3, 1, 1, "bf16"),
+    "3x3_s2_64to128_56to28": (2, 56, 56, 64, 128, 3, 3, 2, 1, "bf16"),
+    "1x7_64to64": (1, 20, 33, 64, 64, 1, 7, 1, 3, "bf16"),
+    "3x3_w112": (1, 9, 112, 64, 64, 3, 3, 1, 1, "bf16"),
+    "5x5_32to32": (2, 17, 19, 32, 32, 5, 5, 1, 2, "bf16"),
+    "7x3_s2_nopad": (1, 23, 17, 32, 96, 7, 3, 2, 0, "bf16"),
+    "1x1_96to40": (3, 10, 10, 96, 40, 1, 1, 1, 0, "bf16"),
+    "3x3_32to200": (1, 12, 12, 32, 200, 3, 3, 1, 1, "bf16"),
+    "3x3_i8_64to64": (2, 14, 14, 64, 64, 3, 3, 1, 1, "i8"),
+    "5x5_s2_i8_128to72": (1, 19, 21, 128, 72, 5, 5, 2, 2, "i8"),
+    "3x3_tiny_image": (1, 2, 3, 32, 8, 3, 3, 1, 1, "bf16"),
+}
+
+
+@pytest.mark.parametrize("case", sorted(IGEMM_CASES))
+def test_conv_family_on_the_matrix_cores(case):
+    """Dense convolution-shaped blocks outside the two tuned shapes run on the general nested-tile kernel: other
+    channel counts, filter extents, strides, image widths, ragged channel tiles, tiles that span rows and images.
+    Position-sensitive first (a delta input reproduces the filter, exactly), then seeded data against the oracle."""
+    N, H, Wd, Ci, Co, R, S, st, pad, dt = IGEMM_CASES[case]
+    odt = "i32" if dt == "i8" else "f32"
+    blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, st, pad, dt, odt)
+    Ho, Wo = (H + 2 * pad - R) // st + 1, (Wd + 2 * pad - S) // st + 1
+    f = W.seeded_tensor((R, S, Co, Ci), dt, 1)
+    i = torch.zeros((N, H, Wd, Ci), dtype=f.dtype)
+    n0, y0, x0, c0 = N - 1, H // 2, Wd - 1, Ci - 3
+    i[n0, y0, x0, c0] = 1
+    gpu, sb = run_gpu(blk, [i, f], return_block=True)
+    assert sb.info["path_name"] == "mfma_conv" and "conv_igemm" in sb.info["kernel"], sb.info
+    say(f"conv family {case}: {sb.info['kernel']} grid {sb.info['grid']}")
+    want = np.full((N, Ho, Wo, Co), float(SENTINEL_I) if dt == "i8" else float(np.float32(SENTINEL_F)), np.float64)
+    for y in range(Ho):
+        for x in range(Wo):
+            if taps(y, st, pad, R, H) and taps(x, st, pad, S, Wd):        # else: no iteration writes this pixel
+                want[:, y, x, :] = 0.0
+            a, b = y0 - st * y + pad, x0 - st * x + pad
+            if 0 <= a < R and 0 <= b < S:
+                want[n0, y, x, :] = f[a, b, :, c0].double().numpy()
+    assert np.array_equal(gpu.reshape(want.shape).astype(np.float64), want)
+    ins = [W.seeded_tensor((N, H, Wd, Ci), dt, 0), f]
+    parity(blk, ins, what=f"conv family {case}")
+    if dt == "i8":
+        assert np.array_equal(run_gpu(blk, ins), run_gpu(blk, ins, "generic"))
+
+
+def test_conv_family_dilated_and_strided_views():
+    """A dilated 3x3 (taps two pixels apart), and a convolution whose tensors are windows of larger ones with more
+    channels than the block uses (pixel strides larger than the channel count)."""
+    N, H, Wd, Ci, Co = 2, 15, 13, 64, 48
+    bufs = [W.Buffer("I", "in", "bf16", (N, H, Wd, Ci)), W.Buffer("F", "in", "bf16", (3, 3, Co, Ci)),
+            W.Buffer("O", "out", "f32", (N, H, Wd, Co))]
+    ya, xa = "y + 2*i - 2", "x + 2*j - 2"
+    blk = W.flat_block(bufs, dict(n=N, y=H, x=Wd, i=3, j=3, c=Ci, k=Co),
+                       [(["n", ya, xa, "c"], "assign"), (["i", "j", "k", "c"], "assign"), (["n", "y", "x", "k"], "add")],
+                       constraints=[f"{ya} >= 0", f"{H + 1} - y - 2*i >= 0", f"{xa} >= 0", f"{Wd + 1} - x - 2*j >= 0"])
+    ins = [W.seeded_tensor((N, H, Wd, Ci), "bf16", 0), W.seeded_tensor((3, 3, Co, Ci), "bf16", 1)]
+    info, _ = parity(blk, ins, what="dilated conv")
+    assert "conv_igemm" in info["kernel"], info
+    ref = torch.nn.functional.conv2d(ins[0].float().permute(0, 3, 1, 2), ins[1].float().permute(2, 3, 0, 1), padding=2, dilation=2)
+    gpu = run_gpu(blk, ins).reshape(N, H, Wd, Co)
+    assert np.allclose(gpu, ref.permute(0, 2, 3, 1).numpy(), rtol=1e-3, atol=1e-2)
+    blk = W.embed(W.conv2d_block(2, 10, 13, 32, 96, 3, 3, 1, 1, "bf16", "f32"), [(1, 2, 3, 64), (1, 0, 8, 32), (0, 1, 2, 4)],
+                  [(3, 14, 20, 128), (4, 3, 112, 64), (2, 12, 18, 100)])
+    ins = [W.seeded_tensor((3, 14, 20, 128), "bf16", 0), W.seeded_tensor((4, 3, 112, 64), "bf16", 1)]
+    info, _ = parity(blk, ins, what="conv family windows")
+    assert "conv_igemm" in info["kernel"], info
+
+
+def test_conv_family_on_the_tuned_shapes(monkeypatch):
+    """conv_tuned=0 sends the two benchmark shapes (small) through the general kernel too: same results as the tuned kernels."""
+    blk = W.conv2d_block(2, 10, 13, 64, 64, 3, 3, 1, 1, "bf16", "f32")
+    ins = [W.seeded_tensor((2, 10, 13, 64), "bf16", 0), W.seeded_tensor((3, 3, 64, 64), "bf16", 1)]
+    tuned = run_gpu(blk, ins)
+    monkeypatch.setenv("STRIPE_TUNE", "conv_tuned=0")
+    info, _ = parity(blk, ins, what="3x3 c64 on the general kernel")
+    assert "conv_igemm" in info["kernel"], info
+    assert np.allclose(run_gpu(blk, ins), tuned, rtol=1e-4, atol=1e-3)
+
+
 # ------------------------------------------------------------------ convolution configs at full size
 def test_resnet_conv_config_full_size():
     name = "resnet_conv_bf16"
