@@ -362,7 +362,7 @@ stripe_status_t run_single(stripe_block* blk, const void* const* inputs, void* o
   switch (p.info.path) {
     case STRIPE_PATH_MFMA_GEMM: e = launch_gemm(p.gemm, blk->gemm, in0, in1, output, ws, s); break;
     case STRIPE_PATH_MFMA_CONV: e = launch_conv(p.conv, blk->conv, in0, in1, output, s); break;
-    case STRIPE_PATH_POOL: e = launch_pool(p.pool, blk->pool, in0, output, s); break;
+    case STRIPE_PATH_POOL: e = launch_pool(p.pool, blk->pool, in0, in1, output, s); break;
     default: e = launch_generic(p, in0, in1, output, s); break;
   }
   if (e != hipSuccess) return fail(STRIPE_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));

@@ -70,7 +70,8 @@ hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_d
 bool conv_i8_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
 hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);
 
-// ---- max aggregation over a 2-d window ------------------------------------
+// ---- aggregation over a 2-d window without a channel reduction: max / min / sum pooling, scaled sums
+// (average pooling), depthwise convolution ------------------------------------
 struct PoolLaunch {
   int variant = -1;
   int rows = 0;      // output rows per workgroup
@@ -79,7 +80,8 @@ struct PoolLaunch {
   int64_t grid = 0;
 };
 bool pool_select(const Pool2dShape& p, int dtype, PoolLaunch* l, stripe_block_info_t* info);
-hipError_t launch_pool(const Pool2dShape& p, const PoolLaunch& l, const void* in, void* out, hipStream_t stream);
+// weights: the second input of a weighted window (scale or depthwise weights), NULL for plain pooling
+hipError_t launch_pool(const Pool2dShape& p, const PoolLaunch& l, const void* in, const void* weights, void* out, hipStream_t stream);
 
 // ---- bandwidth yardstick ---------------------------------------------------
 hipError_t launch_copy(const void* src, void* dst, size_t n_bytes, hipStream_t stream);

@@ -680,9 +680,13 @@ bool match_conv2d(const FlatBlock& fb, Conv2dShape* c) {
 }
 
 bool match_pool2d(const FlatBlock& fb, Pool2dShape* p) {
-  if (fb.empty || fb.n_refs != 2 || fb.intrinsic != STRIPE_INTR_COPY) return false;
+  if (fb.empty) return false;
+  // plain windows: load -> store under max / min / add; weighted windows: load, load, mul -> store under add,
+  // the second input moving with the taps and the channel only (depthwise convolution) or not at all (a scale)
+  const bool weighted = fb.n_refs == 3 && fb.intrinsic == STRIPE_INTR_MUL && fb.agg == STRIPE_AGG_ADD;
+  if (!weighted && (fb.n_refs != 2 || fb.intrinsic != STRIPE_INTR_COPY)) return false;
   if (fb.agg != STRIPE_AGG_MAX && fb.agg != STRIPE_AGG_MIN && fb.agg != STRIPE_AGG_ADD) return false;
-  const FlatRef &I = fb.ref[0], &O = fb.ref[1];
+  const FlatRef &I = fb.ref[0], &O = fb.ref[fb.n_refs - 1];
   Window2d w;
   if (!match_window(fb, I, O.addr, &w)) return false;
   if (!distinct({w.n, w.y, w.x, w.c, w.i, w.j})) return false;
@@ -702,6 +706,19 @@ bool match_pool2d(const FlatBlock& fb, Pool2dShape* p) {
   p->i_base = I.addr.k + w.py * w.st_y + w.px * w.st_x;
   p->o_base = O.addr.k;
   p->agg = fb.agg;
+  p->w_mode = 0;
+  p->w_base = p->w_r = p->w_s = p->w_c = 0;
+  if (weighted) {
+    const Affine& wa = fb.ref[1].addr;
+    for (int t : {w.n, w.y, w.x})
+      if (t >= 0 && wa.c[t] != 0) return false;
+    p->w_base = wa.k;
+    p->w_r = w.i >= 0 ? wa.c[w.i] : 0;
+    p->w_s = w.j >= 0 ? wa.c[w.j] : 0;
+    p->w_c = wa.c[w.c];
+    if (p->w_r < 0 || p->w_s < 0 || p->w_c < 0) return false;
+    p->w_mode = (p->w_r == 0 && p->w_s == 0 && p->w_c == 0) ? 1 : 2;
+  }
   return true;
 }
 

@@ -79,6 +79,11 @@ struct Pool2dShape {     // O[n,y,x,c] = agg over in-bounds taps of I[n, s*y+d*i
   int64_t i_n, i_y, i_x, i_c, o_n, o_y, o_x, o_c;
   int64_t i_base, o_base;
   int agg;                 // STRIPE_AGG_MAX, _MIN or _ADD (sum pooling)
+  // Weighted windows (MUL intrinsic, sum aggregation, no channel reduction): every tap is multiplied by an element of
+  // a second input.  w_mode 0: none (COPY intrinsic); 1: one scalar for all taps (average pooling, the scale as a
+  // one-element buffer); 2: a weight per tap and channel, W[i, j, c] (depthwise convolution).
+  int w_mode;
+  int64_t w_base, w_r, w_s, w_c;
 };
 
 // Parameters of the generic affine-index kernel (passed by value as kernel argument).

@@ -40,6 +40,7 @@ struct PoolParams {
   int32_t rows;                      // output rows per workgroup (rolling kernel)
   int64_t i_n, i_y, i_x, o_n, o_y, o_x;  // element strides (channel stride is 1)
   int64_t i_base, o_base;
+  int64_t w_base, w_r, w_s;              // weighted windows: element offset and tap strides of the weights
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -302,6 +303,83 @@ __global__ __launch_bounds__(128) void pool_f32_strip_kernel(const PoolParams p,
   }
 }
 
+// Weighted windows (sum aggregation of products, no reduction over channels): every tap of the window is multiplied
+// by a weight before it enters the sum.  WMODE 1: one scalar for all taps -- average pooling written as
+// O += I * scale with the scale in a one-element buffer; the kernel sums the in-range taps and scales once.
+// WMODE 2: a weight per tap and channel, W[i, j, c] -- depthwise convolution; a lane keeps the R x S weight quads
+// of its four channels in registers.  Same lane mapping and load pattern as the strip kernel above; taps outside
+// the image are read at a clamped address and replaced by zeros (exact for a sum).
+template <int R, int S, int ST, int TY, int WMODE>
+__global__ __launch_bounds__(128) void window_weighted_f32_kernel(const PoolParams p, const float* __restrict__ in,
+                                                                 const float* __restrict__ wgt, float* __restrict__ out) {
+  constexpr int NR = ST * (TY - 1) + R;
+  const unsigned b = blockIdx.x;
+  const int bx = b % p.blocks_per_row;
+  const int rest = b / p.blocks_per_row;
+  const int ys = rest % p.y_strips;
+  const int n = rest / p.y_strips;
+  const int item = bx * 128 + threadIdx.x;
+  if (item >= p.items) return;
+  const int c4 = item % p.C4;
+  const int xo = item / p.C4;
+  uint32_t voff[S];
+  bool xv[S];
+#pragma unroll
+  for (int j = 0; j < S; ++j) {
+    const int xc = xo * ST - p.pad_x + j;
+    const int xcl = xc < 0 ? 0 : (xc >= p.W ? p.W - 1 : xc);
+    xv[j] = xc == xcl;
+    voff[j] = ((uint32_t)xcl * (uint32_t)p.i_x + (uint32_t)c4 * 4u) * 4u;
+  }
+  const uint32_t ooff = ((uint32_t)xo * (uint32_t)p.o_x + (uint32_t)c4 * 4u) * 4u;
+  const char* ib = (const char*)(in + p.i_base + (int64_t)n * p.i_n);
+  char* ob = (char*)(out + p.o_base + (int64_t)n * p.o_n);
+  const int yo0 = ys * TY;
+  const int y0 = yo0 * ST - p.pad_y;
+
+  f32x4 v[NR][S];
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const int y = y0 + r;
+    const int yc = y < 0 ? 0 : (y >= p.H ? p.H - 1 : y);
+    const char* rp = ib + (int64_t)yc * p.i_y * 4;
+#pragma unroll
+    for (int j = 0; j < S; ++j) v[r][j] = *(const f32x4*)(rp + voff[j]);
+  }
+  f32x4 w[R][S];
+  float scale = 1.f;
+  if constexpr (WMODE == 2) {
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+#pragma unroll
+      for (int j = 0; j < S; ++j) w[i][j] = *(const f32x4*)(wgt + p.w_base + (int64_t)i * p.w_r + (int64_t)j * p.w_s + c4 * 4);
+  } else {
+    scale = wgt[p.w_base];
+  }
+  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int r = 0; r < NR; ++r) {
+    const int y = y0 + r;
+    const bool yv = y >= 0 && y < p.H;
+#pragma unroll
+    for (int j = 0; j < S; ++j) v[r][j] = (yv && xv[j]) ? v[r][j] : zero;
+  }
+#pragma unroll
+  for (int ty = 0; ty < TY; ++ty) {
+    const int yo = yo0 + ty;
+    f32x4 acc = zero;
+#pragma unroll
+    for (int i = 0; i < R; ++i)
+#pragma unroll
+      for (int j = 0; j < S; ++j) {
+        if constexpr (WMODE == 2) acc += v[ty * ST + i][j] * w[i][j];
+        else acc += v[ty * ST + i][j];
+      }
+    if constexpr (WMODE == 1) acc *= scale;
+    if (yo < p.Ho) *(f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff) = acc;
+  }
+}
+
 PoolParams make_params(const Pool2dShape& s, int ty, int wg) {
   PoolParams p;
   p.N = (int)s.N; p.H = (int)s.H; p.W = (int)s.W; p.Ho = (int)s.Ho; p.Wo = (int)s.Wo; p.C4 = (int)(s.C / 4);
@@ -313,6 +391,7 @@ PoolParams make_params(const Pool2dShape& s, int ty, int wg) {
   p.rows = ty;
   p.i_n = s.i_n; p.i_y = s.i_y; p.i_x = s.i_x; p.o_n = s.o_n; p.o_y = s.o_y; p.o_x = s.o_x;
   p.i_base = s.i_base; p.o_base = s.o_base;
+  p.w_base = s.w_base; p.w_r = s.w_r; p.w_s = s.w_s;
   return p;
 }
 
@@ -334,6 +413,8 @@ hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* ou
 constexpr int kRollVariant = 100;
 // other windows, min and sum pooling: lean strip kernel, 2 output rows per strip; variant = kShapeVariant + 3*shape + mode
 constexpr int kShapeVariant = 200;
+// weighted windows: variant = kWeightedVariant + 2*shape + (0: one scale, 1: per tap and channel)
+constexpr int kWeightedVariant = 300;
 struct PoolWindow { int r, s, stride; };
 constexpr PoolWindow kWindows[] = {{3, 3, 2}, {2, 2, 2}, {3, 3, 1}};
 
@@ -355,6 +436,29 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   const bool row_offsets_fit = ((s.W - 1) * s.i_x + s.C) < ((int64_t)1 << 29) && ((s.Wo - 1) * s.o_x + s.C) < ((int64_t)1 << 29) &&
                               s.i_x >= 0 && s.o_x >= 0;
   const int mode = s.agg == STRIPE_AGG_ADD ? 2 : s.agg == STRIPE_AGG_MIN ? 1 : 0;
+  if (s.w_mode) {
+    // weighted window: a scale (one element) or per-tap, per-channel weights with the channels contiguous (16-byte loads)
+    if (mode != 2 || !row_offsets_fit) return false;
+    if (s.w_mode == 2 && (s.w_c != 1 || s.w_r % 4 || s.w_s % 4 || s.w_base % 4)) return false;
+    const PoolParams p = make_params(s, 2, 128);
+    const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
+    if (grid > 0x7fffffffLL) return false;
+    l->variant = kWeightedVariant + 2 * window + (s.w_mode - 1);
+    l->rows = 2;
+    l->wg = 128;
+    l->grid = grid;
+    info->path = STRIPE_PATH_POOL;
+    info->tile_m = 2;
+    info->tile_n = 128;
+    info->tile_k = 0;
+    info->frag_m = info->frag_n = info->frag_k = 0;
+    info->lds_bytes = 0;
+    info->workgroup_size = 128;
+    info->grid = grid;
+    snprintf(info->kernel, sizeof info->kernel, "%s_f32_%dx%ds%d_ty2", s.w_mode == 2 ? "depthwise" : "pool_scaled_sum", kWindows[window].r,
+             kWindows[window].s, kWindows[window].stride);
+    return true;
+  }
   if (window != 0 || mode != 0) {
     if (!row_offsets_fit) return false;
     const PoolParams p = make_params(s, 2, 128);
@@ -434,8 +538,25 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   return true;
 }
 
-hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in, void* out, hipStream_t st) {
+hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in, const void* weights, void* out, hipStream_t st) {
   if (((uintptr_t)in % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
+  if (l.variant >= kWeightedVariant) {
+    if (!weights || ((uintptr_t)weights % (s.w_mode == 2 ? 16 : 4))) return hipErrorInvalidValue;
+    const PoolParams p = make_params(s, 2, 128);
+    const dim3 g((unsigned)l.grid), b(128);
+    const float *i = (const float*)in, *w = (const float*)weights;
+    float* o = (float*)out;
+    switch (l.variant - kWeightedVariant) {
+      case 0: hipLaunchKernelGGL((window_weighted_f32_kernel<3, 3, 2, 2, 1>), g, b, 0, st, p, i, w, o); break;
+      case 1: hipLaunchKernelGGL((window_weighted_f32_kernel<3, 3, 2, 2, 2>), g, b, 0, st, p, i, w, o); break;
+      case 2: hipLaunchKernelGGL((window_weighted_f32_kernel<2, 2, 2, 2, 1>), g, b, 0, st, p, i, w, o); break;
+      case 3: hipLaunchKernelGGL((window_weighted_f32_kernel<2, 2, 2, 2, 2>), g, b, 0, st, p, i, w, o); break;
+      case 4: hipLaunchKernelGGL((window_weighted_f32_kernel<3, 3, 1, 2, 1>), g, b, 0, st, p, i, w, o); break;
+      case 5: hipLaunchKernelGGL((window_weighted_f32_kernel<3, 3, 1, 2, 2>), g, b, 0, st, p, i, w, o); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   if (l.variant >= kShapeVariant) {
     const PoolParams p = make_params(s, 2, 128);
     const dim3 g((unsigned)l.grid), b(128);

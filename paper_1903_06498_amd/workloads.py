@@ -275,6 +275,35 @@ def maxpool_block(N, H, W, C, R, stride, pad, dtype="f32", agg="max") -> Block:
                       constraints=cons, intrinsic="copy")
 
 
+def depthwise_conv_block(N, H, W, C, R, S, stride, pad, dtype="f32", dilation=1) -> Block:
+    """O[n,y,x,c] += I[n, s*y + d*i - p, s*x + d*j - p, c] * F[i,j,c]: a convolution without a reduction over channels
+    (every channel has its own R x S filter); the same affine-access block shape as any other (Section 3.2)."""
+    d = dilation
+    Ho = (H + 2 * pad - d * (R - 1) - 1) // stride + 1
+    Wo = (W + 2 * pad - d * (S - 1) - 1) // stride + 1
+    out_dtype = "i32" if dtype in ("i8", "i32") else "f32"
+    bufs = [Buffer("I", "in", dtype, (N, H, W, C)), Buffer("F", "in", dtype, (R, S, C)), Buffer("O", "out", out_dtype, (N, Ho, Wo, C))]
+    ya, xa = f"{stride}*y + {d}*i - {pad}", f"{stride}*x + {d}*j - {pad}"
+    cons = [f"{ya} >= 0", f"{H - 1 + pad} - {stride}*y - {d}*i >= 0", f"{xa} >= 0", f"{W - 1 + pad} - {stride}*x - {d}*j >= 0"]
+    return flat_block(bufs, dict(n=N, y=Ho, x=Wo, c=C, i=R, j=S),
+                      [(["n", ya, xa, "c"], "assign"), (["i", "j", "c"], "assign"), (["n", "y", "x", "c"], "add")],
+                      constraints=cons, intrinsic="mul")
+
+
+def avgpool_block(N, H, W, C, R, stride, pad, dtype="f32") -> Block:
+    """Average pooling as sum aggregation of scaled taps: O[n,y,x,c] += I[n, s*y+i-p, s*x+j-p, c] * K[0], the scale
+    1/(R*R) held in a one-element buffer K.  Taps outside the image are removed by the constraints, so a border
+    window sums fewer taps but is scaled like an interior one."""
+    Ho = (H + 2 * pad - R) // stride + 1
+    Wo = (W + 2 * pad - R) // stride + 1
+    bufs = [Buffer("I", "in", dtype, (N, H, W, C)), Buffer("K", "in", dtype, (1,)), Buffer("O", "out", "f32", (N, Ho, Wo, C))]
+    ya, xa = f"{stride}*y + i - {pad}", f"{stride}*x + j - {pad}"
+    cons = [f"{ya} >= 0", f"{H - 1 + pad} - {stride}*y - i >= 0", f"{xa} >= 0", f"{W - 1 + pad} - {stride}*x - j >= 0"]
+    return flat_block(bufs, dict(n=N, y=Ho, x=Wo, c=C, i=R, j=R),
+                      [(["n", ya, xa, "c"], "assign"), (["0"], "assign"), (["n", "y", "x", "c"], "add")],
+                      constraints=cons, intrinsic="mul")
+
+
 # --------------------------------------------------------------------------
 # The paper's worked example (Figure 5): a 3x3 convolution over a 12x16
 # spatial extent, 8 -> 16 channels, before and after the 3x4 output tiling.
@@ -389,7 +418,7 @@ def linear_bias_relu_program(M, N, K, out_dtype="bf16", b_transposed=True) -> Bl
 EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32",
                "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "gemm_bf16_1024", "gemm_bf16_2048",
                "linear_bias_relu_4096", "gemm_bf16_256x256x65536", "gemm_i8_256x256x65536_bt", "gemm_bf16_1024x1024x8192", "conv3x3_bf16_128to128", "conv3x3_s2_bf16_64to128", "conv1x7_bf16_64to64",
-               "conv3x3_bf16_w112", "conv5x5_bf16_32to32", "conv3x3_i8_64to64")
+               "conv3x3_bf16_w112", "conv5x5_bf16_32to32", "conv3x3_i8_64to64", "depthwise3x3_f32", "avgpool3x3s2_f32")
 
 
 def extra_block(name: str) -> Block:
@@ -409,6 +438,10 @@ def extra_block(name: str) -> Block:
     if name in family:
         N, H, Wd, Ci, Co, R, S, st, pad, dt = family[name]
         return conv2d_block(N, H, Wd, Ci, Co, R, S, st, pad, dt, "i32" if dt == "i8" else "f32")
+    if name == "depthwise3x3_f32":             # 3x3 depthwise convolution over the max-pooling config's tensor
+        return depthwise_conv_block(32, 112, 112, 64, 3, 3, 1, 1, "f32")
+    if name == "avgpool3x3s2_f32":             # the max-pooling config's window as an average (sum of taps times 1/9)
+        return avgpool_block(32, 112, 112, 64, 3, 2, 1)
     if name == "gemm_bf16_256x256x65536":      # few output tiles, long reduction index: the reduction is split over workgroups
         return matmul_block(256, 256, 65536, "bf16", "f32")
     if name == "gemm_i8_256x256x65536_bt":
@@ -443,6 +476,9 @@ def extra_inputs(name: str):
     if name in ("resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32"):
         return config_inputs("resnet_conv_bf16") + [seeded_tensor((64,), "f32", 2)]
     blk = extra_block(name)
+    if name == "avgpool3x3s2_f32":
+        import torch
+        return [seeded_tensor(blk.refs[0].sizes, "f32", 0), torch.full((1,), 1.0 / 9.0, dtype=torch.float32)]
     return [seeded_tensor(r.sizes, r.dtype, seed) for seed, r in enumerate(blk.refs) if r.dir == "in"]
 
 

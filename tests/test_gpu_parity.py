@@ -519,6 +519,43 @@ def test_pool_other_windows_and_min(R, stride, pad, agg):
         assert np.array_equal(got, np.broadcast_to((cy[:, None] * cx[None, :])[None, :, :, None], got.shape))
 
 
+@pytest.mark.parametrize("R,stride,pad,dtype", [(3, 1, 1, "f32"), (3, 2, 1, "f32"), (2, 2, 0, "f32"), (3, 1, 1, "bf16"), (3, 2, 1, "i8"),
+                                               (5, 1, 2, "f32")])
+def test_depthwise_convolution(R, stride, pad, dtype):
+    """A convolution without a channel reduction: fp32 3x3 / 2x2 windows run on the window family's weighted kernel
+    (a lane keeps the taps' weights of its four channels in registers), everything else on the generic kernels."""
+    N, H, Wd, Cc = 2, 21, 18, 24
+    blk = W.depthwise_conv_block(N, H, Wd, Cc, R, R, stride, pad, dtype)
+    ins = [W.seeded_tensor((N, H, Wd, Cc), dtype, 0), W.seeded_tensor((R, R, Cc), dtype, 1)]
+    info, score = parity(blk, ins, what=f"depthwise {R}x{R} s{stride} {dtype}")
+    say(f"depthwise {R}x{R} s{stride} {dtype}: {info['kernel']} score {score:.3g}")
+    special = dtype == "f32" and R in (2, 3)
+    assert (info["path_name"] == "pool" and info["kernel"].startswith("depthwise")) == special, info
+    if special:
+        assert np.allclose(run_gpu(blk, ins), run_gpu(blk, ins, "generic"), rtol=1e-5, atol=1e-5)
+
+
+def test_depthwise_convolution_dilated_runs_generic():
+    blk = W.depthwise_conv_block(2, 17, 15, 8, 3, 3, 1, 2, "f32", dilation=2)
+    ins = [W.seeded_tensor((2, 17, 15, 8), "f32", 0), W.seeded_tensor((3, 3, 8), "f32", 1)]
+    info, _ = parity(blk, ins, what="dilated depthwise")
+    assert info["path_name"] == "generic", info
+
+
+@pytest.mark.parametrize("R,stride,pad", [(3, 2, 1), (2, 2, 0), (3, 1, 1), (4, 4, 0)])
+def test_average_pooling_with_scale(R, stride, pad):
+    """Average pooling as a sum of scaled taps (the scale in a one-element buffer): the window family's kernel sums
+    the in-range taps and scales once; windows it has no variant for run on the generic kernel."""
+    N, H, Wd, Cc = 2, 24, 20, 16
+    blk = W.avgpool_block(N, H, Wd, Cc, R, stride, pad)
+    ins = [W.seeded_tensor((N, H, Wd, Cc), "f32", 0), torch.full((1,), 1.0 / (R * R), dtype=torch.float32)]
+    info, score = parity(blk, ins, what=f"avgpool {R}x{R} s{stride}")
+    say(f"avgpool {R}x{R} s{stride}: {info['kernel']} rel err {score:.2e}")
+    assert (info["path_name"] == "pool" and info["kernel"].startswith("pool_scaled_sum")) == (R in (2, 3)), info
+    ref = torch.nn.functional.avg_pool2d(ins[0].permute(0, 3, 1, 2), R, stride, pad, count_include_pad=True).permute(0, 2, 3, 1)
+    assert np.allclose(run_gpu(blk, ins).reshape(ref.shape), ref.numpy(), rtol=1e-5, atol=1e-6)
+
+
 def test_pool_all_negative_and_generic_agree():
     blk = W.maxpool_block(2, 21, 17, 8, 3, 2, 1)
     x = -torch.abs(W.seeded_tensor((2, 21, 17, 8), "f32", 1)) - 1

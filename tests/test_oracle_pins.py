@@ -442,3 +442,29 @@ def test_random_tiny_blocks_with_root_origins_against_dictionary_evaluator(seed)
             assert res.touched[e] == 1 and res.out[e] == want[e], (e, res.out[e], want[e])
         else:
             assert res.touched[e] == 0 and res.out[e] == 12345
+
+
+# ------------------------------------------------- shapes without a channel reduction, dilated accesses
+@pytest.mark.parametrize("stride,dilation", [(1, 1), (2, 1), (1, 2)])
+def test_depthwise_and_dilated_convolution_match_library(stride, dilation):
+    """O[n,y,x,c] += I[n, s*y + d*i - p, s*x + d*j - p, c] * F[i,j,c] is the library's grouped convolution with one
+    group per channel (and its dilation argument)."""
+    N, H, Wd, Cc, R, S, p = 2, 11, 9, 5, 3, 3, 2
+    blk = W.depthwise_conv_block(N, H, Wd, Cc, R, S, stride, p, "f32", dilation)
+    i, f = W.seeded_tensor((N, H, Wd, Cc), "f32", 0), W.seeded_tensor((R, S, Cc), "f32", 1)
+    res = O.evaluate(blk, [W.to_numpy(i).ravel(), W.to_numpy(f).ravel()])
+    ref = torch.nn.functional.conv2d(i.double().permute(0, 3, 1, 2), f.double().permute(2, 0, 1)[:, None], stride=stride, padding=p,
+                                     dilation=dilation, groups=Cc).permute(0, 2, 3, 1).numpy()
+    assert res.out.size == ref.size and res.touched.all()
+    assert np.max(np.abs(res.out.reshape(ref.shape) - ref)) <= 1e-12 * np.max(np.abs(ref))
+
+
+def test_average_pooling_as_scaled_sum_matches_library():
+    """Sum of the in-bounds taps times 1/9 = the library's average pooling that counts the padding in the divisor."""
+    N, H, Wd, Cc = 2, 13, 10, 3
+    blk = W.avgpool_block(N, H, Wd, Cc, 3, 2, 1)
+    x = W.seeded_tensor((N, H, Wd, Cc), "f32", 0)
+    k = np.array([1.0 / 9.0], np.float32)
+    res = O.evaluate(blk, [W.to_numpy(x).ravel(), k])
+    ref = torch.nn.functional.avg_pool2d(x.double().permute(0, 3, 1, 2), 3, 2, 1, count_include_pad=True).permute(0, 2, 3, 1).numpy()
+    assert np.max(np.abs(res.out.reshape(ref.shape) - ref * (float(k[0]) * 9.0))) <= 1e-12
