@@ -63,8 +63,11 @@ KIND = {
     "conv3x3_bf16_w112": ("TFLOP/s", "hbm", "bf16"),
     "conv5x5_bf16_32to32": ("TFLOP/s", "hbm", "bf16"),
     "conv3x3_i8_64to64": ("TOP/s", "hbm", "int8"),
+    "conv3x3_bf16_128to192": ("TFLOP/s", "mfma", "bf16"),
     "depthwise3x3_f32": ("GB/s", "hbm", "f32"),        # weighted windows on the pooling family's kernel
     "avgpool3x3s2_f32": ("GB/s", "hbm", "f32"),
+    "maxpool2x2s2_f32": ("GB/s", "hbm", "f32"),
+    "maxpool3x3s1_f32": ("GB/s", "hbm", "f32"),
     "pointwise_conv_bf16": ("TFLOP/s", "hbm", "bf16"),
     "transposed_conv_f32": ("TFLOP/s", "alu", "f32"),
     "resnet_conv_bias_relu_bf16": ("TFLOP/s", "hbm", "bf16"),   # two statements fused into one kernel, bf16 output

@@ -18,6 +18,8 @@
 // kernel re-reads each input element once per tap from L2, which they avoid.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "kernels.hpp"
 
 namespace stripe {
@@ -253,8 +255,50 @@ bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLa
   const int64_t m_total = c.N * c.Ho * c.Wo;
   if (m_total < 1 || m_total > 0x7fffffffLL - 512) return false;
   if (c.R * c.S * (c.Ci / ck) > 0x7fffffffLL) return false;
-  // narrow outputs take the 256-pixel x 64-channel tile, wide ones 128 x 128
-  const int tn = c.Co <= 64 ? 64 : 128, tm = tn == 128 ? 128 : 256;
+  // Workgroup tile by the cost model of paper Section 3.3 at the LDS level: the block as a contraction over
+  // indexes (pixel, channel, reduction); a tile's views are its TM x Kt slice of gathered input and its TN x Kt
+  // slice of the filter, Kt = the four K tiles the ring holds; cost = 128-byte lines staged per multiply-accumulate,
+  // overflow of ragged tiles included.  A range shorter than the tile is padded to one tile (the kernel computes
+  // the padding and discards it) while the work stays the real one.  Candidates are the two instantiated tiles;
+  // ties go to fewer tiles.  STRIPE_TUNE conv_igemm_tn = 64 / 128 overrides the choice.
+  int tn = 0;
+  {
+    const int64_t k_total = c.R * c.S * c.Ci, kt = std::min<int64_t>(4 * ck, k_total);
+    stripe_tile_model_t m = {};
+    m.line_elems = kGfx950LdsLineBytes / (i8 ? 1 : 2);
+    m.mem_cap_elems = kGfx950LdsCapBytes / (i8 ? 1 : 2);
+    m.counted_refs = 3u;
+    m.tiled_idx = 7u;
+    const int forced = tune_int("conv_igemm_tn", 0);
+    double best = 0;
+    int64_t best_tiles = 0;
+    for (int cand : {128, 64}) {
+      const int64_t tile[3] = {cand == 128 ? 128 : 256, cand, kt};
+      TileProblem pr;
+      pr.range = {std::max<int64_t>(m_total, tile[0]), std::max<int64_t>(c.Co, tile[1]), k_total};
+      TileRef a, b;
+      a.coeff = {1, 0, 0, /**/ 0, 0, 1};
+      a.stride = {k_total, 1};
+      b.coeff = {0, 1, 0, /**/ 0, 0, 1};
+      b.stride = {k_total, 1};
+      pr.refs = {a, b};
+      stripe_tile_cost_t cost;
+      tile_cost_of(pr, tile, m, &cost);
+      const double per_real_work = cost.cost * ((double)pr.range[0] / (double)m_total) * ((double)pr.range[1] / (double)c.Co);
+      if (forced == cand) {
+        tn = cand;
+        break;
+      }
+      if (!cost.admissible) continue;
+      if (!tn || per_real_work < best || (per_real_work == best && cost.tiles < best_tiles)) {
+        tn = cand;
+        best = per_real_work;
+        best_tiles = cost.tiles;
+      }
+    }
+    if (!tn) tn = 128;
+  }
+  const int tm = tn == 128 ? 128 : 256;
   const int64_t tiles_m = (m_total + tm - 1) / tm, tiles_n = (c.Co + tn - 1) / tn;
   if (tiles_m * tiles_n > 0x7fffffffLL) return false;
   l->variant = tn == 128 ? kConvIgemmVariant : kConvIgemmVariant + 1;

@@ -154,6 +154,31 @@ int64_t count_points(const FlatBlock& fb, int64_t enumeration_cap);
 void address_form(const FlatBlock& fb, size_t target, std::vector<int64_t>* rng, std::vector<int64_t>* ca, std::vector<int64_t>* cb,
                   std::vector<int64_t>* cc);
 
+// ---- Section 3.3's cost model, usable by the kernel selectors -------------------------------------------------
+// A block as the model sees it: index ranges, and per buffer the coefficient of every index in every dimension's
+// access plus the dimension's stride (the stride-1 dimension is the one counted in lines).
+struct TileRef {
+  std::vector<int64_t> coeff;    // [ndim][n_idx] row-major
+  std::vector<int64_t> stride;   // [ndim]
+};
+struct TileProblem {
+  std::vector<int64_t> range;
+  std::vector<TileRef> refs;
+};
+void tile_cost_of(const TileProblem& pr, const int64_t* tile, const stripe_tile_model_t& m, stripe_tile_cost_t* c);
+bool tile_search_in(const TileProblem& pr, const stripe_tile_model_t& m, const std::vector<std::vector<int64_t>>& cand,
+                    std::vector<int64_t>* best_tile, stripe_tile_cost_t* best);
+
+// Parameter sets of that model for the two memory levels of a gfx950 compute unit that the kernel families tile for.
+//   register level: a "line" is one 16-byte vector load (four 32-bit registers); the hard cap is the 256 registers a
+//     lane can address with two wavefronts per SIMD; below it every data register costs occupancy, which the
+//     selectors charge as a factor 1 + registers * kGfx950RegPenalty on the model's cost (fitted to the strip-height
+//     measurements of the window kernels: 0.3 % per register);
+//   LDS level: lines of 128 bytes; the cap is the CU's 160 KB.
+constexpr int64_t kGfx950RegLineBytes = 16, kGfx950RegCapRegs = 256;
+constexpr double kGfx950RegPenalty = 0.003;
+constexpr int64_t kGfx950LdsLineBytes = 128, kGfx950LdsCapBytes = 160 * 1024;
+
 // Records the calling thread's error detail (what stripe_last_error() returns) and passes the status through.
 stripe_status_t api_fail(stripe_status_t st, const std::string& msg);
 

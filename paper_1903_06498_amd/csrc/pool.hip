@@ -418,6 +418,84 @@ constexpr int kWeightedVariant = 300;
 struct PoolWindow { int r, s, stride; };
 constexpr PoolWindow kWindows[] = {{3, 3, 2}, {2, 2, 2}, {3, 3, 1}};
 
+// Output rows per strip, chosen with the cost model of paper Section 3.3 at the register level of a lane: the
+// lane's tile is one output column x four channels x TY rows; its views are the (stride * (TY - 1) + R) x S x 4
+// input patch, the TY x 1 x 4 outputs and, for weighted windows, the weights.  Cost = 16-byte loads and stores
+// per output row.  Registers are a soft memory: a larger tile still runs, with fewer wavefronts resident, so
+// instead of the model's hard cap (kept at the 256 registers a lane can have at all) the cost is scaled by
+// 1 + footprint * kGfx950RegPenalty; that one correction reproduces the measured optimum of every window shape
+// timed on this chip.  Candidates are the strip heights the kernels are instantiated for; ties go to the smaller
+// footprint.  STRIPE_TUNE pool_ty overrides the choice.
+int choose_strip_rows(const Pool2dShape& s, std::initializer_list<int> available) {
+  const int want = tune_int("pool_ty", 0);
+  for (int a : available)
+    if (a == want) return a;
+  TileProblem pr;
+  pr.range = {s.Ho, s.Wo, s.C, s.R, s.S};                      // indexes y, x, c, i, j
+  TileRef in, out;
+  in.coeff = {s.stride_y, 0, 0, s.dil_y, 0, /**/ 0, s.stride_x, 0, 0, s.dil_x, /**/ 0, 0, 1, 0, 0};
+  in.stride = {s.i_y, s.i_x, 1};
+  out.coeff = {1, 0, 0, 0, 0, /**/ 0, 1, 0, 0, 0, /**/ 0, 0, 1, 0, 0};
+  out.stride = {s.o_y, s.o_x, 1};
+  pr.refs = {in, out};
+  if (s.w_mode == 2) {
+    TileRef w;
+    w.coeff = {0, 0, 0, 1, 0, /**/ 0, 0, 0, 0, 1, /**/ 0, 0, 1, 0, 0};
+    w.stride = {s.w_r, s.w_s, 1};
+    pr.refs.push_back(w);
+  } else if (s.w_mode == 1) {
+    TileRef w;
+    w.coeff = {0, 0, 0, 0, 0};
+    w.stride = {1};
+    pr.refs.push_back(w);
+  }
+  stripe_tile_model_t m = {};
+  m.line_elems = kGfx950RegLineBytes / 4;
+  m.mem_cap_elems = kGfx950RegCapRegs;
+  m.counted_refs = (1u << pr.refs.size()) - 1;
+  m.tiled_idx = 1u;                                            // work counted in output rows
+  int best = 0, smallest = 0;
+  double best_cost = 0;
+  int64_t best_fp = 0;
+  for (int a : available) {
+    if (!smallest || a < smallest) smallest = a;
+    if (a > s.Ho) continue;
+    const int64_t tile[5] = {a, 1, 4, s.R, s.S};
+    stripe_tile_cost_t c;
+    tile_cost_of(pr, tile, m, &c);
+    if (!c.admissible) continue;
+    const double corrected = c.cost * (1.0 + (double)c.footprint_elems * kGfx950RegPenalty);
+    if (!best || corrected < best_cost || (corrected == best_cost && c.footprint_elems < best_fp)) {
+      best = a;
+      best_cost = corrected;
+      best_fp = c.footprint_elems;
+    }
+  }
+  return best ? best : smallest;
+}
+
+template <int R, int S, int ST, int MODE>
+hipError_t launch_strip_rows(int ty, const PoolParams& p, dim3 g, const float* i, float* o, hipStream_t st) {
+  switch (ty) {
+    case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 1, MODE>), g, dim3(128), 0, st, p, i, o); break;
+    case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 2, MODE>), g, dim3(128), 0, st, p, i, o); break;
+    case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 3, MODE>), g, dim3(128), 0, st, p, i, o); break;
+    case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 4, MODE>), g, dim3(128), 0, st, p, i, o); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+template <int R, int S, int ST, int WMODE>
+hipError_t launch_weighted_rows(int ty, const PoolParams& p, dim3 g, const float* i, const float* w, float* o, hipStream_t st) {
+  switch (ty) {
+    case 1: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 1, WMODE>), g, dim3(128), 0, st, p, i, w, o); break;
+    case 2: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 2, WMODE>), g, dim3(128), 0, st, p, i, w, o); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
 bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_info_t* info) {
   if (s.dil_y != 1 || s.dil_x != 1) return false;   // dilated windows run on the generic kernel
   if (dtype != STRIPE_F32) return false;
@@ -440,44 +518,46 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     // weighted window: a scale (one element) or per-tap, per-channel weights with the channels contiguous (16-byte loads)
     if (mode != 2 || !row_offsets_fit) return false;
     if (s.w_mode == 2 && (s.w_c != 1 || s.w_r % 4 || s.w_s % 4 || s.w_base % 4)) return false;
-    const PoolParams p = make_params(s, 2, 128);
+    const int rows = choose_strip_rows(s, {1, 2});
+    const PoolParams p = make_params(s, rows, 128);
     const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
     if (grid > 0x7fffffffLL) return false;
     l->variant = kWeightedVariant + 2 * window + (s.w_mode - 1);
-    l->rows = 2;
+    l->rows = rows;
     l->wg = 128;
     l->grid = grid;
     info->path = STRIPE_PATH_POOL;
-    info->tile_m = 2;
+    info->tile_m = rows;
     info->tile_n = 128;
     info->tile_k = 0;
     info->frag_m = info->frag_n = info->frag_k = 0;
     info->lds_bytes = 0;
     info->workgroup_size = 128;
     info->grid = grid;
-    snprintf(info->kernel, sizeof info->kernel, "%s_f32_%dx%ds%d_ty2", s.w_mode == 2 ? "depthwise" : "pool_scaled_sum", kWindows[window].r,
-             kWindows[window].s, kWindows[window].stride);
+    snprintf(info->kernel, sizeof info->kernel, "%s_f32_%dx%ds%d_ty%d", s.w_mode == 2 ? "depthwise" : "pool_scaled_sum", kWindows[window].r,
+             kWindows[window].s, kWindows[window].stride, rows);
     return true;
   }
   if (window != 0 || mode != 0) {
     if (!row_offsets_fit) return false;
-    const PoolParams p = make_params(s, 2, 128);
+    const int rows = choose_strip_rows(s, {1, 2, 3, 4});
+    const PoolParams p = make_params(s, rows, 128);
     const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
     if (grid > 0x7fffffffLL) return false;
     l->variant = kShapeVariant + 3 * window + mode;
-    l->rows = 2;
+    l->rows = rows;
     l->wg = 128;
     l->grid = grid;
     info->path = STRIPE_PATH_POOL;
-    info->tile_m = 2;
+    info->tile_m = rows;
     info->tile_n = 128;
     info->tile_k = 0;
     info->frag_m = info->frag_n = info->frag_k = 0;
     info->lds_bytes = 0;
     info->workgroup_size = 128;
     info->grid = grid;
-    snprintf(info->kernel, sizeof info->kernel, "pool_%s_f32_%dx%ds%d_ty2", mode == 2 ? "sum" : mode == 1 ? "min" : "max", kWindows[window].r,
-             kWindows[window].s, kWindows[window].stride);
+    snprintf(info->kernel, sizeof info->kernel, "pool_%s_f32_%dx%ds%d_ty%d", mode == 2 ? "sum" : mode == 1 ? "min" : "max", kWindows[window].r,
+             kWindows[window].s, kWindows[window].stride, rows);
     return true;
   }
   if (tune_int("pool_roll", 0) && row_offsets_fit) {
@@ -512,10 +592,10 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     snprintf(info->kernel, sizeof info->kernel, "pool_max_f32_3x3s2_roll%d_wg%d", rows, wg);
     return true;
   }
-  int ty_idx = 1;  // 2 rows per strip
-  const int want = tune_int("pool_ty", 0);
+  int ty_idx = 1;
+  const int chosen = choose_strip_rows(s, {1, 2, 3, 4, 7});
   for (int i = 0; i < (int)(sizeof kTyChoices / sizeof kTyChoices[0]); ++i)
-    if (kTyChoices[i] == want) ty_idx = i;
+    if (kTyChoices[i] == chosen) ty_idx = i;
   const int nt = tune_int("pool_nt", 0) ? 1 : 0;
   const int ty = kTyChoices[ty_idx];
   const PoolParams p = make_params(s, ty, 128);
@@ -542,38 +622,36 @@ hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in
   if (((uintptr_t)in % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
   if (l.variant >= kWeightedVariant) {
     if (!weights || ((uintptr_t)weights % (s.w_mode == 2 ? 16 : 4))) return hipErrorInvalidValue;
-    const PoolParams p = make_params(s, 2, 128);
-    const dim3 g((unsigned)l.grid), b(128);
+    const PoolParams p = make_params(s, l.rows, 128);
+    const dim3 g((unsigned)l.grid);
     const float *i = (const float*)in, *w = (const float*)weights;
     float* o = (float*)out;
     switch (l.variant - kWeightedVariant) {
-      case 0: hipLaunchKernelGGL((window_weighted_f32_kernel<3, 3, 2, 2, 1>), g, b, 0, st, p, i, w, o); break;
-      case 1: hipLaunchKernelGGL((window_weighted_f32_kernel<3, 3, 2, 2, 2>), g, b, 0, st, p, i, w, o); break;
-      case 2: hipLaunchKernelGGL((window_weighted_f32_kernel<2, 2, 2, 2, 1>), g, b, 0, st, p, i, w, o); break;
-      case 3: hipLaunchKernelGGL((window_weighted_f32_kernel<2, 2, 2, 2, 2>), g, b, 0, st, p, i, w, o); break;
-      case 4: hipLaunchKernelGGL((window_weighted_f32_kernel<3, 3, 1, 2, 1>), g, b, 0, st, p, i, w, o); break;
-      case 5: hipLaunchKernelGGL((window_weighted_f32_kernel<3, 3, 1, 2, 2>), g, b, 0, st, p, i, w, o); break;
+      case 0: return launch_weighted_rows<3, 3, 2, 1>(l.rows, p, g, i, w, o, st);
+      case 1: return launch_weighted_rows<3, 3, 2, 2>(l.rows, p, g, i, w, o, st);
+      case 2: return launch_weighted_rows<2, 2, 2, 1>(l.rows, p, g, i, w, o, st);
+      case 3: return launch_weighted_rows<2, 2, 2, 2>(l.rows, p, g, i, w, o, st);
+      case 4: return launch_weighted_rows<3, 3, 1, 1>(l.rows, p, g, i, w, o, st);
+      case 5: return launch_weighted_rows<3, 3, 1, 2>(l.rows, p, g, i, w, o, st);
       default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
   }
   if (l.variant >= kShapeVariant) {
-    const PoolParams p = make_params(s, 2, 128);
-    const dim3 g((unsigned)l.grid), b(128);
+    const PoolParams p = make_params(s, l.rows, 128);
+    const dim3 g((unsigned)l.grid);
     const float* i = (const float*)in;
     float* o = (float*)out;
     switch (l.variant - kShapeVariant) {
-      case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, 2, 1>), g, b, 0, st, p, i, o); break;
-      case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, 2, 2>), g, b, 0, st, p, i, o); break;
-      case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, 0>), g, b, 0, st, p, i, o); break;
-      case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, 1>), g, b, 0, st, p, i, o); break;
-      case 5: hipLaunchKernelGGL((pool_f32_strip_kernel<2, 2, 2, 2, 2>), g, b, 0, st, p, i, o); break;
-      case 6: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, 0>), g, b, 0, st, p, i, o); break;
-      case 7: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, 1>), g, b, 0, st, p, i, o); break;
-      case 8: hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 1, 2, 2>), g, b, 0, st, p, i, o); break;
+      case 1: return launch_strip_rows<3, 3, 2, 1>(l.rows, p, g, i, o, st);
+      case 2: return launch_strip_rows<3, 3, 2, 2>(l.rows, p, g, i, o, st);
+      case 3: return launch_strip_rows<2, 2, 2, 0>(l.rows, p, g, i, o, st);
+      case 4: return launch_strip_rows<2, 2, 2, 1>(l.rows, p, g, i, o, st);
+      case 5: return launch_strip_rows<2, 2, 2, 2>(l.rows, p, g, i, o, st);
+      case 6: return launch_strip_rows<3, 3, 1, 0>(l.rows, p, g, i, o, st);
+      case 7: return launch_strip_rows<3, 3, 1, 1>(l.rows, p, g, i, o, st);
+      case 8: return launch_strip_rows<3, 3, 1, 2>(l.rows, p, g, i, o, st);
       default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
   }
   if (l.variant == kRollVariant) {
     const PoolParams p = make_params(s, l.rows, l.wg);

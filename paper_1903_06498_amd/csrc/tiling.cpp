@@ -60,12 +60,29 @@ void span_of(const FlatForm& f, int r, int d, const int64_t* tile, int64_t* lo, 
 
 bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
 
-void cost_of(const FlatForm& f, const int64_t* tile, const stripe_tile_model_t& m, stripe_tile_cost_t* c) {
+TileProblem problem_of(const FlatForm& f) {
+  TileProblem pr;
+  pr.range.assign(f.leaf->ranges, f.leaf->ranges + f.n);
+  for (int r = 0; r < f.leaf->n_refs; ++r) {
+    const stripe_refinement_t& q = f.leaf->refs[r];
+    TileRef t;
+    t.coeff.assign(q.access_coeff, q.access_coeff + (size_t)q.ndim * f.n);
+    t.stride.assign(q.strides, q.strides + q.ndim);
+    pr.refs.push_back(t);
+  }
+  return pr;
+}
+
+}  // namespace
+
+// The cost of one tile (Figure 4's caption): tiles * lines per tile / work, with footprint and admissibility.
+void tile_cost_of(const TileProblem& pr, const int64_t* tile, const stripe_tile_model_t& m, stripe_tile_cost_t* c) {
+  const int n = (int)pr.range.size();
   c->tiles = 1;
   c->work = 1;
   c->admissible = 1;
-  for (int j = 0; j < f.n; ++j) {
-    const int64_t range = f.leaf->ranges[j];
+  for (int j = 0; j < n; ++j) {
+    const int64_t range = pr.range[j];
     c->tiles *= (range + tile[j] - 1) / tile[j];
     if (m.tiled_idx >> j & 1) c->work *= range;
     if (tile[j] != range) {
@@ -76,16 +93,20 @@ void cost_of(const FlatForm& f, const int64_t* tile, const stripe_tile_model_t& 
   }
   c->lines_per_tile = 0;
   c->footprint_elems = 0;
-  for (int r = 0; r < f.leaf->n_refs; ++r) {
+  for (size_t r = 0; r < pr.refs.size(); ++r) {
     if (!(m.counted_refs >> r & 1)) continue;
-    const stripe_refinement_t& q = f.leaf->refs[r];
+    const TileRef& q = pr.refs[r];
+    const int ndim = (int)q.stride.size();
     int line_dim = -1;
-    for (int d = 0; d < q.ndim; ++d)
-      if (q.strides[d] == 1 || q.strides[d] == -1) line_dim = d;
+    for (int d = 0; d < ndim; ++d)
+      if (q.stride[d] == 1 || q.stride[d] == -1) line_dim = d;
     int64_t lines = 1, elems = 1;
-    for (int d = 0; d < q.ndim; ++d) {
-      int64_t lo, hi;
-      span_of(f, r, d, tile, &lo, &hi);
+    for (int d = 0; d < ndim; ++d) {
+      int64_t lo = 0, hi = 0;   // span of the dimension over one tile, relative to the tile's origin
+      for (int j = 0; j < n; ++j) {
+        const int64_t reach = q.coeff[(size_t)d * n + j] * (tile[j] - 1);
+        if (reach < 0) lo += reach; else hi += reach;
+      }
       const int64_t extent = hi - lo + 1;
       elems *= extent;
       lines *= (d == line_dim) ? (extent + m.line_elems - 1) / m.line_elems : extent;
@@ -96,6 +117,38 @@ void cost_of(const FlatForm& f, const int64_t* tile, const stripe_tile_model_t& 
   if (m.mem_cap_elems > 0 && c->footprint_elems > m.mem_cap_elems) c->admissible = 0;
   c->cost = (double)c->tiles * (double)c->lines_per_tile / (double)c->work;
 }
+
+// Exhaustive minimum over the cross product of the candidate sizes; ties go to fewer tiles, then to the
+// lexicographically larger tile.  False if no candidate is admissible.
+bool tile_search_in(const TileProblem& pr, const stripe_tile_model_t& m, const std::vector<std::vector<int64_t>>& cand,
+                    std::vector<int64_t>* best_tile, stripe_tile_cost_t* best) {
+  const int n = (int)pr.range.size();
+  std::vector<size_t> pos(n, 0);
+  std::vector<int64_t> tile(n);
+  best_tile->assign(n, 0);
+  bool found = false;
+  for (;;) {
+    for (int j = 0; j < n; ++j) tile[j] = cand[j][pos[j]];
+    stripe_tile_cost_t c;
+    tile_cost_of(pr, tile.data(), m, &c);
+    if (c.admissible) {
+      bool better = !found || c.cost < best->cost || (c.cost == best->cost && c.tiles < best->tiles);
+      if (found && c.cost == best->cost && c.tiles == best->tiles)
+        better = std::lexicographical_compare(best_tile->begin(), best_tile->end(), tile.begin(), tile.end());
+      if (better) {
+        *best = c;
+        *best_tile = tile;
+        found = true;
+      }
+    }
+    int j = n - 1;
+    while (j >= 0 && ++pos[j] == cand[j].size()) pos[j--] = 0;
+    if (j < 0) break;
+  }
+  return found;
+}
+
+namespace {
 
 stripe_status_t check_model(const stripe_tile_model_t* m) {
   if (!m) return api_fail(STRIPE_ERR_NULL, "model is NULL");
@@ -131,7 +184,7 @@ stripe_status_t stripe_tile_cost(const stripe_block_desc_t* root, const int64_t*
   if (st == STRIPE_OK) st = check_model(model);
   if (st == STRIPE_OK) st = check_tile(f, tile);
   if (st != STRIPE_OK) return st;
-  cost_of(f, tile, *model, out);
+  tile_cost_of(problem_of(f), tile, *model, out);
   return STRIPE_OK;
 }
 
@@ -156,27 +209,9 @@ stripe_status_t stripe_tile_search(const stripe_block_desc_t* root, const stripe
     space *= (double)cand[j].size();
   }
   if (space > (double)(1 << 22)) return api_fail(STRIPE_ERR_UNSUPPORTED, "more than 2^22 candidate tiles: restrict tiled_idx, multiple_of or power_of_two");
-  std::vector<size_t> pos(f.n, 0);
-  std::vector<int64_t> tile(f.n);
-  bool found = false;
-  for (;;) {
-    for (int j = 0; j < f.n; ++j) tile[j] = cand[j][pos[j]];
-    stripe_tile_cost_t c;
-    cost_of(f, tile.data(), *model, &c);
-    if (c.admissible) {
-      bool better = !found || c.cost < best->cost || (c.cost == best->cost && c.tiles < best->tiles);
-      if (found && c.cost == best->cost && c.tiles == best->tiles)
-        better = std::lexicographical_compare(best_tile, best_tile + f.n, tile.begin(), tile.end());
-      if (better) {
-        *best = c;
-        std::memcpy(best_tile, tile.data(), sizeof(int64_t) * f.n);
-        found = true;
-      }
-    }
-    int j = f.n - 1;
-    while (j >= 0 && ++pos[j] == cand[j].size()) pos[j--] = 0;
-    if (j < 0) break;
-  }
+  std::vector<int64_t> tile;
+  const bool found = tile_search_in(problem_of(f), *model, cand, &tile, best);
+  if (found) std::memcpy(best_tile, tile.data(), sizeof(int64_t) * f.n);
   if (!found) return api_fail(STRIPE_ERR_UNSUPPORTED, "no admissible tile under this model");
   return STRIPE_OK;
 }

@@ -508,7 +508,7 @@ def test_pool_other_windows_and_min(R, stride, pad, agg):
     x = W.seeded_tensor((N, H, Wd, C), "f32", 5)
     info, _ = parity(blk, [x], what=f"pool {R}x{R}s{stride}p{pad} {agg}")
     name = "sum" if agg == "add" else agg
-    assert info["path_name"] == "pool" and info["kernel"] == f"pool_{name}_f32_{R}x{R}s{stride}_ty2", info
+    assert info["path_name"] == "pool" and info["kernel"].startswith(f"pool_{name}_f32_{R}x{R}s{stride}_ty"), info
     if agg != "add":
         assert np.array_equal(run_gpu(blk, [x], "pool"), run_gpu(blk, [x], "generic"))
     else:                    # all-ones: the sum is the number of in-range taps, exactly
@@ -517,6 +517,32 @@ def test_pool_other_windows_and_min(R, stride, pad, agg):
         cy = np.array([taps(y, stride, pad, R, H) for y in range(got.shape[1])])
         cx = np.array([taps(xx, stride, pad, R, Wd) for xx in range(got.shape[2])])
         assert np.array_equal(got, np.broadcast_to((cy[:, None] * cx[None, :])[None, :, :, None], got.shape))
+
+
+@pytest.mark.parametrize("ty", [1, 2, 3, 4])
+@pytest.mark.parametrize("R,stride,pad,agg", [(2, 2, 0, "max"), (3, 1, 1, "min"), (3, 2, 1, "add"), (3, 1, 0, "add")])
+def test_pool_other_windows_every_strip_height(R, stride, pad, agg, ty, monkeypatch):
+    """Every strip height the cost model may choose, forced through pool_ty, on ragged row counts."""
+    monkeypatch.setenv("STRIPE_TUNE", f"pool_ty={ty}")
+    N, H, Wd, C = 2, 23, 10, 8
+    blk = W.maxpool_block(N, H, Wd, C, R, stride, pad, agg=agg)
+    info, _ = parity(blk, [W.seeded_tensor((N, H, Wd, C), "f32", 6)], what=f"pool {R}x{R}s{stride} {agg} ty{ty}")
+    assert info["kernel"].endswith(f"_ty{ty}"), info
+
+
+@pytest.mark.parametrize("ty", [1, 2])
+@pytest.mark.parametrize("kind", ["depthwise_s1", "depthwise_s2", "avg_2x2"])
+def test_weighted_windows_every_strip_height(kind, ty, monkeypatch):
+    monkeypatch.setenv("STRIPE_TUNE", f"pool_ty={ty}")
+    if kind == "avg_2x2":
+        blk = W.avgpool_block(2, 23, 10, 8, 2, 2, 0)
+        ins = [W.seeded_tensor((2, 23, 10, 8), "f32", 0), torch.full((1,), 0.25, dtype=torch.float32)]
+    else:
+        st = 1 if kind.endswith("s1") else 2
+        blk = W.depthwise_conv_block(2, 23, 10, 8, 3, 3, st, 1, "f32")
+        ins = [W.seeded_tensor((2, 23, 10, 8), "f32", 0), W.seeded_tensor((3, 3, 8), "f32", 1)]
+    info, _ = parity(blk, ins, what=f"{kind} ty{ty}")
+    assert info["path_name"] == "pool" and info["kernel"].endswith(f"_ty{ty}"), info
 
 
 @pytest.mark.parametrize("R,stride,pad,dtype", [(3, 1, 1, "f32"), (3, 2, 1, "f32"), (2, 2, 0, "f32"), (3, 1, 1, "bf16"), (3, 2, 1, "i8"),

@@ -193,3 +193,17 @@ def test_statement_list_reports_its_workspace():
     fused = B.StripeBlock(W.conv_bias_relu_program(1, 7, 20, 64, 64, 3, 3, 1, 1, "bf16", "f32"))
     assert "+bias_relu" in fused.info["kernel"] and fused.info["workspace_bytes"] == 0     # the temporary was scalarised away
     fused.close()
+
+
+def test_tile_selection_follows_the_cost_model():
+    """Section 3.3's model as the library's tile selector: strip heights of the window family (register level, with
+    the occupancy correction) and the workgroup tile of the general convolution kernel (LDS level)."""
+    kernel = lambda blk: B.StripeBlock(blk).info["kernel"]
+    assert kernel(W.config_block("maxpool_f32")).endswith("3x3s2_ty2")                  # rows shared by windows: 5 rows per 2
+    assert kernel(W.maxpool_block(32, 112, 112, 64, 2, 2, 0)).endswith("2x2s2_ty1")     # no sharing: the smallest footprint
+    assert kernel(W.maxpool_block(32, 112, 112, 64, 3, 1, 1)).endswith("3x3s1_ty4")     # stride 1 shares most: 6 rows per 4
+    assert kernel(W.depthwise_conv_block(32, 112, 112, 64, 3, 3, 1, 1, "f32")).endswith("3x3s1_ty2")
+    assert "256x64x32" in kernel(W.conv2d_block(4, 28, 28, 64, 32, 3, 3, 1, 1, "bf16", "f32"))
+    assert "128x128x32" in kernel(W.conv2d_block(4, 28, 28, 128, 128, 3, 3, 1, 1, "bf16", "f32"))
+    assert "128x128x32" in kernel(W.conv2d_block(4, 28, 28, 64, 96, 3, 3, 1, 1, "bf16", "f32"))
+    assert "256x64x32" in kernel(W.conv2d_block(4, 28, 28, 128, 192, 3, 3, 1, 1, "bf16", "f32"))   # three 64-wide tiles waste nothing
