@@ -36,6 +36,8 @@ MEASURED_TRAFFIC = {
     "conv7x7_s2_int8": 3.4e6 + 51.4e6,
     "maxpool_f32": 133.1e6 + 25.7e6,
 }
+TRAFFIC_SOURCE = {name: f"profiles/{name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the default kernel, scaled by profiles/device_copy.md)"
+                  for name in MEASURED_TRAFFIC}
 
 # workload -> (metric unit, bound, arithmetic dtype)
 KIND = {
@@ -83,17 +85,10 @@ def oracle_sample(name, root, inputs, cores):
     first = root.child
     lo, hi = [0] * len(first.ranges), list(first.ranges)
     if name == "gemm_bf16_4096":
-        hi[0] = 32                       # 32 full output rows, every k: 537 M points
+        hi[0] = 32                       # 32 full output rows, every k: 537 M points (the whole block is 68.7 G points)
         sample, split = "32 of 4096 output rows (all n, all k), literal loops", 1
-    elif name == "resnet_conv_bf16":
-        hi[0] = 2                        # 2 of 32 images: 231 M points
-        sample, split = "2 of 32 images", 1
-    elif name == "conv7x7_s2_int8":
-        hi[0] = 2
-        sample, split = "2 of 16 images", 1
-    elif name == "maxpool_f32":
-        hi[0] = 32
-        sample, split = "all 32 images", 0
+    elif name in ("resnet_conv_bf16", "conv7x7_s2_int8", "maxpool_f32"):
+        sample, split = "the whole block (every image)", 0     # 3.6 G / 1.9 G / 57 M points: seconds on the host cores
     else:
         sample, split = "the whole block", 1
     np_ins = [W.to_numpy(t).ravel() for t in inputs]
@@ -238,9 +233,9 @@ def main():
     kernel_s = gpu_ms / args.steps * 1e-3      # average launch duration over the timed region (events on the launch stream)
 
     work = info["work_points"]
-    traffic = args.traffic_bytes
+    traffic, traffic_source = args.traffic_bytes, ("--traffic-bytes" if args.traffic_bytes is not None else None)
     if traffic is None and args.path == "auto" and not os.environ.get("STRIPE_TUNE") and args.fill == "config":
-        traffic = MEASURED_TRAFFIC.get(name)
+        traffic, traffic_source = MEASURED_TRAFFIC.get(name), TRAFFIC_SOURCE.get(name)
     flops = 2.0 * work
     nbytes = float(info["algorithmic_bytes"])
     if unit == "GB/s":
@@ -256,6 +251,10 @@ def main():
         achieved = nbytes / kernel_s / 1e9
         roof = {"bound": "hbm", "achieved": round(achieved, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
                 "frac": round(achieved / PEAK["hbm_gbs"], 4), "traffic": traffic}
+    if name == "tiny_conv_f32":
+        # sub-microsecond of work: bound by launch latency, so the figure of merit is time per launch, not a roofline fraction
+        roof = {"bound": "launch", "achieved": round(kernel_s * 1e6, 2), "peak": None, "unit": "us/launch", "frac": None, "traffic": None}
+    roof["traffic_source"] = traffic_source
     roof["kernel"] = info["kernel"]
     roof["kernel_us"] = round(kernel_s * 1e6, 2)
     roof["algorithmic_bytes"] = info["algorithmic_bytes"]
@@ -272,6 +271,10 @@ def main():
             cpu_value = 2.0 * res.n_points / dt / 1e12
         cpu = {"value": float(f"{cpu_value:.6g}"), "unit": unit, "cores": cores, "kind": "oracle",
                "sample": f"{sample}: {res.n_points} points in {dt:.2f} s"}
+        if name == "tiny_conv_f32":      # also on one core: the block is too small for threads to pay
+            _, dt1, _, _ = oracle_sample(name, root, inputs, 1)
+            cpu["single_thread_value"] = float(f"{2.0 * res.n_points / dt1 / 1e12:.6g}")
+            cpu["sample"] += f"; one thread: {dt1 * 1e3:.2f} ms"
 
     line = {
         "metric": "Stripe block throughput: TFLOP/s (% of MFMA peak) for conv/matmul blocks, GB/s for max blocks",

@@ -1,6 +1,7 @@
 // C ABI of the Stripe block executor: see include/stripe.h.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <atomic>
 #include <cstdio>
 #include <cstring>
@@ -148,6 +149,7 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
       if (is_out) stage.dst = j; else stage.src[i] = j;
     }
     written[stage.dst] = 1;
+    const bool updates_in_place = stage.dst == stage.src[0] || (stage.n_in > 1 && stage.dst == stage.src[1]);
     stripe_block_desc_t stmt = *st;
     stmt.next = nullptr;
     stmt.parent_refs = nullptr;
@@ -160,8 +162,83 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
       delete prog;
       return rc;   // detail already recorded
     }
+    if (updates_in_place) {
+      // Definition 2 rule 2: an element one iteration writes may not be read by another.  A statement that reads the
+      // buffer it writes is only legal as a per-element update: the read and write maps coincide, every index moves
+      // the address, and the map is injective (make_plan proved that unless it chose the atomic form).
+      const Plan& sp = stage.blk->plan;
+      bool ok = !sp.noop && sp.info.n_red_idx == 0 && sp.gen.atomic == 0;
+      for (int i = 0; i < stage.n_in && ok; ++i)
+        if (stage.src[i] == stage.dst) {
+          const Affine &rd = sp.flat.ref[i].addr, &wr = sp.flat.ref[sp.flat.n_refs - 1].addr;
+          ok = rd.k == wr.k;
+          for (int j = 0; j < sp.flat.n_idx && ok; ++j) ok = rd.c[j] == wr.c[j];
+        }
+      if (!ok && !sp.noop) {
+        delete stage.blk;
+        delete prog;
+        return fail(STRIPE_ERR_INVALID_DESC, "a statement reads the buffer it writes through a different map (or with a reduction): an element written by "
+                                             "one iteration would be read by another");
+      }
+    }
     prog->stages.push_back(stage);
   }
+  // A temporary element that is read but never written has no defined value (the statements run as if in serial and
+  // nothing initialises a temporary).  Refused where it can be shown: an upper bound on the elements a statement can
+  // write into the temporary (the hull's distinct output elements, one fewer if some output tuple provably has no
+  // point inside the polyhedron) against a lower bound on the elements a later constraint-free statement reads.
+  for (size_t w = 0; w < prog->stages.size(); ++w) {
+    const Stage& ws = prog->stages[w];
+    if (root->refs[ws.dst].dir != STRIPE_TEMP) continue;
+    const Plan& wp = ws.blk->plan;
+    int64_t written_upper = wp.noop ? 0 : wp.info.output_elements;
+    if (!wp.noop) {
+      const FlatBlock& f = wp.flat;
+      const Affine& oaddr = f.ref[f.n_refs - 1].addr;
+      for (const Affine& q : f.cons) {
+        // the most favourable value of the constraint over everything but the least favourable output tuple
+        __int128 worst = q.k;
+        for (int j = 0; j < f.n_idx; ++j) {
+          const __int128 span = (__int128)q.c[j] * (f.range[j] - 1);
+          if (oaddr.c[j]) worst += span < 0 ? span : 0;    // output index: pick the tuple that hurts
+          else worst += span > 0 ? span : 0;               // reduction index: pick the point that helps
+        }
+        if (worst < 0) {
+          --written_upper;
+          break;
+        }
+      }
+    }
+    for (size_t r = w + 1; r < prog->stages.size(); ++r) {
+      const Stage& rs = prog->stages[r];
+      if (rs.dst == ws.dst) break;                         // rewritten before any further read
+      for (int i = 0; i < rs.n_in; ++i) {
+        if (rs.src[i] != ws.dst) continue;
+        const Plan& rp = rs.blk->plan;
+        if (rp.noop || !rp.flat.cons.empty()) continue;
+        // distinct elements read: product of the ranges of the indexes that move the address, if that map is
+        // injective (strides sorted by magnitude, each exceeding the span of the smaller ones)
+        const FlatBlock& f = rp.flat;
+        std::vector<std::pair<int64_t, int64_t>> terms;
+        for (int j = 0; j < f.n_idx; ++j)
+          if (f.ref[i].addr.c[j] && f.range[j] > 1) terms.push_back({f.ref[i].addr.c[j] < 0 ? -f.ref[i].addr.c[j] : f.ref[i].addr.c[j], f.range[j]});
+        std::sort(terms.begin(), terms.end());
+        __int128 span = 0, count = 1;
+        bool injective = true;
+        for (const auto& t : terms) {
+          if ((__int128)t.first <= span) injective = false;
+          span += (__int128)t.first * (t.second - 1);
+          count *= t.second;
+        }
+        if (injective && count > (__int128)written_upper) {
+          delete prog;
+          return fail(STRIPE_ERR_INVALID_DESC, "a statement reads elements of a temporary that no earlier statement writes (at most " +
+                                                   std::to_string((long long)written_upper) + " written, " + std::to_string((long long)count) + " read)");
+        }
+      }
+    }
+  }
+
   // Fusion and scalarisation (Section 2.3): a convolution into a temporary followed by O = relu(T + bias[k]) over
   // the same dense image runs as one kernel whose accumulators are the temporary, which then needs no memory.
   if (prog->stages.size() == 2 && tune_int("fuse", 1)) {

@@ -864,6 +864,12 @@ stripe_status_t make_plan(const FlatBlock& fb, stripe_path_t forced, Plan* plan,
       g.cons_const[q] = c.k;
       for (int t = 0; t < g.n_out; ++t) g.cons_out[q][t] = (int32_t)c.c[out_idx[t]];
       for (int t = 0; t < g.n_red; ++t) g.cons_red[q][t] = (int32_t)c.c[red_idx[t]];
+      // the kernel holds constraint coefficients in 32 bits; flattening multiplies passed coefficients into them
+      for (int j = 0; j < fb.n_idx; ++j)
+        if (c.c[j] > 0x7fffffffLL || c.c[j] < -0x7fffffffLL) {
+          gen_ok = false;
+          gen_why = "a constraint coefficient exceeds 32 bits after substituting passed values";
+        }
     }
     // One lane per output when neighbouring outputs read neighbouring (or the
     // same) input elements; otherwise one wavefront per output with the lanes

@@ -207,3 +207,62 @@ def test_tile_selection_follows_the_cost_model():
     assert "128x128x32" in kernel(W.conv2d_block(4, 28, 28, 128, 128, 3, 3, 1, 1, "bf16", "f32"))
     assert "128x128x32" in kernel(W.conv2d_block(4, 28, 28, 64, 96, 3, 3, 1, 1, "bf16", "f32"))
     assert "256x64x32" in kernel(W.conv2d_block(4, 28, 28, 128, 192, 3, 3, 1, 1, "bf16", "f32"))   # three 64-wide tiles waste nothing
+
+
+def _two_statements(t_access_write, t_access_read, write_constraints=(), write_range=8):
+    """0: T[<t_access_write>] = A[x] * A[x]  (x in 0..write_range-1);   1: O[x] = relu(T[<t_access_read>] + B[x])  (x in 0..7)."""
+    bufs = [W.Buffer("A", "in", "f32", (16,)), W.Buffer("B", "in", "f32", (8,)), W.Buffer("T", "temp", "f32", (16,)),
+            W.Buffer("O", "out", "f32", (8,))]
+    s0 = W.make_level(dict(x=write_range), [(["x"], "assign"), (["x"], "assign"), ([t_access_write], "assign")],
+                      buffers=[bufs[0], bufs[0], W.Buffer("T", "out", "f32", (16,))], constraints=list(write_constraints), intrinsic="mul")
+    s0.parent_refs = [0, 0, 2]
+    s1 = W.make_level(dict(x=8), [([t_access_read], "assign"), (["x"], "assign"), (["x"], "assign")],
+                      buffers=[W.Buffer("T", "in", "f32", (16,)), bufs[1], bufs[3]], intrinsic="add_relu")
+    s1.parent_refs = [2, 1, 3]
+    s0.next = s1
+    return W.make_root(bufs, s0)
+
+
+def test_statement_list_that_reads_unwritten_temporary_elements_is_refused():
+    B.StripeBlock(_two_statements("x", "x")).close()                       # writes T[0..7], reads T[0..7]
+    with pytest.raises(B.StripeError) as e:
+        B.StripeBlock(_two_statements("x", "x", write_range=6))            # writes six elements, reads eight
+    assert e.value.status == 2 and "temporary" in str(e.value)
+    with pytest.raises(B.StripeError) as e:
+        B.StripeBlock(_two_statements("x", "x", write_constraints=["x - 2 >= 0"]))   # T[0], T[1] have no iteration
+    assert e.value.status == 2 and "temporary" in str(e.value)
+
+
+def test_statement_that_reads_its_own_output_through_another_map_is_refused():
+    """Definition 2 rule 2: an element written by one iteration may not be read by another.  T[x] = relu(T[x] + B[x])
+    is a per-element update; T[x] = relu(T[x + 1] + B[x]) is not."""
+    def prog(read_access):
+        bufs = [W.Buffer("A", "in", "f32", (16,)), W.Buffer("B", "in", "f32", (8,)), W.Buffer("T", "temp", "f32", (16,)),
+                W.Buffer("O", "out", "f32", (8,))]
+        s0 = W.make_level(dict(x=16), [(["x"], "assign"), (["x"], "assign"), (["x"], "assign")],
+                          buffers=[bufs[0], bufs[0], W.Buffer("T", "out", "f32", (16,))], intrinsic="mul")
+        s0.parent_refs = [0, 0, 2]
+        s1 = W.make_level(dict(x=8), [([read_access], "assign"), (["x"], "assign"), (["x"], "assign")],
+                          buffers=[W.Buffer("T", "in", "f32", (16,)), bufs[1], W.Buffer("T", "out", "f32", (16,))], intrinsic="add_relu")
+        s1.parent_refs = [2, 1, 2]
+        s2 = W.make_level(dict(x=8), [(["x"], "assign"), (["x"], "assign"), (["x"], "assign")],
+                          buffers=[W.Buffer("T", "in", "f32", (16,)), bufs[1], bufs[3]], intrinsic="add")
+        s2.parent_refs = [2, 1, 3]
+        s0.next, s1.next = s1, s2
+        return W.make_root(bufs, s0)
+    B.StripeBlock(prog("x")).close()
+    with pytest.raises(B.StripeError) as e:
+        B.StripeBlock(prog("x + 1"))
+    assert e.value.status == 2 and "reads the buffer it writes" in str(e.value)
+
+
+def test_constraint_coefficient_beyond_32_bits_is_refused_not_truncated():
+    """A passed value scaled by 2^20 inside a constraint scaled by 2^12: the flattened coefficient is 2^32."""
+    bufs = [W.Buffer("A", "in", "i32", (2, 3)), W.Buffer("O", "out", "i32", (2, 3))]
+    outer = W.make_level(dict(x=2), [(["x", "0"], "assign", (1, 3)), (["x", "0"], "assign", (1, 3))], buffers=bufs)
+    inner = W.make_level(dict(y=3), [(["0", "y"], "assign"), (["0", "y"], "assign")], buffers=bufs, passed=dict(p="1048576*x"),
+                         parent=outer, constraints=["5 - 4096*p - y >= 0"], intrinsic="copy")
+    outer.child = inner
+    with pytest.raises(B.StripeError) as e:
+        B.StripeBlock(W.make_root(bufs, outer))
+    assert e.value.status == 3
