@@ -47,6 +47,11 @@ KIND = {
     "maxpool_f32": ("GB/s", "hbm", "f32"),
     "tiny_conv_f32": ("TFLOP/s", "hbm", "f32"),
     "device_copy": ("GB/s", "hbm", "u8"),     # the plain copy kernel: calibrates traffic counters and the HBM yardstick
+    # streaming yardsticks sized like the max-pooling block (102.8 MB in, 25.7 MB out): read only, write only, 1 : 1, 4 : 1
+    "stream_read": ("GB/s", "hbm", "f32"),
+    "stream_write": ("GB/s", "hbm", "f32"),
+    "stream_1r1w": ("GB/s", "hbm", "f32"),
+    "stream_4r1w": ("GB/s", "hbm", "f32"),
     "library_gemm": ("TFLOP/s", "mfma", "bf16"),  # torch.mm (the vendor BLAS) on the GEMM workload's operands: a yardstick
     # further shapes the kernel families cover (workloads.extra_block)
     "gemm_bf16_4096_bt": ("TFLOP/s", "mfma", "bf16"),
@@ -127,6 +132,44 @@ def bench_copy(args, torch, B):
                                    "kernel_us": round(us, 2)}}), flush=True)
 
 
+def bench_stream(args, torch, B, name):
+    """stripe_device_stream with the pooling block's byte counts over rotating buffers; every grid size is timed and
+    the best one is the yardstick (all of them are listed in config)."""
+    dev = torch.device("cuda:0")
+    n16 = 25690112 // 16                       # vectors per stream = the pooling block's output
+    reads, write = {"stream_read": (4, 0), "stream_write": (0, 1), "stream_1r1w": (1, 1), "stream_4r1w": (4, 1)}[name]
+    nbytes = 16 * n16 * (reads + write)
+    n_sets = args.rotate if args.rotate > 0 else max(2, int(640e6 // nbytes) + 1)
+    sets = [(torch.ones(max(1, reads) * n16 * 4, dtype=torch.float32, device=dev), torch.empty(n16 * 4, dtype=torch.float32, device=dev))
+            for _ in range(n_sets)]
+    stream = torch.cuda.current_stream()
+    results = {}
+    for grid in (512, 1024, 2048, 4096, 8192, 16384):
+        run = lambda i: B.stripe_device_stream(sets[i % n_sets][0].data_ptr(), sets[i % n_sets][1].data_ptr(), n16, reads, write, grid,
+                                               stream.cuda_stream)
+        for i in range(args.warmup):
+            run(i)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        ev0.record(stream)
+        for i in range(args.steps):
+            run(i)
+        ev1.record(stream)
+        torch.cuda.synchronize()
+        results[grid] = ev0.elapsed_time(ev1) / args.steps * 1e3
+    grid = min(results, key=results.get)
+    us = results[grid]
+    gbs = nbytes / us / 1e3
+    print(json.dumps({"metric": "streaming bandwidth (yardstick)", "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5), "higher_is_better": True,
+                      "dtype": "f32", "data": "synthetic",
+                      "config": {"workload": name, "bytes_read": 16 * n16 * reads, "bytes_written": 16 * n16 * write, "buffer_sets": n_sets,
+                                 "best_grid": grid, "us_by_grid": {str(k): round(v, 2) for k, v in results.items()}},
+                      "roofline": {"bound": "hbm", "achieved": round(gbs, 1), "peak": PEAK["hbm_gbs"], "unit": "GB/s",
+                                   "frac": round(gbs / PEAK["hbm_gbs"], 4), "traffic": None, "kernel": "stream_kernel", "kernel_us": round(us, 2)}}),
+          flush=True)
+
+
 def bench_library_gemm(args, torch, W):
     """The vendor library's bf16 x bf16 -> fp32 GEMM on the same seeded operands, same box, same clocks."""
     dev = torch.device("cuda:0")
@@ -195,6 +238,8 @@ def main():
         return bench_copy(args, torch, B)
     if name == "library_gemm":
         return bench_library_gemm(args, torch, W)
+    if name.startswith("stream_"):
+        return bench_stream(args, torch, B, name)
     extra = name in W.EXTRA_NAMES
     root = W.extra_block(name) if extra else W.config_block(name)
     inputs = W.extra_inputs(name) if extra else W.config_inputs(name)

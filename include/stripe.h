@@ -257,6 +257,15 @@ const char* stripe_last_error(void);
  */
 stripe_status_t stripe_device_copy(const void* src, void* dst, size_t n_bytes, void* hip_stream);
 
+/*
+ * Streaming yardsticks with a chosen read : write mix: `reads` input streams (0, 1, 2 or 4) of n_vectors 16-byte
+ * vectors each, laid one after the other from `src`, are added into one output stream of n_vectors vectors at
+ * `dst` (write != 0), or only read (write == 0; dst then points at 4 spare bytes).  Streaming loads and stores, four
+ * independent vectors per lane and trip, `grid` workgroups of 256 lanes.  DEVICE pointers, 16-byte aligned.  They
+ * state what a perfectly regular kernel with the window kernels' 4 : 1 mix reaches on this chip.
+ */
+stripe_status_t stripe_device_stream(const void* src, void* dst, size_t n_vectors, int reads, int write, int grid, void* hip_stream);
+
 /* ------------------------------------------------------------------------
  * Autotiling (paper Section 3.3, Figures 4 and 5): host-only integer code.
  *

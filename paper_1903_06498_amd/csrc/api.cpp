@@ -591,4 +591,14 @@ stripe_status_t stripe_device_copy(const void* src, void* dst, size_t n_bytes, v
   return STRIPE_OK;
 }
 
+stripe_status_t stripe_device_stream(const void* src, void* dst, size_t n_vectors, int reads, int write, int grid, void* hip_stream) {
+  if (!dst || (reads > 0 && !src)) return fail(STRIPE_ERR_NULL, "src or dst is NULL");
+  if ((reads != 0 && reads != 1 && reads != 2 && reads != 4) || (reads == 0 && !write) || (reads == 2 && !write) || grid < 1 || grid > (1 << 20))
+    return fail(STRIPE_ERR_INVALID_DESC, "reads is 0, 1, 2 or 4 (0 and 2 only with write); grid is 1 .. 2^20 workgroups");
+  if (((uintptr_t)src % 16) || ((uintptr_t)dst % 16)) return fail(STRIPE_ERR_MISALIGNED, "stream yardstick needs 16-byte aligned pointers");
+  const hipError_t e = launch_stream(src, dst, n_vectors, reads, write, grid, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(STRIPE_ERR_HIP, std::string("stream launch failed: ") + hipGetErrorString(e));
+  return STRIPE_OK;
+}
+
 }  // extern "C"

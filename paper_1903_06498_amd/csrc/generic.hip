@@ -418,6 +418,60 @@ __global__ __launch_bounds__(256) void copy_kernel(const uint4* __restrict__ src
 }
 }  // namespace
 
+// ---------------------------------------------------------------------------
+// Streaming yardsticks: R input streams folded into one output stream (R = 0: write only; write = 0: read only),
+// 16 bytes per lane, four independent vectors per lane and trip so that 4 * R loads are in flight per lane,
+// streaming (non-temporal) loads and stores, grid chosen by the caller.  They state what a perfectly regular
+// kernel with a given read : write mix reaches on this chip, next to the window kernels.
+// ---------------------------------------------------------------------------
+namespace {
+typedef float y_f32x4 __attribute__((ext_vector_type(4)));
+template <int R, bool WRITE>
+__global__ __launch_bounds__(256) void stream_kernel(const y_f32x4* __restrict__ src, y_f32x4* __restrict__ dst, size_t n16, float* __restrict__ flag) {
+  constexpr int U = 4;
+  const size_t step = (size_t)gridDim.x * 256;
+  y_f32x4 keep = {0.f, 0.f, 0.f, 0.f};
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += step * U) {
+    y_f32x4 v[U][R > 0 ? R : 1];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int r = 0; r < R; ++r) {
+        const size_t at = i + u * step;
+        v[u][r] = at < n16 ? __builtin_nontemporal_load(src + (size_t)r * n16 + at) : keep;
+      }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      y_f32x4 sum = {1.f, 2.f, 3.f, 4.f};
+#pragma unroll
+      for (int r = 0; r < R; ++r) sum = r ? sum + v[u][r] : v[u][0];
+      const size_t at = i + u * step;
+      if (WRITE) {
+        if (at < n16) __builtin_nontemporal_store(sum, dst + at);
+      } else {
+        keep += sum;
+      }
+    }
+  }
+  if (!WRITE && keep.x + keep.y + keep.z + keep.w == 12345.678f) flag[0] = 1.f;   // keeps the loads alive; practically never true
+}
+}  // namespace
+
+hipError_t launch_stream(const void* src, void* dst, size_t n16, int reads, int write, int grid, hipStream_t stream) {
+  if (n16 == 0) return hipSuccess;
+  const dim3 g((unsigned)grid), b(256);
+  const y_f32x4* s = (const y_f32x4*)src;
+  y_f32x4* d = (y_f32x4*)dst;
+  if (reads == 0 && write) hipLaunchKernelGGL((stream_kernel<0, true>), g, b, 0, stream, s, d, n16, (float*)dst);
+  else if (reads == 1 && write) hipLaunchKernelGGL((stream_kernel<1, true>), g, b, 0, stream, s, d, n16, (float*)dst);
+  else if (reads == 2 && write) hipLaunchKernelGGL((stream_kernel<2, true>), g, b, 0, stream, s, d, n16, (float*)dst);
+  else if (reads == 4 && write) hipLaunchKernelGGL((stream_kernel<4, true>), g, b, 0, stream, s, d, n16, (float*)dst);
+  else if (reads == 1 && !write) hipLaunchKernelGGL((stream_kernel<1, false>), g, b, 0, stream, s, d, n16, (float*)dst);
+  else if (reads == 4 && !write) hipLaunchKernelGGL((stream_kernel<4, false>), g, b, 0, stream, s, d, n16, (float*)dst);
+  else return hipErrorInvalidValue;
+  return hipGetLastError();
+}
+
 hipError_t launch_copy(const void* src, void* dst, size_t n_bytes, hipStream_t stream) {
   const size_t n16 = n_bytes / 16;
   if (n16 == 0) return hipSuccess;
