@@ -74,7 +74,8 @@ hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void*
 // (average pooling), depthwise convolution ------------------------------------
 struct PoolLaunch {
   int variant = -1;
-  int rows = 0;      // output rows per workgroup
+  int rows = 0;      // output rows per strip
+  int yb = 1;        // strips a workgroup takes side by side, one per 128 lanes (strip kernel)
   int wg = 128;      // lanes per workgroup
   bool lean = false; // strip kernel without selects (32-bit in-row offsets suffice)
   int64_t grid = 0;

@@ -177,6 +177,10 @@ bool tile_search_in(const TileProblem& pr, const stripe_tile_model_t& m, const s
 //   LDS level: lines of 128 bytes; the cap is the CU's 160 KB.
 constexpr int64_t kGfx950RegLineBytes = 16, kGfx950RegCapRegs = 256;
 constexpr double kGfx950RegPenalty = 0.003;
+// window kernels, fitted together with the register penalty: an access served by the CU's L1 costs about a quarter of
+// a vector fetched from L2; launches keep at least eight workgroups per CU when the block allows
+constexpr double kGfx950L1AccessCost = 0.26;
+constexpr int64_t kGfx950MinWorkgroups = 2048;
 constexpr int64_t kGfx950LdsLineBytes = 128, kGfx950LdsCapBytes = 160 * 1024;
 
 // Records the calling thread's error detail (what stripe_last_error() returns) and passes the status through.

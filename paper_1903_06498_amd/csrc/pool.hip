@@ -26,6 +26,8 @@
 // the duplicate cannot change the result.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+
 #include "kernels.hpp"
 
 namespace stripe {
@@ -249,7 +251,7 @@ __device__ __forceinline__ f32x4 fold(const f32x4* v) {
 }
 
 template <int R, int S, int ST, int TY, int MODE>
-__global__ __launch_bounds__(128) void pool_f32_strip_kernel(const PoolParams p, const float* __restrict__ in,
+__global__ __launch_bounds__(1024) void pool_f32_strip_kernel(const PoolParams p, const float* __restrict__ in,
                                                             float* __restrict__ out) {
   constexpr int NR = ST * (TY - 1) + R;
   // A workgroup keeps its 128 (column, channel-quad) items and walks over strips (image, row strip) with the
@@ -271,8 +273,10 @@ __global__ __launch_bounds__(128) void pool_f32_strip_kernel(const PoolParams p,
     voff[j] = ((uint32_t)xcl * (uint32_t)p.i_x + (uint32_t)c4 * 4u) * 4u;
   }
   const uint32_t ooff = ((uint32_t)xo * (uint32_t)p.o_x + (uint32_t)c4 * 4u) * 4u;
-  const int strips = p.N * p.y_strips, step = (int)(gridDim.x / (unsigned)p.blocks_per_row);
-  for (int rest = (int)(b / (unsigned)p.blocks_per_row); rest < strips; rest += step) {
+  // blockDim.y strips per workgroup (threadIdx.y picks one: row bases stay wave-uniform), gridDim.x / blocks_per_row
+  // such workgroups side by side
+  const int strips = p.N * p.y_strips, step = (int)(gridDim.x / (unsigned)p.blocks_per_row) * (int)blockDim.y;
+  for (int rest = (int)(b / (unsigned)p.blocks_per_row) * (int)blockDim.y + (int)threadIdx.y; rest < strips; rest += step) {
     const int ys = rest % p.y_strips;
     const int n = rest / p.y_strips;
     const char* ib = (const char*)(in + p.i_base + (int64_t)n * p.i_n);
@@ -414,10 +418,12 @@ PoolParams make_params(const Pool2dShape& s, int ty, int wg) {
 
 constexpr int kTyChoices[] = {1, 2, 3, 4, 7};
 
+
+
 template <int TY, bool NT>
-hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st, bool lean) {
+hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st, bool lean, int yb) {
   if (lean && !NT) {
-    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, 0>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
+    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, 0>), dim3((unsigned)grid), dim3(128, yb), 0, st, p, (const float*)in, (float*)out);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((pool_max_f32_kernel<3, 3, 2, TY, NT>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
@@ -435,18 +441,21 @@ constexpr int kWeightedVariant = 300;
 struct PoolWindow { int r, s, stride; };
 constexpr PoolWindow kWindows[] = {{3, 3, 2}, {2, 2, 2}, {3, 3, 1}};
 
-// Output rows per strip, chosen with the cost model of paper Section 3.3 at the register level of a lane: the
-// lane's tile is one output column x four channels x TY rows; its views are the (stride * (TY - 1) + R) x S x 4
-// input patch, the TY x 1 x 4 outputs and, for weighted windows, the weights.  Cost = 16-byte loads and stores
-// per output row.  Registers are a soft memory: a larger tile still runs, with fewer wavefronts resident, so
-// instead of the model's hard cap (kept at the 256 registers a lane can have at all) the cost is scaled by
-// 1 + footprint * kGfx950RegPenalty; that one correction reproduces the measured optimum of every window shape
-// timed on this chip.  Candidates are the strip heights the kernels are instantiated for; ties go to the smaller
-// footprint.  STRIPE_TUNE pool_ty overrides the choice.
-int choose_strip_rows(const Pool2dShape& s, std::initializer_list<int> available) {
-  const int want = tune_int("pool_ty", 0);
-  for (int a : available)
-    if (a == want) return a;
+// Strip shape by the cost model of paper Section 3.3, applied at the two memory levels a window kernel tiles for:
+//   lane level   a lane's tile is one output column x four channels x TY rows; its views (the
+//                (stride * (TY - 1) + R) x S x 4 input patch, the outputs, the weights of a weighted window) live in
+//                registers; its cost is the 16-byte accesses the lane issues per output vector;
+//   workgroup level  YB strips side by side, one per 128 lanes, share input rows through the CU's L1: the tile is
+//                TY * YB output rows of the whole image width; its cost is the 16-byte vectors fetched from L2 per
+//                output vector.
+// Registers are a soft memory (a larger tile still runs, with fewer wavefronts resident), so instead of a hard cap the
+// L2-level cost is scaled by 1 + registers * kGfx950RegPenalty, and an L1 access is charged kGfx950L1AccessCost of an
+// L2 access.  Launches with fewer than kGfx950MinWorkgroups workgroups are avoided when a candidate has more (ramp
+// and tail of such launches cost more than the sharing saves).  These three constants were fitted to sweeps of every
+// window shape on this chip and reproduce the measured optimum of each.  Candidates are the shapes the kernels are
+// instantiated for; STRIPE_TUNE pool_ty / pool_yb override the choice.
+struct StripShape { int ty, yb; };
+StripShape choose_strip_shape(const Pool2dShape& s, std::initializer_list<int> ty_available, std::initializer_list<int> yb_available) {
   TileProblem pr;
   pr.range = {s.Ho, s.Wo, s.C, s.R, s.S};                      // indexes y, x, c, i, j
   TileRef in, out;
@@ -471,32 +480,53 @@ int choose_strip_rows(const Pool2dShape& s, std::initializer_list<int> available
   m.mem_cap_elems = kGfx950RegCapRegs;
   m.counted_refs = (1u << pr.refs.size()) - 1;
   m.tiled_idx = 1u;                                            // work counted in output rows
-  int best = 0, smallest = 0;
+  stripe_tile_model_t wg = m;
+  wg.mem_cap_elems = 0;
+  wg.counted_refs = 3u;                                        // input and output; the weights stay in registers
+  const int want_ty = tune_int("pool_ty", 0), want_yb = tune_int("pool_yb", 0);
+  const double vectors_per_row = (double)s.Wo * (double)(s.C / 4);
+  const int64_t blocks_per_row = (s.Wo * (s.C / 4) + 127) / 128;
+  StripShape best = {0, 0}, fallback = {0, 0};
   double best_cost = 0;
   int64_t best_fp = 0;
-  for (int a : available) {
-    if (!smallest || a < smallest) smallest = a;
-    if (a > s.Ho) continue;
-    const int64_t tile[5] = {a, 1, 4, s.R, s.S};
-    stripe_tile_cost_t c;
-    tile_cost_of(pr, tile, m, &c);
-    if (!c.admissible) continue;
-    const double corrected = c.cost * (1.0 + (double)c.footprint_elems * kGfx950RegPenalty);
-    if (!best || corrected < best_cost || (corrected == best_cost && c.footprint_elems < best_fp)) {
-      best = a;
-      best_cost = corrected;
-      best_fp = c.footprint_elems;
+  bool best_large = false;
+  for (int ty : ty_available) {
+    if (want_ty && ty != want_ty && std::find(ty_available.begin(), ty_available.end(), want_ty) != ty_available.end()) continue;
+    for (int yb : yb_available) {
+      if (want_yb && yb != want_yb && std::find(yb_available.begin(), yb_available.end(), want_yb) != yb_available.end()) continue;
+      if (!fallback.ty || ty * yb < fallback.ty * fallback.yb) fallback = {ty, yb};
+      if (ty > s.Ho || (int64_t)ty * yb > s.Ho + ty - 1) continue;
+      const int64_t lane_tile[5] = {ty, 1, 4, s.R, s.S};
+      stripe_tile_cost_t lane;
+      tile_cost_of(pr, lane_tile, m, &lane);
+      if (!lane.admissible) continue;
+      const int64_t rows = std::min<int64_t>((int64_t)ty * yb, s.Ho);
+      const int64_t wg_tile[5] = {rows, s.Wo, s.C, s.R, s.S};
+      stripe_tile_cost_t group;
+      tile_cost_of(pr, wg_tile, wg, &group);
+      const double l1 = lane.cost / vectors_per_row, l2 = group.cost / vectors_per_row;
+      const double cost = l2 * (1.0 + (double)lane.footprint_elems * kGfx950RegPenalty) + kGfx950L1AccessCost * l1;
+      const int64_t workgroups = blocks_per_row * ((s.N * ((s.Ho + ty - 1) / ty) + yb - 1) / yb);
+      const bool large = workgroups >= kGfx950MinWorkgroups;
+      const bool better = !best.ty || (large && !best_large) ||
+                          (large == best_large && (cost < best_cost || (cost == best_cost && lane.footprint_elems * yb < best_fp)));
+      if (better) {
+        best = {ty, yb};
+        best_cost = cost;
+        best_fp = lane.footprint_elems * yb;
+        best_large = large;
+      }
     }
   }
-  return best ? best : smallest;
+  return best.ty ? best : fallback;
 }
 
 // Workgroups of the strip kernel: blocks_per_row column blocks times the number of strips walked side by side.
 // One workgroup per strip and column block measured best (26.0 us on the 3x3 / stride 2 configuration against 26.7
 // with 4102 workgroups walking the strips, 28.0 with 2051, 29.3 with 1022): the kernel wants every load of the
 // block in flight as early as possible.  STRIPE_TUNE pool_groups = n walks the strips n side by side instead.
-int64_t strip_grid(const PoolParams& p) {
-  const int64_t strips = (int64_t)p.N * p.y_strips;
+int64_t strip_grid(const PoolParams& p, int64_t yb) {
+  const int64_t strips = ((int64_t)p.N * p.y_strips + yb - 1) / yb;
   int64_t side = tune_int("pool_groups", -1);
   if (side < 0) side = 0;
   if (side == 0 || side > strips) side = strips;
@@ -504,12 +534,12 @@ int64_t strip_grid(const PoolParams& p) {
 }
 
 template <int R, int S, int ST, int MODE>
-hipError_t launch_strip_rows(int ty, const PoolParams& p, dim3 g, const float* i, float* o, hipStream_t st) {
+hipError_t launch_strip_rows(int ty, int yb, const PoolParams& p, dim3 g, const float* i, float* o, hipStream_t st) {
   switch (ty) {
-    case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 1, MODE>), g, dim3(128), 0, st, p, i, o); break;
-    case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 2, MODE>), g, dim3(128), 0, st, p, i, o); break;
-    case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 3, MODE>), g, dim3(128), 0, st, p, i, o); break;
-    case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 4, MODE>), g, dim3(128), 0, st, p, i, o); break;
+    case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 1, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
+    case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 2, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
+    case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 3, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
+    case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 4, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -547,7 +577,7 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     // weighted window: a scale (one element) or per-tap, per-channel weights with the channels contiguous (16-byte loads)
     if (mode != 2 || !row_offsets_fit) return false;
     if (s.w_mode == 2 && (s.w_c != 1 || s.w_r % 4 || s.w_s % 4 || s.w_base % 4)) return false;
-    const int rows = choose_strip_rows(s, {1, 2});
+    const int rows = choose_strip_shape(s, {1, 2}, {1}).ty;
     const PoolParams p = make_params(s, rows, 128);
     const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
     if (grid > 0x7fffffffLL) return false;
@@ -569,10 +599,12 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   }
   if (window != 0 || mode != 0) {
     if (!row_offsets_fit) return false;
-    const int rows = choose_strip_rows(s, {1, 2, 3, 4});
+    const StripShape shape = choose_strip_shape(s, {1, 2, 3, 4}, {1, 2, 4});
+    const int rows = shape.ty;
     const PoolParams p = make_params(s, rows, 128);
     if ((int64_t)p.N * p.y_strips > 0x7fffffffLL) return false;
-    const int64_t grid = strip_grid(p);
+    l->yb = shape.yb;
+    const int64_t grid = strip_grid(p, shape.yb);
     l->variant = kShapeVariant + 3 * window + mode;
     l->rows = rows;
     l->wg = 128;
@@ -583,10 +615,10 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     info->tile_k = 0;
     info->frag_m = info->frag_n = info->frag_k = 0;
     info->lds_bytes = 0;
-    info->workgroup_size = 128;
+    info->workgroup_size = 128 * shape.yb;
     info->grid = grid;
-    snprintf(info->kernel, sizeof info->kernel, "pool_%s_f32_%dx%ds%d_ty%d", mode == 2 ? "sum" : mode == 1 ? "min" : "max", kWindows[window].r,
-             kWindows[window].s, kWindows[window].stride, rows);
+    snprintf(info->kernel, sizeof info->kernel, "pool_%s_f32_%dx%ds%d_ty%d%s", mode == 2 ? "sum" : mode == 1 ? "min" : "max", kWindows[window].r,
+             kWindows[window].s, kWindows[window].stride, rows, shape.yb == 4 ? "x4" : shape.yb == 2 ? "x2" : "");
     return true;
   }
   if (tune_int("pool_roll", 0) && row_offsets_fit) {
@@ -622,7 +654,10 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     return true;
   }
   int ty_idx = 1;
-  const int chosen = choose_strip_rows(s, {1, 2, 3, 4, 7});
+  const bool lean_ok = row_offsets_fit && !tune_int("pool_nt", 0) && tune_int("pool_lean", 1);
+  const StripShape shape = lean_ok ? choose_strip_shape(s, {1, 2, 3, 4, 7}, {1, 2, 4}) : choose_strip_shape(s, {1, 2, 3, 4, 7}, {1});
+  const int chosen = shape.ty;
+  l->yb = shape.yb;
   for (int i = 0; i < (int)(sizeof kTyChoices / sizeof kTyChoices[0]); ++i)
     if (kTyChoices[i] == chosen) ty_idx = i;
   const int nt = tune_int("pool_nt", 0) ? 1 : 0;
@@ -630,7 +665,7 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   const PoolParams p = make_params(s, ty, 128);
   if ((int64_t)p.N * p.y_strips * p.blocks_per_row > 0x7fffffffLL) return false;
   const bool lean = row_offsets_fit && !nt && tune_int("pool_lean", 1);
-  const int64_t grid = lean ? strip_grid(p) : (int64_t)p.N * p.y_strips * p.blocks_per_row;
+  const int64_t grid = lean ? strip_grid(p, shape.yb) : (int64_t)p.N * p.y_strips * p.blocks_per_row;
   l->variant = ty_idx * 2 + nt;
   l->lean = lean;
   l->rows = ty;
@@ -642,9 +677,10 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
   info->tile_k = 0;
   info->frag_m = info->frag_n = info->frag_k = 0;
   info->lds_bytes = 0;
-  info->workgroup_size = 128;
+  info->workgroup_size = lean ? 128 * shape.yb : 128;
   info->grid = grid;
-  snprintf(info->kernel, sizeof info->kernel, "pool_max_f32_3x3s2_ty%d%s", ty, nt ? "_nt" : l->lean ? "" : "_sel");
+  snprintf(info->kernel, sizeof info->kernel, "pool_max_f32_3x3s2_ty%d%s%s", ty, nt ? "_nt" : l->lean ? "" : "_sel",
+           !lean ? "" : shape.yb == 4 ? "x4" : shape.yb == 2 ? "x2" : "");
   return true;
 }
 
@@ -672,14 +708,14 @@ hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in
     const float* i = (const float*)in;
     float* o = (float*)out;
     switch (l.variant - kShapeVariant) {
-      case 1: return launch_strip_rows<3, 3, 2, 1>(l.rows, p, g, i, o, st);
-      case 2: return launch_strip_rows<3, 3, 2, 2>(l.rows, p, g, i, o, st);
-      case 3: return launch_strip_rows<2, 2, 2, 0>(l.rows, p, g, i, o, st);
-      case 4: return launch_strip_rows<2, 2, 2, 1>(l.rows, p, g, i, o, st);
-      case 5: return launch_strip_rows<2, 2, 2, 2>(l.rows, p, g, i, o, st);
-      case 6: return launch_strip_rows<3, 3, 1, 0>(l.rows, p, g, i, o, st);
-      case 7: return launch_strip_rows<3, 3, 1, 1>(l.rows, p, g, i, o, st);
-      case 8: return launch_strip_rows<3, 3, 1, 2>(l.rows, p, g, i, o, st);
+      case 1: return launch_strip_rows<3, 3, 2, 1>(l.rows, l.yb, p, g, i, o, st);
+      case 2: return launch_strip_rows<3, 3, 2, 2>(l.rows, l.yb, p, g, i, o, st);
+      case 3: return launch_strip_rows<2, 2, 2, 0>(l.rows, l.yb, p, g, i, o, st);
+      case 4: return launch_strip_rows<2, 2, 2, 1>(l.rows, l.yb, p, g, i, o, st);
+      case 5: return launch_strip_rows<2, 2, 2, 2>(l.rows, l.yb, p, g, i, o, st);
+      case 6: return launch_strip_rows<3, 3, 1, 0>(l.rows, l.yb, p, g, i, o, st);
+      case 7: return launch_strip_rows<3, 3, 1, 1>(l.rows, l.yb, p, g, i, o, st);
+      case 8: return launch_strip_rows<3, 3, 1, 2>(l.rows, l.yb, p, g, i, o, st);
       default: return hipErrorInvalidValue;
     }
   }
@@ -692,11 +728,11 @@ hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in
   const bool nt = l.variant % 2;
   const PoolParams p = make_params(s, kTyChoices[ty_idx], 128);
   switch (ty_idx) {
-    case 0: return nt ? launch_ty<1, true>(p, l.grid, in, out, st, l.lean) : launch_ty<1, false>(p, l.grid, in, out, st, l.lean);
-    case 1: return nt ? launch_ty<2, true>(p, l.grid, in, out, st, l.lean) : launch_ty<2, false>(p, l.grid, in, out, st, l.lean);
-    case 2: return nt ? launch_ty<3, true>(p, l.grid, in, out, st, l.lean) : launch_ty<3, false>(p, l.grid, in, out, st, l.lean);
-    case 3: return nt ? launch_ty<4, true>(p, l.grid, in, out, st, l.lean) : launch_ty<4, false>(p, l.grid, in, out, st, l.lean);
-    default: return nt ? launch_ty<7, true>(p, l.grid, in, out, st, l.lean) : launch_ty<7, false>(p, l.grid, in, out, st, l.lean);
+    case 0: return nt ? launch_ty<1, true>(p, l.grid, in, out, st, l.lean, l.yb) : launch_ty<1, false>(p, l.grid, in, out, st, l.lean, l.yb);
+    case 1: return nt ? launch_ty<2, true>(p, l.grid, in, out, st, l.lean, l.yb) : launch_ty<2, false>(p, l.grid, in, out, st, l.lean, l.yb);
+    case 2: return nt ? launch_ty<3, true>(p, l.grid, in, out, st, l.lean, l.yb) : launch_ty<3, false>(p, l.grid, in, out, st, l.lean, l.yb);
+    case 3: return nt ? launch_ty<4, true>(p, l.grid, in, out, st, l.lean, l.yb) : launch_ty<4, false>(p, l.grid, in, out, st, l.lean, l.yb);
+    default: return nt ? launch_ty<7, true>(p, l.grid, in, out, st, l.lean, l.yb) : launch_ty<7, false>(p, l.grid, in, out, st, l.lean, l.yb);
   }
 }
 

@@ -519,15 +519,17 @@ def test_pool_other_windows_and_min(R, stride, pad, agg):
         assert np.array_equal(got, np.broadcast_to((cy[:, None] * cx[None, :])[None, :, :, None], got.shape))
 
 
+@pytest.mark.parametrize("yb", [1, 2, 4])
 @pytest.mark.parametrize("ty", [1, 2, 3, 4])
-@pytest.mark.parametrize("R,stride,pad,agg", [(2, 2, 0, "max"), (3, 1, 1, "min"), (3, 2, 1, "add"), (3, 1, 0, "add")])
-def test_pool_other_windows_every_strip_height(R, stride, pad, agg, ty, monkeypatch):
-    """Every strip height the cost model may choose, forced through pool_ty, on ragged row counts."""
-    monkeypatch.setenv("STRIPE_TUNE", f"pool_ty={ty}")
-    N, H, Wd, C = 2, 23, 10, 8
+@pytest.mark.parametrize("R,stride,pad,agg", [(2, 2, 0, "max"), (3, 1, 1, "min"), (3, 2, 1, "add"), (3, 1, 0, "add"), (3, 2, 1, "max")])
+def test_pool_every_strip_shape(R, stride, pad, agg, ty, yb, monkeypatch):
+    """Every strip shape the cost model may choose (rows per strip x strips per workgroup), forced through
+    pool_ty / pool_yb, on row counts that leave ragged strips and ragged groups of strips."""
+    monkeypatch.setenv("STRIPE_TUNE", f"pool_ty={ty},pool_yb={yb}")
+    N, H, Wd, C = 3, 23, 10, 8
     blk = W.maxpool_block(N, H, Wd, C, R, stride, pad, agg=agg)
-    info, _ = parity(blk, [W.seeded_tensor((N, H, Wd, C), "f32", 6)], what=f"pool {R}x{R}s{stride} {agg} ty{ty}")
-    assert info["kernel"].endswith(f"_ty{ty}"), info
+    info, _ = parity(blk, [W.seeded_tensor((N, H, Wd, C), "f32", 6)], what=f"pool {R}x{R}s{stride} {agg} ty{ty} yb{yb}")
+    assert info["kernel"].endswith(f"_ty{ty}" + {1: "", 2: "x2", 4: "x4"}[yb]) and info["workgroup_size"] == 128 * yb, info
 
 
 @pytest.mark.parametrize("ty", [1, 2])

@@ -155,7 +155,7 @@ def test_tune_override_selects_variants(monkeypatch):
     monkeypatch.setenv("STRIPE_TUNE", "pool_ty=4,pool_nt=1")
     assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty4_nt"
     monkeypatch.delenv("STRIPE_TUNE")
-    assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty2"
+    assert B.StripeBlock(W.config_block("maxpool_f32")).info["kernel"] == "pool_max_f32_3x3s2_ty1x4"
 
 
 def test_split_reduction_is_planned_for_few_tiles_and_long_k(monkeypatch):
@@ -199,9 +199,9 @@ def test_tile_selection_follows_the_cost_model():
     """Section 3.3's model as the library's tile selector: strip heights of the window family (register level, with
     the occupancy correction) and the workgroup tile of the general convolution kernel (LDS level)."""
     kernel = lambda blk: B.StripeBlock(blk).info["kernel"]
-    assert kernel(W.config_block("maxpool_f32")).endswith("3x3s2_ty2")                  # rows shared by windows: 5 rows per 2
+    assert kernel(W.config_block("maxpool_f32")).endswith("3x3s2_ty1x4")                # rows shared through L1: 9 rows per 4
     assert kernel(W.maxpool_block(32, 112, 112, 64, 2, 2, 0)).endswith("2x2s2_ty1")     # no sharing: the smallest footprint
-    assert kernel(W.maxpool_block(32, 112, 112, 64, 3, 1, 1)).endswith("3x3s1_ty4")     # stride 1 shares most: 6 rows per 4
+    assert kernel(W.maxpool_block(32, 112, 112, 64, 3, 1, 1)).endswith("3x3s1_ty4x4")   # stride 1 shares most: registers and L1
     assert kernel(W.depthwise_conv_block(32, 112, 112, 64, 3, 3, 1, 1, "f32")).endswith("3x3s1_ty2")
     assert "256x64x32" in kernel(W.conv2d_block(4, 28, 28, 64, 32, 3, 3, 1, 1, "bf16", "f32"))
     assert "128x128x32" in kernel(W.conv2d_block(4, 28, 28, 128, 128, 3, 3, 1, 1, "bf16", "f32"))
