@@ -322,6 +322,77 @@ __global__ __launch_bounds__(1024) void pool_f32_strip_kernel(const PoolParams p
   }
 }
 
+// ---------------------------------------------------------------------------
+// LDS-staged strip kernel.  The workgroup's input patch -- every input row of its blockDim.y output rows, the
+// columns its 128 (column, channel-quad) items reach -- goes global -> LDS once, by LDS-direct 16-byte loads (no
+// staging registers, no LDS-store instructions); every lane then takes its R x S taps from LDS.  Each input vector
+// is requested from L1 / L2 once per workgroup instead of once per tap that uses it, which is what separates the
+// register kernel above from a plain 4 : 1 stream.  Taps outside the image: max / min stage the clamped pixel (a
+// duplicate of a tap the window holds anyway), sums stage zeros.  One output row per 128 lanes (threadIdx.y).
+// ---------------------------------------------------------------------------
+__device__ __attribute__((aligned(16))) unsigned char pool_zero_chunk[16];
+
+// M0 (the wave-uniform LDS destination of an LDS-direct load) is written here and nowhere else in this kernel.
+__device__ __forceinline__ void pool_load_lds16(const void* src, unsigned lds_off) {
+  const unsigned uniform_off = __builtin_amdgcn_readfirstlane(lds_off);
+  asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform_off) : "memory", "m0");
+}
+
+template <int R, int S, int ST, int MODE>
+__global__ __launch_bounds__(1024) void pool_f32_lds_kernel(const PoolParams p, const float* __restrict__ in, float* __restrict__ out) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char patch[];
+  const unsigned b = blockIdx.x;
+  const int bx = b % p.blocks_per_row;
+  const int rest = b / p.blocks_per_row;
+  const int yg = rest % p.y_strips;               // group of blockDim.y output rows
+  const int n = rest / p.y_strips;
+  const int rows_out = (int)blockDim.y;
+  const int t = threadIdx.y * 128 + threadIdx.x, lanes = 128 * rows_out;
+  // columns of the patch: the items bx*128 .. bx*128+127 of the row (clipped) cover output columns xo_first .. xo_last
+  const int item_first = bx * 128, item_last = min(item_first + 127, p.items - 1);
+  const int xo_first = item_first / p.C4, xo_last = item_last / p.C4;
+  const int x0 = xo_first * ST - p.pad_x;                              // first input column (may be -1: clamped)
+  const int pw = (xo_last - xo_first) * ST + S;                        // patch width in pixels
+  const int pwv = pw * p.C4;                                           // ... in 16-byte vectors
+  const int y0 = yg * rows_out * ST - p.pad_y;                         // first input row
+  const int nr = ST * (rows_out - 1) + R;                              // patch rows
+  const int total = nr * pwv;
+  const char* ib = (const char*)(in + p.i_base + (int64_t)n * p.i_n);
+  // ---- stage: vector g of the patch = (row g / pwv, pixel (g % pwv) / C4, channel quad (g % pwv) % C4); every
+  // wavefront issues whole loads, lanes past the end fetch a dummy vector into the slack behind the patch
+  for (int g0 = 0; g0 < total; g0 += lanes) {
+    const int g = g0 + t;
+    const int gc = g < total ? g : 0;
+    const int row = gc / pwv, col = gc - row * pwv;
+    const int px = col / p.C4, c4 = col - px * p.C4;
+    const int y = y0 + row, x = x0 + px;
+    const int yc = y < 0 ? 0 : (y >= p.H ? p.H - 1 : y), xc = x < 0 ? 0 : (x >= p.W ? p.W - 1 : x);
+    const void* src = ib + ((int64_t)yc * p.i_y + (int64_t)xc * p.i_x + c4 * 4) * 4;
+    if (MODE == 2 && (y != yc || x != xc)) src = pool_zero_chunk;
+    pool_load_lds16(src, (unsigned)((g0 + (t & ~63)) * 16));
+  }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  // ---- reduce: lane = one (column, channel quad) item of output row threadIdx.y
+  const int item = item_first + threadIdx.x;
+  const int yo = yg * rows_out + threadIdx.y;
+  if (item >= p.items || yo >= p.Ho) return;
+  const int c4 = item % p.C4, xo = item / p.C4;
+  const unsigned char* lp = patch + ((threadIdx.y * ST) * pwv + (xo - xo_first) * ST * p.C4 + c4) * 16;
+  f32x4 hm[R];
+#pragma unroll
+  for (int r = 0; r < R; ++r) {
+    f32x4 v[S];
+#pragma unroll
+    for (int j = 0; j < S; ++j) v[j] = *(const f32x4*)(lp + (r * pwv + j * p.C4) * 16);
+    hm[r] = fold<S, MODE>(v);
+  }
+  const f32x4 res = fold<R, MODE>(hm);
+  float* op = out + p.o_base + (int64_t)n * p.o_n + (int64_t)yo * p.o_y + (int64_t)xo * p.o_x + c4 * 4;
+  if (p.stream_stores) __builtin_nontemporal_store(res, (f32x4*)op);
+  else *(f32x4*)op = res;
+}
+
 // Weighted windows (sum aggregation of products, no reduction over channels): every tap of the window is multiplied
 // by a weight before it enters the sum.  WMODE 1: one scalar for all taps -- average pooling written as
 // O += I * scale with the scale in a one-element buffer; the kernel sums the in-range taps and scales once.
@@ -438,6 +509,8 @@ constexpr int kRollVariant = 100;
 constexpr int kShapeVariant = 200;
 // weighted windows: variant = kWeightedVariant + 2*shape + (0: one scale, 1: per tap and channel)
 constexpr int kWeightedVariant = 300;
+// LDS-staged kernel: variant = kLdsVariant + 3*shape + mode, rows per workgroup in PoolLaunch::rows
+constexpr int kLdsVariant = 400;
 struct PoolWindow { int r, s, stride; };
 constexpr PoolWindow kWindows[] = {{3, 3, 2}, {2, 2, 2}, {3, 3, 1}};
 
@@ -533,6 +606,21 @@ int64_t strip_grid(const PoolParams& p, int64_t yb) {
   return side * p.blocks_per_row;
 }
 
+// LDS bytes of the staged kernel's patch for `rows` output rows per workgroup, slack for whole loads included
+int64_t lds_patch_bytes(const Pool2dShape& s, int rows) {
+  const int64_t c4 = s.C / 4, st = s.stride_x;
+  const int64_t px_out = std::min<int64_t>((127 + c4 - 1) / c4 + 1, s.Wo);   // output columns 128 consecutive items can touch
+  const int64_t pw = (px_out - 1) * st + s.S, nr = s.stride_y * (rows - 1) + s.R, lanes = 128 * rows;
+  const int64_t vectors = (nr * pw * c4 + lanes - 1) / lanes * lanes;
+  return vectors * 16;
+}
+
+template <int R, int S, int ST, int MODE>
+hipError_t launch_lds_rows(int rows, int lds_bytes, const PoolParams& p, dim3 g, const float* i, float* o, hipStream_t st) {
+  hipLaunchKernelGGL((pool_f32_lds_kernel<R, S, ST, MODE>), g, dim3(128, rows), lds_bytes, st, p, i, o);
+  return hipGetLastError();
+}
+
 template <int R, int S, int ST, int MODE>
 hipError_t launch_strip_rows(int ty, int yb, const PoolParams& p, dim3 g, const float* i, float* o, hipStream_t st) {
   switch (ty) {
@@ -595,6 +683,28 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     info->grid = grid;
     snprintf(info->kernel, sizeof info->kernel, "%s_f32_%dx%ds%d_ty%d", s.w_mode == 2 ? "depthwise" : "pool_scaled_sum", kWindows[window].r,
              kWindows[window].s, kWindows[window].stride, rows);
+    return true;
+  }
+  // LDS-staged kernel (STRIPE_TUNE pool_lds = rows per workgroup, 1..8)
+  if (const int lds_rows = tune_int("pool_lds", 0); lds_rows >= 1 && lds_rows <= 8 && row_offsets_fit && lds_patch_bytes(s, lds_rows) <= 64 * 1024) {
+    const PoolParams p = make_params(s, lds_rows, 128);
+    const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
+    if (grid > 0x7fffffffLL) return false;
+    l->variant = kLdsVariant + 3 * window + mode;
+    l->rows = lds_rows;
+    l->yb = lds_rows;
+    l->wg = 128;
+    l->grid = grid;
+    info->path = STRIPE_PATH_POOL;
+    info->tile_m = lds_rows;
+    info->tile_n = 128;
+    info->tile_k = 0;
+    info->frag_m = info->frag_n = info->frag_k = 0;
+    info->lds_bytes = (int)lds_patch_bytes(s, lds_rows);
+    info->workgroup_size = 128 * lds_rows;
+    info->grid = grid;
+    snprintf(info->kernel, sizeof info->kernel, "pool_%s_f32_%dx%ds%d_lds%d", mode == 2 ? "sum" : mode == 1 ? "min" : "max", kWindows[window].r,
+             kWindows[window].s, kWindows[window].stride, lds_rows);
     return true;
   }
   if (window != 0 || mode != 0) {
@@ -686,6 +796,25 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
 
 hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in, const void* weights, void* out, hipStream_t st) {
   if (((uintptr_t)in % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
+  if (l.variant >= kLdsVariant) {
+    const PoolParams p = make_params(s, l.rows, 128);
+    const dim3 g((unsigned)l.grid);
+    const float* i = (const float*)in;
+    float* o = (float*)out;
+    const int lds = (int)lds_patch_bytes(s, l.rows);
+    switch (l.variant - kLdsVariant) {
+      case 0: return launch_lds_rows<3, 3, 2, 0>(l.rows, lds, p, g, i, o, st);
+      case 1: return launch_lds_rows<3, 3, 2, 1>(l.rows, lds, p, g, i, o, st);
+      case 2: return launch_lds_rows<3, 3, 2, 2>(l.rows, lds, p, g, i, o, st);
+      case 3: return launch_lds_rows<2, 2, 2, 0>(l.rows, lds, p, g, i, o, st);
+      case 4: return launch_lds_rows<2, 2, 2, 1>(l.rows, lds, p, g, i, o, st);
+      case 5: return launch_lds_rows<2, 2, 2, 2>(l.rows, lds, p, g, i, o, st);
+      case 6: return launch_lds_rows<3, 3, 1, 0>(l.rows, lds, p, g, i, o, st);
+      case 7: return launch_lds_rows<3, 3, 1, 1>(l.rows, lds, p, g, i, o, st);
+      case 8: return launch_lds_rows<3, 3, 1, 2>(l.rows, lds, p, g, i, o, st);
+      default: return hipErrorInvalidValue;
+    }
+  }
   if (l.variant >= kWeightedVariant) {
     if (!weights || ((uintptr_t)weights % (s.w_mode == 2 ? 16 : 4))) return hipErrorInvalidValue;
     const PoolParams p = make_params(s, l.rows, 128);

@@ -532,6 +532,21 @@ def test_pool_every_strip_shape(R, stride, pad, agg, ty, yb, monkeypatch):
     assert info["kernel"].endswith(f"_ty{ty}" + {1: "", 2: "x2", 4: "x4"}[yb]) and info["workgroup_size"] == 128 * yb, info
 
 
+@pytest.mark.parametrize("rows", [1, 2, 4, 8])
+@pytest.mark.parametrize("R,stride,pad,agg,C", [(2, 2, 0, "max", 8), (3, 1, 1, "min", 24), (3, 2, 1, "add", 8), (3, 2, 1, "max", 64), (3, 1, 0, "add", 4),
+                                                (3, 2, 1, "max", 256)])
+def test_pool_lds_staged_kernel(R, stride, pad, agg, C, rows, monkeypatch):
+    """The LDS-staged strip kernel (input patch global -> LDS once, taps from LDS): every window, aggregation and
+    number of rows per workgroup, channel counts that put several pixels, one pixel or a fraction of a pixel into a
+    workgroup's 128 items, ragged row groups, clamped / zeroed taps on all four borders."""
+    monkeypatch.setenv("STRIPE_TUNE", f"pool_lds={rows}")
+    N, H, Wd = 2, 23, 21
+    blk = W.maxpool_block(N, H, Wd, C, R, stride, pad, agg=agg)
+    info, _ = parity(blk, [W.seeded_tensor((N, H, Wd, C), "f32", 6)], what=f"pool lds {R}x{R}s{stride} {agg} C{C} rows{rows}")
+    staged = info["kernel"].endswith(f"_lds{rows}") and info["lds_bytes"] > 0
+    assert staged or (rows == 8 and C >= 64), info          # a patch beyond 64 KB of LDS falls back to the register kernel
+
+
 @pytest.mark.parametrize("ty", [1, 2])
 @pytest.mark.parametrize("kind", ["depthwise_s1", "depthwise_s2", "avg_2x2"])
 def test_weighted_windows_every_strip_height(kind, ty, monkeypatch):
