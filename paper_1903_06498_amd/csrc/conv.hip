@@ -213,6 +213,15 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   constexpr int PR = W4_ROWS + 2;
   // bytes of the patch image rounded up to whole 1 KB load blocks (DMA); the output transposition buffers follow
   const int patch_bytes = DMA ? ((PR * PW * 128 + 1023) & ~1023) : PR * PW * 128;
+  // The fused epilogue's bias values are fetched first, so that they are the oldest entries of the load queue: the
+  // hand-placed s_waitcnt of the LDS-direct staging below count the younger loads still in flight.
+  f32x4s bias4 = {0.f, 0.f, 0.f, 0.f};               // store phase, fp32 form: the lane's four channels
+  f32x4s bias8a = {0.f, 0.f, 0.f, 0.f}, bias8b = {0.f, 0.f, 0.f, 0.f};   // bf16 form: the lane's eight channels
+  if constexpr (EPI == 1 || (EPI == 2 && TEAMS != 2)) bias4 = *(const f32x4s*)(bias + (wave & 1) * 32 + (lane & 7) * 4);
+  if constexpr (EPI == 2 && TEAMS == 2) {
+    bias8a = *(const f32x4s*)(bias + (wave & 1) * 32 + (lane & 3) * 8);
+    bias8b = *(const f32x4s*)(bias + (wave & 1) * 32 + (lane & 3) * 8 + 4);
+  }
   if constexpr (DMA) {
     // ---- staging by LDS-direct loads: 9 patch blocks, then 3 filter blocks per slice, per wavefront (18 loads)
     const int sub = lane >> 3, slot = lane & 7;
@@ -313,8 +322,6 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   const int sp = lane >> 3, sc = lane & 7;          // store phase: pixel sp (+8j) of the fragment, channel quad sc
   constexpr int OB = EPI == 2 ? 2 : 4;               // bytes per output element
   char* og = (char*)O + (p.o_base + (int64_t)n * p.o_n + nh * 32 + sc * 4) * OB;
-  f32x4s bias4 = {0.f, 0.f, 0.f, 0.f};               // the lane's four channels in the store phase
-  if constexpr (EPI != 0) bias4 = *(const f32x4s*)(bias + nh * 32 + sc * 4);
   unsigned char* wbase[4];     // write address of accumulator elements v = 0..3 (pixel 4*fh + v); + 1 KB per further 8 pixels
 #pragma unroll
   for (int v = 0; v < 4; ++v) {
@@ -328,6 +335,20 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
     const int x = mh * 32 + sp + 8 * j;
     ovalid[j] = x < p.W;
     ooff[j] = (uint32_t)((x < p.W ? x : 0) * (int)p.o_x) * (unsigned)OB;
+  }
+  // bf16 output: a pixel's 32 channels are 64 bytes, so four lanes (eight channels, 16 bytes each) cover a pixel and
+  // one store instruction covers the 16 pixels of a round -- half as many store instructions as the fp32 form
+  const int sp2 = lane >> 2, sc2 = lane & 3;
+  char* og2 = (char*)O + (p.o_base + (int64_t)n * p.o_n + nh * 32 + sc2 * 8) * 2;
+  uint32_t ooff2[2] = {0u, 0u};
+  bool ovalid2[2] = {false, false};
+  if constexpr (EPI == 2 && TEAMS == 2) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int x = mh * 32 + 16 * h + sp2;
+      ovalid2[h] = x < p.W;
+      ooff2[h] = (uint32_t)((x < p.W ? x : 0) * (int)p.o_x) * 2u;
+    }
   }
 
   // Output rows are finished in three groups (3 + 2 + 2 rows) rather than all at the end, so that the stores
@@ -394,6 +415,27 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
 #pragma unroll
           for (int v = h * 4 * G; v < (h + 1) * 4 * G; ++v) *(float*)(wbase[v % 4] + (v / 4 - h * G) * 1024) = acc[r][v];
           __builtin_amdgcn_wave_barrier();
+          if constexpr (EPI == 2 && TEAMS == 2) {
+            // round h holds pixels 16h .. 16h+15 of the fragment: lane = (pixel sp2, channels 8*sc2 .. +7)
+            f32x4s va = *(const f32x4s*)(ot + sp2 * 128 + (((2 * sc2) ^ (sp2 & 7)) << 4));
+            f32x4s vb = *(const f32x4s*)(ot + sp2 * 128 + (((2 * sc2 + 1) ^ (sp2 & 7)) << 4));
+            va.x = __builtin_fmaxf(va.x + bias8a.x, 0.f);
+            va.y = __builtin_fmaxf(va.y + bias8a.y, 0.f);
+            va.z = __builtin_fmaxf(va.z + bias8a.z, 0.f);
+            va.w = __builtin_fmaxf(va.w + bias8a.w, 0.f);
+            vb.x = __builtin_fmaxf(vb.x + bias8b.x, 0.f);
+            vb.y = __builtin_fmaxf(vb.y + bias8b.y, 0.f);
+            vb.z = __builtin_fmaxf(vb.z + bias8b.z, 0.f);
+            vb.w = __builtin_fmaxf(vb.w + bias8b.w, 0.f);
+            typedef float f32x2d __attribute__((ext_vector_type(2)));
+            typedef __bf16 bf16x2d __attribute__((ext_vector_type(2)));
+            const bf16x2d q0 = __builtin_convertvector((f32x2d){va.x, va.y}, bf16x2d), q1 = __builtin_convertvector((f32x2d){va.z, va.w}, bf16x2d);
+            const bf16x2d q2 = __builtin_convertvector((f32x2d){vb.x, vb.y}, bf16x2d), q3 = __builtin_convertvector((f32x2d){vb.z, vb.w}, bf16x2d);
+            const u32x4 packed = {__builtin_bit_cast(unsigned, q0), __builtin_bit_cast(unsigned, q1), __builtin_bit_cast(unsigned, q2),
+                                  __builtin_bit_cast(unsigned, q3)};
+            char* orow2 = og2 + (int64_t)y * p.o_y * 2;
+            if (ovalid2[h]) __builtin_nontemporal_store(packed, (u32x4*)(orow2 + ooff2[h]));
+          } else
 #pragma unroll
           for (int j = 0; j < G; ++j) {
             const int pixel = sp + 8 * j;            // within the round; (pixel & 7) == sp either way
