@@ -400,12 +400,14 @@ __global__ __launch_bounds__(1024) void pool_f32_lds_kernel(const PoolParams p, 
 // of its four channels in registers.  Same lane mapping and load pattern as the strip kernel above; taps outside
 // the image are read at a clamped address and replaced by zeros (exact for a sum).
 template <int R, int S, int ST, int TY, int WMODE>
-__global__ __launch_bounds__(128) void window_weighted_f32_kernel(const PoolParams p, const float* __restrict__ in,
+__global__ __launch_bounds__(512) void window_weighted_f32_kernel(const PoolParams p, const float* __restrict__ in,
                                                                  const float* __restrict__ wgt, float* __restrict__ out) {
   constexpr int NR = ST * (TY - 1) + R;
   const unsigned b = p.xcd_remap ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
   const int bx = b % p.blocks_per_row;
-  const int rest = b / p.blocks_per_row;
+  // blockDim.y strips side by side per workgroup, one per 128 lanes (they share input rows through L1)
+  const int rest = (int)(b / (unsigned)p.blocks_per_row) * (int)blockDim.y + (int)threadIdx.y;
+  if (rest >= p.N * p.y_strips) return;
   const int ys = rest % p.y_strips;
   const int n = rest / p.y_strips;
   const int item = bx * 128 + threadIdx.x;
@@ -542,12 +544,7 @@ StripShape choose_strip_shape(const Pool2dShape& s, std::initializer_list<int> t
     w.coeff = {0, 0, 0, 1, 0, /**/ 0, 0, 0, 0, 1, /**/ 0, 0, 1, 0, 0};
     w.stride = {s.w_r, s.w_s, 1};
     pr.refs.push_back(w);
-  } else if (s.w_mode == 1) {
-    TileRef w;
-    w.coeff = {0, 0, 0, 0, 0};
-    w.stride = {1};
-    pr.refs.push_back(w);
-  }
+  }                                                            // (a scale is one scalar register: not a view of the lane's tile)
   stripe_tile_model_t m = {};
   m.line_elems = kGfx950RegLineBytes / 4;
   m.mem_cap_elems = kGfx950RegCapRegs;
@@ -634,10 +631,10 @@ hipError_t launch_strip_rows(int ty, int yb, const PoolParams& p, dim3 g, const 
 }
 
 template <int R, int S, int ST, int WMODE>
-hipError_t launch_weighted_rows(int ty, const PoolParams& p, dim3 g, const float* i, const float* w, float* o, hipStream_t st) {
+hipError_t launch_weighted_rows(int ty, int yb, const PoolParams& p, dim3 g, const float* i, const float* w, float* o, hipStream_t st) {
   switch (ty) {
-    case 1: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 1, WMODE>), g, dim3(128), 0, st, p, i, w, o); break;
-    case 2: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 2, WMODE>), g, dim3(128), 0, st, p, i, w, o); break;
+    case 1: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 1, WMODE>), g, dim3(128, yb), 0, st, p, i, w, o); break;
+    case 2: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 2, WMODE>), g, dim3(128, yb), 0, st, p, i, w, o); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -665,10 +662,14 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     // weighted window: a scale (one element) or per-tap, per-channel weights with the channels contiguous (16-byte loads)
     if (mode != 2 || !row_offsets_fit) return false;
     if (s.w_mode == 2 && (s.w_c != 1 || s.w_r % 4 || s.w_s % 4 || s.w_base % 4)) return false;
-    const int rows = choose_strip_shape(s, {1, 2}, {1}).ty;
+    // per-tap weights: strips side by side measured slower (3x3 stride 1, two rows per strip: 59.6 us alone, 66.8 us
+    // four side by side), so only the scaled sum takes them
+    const StripShape shape = s.w_mode == 2 ? choose_strip_shape(s, {1, 2}, {1}) : choose_strip_shape(s, {1, 2}, {1, 2, 4});
+    const int rows = shape.ty;
     const PoolParams p = make_params(s, rows, 128);
-    const int64_t grid = (int64_t)p.N * p.y_strips * p.blocks_per_row;
-    if (grid > 0x7fffffffLL) return false;
+    if ((int64_t)p.N * p.y_strips * p.blocks_per_row > 0x7fffffffLL) return false;
+    l->yb = shape.yb;
+    const int64_t grid = (((int64_t)p.N * p.y_strips + shape.yb - 1) / shape.yb) * p.blocks_per_row;
     l->variant = kWeightedVariant + 2 * window + (s.w_mode - 1);
     l->rows = rows;
     l->wg = 128;
@@ -679,10 +680,10 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     info->tile_k = 0;
     info->frag_m = info->frag_n = info->frag_k = 0;
     info->lds_bytes = 0;
-    info->workgroup_size = 128;
+    info->workgroup_size = 128 * shape.yb;
     info->grid = grid;
-    snprintf(info->kernel, sizeof info->kernel, "%s_f32_%dx%ds%d_ty%d", s.w_mode == 2 ? "depthwise" : "pool_scaled_sum", kWindows[window].r,
-             kWindows[window].s, kWindows[window].stride, rows);
+    snprintf(info->kernel, sizeof info->kernel, "%s_f32_%dx%ds%d_ty%d%s", s.w_mode == 2 ? "depthwise" : "pool_scaled_sum", kWindows[window].r,
+             kWindows[window].s, kWindows[window].stride, rows, shape.yb == 4 ? "x4" : shape.yb == 2 ? "x2" : "");
     return true;
   }
   // LDS-staged kernel (STRIPE_TUNE pool_lds = rows per workgroup, 1..8)
@@ -822,12 +823,12 @@ hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in
     const float *i = (const float*)in, *w = (const float*)weights;
     float* o = (float*)out;
     switch (l.variant - kWeightedVariant) {
-      case 0: return launch_weighted_rows<3, 3, 2, 1>(l.rows, p, g, i, w, o, st);
-      case 1: return launch_weighted_rows<3, 3, 2, 2>(l.rows, p, g, i, w, o, st);
-      case 2: return launch_weighted_rows<2, 2, 2, 1>(l.rows, p, g, i, w, o, st);
-      case 3: return launch_weighted_rows<2, 2, 2, 2>(l.rows, p, g, i, w, o, st);
-      case 4: return launch_weighted_rows<3, 3, 1, 1>(l.rows, p, g, i, w, o, st);
-      case 5: return launch_weighted_rows<3, 3, 1, 2>(l.rows, p, g, i, w, o, st);
+      case 0: return launch_weighted_rows<3, 3, 2, 1>(l.rows, l.yb, p, g, i, w, o, st);
+      case 1: return launch_weighted_rows<3, 3, 2, 2>(l.rows, l.yb, p, g, i, w, o, st);
+      case 2: return launch_weighted_rows<2, 2, 2, 1>(l.rows, l.yb, p, g, i, w, o, st);
+      case 3: return launch_weighted_rows<2, 2, 2, 2>(l.rows, l.yb, p, g, i, w, o, st);
+      case 4: return launch_weighted_rows<3, 3, 1, 1>(l.rows, l.yb, p, g, i, w, o, st);
+      case 5: return launch_weighted_rows<3, 3, 1, 2>(l.rows, l.yb, p, g, i, w, o, st);
       default: return hipErrorInvalidValue;
     }
   }
