@@ -18,16 +18,20 @@
 // with the 16-byte chunks XOR-swizzled by (row>>1)&7, so the 16-byte fragment
 // reads of 32 consecutive pixels / filter rows are bank-conflict free.
 //
-// Two kernels, in this order in the file:
+// Three kernels, in this order in the file:
 //   conv3x3_bf16_kernel     one wavefront per output row (2 x 2 fragments), staged through registers;
 //                           the fallback for widths whose buffers leave no room for the second kernel's;
 //   conv3x3_bf16_w4_kernel  the default: wavefront = (pixel half, channel half), rows taken in groups so that
 //                           pixel fragments are shared between filter rows and finished rows are stored while
 //                           others are computed; one or two teams of four wavefronts; staging through registers
-//                           or by LDS-direct loads that the first row group meets on the way.
+//                           or by LDS-direct loads that the first row group meets on the way;
+//   conv3x3_bf16_ks_kernel  an alternative with the same footprint: the filter in registers, rows walked from top to
+//                           bottom with the image still arriving, the reduction split over two teams.  Measured level
+//                           with the row-group kernel, kept selectable (conv_ks=1) and tested.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "kernels.hpp"
 
@@ -479,6 +483,233 @@ __global__ __launch_bounds__(256 * TEAMS, 1) void conv3x3_bf16_w4_kernel(const C
   }
 }
 
+template <int... Is, class Fn>
+__device__ __forceinline__ void conv_static_for(std::integer_sequence<int, Is...>, Fn&& fn) {
+  (fn(std::integral_constant<int, Is>{}), ...);
+}
+
+// ---------------------------------------------------------------------------
+// Rolling rows with the reduction split over two teams.  Wavefront = (team,
+// pixel half, channel half); a team takes one half of the 64 input channels,
+// so a wavefront keeps 18 filter fragments (9 taps x 2 K steps) in registers,
+// walks ALL nine input rows of the strip from top to bottom and holds partial
+// sums of its 32 pixels x 32 channels.  Every wavefront executes the same
+// instruction stream, which makes three kinds of overlap a matter of placing
+// instructions in that stream (it is unrolled at compile time):
+//   * image rows are requested (LDS-direct) a few rows ahead of their use,
+//     the later ones from inside the compute phase, so the matrix cores start
+//     once the filter and the first row have landed instead of after the
+//     whole patch;
+//   * a finished output row is handed over one input row later: each
+//     wavefront keeps the partial sums of half of the fragment's pixels and
+//     passes the other half to its partner team through LDS (two 16-byte
+//     writes per lane, in the accumulator's own lane layout);
+//   * one input row after that it adds the partner's half to its own and
+//     stores: in the accumulator layout 32 lanes hold the 32 channels of one
+//     pixel, i.e. one whole 128-byte line per pixel and store instruction.
+// One workgroup barrier per input row orders all of this (arrival of rows,
+// hand-over buffers), two buffers per wavefront alternate between rows.
+// ---------------------------------------------------------------------------
+template <int EPI>
+__global__ __launch_bounds__(512, 1) void conv3x3_bf16_ks_kernel(const ConvParams p, const uint16_t* __restrict__ I,
+                                                                 const uint16_t* __restrict__ F, void* __restrict__ O,
+                                                                 const float* __restrict__ bias) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
+  unsigned char* lf = lds;                          // the filter image; afterwards the hand-over buffers
+  unsigned char* lp = lds + C_FILTER_BYTES;         // the patch
+  const int t = threadIdx.x, lane = t & 63, wave = __builtin_amdgcn_readfirstlane(t >> 6);
+
+  const int n = blockIdx.x / p.strips_per_image;
+  const int y0 = (blockIdx.x - n * p.strips_per_image) * W4_ROWS;
+  const int PW = p.W + 2;
+  constexpr int PR = W4_ROWS + 2;
+  const int patch_bytes = (PR * PW * 128 + 1023) & ~1023;
+  const int kh = wave >> 2, mh = (wave >> 1) & 1, nh = wave & 1;
+  const int fr = lane & 31, fh = lane >> 5;
+  // the bias values first: the oldest entries of the load queue, the hand-placed waits below count younger loads
+  f32x4s bias4 = {0.f, 0.f, 0.f, 0.f}, bias4b = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (EPI == 1) bias4 = *(const f32x4s*)(bias + nh * 32 + (lane & 7) * 4);
+  if constexpr (EPI == 2) {
+    bias4 = *(const f32x4s*)(bias + nh * 32 + (lane & 3) * 8);
+    bias4b = *(const f32x4s*)(bias + nh * 32 + (lane & 3) * 8 + 4);
+  }
+
+  // ---- staging by LDS-direct loads: 9 filter blocks per wavefront, then the patch in 9 blocks per wavefront;
+  // block e of a wavefront covers LDS pixels 8 (wave + 8e) .. +7, so input row q lies within blocks e <= q
+  const int sub = lane >> 3, slot = lane & 7;
+  const char* ig = (const char*)(I + p.i_base + (int64_t)n * p.i_n);
+  const int n_blocks = patch_bytes >> 10;
+  auto load_patch = [&](int e) {
+    const int b = wave + 8 * e;
+    const int pix = b * 8 + sub;
+    const int r = (int)__umulhi((unsigned)pix, (unsigned)p.pad_), col = pix - r * PW;   // pad_ carries ceil(2^32 / PW)
+    const int y = y0 - 1 + r, x = col - 1;
+    const int c = slot ^ ((pix >> 1) & 7);
+    const bool inside = r < PR && y >= 0 && y < p.H && x >= 0 && x < p.W;
+    const void* src = inside ? (const void*)(ig + (uint32_t)(y * (int)p.i_y + x * (int)p.i_x + c * 8) * 2u) : (const void*)conv_zero_chunk;
+    // a wavefront issues nine loads whatever the width (the waits count them); blocks past the patch land behind it
+    const unsigned dst = C_FILTER_BYTES + (b < n_blocks ? b * 1024 : patch_bytes + wave * 1024);
+    c_load_lds16(b < n_blocks ? src : (const void*)conv_zero_chunk, dst);
+  };
+  {
+    const char* fgb = (const char*)(F + p.f_base);
+#pragma unroll
+    for (int tap = 0; tap < C_TAPS; ++tap) {
+      const int row = tap * C_CO + wave * 8 + sub;     // filter row (tap, k)
+      const int c = slot ^ ((row >> 1) & 7);
+      c_load_lds16(fgb + (row * C_CI + c * 8) * 2, (tap * C_CO + wave * 8) * 128);
+    }
+    load_patch(0);
+    load_patch(1);
+    load_patch(2);
+    asm volatile("s_waitcnt vmcnt(3)" ::: "memory");   // this wavefront's filter blocks
+    __syncthreads();                                    // everybody's
+  }
+
+  // ---- the filter fragments of this channel half and K half, LDS -> registers
+  bf16x8 b[C_TAPS][2];
+  {
+    const unsigned b_base = (unsigned)((nh * 32 + fr) * 128 + ((fh ^ ((fr >> 1) & 7)) << 4)) ^ (unsigned)(kh << 6);
+#pragma unroll
+    for (int tap = 0; tap < C_TAPS; ++tap)
+#pragma unroll
+      for (int s = 0; s < 2; ++s) b[tap][s] = *(const bf16x8*)(lf + tap * (C_CO * 128) + (b_base ^ (unsigned)(s << 5)));
+  }
+  load_patch(3);
+  asm volatile("s_waitcnt vmcnt(3)" ::: "memory");     // block 0 of this wavefront: input row 0
+  __syncthreads();
+
+  const int xcl = mh * 32 + fr < p.W ? mh * 32 + fr : p.W - 1;   // columns beyond W are computed on a clamped pixel, never stored
+  // hand-over buffers: 2 per wavefront, 4 KB each = one fragment as [pixel][32 channels], 16-byte slots swizzled by
+  // the pixel.  Accumulator element v of lane l is pixel 8*(v/4) + 4*(l>>5) + v%4 of the fragment, channel l&31.
+  unsigned char* const outbox = lf + wave * 8192;
+  const unsigned char* const inbox = lf + (wave ^ 4) * 8192;
+  unsigned wofs[4];            // element v goes to wofs[v % 4] + 1024 * (v / 4)
+#pragma unroll
+  for (int v = 0; v < 4; ++v) {
+    const int pixel = 4 * fh + v;
+    wofs[v] = (unsigned)(pixel * 128 + ((((fr >> 2) ^ pixel) << 4) | ((fr & 3) << 2)));
+  }
+  // a team finishes half of the fragment's pixels.  fp32 output: pixels 16 kh + 8 j + sp for j = 0, 1 with lane =
+  // (pixel sp, channel quad sc), 16 bytes per lane.  bf16 output: a pixel's 32 channels are 64 bytes, so lane =
+  // (pixel sp of 16, eight channels sc): two 16-byte slots per buffer in, 16 bytes out, one store for the 16 pixels.
+  const int sp = EPI == 2 ? lane >> 2 : lane >> 3, sc = EPI == 2 ? lane & 3 : lane & 7;
+  const unsigned rofs = EPI == 2 ? (unsigned)((16 * kh + sp) * 128 + (((2 * sc) ^ (sp & 7)) << 4))
+                                 : (unsigned)((16 * kh + sp) * 128 + ((sc ^ sp) << 4));     // + 1024 j
+  const unsigned rofs_b = (unsigned)((16 * kh + sp) * 128 + (((2 * sc + 1) ^ (sp & 7)) << 4));   // bf16: the second slot
+  const int xs = mh * 32 + 16 * kh + sp;                                                  // + 8 j
+  constexpr int OB = EPI == 2 ? 2 : 4;
+  char* const og = (char*)O + (p.o_base + (int64_t)n * p.o_n + nh * 32 + sc * (EPI == 2 ? 8 : 4) + (int64_t)xs * p.o_x) * OB;
+
+  constexpr int STEPS = PR * 6;                       // step = q * 6 + tj * 2 + s
+  f32x16 acc[4];                                      // output row r accumulates in acc[r & 3]
+  bf16x8 a[3];                                        // pixel fragments, requested two steps ahead
+  auto read_a = [&](int step) -> bf16x8 {             // step: a constant at every call
+    const int q = step / 6, tj = (step % 6) >> 1, s = step & 1;
+    const int pix = q * PW + xcl + tj;
+    const unsigned base = (unsigned)(pix * 128 + ((fh ^ ((pix >> 1) & 7)) << 4)) ^ (unsigned)(kh << 6);
+    return *(const bf16x8*)(lp + (base ^ (unsigned)(s << 5)));
+  };
+  // hand-over of output row r (its partial sums are complete): the whole fragment into this wavefront's buffer
+  auto hand_over = [&](auto r_tag) {
+    constexpr int r = decltype(r_tag)::value;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) *(float*)(outbox + (r & 1) * 4096 + wofs[v % 4] + (v / 4) * 1024) = acc[r & 3][v];
+  };
+  // both teams' partial sums of this team's pixels: fetched in one step, added, finished and stored (16 bytes per
+  // lane, a pixel's 128 bytes per 8 lanes) in the next, so that the LDS latency passes behind matrix instructions
+  f32x4s mine[2], theirs[2];
+  auto fetch_row = [&](auto r_tag) {
+    constexpr int r = decltype(r_tag)::value;
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const unsigned o = (r & 1) * 4096 + (EPI == 2 ? (j ? rofs_b : rofs) : rofs + j * 1024);
+      mine[j] = *(const f32x4s*)(outbox + o);
+      theirs[j] = *(const f32x4s*)(inbox + o);
+    }
+  };
+  auto finish_row = [&](auto r_tag) {
+    constexpr int r = decltype(r_tag)::value;
+    const int y = y0 + r;
+    f32x4s v[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      v[j] = (f32x4s){mine[j].x + theirs[j].x, mine[j].y + theirs[j].y, mine[j].z + theirs[j].z, mine[j].w + theirs[j].w};
+      if constexpr (EPI != 0) {
+        const f32x4s bj = (EPI == 2 && j == 1) ? bias4b : bias4;
+        v[j].x = __builtin_fmaxf(v[j].x + bj.x, 0.f);   // relu; a NaN becomes 0
+        v[j].y = __builtin_fmaxf(v[j].y + bj.y, 0.f);
+        v[j].z = __builtin_fmaxf(v[j].z + bj.z, 0.f);
+        v[j].w = __builtin_fmaxf(v[j].w + bj.w, 0.f);
+      }
+    }
+    char* orow = og + (int64_t)y * p.o_y * OB;
+    if constexpr (EPI == 2) {
+      // fp32 -> bf16, round to nearest even, two values per conversion instruction
+      typedef float f32x2c __attribute__((ext_vector_type(2)));
+      typedef __bf16 bf16x2c __attribute__((ext_vector_type(2)));
+      const bf16x2c q0 = __builtin_convertvector((f32x2c){v[0].x, v[0].y}, bf16x2c), q1 = __builtin_convertvector((f32x2c){v[0].z, v[0].w}, bf16x2c);
+      const bf16x2c q2 = __builtin_convertvector((f32x2c){v[1].x, v[1].y}, bf16x2c), q3 = __builtin_convertvector((f32x2c){v[1].z, v[1].w}, bf16x2c);
+      const u32x4 packed = {__builtin_bit_cast(unsigned, q0), __builtin_bit_cast(unsigned, q1), __builtin_bit_cast(unsigned, q2),
+                            __builtin_bit_cast(unsigned, q3)};
+      if (y < p.H && xs < p.W) __builtin_nontemporal_store(packed, (u32x4*)orow);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+        if (y < p.H && xs + 8 * j < p.W) __builtin_nontemporal_store(v[j], (f32x4s*)(orow + (int64_t)(8 * j) * p.o_x * OB));
+    }
+  };
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+  // The two teams' wavefronts share SIMDs pairwise (wavefront w and w + 4), and a wavefront issues in order: while
+  // it hands a row over or stores one it feeds no matrix instructions.  The teams therefore do these chores at
+  // different steps of an input row (team 0 early, team 1 late), so that one of the two always has matrix work.
+  auto run = [&](auto team_tag) {
+    constexpr int TEAM = decltype(team_tag)::value;
+    constexpr int K_FETCH = TEAM ? 2 : 0, K_FINISH = TEAM ? 5 : 1, K_HAND = TEAM ? 3 : 2;
+    a[0] = read_a(0);
+    a[1] = read_a(1);
+    conv_static_for(std::make_integer_sequence<int, STEPS>{}, [&](auto step_tag) {
+      constexpr int step = decltype(step_tag)::value;
+      constexpr int q = step / 6, k = step % 6, tj = k >> 1, s = k & 1;
+      __builtin_amdgcn_sched_barrier(0);
+      if constexpr (k == 4) {
+        // the next input row must have landed (everybody's blocks), the hand-over buffers change roles
+        if constexpr (q == 0) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");   // blocks 2, 3, 4 may be in flight
+        if constexpr (q == 1) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");   // blocks 3 .. 6
+        if constexpr (q == 2) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");   // blocks 4 .. 8
+        if constexpr (q == 3) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // all of them, before the first store is issued
+        __syncthreads();
+      }
+      if constexpr (step + 2 < STEPS) a[(step + 2) % 3] = read_a(step + 2);
+      if constexpr (q - 2 >= 0 && q - 2 < W4_ROWS) acc[(q - 2) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[step % 3], b[6 + tj][s], acc[(q - 2) & 3], 0, 0, 0);
+      if constexpr (q - 1 >= 0 && q - 1 < W4_ROWS) acc[(q - 1) & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[step % 3], b[3 + tj][s], acc[(q - 1) & 3], 0, 0, 0);
+      if constexpr (q < W4_ROWS) acc[q & 3] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[step % 3], b[tj][s], k == 0 ? zero16 : acc[q & 3], 0, 0, 0);
+      // the later patch blocks, requested from inside the compute phase
+      if constexpr (q == 0 && k == 1) load_patch(4);
+      if constexpr (q == 1 && k == 1) load_patch(5);
+      if constexpr (q == 1 && k == 2) load_patch(6);
+      if constexpr (q == 2 && k == 1) load_patch(7);
+      if constexpr (q == 2 && k == 2) load_patch(8);
+      // output row q-4 was handed over during the previous input row (a barrier ago)
+      if constexpr (k == K_FETCH && q >= 4) fetch_row(std::integral_constant<int, q - 4>{});
+      if constexpr (k == K_FINISH && q >= 4) finish_row(std::integral_constant<int, q - 4>{});
+      // output row q-3 met its last input row (q-1) in the previous six steps; handed over before this row's barrier
+      if constexpr (k == K_HAND && q >= 3) hand_over(std::integral_constant<int, q - 3>{});
+      __builtin_amdgcn_sched_barrier(0);
+    });
+    // the last rows: 5 was handed over during input row 8; 6 is complete only now
+    fetch_row(std::integral_constant<int, 5>{});
+    hand_over(std::integral_constant<int, 6>{});
+    finish_row(std::integral_constant<int, 5>{});
+    __syncthreads();
+    fetch_row(std::integral_constant<int, 6>{});
+    finish_row(std::integral_constant<int, 6>{});
+  };
+  if (kh == 0) run(std::integral_constant<int, 0>{});
+  else run(std::integral_constant<int, 1>{});
+}
+
 constexpr int W4_LDS_EXTRA = 4 * 4096;   // per-wavefront output transposition buffers
 
 constexpr int kConvW4Variant = 200;
@@ -539,7 +770,9 @@ static bool conv3x3_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, st
   if (tune_int("conv_w4", 1) && offsets_fit && w4_lds <= 160 * 1024 && (c.W + 2) * 8 <= 512) {
     const int64_t grid = c.N * ((c.Ho + W4_ROWS - 1) / W4_ROWS);
     if (grid > 0x7fffffffLL) return false;
-    l->variant = kConvW4Variant + (w4_dma ? 3 : w4_teams);
+    // 1: the rolling-row kernel whose teams split the reduction (measured level with the row-group kernel)
+    const bool ks = w4_dma && tune_int("conv_ks", 0) != 0;
+    l->variant = kConvW4Variant + (ks ? 4 : w4_dma ? 3 : w4_teams);
     l->grid = grid;
     info->path = STRIPE_PATH_MFMA_CONV;
     info->tile_m = W4_ROWS * (int)c.W;
@@ -549,7 +782,8 @@ static bool conv3x3_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, st
     info->lds_bytes = w4_lds;
     info->workgroup_size = 256 * w4_teams;
     info->grid = grid;
-    snprintf(info->kernel, sizeof info->kernel, "conv3x3_bf16_c64k64_strip7_w%d%s_mfma32x32x16", 4 * w4_teams, w4_dma ? "_dma" : "");
+    snprintf(info->kernel, sizeof info->kernel, "conv3x3_bf16_c64k64_strip7_w%d%s_mfma32x32x16", 4 * w4_teams,
+             ks ? "_ksplit" : w4_dma ? "_dma" : "");
     return true;
   }
   const int rows = rows_per_strip(c);
@@ -574,7 +808,7 @@ static bool conv3x3_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, st
 
 bool conv_can_fuse_bias_relu(const Conv2dShape& c, const ConvLaunch& l) {
   // the LDS-direct row-group kernel, writing a dense [n][y][x][k] image (the fused statement's output shares its layout)
-  return l.variant == kConvW4Variant + 3 && c.o_x == C_CO && (c.H == 1 || c.o_y == c.W * C_CO) && (c.N == 1 || c.o_n == c.H * c.W * C_CO) &&
+  return (l.variant == kConvW4Variant + 3 || l.variant == kConvW4Variant + 4) && c.o_x == C_CO && (c.H == 1 || c.o_y == c.W * C_CO) && (c.N == 1 || c.o_n == c.H * c.W * C_CO) &&
          c.o_base == 0;
 }
 
@@ -597,14 +831,15 @@ static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, con
   if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
   if (l.variant > kConvW4Variant) {
-    const int mode = l.variant - kConvW4Variant;   // 1: four wavefronts, 2: eight, 3: eight with LDS-direct staging
+    const int mode = l.variant - kConvW4Variant;   // 1: four wavefronts, 2: eight, 3: eight with LDS-direct staging, 4: rolling rows with the reduction split over the teams
     ConvParams pp = make_params(c, W4_ROWS);
     const uint32_t pw = (uint32_t)c.W + 2;
     pp.pad_ = (int32_t)(uint32_t)((((uint64_t)1 << 32) + pw - 1) / pw);   // reciprocal of the patch width, for the LDS-direct staging
     const int patch = (W4_ROWS + 2) * ((int)c.W + 2) * 128;
-    const int lds_w4 = C_FILTER_BYTES + (mode == 3 ? ((patch + 1023) & ~1023) : patch) + W4_LDS_EXTRA;
+    const int lds_w4 = C_FILTER_BYTES + (mode >= 3 ? ((patch + 1023) & ~1023) : patch) + W4_LDS_EXTRA;
     typedef void (*kern_t)(const ConvParams, const uint16_t*, const uint16_t*, void*, const float*);
-    const kern_t fn = (mode == 3 && epi == 1) ? (kern_t)conv3x3_bf16_w4_kernel<2, true, 1>
+    const kern_t fn = mode == 4 ? (epi == 1 ? (kern_t)conv3x3_bf16_ks_kernel<1> : epi == 2 ? (kern_t)conv3x3_bf16_ks_kernel<2> : (kern_t)conv3x3_bf16_ks_kernel<0>)
+                    : (mode == 3 && epi == 1) ? (kern_t)conv3x3_bf16_w4_kernel<2, true, 1>
                     : (mode == 3 && epi == 2) ? (kern_t)conv3x3_bf16_w4_kernel<2, true, 2>
                     : mode == 3 ? (kern_t)conv3x3_bf16_w4_kernel<2, true> : mode == 2 ? (kern_t)conv3x3_bf16_w4_kernel<2, false>
                                                                                       : (kern_t)conv3x3_bf16_w4_kernel<1, false>;
@@ -637,3 +872,4 @@ static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, con
 }
 
 }  // namespace stripe
+

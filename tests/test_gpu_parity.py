@@ -377,16 +377,18 @@ def test_two_statement_program_small(shape, in_dt, out_dt):
     assert " ; " in info["kernel"], info["kernel"]
 
 
-@pytest.mark.parametrize("fuse", [1, 0])
+@pytest.mark.parametrize("fuse", [1, 2, 0])
 @pytest.mark.parametrize("out_dt", ["bf16", "f32"])
 @pytest.mark.parametrize("N,H,Wd", [(2, 10, 13), (1, 7, 56), (2, 15, 31)])
 def test_fused_convolution_bias_relu(N, H, Wd, out_dt, fuse, monkeypatch):
     """3x3, 64 -> 64 channels: the planner fuses the two statements into the matrix-core convolution kernel with a
     bias + relu epilogue (the temporary stays in the accumulators); with fuse=0 the same program runs as two
-    launches through a real temporary.  Both against the oracle's serial evaluation."""
-    monkeypatch.setenv("STRIPE_TUNE", f"fuse={fuse}")
+    launches through a real temporary; fuse=2 is the fused form on the rolling-row kernel.  All against the oracle's
+    serial evaluation."""
+    monkeypatch.setenv("STRIPE_TUNE", f"fuse={min(fuse, 1)},conv_ks={int(fuse == 2)}")
     info = program_parity(N, H, Wd, 64, 64, 3, 1, 1, "bf16", out_dt)
     if fuse:
+        assert {1: "_dma_", 2: "_ksplit_"}[fuse] in info["kernel"], info["kernel"]
         assert info["kernel"].endswith("+bias_relu" + ("_bf16" if out_dt == "bf16" else "")) and info["path_name"] == "mfma_conv", info["kernel"]
     else:
         assert " ; " in info["kernel"], info["kernel"]
@@ -841,29 +843,35 @@ def test_gemm_config_full_size():
 
 
 # ------------------------------------------------------------------ convolution path (matrix cores)
-@pytest.mark.parametrize("w4", [3, 2, 1, 0])
+def conv_tune(w4):
+    """STRIPE_TUNE string of one 3x3 kernel: 4 = rolling rows with the reduction split over the teams, 3 = row groups
+    with LDS-direct staging (the default), 2 / 1 = row groups with register staging and two teams of wavefronts / one,
+    0 = wavefront per row."""
+    return f"conv_w4={min(w4, 1)},conv_w4_teams={min(max(w4, 1), 2)},conv_dma={int(w4 >= 3)},conv_ks={int(w4 == 4)}"
+
+
+@pytest.mark.parametrize("w4", [4, 3, 2, 1, 0])
 @pytest.mark.parametrize("N,H,Wd", [(2, 10, 13), (1, 7, 56), (3, 20, 64), (1, 2, 2), (2, 9, 33), (1, 15, 31), (2, 11, 58), (1, 8, 62)])
 def test_conv_mfma_bf16_small(N, H, Wd, w4, monkeypatch):
     """3x3, 64 -> 64 channels, 'same' padding: ragged strips, both pixel fragments, halo on all four sides;
-    the row-group kernel with LDS-direct staging (3, the default), with register staging and two teams of wavefronts
-    (2) or one (1), and the wavefront-per-row kernel (0)."""
-    monkeypatch.setenv("STRIPE_TUNE", f"conv_w4={min(w4, 1)},conv_w4_teams={min(max(w4, 1), 2)},conv_dma={int(w4 == 3)}")
+    every kernel of the shape (see conv_tune)."""
+    monkeypatch.setenv("STRIPE_TUNE", conv_tune(w4))
     blk = W.conv2d_block(N, H, Wd, 64, 64, 3, 3, 1, 1, "bf16", "f32")
     ins = [W.seeded_tensor((N, H, Wd, 64), "bf16", 0), W.seeded_tensor((3, 3, 64, 64), "bf16", 1)]
     info, score = parity(blk, ins, what=f"conv mfma {N}x{H}x{Wd}")
     say(f"conv mfma {N}x{H}x{Wd}: {info['kernel']} err/bound {score:.3f}")
     patch = 9 * (Wd + 2) * 128
-    if w4 == 3:
+    if w4 >= 3:
         patch = (patch + 1023) // 1024 * 1024                    # whole 1 KB load blocks
     fits = 73728 + patch + 16384 <= 160 * 1024                   # filter + haloed strip + store buffers in LDS
-    want = (f"_w{4 * min(w4, 2)}_" + ("dma_" if w4 == 3 else "mfma")) if (w4 and fits) else "_strip7_mfma"
+    want = (f"_w{4 * min(w4, 2)}_" + ("ksplit_" if w4 == 4 else "dma_" if w4 == 3 else "mfma")) if (w4 and fits) else "_strip7_mfma"
     assert info["path_name"] == "mfma_conv" and want in info["kernel"], info
 
 
-@pytest.mark.parametrize("w4", [3, 2, 1, 0])
+@pytest.mark.parametrize("w4", [4, 3, 2, 1, 0])
 def test_conv_mfma_position_sensitive(w4, monkeypatch):
     """Delta input: the output is the (flipped) filter patch, exactly -- catches any mix-up of taps, pixels or channels."""
-    monkeypatch.setenv("STRIPE_TUNE", f"conv_w4={min(w4, 1)},conv_w4_teams={min(max(w4, 1), 2)},conv_dma={int(w4 == 3)}")
+    monkeypatch.setenv("STRIPE_TUNE", conv_tune(w4))
     N, H, Wd = 1, 9, 40
     blk = W.conv2d_block(N, H, Wd, 64, 64, 3, 3, 1, 1, "bf16", "f32")
     f = W.seeded_tensor((3, 3, 64, 64), "bf16", 1)
