@@ -79,6 +79,7 @@ KIND = {
     "transposed_conv_f32": ("TFLOP/s", "alu", "f32"),
     "resnet_conv_bias_relu_bf16": ("TFLOP/s", "hbm", "bf16"),   # two statements fused into one kernel, bf16 output
     "resnet_conv_bias_relu_f32": ("TFLOP/s", "hbm", "bf16"),
+    "conv3x3_bias_relu_bf16_128to128": ("TFLOP/s", "mfma", "bf16"),   # the same fusion on the general convolution kernel
 }
 
 

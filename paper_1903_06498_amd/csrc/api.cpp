@@ -252,7 +252,7 @@ stripe_status_t create_program(const stripe_block_desc_t* root, stripe_path_t pa
       // the second statement as its address maps see it: one merged pixel index and the channel index
       std::vector<int64_t> rng, ct, cbias, co;
       address_form(e, 2, &rng, &ct, &cbias, &co);
-      const int64_t pixels = c.conv.N * c.conv.H * c.conv.W;
+      const int64_t pixels = c.conv.N * c.conv.Ho * c.conv.Wo;
       ok = rng.size() == 2;
       if (ok) {
         const int k = (rng[0] == c.conv.Co && cbias[0] == 1) ? 0 : 1, px = 1 - k;

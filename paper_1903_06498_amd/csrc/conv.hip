@@ -807,9 +807,26 @@ static bool conv3x3_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, st
 }
 
 bool conv_can_fuse_bias_relu(const Conv2dShape& c, const ConvLaunch& l) {
-  // the LDS-direct row-group kernel, writing a dense [n][y][x][k] image (the fused statement's output shares its layout)
-  return (l.variant == kConvW4Variant + 3 || l.variant == kConvW4Variant + 4) && c.o_x == C_CO && (c.H == 1 || c.o_y == c.W * C_CO) && (c.N == 1 || c.o_n == c.H * c.W * C_CO) &&
-         c.o_base == 0;
+  // the fused statement's output shares the layout of the temporary: a dense [n][y][x][k] image
+  const bool dense = c.o_x == c.Co && (c.Ho == 1 || c.o_y == c.Wo * c.Co) && (c.N == 1 || c.o_n == c.Ho * c.Wo * c.Co) && c.o_base == 0;
+  if (!dense) return false;
+  if (l.variant == kConvW4Variant + 3 || l.variant == kConvW4Variant + 4) return true;   // the LDS-direct 3x3 kernels
+  if (l.variant >= kConvIgemmVariant && l.in_dtype == STRIPE_BF16 && c.Co % 4 == 0) {
+    // the general kernel leaves a pixel none of whose taps lies inside the image unwritten: with such a pixel the
+    // temporary would hold an undefined element, and the two statements stay apart
+    for (int64_t y = 0; y < c.Ho; ++y) {
+      bool any = false;
+      for (int64_t i = 0; i < c.R && !any; ++i) any = y * c.stride_y - c.pad_y + i * c.dil_y >= 0 && y * c.stride_y - c.pad_y + i * c.dil_y < c.H;
+      if (!any) return false;
+    }
+    for (int64_t x = 0; x < c.Wo; ++x) {
+      bool any = false;
+      for (int64_t j = 0; j < c.S && !any; ++j) any = x * c.stride_x - c.pad_x + j * c.dil_x >= 0 && x * c.stride_x - c.pad_x + j * c.dil_x < c.W;
+      if (!any) return false;
+    }
+    return true;
+  }
+  return false;
 }
 
 static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias,
@@ -827,7 +844,7 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
 
 static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias,
                                   int epi, hipStream_t st) {
-  if (l.variant >= kConvIgemmVariant) return launch_conv_igemm(c, l, l.in_dtype, false, in, flt, out, st);
+  if (l.variant >= kConvIgemmVariant) return launch_conv_igemm(c, l, l.in_dtype, epi == 2, in, flt, out, epi ? bias : nullptr, st);
   if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;
   if (l.variant > kConvW4Variant) {

@@ -42,6 +42,8 @@ struct IgemmParams {
   int32_t chunks;                 // 64-byte channel chunks per tap
   int32_t k_tiles;                // R * S * chunks
   int32_t out_bf16;               // float blocks: round the result to bf16 on store
+  int32_t epi;                    // 1: the fused form of a following statement O = relu(T + bias[k]) (float blocks)
+  int32_t vec_out;                // output strides, base and pointer allow one store per four channels
 };
 
 // Lanes whose tap lies outside the image fetch these 16 zero bytes instead.
@@ -84,7 +86,8 @@ __device__ __forceinline__ void g_wait_loads() {
 // them (TN rows, same layout); an LDS-direct load fills one 1 KB block = 16 rows.
 template <int TN, bool I8>
 __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p, const unsigned char* __restrict__ I,
-                                                            const unsigned char* __restrict__ F, void* __restrict__ O) {
+                                                            const unsigned char* __restrict__ F, void* __restrict__ O,
+                                                            const float* __restrict__ bias) {
   constexpr int TM = TN == 128 ? 128 : 256;
   constexpr int WN = TN / 32;                 // wavefronts side by side along the channels
   constexpr int LA = TM / 128;                // 1 KB A blocks per wavefront and K tile
@@ -219,8 +222,79 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
     out_off[t] = off;
   }
   __syncthreads();
+  if (p.vec_out) {
+    // A fragment (32 pixels x 32 channels) goes through a 4 KB buffer of the wavefront, [pixel][32 channels] with the
+    // 16-byte slots swizzled by the pixel, and leaves as one store per pixel and channel quad: eight lanes write
+    // the 128 contiguous bytes of a pixel's channels (accumulator element v of lane l is pixel 8*(v/4) + 4*(l>>5) +
+    // v%4, channel l&31).  The fused form adds the bias and applies the relu on the way (Section 2.3: the
+    // temporary of the two statements never exists in memory).
+    unsigned char* buf = lds + TM * 8 + wv * 4096;
+    const int sp = lane >> 3, sc = lane & 7;
+    const int k0 = tn * TN + wn * 32 + sc * 4;   // the lane's four output channels
+    float b4[4] = {0.f, 0.f, 0.f, 0.f};
+    if (!I8 && p.epi) {
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        if (k0 + e < p.Co) b4[e] = bias[k0 + e];
+    }
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int pixel = 8 * (v / 4) + 4 * fh + (v % 4);
+        *(float*)(buf + pixel * 128 + ((((fr >> 2) ^ (pixel & 7)) << 4) | ((fr & 3) << 2))) = acc[q][v];
+      }
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int pixel = 8 * j + sp;
+        typedef __attribute__((ext_vector_type(4))) float f4;
+        f4 val = *(const f4*)(buf + pixel * 128 + ((sc ^ sp) << 4));
+        const int64_t off = out_off[wm * 64 + 32 * q + pixel];
+        if (off < 0 || k0 >= p.Co) continue;
+        if (!I8 && p.epi) {
+          val.x = __builtin_fmaxf(val.x + b4[0], 0.f);   // relu; a NaN becomes 0
+          val.y = __builtin_fmaxf(val.y + b4[1], 0.f);
+          val.z = __builtin_fmaxf(val.z + b4[2], 0.f);
+          val.w = __builtin_fmaxf(val.w + b4[3], 0.f);
+        }
+        const float ve[4] = {val.x, val.y, val.z, val.w};
+        if (!I8 && p.out_bf16) {
+          uint16_t h[4];
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const uint32_t u = __float_as_uint(ve[e]);
+            h[e] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);   // round to nearest even
+          }
+          uint16_t* dst = (uint16_t*)O + off + k0;
+          if (k0 + 3 < p.Co) {
+            typedef __attribute__((ext_vector_type(2))) unsigned u2;
+            const u2 packed = {(unsigned)h[0] | ((unsigned)h[1] << 16), (unsigned)h[2] | ((unsigned)h[3] << 16)};
+            __builtin_nontemporal_store(packed, (u2*)dst);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (k0 + e < p.Co) dst[e] = h[e];
+          }
+        } else {
+          float* dst = (float*)O + off + k0;             // int32 results travel as bit patterns
+          if (k0 + 3 < p.Co) {
+            __builtin_nontemporal_store(val, (f4*)dst);
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (k0 + e < p.Co) __builtin_nontemporal_store(ve[e], dst + e);
+          }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+    return;
+  }
   const int k = tn * TN + wn * 32 + fr;       // the lane's output channel
   if (k >= p.Co) return;
+  float b1 = 0.f;
+  if (!I8 && p.epi) b1 = bias[k];
 #pragma unroll
   for (int q = 0; q < 2; ++q)
 #pragma unroll
@@ -228,11 +302,13 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
       const int row = wm * 64 + 32 * q + 8 * (v / 4) + (v % 4) + 4 * fh;
       const int64_t off = out_off[row];
       if (off < 0) continue;
+      float val = acc[q][v];
+      if (!I8 && p.epi) val = __builtin_fmaxf(val + b1, 0.f);
       if (!I8 && p.out_bf16) {
-        const uint32_t u = __float_as_uint(acc[q][v]);
+        const uint32_t u = __float_as_uint(val);
         ((uint16_t*)O)[off + k] = (uint16_t)((u + 0x7fffu + ((u >> 16) & 1u)) >> 16);   // round to nearest even
       } else {
-        __builtin_nontemporal_store(acc[q][v], (float*)O + off + k);   // int32 results travel as bit patterns
+        __builtin_nontemporal_store(val, (float*)O + off + k);   // int32 results travel as bit patterns
       }
     }
 }
@@ -315,9 +391,10 @@ bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLa
 }
 
 hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_dtype, bool out_bf16, const void* in, const void* flt, void* out,
-                             hipStream_t st) {
+                             const void* bias, hipStream_t st) {
   const bool i8 = in_dtype == STRIPE_I8;
-  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
+  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % (out_bf16 ? 2 : 4)) || ((uintptr_t)bias % 4)) return hipErrorInvalidValue;
+  if (bias && i8) return hipErrorInvalidValue;
   IgemmParams p;
   p.i_n = c.i_n; p.i_y = c.i_y; p.i_x = c.i_x;
   p.f_r = c.f_r; p.f_s = c.f_s; p.f_k = c.f_k;
@@ -333,10 +410,13 @@ hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_d
   p.chunks = (int)(c.Ci / (i8 ? 64 : 32));
   p.k_tiles = (int)(c.R * c.S) * p.chunks;
   p.out_bf16 = out_bf16 ? 1 : 0;
-  typedef void (*kern_t)(const IgemmParams, const unsigned char*, const unsigned char*, void*);
+  p.epi = bias ? 1 : 0;
+  // one store per pixel and four channels where every such group starts on a 16-byte (bf16 output: 8-byte) boundary
+  p.vec_out = (c.o_n % 4 == 0 && c.o_y % 4 == 0 && c.o_x % 4 == 0 && c.o_base % 4 == 0 && (uintptr_t)out % (out_bf16 ? 8 : 16) == 0) ? 1 : 0;
+  typedef void (*kern_t)(const IgemmParams, const unsigned char*, const unsigned char*, void*, const float*);
   const kern_t fn = tn == 128 ? (i8 ? (kern_t)conv_igemm_kernel<128, true> : (kern_t)conv_igemm_kernel<128, false>)
                               : (i8 ? (kern_t)conv_igemm_kernel<64, true> : (kern_t)conv_igemm_kernel<64, false>);
-  const int lds_bytes = 4 * (tm + tn) * 64;
+  const int lds_bytes = 4 * (tm + tn) * 64;   // the ring; the store phase needs tm * 8 + 8 * 4096 of it
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;
@@ -345,7 +425,8 @@ hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_d
     if (e != hipSuccess) return e;
     l.lds_enabled_on = dev;
   }
-  hipLaunchKernelGGL(fn, dim3((unsigned)l.grid), dim3(512), lds_bytes, st, p, (const unsigned char*)in, (const unsigned char*)flt, out);
+  hipLaunchKernelGGL(fn, dim3((unsigned)l.grid), dim3(512), lds_bytes, st, p, (const unsigned char*)in, (const unsigned char*)flt, out,
+                     (const float*)bias);
   return hipGetLastError();
 }
 

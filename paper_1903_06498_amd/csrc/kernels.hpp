@@ -64,8 +64,9 @@ hipError_t launch_conv_bias_relu(const Conv2dShape& c, const ConvLaunch& l, cons
 // general convolution kernel (implicit contraction: any filter extent, stride, dilation, padding, image width;
 // bf16 with Ci % 32 == 0 or int8 with Ci % 64 == 0; channels contiguous); conv_select falls back to it
 bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLaunch* l, stripe_block_info_t* info);
+// bias != nullptr: the fused form of a following statement O = relu(T + bias[k]) (float blocks only)
 hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_dtype, bool out_bf16, const void* in, const void* flt, void* out,
-                             hipStream_t stream);
+                             const void* bias, hipStream_t stream);
 // strided 7x7 int8 variant (dispatched to by conv_select / launch_conv)
 bool conv_i8_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
 hipError_t launch_conv_i8(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);

@@ -416,7 +416,7 @@ def linear_bias_relu_program(M, N, K, out_dtype="bf16", b_transposed=True) -> Bl
 
 # Further shapes the kernel families cover, for measurements beyond the five configurations (bench.py --workload).
 EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32",
-               "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "gemm_bf16_1024", "gemm_bf16_2048",
+               "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "conv3x3_bias_relu_bf16_128to128", "gemm_bf16_1024", "gemm_bf16_2048",
                "linear_bias_relu_4096", "gemm_bf16_256x256x65536", "gemm_i8_256x256x65536_bt", "gemm_bf16_1024x1024x8192", "conv3x3_bf16_128to128", "conv3x3_s2_bf16_64to128", "conv1x7_bf16_64to64",
                "conv3x3_bf16_w112", "conv5x5_bf16_32to32", "conv3x3_i8_64to64", "conv3x3_bf16_128to192", "depthwise3x3_f32", "avgpool3x3s2_f32", "maxpool2x2s2_f32", "maxpool3x3s1_f32")
 
@@ -461,6 +461,8 @@ def extra_block(name: str) -> Block:
         return conv_bias_relu_program(32, 56, 56, 64, 64, 3, 3, 1, 1, "bf16", "bf16")
     if name == "linear_bias_relu_4096":        # relu(X * W^T + b), 4096^3, bf16 output: two statements fused into the GEMM
         return linear_bias_relu_program(4096, 4096, 4096, "bf16", b_transposed=True)
+    if name == "conv3x3_bias_relu_bf16_128to128":   # the same two statements on a shape of the general convolution kernel
+        return conv_bias_relu_program(32, 28, 28, 128, 128, 3, 3, 1, 1, "bf16", "bf16")
     if name == "resnet_conv_bias_relu_f32":    # the same with an fp32 output
         return conv_bias_relu_program(32, 56, 56, 64, 64, 3, 3, 1, 1, "bf16", "f32")
     if name == "pointwise_conv_bf16":          # 1x1 convolution, 256 -> 64 channels on the ResNet block's 32 x 56 x 56 pixels
@@ -481,6 +483,10 @@ def extra_inputs(name: str):
     if name in ("resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32"):
         return config_inputs("resnet_conv_bf16") + [seeded_tensor((64,), "f32", 2)]
     blk = extra_block(name)
+    if name == "conv3x3_bias_relu_bf16_128to128":
+        return [seeded_tensor((32, 28, 28, 128), "bf16", 0),
+                (seeded_tensor((3, 3, 128, 128), "bf16", 1).float() * (2.0 / 1152.0) ** 0.5).to(seeded_tensor((1,), "bf16", 0).dtype),
+                seeded_tensor((128,), "f32", 2)]
     if name == "avgpool3x3s2_f32":
         import torch
         return [seeded_tensor(blk.refs[0].sizes, "f32", 0), torch.full((1,), 1.0 / 9.0, dtype=torch.float32)]

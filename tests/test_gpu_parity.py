@@ -395,6 +395,22 @@ def test_fused_convolution_bias_relu(N, H, Wd, out_dt, fuse, monkeypatch):
 
 
 @pytest.mark.parametrize("fuse", [1, 0])
+@pytest.mark.parametrize("out_dt", ["bf16", "f32"])
+@pytest.mark.parametrize("shape", [(2, 14, 14, 128, 128, 3, 1, 1), (2, 17, 19, 64, 128, 3, 2, 1), (1, 12, 40, 32, 96, 5, 1, 2),
+                                   (3, 9, 11, 64, 36, 1, 1, 0), (1, 30, 30, 32, 64, 3, 2, 0)])
+def test_fused_convolution_bias_relu_general_kernel(shape, out_dt, fuse, monkeypatch):
+    """The same two statements on shapes of the general matrix-core convolution kernel (channel counts, strides, filter
+    extents and paddings the tuned kernel does not take; ragged pixel and channel tiles): fused into its store phase,
+    and unfused through a temporary; both against the oracle's serial evaluation."""
+    monkeypatch.setenv("STRIPE_TUNE", f"fuse={fuse}")
+    info = program_parity(*shape, "bf16", out_dt)
+    if fuse:
+        assert info["kernel"].startswith("conv_igemm_bf16_") and info["kernel"].endswith("+bias_relu" + ("_bf16" if out_dt == "bf16" else "")), info
+    else:
+        assert " ; " in info["kernel"] and "conv_igemm_bf16_" in info["kernel"], info["kernel"]
+
+
+@pytest.mark.parametrize("fuse", [1, 0])
 @pytest.mark.parametrize("M,N,K,bt,out_dt", [(256, 256, 128, True, "bf16"), (300, 520, 256, True, "f32"), (512, 256, 128, False, "bf16"),
                                              (384, 640, 256, True, "f32"), (70, 264, 128, False, "f32"), (1024, 1024, 256, True, "bf16")])
 def test_fused_linear_bias_relu(M, N, K, bt, out_dt, fuse, monkeypatch):

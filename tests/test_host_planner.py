@@ -266,3 +266,11 @@ def test_constraint_coefficient_beyond_32_bits_is_refused_not_truncated():
     with pytest.raises(B.StripeError) as e:
         B.StripeBlock(W.make_root(bufs, outer))
     assert e.value.status == 3
+
+
+def test_fusion_keeps_apart_what_the_general_kernel_leaves_unwritten():
+    """Padding beyond the filter: some output pixels have no tap inside the image, the convolution writes nothing there
+    and the temporary would hold an undefined element: such a list is refused (unwritten temporary) rather than fused."""
+    prog = W.conv_bias_relu_program(1, 8, 8, 32, 32, 3, 3, 1, 3, "bf16", "f32")
+    with pytest.raises(B.StripeError):
+        B.StripeBlock(prog)
