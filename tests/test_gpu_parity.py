@@ -410,13 +410,14 @@ def test_fused_convolution_bias_relu_general_kernel(shape, out_dt, fuse, monkeyp
         assert " ; " in info["kernel"] and "conv_igemm_bf16_" in info["kernel"], info["kernel"]
 
 
-@pytest.mark.parametrize("fuse", [1, 0])
+@pytest.mark.parametrize("fuse", [1, 2, 0])
 @pytest.mark.parametrize("M,N,K,bt,out_dt", [(256, 256, 128, True, "bf16"), (300, 520, 256, True, "f32"), (512, 256, 128, False, "bf16"),
                                              (384, 640, 256, True, "f32"), (70, 264, 128, False, "f32"), (1024, 1024, 256, True, "bf16")])
 def test_fused_linear_bias_relu(M, N, K, bt, out_dt, fuse, monkeypatch):
     """O = relu(X * W^T + b) as two statements: fused into the dense-contraction kernels' epilogue (all their float
-    modes: 256 and 128 tiles, transposed / row-major W, ragged edges), or unfused through a temporary."""
-    monkeypatch.setenv("STRIPE_TUNE", f"fuse={fuse}")
+    modes: 256 and 128 tiles, transposed / row-major W, ragged edges; fuse=2: with the 4-byte stores of the 256-tile
+    kernel instead of its 16-byte ones), or unfused through a temporary."""
+    monkeypatch.setenv("STRIPE_TUNE", f"fuse={min(fuse, 1)},gemm_epi16={-1 if fuse == 1 else 0}")
     prog = W.linear_bias_relu_program(M, N, K, out_dt, b_transposed=bt)
     x = W.seeded_tensor((M, K), "bf16", 0)
     w = (W.seeded_tensor((N, K) if bt else (K, N), "bf16", 1).float() * (1.0 / K) ** 0.5).to(torch.bfloat16)
@@ -646,6 +647,8 @@ def test_gemm_mfma_small(M, N, K):
 
 @pytest.mark.parametrize("tune,name", [("gemm_t128=0,gemm_dma_waves=4", "256x256x32_mfma32x32x16_w4_lds_direct"),
                                        ("gemm_t128=0,gemm_dma_waves=8", "w8_lds_direct"),
+                                       ("gemm_t128=0,gemm_dma_waves=4,gemm_epi16=1", "256x256x32_mfma32x32x16_w4_lds_direct"),
+                                       ("gemm_t128=0,gemm_dma_waves=8,gemm_epi16=1", "w8_lds_direct"),
                                        ("gemm_t128=0,gemm_sched=0", "w4_lds_direct_s0"), ("gemm_t128=0,gemm_sched=2", "w4_lds_direct_s2"),
                                        ("gemm_t128=1", "128x128x32_mfma32x32x16_w8_lds_direct"),
                                        ("gemm_t128=1,gemm_t128_waves=4", "128x128x32_mfma32x32x16_w4_lds_direct"),
@@ -692,13 +695,14 @@ def test_gemm_transposed_b_and_ragged_edges(M, N, K, bt, monkeypatch):
     parity(blk, ins, what=f"gemm {M}x{N}x{K} bt={bt}")          # also checks that nothing outside C[0:M, 0:N] changed
 
 
-@pytest.mark.parametrize("t128", [1, 0])
+@pytest.mark.parametrize("t128", [1, 0, -1])
 @pytest.mark.parametrize("M,N,K", [(256, 256, 256), (512, 768, 512), (300, 333, 256), (70, 9, 512), (257, 8, 256), (128, 384, 256)])
 def test_gemm_int8_transposed_b(M, N, K, t128, monkeypatch):
     """int8 x int8 -> int32 on the matrix cores (C = A * B^T, both operands k-contiguous): bit-exact, including
     extreme values (-128 * -128 summed over K) and edges that are not multiples of the tile; small aligned
-    products on the 128 x 128-tile kernel (t128=1) and on the 256 x 256 one."""
-    monkeypatch.setenv("STRIPE_TUNE", f"gemm_t128={t128}")
+    products on the 128 x 128-tile kernel (t128=1) and on the 256 x 256 one (0; -1: with its 16-byte stores)."""
+    monkeypatch.setenv("STRIPE_TUNE", f"gemm_t128={max(t128, 0)},gemm_epi16={int(t128 < 0)}")
+    t128 = max(t128, 0)
     blk = W.matmul_block(M, N, K, "i8", "i32", b_transposed=True)
     a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.int8)
     sel = (torch.arange(N) + 37) % K
