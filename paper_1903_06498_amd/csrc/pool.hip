@@ -65,10 +65,24 @@ __device__ __forceinline__ unsigned xcd_contiguous(unsigned b, unsigned grid) {
   return (b % 8u) * (grid / 8u) + b / 8u;
 }
 
+// The same idea at a finer grain: every XCD takes runs of `group` consecutive logical ids (whole rows of
+// workgroups, so that the columns and rows shared between neighbours are fetched into one L2 once) and the runs go
+// round-robin over the XCDs, which keeps the chip as a whole streaming through the tensor front to back.
+__device__ __forceinline__ unsigned xcd_grouped(unsigned b, unsigned grid, unsigned group) {
+  const unsigned full = grid / (8u * group) * (8u * group);
+  if (b >= full) return b;
+  const unsigned x = b % 8u, t = b / 8u;
+  return ((t / group) * 8u + x) * group + t % group;
+}
+
+__device__ __forceinline__ unsigned logical_block(int mode, unsigned b, unsigned grid) {
+  return mode == 1 ? xcd_contiguous(b, grid) : mode > 1 ? xcd_grouped(b, grid, (unsigned)mode) : b;
+}
+
 template <int R, int S, int ST, int TY, bool NT>
 __global__ __launch_bounds__(128) void pool_max_f32_kernel(const PoolParams p, const float* __restrict__ in,
                                                           float* __restrict__ out) {
-  const unsigned b = p.xcd_remap ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
+  const unsigned b = logical_block(p.xcd_remap, blockIdx.x, gridDim.x);
   const int bx = b % p.blocks_per_row;
   const int rest = b / p.blocks_per_row;
   const int ys = rest % p.y_strips;
@@ -257,7 +271,7 @@ __global__ __launch_bounds__(1024) void pool_f32_strip_kernel(const PoolParams p
   // A workgroup keeps its 128 (column, channel-quad) items and walks over strips (image, row strip) with the
   // grid's stride: gridDim.x = blocks_per_row * (strips walked side by side), so everything that depends on the
   // column is computed once.  Fewer, longer-lived workgroups stream better than one short workgroup per strip.
-  const unsigned b = p.xcd_remap ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
+  const unsigned b = logical_block(p.xcd_remap, blockIdx.x, gridDim.x);
   const int bx = b % p.blocks_per_row;
   const int item = bx * 128 + threadIdx.x;
   if (item >= p.items) return;
@@ -403,7 +417,7 @@ template <int R, int S, int ST, int TY, int WMODE>
 __global__ __launch_bounds__(512) void window_weighted_f32_kernel(const PoolParams p, const float* __restrict__ in,
                                                                  const float* __restrict__ wgt, float* __restrict__ out) {
   constexpr int NR = ST * (TY - 1) + R;
-  const unsigned b = p.xcd_remap ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
+  const unsigned b = logical_block(p.xcd_remap, blockIdx.x, gridDim.x);
   const int bx = b % p.blocks_per_row;
   // blockDim.y strips side by side per workgroup, one per 128 lanes (they share input rows through L1)
   const int rest = (int)(b / (unsigned)p.blocks_per_row) * (int)blockDim.y + (int)threadIdx.y;
@@ -479,7 +493,9 @@ PoolParams make_params(const Pool2dShape& s, int ty, int wg) {
   p.items = p.Wo * p.C4;
   p.blocks_per_row = (p.items + wg - 1) / wg;
   p.y_strips = (p.Ho + ty - 1) / ty;
-  p.xcd_remap = tune_int("pool_xcd", 0);
+  p.xcd_remap = tune_int("pool_xcd", 0);      // 1: one contiguous range of workgroups per XCD
+  if (const int rows = tune_int("pool_xcd_rows", 0); rows > 0 && p.xcd_remap == 0)
+    p.xcd_remap = rows * p.blocks_per_row > 1 ? rows * p.blocks_per_row : 2;   // runs of `rows` whole rows of workgroups per XCD
   p.stream_loads = tune_int("pool_ntl", 0);
   p.stream_stores = tune_int("pool_nts", 0);
   p.rows = ty;
@@ -635,6 +651,8 @@ hipError_t launch_weighted_rows(int ty, int yb, const PoolParams& p, dim3 g, con
   switch (ty) {
     case 1: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 1, WMODE>), g, dim3(128, yb), 0, st, p, i, w, o); break;
     case 2: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 2, WMODE>), g, dim3(128, yb), 0, st, p, i, w, o); break;
+    case 3: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 3, WMODE>), g, dim3(128, yb), 0, st, p, i, w, o); break;
+    case 4: hipLaunchKernelGGL((window_weighted_f32_kernel<R, S, ST, 4, WMODE>), g, dim3(128, yb), 0, st, p, i, w, o); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -664,7 +682,7 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     if (s.w_mode == 2 && (s.w_c != 1 || s.w_r % 4 || s.w_s % 4 || s.w_base % 4)) return false;
     // per-tap weights: strips side by side measured slower (3x3 stride 1, two rows per strip: 59.6 us alone, 66.8 us
     // four side by side), so only the scaled sum takes them
-    const StripShape shape = s.w_mode == 2 ? choose_strip_shape(s, {1, 2}, {1}) : choose_strip_shape(s, {1, 2}, {1, 2, 4});
+    const StripShape shape = s.w_mode == 2 ? choose_strip_shape(s, {1, 2, 3, 4}, {1}) : choose_strip_shape(s, {1, 2, 3, 4}, {1, 2, 4});
     const int rows = shape.ty;
     const PoolParams p = make_params(s, rows, 128);
     if ((int64_t)p.N * p.y_strips * p.blocks_per_row > 0x7fffffffLL) return false;

@@ -567,7 +567,7 @@ def test_pool_lds_staged_kernel(R, stride, pad, agg, C, rows, monkeypatch):
 
 
 @pytest.mark.parametrize("yb", [1, 2, 4])
-@pytest.mark.parametrize("ty", [1, 2])
+@pytest.mark.parametrize("ty", [1, 2, 3, 4])
 @pytest.mark.parametrize("kind", ["depthwise_s1", "depthwise_s2", "avg_2x2"])
 def test_weighted_windows_every_strip_shape(kind, ty, yb, monkeypatch):
     """Depthwise convolutions and an average pooling on every strip height and number of strips side by side."""
