@@ -652,6 +652,7 @@ def test_gemm_mfma_small(M, N, K):
                                        ("gemm_t128=0,gemm_dma_waves=4,gemm_epi16=1", "256x256x32_mfma32x32x16_w4_lds_direct"),
                                        ("gemm_t128=0,gemm_dma_waves=8,gemm_epi16=1", "w8_lds_direct"),
                                        ("gemm_t128=0,gemm_sched=0", "w4_lds_direct_s0"), ("gemm_t128=0,gemm_sched=2", "w4_lds_direct_s2"),
+                                       ("gemm_t128=0,gemm_sched=3", "w4_lds_direct_s3"),
                                        ("gemm_t128=1", "128x128x32_mfma32x32x16_w8_lds_direct"),
                                        ("gemm_t128=1,gemm_t128_waves=4", "128x128x32_mfma32x32x16_w4_lds_direct"),
                                        ("gemm_dma=0,gemm_waves=4", "w4_swz2"), ("gemm_dma=0,gemm_waves=8,gemm_swz=1", "w8_swz1"),
