@@ -34,7 +34,7 @@ MEASURED_TRAFFIC = {
     "gemm_bf16_4096": 201.6e6 + 67.1e6,
     "resnet_conv_bf16": 16.9e6 + 25.7e6,
     "conv7x7_s2_int8": 3.4e6 + 51.4e6,
-    "maxpool_f32": 133.1e6 + 25.7e6,
+    "maxpool_f32": 120.2e6 + 25.7e6,
 }
 TRAFFIC_SOURCE = {name: f"profiles/{name}.md (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of the default kernel, scaled by profiles/device_copy.md)"
                   for name in MEASURED_TRAFFIC}
