@@ -47,6 +47,8 @@ KIND = {
     "maxpool_f32": ("GB/s", "hbm", "f32"),
     "tiny_conv_f32": ("TFLOP/s", "hbm", "f32"),
     "device_copy": ("GB/s", "hbm", "u8"),     # the plain copy kernel: calibrates traffic counters and the HBM yardstick
+    "mfma_probe": ("TFLOP/s", "mfma", "bf16"),   # the matrix instruction on register-resident operands: the sustained compute roof
+    "mfma_probe_lds": ("TFLOP/s", "mfma", "bf16"),   # the same with the operand fragments fetched from LDS for every pass
     # streaming yardsticks sized like the max-pooling block (102.8 MB in, 25.7 MB out): read only, write only, 1 : 1, 4 : 1
     "stream_read": ("GB/s", "hbm", "f32"),
     "stream_write": ("GB/s", "hbm", "f32"),
@@ -171,6 +173,40 @@ def bench_stream(args, torch, B, name):
           flush=True)
 
 
+def bench_mfma(args, torch, B, from_lds):
+    """stripe_device_mfma: the contraction kernels' matrix instruction on operands resident in registers (mfma_probe) or
+    fetched from LDS for every pass (mfma_probe_lds), one workgroup of four wavefronts per CU; operands N(0,1) rounded
+    to bf16 (seed 0), or constant with --fill."""
+    dev = torch.device("cuda:0")
+    g = torch.Generator(device="cpu")
+    g.manual_seed(0)
+    ops = torch.randn((16 * 256, 8), generator=g, dtype=torch.float32).to(torch.bfloat16)
+    ops = fill_like(ops, args.fill).to(dev)
+    grid, iters = 256, 512
+    out = torch.empty(grid * 256, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+    run = lambda: B.stripe_device_mfma(ops.data_ptr(), out.data_ptr(), iters, grid, stream.cuda_stream, from_lds)
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(args.steps):
+        run()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) / args.steps * 1e3
+    flops = grid * 4 * iters * 16 * 32768.0
+    tf = flops / us / 1e6
+    print(json.dumps({"metric": "matrix-core rate on operands from " + ("LDS" if from_lds else "registers") + " (yardstick)", "value": round(tf, 2), "unit": "TFLOP/s", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(us / 1e3, 5), "higher_is_better": True,
+                      "dtype": "bf16", "data": "synthetic" if args.fill == "config" else f"diagnostic constant fill ({args.fill})",
+                      "config": {"workload": "mfma_probe_lds" if from_lds else "mfma_probe", "grid": grid, "iters": iters, "instructions_per_wavefront": iters * 16, "fill": args.fill},
+                      "roofline": {"bound": "mfma", "achieved": round(tf, 2), "peak": PEAK["bf16_mfma_tflops"], "unit": "TFLOP/s",
+                                   "frac": round(tf / PEAK["bf16_mfma_tflops"], 4), "traffic": None, "kernel": "mfma_probe_kernel",
+                                   "kernel_us": round(us, 2), "algorithmic_flops": int(flops)}}), flush=True)
+
+
 def bench_library_gemm(args, torch, W):
     """The vendor library's bf16 x bf16 -> fp32 GEMM on the same seeded operands, same box, same clocks."""
     dev = torch.device("cuda:0")
@@ -241,6 +277,8 @@ def main():
         return bench_library_gemm(args, torch, W)
     if name.startswith("stream_"):
         return bench_stream(args, torch, B, name)
+    if name in ("mfma_probe", "mfma_probe_lds"):
+        return bench_mfma(args, torch, B, name == "mfma_probe_lds")
     extra = name in W.EXTRA_NAMES
     root = W.extra_block(name) if extra else W.config_block(name)
     inputs = W.extra_inputs(name) if extra else W.config_inputs(name)

@@ -266,6 +266,20 @@ stripe_status_t stripe_device_copy(const void* src, void* dst, size_t n_bytes, v
  */
 stripe_status_t stripe_device_stream(const void* src, void* dst, size_t n_vectors, int reads, int write, int grid, void* hip_stream);
 
+/*
+ * Matrix-core yardstick: every wavefront of `grid` workgroups of 256 lanes runs `iters` (even) passes over a
+ * 4 x 4 tile of 32 x 32 x 16 bf16 matrix instructions whose operand fragments stay in registers (no LDS or global
+ * traffic inside the loop): iters * 16 instructions = iters * 524,288 flop per wavefront, 4 wavefronts per
+ * workgroup.  `operands`: DEVICE, 16-byte aligned, 16 * 256 vectors of 8 bf16 (64 KB): vector (s * 8 + f) * 256 + lane
+ * is fragment f (0-3: A, 4-7: B) of operand set s (0, 1; the sets alternate from pass to pass) for lane `lane` of
+ * the workgroup.  `out`: DEVICE, grid * 256 floats; each receives the sum of its lane's 256 accumulator elements.
+ * from_lds != 0: the fragments are parked in LDS and fetched again before every pass (eight 16-byte reads per lane
+ * for sixteen instructions, the contraction kernels' ratio) instead of staying in registers.
+ * It states what the chip sustains for the contraction kernels' instruction on given operand values, apart from
+ * the memory system (Section 3.3's roofline speaks of the compute roof; this measures it).
+ */
+stripe_status_t stripe_device_mfma(const void* operands, void* out, int iters, int from_lds, int grid, void* hip_stream);
+
 /* ------------------------------------------------------------------------
  * Autotiling (paper Section 3.3, Figures 4 and 5): host-only integer code.
  *

@@ -30,7 +30,7 @@ _INTR = {"mul": 0, "copy": 1, "add": 2, "add_relu": 3}
 
 EXPORTS = ("stripe_block_create", "stripe_block_create_for_path", "stripe_block_run", "stripe_block_run_static", "stripe_block_query",
            "stripe_block_workspace_size", "stripe_block_set_workspace",
-           "stripe_block_destroy", "stripe_status_string", "stripe_last_error", "stripe_device_copy", "stripe_device_stream",
+           "stripe_block_destroy", "stripe_status_string", "stripe_last_error", "stripe_device_copy", "stripe_device_stream", "stripe_device_mfma",
            "stripe_tile_cost", "stripe_tile_search", "stripe_block_tile", "stripe_desc_free")
 
 
@@ -115,6 +115,8 @@ def _load():
     lib.stripe_last_error.argtypes = []
     lib.stripe_device_copy.restype = C.c_int
     lib.stripe_device_copy.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.stripe_device_mfma.restype = C.c_int
+    lib.stripe_device_mfma.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p]
     lib.stripe_device_stream.restype = C.c_int
     lib.stripe_device_stream.argtypes = [C.c_void_p, C.c_void_p, C.c_size_t, C.c_int, C.c_int, C.c_int, C.c_void_p]
     lib.stripe_tile_cost.restype = C.c_int
@@ -248,6 +250,11 @@ def stripe_device_copy(src_ptr: int, dst_ptr: int, n_bytes: int, stream: int = 0
 def stripe_device_stream(src_ptr: int, dst_ptr: int, n_vectors: int, reads: int, write: int, grid: int, stream: int = 0) -> None:
     _check(lib.stripe_device_stream(C.c_void_p(int(src_ptr)), C.c_void_p(int(dst_ptr)), C.c_size_t(int(n_vectors)), int(reads), int(write),
                                     int(grid), C.c_void_p(int(stream))))
+
+
+def stripe_device_mfma(operands_ptr: int, out_ptr: int, iters: int, grid: int, stream: int = 0, from_lds: bool = False) -> None:
+    _check(lib.stripe_device_mfma(C.c_void_p(int(operands_ptr)), C.c_void_p(int(out_ptr)), int(iters), int(bool(from_lds)), int(grid),
+                                  C.c_void_p(int(stream))))
 
 
 # ---- autotiling (host only) ------------------------------------------------

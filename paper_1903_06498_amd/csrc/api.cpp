@@ -601,4 +601,14 @@ stripe_status_t stripe_device_stream(const void* src, void* dst, size_t n_vector
   return STRIPE_OK;
 }
 
+stripe_status_t stripe_device_mfma(const void* operands, void* out, int iters, int from_lds, int grid, void* hip_stream) {
+  if (!operands || !out) return fail(STRIPE_ERR_NULL, "operands or out is NULL");
+  if (iters < 2 || (iters & 1) || iters > (1 << 24) || grid < 1 || grid > (1 << 20))
+    return fail(STRIPE_ERR_INVALID_DESC, "iters is even, 2 .. 2^24; grid is 1 .. 2^20 workgroups");
+  if (((uintptr_t)operands % 16) || ((uintptr_t)out % 4)) return fail(STRIPE_ERR_MISALIGNED, "matrix-core yardstick needs 16-byte aligned operands");
+  const hipError_t e = launch_mfma_probe(operands, out, iters, grid, from_lds != 0, (hipStream_t)hip_stream);
+  if (e != hipSuccess) return fail(STRIPE_ERR_HIP, std::string("matrix-core yardstick launch failed: ") + hipGetErrorString(e));
+  return STRIPE_OK;
+}
+
 }  // extern "C"

@@ -1289,4 +1289,76 @@ static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------
+// Matrix-core yardstick: the 4 x 4 fragment tile of the 256-tile kernel's wavefront with both operands resident in
+// registers -- no LDS, no global traffic inside the loop.  Two sets of 4 + 4 operand fragments (loaded once from
+// `operands`) take turns, so that the operands of consecutive matrix instructions differ as they do in the real
+// kernel; what the loop reaches is the rate the chip sustains for this instruction on these operand values.
+// ---------------------------------------------------------------------------
+namespace {
+// LDS: the operand fragments are fetched again from LDS before every pass (eight 16-byte reads per lane for sixteen
+// matrix instructions, the real kernel's ratio), one pass ahead of their use.
+template <bool LDS>
+__global__ __launch_bounds__(256, 1) void mfma_probe_kernel(const bf16x8* __restrict__ operands, float* __restrict__ out, int iters) {
+  __shared__ bf16x8 frag[LDS ? 16 * 256 : 1];
+  const int t = threadIdx.x;
+  bf16x8 a[2][4], b[2][4];
+#pragma unroll
+  for (int s = 0; s < 2; ++s)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      a[s][i] = operands[((s * 8 + i) * 256) + t];
+      b[s][i] = operands[((s * 8 + 4 + i) * 256) + t];
+      if constexpr (LDS) {
+        frag[(s * 8 + i) * 256 + t] = a[s][i];
+        frag[(s * 8 + 4 + i) * 256 + t] = b[s][i];
+      }
+    }
+  if constexpr (LDS) __syncthreads();
+  f32x16 acc[4][4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+  for (int it = 0; it < iters; it += 2) {
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+      if constexpr (LDS) {   // the other set's fragments for the next pass (a lane reads what it wrote: no barrier needed)
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("" ::: "memory");   // the fragments are fetched again, not kept from the previous pass
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          a[s ^ 1][i] = frag[((s ^ 1) * 8 + i) * 256 + t];
+          b[s ^ 1][i] = frag[((s ^ 1) * 8 + 4 + i) * 256 + t];
+        }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int jj = (i & 1) ? 3 - j : j;   // the order of the real kernel: one operand stays between consecutive instructions
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[s][i], b[s][jj], acc[i][jj], 0, 0, 0);
+        }
+      if constexpr (LDS) __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) sum += acc[i][j][v];
+  out[(size_t)blockIdx.x * 256 + t] = sum;
+}
+}  // namespace
+
+hipError_t launch_mfma_probe(const void* operands, void* out, int iters, int grid, bool lds, hipStream_t st) {
+  if (lds) hipLaunchKernelGGL(mfma_probe_kernel<true>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16x8*)operands, (float*)out, iters);
+  else hipLaunchKernelGGL(mfma_probe_kernel<false>, dim3((unsigned)grid), dim3(256), 0, st, (const bf16x8*)operands, (float*)out, iters);
+  return hipGetLastError();
+}
+
 }  // namespace stripe

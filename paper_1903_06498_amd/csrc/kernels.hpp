@@ -89,6 +89,9 @@ hipError_t launch_pool(const Pool2dShape& p, const PoolLaunch& l, const void* in
 hipError_t launch_copy(const void* src, void* dst, size_t n_bytes, hipStream_t stream);
 // `reads` input streams of n16 16-byte vectors each (0, 1, 2 or 4) folded into one output stream of n16 vectors (write != 0)
 // or into nothing (write == 0: dst is a 4-byte flag that is practically never written)
+// matrix-core yardstick (gemm.hip): iters (even) passes over a 4 x 4 fragment tile per wavefront, operands resident in
+// registers or (lds) fetched again from LDS for every pass
+hipError_t launch_mfma_probe(const void* operands, void* out, int iters, int grid, bool lds, hipStream_t stream);
 hipError_t launch_stream(const void* src, void* dst, size_t n16, int reads, int write, int grid, hipStream_t stream);
 
 }  // namespace stripe

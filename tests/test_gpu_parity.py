@@ -1079,3 +1079,33 @@ def test_int8_conv_config_full_size():
     cy = np.array([taps(y, 2, 3, 7, 224) for y in range(112)])
     want = 16384 * 3 * cy[:, None] * cy[None, :]
     assert np.array_equal(gpu, np.broadcast_to(want[None, :, :, None], gpu.shape))
+
+
+# ------------------------------------------------------------------ yardsticks
+@pytest.mark.parametrize("from_lds", [False, True])
+def test_matrix_core_yardstick_closed_form(from_lds):
+    """All-ones operands: every accumulator element gains 16 per instruction (K = 16), a lane holds 256 elements."""
+    iters, grid = 6, 3
+    ops = torch.ones((16 * 256, 8), dtype=torch.bfloat16, device="cuda")
+    out = torch.zeros(grid * 256, dtype=torch.float32, device="cuda")
+    B.stripe_device_mfma(ops.data_ptr(), out.data_ptr(), iters, grid, torch.cuda.current_stream().cuda_stream, from_lds)
+    torch.cuda.synchronize()
+    assert np.all(out.cpu().numpy() == 256 * 16 * iters)
+    # two operand sets taking turns: set 0 ones, set 1 twos -> half of the passes contribute 4 x 16
+    ops2 = ops.clone().reshape(2, 8 * 256, 8)
+    ops2[1] = 2.0
+    B.stripe_device_mfma(ops2.data_ptr(), out.data_ptr(), iters, grid, torch.cuda.current_stream().cuda_stream, from_lds)
+    torch.cuda.synchronize()
+    assert np.all(out.cpu().numpy() == 256 * 16 * (iters // 2) * (1 + 4))
+    with pytest.raises(B.StripeError):
+        B.stripe_device_mfma(ops.data_ptr(), out.data_ptr(), 3, grid)        # odd pass count
+
+
+def test_streaming_yardstick_sums_its_streams():
+    n16 = 1000
+    src = torch.arange(4 * n16 * 4, dtype=torch.float32, device="cuda")
+    dst = torch.zeros(n16 * 4, dtype=torch.float32, device="cuda")
+    B.stripe_device_stream(src.data_ptr(), dst.data_ptr(), n16, 4, 1, 7, torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    want = src.reshape(4, n16 * 4).sum(dim=0)
+    assert torch.equal(dst, want)
