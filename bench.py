@@ -207,6 +207,28 @@ def bench_mfma(args, torch, B, from_lds):
                                    "kernel_us": round(us, 2), "algorithmic_flops": int(flops)}}), flush=True)
 
 
+def sustained_mfma_roof(torch, B, dev, stream, warm=200, timed=100):
+    g = torch.Generator(device="cpu")
+    g.manual_seed(0)
+    ops = torch.randn((16 * 256, 8), generator=g, dtype=torch.float32).to(torch.bfloat16).to(dev)
+    grid, iters = 256, 512
+    out = torch.empty(grid * 256, dtype=torch.float32, device=dev)
+    run = lambda: B.stripe_device_mfma(ops.data_ptr(), out.data_ptr(), iters, grid, stream.cuda_stream, True)
+    for _ in range(warm):
+        run()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record(stream)
+    for _ in range(timed):
+        run()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    us = ev0.elapsed_time(ev1) / timed * 1e3
+    tf = grid * 4 * iters * 16 * 32768.0 / us / 1e6
+    return {"value": round(tf, 1), "unit": "TFLOP/s", "kind": "32x32x16 bf16 matrix instructions on N(0,1) operands fetched from LDS, "
+            "8 reads of 16 bytes per 16 instructions, no global traffic; %d launches after %d" % (timed, warm)}
+
+
 def bench_library_gemm(args, torch, W):
     """The vendor library's bf16 x bf16 -> fp32 GEMM on the same seeded operands, same box, same clocks."""
     dev = torch.device("cuda:0")
@@ -257,6 +279,8 @@ def main():
     ap.add_argument("--fill", default="config", choices=["config", "zeros", "ones"],
                     help="diagnostic: replace the seeded inputs by constants (shows how far the chip's power management, "
                          "not the kernel, sets the time); only 'config' is a valid measurement")
+    ap.add_argument("--sustained-roof", type=int, default=1, help="1: after the timed region of the default workload, also measure the "
+                    "matrix-core rate the chip sustains (roofline.sustained_roof); 0: skip")
     ap.add_argument("--traffic-bytes", type=float, default=None, help="HBM bytes per launch from rocprofv3 counters, if measured")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -340,6 +364,11 @@ def main():
     if name == "tiny_conv_f32":
         # sub-microsecond of work: bound by launch latency, so the figure of merit is time per launch, not a roofline fraction
         roof = {"bound": "launch", "achieved": round(kernel_s * 1e6, 2), "peak": None, "unit": "us/launch", "frac": None, "traffic": None}
+    if name == "gemm_bf16_4096" and args.fill == "config" and args.sustained_roof:
+        # what the chip sustains for this kernel's matrix instruction with operands of the same distribution fetched from
+        # LDS at this kernel's ratio and nothing else going on (stripe_device_mfma), measured after the timed region
+        roof["sustained_roof"] = sustained_mfma_roof(torch, B, dev, stream)
+        roof["sustained_roof"]["frac_of_it"] = round(achieved / roof["sustained_roof"]["value"], 4)
     roof["traffic_source"] = traffic_source
     roof["kernel"] = info["kernel"]
     roof["kernel_us"] = round(kernel_s * 1e6, 2)
