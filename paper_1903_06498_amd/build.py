@@ -10,7 +10,10 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libstripe_hip.so")
 SOURCES = ["api.cpp", "plan.cpp", "tiling.cpp", "generic.hip", "generic_tiled.hip", "pool.hip", "gemm.hip", "conv.hip", "conv_i8.hip", "conv_igemm.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument",
+         # the LDS-direct load helpers name M0 in their clobber lists on purpose (see their comments); the compiler
+         # notes that it treats M0 as reserved, once per unrolled copy
+         "-Wno-inline-asm"]
 
 
 def needs_build() -> bool:
