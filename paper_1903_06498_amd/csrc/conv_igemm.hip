@@ -136,15 +136,21 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
     if (gn >= p.Co) gn = p.Co - 1;
     b_base = F + (p.f_base + (int64_t)gn * p.f_k) * ES + chunk * 16;
   }
-  // the K tile the next issue() fetches: filter tap (ti, tj), channel chunk tc; all wave-uniform
+  // the K tile the next issue() fetches: filter tap (ti, tj), channel chunk tc, and its byte offsets in the image and
+  // the filter, advanced by additions (all wave-uniform): next chunk +64; next filter column: back to chunk 0 and one
+  // column on; next filter row: back to column 0 and one row on
   int ti = 0, tj = 0, tc = 0;
+  int64_t a_off = 0, b_off = 0;
+  const unsigned char* zero_chunk = igemm_zero_chunk;
+  asm volatile("" : "+s"(zero_chunk));   // held in registers: the compiler would otherwise re-read its address from memory for every K tile
+  const int64_t a_col = (int64_t)p.dil_x * p.i_x * ES - (int64_t)(p.chunks - 1) * 64, b_col = p.f_s * ES - (int64_t)(p.chunks - 1) * 64;
+  const int64_t a_row = (int64_t)p.dil_y * p.i_y * ES - (int64_t)(p.S - 1) * p.dil_x * p.i_x * ES - (int64_t)(p.chunks - 1) * 64;
+  const int64_t b_row = p.f_r * ES - (int64_t)(p.S - 1) * p.f_s * ES - (int64_t)(p.chunks - 1) * 64;
   auto issue = [&](int stage) {
-    const int64_t a_off = ((int64_t)(ti * p.dil_y) * p.i_y + (int64_t)(tj * p.dil_x) * p.i_x) * ES + tc * 64;
-    const int64_t b_off = ((int64_t)ti * p.f_r + (int64_t)tj * p.f_s) * ES + tc * 64;
 #pragma unroll
     for (int u = 0; u < LA; ++u) {
       const bool inside = ((rmask[u] >> ti) & (cmask[u] >> tj) & 1u) != 0;
-      const void* src = inside ? (const void*)(a_base[u] + a_off) : (const void*)igemm_zero_chunk;
+      const void* src = inside ? (const void*)(a_base[u] + a_off) : (const void*)zero_chunk;
       g_load_lds16(src, stage * A_STAGE + (wv + 8 * u) * 1024);
     }
     g_load_lds16(b_base + b_off, B0 + stage * B_STAGE + bb * 1024);
@@ -153,7 +159,15 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
       if (++tj == p.S) {
         tj = 0;
         ++ti;
+        a_off += a_row;
+        b_off += b_row;
+      } else {
+        a_off += a_col;
+        b_off += b_col;
       }
+    } else {
+      a_off += 64;
+      b_off += 64;
     }
   };
 
