@@ -39,7 +39,7 @@ struct IgemmParams {
   int32_t R, S, stride_y, stride_x, pad_y, pad_x, dil_y, dil_x;
   int32_t m_total;                // output pixels N * Ho * Wo
   int32_t tiles_n;                // workgroup tiles along the output channels
-  int32_t chunks;                 // 64-byte channel chunks per tap
+  int32_t chunks;                 // channel chunks (one K tile row each: 64 or 128 bytes) per tap
   int32_t k_tiles;                // R * S * chunks
   int32_t out_bf16;               // float blocks: round the result to bf16 on store
   int32_t epi;                    // 1: the fused form of a following statement O = relu(T + bias[k]) (float blocks)
@@ -70,29 +70,44 @@ __device__ __forceinline__ g_f32x16 g_mma(g_bf16x8 a, g_bf16x8 b, g_f32x16 acc) 
 
 #define G_FENCE() __builtin_amdgcn_sched_barrier(0)
 
+// The variants that leave room for one workgroup per CU only (256 x 128 tiles, 128-byte K tile rows) are used where
+// one round of workgroups covers the block anyway: at most one tile per CU; the large tile from 160 tiles on.
+constexpr int64_t kIgemmMinBigTiles = 160, kIgemmCus = 256;
+
 template <int N>
-__device__ __forceinline__ void g_wait_loads() {
-  static_assert(N == 0 || N == 2 || N == 3 || N == 4 || N == 6, "load queue depths used below");
-  if (N == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
-  else if (N == 4) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-  else if (N == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
-  else if (N == 2) asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+__device__ __forceinline__ void g_wait_loads() {   // until at most N of the wavefront's loads are outstanding
+  static_assert(N >= 0 && N < 64, "the counter's range");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// TN = 128: tiles of 128 pixels x 128 channels, wavefronts 2 (pixels) x 4 (channels);
-// TN = 64 : tiles of 256 pixels x  64 channels, wavefronts 4 x 2.
-// LDS: A stages at 0 (TM rows of 64 bytes, 16-byte chunk c of row r in slot c ^ ((r >> 2) & 3)), B stages behind
-// them (TN rows, same layout); an LDS-direct load fills one 1 KB block = 16 rows.
-template <int TN, bool I8>
+// Tiles of TM pixels x TN channels, eight wavefronts:
+//   128 x 128: wavefronts 2 (pixels) x 4 (channels), each 64 x 32;
+//   256 x  64: wavefronts 4 x 2, each 64 x 32;
+//   256 x 128: wavefronts 4 x 2, each 64 x 64 -- 24 KB staged per 2.1 Mflop of a K tile instead of 16 KB per 1.05,
+//              for shapes whose staging rate (the LDS-direct loads fill about 45 bytes per clock and CU) and not
+//              the matrix cores bounds the smaller tiles.
+// A K tile is one filter tap x KB bytes of channels (64, or 128 where the channel count allows: whole 128-byte
+// lines per pixel, half as many requests and barriers per byte).
+// LDS: A stages at 0 (TM rows of KB bytes; 16-byte chunk c of row r in slot c ^ ((r >> 2) & 3) for 64-byte rows,
+// c ^ ((r >> 1) & 7) for 128-byte rows), B stages behind them (TN rows, same layout); an LDS-direct load fills one
+// 1 KB block = 16 or 8 rows.
+template <int TM, int TN, bool I8, int KB>
 __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p, const unsigned char* __restrict__ I,
                                                             const unsigned char* __restrict__ F, void* __restrict__ O,
                                                             const float* __restrict__ bias) {
-  constexpr int TM = TN == 128 ? 128 : 256;
-  constexpr int WN = TN / 32;                 // wavefronts side by side along the channels
-  constexpr int LA = TM / 128;                // 1 KB A blocks per wavefront and K tile
-  constexpr int LPT = LA + 1;                 // loads per wavefront and K tile (one B block each)
-  constexpr int A_STAGE = TM * 64, B_STAGE = TN * 64, B0 = 4 * A_STAGE;
+  static_assert((TM == 128 && TN == 128) || (TM == 256 && (TN == 64 || TN == 128)), "instantiated tiles");
+  constexpr int FB = TM * TN / (8 * 64 * 32); // 32-channel fragments of a wavefront's tile (its pixels: always 64)
+  constexpr int WN = TN / (32 * FB);          // wavefronts side by side along the channels
+  static_assert(KB == 64 || KB == 128, "K tile rows");
+  constexpr int RPB = 1024 / KB;              // rows of a 1 KB block
+  constexpr int LPR = KB / 16;                // lanes (16-byte chunks) per row
+  constexpr int LA = TM / RPB / 8;            // 1 KB A blocks per wavefront and K tile
+  constexpr int NBB = TN / RPB;               // B blocks per K tile
+  constexpr int LB = NBB > 8 ? NBB / 8 : 1;   // of them per wavefront
+  constexpr int LPT = LA + LB;                // loads per wavefront and K tile
+  constexpr int KS = KB / 32;                 // matrix-instruction K steps per K tile
+  constexpr int A_STAGE = TM * KB, B_STAGE = TN * KB, B0 = 4 * A_STAGE;
+  auto key = [](int row) { return KB == 64 ? ((row >> 2) & 3) : ((row >> 1) & 7); };
   constexpr int ES = I8 ? 1 : 2;              // bytes per input element
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6, wn = wv % WN, wm = wv / WN;
@@ -107,8 +122,8 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
   unsigned rmask[LA], cmask[LA];
 #pragma unroll
   for (int u = 0; u < LA; ++u) {
-    const int row = 16 * (wv + 8 * u) + (lane >> 2);
-    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    const int row = RPB * (wv + 8 * u) + lane / LPR;
+    const int chunk = (lane % LPR) ^ key(row);
     int m = tm * TM + row;
     if (m >= p.m_total) m = p.m_total - 1;    // rows past the end repeat the last pixel; they are never stored
     const int x = m % p.Wo, q = m / p.Wo, y = q % p.Ho, n = q / p.Ho;
@@ -127,25 +142,26 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
     cmask[u] = cm;
   }
   // ---- B side: the lane's filter row (an output channel; rows past Co repeat the last one, never stored)
-  const int bb = wv % (TN / 16);              // with TN = 64 wavefronts 4..7 repeat the loads of 0..3 (same bytes, same place)
-  const unsigned char* b_base;
-  {
-    const int row = 16 * bb + (lane >> 2);
-    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+  const unsigned char* b_base[LB];
+#pragma unroll
+  for (int u = 0; u < LB; ++u) {
+    const int bb = (wv + 8 * u) % NBB;        // fewer blocks than wavefronts: 4..7 repeat the loads of 0..3 (same bytes, same place)
+    const int row = RPB * bb + lane / LPR;
+    const int chunk = (lane % LPR) ^ key(row);
     int gn = tn * TN + row;
     if (gn >= p.Co) gn = p.Co - 1;
-    b_base = F + (p.f_base + (int64_t)gn * p.f_k) * ES + chunk * 16;
+    b_base[u] = F + (p.f_base + (int64_t)gn * p.f_k) * ES + chunk * 16;
   }
   // the K tile the next issue() fetches: filter tap (ti, tj), channel chunk tc, and its byte offsets in the image and
-  // the filter, advanced by additions (all wave-uniform): next chunk +64; next filter column: back to chunk 0 and one
+  // the filter, advanced by additions (all wave-uniform): next chunk +KB; next filter column: back to chunk 0 and one
   // column on; next filter row: back to column 0 and one row on
   int ti = 0, tj = 0, tc = 0;
   int64_t a_off = 0, b_off = 0;
   const unsigned char* zero_chunk = igemm_zero_chunk;
   asm volatile("" : "+s"(zero_chunk));   // held in registers: the compiler would otherwise re-read its address from memory for every K tile
-  const int64_t a_col = (int64_t)p.dil_x * p.i_x * ES - (int64_t)(p.chunks - 1) * 64, b_col = p.f_s * ES - (int64_t)(p.chunks - 1) * 64;
-  const int64_t a_row = (int64_t)p.dil_y * p.i_y * ES - (int64_t)(p.S - 1) * p.dil_x * p.i_x * ES - (int64_t)(p.chunks - 1) * 64;
-  const int64_t b_row = p.f_r * ES - (int64_t)(p.S - 1) * p.f_s * ES - (int64_t)(p.chunks - 1) * 64;
+  const int64_t a_col = (int64_t)p.dil_x * p.i_x * ES - (int64_t)(p.chunks - 1) * KB, b_col = p.f_s * ES - (int64_t)(p.chunks - 1) * KB;
+  const int64_t a_row = (int64_t)p.dil_y * p.i_y * ES - (int64_t)(p.S - 1) * p.dil_x * p.i_x * ES - (int64_t)(p.chunks - 1) * KB;
+  const int64_t b_row = p.f_r * ES - (int64_t)(p.S - 1) * p.f_s * ES - (int64_t)(p.chunks - 1) * KB;
   auto issue = [&](int stage) {
 #pragma unroll
     for (int u = 0; u < LA; ++u) {
@@ -153,7 +169,8 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
       const void* src = inside ? (const void*)(a_base[u] + a_off) : (const void*)zero_chunk;
       g_load_lds16(src, stage * A_STAGE + (wv + 8 * u) * 1024);
     }
-    g_load_lds16(b_base + b_off, B0 + stage * B_STAGE + bb * 1024);
+#pragma unroll
+    for (int u = 0; u < LB; ++u) g_load_lds16(b_base[u] + b_off, B0 + stage * B_STAGE + ((wv + 8 * u) % NBB) * 1024);
     if (++tc == p.chunks) {
       tc = 0;
       if (++tj == p.S) {
@@ -166,55 +183,69 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
         b_off += b_col;
       }
     } else {
-      a_off += 64;
-      b_off += 64;
+      a_off += KB;
+      b_off += KB;
     }
   };
 
   // ---- fragments: lane supplies row (lane & 31) and 16-byte chunk 2 * s + (lane >> 5) of K step s
   const int fr = lane & 31, fh = lane >> 5;
-  const unsigned a_fr = (unsigned)((wm * 64 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
-  const unsigned b_fr = (unsigned)(B0 + (wn * 32 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
-  auto read_frags = [&](int stage, int s, g_bf16x8 (&af)[2], g_bf16x8& bf) {
+  const unsigned a_fr = (unsigned)((wm * 64 + fr) * KB + ((fh ^ key(fr)) << 4));
+  const unsigned b_fr = (unsigned)(B0 + (wn * 32 * FB + fr) * KB + ((fh ^ key(fr)) << 4));
+  auto read_frags = [&](int stage, int s, g_bf16x8 (&af)[2], g_bf16x8 (&bf)[FB]) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) af[q] = *(const g_bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * A_STAGE + q * 32 * 64);
-    bf = *(const g_bf16x8*)(lds + (b_fr ^ (unsigned)(s << 5)) + stage * B_STAGE);
+    for (int q = 0; q < 2; ++q) af[q] = *(const g_bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * A_STAGE + q * 32 * KB);
+#pragma unroll
+    for (int f = 0; f < FB; ++f) bf[f] = *(const g_bf16x8*)(lds + (b_fr ^ (unsigned)(s << 5)) + stage * B_STAGE + f * 32 * KB);
   };
 
-  g_f32x16 acc[2];
+  g_f32x16 acc[2][FB];
 #pragma unroll
   for (int q = 0; q < 2; ++q)
 #pragma unroll
-    for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
+    for (int f = 0; f < FB; ++f)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[q][f][v] = 0.f;
 
   const int k_tiles = p.k_tiles;   // >= 1
+  // The ring holds four K tiles.  During iteration kt the wavefronts multiply tile kt from registers and read the
+  // fragments of tile kt+1 (a whole tile ahead, so that an LDS read has an iteration to land before the matrix
+  // cores need it); tile kt+2 must have landed by the iteration's end, tile kt+3 is in flight, and after the
+  // barrier, when nobody reads tile kt any more, its slot takes tile kt+4.
   issue(0);
   if (k_tiles > 1) issue(1);
   if (k_tiles > 2) issue(2);
-  if (k_tiles > 2) g_wait_loads<2 * LPT>();
-  else if (k_tiles > 1) g_wait_loads<LPT>();
+  if (k_tiles > 3) issue(3);
+  if (k_tiles > 3) g_wait_loads<2 * LPT>();      // tiles 0 and 1 have landed
+  else if (k_tiles > 2) g_wait_loads<LPT>();
   else g_wait_loads<0>();
   __syncthreads();
-  g_bf16x8 af[2][2], bf[2];
-  read_frags(0, 0, af[0], bf[0]);
-  for (int kt = 0; kt < k_tiles; ++kt) {
-    const int stage = kt & 3;
-    G_FENCE();
-    read_frags(stage, 1, af[1], bf[1]);
+  g_bf16x8 af[2][KS][2], bf[2][KS][FB];          // [tile parity][K step]
 #pragma unroll
-    for (int q = 0; q < 2; ++q) acc[q] = g_mma<I8>(af[0][q], bf[0], acc[q]);
+  for (int ks = 0; ks < KS; ++ks) read_frags(0, ks, af[0][ks], bf[0][ks]);
+  __syncthreads();   // (the compiler waits for these reads here, and so knows in the loop that only the reads ahead are outstanding)
+  auto iteration = [&](int kt, g_bf16x8 (&ca)[KS][2], g_bf16x8 (&cb)[KS][FB], g_bf16x8 (&na)[KS][2], g_bf16x8 (&nb)[KS][FB]) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      G_FENCE();
+      // unconditional: behind the last tile this reads a stale ring slot and nobody uses it; under a condition the
+      // compiler would make the matrix instructions wait for the reads ahead as well
+      read_frags((kt + 1) & 3, ks, na[ks], nb[ks]);
+#pragma unroll
+      for (int q = 0; q < 2; ++q)
+#pragma unroll
+        for (int f = 0; f < FB; ++f) acc[q][f] = g_mma<I8>(ca[ks][q], cb[ks][f], acc[q][f]);
+    }
     G_FENCE();
-    // tile kt+1 must have landed (its loads were issued two tiles ago); after the barrier every wavefront is done
-    // with tile kt-1, whose ring slot then takes tile kt+3
-    if (kt + 2 >= k_tiles) g_wait_loads<0>();
-    else g_wait_loads<LPT>();
+    if (kt + 3 < k_tiles) g_wait_loads<LPT>();   // all but tile kt+3: tile kt+2 has landed
+    else g_wait_loads<0>();
     __syncthreads();
-    if (kt + 3 < k_tiles) issue((kt + 3) & 3);
+    if (kt + 4 < k_tiles) issue(kt & 3);
     G_FENCE();
-    if (kt + 1 < k_tiles) read_frags((kt + 1) & 3, 0, af[0], bf[0]);
-#pragma unroll
-    for (int q = 0; q < 2; ++q) acc[q] = g_mma<I8>(af[1][q], bf[1], acc[q]);
-    G_FENCE();
+  };
+  for (int kt = 0; kt < k_tiles; kt += 2) {
+    iteration(kt, af[0], bf[0], af[1], bf[1]);
+    if (kt + 1 < k_tiles) iteration(kt + 1, af[1], bf[1], af[0], bf[0]);
   }
 
   // ---- store.  The ring is no longer needed: its first bytes take the output offset of each of the tile's pixels
@@ -244,19 +275,20 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
     // temporary of the two statements never exists in memory).
     unsigned char* buf = lds + TM * 8 + wv * 4096;
     const int sp = lane >> 3, sc = lane & 7;
-    const int k0 = tn * TN + wn * 32 + sc * 4;   // the lane's four output channels
-    float b4[4] = {0.f, 0.f, 0.f, 0.f};
-    if (!I8 && p.epi) {
 #pragma unroll
-      for (int e = 0; e < 4; ++e)
-        if (k0 + e < p.Co) b4[e] = bias[k0 + e];
-    }
+    for (int qf = 0; qf < 2 * FB; ++qf) {
+      const int q = qf % 2, f = qf / 2;
+      const int k0 = tn * TN + (wn * FB + f) * 32 + sc * 4;   // the lane's four output channels
+      float b4[4] = {0.f, 0.f, 0.f, 0.f};
+      if (!I8 && p.epi) {
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
+        for (int e = 0; e < 4; ++e)
+          if (k0 + e < p.Co) b4[e] = bias[k0 + e];
+      }
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
         const int pixel = 8 * (v / 4) + 4 * fh + (v % 4);
-        *(float*)(buf + pixel * 128 + ((((fr >> 2) ^ (pixel & 7)) << 4) | ((fr & 3) << 2))) = acc[q][v];
+        *(float*)(buf + pixel * 128 + ((((fr >> 2) ^ (pixel & 7)) << 4) | ((fr & 3) << 2))) = acc[q][f][v];
       }
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -305,18 +337,19 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
     }
     return;
   }
-  const int k = tn * TN + wn * 32 + fr;       // the lane's output channel
-  if (k >= p.Co) return;
-  float b1 = 0.f;
-  if (!I8 && p.epi) b1 = bias[k];
 #pragma unroll
-  for (int q = 0; q < 2; ++q)
+  for (int qf = 0; qf < 2 * FB; ++qf) {
+    const int q = qf % 2, f = qf / 2;
+    const int k = tn * TN + (wn * FB + f) * 32 + fr;   // the lane's output channel
+    if (k >= p.Co) continue;
+    float b1 = 0.f;
+    if (!I8 && p.epi) b1 = bias[k];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int row = wm * 64 + 32 * q + 8 * (v / 4) + (v % 4) + 4 * fh;
       const int64_t off = out_off[row];
       if (off < 0) continue;
-      float val = acc[q][v];
+      float val = acc[q][f][v];
       if (!I8 && p.epi) val = __builtin_fmaxf(val + b1, 0.f);
       if (!I8 && p.out_bf16) {
         const uint32_t u = __float_as_uint(val);
@@ -325,6 +358,7 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
         __builtin_nontemporal_store(val, (float*)O + off + k);   // int32 results travel as bit patterns
       }
     }
+  }
 }
 
 }  // namespace
@@ -349,9 +383,12 @@ bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLa
   // indexes (pixel, channel, reduction); a tile's views are its TM x Kt slice of gathered input and its TN x Kt
   // slice of the filter, Kt = the four K tiles the ring holds; cost = 128-byte lines staged per multiply-accumulate,
   // overflow of ragged tiles included.  A range shorter than the tile is padded to one tile (the kernel computes
-  // the padding and discards it) while the work stays the real one.  Candidates are the two instantiated tiles;
-  // ties go to fewer tiles.  STRIPE_TUNE conv_igemm_tn = 64 / 128 overrides the choice.
-  int tn = 0;
+  // the padding and discards it) while the work stays the real one.  Candidates are the instantiated tiles; the
+  // largest, 256 x 128 with one workgroup per CU, only where its tiles cover most of the chip's 256 CUs and no more
+  // (the model has no term for idle CUs or for rounds of workgroups; measured: 196 such tiles beat 392 of 128 x 128,
+  // 392 of them lose to 784); ties go to fewer tiles.  STRIPE_TUNE conv_igemm_tn = 64 / 128, conv_igemm_tm =
+  // 128 / 256 and conv_igemm_kb = 64 / 128 override the choices.
+  int tn = 0, tm = 0;
   {
     const int64_t k_total = c.R * c.S * c.Ci, kt = std::min<int64_t>(4 * ck, k_total);
     stripe_tile_model_t m = {};
@@ -359,11 +396,16 @@ bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLa
     m.mem_cap_elems = kGfx950LdsCapBytes / (i8 ? 1 : 2);
     m.counted_refs = 3u;
     m.tiled_idx = 7u;
-    const int forced = tune_int("conv_igemm_tn", 0);
+    const int forced = tune_int("conv_igemm_tn", 0), forced_tm = tune_int("conv_igemm_tm", 0);
     double best = 0;
     int64_t best_tiles = 0;
-    for (int cand : {128, 64}) {
-      const int64_t tile[3] = {cand == 128 ? 128 : 256, cand, kt};
+    const int cands[3][2] = {{256, 128}, {128, 128}, {256, 64}};
+    for (const auto& cd : cands) {
+      const int cand = cd[1], cand_tm = cd[0];
+      if (cand == 128 && forced_tm && forced_tm != cand_tm) continue;
+      const int64_t big_tiles = ((m_total + 255) / 256) * ((c.Co + 127) / 128);
+      if (cand_tm == 256 && cand == 128 && forced_tm != 256 && (big_tiles < kIgemmMinBigTiles || big_tiles > kIgemmCus)) continue;
+      const int64_t tile[3] = {cand_tm, cand, kt};
       TileProblem pr;
       pr.range = {std::max<int64_t>(m_total, tile[0]), std::max<int64_t>(c.Co, tile[1]), k_total};
       TileRef a, b;
@@ -377,29 +419,35 @@ bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLa
       const double per_real_work = cost.cost * ((double)pr.range[0] / (double)m_total) * ((double)pr.range[1] / (double)c.Co);
       if (forced == cand) {
         tn = cand;
+        tm = cand_tm;
         break;
       }
       if (!cost.admissible) continue;
       if (!tn || per_real_work < best || (per_real_work == best && cost.tiles < best_tiles)) {
         tn = cand;
+        tm = cand_tm;
         best = per_real_work;
         best_tiles = cost.tiles;
       }
     }
-    if (!tn) tn = 128;
+    if (!tn) tn = 128, tm = 128;
   }
-  const int tm = tn == 128 ? 128 : 256;
   const int64_t tiles_m = (m_total + tm - 1) / tm, tiles_n = (c.Co + tn - 1) / tn;
   if (tiles_m * tiles_n > 0x7fffffffLL) return false;
-  l->variant = tn == 128 ? kConvIgemmVariant : kConvIgemmVariant + 1;
+  // 128-byte K tile rows where a tap's channels are whole 128-byte lines, on the 128 x 128 tile (four such stages of
+  // the 256-pixel tiles would not fit the LDS), for blocks of at most one tile per CU (128 KB: one workgroup per CU)
+  const int forced_kb = tune_int("conv_igemm_kb", 0);
+  const bool kb128 = (c.Ci * (i8 ? 1 : 2)) % 128 == 0 && tm == 128 && (forced_kb ? forced_kb == 128 : tiles_m * tiles_n <= kIgemmCus);
+  const int kb = kb128 ? 128 : 64;
+  l->variant = kConvIgemmVariant + (tn == 64 ? 1 : tm == 256 ? 2 : 0) + (kb128 ? 4 : 0);
   l->grid = tiles_m * tiles_n;
   info->path = STRIPE_PATH_MFMA_CONV;
-  info->tile_m = tm; info->tile_n = tn; info->tile_k = (int)ck;
+  info->tile_m = tm; info->tile_n = tn; info->tile_k = kb / (i8 ? 1 : 2);
   info->frag_m = 32; info->frag_n = 32; info->frag_k = i8 ? 32 : 16;
-  info->lds_bytes = 4 * (tm + tn) * 64;
+  info->lds_bytes = 4 * (tm + tn) * kb;
   info->workgroup_size = 512;
   info->grid = l->grid;
-  snprintf(info->kernel, sizeof info->kernel, "conv_igemm_%s_%dx%dx%d_mfma32x32x%d_w8_lds_direct%s", i8 ? "i8" : "bf16", tm, tn, (int)ck,
+  snprintf(info->kernel, sizeof info->kernel, "conv_igemm_%s_%dx%dx%d_mfma32x32x%d_w8_lds_direct%s", i8 ? "i8" : "bf16", tm, tn, kb / (i8 ? 1 : 2),
            i8 ? 32 : 16, (!i8 && out_bf16) ? "_obf16" : "");
   return true;
 }
@@ -419,18 +467,26 @@ hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_d
   p.stride_y = (int)c.stride_y; p.stride_x = (int)c.stride_x; p.pad_y = (int)c.pad_y; p.pad_x = (int)c.pad_x;
   p.dil_y = (int)c.dil_y; p.dil_x = (int)c.dil_x;
   p.m_total = (int)(c.N * c.Ho * c.Wo);
-  const int tn = l.variant == kConvIgemmVariant ? 128 : 64, tm = tn == 128 ? 128 : 256;
+  const int shape = (l.variant - kConvIgemmVariant) & 3, kb = ((l.variant - kConvIgemmVariant) & 4) ? 128 : 64;
+  const int tn = shape == 1 ? 64 : 128, tm = shape == 0 ? 128 : 256;
+  if (kb == 128 && shape != 0) return hipErrorInvalidValue;
   p.tiles_n = (int)((c.Co + tn - 1) / tn);
-  p.chunks = (int)(c.Ci / (i8 ? 64 : 32));
+  p.chunks = (int)(c.Ci * (i8 ? 1 : 2) / kb);
   p.k_tiles = (int)(c.R * c.S) * p.chunks;
   p.out_bf16 = out_bf16 ? 1 : 0;
   p.epi = bias ? 1 : 0;
   // one store per pixel and four channels where every such group starts on a 16-byte (bf16 output: 8-byte) boundary
   p.vec_out = (c.o_n % 4 == 0 && c.o_y % 4 == 0 && c.o_x % 4 == 0 && c.o_base % 4 == 0 && (uintptr_t)out % (out_bf16 ? 8 : 16) == 0) ? 1 : 0;
   typedef void (*kern_t)(const IgemmParams, const unsigned char*, const unsigned char*, void*, const float*);
-  const kern_t fn = tn == 128 ? (i8 ? (kern_t)conv_igemm_kernel<128, true> : (kern_t)conv_igemm_kernel<128, false>)
-                              : (i8 ? (kern_t)conv_igemm_kernel<64, true> : (kern_t)conv_igemm_kernel<64, false>);
-  const int lds_bytes = 4 * (tm + tn) * 64;   // the ring; the store phase needs tm * 8 + 8 * 4096 of it
+  kern_t fn;
+  if (kb == 64) {
+    fn = tn == 64    ? (i8 ? (kern_t)conv_igemm_kernel<256, 64, true, 64> : (kern_t)conv_igemm_kernel<256, 64, false, 64>)
+         : tm == 256 ? (i8 ? (kern_t)conv_igemm_kernel<256, 128, true, 64> : (kern_t)conv_igemm_kernel<256, 128, false, 64>)
+                     : (i8 ? (kern_t)conv_igemm_kernel<128, 128, true, 64> : (kern_t)conv_igemm_kernel<128, 128, false, 64>);
+  } else {
+    fn = i8 ? (kern_t)conv_igemm_kernel<128, 128, true, 128> : (kern_t)conv_igemm_kernel<128, 128, false, 128>;
+  }
+  const int lds_bytes = 4 * (tm + tn) * kb;   // the ring; the store phase needs tm * 8 + 8 * 4096 of it
   int dev = -1;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return e;

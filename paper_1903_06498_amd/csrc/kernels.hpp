@@ -47,7 +47,7 @@ hipError_t launch_gemm_bias_relu(const GemmShape& g, const GemmLaunch& l, const 
                                  int64_t o_m, int64_t o_base, bool out_bf16, hipStream_t stream);
 
 // ---- nested-tile convolution-shaped contraction on matrix cores -----------
-constexpr int kConvIgemmVariant = 300;   // 300: 128 x 128 tiles, 301: 256 x 64 tiles of the general convolution kernel
+constexpr int kConvIgemmVariant = 300;   // general convolution kernel; 300: 128 x 128 tiles, 301: 256 x 64, 302: 256 x 128
 struct ConvLaunch {
   int variant = -1;
   int64_t grid = 0;

@@ -394,17 +394,19 @@ def test_fused_convolution_bias_relu(N, H, Wd, out_dt, fuse, monkeypatch):
         assert " ; " in info["kernel"], info["kernel"]
 
 
-@pytest.mark.parametrize("fuse", [1, 0])
+@pytest.mark.parametrize("fuse", [1, 2, 0])
 @pytest.mark.parametrize("out_dt", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", [(2, 14, 14, 128, 128, 3, 1, 1), (2, 17, 19, 64, 128, 3, 2, 1), (1, 12, 40, 32, 96, 5, 1, 2),
                                    (3, 9, 11, 64, 36, 1, 1, 0), (1, 30, 30, 32, 64, 3, 2, 0)])
 def test_fused_convolution_bias_relu_general_kernel(shape, out_dt, fuse, monkeypatch):
     """The same two statements on shapes of the general matrix-core convolution kernel (channel counts, strides, filter
     extents and paddings the tuned kernel does not take; ragged pixel and channel tiles): fused into its store phase,
-    and unfused through a temporary; both against the oracle's serial evaluation."""
-    monkeypatch.setenv("STRIPE_TUNE", f"fuse={fuse}")
+    (fuse=2: on the kernel's largest tile, 256 pixels x 128 channels), and unfused through a temporary; all against
+    the oracle's serial evaluation."""
+    monkeypatch.setenv("STRIPE_TUNE", f"fuse={min(fuse, 1)}" + (",conv_igemm_tn=128,conv_igemm_tm=256" if fuse == 2 else ""))
     info = program_parity(*shape, "bf16", out_dt)
     if fuse:
+        assert fuse == 1 or "_256x128x" in info["kernel"], info["kernel"]
         assert info["kernel"].startswith("conv_igemm_bf16_") and info["kernel"].endswith("+bias_relu" + ("_bf16" if out_dt == "bf16" else "")), info
     else:
         assert " ; " in info["kernel"] and "conv_igemm_bf16_" in info["kernel"], info["kernel"]
@@ -952,13 +954,18 @@ IGEMM_CASES = {
 }
 
 
+@pytest.mark.parametrize("tile", ["chosen", "256x128", "128x128_k64"])
 @pytest.mark.parametrize("case", sorted(IGEMM_CASES))
-def test_conv_family_on_the_matrix_cores(case):
+def test_conv_family_on_the_matrix_cores(case, tile, monkeypatch):
     """Dense convolution-shaped blocks outside the two tuned shapes run on the general nested-tile kernel: other
     channel counts, filter extents, strides, image widths, ragged channel tiles, tiles that span rows and images.
     Position-sensitive first (a delta input reproduces the filter, exactly), then seeded data against the oracle."""
     N, H, Wd, Ci, Co, R, S, st, pad, dt = IGEMM_CASES[case]
     odt = "i32" if dt == "i8" else "f32"
+    if tile == "256x128":   # the largest tile, which the selector keeps for blocks of 160 to 256 such tiles
+        monkeypatch.setenv("STRIPE_TUNE", "conv_igemm_tn=128,conv_igemm_tm=256")
+    elif tile == "128x128_k64":   # 64-byte K tile rows, which blocks of more than 256 tiles take also where 128-byte rows are possible
+        monkeypatch.setenv("STRIPE_TUNE", "conv_igemm_tn=128,conv_igemm_tm=128,conv_igemm_kb=64")
     blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, st, pad, dt, odt)
     Ho, Wo = (H + 2 * pad - R) // st + 1, (Wd + 2 * pad - S) // st + 1
     f = W.seeded_tensor((R, S, Co, Ci), dt, 1)
@@ -967,6 +974,8 @@ def test_conv_family_on_the_matrix_cores(case):
     i[n0, y0, x0, c0] = 1
     gpu, sb = run_gpu(blk, [i, f], return_block=True)
     assert sb.info["path_name"] == "mfma_conv" and "conv_igemm" in sb.info["kernel"], sb.info
+    assert tile != "256x128" or "_256x128x" in sb.info["kernel"], sb.info
+    assert tile != "128x128_k64" or ("_128x128x64_" if dt == "i8" else "_128x128x32_") in sb.info["kernel"], sb.info
     say(f"conv family {case}: {sb.info['kernel']} grid {sb.info['grid']}")
     want = np.full((N, Ho, Wo, Co), float(SENTINEL_I) if dt == "i8" else float(np.float32(SENTINEL_F)), np.float64)
     for y in range(Ho):

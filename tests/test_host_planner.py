@@ -204,9 +204,14 @@ def test_tile_selection_follows_the_cost_model():
     assert kernel(W.maxpool_block(32, 112, 112, 64, 3, 1, 1)).endswith("3x3s1_ty4x4")   # stride 1 shares most: registers and L1
     assert "3x3s1_ty4" in kernel(W.depthwise_conv_block(32, 112, 112, 64, 3, 3, 1, 1, "f32"))   # measured best: 3 rows, 4 % ahead
     assert "256x64x32" in kernel(W.conv2d_block(4, 28, 28, 64, 32, 3, 3, 1, 1, "bf16", "f32"))
-    assert "128x128x32" in kernel(W.conv2d_block(4, 28, 28, 128, 128, 3, 3, 1, 1, "bf16", "f32"))
-    assert "128x128x32" in kernel(W.conv2d_block(4, 28, 28, 64, 96, 3, 3, 1, 1, "bf16", "f32"))
+    # (the K tile: 128-byte rows = 64 bf16 channels on the 128 x 128 tile where the block has at most one tile per CU)
+    assert "128x128x64" in kernel(W.conv2d_block(4, 28, 28, 128, 128, 3, 3, 1, 1, "bf16", "f32"))
+    assert "128x128x64" in kernel(W.conv2d_block(4, 28, 28, 64, 96, 3, 3, 1, 1, "bf16", "f32"))
+    assert "128x128x32" in kernel(W.conv2d_block(4, 28, 28, 32, 96, 3, 3, 1, 1, "bf16", "f32"))    # 32 channels: 64-byte rows
     assert "256x64x32" in kernel(W.conv2d_block(4, 28, 28, 128, 192, 3, 3, 1, 1, "bf16", "f32"))   # three 64-wide tiles waste nothing
+    # the largest tile where its tiles fill one round of workgroups: 196 of them here, 392 there (then 784 smaller ones, two per CU)
+    assert "256x128x32" in kernel(W.conv2d_block(32, 28, 28, 128, 192, 3, 3, 1, 1, "bf16", "f32"))
+    assert "128x128x32" in kernel(W.conv2d_block(16, 56, 56, 128, 256, 3, 3, 1, 1, "bf16", "f32"))
 
 
 def _two_statements(t_access_write, t_access_read, write_constraints=(), write_range=8):
