@@ -421,24 +421,27 @@ EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", 
                "conv3x3_bf16_w112", "conv5x5_bf16_32to32", "conv3x3_i8_64to64", "conv3x3_bf16_128to192", "conv3x3_bf16_128to256_56", "depthwise3x3_f32", "avgpool3x3s2_f32", "maxpool2x2s2_f32", "maxpool3x3s1_f32")
 
 
+# convolution shapes beyond the two tuned ones (the general matrix-core convolution kernel)
+CONV_FAMILY = {   # name: (N, H, W, Ci, Co, R, S, stride, pad, dtype)
+    "conv3x3_bf16_128to128": (32, 28, 28, 128, 128, 3, 3, 1, 1, "bf16"),
+    "conv3x3_s2_bf16_64to128": (32, 56, 56, 64, 128, 3, 3, 2, 1, "bf16"),
+    "conv1x7_bf16_64to64": (32, 56, 56, 64, 64, 1, 7, 1, 3, "bf16"),
+    "conv3x3_bf16_w112": (8, 112, 112, 64, 64, 3, 3, 1, 1, "bf16"),
+    "conv5x5_bf16_32to32": (32, 56, 56, 32, 32, 5, 5, 1, 2, "bf16"),
+    "conv3x3_i8_64to64": (32, 56, 56, 64, 64, 3, 3, 1, 1, "i8"),
+    "conv3x3_bf16_128to256_56": (16, 56, 56, 128, 256, 3, 3, 1, 1, "bf16"),   # 784 tiles of 128 x 128 (or 392 of 256 x 128: two rounds of workgroups)
+    "conv3x3_bf16_128to192": (32, 28, 28, 128, 192, 3, 3, 1, 1, "bf16"),   # 192 channels: one and a half 128-wide tiles or three 64-wide ones; 196 tiles of 256 x 128
+}
+
+
 def extra_block(name: str) -> Block:
     if name == "gemm_bf16_4096_bt":
         return matmul_block(4096, 4096, 4096, "bf16", "f32", b_transposed=True)
     if name in ("gemm_bf16_1024", "gemm_bf16_2048"):      # fewer 256 x 256 tiles than CUs: the 128 x 128-tile kernel
         n = int(name.rsplit("_", 1)[1])
         return matmul_block(n, n, n, "bf16", "f32")
-    family = {   # convolution shapes beyond the two tuned ones (the general matrix-core convolution kernel)
-        "conv3x3_bf16_128to128": (32, 28, 28, 128, 128, 3, 3, 1, 1, "bf16"),
-        "conv3x3_s2_bf16_64to128": (32, 56, 56, 64, 128, 3, 3, 2, 1, "bf16"),
-        "conv1x7_bf16_64to64": (32, 56, 56, 64, 64, 1, 7, 1, 3, "bf16"),
-        "conv3x3_bf16_w112": (8, 112, 112, 64, 64, 3, 3, 1, 1, "bf16"),
-        "conv5x5_bf16_32to32": (32, 56, 56, 32, 32, 5, 5, 1, 2, "bf16"),
-        "conv3x3_i8_64to64": (32, 56, 56, 64, 64, 3, 3, 1, 1, "i8"),
-        "conv3x3_bf16_128to256_56": (16, 56, 56, 128, 256, 3, 3, 1, 1, "bf16"),   # 392 tiles of 256 pixels x 128 channels: the largest tile's case
-        "conv3x3_bf16_128to192": (32, 28, 28, 128, 192, 3, 3, 1, 1, "bf16"),   # 192 channels: one and a half 128-wide tiles or three 64-wide ones
-    }
-    if name in family:
-        N, H, Wd, Ci, Co, R, S, st, pad, dt = family[name]
+    if name in CONV_FAMILY:
+        N, H, Wd, Ci, Co, R, S, st, pad, dt = CONV_FAMILY[name]
         return conv2d_block(N, H, Wd, Ci, Co, R, S, st, pad, dt, "i32" if dt == "i8" else "f32")
     if name == "maxpool2x2s2_f32":             # other windows over the max-pooling config's tensor
         return maxpool_block(32, 112, 112, 64, 2, 2, 0)

@@ -1027,6 +1027,41 @@ def test_conv_family_on_the_tuned_shapes(monkeypatch):
 
 
 # ------------------------------------------------------------------ convolution configs at full size
+CONV_FAMILY_KERNELS = {   # the benchmark's shapes of the general kernel and the tile / K tile row its selector gives them
+    "conv3x3_bf16_128to128": "_128x128x64_", "conv3x3_s2_bf16_64to128": "_128x128x64_", "conv1x7_bf16_64to64": "_256x64x32_",
+    "conv3x3_bf16_w112": "_256x64x32_", "conv5x5_bf16_32to32": "_256x64x32_", "conv3x3_i8_64to64": "_256x64x64_",
+    "conv3x3_bf16_128to192": "_256x128x32_", "conv3x3_bf16_128to256_56": "_128x128x32_",
+}
+
+
+@pytest.mark.parametrize("name", sorted(CONV_FAMILY_KERNELS))
+def test_conv_family_bench_shapes_full_size(name):
+    """The general kernel at the sizes and in the launch configurations bench.py times: all-ones operands give
+    Ci * (taps inside the image) exactly on every element (pixels without any are left as they were); seeded data against the oracle on two whole images (the
+    first, whose tiles start at pixel 0, and one in the middle, whose tiles straddle image borders)."""
+    N, H, Wd, Ci, Co, R, S, st, pad, dt = W.CONV_FAMILY[name]
+    blk, ins = W.extra_block(name), W.extra_inputs(name)
+    Ho, Wo = (H + 2 * pad - R) // st + 1, (Wd + 2 * pad - S) // st + 1
+    ones = [torch.ones_like(ins[0]), torch.ones_like(ins[1])]
+    gpu, sb = run_gpu(blk, ones, return_block=True)
+    say(f"{name}: {sb.info['kernel']} grid {sb.info['grid']}")
+    assert "conv_igemm" in sb.info["kernel"] and CONV_FAMILY_KERNELS[name] in sb.info["kernel"], sb.info
+    cy = np.array([taps(y, st, pad, R, H) for y in range(Ho)])
+    cx = np.array([taps(x, st, pad, S, Wd) for x in range(Wo)])
+    want = float(Ci) * cy[:, None] * cx[None, :]
+    want[want == 0] = float(SENTINEL_I) if dt == "i8" else float(np.float32(SENTINEL_F))   # no tap inside the image: no iteration writes the pixel
+    assert np.array_equal(gpu.reshape(N, Ho, Wo, Co).astype(np.float64), np.broadcast_to(want[None, :, :, None], (N, Ho, Wo, Co)))
+    gpu = run_gpu(blk, ins)
+    np_ins = [W.to_numpy(t).ravel() for t in ins]
+    np_abs = None if dt == "i8" else abs_inputs(np_ins, ["bf16", "bf16"])
+    for n in (0, N // 2 + 1):
+        lo, hi = [n, 0, 0, 0, 0, 0, 0], [n + 1, Ho, Wo, R, S, Ci, Co]
+        res = O.evaluate(blk, np_ins, window=(lo, hi), threads=16, split_index=1)
+        ares = None if np_abs is None else O.evaluate(blk, np_abs, window=(lo, hi), threads=16, split_index=1)
+        score = compare(blk, ins, gpu, res, what=f"{name} image {n}", abs_res=ares)
+        say(f"  image {n}: err/bound {score:.3f}")
+
+
 def test_resnet_conv_config_full_size():
     name = "resnet_conv_bf16"
     blk, ins = W.config_block(name), W.config_inputs(name)
