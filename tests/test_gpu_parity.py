@@ -1125,6 +1125,80 @@ def test_int8_conv_config_full_size():
     assert np.array_equal(gpu, np.broadcast_to(want[None, :, :, None], gpu.shape))
 
 
+# ------------------------------------------------------------------ the benchmark's further workloads at full size
+def _bands(extent, width):
+    """Index bands at the start, around an unaligned middle and at the end."""
+    if extent <= 3 * width:
+        return [(0, extent)]
+    mid = extent // 2 + 3
+    return [(0, width), (mid, mid + width), (extent - width, extent)]
+
+
+BENCH_FURTHER = ["gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32", "gemm_bf16_1024",
+                 "gemm_bf16_2048", "gemm_bf16_256x256x65536", "gemm_i8_256x256x65536_bt", "gemm_bf16_1024x1024x8192", "depthwise3x3_f32",
+                 "avgpool3x3s2_f32", "maxpool2x2s2_f32", "maxpool3x3s1_f32"]
+
+
+@pytest.mark.parametrize("name", BENCH_FURTHER)
+def test_bench_further_workloads_full_size(name):
+    """bench.py's further single-statement workloads at the sizes and in the launch configurations it times, against
+    the oracle on bands of the first index (for the products also of the second) that reach over every tile of the
+    other indexes: first, an unaligned middle, last."""
+    blk, ins = W.extra_block(name), W.extra_inputs(name)
+    gpu, sb = run_gpu(blk, ins, return_block=True)
+    say(f"{name}: {sb.info['kernel']} grid {sb.info['grid']} path {sb.info['path_name']}")
+    assert sb.info["path_name"] != "generic" or name == "transposed_conv_f32", sb.info
+    lv = blk
+    while not lv.idx_names:
+        lv = lv.child
+    ranges = list(lv.ranges)
+    points = math.prod(ranges)
+    np_ins = [W.to_numpy(t).ravel() for t in ins]
+    in_dts = [r.dtype for r in blk.refs if r.dir == "in"]
+    np_abs = abs_inputs(np_ins, in_dts) if in_dts[0] == "bf16" else None
+    banded = [0, 1] if lv.idx_names[:3] == ["m", "n", "k"] else [0]
+    for ax in banded:
+        width = max(1, min(ranges[ax], int(3e8 / (points / ranges[ax]))))
+        for a, b in _bands(ranges[ax], width):
+            lo, hi = [0] * len(ranges), list(ranges)
+            lo[ax], hi[ax] = a, b
+            split = 1 if ax == 0 else 0          # the index the oracle's threads share out: an output index apart from the band's
+            if name == "transposed_conv_f32":
+                split = len(ranges) - 1          # O[2y+i, 2x+j]: y and i write the same elements, k does not
+            res = O.evaluate(blk, np_ins, window=(lo, hi), threads=16, split_index=split)
+            ares = None if np_abs is None else O.evaluate(blk, np_abs, window=(lo, hi), threads=16, split_index=split)
+            score = compare(blk, ins, gpu, res, what=f"{name} index {ax} in [{a}, {b})", abs_res=ares)
+            say(f"  index {lv.idx_names[ax]} in [{a}, {b}): {res.n_points} points, score {score:.3g}")
+
+
+def test_bench_fused_programs_full_size(monkeypatch):
+    """The two-statement workloads of bench.py beyond the ResNet-shaped one: the 128 -> 128 convolution + bias + relu
+    on every element against the oracle's serial evaluation; the 4096^3 linear layer fused against the same
+    program run as two launches (the product and the pointwise statement, each covered at full size on its own):
+    the same sums in the same order, so equal bit for bit."""
+    name = "conv3x3_bias_relu_bf16_128to128"
+    prog, ins = W.extra_block(name), W.extra_inputs(name)
+    fused, sb = run_gpu(prog, ins, return_block=True)
+    say(f"{name}: {sb.info['kernel']}")
+    assert sb.info["kernel"].startswith("conv_igemm_bf16_") and sb.info["kernel"].endswith("+bias_relu_bf16"), sb.info["kernel"]
+    res = O.evaluate_program(prog, [W.to_numpy(t).ravel() for t in ins], threads=16)
+    assert res.touched.all()
+    err = np.abs(fused.astype(np.float64) - res.out)
+    tol = 4e-3 * math.sqrt(1152) * float(ins[0].float().abs().max()) * float(ins[1].float().abs().max()) + 2.0 ** -8 * np.abs(res.out)
+    assert np.all(err <= tol), float(np.max(err - tol))
+    assert (fused == 0).any() and (fused > 0).any()
+    name = "linear_bias_relu_4096"
+    prog, ins = W.extra_block(name), W.extra_inputs(name)
+    fused, sb = run_gpu(prog, ins, return_block=True)
+    say(f"{name}: {sb.info['kernel']}")
+    assert "+bias_relu" in sb.info["kernel"] and " ; " not in sb.info["kernel"], sb.info["kernel"]
+    monkeypatch.setenv("STRIPE_TUNE", "fuse=0")
+    unfused, sb = run_gpu(prog, ins, return_block=True)
+    assert " ; " in sb.info["kernel"], sb.info["kernel"]
+    assert np.array_equal(fused, unfused)
+    assert (fused == 0).any() and (fused > 0).any()
+
+
 # ------------------------------------------------------------------ yardsticks
 @pytest.mark.parametrize("from_lds", [False, True])
 def test_matrix_core_yardstick_closed_form(from_lds):
