@@ -972,28 +972,46 @@ __global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const
 // Split reduction (Section 2.1, last paragraph; Definition 2 rule 3: an aggregation may be regrouped because the
 // operation is associative and commutative).  A product with few output tiles and a long reduction index is run
 // as S products over K / S each -- the batch mechanism of the kernels above, every slice writing its own M x N
-// image of partial sums into a workspace -- and this kernel adds the S images in slice order, so the result does
+// image of partial sums into a workspace -- and this kernel adds the S images in a fixed order, so the result does
 // not depend on scheduling: integer sums are exact, float sums are reproducible from run to run.
+// Where the output is small (few items, many slices) a thread per item would add its S values one after the other
+// from a handful of workgroups, bound by the latency of the loads; then G threads share an item, each adding a run
+// of consecutive slices, and the G sums meet in LDS, again in slice order.
 // ---------------------------------------------------------------------------
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const T* __restrict__ part, T* __restrict__ C, int64_t M, int64_t N, int64_t c_m,
-                                                            int64_t c_base, int S) {
+                                                            int64_t c_base, int S, int G) {
   typedef T vec_t __attribute__((ext_vector_type(VEC)));
+  __shared__ vec_t partial[256];
   const int64_t per_row = N / VEC, total = M * per_row, image = M * N;
-  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
-    const int64_t m = e / per_row, n = (e - m * per_row) * VEC;
+  const int items = 256 / G;                      // items of a workgroup; G is a power of two, at most 16
+  const int grp = (int)threadIdx.x / items, it = (int)threadIdx.x % items;
+  const int run = (S + G - 1) / G, first = grp * run, last = first + run < S ? first + run : S;
+  for (int64_t base = (int64_t)blockIdx.x * items; base < total; base += (int64_t)gridDim.x * items) {
+    const int64_t e = base + it;
+    const bool valid = e < total;
+    const int64_t m = valid ? e / per_row : 0, n = valid ? (e - m * per_row) * VEC : 0;
     const T* src = part + m * N + n;
-    vec_t acc = *(const vec_t*)src;
-    int sl = 1;
-    for (; sl + 8 <= S; sl += 8) {   // eight loads in flight, added in slice order
-      vec_t v[8];
+    vec_t acc = {};
+    if (valid) {
+      int sl = first;
+      for (; sl + 8 <= last; sl += 8) {   // eight loads in flight, added in slice order
+        vec_t v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load((const vec_t*)(src + (int64_t)(sl + u) * image));
+        for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load((const vec_t*)(src + (int64_t)(sl + u) * image));
 #pragma unroll
-      for (int u = 0; u < 8; ++u) acc += v[u];
+        for (int u = 0; u < 8; ++u) acc += v[u];
+      }
+      for (; sl < last; ++sl) acc += __builtin_nontemporal_load((const vec_t*)(src + (int64_t)sl * image));
     }
-    for (; sl < S; ++sl) acc += __builtin_nontemporal_load((const vec_t*)(src + (int64_t)sl * image));
-    *(vec_t*)(C + c_base + m * c_m + n) = acc;
+    if (G > 1) {
+      partial[threadIdx.x] = acc;
+      __syncthreads();
+      if (grp == 0)
+        for (int q = 1; q < G; ++q) acc += partial[q * items + it];
+      __syncthreads();
+    }
+    if (valid && grp == 0) *(vec_t*)(C + c_base + m * c_m + n) = acc;
   }
 }
 
@@ -1218,13 +1236,18 @@ hipError_t launch_gemm(const GemmShape& g, const GemmLaunch& l, const void* a, c
   const bool i8 = (l.variant >= 40 && l.variant < 50) || l.variant == 52;
   const bool vec4 = g.N % 4 == 0 && g.c_m % 4 == 0 && g.c_base % 4 == 0 && ((uintptr_t)c % 16) == 0;
   const int64_t items = g.M * (vec4 ? g.N / 4 : g.N);
-  const unsigned blocks = (unsigned)((items + 255) / 256 < 8192 ? (items + 255) / 256 : 8192);
+  int G = 1;                                            // threads per item: enough workgroups to fill the chip
+  while (G < 16 && 2 * G <= l.split_k && items * G < 1024 * 256) G *= 2;
+  G = tune_int("gemm_reduce_g", G);
+  if (G < 1 || G > 16 || (G & (G - 1))) return hipErrorInvalidValue;
+  const int64_t wgs = (items * G + 255) / 256;
+  const unsigned blocks = (unsigned)(wgs < 8192 ? wgs : 8192);
   if (i8) {
-    if (vec4) hipLaunchKernelGGL((splitk_reduce_kernel<int, 4>), dim3(blocks), dim3(256), 0, st, (const int*)workspace, (int*)c, g.M, g.N, g.c_m, g.c_base, l.split_k);
-    else hipLaunchKernelGGL((splitk_reduce_kernel<int, 1>), dim3(blocks), dim3(256), 0, st, (const int*)workspace, (int*)c, g.M, g.N, g.c_m, g.c_base, l.split_k);
+    if (vec4) hipLaunchKernelGGL((splitk_reduce_kernel<int, 4>), dim3(blocks), dim3(256), 0, st, (const int*)workspace, (int*)c, g.M, g.N, g.c_m, g.c_base, l.split_k, G);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<int, 1>), dim3(blocks), dim3(256), 0, st, (const int*)workspace, (int*)c, g.M, g.N, g.c_m, g.c_base, l.split_k, G);
   } else {
-    if (vec4) hipLaunchKernelGGL((splitk_reduce_kernel<float, 4>), dim3(blocks), dim3(256), 0, st, (const float*)workspace, (float*)c, g.M, g.N, g.c_m, g.c_base, l.split_k);
-    else hipLaunchKernelGGL((splitk_reduce_kernel<float, 1>), dim3(blocks), dim3(256), 0, st, (const float*)workspace, (float*)c, g.M, g.N, g.c_m, g.c_base, l.split_k);
+    if (vec4) hipLaunchKernelGGL((splitk_reduce_kernel<float, 4>), dim3(blocks), dim3(256), 0, st, (const float*)workspace, (float*)c, g.M, g.N, g.c_m, g.c_base, l.split_k, G);
+    else hipLaunchKernelGGL((splitk_reduce_kernel<float, 1>), dim3(blocks), dim3(256), 0, st, (const float*)workspace, (float*)c, g.M, g.N, g.c_m, g.c_base, l.split_k, G);
   }
   return hipGetLastError();
 }

@@ -772,7 +772,10 @@ def test_gemm_small_tile_kernel(M, N, K, bt, waves, monkeypatch):
                                               (128, 256, 16384, "i8", True, ""), (200, 136, 8192, "bf16", False, ""),
                                               (300, 264, 4096, "i8", True, ""), (256, 384, 1536, "bf16", False, "gemm_splitk=3"),
                                               (512, 512, 2048, "bf16", True, "gemm_splitk=2,gemm_t128=0"),
-                                              (256, 256, 1024, "i8", True, "gemm_splitk=4")])
+                                              (256, 256, 1024, "i8", True, "gemm_splitk=4"),
+                                              # threads per output item in the kernel that adds the slices: one, more than slices, some
+                                              (256, 256, 16384, "bf16", False, "gemm_reduce_g=1"), (256, 384, 1536, "bf16", False, "gemm_splitk=3,gemm_reduce_g=16"),
+                                              (300, 264, 4096, "i8", True, "gemm_reduce_g=4"), (70, 9, 8192, "bf16", True, "gemm_reduce_g=8")])
 def test_split_reduction(M, N, K, dt, bt, tune, monkeypatch):
     """A product with few output tiles and a long reduction index: the reduction is cut into slices that run as
     separate workgroups, partial sums go through the handle's workspace and are added in slice order.  int8
