@@ -432,10 +432,10 @@ stripe_status_t run_single(stripe_block* blk, const void* const* inputs, void* o
   const void* in0 = inputs[0];
   const void* in1 = blk->n_inputs > 1 ? inputs[1] : nullptr;
   hipError_t e = hipSuccess;
-  if (p.info.path != STRIPE_PATH_GENERIC &&
-      (((uintptr_t)in0 % 16) || (in1 && ((uintptr_t)in1 % 16)) || ((uintptr_t)output % (p.info.path == STRIPE_PATH_MFMA_GEMM ? 4 : 16))))
+  const bool out4 = p.info.path == STRIPE_PATH_MFMA_GEMM || (p.info.path == STRIPE_PATH_MFMA_CONV && blk->conv.variant >= kConvIgemmVariant);
+  if (p.info.path != STRIPE_PATH_GENERIC && (((uintptr_t)in0 % 16) || (in1 && ((uintptr_t)in1 % 16)) || ((uintptr_t)output % (out4 ? 4 : 16))))
     return fail(STRIPE_ERR_MISALIGNED, "this handle was planned for a kernel family that moves 16 bytes per lane: input pointers (and, except for "
-                                       "dense contractions, the output pointer) must be 16-byte aligned");
+                                       "dense contractions and the general convolution kernel, the output pointer) must be 16-byte aligned");
   switch (p.info.path) {
     case STRIPE_PATH_MFMA_GEMM: e = launch_gemm(p.gemm, blk->gemm, in0, in1, output, ws, s); break;
     case STRIPE_PATH_MFMA_CONV: e = launch_conv(p.conv, blk->conv, in0, in1, output, s); break;
@@ -481,7 +481,9 @@ stripe_status_t create_single(const stripe_block_desc_t* desc, stripe_path_t pat
   if (!p.noop) {
     const bool forced = path != STRIPE_PATH_AUTO;
     bool picked = false;
-    switch (p.info.path) {
+    // a narrow product runs as a 1x1 convolution on the general convolution kernel, whose 256 x 64 tile it fills
+    if (!forced && p.info.path == STRIPE_PATH_MFMA_GEMM) picked = conv_select_narrow_product(p.gemm, p.in_dtype, &p.conv, &blk->conv, &p.info);
+    if (!picked) switch (p.info.path) {
       case STRIPE_PATH_MFMA_GEMM: picked = gemm_select(p.gemm, p.in_dtype, &blk->gemm, &p.info); break;
       case STRIPE_PATH_MFMA_CONV: picked = conv_select(p.conv, p.in_dtype, &blk->conv, &p.info); break;
       case STRIPE_PATH_POOL: picked = pool_select(p.pool, p.in_dtype, &blk->pool, &p.info); break;

@@ -747,6 +747,27 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
   return conv_igemm_select(c, in_dtype, false, l, info);
 }
 
+// A dense product C[m][n] = sum_k A[m][k] * B[n][k] with at most 64 columns would leave three quarters of the
+// contraction kernels' 256-wide tiles (half of the 128-wide ones) to padding.  Seen as a 1 x 1 convolution -- rows of
+// A are the pixels, K the input channels, N the output channels -- it fits the general convolution kernel's
+// 256 x 64 tile exactly.  Fills *c and picks that kernel, or returns false (then the contraction kernels take it).
+bool conv_select_narrow_product(const GemmShape& g, int in_dtype, Conv2dShape* c, ConvLaunch* l, stripe_block_info_t* info) {
+  if (tune_int("gemm_narrow_conv", 1) == 0 || tune_int("conv_mfma", 1) == 0) return false;
+  if (g.batch != 1 || g.N > 64 || g.M < 64 * 256) return false;   // at least 64 tiles: shorter products keep the contraction kernels and their split reduction
+  if (g.a_k != 1 || g.b_k != 1 || g.c_n != 1) return false;   // K contiguous in both operands, N contiguous in the output
+  Conv2dShape s = {};
+  s.N = 1; s.Ho = 1; s.Wo = g.M; s.H = 1; s.W = g.M; s.Co = g.N; s.Ci = g.K; s.R = 1; s.S = 1;
+  s.stride_y = s.stride_x = 1; s.pad_y = s.pad_x = 0; s.dil_y = s.dil_x = 1;
+  s.i_n = 0; s.i_y = 0; s.i_x = g.a_m; s.i_c = 1;
+  s.f_r = 0; s.f_s = 0; s.f_k = g.b_n; s.f_c = 1;
+  s.o_n = 0; s.o_y = 0; s.o_x = g.c_m; s.o_k = 1;
+  s.i_base = g.a_base; s.f_base = g.b_base; s.o_base = g.c_base;
+  l->in_dtype = in_dtype;
+  if (!conv_igemm_select(s, in_dtype, false, l, info)) return false;
+  *c = s;
+  return true;
+}
+
 static bool conv3x3_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info) {
   if (in_dtype != STRIPE_BF16) return false;
   if (c.dil_y != 1 || c.dil_x != 1) return false;

@@ -55,6 +55,8 @@ struct ConvLaunch {
   mutable int lds_enabled_on = -1;
 };
 bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
+// a dense product with at most 64 columns and K-contiguous operands as a 1 x 1 convolution on the general kernel
+bool conv_select_narrow_product(const GemmShape& g, int in_dtype, Conv2dShape* c, ConvLaunch* l, stripe_block_info_t* info);
 hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t stream);
 // The 3x3 bf16 kernel fused with a following statement O = relu(T + bias[k]) (T = the convolution's output):
 // bias fp32 [64], out fp32 or bf16 in the convolution output's dense layout.

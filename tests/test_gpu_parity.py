@@ -843,6 +843,34 @@ def test_pointwise_convolution_runs_on_the_gemm_kernel():
     assert info["path_name"] == "mfma_gemm" and info["kernel"].endswith("_bt_ragged"), info
 
 
+@pytest.mark.parametrize("M,N,K,dt", [(16384, 64, 256, "bf16"), (20000, 40, 128, "bf16"), (16500, 9, 64, "bf16"), (16384, 64, 256, "i8"), (17000, 33, 128, "i8")])
+def test_narrow_product_runs_as_pointwise_convolution(M, N, K, dt, monkeypatch):
+    """C = A * B^T with at most 64 columns and many rows: planned onto the general convolution kernel's 256 x 64 tile
+    (rows as pixels) instead of the 256-wide tiles of the contraction kernels.  A selector operand takes each output
+    column from one k (the first operand must come through exactly), then seeded data against the oracle; with
+    gemm_narrow_conv=0 the contraction kernel gives the same integers / close floats."""
+    odt = "i32" if dt == "i8" else "f32"
+    blk = W.matmul_block(M, N, K, dt, odt, b_transposed=True)
+    tdt = torch.int8 if dt == "i8" else torch.bfloat16
+    a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(tdt)
+    sel = (torch.arange(N) * 37 + 5) % K
+    b = torch.zeros((N, K), dtype=tdt)
+    b[torch.arange(N), sel] = 1
+    gpu, sb = run_gpu(blk, [a, b], return_block=True)
+    assert sb.info["path_name"] == "mfma_conv" and "conv_igemm" in sb.info["kernel"] and "_256x64x" in sb.info["kernel"], sb.info
+    assert np.array_equal(gpu.reshape(M, N), a.float()[:, sel].numpy())
+    ins = [W.seeded_tensor((M, K), dt, 0), W.seeded_tensor((N, K), dt, 1)]
+    parity(blk, ins, threads=16, what=f"narrow product {M}x{N}x{K} {dt}")
+    narrow = run_gpu(blk, ins)
+    monkeypatch.setenv("STRIPE_TUNE", "gemm_narrow_conv=0")
+    wide, sb2 = run_gpu(blk, ins, return_block=True)
+    assert sb2.info["path_name"] in ("mfma_gemm", "generic"), sb2.info     # (a reduction shorter than the contraction kernels' ring: generic)
+    if dt == "i8":
+        assert np.array_equal(narrow, wide)
+    else:
+        assert np.allclose(narrow, wide, rtol=1e-4, atol=1e-3)
+
+
 def test_gemm_config_full_size():
     """4096^3 in the benchmark's launch configuration: oracle slabs + identity property."""
     name = "gemm_bf16_4096"
