@@ -44,7 +44,13 @@ struct PoolParams {
   int64_t i_n, i_y, i_x, o_n, o_y, o_x;  // element strides (channel stride is 1)
   int64_t i_base, o_base;
   int64_t w_base, w_r, w_s;              // weighted windows: element offset and tap strides of the weights
+  uint32_t bpr_mul, bpr_shr, ys_mul, ys_shr, c4_mul, c4_shr, step_;   // divisions by blocks_per_row, y_strips and C4 as multiply-high and shift (fast_div)
 };
+
+// n / d for 0 <= n < 2^31 without a division: with l = ceil(log2 d), p = 31 + l and mul = ceil(2^p / d) < 2^32,
+// floor(n * mul / 2^p) = floor(n / d), because mul * d - 2^p < d <= 2^(p - 31) adds less than 1 / d to n / d.
+// The host passes mul and shr = p - 32 (magic_of); mul = 0 stands for d = 1.
+__device__ __forceinline__ unsigned fast_div(unsigned n, uint32_t mul, uint32_t shr) { return mul ? __umulhi(n, mul) >> shr : n; }
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -271,12 +277,19 @@ __global__ __launch_bounds__(1024) void pool_f32_strip_kernel(const PoolParams p
   // A workgroup keeps its 128 (column, channel-quad) items and walks over strips (image, row strip) with the
   // grid's stride: gridDim.x = blocks_per_row * (strips walked side by side), so everything that depends on the
   // column is computed once.  Fewer, longer-lived workgroups stream better than one short workgroup per strip.
-  const unsigned b = logical_block(p.xcd_remap, blockIdx.x, gridDim.x);
-  const int bx = b % p.blocks_per_row;
+  // A workgroup lives for a few thousand cycles, so what precedes its first load counts: the arguments are all
+  // fetched at once (the compiler would fetch them group by group where first used, one memory latency each), and
+  // the quotients come from multiplications.
+  const unsigned grid_x = gridDim.x, strips_per_wg = blockDim.y;
+  asm volatile("" ::"s"(p.N), "s"(p.items), "s"(p.i_n), "s"(p.o_n), "s"(p.i_base), "s"(p.o_base), "s"(p.bpr_mul), "s"(p.ys_mul), "s"(p.ys_shr),
+               "s"(p.c4_mul), "s"(p.c4_shr), "s"(p.step_), "s"(grid_x), "s"(strips_per_wg), "s"(in), "s"(out));
+  const unsigned b = logical_block(p.xcd_remap, blockIdx.x, grid_x);
+  const unsigned brow = fast_div(b, p.bpr_mul, p.bpr_shr);
+  const int bx = (int)(b - brow * (unsigned)p.blocks_per_row);
   const int item = bx * 128 + threadIdx.x;
   if (item >= p.items) return;
-  const int c4 = item % p.C4;
-  const int xo = item / p.C4;
+  const int xo = (int)fast_div((unsigned)item, p.c4_mul, p.c4_shr);
+  const int c4 = item - xo * p.C4;
   uint32_t voff[S];
   bool xv[S];
 #pragma unroll
@@ -289,10 +302,10 @@ __global__ __launch_bounds__(1024) void pool_f32_strip_kernel(const PoolParams p
   const uint32_t ooff = ((uint32_t)xo * (uint32_t)p.o_x + (uint32_t)c4 * 4u) * 4u;
   // blockDim.y strips per workgroup (threadIdx.y picks one: row bases stay wave-uniform), gridDim.x / blocks_per_row
   // such workgroups side by side
-  const int strips = p.N * p.y_strips, step = (int)(gridDim.x / (unsigned)p.blocks_per_row) * (int)blockDim.y;
-  for (int rest = (int)(b / (unsigned)p.blocks_per_row) * (int)blockDim.y + (int)threadIdx.y; rest < strips; rest += step) {
-    const int ys = rest % p.y_strips;
-    const int n = rest / p.y_strips;
+  const int strips = p.N * p.y_strips, step = (int)p.step_ * (int)strips_per_wg;
+  for (int rest = (int)brow * (int)strips_per_wg + (int)threadIdx.y; rest < strips; rest += step) {
+    const int n = (int)fast_div((unsigned)rest, p.ys_mul, p.ys_shr);
+    const int ys = rest - n * p.y_strips;
     const char* ib = (const char*)(in + p.i_base + (int64_t)n * p.i_n);
     char* ob = (char*)(out + p.o_base + (int64_t)n * p.o_n);
     const int yo0 = ys * TY;
@@ -417,17 +430,23 @@ template <int R, int S, int ST, int TY, int WMODE>
 __global__ __launch_bounds__(512) void window_weighted_f32_kernel(const PoolParams p, const float* __restrict__ in,
                                                                  const float* __restrict__ wgt, float* __restrict__ out) {
   constexpr int NR = ST * (TY - 1) + R;
-  const unsigned b = logical_block(p.xcd_remap, blockIdx.x, gridDim.x);
-  const int bx = b % p.blocks_per_row;
+  // (arguments fetched at once and quotients by multiplication, as in the strip kernel)
+  const unsigned grid_x = gridDim.x, strips_per_wg = blockDim.y;
+  if constexpr (WMODE == 2)
+    asm volatile("" ::"s"(p.N), "s"(p.items), "s"(p.i_n), "s"(p.o_n), "s"(p.i_base), "s"(p.o_base), "s"(p.w_base), "s"(p.bpr_mul), "s"(p.ys_mul),
+                 "s"(p.ys_shr), "s"(p.c4_mul), "s"(p.c4_shr), "s"(grid_x), "s"(strips_per_wg), "s"(in), "s"(wgt), "s"(out));
+  const unsigned b = logical_block(p.xcd_remap, blockIdx.x, grid_x);
+  const unsigned brow = fast_div(b, p.bpr_mul, p.bpr_shr);
+  const int bx = (int)(b - brow * (unsigned)p.blocks_per_row);
   // blockDim.y strips side by side per workgroup, one per 128 lanes (they share input rows through L1)
-  const int rest = (int)(b / (unsigned)p.blocks_per_row) * (int)blockDim.y + (int)threadIdx.y;
+  const int rest = (int)brow * (int)strips_per_wg + (int)threadIdx.y;
   if (rest >= p.N * p.y_strips) return;
-  const int ys = rest % p.y_strips;
-  const int n = rest / p.y_strips;
+  const int n = (int)fast_div((unsigned)rest, p.ys_mul, p.ys_shr);
+  const int ys = rest - n * p.y_strips;
   const int item = bx * 128 + threadIdx.x;
   if (item >= p.items) return;
-  const int c4 = item % p.C4;
-  const int xo = item / p.C4;
+  const int xo = (int)fast_div((unsigned)item, p.c4_mul, p.c4_shr);
+  const int c4 = item - xo * p.C4;
   uint32_t voff[S];
   bool xv[S];
 #pragma unroll
@@ -486,6 +505,20 @@ __global__ __launch_bounds__(512) void window_weighted_f32_kernel(const PoolPara
   }
 }
 
+// multiplier and shift of fast_div for the divisor d >= 1
+static void magic_of(int64_t d, uint32_t* mul, uint32_t* shr) {
+  if (d <= 1) {
+    *mul = 0;
+    *shr = 0;
+    return;
+  }
+  int l = 0;
+  while (((int64_t)1 << l) < d) ++l;
+  const int pw = 31 + l;
+  *mul = (uint32_t)((((unsigned __int128)1 << pw) + (unsigned __int128)d - 1) / (unsigned __int128)d);
+  *shr = (uint32_t)(pw - 32);
+}
+
 PoolParams make_params(const Pool2dShape& s, int ty, int wg) {
   PoolParams p;
   p.N = (int)s.N; p.H = (int)s.H; p.W = (int)s.W; p.Ho = (int)s.Ho; p.Wo = (int)s.Wo; p.C4 = (int)(s.C / 4);
@@ -502,6 +535,10 @@ PoolParams make_params(const Pool2dShape& s, int ty, int wg) {
   p.i_n = s.i_n; p.i_y = s.i_y; p.i_x = s.i_x; p.o_n = s.o_n; p.o_y = s.o_y; p.o_x = s.o_x;
   p.i_base = s.i_base; p.o_base = s.o_base;
   p.w_base = s.w_base; p.w_r = s.w_r; p.w_s = s.w_s;
+  magic_of(p.blocks_per_row, &p.bpr_mul, &p.bpr_shr);
+  magic_of(p.y_strips, &p.ys_mul, &p.ys_shr);
+  magic_of(p.C4, &p.c4_mul, &p.c4_shr);
+  p.step_ = 0;   // workgroups side by side (grid / blocks_per_row): set at launch
   return p;
 }
 
@@ -512,7 +549,9 @@ constexpr int kTyChoices[] = {1, 2, 3, 4, 7};
 template <int TY, bool NT>
 hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* out, hipStream_t st, bool lean, int yb) {
   if (lean && !NT) {
-    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, 0>), dim3((unsigned)grid), dim3(128, yb), 0, st, p, (const float*)in, (float*)out);
+    PoolParams q = p;
+    q.step_ = (uint32_t)(grid / p.blocks_per_row);
+    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, 0>), dim3((unsigned)grid), dim3(128, yb), 0, st, q, (const float*)in, (float*)out);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((pool_max_f32_kernel<3, 3, 2, TY, NT>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
@@ -635,7 +674,9 @@ hipError_t launch_lds_rows(int rows, int lds_bytes, const PoolParams& p, dim3 g,
 }
 
 template <int R, int S, int ST, int MODE>
-hipError_t launch_strip_rows(int ty, int yb, const PoolParams& p, dim3 g, const float* i, float* o, hipStream_t st) {
+hipError_t launch_strip_rows(int ty, int yb, const PoolParams& p_, dim3 g, const float* i, float* o, hipStream_t st) {
+  PoolParams p = p_;
+  p.step_ = g.x / (unsigned)p.blocks_per_row;
   switch (ty) {
     case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 1, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
     case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 2, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
