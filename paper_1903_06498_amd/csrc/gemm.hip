@@ -16,6 +16,8 @@
 // reads (16 bytes per lane) spread over all banks.
 #include <hip/hip_runtime.h>
 
+#include <string>
+
 #include "kernels.hpp"
 
 namespace stripe {
@@ -842,17 +844,33 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
 // M and N multiples of 128, K a multiple of 128 (256 for int8).  MODE as in the large-tile kernel: D_BT for a
 // transposed B (its tile then lies in LDS like A's), D_I8 for int8 operands with int32 accumulation.
 // ---------------------------------------------------------------------------
-constexpr int T_BM = 128, T_BN = 128, T_A_STAGE = T_BM * 64, T_B_STAGE = D_BK * T_BN * 2, T_B0 = D_STAGES * T_A_STAGE;
-constexpr int T_LDS = D_STAGES * (T_A_STAGE + T_B_STAGE);   // 64 KB
+constexpr int T_BM = 128, T_BN = 128;
+constexpr int t128_lds_bytes(int kb) { return D_STAGES * (T_BM + T_BN) * kb; }   // 64 KB, or 128 KB with 128-byte K tile rows
+
+template <int N>
+__device__ __forceinline__ void t_wait_loads() {   // until at most N of the wavefront's loads are outstanding
+  static_assert(N >= 0 && N < 64, "the counter's range");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
 
 // W8: eight wavefronts (2 along m x 4 along n, 64 x 32 each) instead of four (128 x 32 each): two wavefronts per
 // SIMD, so that one's waits (LDS latency, barrier) are covered by the other's matrix instructions.
-template <int MODE, int W8 = 0>
+// KB: bytes of a K tile row of A (and of a transposed B): 64, or 128 -- K tiles of 64 instead of 32 deep, half as
+// many barriers per matrix instruction, whole 128-byte lines per row -- where one workgroup per CU covers the
+// product anyway (the ring then takes 128 KB).
+template <int MODE, int W8 = 0, int KB = 64>
 __global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const GemmParams p, const uint16_t* __restrict__ A,
                                                                          const uint16_t* __restrict__ B, float* __restrict__ C) {
+  static_assert(KB == 64 || KB == 128, "K tile rows");
   constexpr int NW = 4 * (1 + W8);          // wavefronts
   constexpr int NF = 4 / (1 + W8);          // A fragments (32 rows each) per wavefront
-  constexpr int LPW = 2 / (1 + W8);         // 1 KB load blocks per wavefront, per operand and K tile
+  constexpr int BKE = KB / 2;               // depth of a K tile in 16-bit elements
+  constexpr int T_A_STAGE = T_BM * KB, T_B_STAGE = T_BN * KB, T_B0 = D_STAGES * T_A_STAGE;
+  constexpr int LPW = T_A_STAGE / 1024 / NW;   // 1 KB load blocks per wavefront, per operand and K tile
+  constexpr int LPT = 2 * LPW;                 // loads per wavefront and K tile
+  constexpr int KS = KB / 32;                  // matrix-instruction K steps per K tile
+  constexpr int RPB = 1024 / KB, LPR = KB / 16;   // rows of a 1 KB block of A, lanes per row
+  auto key = [](int row) { return KB == 64 ? ((row >> 2) & 3) : ((row >> 1) & 7); };
   extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
   typedef __attribute__((address_space(3))) s16x4* lptr;
   const int t = threadIdx.x, lane = t & 63, wv = t >> 6, wn = wv & 3, wm = wv >> 2;
@@ -867,8 +885,8 @@ __global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const
   const uint16_t* a_src;
   const uint16_t* b_src;
   {
-    const int row = 16 * wv + (lane >> 2);              // + 16*NW*u
-    const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+    const int row = RPB * wv + lane / LPR;              // + RPB*NW*u
+    const int chunk = (lane % LPR) ^ key(row);
     a_src = A + p.a_base + ((int64_t)tm * T_BM + row) * p.a_m + chunk * 8;
     if constexpr (MODE & D_BT) {
       b_src = B + p.b_base + ((int64_t)tn * T_BN + row) * p.b_k + chunk * 8;
@@ -878,11 +896,11 @@ __global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const
       b_src = B + p.b_base + (int64_t)k * p.b_k + (int64_t)tn * T_BN + bchunk * 8;
     }
   }
-  const size_t a_step = (size_t)(16 * NW) * p.a_m, b_step = (MODE & D_BT) ? (size_t)(16 * NW) * p.b_k : (size_t)(4 * NW) * p.b_k,
-               b_kstep = (MODE & D_BT) ? (size_t)D_BK : (size_t)D_BK * p.b_k;
+  const size_t a_step = (size_t)(RPB * NW) * p.a_m, b_step = (MODE & D_BT) ? (size_t)(RPB * NW) * p.b_k : (size_t)(4 * NW) * p.b_k,
+               b_kstep = (MODE & D_BT) ? (size_t)BKE : (size_t)BKE * p.b_k;
   const unsigned wave_lds = wv * 1024;
   auto issue = [&](int stage, int kt) {
-    const uint16_t* a = a_src + (size_t)kt * D_BK;
+    const uint16_t* a = a_src + (size_t)kt * BKE;
     const uint16_t* b = b_src + (size_t)kt * b_kstep;
 #pragma unroll
     for (int u = 0; u < LPW; ++u) d_load_lds16(a + u * a_step, stage * T_A_STAGE + u * (NW * 1024) + wave_lds);
@@ -891,18 +909,18 @@ __global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const
   };
   // fragment addresses
   const int fr = lane & 31, fh = lane >> 5;
-  const unsigned a_fr = (unsigned)((wm * 64 * W8 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
+  const unsigned a_fr = (unsigned)((wm * 64 * W8 + fr) * KB + ((fh ^ key(fr)) << 4));
   unsigned b_fr;
   {
     const int g = lane >> 4, pl = lane & 15;
     const int k = 8 * (g >> 1) + (pl >> 2);
     const int low2 = 2 * (g & 1) + ((pl & 3) >> 1);
     b_fr = (unsigned)(T_B0 + k * 256 + (((wn * 4 + low2) ^ (4 * (k & 3))) << 4) + (pl & 1) * 8);
-    if constexpr (MODE & D_BT) b_fr = (unsigned)(T_B0 + (wn * 32 + fr) * 64 + ((fh ^ ((fr >> 2) & 3)) << 4));
+    if constexpr (MODE & D_BT) b_fr = (unsigned)(T_B0 + (wn * 32 + fr) * KB + ((fh ^ key(fr)) << 4));
   }
   auto read_frags = [&](int stage, int s, bf16x8 (&af)[NF], bf16x8& bf) {
 #pragma unroll
-    for (int q = 0; q < NF; ++q) af[q] = *(const bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * T_A_STAGE + q * 32 * 64);
+    for (int q = 0; q < NF; ++q) af[q] = *(const bf16x8*)(lds + (a_fr ^ (unsigned)(s << 5)) + stage * T_A_STAGE + q * 32 * KB);
     if constexpr (MODE & D_BT) {
       bf = *(const bf16x8*)(lds + (b_fr ^ (unsigned)(s << 5)) + stage * T_B_STAGE);
     } else {
@@ -919,34 +937,43 @@ __global__ __launch_bounds__(256 * (1 + W8), 1) void gemm_bf16_t128_kernel(const
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[q][v] = 0.f;
 
-  const int k_tiles = p.k_tiles;   // a multiple of 4, at least 4 (host)
+  const int k_tiles = p.k_tiles;   // at least 2 (host)
+  // The ring holds four K tiles.  During iteration kt the wavefronts multiply tile kt from registers and read the
+  // fragments of tile kt+1 (a whole tile ahead, so that an LDS read has an iteration to land before the matrix
+  // cores need it); tile kt+2 must have landed by the iteration's end, tile kt+3 is in flight, and after the
+  // barrier, when nobody reads tile kt any more, its slot takes tile kt+4.
   issue(0, 0);
   issue(1, 1);
-  issue(2, 2);
-  if (LPW == 2) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-  else asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
+  if (k_tiles > 2) issue(2, 2);
+  if (k_tiles > 3) issue(3, 3);
+  if (k_tiles > 3) t_wait_loads<2 * LPT>();      // tiles 0 and 1 have landed
+  else if (k_tiles > 2) t_wait_loads<LPT>();
+  else t_wait_loads<0>();
   __syncthreads();
-  bf16x8 af[2][NF], bf[2];
-  read_frags(0, 0, af[0], bf[0]);
-  for (int kt = 0; kt < k_tiles; ++kt) {
-    const int stage = kt & 3;
-    // K step 0 of this tile, while its K step 1 is read
-    D_FENCE();
-    read_frags(stage, 1, af[1], bf[1]);
+  bf16x8 af[2][KS][NF], bf[2][KS];               // [tile parity][K step]
 #pragma unroll
-    for (int q = 0; q < NF; ++q) acc[q] = d_mma<MODE>(af[0][q], bf[0], acc[q]);
+  for (int ks = 0; ks < KS; ++ks) read_frags(0, ks, af[0][ks], bf[0][ks]);
+  __syncthreads();   // (the compiler waits for these reads here, and so knows in the loop that only the reads ahead are outstanding)
+  auto iteration = [&](int kt, bf16x8 (&ca)[KS][NF], bf16x8 (&cb)[KS], bf16x8 (&na)[KS][NF], bf16x8 (&nb)[KS]) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      D_FENCE();
+      // unconditional: behind the last tile this reads a stale ring slot and nobody uses it; under a condition the
+      // compiler would make the matrix instructions wait for the reads ahead as well
+      read_frags((kt + 1) & 3, ks, na[ks], nb[ks]);
+#pragma unroll
+      for (int q = 0; q < NF; ++q) acc[q] = d_mma<MODE>(ca[ks][q], cb[ks], acc[q]);
+    }
     D_FENCE();
-    // tile kt+1 must have landed (its loads were issued two tiles ago); then the ring slot of tile kt-1 is free for kt+3
-    if (kt + 2 >= k_tiles) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    else if (LPW == 2) asm volatile("s_waitcnt vmcnt(4)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(2)" ::: "memory");
+    if (kt + 3 < k_tiles) t_wait_loads<LPT>();   // all but tile kt+3: tile kt+2 has landed
+    else t_wait_loads<0>();
     __syncthreads();
-    if (kt + 3 < k_tiles) issue((kt + 3) & 3, kt + 3);
+    if (kt + 4 < k_tiles) issue(kt & 3, kt + 4);
     D_FENCE();
-    if (kt + 1 < k_tiles) read_frags((kt + 1) & 3, 0, af[0], bf[0]);
-#pragma unroll
-    for (int q = 0; q < NF; ++q) acc[q] = d_mma<MODE>(af[1][q], bf[1], acc[q]);
-    D_FENCE();
+  };
+  for (int kt = 0; kt < k_tiles; kt += 2) {
+    iteration(kt, af[0], bf[0], af[1], bf[1]);
+    if (kt + 1 < k_tiles) iteration(kt + 1, af[1], bf[1], af[0], bf[0]);
   }
 
   if (!(MODE & D_I8) && p.epi) {   // fused relu(C + bias)
@@ -1084,6 +1111,24 @@ bool gemm_select(const GemmShape& g, int in_dtype, GemmLaunch* l, stripe_block_i
   if (!gemm_select_one(g, in_dtype, l, info)) return false;
   l->split_k = choose_split_k(g, in_dtype, *l);
   l->ws_bytes = 0;
+  l->t128_kb = 64;
+  if (l->variant >= 50 && l->t128_waves == 8) {
+    // 128-byte K tile rows (a 128 KB ring: one workgroup per CU) where one round of workgroups covers the product anyway
+    const int64_t final_grid = l->grid * (l->split_k > 1 ? l->split_k : 1) * (g.batch > 1 ? g.batch : 1);
+    const int forced = tune_int("gemm_t128_kb", 0);
+    if (forced ? forced == 128 : final_grid <= 256) {
+      l->t128_kb = 128;
+      info->tile_k *= 2;
+      info->lds_bytes = t128_lds_bytes(128);
+      char* at = strstr(info->kernel, in_dtype == STRIPE_I8 ? "128x128x64_" : "128x128x32_");
+      if (at) {   // the K tile's depth in the name: 32 -> 64 elements (int8: 64 -> 128; one character longer)
+        std::string name(info->kernel, at);
+        name += in_dtype == STRIPE_I8 ? "128x128x128_" : "128x128x64_";
+        name += at + 11;
+        snprintf(info->kernel, sizeof info->kernel, "%s", name.c_str());
+      }
+    }
+  }
   if (l->split_k > 1) {
     l->ws_bytes = (int64_t)l->split_k * g.M * g.N * 4;
     l->grid *= l->split_k;
@@ -1120,7 +1165,7 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
       info->path = STRIPE_PATH_MFMA_GEMM;
       info->tile_m = T_BM; info->tile_n = T_BN; info->tile_k = 64;
       info->frag_m = 32; info->frag_n = 32; info->frag_k = 32;
-      info->lds_bytes = T_LDS;
+      info->lds_bytes = t128_lds_bytes(64);
       info->workgroup_size = 64 * l->t128_waves;
       info->grid = l->grid;
       snprintf(info->kernel, sizeof info->kernel, "gemm_i8_128x128x64_mfma32x32x32_w%d_lds_direct_bt", l->t128_waves);
@@ -1156,7 +1201,7 @@ static bool gemm_select_one(const GemmShape& g, int in_dtype, GemmLaunch* l, str
     info->path = STRIPE_PATH_MFMA_GEMM;
     info->tile_m = T_BM; info->tile_n = T_BN; info->tile_k = D_BK;
     info->frag_m = 32; info->frag_n = 32; info->frag_k = 16;
-    info->lds_bytes = T_LDS;
+    info->lds_bytes = t128_lds_bytes(64);
     info->workgroup_size = 64 * l->t128_waves;
     info->grid = l->grid;
     snprintf(info->kernel, sizeof info->kernel, "gemm_bf16_128x128x32_mfma32x32x16_w%d_lds_direct%s", l->t128_waves, bt ? "_bt" : "");
@@ -1257,7 +1302,7 @@ static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const
   if (((uintptr_t)a % 16) || ((uintptr_t)b % 16) || ((uintptr_t)c % (epi == 2 ? 2 : 4))) return hipErrorInvalidValue;
   const bool i8 = (l.variant >= 40 && l.variant < 50) || l.variant == 52;
   const GemmParams p = make_params(g, i8);
-  const bool t128_w8 = l.variant >= 50 && l.t128_waves == 8;
+  const bool t128_w8 = l.variant >= 50 && l.t128_waves == 8, t128_kb128 = t128_w8 && l.t128_kb == 128;
   void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = nullptr;
   switch (l.variant) {
     case 0: case 1: case 2: kernel = gemm_bf16_w4_kernel; break;
@@ -1269,9 +1314,9 @@ static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const
     case 30 + D_BT: kernel = gemm_bf16_dma_kernel<4, 1, D_BT>; break;
     case 30 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_RAGGED>; break;
     case 30 + D_BT + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED>; break;
-    case 50: kernel = t128_w8 ? gemm_bf16_t128_kernel<0, 1> : gemm_bf16_t128_kernel<0, 0>; break;
-    case 51: kernel = t128_w8 ? gemm_bf16_t128_kernel<D_BT, 1> : gemm_bf16_t128_kernel<D_BT, 0>; break;
-    case 52: kernel = t128_w8 ? gemm_bf16_t128_kernel<D_BT + D_I8, 1> : gemm_bf16_t128_kernel<D_BT + D_I8, 0>; break;
+    case 50: kernel = t128_kb128 ? gemm_bf16_t128_kernel<0, 1, 128> : t128_w8 ? gemm_bf16_t128_kernel<0, 1> : gemm_bf16_t128_kernel<0, 0>; break;
+    case 51: kernel = t128_kb128 ? gemm_bf16_t128_kernel<D_BT, 1, 128> : t128_w8 ? gemm_bf16_t128_kernel<D_BT, 1> : gemm_bf16_t128_kernel<D_BT, 0>; break;
+    case 52: kernel = t128_kb128 ? gemm_bf16_t128_kernel<D_BT + D_I8, 1, 128> : t128_w8 ? gemm_bf16_t128_kernel<D_BT + D_I8, 1> : gemm_bf16_t128_kernel<D_BT + D_I8, 0>; break;
     case 40: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_I8>; break;
     case 40 + D_RAGGED: kernel = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED + D_I8>; break;
     case 10: kernel = gemm_bf16_w8_kernel<0>; break;
@@ -1279,9 +1324,9 @@ static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const
     default: kernel = gemm_bf16_w8_kernel<2>; break;
   }
   const int threads = (l.variant == 21 || (l.variant >= 10 && l.variant < 20) || t128_w8) ? THREADS : W4_THREADS;
-  const int lds_bytes = l.variant >= 50 ? T_LDS : l.variant >= 20 ? D_LDS : 2 * STAGE;
+  const int lds_bytes = l.variant >= 50 ? t128_lds_bytes(l.t128_kb) : l.variant >= 20 ? D_LDS : 2 * STAGE;
   GemmParams pk = p;
-  if (l.variant >= 20) pk.k_tiles = (int)(g.K / (i8 ? 64 : D_BK));
+  if (l.variant >= 20) pk.k_tiles = (int)(g.K / ((i8 ? 64 : D_BK) * (t128_kb128 ? 2 : 1)));
   pk.bias = bias;
   pk.epi = epi;
   pk.c_m = o_m;

@@ -32,6 +32,7 @@ hipError_t launch_generic_tiled(const Plan& plan, const void* in0, const void* i
 struct GemmLaunch {
   int variant = -1;
   int t128_waves = 4;   // wavefronts of the 128 x 128-tile kernel: 4 or 8
+  int t128_kb = 64;     // bytes of its K tile rows: 64, or 128 where one workgroup per CU covers the product
   int64_t grid = 0;
   int split_k = 1;       // slices of the reduction index, each run as one product of a batch into the workspace
   int64_t ws_bytes = 0;  // workspace launch_gemm needs: split_k images of M x N partial sums

@@ -655,7 +655,8 @@ def test_gemm_mfma_small(M, N, K):
                                        ("gemm_t128=0,gemm_dma_waves=8,gemm_epi16=1", "w8_lds_direct"),
                                        ("gemm_t128=0,gemm_sched=0", "w4_lds_direct_s0"), ("gemm_t128=0,gemm_sched=2", "w4_lds_direct_s2"),
                                        ("gemm_t128=0,gemm_sched=3", "w4_lds_direct_s3"),
-                                       ("gemm_t128=1", "128x128x32_mfma32x32x16_w8_lds_direct"),
+                                       ("gemm_t128=1", "128x128x64_mfma32x32x16_w8_lds_direct"),
+                                       ("gemm_t128=1,gemm_t128_kb=64", "128x128x32_mfma32x32x16_w8_lds_direct"),
                                        ("gemm_t128=1,gemm_t128_waves=4", "128x128x32_mfma32x32x16_w4_lds_direct"),
                                        ("gemm_dma=0,gemm_waves=4", "w4_swz2"), ("gemm_dma=0,gemm_waves=8,gemm_swz=1", "w8_swz1"),
                                        ("gemm_dma=0,gemm_waves=8,gemm_swz=0", "w8_swz0")])
@@ -700,14 +701,16 @@ def test_gemm_transposed_b_and_ragged_edges(M, N, K, bt, monkeypatch):
     parity(blk, ins, what=f"gemm {M}x{N}x{K} bt={bt}")          # also checks that nothing outside C[0:M, 0:N] changed
 
 
-@pytest.mark.parametrize("t128", [1, 0, -1])
+@pytest.mark.parametrize("t128", [1, 2, 0, -1])
 @pytest.mark.parametrize("M,N,K", [(256, 256, 256), (512, 768, 512), (300, 333, 256), (70, 9, 512), (257, 8, 256), (128, 384, 256)])
 def test_gemm_int8_transposed_b(M, N, K, t128, monkeypatch):
     """int8 x int8 -> int32 on the matrix cores (C = A * B^T, both operands k-contiguous): bit-exact, including
     extreme values (-128 * -128 summed over K) and edges that are not multiples of the tile; small aligned
-    products on the 128 x 128-tile kernel (t128=1) and on the 256 x 256 one (0; -1: with its 16-byte stores)."""
-    monkeypatch.setenv("STRIPE_TUNE", f"gemm_t128={max(t128, 0)},gemm_epi16={int(t128 < 0)}")
-    t128 = max(t128, 0)
+    products on the 128 x 128-tile kernel (t128=1: K tiles 128 deep, as chosen for products of one round of
+    workgroups; 2: 64 deep) and on the 256 x 256 one (0; -1: with its 16-byte stores)."""
+    monkeypatch.setenv("STRIPE_TUNE", f"gemm_t128={min(max(t128, 0), 1)},gemm_epi16={int(t128 < 0)}" + (",gemm_t128_kb=64" if t128 == 2 else ""))
+    deep = 64 if t128 == 2 else 128
+    t128 = min(max(t128, 0), 1)
     blk = W.matmul_block(M, N, K, "i8", "i32", b_transposed=True)
     a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.int8)
     sel = (torch.arange(N) + 37) % K
@@ -716,7 +719,7 @@ def test_gemm_int8_transposed_b(M, N, K, t128, monkeypatch):
     gpu, sb = run_gpu(blk, [a, b], return_block=True)
     ragged = M % 256 != 0 or N % 256 != 0
     small = bool(t128) and M % 128 == 0 and N % 128 == 0
-    want = "gemm_i8_128x128x64_mfma32x32x32_w8_lds_direct_bt" if small else "gemm_i8_256x256x64_mfma32x32x32_w4_lds_direct_bt" + ("_ragged" if ragged else "")
+    want = f"gemm_i8_128x128x{deep}_mfma32x32x32_w8_lds_direct_bt" if small else "gemm_i8_256x256x64_mfma32x32x32_w4_lds_direct_bt" + ("_ragged" if ragged else "")
     assert sb.info["path_name"] == "mfma_gemm" and sb.info["kernel"] == want, sb.info["kernel"]
     assert np.array_equal(gpu.reshape(M, N), a.to(torch.int32)[:, sel].numpy())
     ins = [W.seeded_tensor((M, K), "i8", 0), W.seeded_tensor((N, K), "i8", 1)]
@@ -750,19 +753,19 @@ def test_batched_gemm(batch, M, N, K, dtype, bt, shared):
     parity(blk, ins, what=f"batched gemm {batch}x{M}x{N}x{K} {dtype}")
 
 
-@pytest.mark.parametrize("waves", [8, 4])
-@pytest.mark.parametrize("M,N,K,bt", [(128, 128, 128, False), (384, 640, 256, True), (1024, 256, 384, False), (256, 1152, 128, True)])
-def test_gemm_small_tile_kernel(M, N, K, bt, waves, monkeypatch):
+@pytest.mark.parametrize("waves,deep", [(8, 64), (8, 32), (4, 32)])
+@pytest.mark.parametrize("M,N,K,bt", [(128, 128, 128, False), (384, 640, 256, True), (1024, 256, 384, False), (256, 1152, 128, True), (512, 384, 1152, False)])
+def test_gemm_small_tile_kernel(M, N, K, bt, waves, deep, monkeypatch):
     """Products with few 256 x 256 tiles run on the 128 x 128-tile kernel (row-major and transposed B, eight or four
-    wavefronts): position-sensitive operands exactly, then seeded data."""
-    monkeypatch.setenv("STRIPE_TUNE", f"gemm_t128_waves={waves}")
+    wavefronts, K tiles 64 or 32 deep): position-sensitive operands exactly, then seeded data."""
+    monkeypatch.setenv("STRIPE_TUNE", f"gemm_t128_waves={waves},gemm_t128_kb={2 * deep}")
     blk = W.matmul_block(M, N, K, "bf16", "f32", b_transposed=bt)
     a = ((torch.arange(M)[:, None] * 7 + torch.arange(K)[None, :] * 3) % 251 - 125).to(torch.bfloat16)
     sel = (torch.arange(N) + 37) % K
     b = torch.zeros((K, N), dtype=torch.bfloat16)
     b[sel, torch.arange(N)] = 1.0
     gpu, sb = run_gpu(blk, [a, b.t().contiguous() if bt else b], return_block=True)
-    assert sb.info["kernel"] == f"gemm_bf16_128x128x32_mfma32x32x16_w{waves}_lds_direct" + ("_bt" if bt else ""), sb.info["kernel"]
+    assert sb.info["kernel"] == f"gemm_bf16_128x128x{deep}_mfma32x32x16_w{waves}_lds_direct" + ("_bt" if bt else ""), sb.info["kernel"]
     assert np.array_equal(gpu.reshape(M, N), a.float()[:, sel].numpy())
     ins = [W.seeded_tensor((M, K), "bf16", 0), W.seeded_tensor((N, K) if bt else (K, N), "bf16", 1)]
     parity(blk, ins, what=f"small-tile gemm {M}x{N}x{K} bt={bt}")
