@@ -145,13 +145,15 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
   const unsigned char* b_base[LB];
 #pragma unroll
   for (int u = 0; u < LB; ++u) {
-    const int bb = (wv + 8 * u) % NBB;        // fewer blocks than wavefronts: 4..7 repeat the loads of 0..3 (same bytes, same place)
+    const int bb = (wv + 8 * u) % NBB;        // fewer blocks than wavefronts: only wavefronts 0 .. NBB-1 load B (loads_b)
     const int row = RPB * bb + lane / LPR;
     const int chunk = (lane % LPR) ^ key(row);
     int gn = tn * TN + row;
     if (gn >= p.Co) gn = p.Co - 1;
     b_base[u] = F + (p.f_base + (int64_t)gn * p.f_k) * ES + chunk * 16;
   }
+  // with fewer B blocks than wavefronts the higher wavefronts issue one load less per K tile; the waits below count accordingly
+  const bool loads_b = NBB >= 8 || __builtin_amdgcn_readfirstlane(wv) < NBB;
   // the K tile the next issue() fetches: filter tap (ti, tj), channel chunk tc, and its byte offsets in the image and
   // the filter, advanced by additions (all wave-uniform): next chunk +KB; next filter column: back to chunk 0 and one
   // column on; next filter row: back to column 0 and one row on
@@ -170,7 +172,8 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
       g_load_lds16(src, stage * A_STAGE + (wv + 8 * u) * 1024);
     }
 #pragma unroll
-    for (int u = 0; u < LB; ++u) g_load_lds16(b_base[u] + b_off, B0 + stage * B_STAGE + ((wv + 8 * u) % NBB) * 1024);
+    for (int u = 0; u < LB; ++u)
+      if (loads_b) g_load_lds16(b_base[u] + b_off, B0 + stage * B_STAGE + ((wv + 8 * u) % NBB) * 1024);
     if (++tc == p.chunks) {
       tc = 0;
       if (++tj == p.S) {
@@ -216,8 +219,13 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
   if (k_tiles > 1) issue(1);
   if (k_tiles > 2) issue(2);
   if (k_tiles > 3) issue(3);
-  if (k_tiles > 3) g_wait_loads<2 * LPT>();      // tiles 0 and 1 have landed
-  else if (k_tiles > 2) g_wait_loads<LPT>();
+  if (k_tiles > 3) {                             // tiles 0 and 1 have landed
+    if (loads_b) g_wait_loads<2 * LPT>();
+    else g_wait_loads<2 * LA>();
+  } else if (k_tiles > 2) {
+    if (loads_b) g_wait_loads<LPT>();
+    else g_wait_loads<LA>();
+  }
   else g_wait_loads<0>();
   __syncthreads();
   g_bf16x8 af[2][KS][2], bf[2][KS][FB];          // [tile parity][K step]
@@ -237,8 +245,9 @@ __global__ __launch_bounds__(512, 1) void conv_igemm_kernel(const IgemmParams p,
         for (int f = 0; f < FB; ++f) acc[q][f] = g_mma<I8>(ca[ks][q], cb[ks][f], acc[q][f]);
     }
     G_FENCE();
-    if (kt + 3 < k_tiles) g_wait_loads<LPT>();   // all but tile kt+3: tile kt+2 has landed
-    else g_wait_loads<0>();
+    if (kt + 3 >= k_tiles) g_wait_loads<0>();
+    else if (loads_b) g_wait_loads<LPT>();       // all but tile kt+3: tile kt+2 has landed
+    else g_wait_loads<LA>();
     __syncthreads();
     if (kt + 4 < k_tiles) issue(kt & 3);
     G_FENCE();
