@@ -26,6 +26,8 @@
 // the duplicate cannot change the result.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
+
 #include <algorithm>
 
 #include "kernels.hpp"
@@ -630,7 +632,12 @@ StripShape choose_strip_shape(const Pool2dShape& s, std::initializer_list<int> t
       stripe_tile_cost_t group;
       tile_cost_of(pr, wg_tile, wg, &group);
       const double l1 = lane.cost / vectors_per_row, l2 = group.cost / vectors_per_row;
-      const double cost = l2 * (1.0 + (double)lane.footprint_elems * kGfx950RegPenalty) + kGfx950L1AccessCost * l1;
+      double cost = l2 * (1.0 + (double)lane.footprint_elems * kGfx950RegPenalty) + kGfx950L1AccessCost * l1;
+      // occupancy cliff: the tile's registers plus about eight for addresses, in granules of eight, divide the SIMD's 512;
+      // under four wavefronts per SIMD the loads in flight no longer cover the memory latency (per-tap weights, four
+      // rows: 130 registers, three wavefronts, 52.7 us against 50.5 for three rows)
+      const int64_t regs = (lane.footprint_elems + 8 + 7) / 8 * 8, waves = regs > 0 ? 512 / regs : 8;
+      if (waves < 4) cost *= std::sqrt(4.0 / (double)(waves > 0 ? waves : 1));
       const int64_t workgroups = blocks_per_row * ((s.N * ((s.Ho + ty - 1) / ty) + yb - 1) / yb);
       const bool large = workgroups >= kGfx950MinWorkgroups;
       const bool better = !best.ty || (large && !best_large) ||
@@ -721,9 +728,9 @@ bool pool_select(const Pool2dShape& s, int dtype, PoolLaunch* l, stripe_block_in
     // weighted window: a scale (one element) or per-tap, per-channel weights with the channels contiguous (16-byte loads)
     if (mode != 2 || !row_offsets_fit) return false;
     if (s.w_mode == 2 && (s.w_c != 1 || s.w_r % 4 || s.w_s % 4 || s.w_base % 4)) return false;
-    // per-tap weights: strips side by side measured slower (3x3 stride 1, two rows per strip: 59.6 us alone, 66.8 us
-    // four side by side), so only the scaled sum takes them
-    const StripShape shape = s.w_mode == 2 ? choose_strip_shape(s, {1, 2, 3, 4}, {1}) : choose_strip_shape(s, {1, 2, 3, 4}, {1, 2, 4});
+    // per-tap weights: four strips side by side measured slower than two or one (3x3 stride 1: three rows per strip
+    // 50.5 us alone, 49.4 two side by side, 54.5 four), so only the scaled sum is offered four
+    const StripShape shape = s.w_mode == 2 ? choose_strip_shape(s, {1, 2, 3, 4}, {1, 2}) : choose_strip_shape(s, {1, 2, 3, 4}, {1, 2, 4});
     const int rows = shape.ty;
     const PoolParams p = make_params(s, rows, 128);
     if ((int64_t)p.N * p.y_strips * p.blocks_per_row > 0x7fffffffLL) return false;
