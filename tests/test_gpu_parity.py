@@ -988,6 +988,9 @@ IGEMM_CASES = {
     "3x3_i8_64to64": (2, 14, 14, 64, 64, 3, 3, 1, 1, "i8"),
     "5x5_s2_i8_128to72": (1, 19, 21, 128, 72, 5, 5, 2, 2, "i8"),
     "3x3_tiny_image": (1, 2, 3, 32, 8, 3, 3, 1, 1, "bf16"),
+    "1x1_64to128_one_k_tile": (2, 10, 10, 64, 128, 1, 1, 1, 0, "bf16"),      # 128-byte K tile rows: the whole reduction is one tile
+    "1x1_i8_128to72_one_k_tile": (1, 12, 9, 128, 72, 1, 1, 1, 0, "i8"),
+    "1x3_64to128_three_k_tiles": (1, 9, 20, 64, 128, 1, 3, 1, 1, "bf16"),
 }
 
 
