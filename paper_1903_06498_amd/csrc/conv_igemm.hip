@@ -6,11 +6,11 @@
 // The nesting of paper Section 3.1.3 (Figure 3's three columns), mapped by hand:
 //   outer block  -> one workgroup per tile of TM output pixels x TN output channels; the pixels of a tile are
 //                   consecutive in the flattened (n, y, x) order, so a tile may span rows and images;
-//   middle block -> the reduction (i, j, c) walked as K tiles of one filter tap x 64 bytes of channels, staged in a
+//   middle block -> the reduction (i, j, c) walked as K tiles of one filter tap x 64 or 128 bytes of channels, staged in a
 //                   four-stage LDS ring by LDS-direct loads: the A side gathers each pixel's channels for that tap
 //                   straight from the image (the view of Figure 5b, built by address arithmetic instead of a copy),
 //                   the B side takes the tap's [k][c] slice of the filter;
-//   inner block  -> v_mfma_f32_32x32x16_bf16 / v_mfma_i32_32x32x32_i8 fragments, 64 pixels x 32 channels per wavefront.
+//   inner block  -> v_mfma_f32_32x32x16_bf16 / v_mfma_i32_32x32x32_i8 fragments, 64 pixels x 32 or 64 channels per wavefront.
 // Constraints (padding) are realised per pixel and tap: a lane whose tap falls outside the image fetches 16 zero
 // bytes instead (adding zero is the identity of the sum), so interior and boundary tiles run the same code and no
 // per-point test reaches the matrix instructions (Section 2.3: keep the hot loop rectilinear).
