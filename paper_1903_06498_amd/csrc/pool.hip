@@ -274,7 +274,8 @@ __device__ __forceinline__ f32x4 fold(const f32x4* v) {
 
 template <int R, int S, int ST, int TY, int MODE>
 __global__ __launch_bounds__(1024) void pool_f32_strip_kernel(const PoolParams p, const float* __restrict__ in,
-                                                            float* __restrict__ out) {
+                                                            float* __restrict__ out, const float* __restrict__ scale) {
+  // scale: a sum (MODE 2) times one factor kept in a one-element buffer (average pooling), or NULL
   constexpr int NR = ST * (TY - 1) + R;
   // A workgroup keeps its 128 (column, channel-quad) items and walks over strips (image, row strip) with the
   // grid's stride: gridDim.x = blocks_per_row * (strips walked side by side), so everything that depends on the
@@ -284,7 +285,10 @@ __global__ __launch_bounds__(1024) void pool_f32_strip_kernel(const PoolParams p
   // the quotients come from multiplications.
   const unsigned grid_x = gridDim.x, strips_per_wg = blockDim.y;
   asm volatile("" ::"s"(p.N), "s"(p.items), "s"(p.i_n), "s"(p.o_n), "s"(p.i_base), "s"(p.o_base), "s"(p.bpr_mul), "s"(p.ys_mul), "s"(p.ys_shr),
-               "s"(p.c4_mul), "s"(p.c4_shr), "s"(p.step_), "s"(grid_x), "s"(strips_per_wg), "s"(in), "s"(out));
+               "s"(p.c4_mul), "s"(p.c4_shr), "s"(p.step_), "s"(grid_x), "s"(strips_per_wg), "s"(in), "s"(out), "s"(scale));
+  float factor = 1.f;
+  if constexpr (MODE == 2)
+    if (scale) factor = scale[p.w_base];
   const unsigned b = logical_block(p.xcd_remap, blockIdx.x, grid_x);
   const unsigned brow = fast_div(b, p.bpr_mul, p.bpr_shr);
   const int bx = (int)(b - brow * (unsigned)p.blocks_per_row);
@@ -343,7 +347,8 @@ __global__ __launch_bounds__(1024) void pool_f32_strip_kernel(const PoolParams p
     for (int ty = 0; ty < TY; ++ty) {
       const int yo = yo0 + ty;
       if (yo < p.Ho) {
-        const f32x4 res = fold<R, MODE>(hm + ty * ST);
+        f32x4 res = fold<R, MODE>(hm + ty * ST);
+        if constexpr (MODE == 2) res *= factor;
         if (p.stream_stores) __builtin_nontemporal_store(res, (f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff));
         else *(f32x4*)(ob + (int64_t)yo * p.o_y * 4 + ooff) = res;
       }
@@ -553,7 +558,7 @@ hipError_t launch_ty(const PoolParams& p, int64_t grid, const void* in, void* ou
   if (lean && !NT) {
     PoolParams q = p;
     q.step_ = (uint32_t)(grid / p.blocks_per_row);
-    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, 0>), dim3((unsigned)grid), dim3(128, yb), 0, st, q, (const float*)in, (float*)out);
+    hipLaunchKernelGGL((pool_f32_strip_kernel<3, 3, 2, TY, 0>), dim3((unsigned)grid), dim3(128, yb), 0, st, q, (const float*)in, (float*)out, (const float*)nullptr);
     return hipGetLastError();
   }
   hipLaunchKernelGGL((pool_max_f32_kernel<3, 3, 2, TY, NT>), dim3((unsigned)grid), dim3(128), 0, st, p, (const float*)in, (float*)out);
@@ -681,14 +686,14 @@ hipError_t launch_lds_rows(int rows, int lds_bytes, const PoolParams& p, dim3 g,
 }
 
 template <int R, int S, int ST, int MODE>
-hipError_t launch_strip_rows(int ty, int yb, const PoolParams& p_, dim3 g, const float* i, float* o, hipStream_t st) {
+hipError_t launch_strip_rows(int ty, int yb, const PoolParams& p_, dim3 g, const float* i, float* o, hipStream_t st, const float* w = nullptr) {
   PoolParams p = p_;
   p.step_ = g.x / (unsigned)p.blocks_per_row;
   switch (ty) {
-    case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 1, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
-    case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 2, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
-    case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 3, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
-    case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 4, MODE>), g, dim3(128, yb), 0, st, p, i, o); break;
+    case 1: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 1, MODE>), g, dim3(128, yb), 0, st, p, i, o, w); break;
+    case 2: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 2, MODE>), g, dim3(128, yb), 0, st, p, i, o, w); break;
+    case 3: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 3, MODE>), g, dim3(128, yb), 0, st, p, i, o, w); break;
+    case 4: hipLaunchKernelGGL((pool_f32_strip_kernel<R, S, ST, 4, MODE>), g, dim3(128, yb), 0, st, p, i, o, w); break;
     default: return hipErrorInvalidValue;
   }
   return hipGetLastError();
@@ -889,11 +894,12 @@ hipError_t launch_pool(const Pool2dShape& s, const PoolLaunch& l, const void* in
     const float *i = (const float*)in, *w = (const float*)weights;
     float* o = (float*)out;
     switch (l.variant - kWeightedVariant) {
-      case 0: return launch_weighted_rows<3, 3, 2, 1>(l.rows, l.yb, p, g, i, w, o, st);
+      // a scaled sum is the strip kernel's sum with one factor; per-tap weights have a kernel of their own
+      case 0: return tune_int("pool_scaled_strip", 1) ? launch_strip_rows<3, 3, 2, 2>(l.rows, l.yb, p, g, i, o, st, w) : launch_weighted_rows<3, 3, 2, 1>(l.rows, l.yb, p, g, i, w, o, st);
       case 1: return launch_weighted_rows<3, 3, 2, 2>(l.rows, l.yb, p, g, i, w, o, st);
-      case 2: return launch_weighted_rows<2, 2, 2, 1>(l.rows, l.yb, p, g, i, w, o, st);
+      case 2: return tune_int("pool_scaled_strip", 1) ? launch_strip_rows<2, 2, 2, 2>(l.rows, l.yb, p, g, i, o, st, w) : launch_weighted_rows<2, 2, 2, 1>(l.rows, l.yb, p, g, i, w, o, st);
       case 3: return launch_weighted_rows<2, 2, 2, 2>(l.rows, l.yb, p, g, i, w, o, st);
-      case 4: return launch_weighted_rows<3, 3, 1, 1>(l.rows, l.yb, p, g, i, w, o, st);
+      case 4: return tune_int("pool_scaled_strip", 1) ? launch_strip_rows<3, 3, 1, 2>(l.rows, l.yb, p, g, i, o, st, w) : launch_weighted_rows<3, 3, 1, 1>(l.rows, l.yb, p, g, i, w, o, st);
       case 5: return launch_weighted_rows<3, 3, 1, 2>(l.rows, l.yb, p, g, i, w, o, st);
       default: return hipErrorInvalidValue;
     }
