@@ -612,10 +612,14 @@ def test_depthwise_convolution_dilated_runs_generic():
     assert info["path_name"] == "generic", info
 
 
+@pytest.mark.parametrize("own_kernel", [0, 1])
 @pytest.mark.parametrize("R,stride,pad", [(3, 2, 1), (2, 2, 0), (3, 1, 1), (4, 4, 0)])
-def test_average_pooling_with_scale(R, stride, pad):
-    """Average pooling as a sum of scaled taps (the scale in a one-element buffer): the window family's kernel sums
-    the in-range taps and scales once; windows it has no variant for run on the generic kernel."""
+def test_average_pooling_with_scale(R, stride, pad, own_kernel, monkeypatch):
+    """Average pooling as a sum of scaled taps (the scale in a one-element buffer): the window family's strip kernel
+    sums the in-range taps and scales once (own_kernel: the same in the weighted-window kernel's scaled form); windows
+    it has no variant for run on the generic kernel."""
+    if own_kernel:
+        monkeypatch.setenv("STRIPE_TUNE", "pool_scaled_strip=0")
     N, H, Wd, Cc = 2, 24, 20, 16
     blk = W.avgpool_block(N, H, Wd, Cc, R, stride, pad)
     ins = [W.seeded_tensor((N, H, Wd, Cc), "f32", 0), torch.full((1,), 1.0 / (R * R), dtype=torch.float32)]
