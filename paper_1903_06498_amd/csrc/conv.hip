@@ -744,6 +744,7 @@ bool conv_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block
   const bool tuned = tune_int("conv_tuned", 1) != 0;   // 0: measure the general kernel on the tuned kernels' shapes
   if (tuned && in_dtype == STRIPE_I8 && conv_i8_select(c, in_dtype, l, info)) return true;
   if (tuned && in_dtype == STRIPE_BF16 && conv3x3_select(c, in_dtype, l, info)) return true;
+  if (conv_gemm_select(c, in_dtype, l, info)) return true;
   return conv_igemm_select(c, in_dtype, false, l, info);
 }
 
@@ -832,7 +833,7 @@ bool conv_can_fuse_bias_relu(const Conv2dShape& c, const ConvLaunch& l) {
   const bool dense = c.o_x == c.Co && (c.Ho == 1 || c.o_y == c.Wo * c.Co) && (c.N == 1 || c.o_n == c.Ho * c.Wo * c.Co) && c.o_base == 0;
   if (!dense) return false;
   if (l.variant == kConvW4Variant + 3 || l.variant == kConvW4Variant + 4) return true;   // the LDS-direct 3x3 kernels
-  if (l.variant >= kConvIgemmVariant && l.in_dtype == STRIPE_BF16 && c.Co % 4 == 0) {
+  if (l.variant >= kConvIgemmVariant && l.variant < kConvGemmVariant && l.in_dtype == STRIPE_BF16 && c.Co % 4 == 0) {
     // the general kernel leaves a pixel none of whose taps lies inside the image unwritten: with such a pixel the
     // temporary would hold an undefined element, and the two statements stay apart
     for (int64_t y = 0; y < c.Ho; ++y) {
@@ -865,6 +866,7 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
 
 static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias,
                                   int epi, hipStream_t st) {
+  if (l.variant >= kConvGemmVariant) return epi ? hipErrorInvalidValue : launch_conv_gemm(c, l, in, flt, out, st);
   if (l.variant >= kConvIgemmVariant) return launch_conv_igemm(c, l, l.in_dtype, epi == 2, in, flt, out, epi ? bias : nullptr, st);
   if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;

@@ -39,6 +39,10 @@ struct GemmParams {
   const float* bias;
   int32_t epi;
   int32_t vec_c;              // LDS-direct 256-tile kernel: C strides, base and pointer allow one store per row and four columns
+  // Convolution mode of the LDS-direct 256-tile kernel (D_CONV): row m of A is output pixel m (flattened n, y, x), the
+  // reduction walks filter taps (i, j) and channel chunks of 32; a_base / b_base are the input's and the filter's.
+  int32_t cv_Ho, cv_Wo, cv_H, cv_W, cv_sy, cv_sx, cv_py, cv_px, cv_dy, cv_dx, cv_R, cv_S, cv_chunks, cv_pad_;
+  int64_t cv_i_n, cv_i_y, cv_i_x, cv_f_r, cv_f_s;   // element strides of the input (image, row, pixel) and of the filter's taps
 };
 
 // Fused epilogue of one accumulator value: bias, relu, store as fp32 or bf16 (round to nearest even).
@@ -422,6 +426,9 @@ constexpr int D_LDS = D_STAGES * (D_A_STAGE + D_B_STAGE);      // 128 KB
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 typedef __attribute__((ext_vector_type(8))) short s16x8;
 
+// Convolution mode: lanes whose tap lies outside the image fetch these 16 zero bytes instead.
+__device__ __attribute__((aligned(16))) uint16_t d_zero_chunk[8];
+
 struct DCtx {
   const uint16_t* a_src;   // per-lane global address of the lane's first A chunk (tile 0, load 0)
   const uint16_t* b_src;   // per-lane global address of the lane's first B chunk (tile 0, load 0)
@@ -432,6 +439,34 @@ struct DCtx {
   unsigned wave_lds;       // LDS byte offset of this wavefront's 1 KB load slot within a stage
   const uint16_t* a_ptr[4];  // ragged variants: the lane's load addresses one by one (rows clamped into the matrix)
   const uint16_t* b_ptr[4];
+  unsigned rmask[4], cmask[4];   // convolution mode: which filter rows / columns of the load's pixel lie inside the image
+  const uint16_t* zero;          // convolution mode: 16 zero bytes, fetched for taps outside the image
+};
+
+// Convolution mode: the K tile the next issue fetches -- filter tap (ti, tj), channel chunk tc -- and its element
+// offsets in the image and in the filter, advanced by additions (all wave-uniform).
+struct DWalk {
+  int ti, tj, tc;
+  int64_t a_off, b_off;
+  int64_t a_col, a_row, b_col, b_row;   // what a step to the next filter column / row adds (the chunk walk undone)
+  int S, chunks;
+  __device__ __forceinline__ void advance() {
+    if (++tc == chunks) {
+      tc = 0;
+      if (++tj == S) {
+        tj = 0;
+        ++ti;
+        a_off += a_row;
+        b_off += b_row;
+      } else {
+        a_off += a_col;
+        b_off += b_col;
+      }
+    } else {
+      a_off += D_BK;
+      b_off += D_BK;
+    }
+  }
 };
 
 // MODE bit 0: B is stored transposed, [n][k] with k contiguous (C = A * B^T as Linear layers and 1x1 convolutions
@@ -443,7 +478,7 @@ struct DCtx {
 // and the 32 x 32 result layout is the same, so the host hands the int8 matrices over as 16-bit matrices of half
 // the width (strides and bases in 2-byte units) and the accumulators are kept as bit patterns in the same registers.
 // Needs D_BT: with k contiguous in both operands no transposition of bytes is required.
-constexpr int D_BT = 1, D_RAGGED = 2, D_I8 = 4;
+constexpr int D_BT = 1, D_RAGGED = 2, D_I8 = 4, D_CONV = 8;   // D_CONV: see GemmParams; needs D_BT and D_RAGGED
 typedef __attribute__((ext_vector_type(4))) int d_i32x4;
 typedef __attribute__((ext_vector_type(16))) int d_i32x16;
 
@@ -541,12 +576,20 @@ __device__ __forceinline__ void d_mfma_part(const bf16x8 (&af)[4], const bf16x8 
 // a, b: the lane's first A and B address of the tile (plain variants) or the tile's K offset in elements cast into
 // a pointer-sized integer (ragged variants, which add it to the per-load addresses).
 template <int LD, int WAVES, int G, int MODE = 0>
-__device__ __forceinline__ void d_issue_group(const DCtx& c, const uint16_t* a, const uint16_t* b, size_t a_koff = 0, size_t b_koff = 0) {
+__device__ __forceinline__ void d_issue_group(const DCtx& c, const uint16_t* a, const uint16_t* b, size_t a_koff = 0, size_t b_koff = 0, int ti = 0,
+                                              int tj = 0) {
   constexpr int LPT = 32 / WAVES, HALF = LPT / 2, PER = LPT / 4 > 0 ? LPT / 4 : 1;
 #pragma unroll
   for (int e = 0; e < PER; ++e) {
     const int u = G * PER + e;
-    if constexpr (MODE & D_RAGGED) {
+    if constexpr (MODE & D_CONV) {
+      if (u < HALF) {
+        const bool inside = ((c.rmask[u < 4 ? u : 0] >> ti) & (c.cmask[u < 4 ? u : 0] >> tj) & 1u) != 0;
+        d_load_lds16(inside ? c.a_ptr[u < 4 ? u : 0] + a_koff : c.zero, LD * D_A_STAGE + u * (1024 * WAVES) + c.wave_lds);
+      } else if (u < LPT) {
+        d_load_lds16(c.b_ptr[u - HALF] + b_koff, D_B0 + LD * D_B_STAGE + (u - HALF) * (1024 * WAVES) + c.wave_lds);
+      }
+    } else if constexpr (MODE & D_RAGGED) {
       if (u < HALF) d_load_lds16(c.a_ptr[u] + a_koff, LD * D_A_STAGE + u * (1024 * WAVES) + c.wave_lds);
       else if (u < LPT) d_load_lds16(c.b_ptr[u - HALF] + b_koff, D_B0 + LD * D_B_STAGE + (u - HALF) * (1024 * WAVES) + c.wave_lds);
     } else {
@@ -575,13 +618,21 @@ __device__ __forceinline__ void d_wait_loads() {
 // have landed.
 template <int WAVES, int SCHED, int STAGE_N, bool ISSUE, int PENDING, bool NEXT_FRAGS, int MODE = 0>
 __device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt, bf16x8 (&af)[2][4],
-                                       bf16x8 (&bf)[2][WAVES == 4 ? 4 : 2], f32x16 (&acc)[4][WAVES == 4 ? 4 : 2]) {
+                                       bf16x8 (&bf)[2][WAVES == 4 ? 4 : 2], f32x16 (&acc)[4][WAVES == 4 ? 4 : 2], DWalk* walk = nullptr) {
   constexpr int FN = WAVES == 4 ? 4 : 2;
   constexpr int NXT = (STAGE_N + 1) % D_STAGES;
   constexpr int LD = (STAGE_N + 3) % D_STAGES;
   const uint16_t* a = c.a_src + (size_t)(kt + 3) * D_BK;
   const uint16_t* b = c.b_src + (size_t)(kt + 3) * c.b_kstep;
-  const size_t a_koff = (size_t)(kt + 3) * D_BK, b_koff = (size_t)(kt + 3) * c.b_kstep;
+  size_t a_koff = (size_t)(kt + 3) * D_BK, b_koff = (size_t)(kt + 3) * c.b_kstep;
+  int ti = 0, tj = 0;
+  if constexpr ((MODE & D_CONV) != 0) {   // tile kt+3 is the walk's next tile
+    a_koff = (size_t)walk->a_off;
+    b_koff = (size_t)walk->b_off;
+    ti = walk->ti;
+    tj = walk->tj;
+    if (ISSUE) walk->advance();
+  }
   D_FENCE();
   d_mfma_row<0, FN, MODE, SCHED == 1>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 0, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
   d_mfma_row<1, FN, MODE, SCHED == 1>(af[0], bf[0], acc); d_read_group<SCHED, STAGE_N, 1, 1, FN, MODE>(c, lds, af[1], bf[1]); D_FENCE();
@@ -597,19 +648,19 @@ __device__ __forceinline__ void d_tile(const DCtx& c, unsigned char* lds, int kt
   d_mfma_part<3, EARLY, FN, FN, MODE, SCHED == 1>(af[0], bf[0], acc);
   d_mfma_row<0, FN, MODE, SCHED == 1>(af[1], bf[1], acc);
   if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 0, FN, MODE>(c, lds, af[0], bf[0]);
-  if (ISSUE) d_issue_group<LD, WAVES, 0, MODE>(c, a, b, a_koff, b_koff);
+  if (ISSUE) d_issue_group<LD, WAVES, 0, MODE>(c, a, b, a_koff, b_koff, ti, tj);
   D_FENCE();
   d_mfma_row<1, FN, MODE, SCHED == 1>(af[1], bf[1], acc);
   if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 1, FN, MODE>(c, lds, af[0], bf[0]);
-  if (ISSUE) d_issue_group<LD, WAVES, 1, MODE>(c, a, b, a_koff, b_koff);
+  if (ISSUE) d_issue_group<LD, WAVES, 1, MODE>(c, a, b, a_koff, b_koff, ti, tj);
   D_FENCE();
   d_mfma_row<2, FN, MODE, SCHED == 1>(af[1], bf[1], acc);
   if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 2, FN, MODE>(c, lds, af[0], bf[0]);
-  if (ISSUE) d_issue_group<LD, WAVES, 2, MODE>(c, a, b, a_koff, b_koff);
+  if (ISSUE) d_issue_group<LD, WAVES, 2, MODE>(c, a, b, a_koff, b_koff, ti, tj);
   D_FENCE();
   d_mfma_row<3, FN, MODE, SCHED == 1>(af[1], bf[1], acc);
   if (NEXT_FRAGS) d_read_group<SCHED, NXT, 0, 3, FN, MODE>(c, lds, af[0], bf[0]);
-  if (ISSUE) d_issue_group<LD, WAVES, 3, MODE>(c, a, b, a_koff, b_koff);
+  if (ISSUE) d_issue_group<LD, WAVES, 3, MODE>(c, a, b, a_koff, b_koff, ti, tj);
   D_FENCE();
 }
 
@@ -673,6 +724,42 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
       }
     }
   }
+  DWalk walk = {};
+  if constexpr ((MODE & D_CONV) != 0) {
+    static_assert((MODE & D_BT) && (MODE & D_RAGGED) && WAVES == 4, "the convolution mode builds on the transposed-B, ragged, four-wavefront form");
+    // Row m of A is output pixel m = (n, y, x): the load's address for filter tap (0, 0) and the masks of the taps
+    // inside the image; rows past the last pixel repeat it (they feed accumulators that are never stored).
+    const uint16_t* zero = d_zero_chunk;
+    asm volatile("" : "+s"(zero));   // held in registers (else its address is re-read from memory before every load)
+    c.zero = zero;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = 16 * wave + (lane >> 2) + 64 * u;
+      const int chunk = (lane & 3) ^ ((row >> 2) & 3);
+      int64_t gm = (int64_t)tm * BM + row;
+      if (gm >= p.M) gm = p.M - 1;
+      const int m = (int)gm, x = m % p.cv_Wo, q = m / p.cv_Wo, y = q % p.cv_Ho, n = q / p.cv_Ho;
+      const int iy0 = y * p.cv_sy - p.cv_py, ix0 = x * p.cv_sx - p.cv_px;
+      c.a_ptr[u] = A + p.a_base + (int64_t)n * p.cv_i_n + (int64_t)iy0 * p.cv_i_y + (int64_t)ix0 * p.cv_i_x + chunk * 8;
+      unsigned rm = 0, cm = 0;
+      for (int i = 0; i < p.cv_R; ++i) {
+        const int yy = iy0 + i * p.cv_dy;
+        if (yy >= 0 && yy < p.cv_H) rm |= 1u << i;
+      }
+      for (int j = 0; j < p.cv_S; ++j) {
+        const int xx = ix0 + j * p.cv_dx;
+        if (xx >= 0 && xx < p.cv_W) cm |= 1u << j;
+      }
+      c.rmask[u] = rm;
+      c.cmask[u] = cm;
+    }
+    walk.S = p.cv_S;
+    walk.chunks = p.cv_chunks;
+    walk.a_col = (int64_t)p.cv_dx * p.cv_i_x - (int64_t)(p.cv_chunks - 1) * D_BK;
+    walk.b_col = p.cv_f_s - (int64_t)(p.cv_chunks - 1) * D_BK;
+    walk.a_row = (int64_t)p.cv_dy * p.cv_i_y - (int64_t)(p.cv_S - 1) * p.cv_dx * p.cv_i_x - (int64_t)(p.cv_chunks - 1) * D_BK;
+    walk.b_row = p.cv_f_r - (int64_t)(p.cv_S - 1) * p.cv_f_s - (int64_t)(p.cv_chunks - 1) * D_BK;
+  }
   c.wave_lds = wave * 1024;
   // A fragments: lane supplies row (lane&31) (+32*i) and chunk 2*s + (lane>>5)
   {
@@ -708,7 +795,19 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   // prologue: tiles 0, 1, 2 in flight, wait for tile 0   (k_tiles is a multiple of 4, checked on the host)
-  {
+  if constexpr ((MODE & D_CONV) != 0) {
+    const uint16_t* a = nullptr;
+    const uint16_t* b = nullptr;
+    d_issue_group<0, WAVES, 0, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj); d_issue_group<0, WAVES, 1, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj);
+    d_issue_group<0, WAVES, 2, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj); d_issue_group<0, WAVES, 3, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj);
+    walk.advance();
+    d_issue_group<1, WAVES, 0, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj); d_issue_group<1, WAVES, 1, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj);
+    d_issue_group<1, WAVES, 2, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj); d_issue_group<1, WAVES, 3, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj);
+    walk.advance();
+    d_issue_group<2, WAVES, 0, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj); d_issue_group<2, WAVES, 1, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj);
+    d_issue_group<2, WAVES, 2, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj); d_issue_group<2, WAVES, 3, MODE>(c, a, b, (size_t)walk.a_off, (size_t)walk.b_off, walk.ti, walk.tj);
+    walk.advance();   // the walk now stands at tile 3, the first one the loop issues
+  } else {
     const uint16_t* a = c.a_src;
     const uint16_t* b = c.b_src;
     size_t ak = 0, bk = 0;
@@ -724,15 +823,15 @@ __global__ __launch_bounds__(WAVES * 64, 1) void gemm_bf16_dma_kernel(const Gemm
 
   const int last4 = p.k_tiles - 4;
   for (int kt = 0; kt < last4; kt += 4) {
-    d_tile<WAVES, SCHED, 0, true, LPT, true, MODE>(c, lds, kt, af, bf, acc);
-    d_tile<WAVES, SCHED, 1, true, LPT, true, MODE>(c, lds, kt + 1, af, bf, acc);
-    d_tile<WAVES, SCHED, 2, true, LPT, true, MODE>(c, lds, kt + 2, af, bf, acc);
-    d_tile<WAVES, SCHED, 3, true, LPT, true, MODE>(c, lds, kt + 3, af, bf, acc);
+    d_tile<WAVES, SCHED, 0, true, LPT, true, MODE>(c, lds, kt, af, bf, acc, &walk);
+    d_tile<WAVES, SCHED, 1, true, LPT, true, MODE>(c, lds, kt + 1, af, bf, acc, &walk);
+    d_tile<WAVES, SCHED, 2, true, LPT, true, MODE>(c, lds, kt + 2, af, bf, acc, &walk);
+    d_tile<WAVES, SCHED, 3, true, LPT, true, MODE>(c, lds, kt + 3, af, bf, acc, &walk);
   }
-  d_tile<WAVES, SCHED, 0, true, LPT, true, MODE>(c, lds, last4, af, bf, acc);        // issues the last tile's loads
-  d_tile<WAVES, SCHED, 1, false, LPT, true, MODE>(c, lds, last4 + 1, af, bf, acc);
-  d_tile<WAVES, SCHED, 2, false, 0, true, MODE>(c, lds, last4 + 2, af, bf, acc);
-  d_tile<WAVES, SCHED, 3, false, 0, false, MODE>(c, lds, last4 + 3, af, bf, acc);
+  d_tile<WAVES, SCHED, 0, true, LPT, true, MODE>(c, lds, last4, af, bf, acc, &walk);        // issues the last tile's loads
+  d_tile<WAVES, SCHED, 1, false, LPT, true, MODE>(c, lds, last4 + 1, af, bf, acc, &walk);
+  d_tile<WAVES, SCHED, 2, false, 0, true, MODE>(c, lds, last4 + 2, af, bf, acc, &walk);
+  d_tile<WAVES, SCHED, 3, false, 0, false, MODE>(c, lds, last4 + 3, af, bf, acc, &walk);
 
   const int fr = lane & 31, fh = lane >> 5;
   if constexpr (!(MODE & D_RAGGED)) {
@@ -1354,6 +1453,87 @@ static hipError_t launch_gemm_epi(const GemmShape& g, const GemmLaunch& l, const
   }
   hipLaunchKernelGGL(kernel, dim3((unsigned)l.grid), dim3(threads), lds_bytes, st, pk, (const uint16_t*)a,
                      (const uint16_t*)b, (float*)c);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------
+// Convolutions on the 256 x 256-tile kernel (its D_CONV mode): the nesting of paper Section 3.1.3 with the output
+// pixels (flattened n, y, x) as the rows of A and the filter taps and channel chunks as the K walk -- Figure 5b's
+// view by address arithmetic, as in the general convolution kernel, but with this kernel's 128 x 128 register tiles
+// and schedule.  For convolutions large enough to fill the chip with such tiles.
+// ---------------------------------------------------------------------------
+bool conv_gemm_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info) {
+  const int mode = tune_int("conv_gemm", 1);   // 0: never, 2: whatever the tile count and the padding of the channel tile
+  if (mode == 0 || in_dtype != STRIPE_BF16 || tune_int("gemm_dma", 1) == 0) return false;
+  if (c.i_c != 1 || c.f_c != 1 || c.o_k != 1) return false;
+  if (c.Ci % D_BK || c.R < 1 || c.S < 1 || c.R > 32 || c.S > 32 || c.Co < 8) return false;
+  const int64_t k_tiles = c.R * c.S * (c.Ci / D_BK);
+  if (k_tiles % D_STAGES || k_tiles < D_STAGES || k_tiles > 0x7fffffffLL) return false;
+  if (c.stride_y < 1 || c.stride_x < 1 || c.dil_y < 1 || c.dil_x < 1 || c.pad_y < 0 || c.pad_x < 0) return false;
+  for (int64_t v : {c.i_n, c.i_y, c.i_x, c.i_base, c.f_r, c.f_s, c.f_k, c.f_base})
+    if (v % 8) return false;                   // 16-byte loads
+  for (int64_t v : {c.N, c.Ho, c.Wo, c.H, c.W, c.Co, c.stride_y, c.stride_x, c.pad_y, c.pad_x, c.dil_y, c.dil_x})
+    if (v > 0x3fffffff) return false;
+  // pixel m = (n * Ho + y) * Wo + x at o_base + m * o_x: the output as a row-major matrix (strides of one-element indexes do not matter)
+  if ((c.Ho > 1 && c.o_y != c.Wo * c.o_x) || (c.N > 1 && c.o_n != c.Ho * c.Wo * c.o_x)) return false;
+  const int64_t m_total = c.N * c.Ho * c.Wo;
+  if (m_total < 1 || m_total > 0x7fffffffLL - 512) return false;
+  // every pixel has a tap inside the image in each direction, so every row of the output matrix is stored
+  auto all_have_tap = [](int64_t outs, int64_t stride, int64_t pad, int64_t dil, int64_t taps, int64_t extent) {
+    if (outs > ((int64_t)1 << 20)) return false;
+    for (int64_t o = 0; o < outs; ++o) {
+      bool any = false;
+      for (int64_t i = 0; i < taps && !any; ++i) {
+        const int64_t v = o * stride - pad + i * dil;
+        any = v >= 0 && v < extent;
+      }
+      if (!any) return false;
+    }
+    return true;
+  };
+  if (!all_have_tap(c.Ho, c.stride_y, c.pad_y, c.dil_y, c.R, c.H) || !all_have_tap(c.Wo, c.stride_x, c.pad_x, c.dil_x, c.S, c.W)) return false;
+  const int64_t tiles_m = (m_total + BM - 1) / BM, tiles_n = (c.Co + BN - 1) / BN;
+  if (tiles_m > 32767 || tiles_n > 32767) return false;
+  if (mode != 2 && (tiles_m * tiles_n < 128 || (tiles_n * BN - c.Co) * 4 > tiles_n * BN)) return false;   // fill the chip; at most a quarter of the channel tiles padding
+  l->variant = kConvGemmVariant;
+  l->in_dtype = in_dtype;
+  l->grid = tiles_m * tiles_n;
+  info->path = STRIPE_PATH_MFMA_CONV;
+  info->tile_m = BM; info->tile_n = BN; info->tile_k = D_BK;
+  info->frag_m = 32; info->frag_n = 32; info->frag_k = 16;
+  info->lds_bytes = D_LDS;
+  info->workgroup_size = 256;
+  info->grid = l->grid;
+  snprintf(info->kernel, sizeof info->kernel, "conv_gemm_bf16_256x256x32_mfma32x32x16_w4_lds_direct");
+  return true;
+}
+
+hipError_t launch_conv_gemm(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
+  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
+  GemmParams p = {};
+  const int64_t m_total = c.N * c.Ho * c.Wo;
+  p.tiles_m = (int)((m_total + BM - 1) / BM);
+  p.tiles_n = (int)((c.Co + BN - 1) / BN);
+  p.k_tiles = (int)(c.R * c.S * (c.Ci / D_BK));
+  p.M = (int)m_total;
+  p.N = (int)c.Co;
+  p.a_m = 0; p.b_k = c.f_k; p.c_m = c.o_x;
+  p.a_base = c.i_base; p.b_base = c.f_base; p.c_base = c.o_base;
+  p.bias = nullptr; p.epi = 0; p.vec_c = 0;
+  p.cv_Ho = (int)c.Ho; p.cv_Wo = (int)c.Wo; p.cv_H = (int)c.H; p.cv_W = (int)c.W;
+  p.cv_sy = (int)c.stride_y; p.cv_sx = (int)c.stride_x; p.cv_py = (int)c.pad_y; p.cv_px = (int)c.pad_x;
+  p.cv_dy = (int)c.dil_y; p.cv_dx = (int)c.dil_x; p.cv_R = (int)c.R; p.cv_S = (int)c.S; p.cv_chunks = (int)(c.Ci / D_BK);
+  p.cv_i_n = c.i_n; p.cv_i_y = c.i_y; p.cv_i_x = c.i_x; p.cv_f_r = c.f_r; p.cv_f_s = c.f_s;
+  void (*kernel)(const GemmParams, const uint16_t*, const uint16_t*, float*) = gemm_bf16_dma_kernel<4, 1, D_BT + D_RAGGED + D_CONV>;
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev != l.lds_enabled_on) {   // more than 64 KB of dynamic LDS has to be enabled once per device
+    e = hipFuncSetAttribute((const void*)kernel, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS);
+    if (e != hipSuccess) return e;
+    l.lds_enabled_on = dev;
+  }
+  hipLaunchKernelGGL(kernel, dim3((unsigned)l.grid), dim3(W4_THREADS), D_LDS, st, p, (const uint16_t*)in, (const uint16_t*)flt, (float*)out);
   return hipGetLastError();
 }
 

@@ -49,6 +49,7 @@ hipError_t launch_gemm_bias_relu(const GemmShape& g, const GemmLaunch& l, const 
 
 // ---- nested-tile convolution-shaped contraction on matrix cores -----------
 constexpr int kConvIgemmVariant = 300;   // general convolution kernel; 300: 128 x 128 tiles, 301: 256 x 64, 302: 256 x 128
+constexpr int kConvGemmVariant = 400;    // large convolutions on the 256 x 256-tile contraction kernel's convolution mode
 struct ConvLaunch {
   int variant = -1;
   int64_t grid = 0;
@@ -67,6 +68,10 @@ hipError_t launch_conv_bias_relu(const Conv2dShape& c, const ConvLaunch& l, cons
 // general convolution kernel (implicit contraction: any filter extent, stride, dilation, padding, image width;
 // bf16 with Ci % 32 == 0 or int8 with Ci % 64 == 0; channels contiguous); conv_select falls back to it
 bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLaunch* l, stripe_block_info_t* info);
+// large bf16 convolutions (at least 128 tiles of 256 pixels x 256 channels, reduction a multiple of four 32-deep K tiles,
+// dense output, every pixel written) on the contraction kernel: pixels as rows of A, gathered per filter tap
+bool conv_gemm_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
+hipError_t launch_conv_gemm(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st);
 // bias != nullptr: the fused form of a following statement O = relu(T + bias[k]) (float blocks only)
 hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_dtype, bool out_bf16, const void* in, const void* flt, void* out,
                              const void* bias, hipStream_t stream);

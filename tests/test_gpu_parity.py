@@ -995,10 +995,14 @@ IGEMM_CASES = {
     "1x1_64to128_one_k_tile": (2, 10, 10, 64, 128, 1, 1, 1, 0, "bf16"),      # 128-byte K tile rows: the whole reduction is one tile
     "1x1_i8_128to72_one_k_tile": (1, 12, 9, 128, 72, 1, 1, 1, 0, "i8"),
     "1x3_64to128_three_k_tiles": (1, 9, 20, 64, 128, 1, 3, 1, 1, "bf16"),
+    "3x3_128to264": (2, 19, 23, 128, 264, 3, 3, 1, 1, "bf16"),               # 36 K tiles; two channel tiles of 256, the second ragged
+    "2x2_s2_64to72": (3, 20, 18, 64, 72, 2, 2, 2, 0, "bf16"),                 # 8 K tiles
+    "3x3_pad2_128to40": (1, 21, 17, 128, 40, 3, 3, 1, 2, "bf16"),             # padding 2 of a 3x3: the pixels at the edges keep one tap
+    "1x2_64to300": (2, 15, 20, 64, 300, 1, 2, 1, 0, "bf16"),                  # 4 K tiles: the shortest walk
 }
 
 
-@pytest.mark.parametrize("tile", ["chosen", "256x128", "128x128_k64"])
+@pytest.mark.parametrize("tile", ["chosen", "256x128", "128x128_k64", "contraction_kernel"])
 @pytest.mark.parametrize("case", sorted(IGEMM_CASES))
 def test_conv_family_on_the_matrix_cores(case, tile, monkeypatch):
     """Dense convolution-shaped blocks outside the two tuned shapes run on the general nested-tile kernel: other
@@ -1010,6 +1014,8 @@ def test_conv_family_on_the_matrix_cores(case, tile, monkeypatch):
         monkeypatch.setenv("STRIPE_TUNE", "conv_igemm_tn=128,conv_igemm_tm=256")
     elif tile == "128x128_k64":   # 64-byte K tile rows, which blocks of more than 256 tiles take also where 128-byte rows are possible
         monkeypatch.setenv("STRIPE_TUNE", "conv_igemm_tn=128,conv_igemm_tm=128,conv_igemm_kb=64")
+    elif tile == "contraction_kernel":   # the 256 x 256-tile contraction kernel's convolution mode, chosen from 128 such tiles on
+        monkeypatch.setenv("STRIPE_TUNE", "conv_gemm=2")
     blk = W.conv2d_block(N, H, Wd, Ci, Co, R, S, st, pad, dt, odt)
     Ho, Wo = (H + 2 * pad - R) // st + 1, (Wd + 2 * pad - S) // st + 1
     f = W.seeded_tensor((R, S, Co, Ci), dt, 1)
@@ -1017,7 +1023,10 @@ def test_conv_family_on_the_matrix_cores(case, tile, monkeypatch):
     n0, y0, x0, c0 = N - 1, H // 2, Wd - 1, Ci - 3
     i[n0, y0, x0, c0] = 1
     gpu, sb = run_gpu(blk, [i, f], return_block=True)
-    assert sb.info["path_name"] == "mfma_conv" and "conv_igemm" in sb.info["kernel"], sb.info
+    assert sb.info["path_name"] == "mfma_conv" and ("conv_igemm" in sb.info["kernel"] or tile == "contraction_kernel"), sb.info
+    if tile == "contraction_kernel":   # bf16, the reduction a multiple of four 32-deep K tiles, every pixel written: else the general kernel
+        takes = dt == "bf16" and (R * S * (Ci // 32)) % 4 == 0 and Co >= 8 and all(taps(y, st, pad, R, H) for y in range(Ho)) and all(taps(x, st, pad, S, Wd) for x in range(Wo))
+        assert ("conv_gemm_bf16_256x256x32" in sb.info["kernel"]) == takes, sb.info
     assert tile != "256x128" or "_256x128x" in sb.info["kernel"], sb.info
     assert tile != "128x128_k64" or ("_128x128x64_" if dt == "i8" else "_128x128x32_") in sb.info["kernel"], sb.info
     say(f"conv family {case}: {sb.info['kernel']} grid {sb.info['grid']}")
@@ -1071,10 +1080,10 @@ def test_conv_family_on_the_tuned_shapes(monkeypatch):
 
 
 # ------------------------------------------------------------------ convolution configs at full size
-CONV_FAMILY_KERNELS = {   # the benchmark's shapes of the general kernel and the tile / K tile row its selector gives them
+CONV_FAMILY_KERNELS = {   # the benchmark's shapes of the general kernel (one: of the contraction kernel) and the tile / K tile row the selectors give them
     "conv3x3_bf16_128to128": "_128x128x64_", "conv3x3_s2_bf16_64to128": "_128x128x64_", "conv1x7_bf16_64to64": "_256x64x32_",
     "conv3x3_bf16_w112": "_256x64x32_", "conv5x5_bf16_32to32": "_256x64x32_", "conv3x3_i8_64to64": "_256x64x64_",
-    "conv3x3_bf16_128to192": "_256x128x32_", "conv3x3_bf16_128to256_56": "_128x128x32_",
+    "conv3x3_bf16_128to192": "_256x128x32_", "conv3x3_bf16_128to256_56": "conv_gemm_bf16_256x256x32_",
 }
 
 
@@ -1089,7 +1098,7 @@ def test_conv_family_bench_shapes_full_size(name):
     ones = [torch.ones_like(ins[0]), torch.ones_like(ins[1])]
     gpu, sb = run_gpu(blk, ones, return_block=True)
     say(f"{name}: {sb.info['kernel']} grid {sb.info['grid']}")
-    assert "conv_igemm" in sb.info["kernel"] and CONV_FAMILY_KERNELS[name] in sb.info["kernel"], sb.info
+    assert sb.info["path_name"] == "mfma_conv" and CONV_FAMILY_KERNELS[name] in sb.info["kernel"], sb.info
     cy = np.array([taps(y, st, pad, R, H) for y in range(Ho)])
     cx = np.array([taps(x, st, pad, S, Wd) for x in range(Wo)])
     want = float(Ci) * cy[:, None] * cx[None, :]

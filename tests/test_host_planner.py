@@ -211,7 +211,8 @@ def test_tile_selection_follows_the_cost_model():
     assert "256x64x32" in kernel(W.conv2d_block(4, 28, 28, 128, 192, 3, 3, 1, 1, "bf16", "f32"))   # three 64-wide tiles waste nothing
     # the largest tile where its tiles fill one round of workgroups: 196 of them here, 392 there (then 784 smaller ones, two per CU)
     assert "256x128x32" in kernel(W.conv2d_block(32, 28, 28, 128, 192, 3, 3, 1, 1, "bf16", "f32"))
-    assert "128x128x32" in kernel(W.conv2d_block(16, 56, 56, 128, 256, 3, 3, 1, 1, "bf16", "f32"))
+    assert "conv_gemm_bf16_256x256x32" in kernel(W.conv2d_block(16, 56, 56, 128, 256, 3, 3, 1, 1, "bf16", "f32"))   # 196 tiles of 256 x 256: the contraction kernel
+    assert "conv_igemm_bf16_128x128x32" in kernel(W.conv2d_block(32, 56, 56, 128, 128, 3, 3, 1, 1, "bf16", "f32"))   # half a 256-wide tile would be padding: 784 tiles of 128 x 128, two per CU
 
 
 def _two_statements(t_access_write, t_access_read, write_constraints=(), write_range=8):
