@@ -74,6 +74,7 @@ KIND = {
     "conv3x3_i8_64to64": ("TOP/s", "hbm", "int8"),
     "conv3x3_bf16_128to192": ("TFLOP/s", "mfma", "bf16"),
     "conv3x3_bf16_128to256_56": ("TFLOP/s", "mfma", "bf16"),
+    "conv3x3_bf16_256to256_56": ("TFLOP/s", "mfma", "bf16"),
     "depthwise3x3_f32": ("GB/s", "hbm", "f32"),        # weighted windows on the pooling family's kernel
     "avgpool3x3s2_f32": ("GB/s", "hbm", "f32"),
     "maxpool2x2s2_f32": ("GB/s", "hbm", "f32"),

@@ -418,7 +418,7 @@ def linear_bias_relu_program(M, N, K, out_dtype="bf16", b_transposed=True) -> Bl
 EXTRA_NAMES = ("gemm_bf16_4096_bt", "gemm_bf16_4000_ragged", "gemm_i8_4096_bt", "pointwise_conv_bf16", "transposed_conv_f32",
                "resnet_conv_bias_relu_bf16", "resnet_conv_bias_relu_f32", "conv3x3_bias_relu_bf16_128to128", "gemm_bf16_1024", "gemm_bf16_2048",
                "linear_bias_relu_4096", "gemm_bf16_256x256x65536", "gemm_i8_256x256x65536_bt", "gemm_bf16_1024x1024x8192", "conv3x3_bf16_128to128", "conv3x3_s2_bf16_64to128", "conv1x7_bf16_64to64",
-               "conv3x3_bf16_w112", "conv5x5_bf16_32to32", "conv3x3_i8_64to64", "conv3x3_bf16_128to192", "conv3x3_bf16_128to256_56", "depthwise3x3_f32", "avgpool3x3s2_f32", "maxpool2x2s2_f32", "maxpool3x3s1_f32")
+               "conv3x3_bf16_w112", "conv5x5_bf16_32to32", "conv3x3_i8_64to64", "conv3x3_bf16_128to192", "conv3x3_bf16_128to256_56", "conv3x3_bf16_256to256_56", "depthwise3x3_f32", "avgpool3x3s2_f32", "maxpool2x2s2_f32", "maxpool3x3s1_f32")
 
 
 # convolution shapes beyond the two tuned ones (the general matrix-core convolution kernel)
@@ -430,6 +430,7 @@ CONV_FAMILY = {   # name: (N, H, W, Ci, Co, R, S, stride, pad, dtype)
     "conv5x5_bf16_32to32": (32, 56, 56, 32, 32, 5, 5, 1, 2, "bf16"),
     "conv3x3_i8_64to64": (32, 56, 56, 64, 64, 3, 3, 1, 1, "i8"),
     "conv3x3_bf16_128to256_56": (16, 56, 56, 128, 256, 3, 3, 1, 1, "bf16"),   # 784 tiles of 128 x 128 (or 392 of 256 x 128: two rounds of workgroups)
+    "conv3x3_bf16_256to256_56": (32, 56, 56, 256, 256, 3, 3, 1, 1, "bf16"),   # 392 tiles of 256 x 256, 72 K tiles: the contraction kernel's convolution mode
     "conv3x3_bf16_128to192": (32, 28, 28, 128, 192, 3, 3, 1, 1, "bf16"),   # 192 channels: one and a half 128-wide tiles or three 64-wide ones; 196 tiles of 256 x 128
 }
 

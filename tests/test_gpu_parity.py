@@ -1083,7 +1083,7 @@ def test_conv_family_on_the_tuned_shapes(monkeypatch):
 CONV_FAMILY_KERNELS = {   # the benchmark's shapes of the general kernel (one: of the contraction kernel) and the tile / K tile row the selectors give them
     "conv3x3_bf16_128to128": "_128x128x64_", "conv3x3_s2_bf16_64to128": "_128x128x64_", "conv1x7_bf16_64to64": "_256x64x32_",
     "conv3x3_bf16_w112": "_256x64x32_", "conv5x5_bf16_32to32": "_256x64x32_", "conv3x3_i8_64to64": "_256x64x64_",
-    "conv3x3_bf16_128to192": "_256x128x32_", "conv3x3_bf16_128to256_56": "conv_gemm_bf16_256x256x32_",
+    "conv3x3_bf16_128to192": "_256x128x32_", "conv3x3_bf16_128to256_56": "conv_gemm_bf16_256x256x32_", "conv3x3_bf16_256to256_56": "conv_gemm_bf16_256x256x32_",
 }
 
 
