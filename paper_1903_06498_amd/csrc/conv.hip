@@ -833,6 +833,7 @@ bool conv_can_fuse_bias_relu(const Conv2dShape& c, const ConvLaunch& l) {
   const bool dense = c.o_x == c.Co && (c.Ho == 1 || c.o_y == c.Wo * c.Co) && (c.N == 1 || c.o_n == c.Ho * c.Wo * c.Co) && c.o_base == 0;
   if (!dense) return false;
   if (l.variant == kConvW4Variant + 3 || l.variant == kConvW4Variant + 4) return true;   // the LDS-direct 3x3 kernels
+  if (l.variant >= kConvGemmVariant) return true;   // the contraction kernel's convolution mode: chosen only where every pixel is written
   if (l.variant >= kConvIgemmVariant && l.variant < kConvGemmVariant && l.in_dtype == STRIPE_BF16 && c.Co % 4 == 0) {
     // the general kernel leaves a pixel none of whose taps lies inside the image unwritten: with such a pixel the
     // temporary would hold an undefined element, and the two statements stay apart
@@ -866,7 +867,7 @@ hipError_t launch_conv(const Conv2dShape& c, const ConvLaunch& l, const void* in
 
 static hipError_t launch_conv_epi(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias,
                                   int epi, hipStream_t st) {
-  if (l.variant >= kConvGemmVariant) return epi ? hipErrorInvalidValue : launch_conv_gemm(c, l, in, flt, out, st);
+  if (l.variant >= kConvGemmVariant) return launch_conv_gemm(c, l, in, flt, out, epi ? bias : nullptr, epi, st);
   if (l.variant >= kConvIgemmVariant) return launch_conv_igemm(c, l, l.in_dtype, epi == 2, in, flt, out, epi ? bias : nullptr, st);
   if (l.variant >= 100 && l.variant < kConvW4Variant) return launch_conv_i8(c, l, in, flt, out, st);
   if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 16)) return hipErrorInvalidValue;

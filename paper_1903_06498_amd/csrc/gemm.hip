@@ -1508,8 +1508,10 @@ bool conv_gemm_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_
   return true;
 }
 
-hipError_t launch_conv_gemm(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st) {
-  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % 4)) return hipErrorInvalidValue;
+// bias / epi: the fused form of a following statement O = relu(T + bias[k]); epi 1 = fp32 output, 2 = bf16 output (out then is O)
+hipError_t launch_conv_gemm(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias, int epi,
+                            hipStream_t st) {
+  if (((uintptr_t)in % 16) || ((uintptr_t)flt % 16) || ((uintptr_t)out % (epi == 2 ? 2 : 4)) || ((uintptr_t)bias % 4) || (epi && !bias)) return hipErrorInvalidValue;
   GemmParams p = {};
   const int64_t m_total = c.N * c.Ho * c.Wo;
   p.tiles_m = (int)((m_total + BM - 1) / BM);
@@ -1519,7 +1521,7 @@ hipError_t launch_conv_gemm(const Conv2dShape& c, const ConvLaunch& l, const voi
   p.N = (int)c.Co;
   p.a_m = 0; p.b_k = c.f_k; p.c_m = c.o_x;
   p.a_base = c.i_base; p.b_base = c.f_base; p.c_base = c.o_base;
-  p.bias = nullptr; p.epi = 0; p.vec_c = 0;
+  p.bias = (const float*)bias; p.epi = epi; p.vec_c = 0;
   p.cv_Ho = (int)c.Ho; p.cv_Wo = (int)c.Wo; p.cv_H = (int)c.H; p.cv_W = (int)c.W;
   p.cv_sy = (int)c.stride_y; p.cv_sx = (int)c.stride_x; p.cv_py = (int)c.pad_y; p.cv_px = (int)c.pad_x;
   p.cv_dy = (int)c.dil_y; p.cv_dx = (int)c.dil_x; p.cv_R = (int)c.R; p.cv_S = (int)c.S; p.cv_chunks = (int)(c.Ci / D_BK);

@@ -71,7 +71,8 @@ bool conv_igemm_select(const Conv2dShape& c, int in_dtype, bool out_bf16, ConvLa
 // large bf16 convolutions (at least 128 tiles of 256 pixels x 256 channels, reduction a multiple of four 32-deep K tiles,
 // dense output, every pixel written) on the contraction kernel: pixels as rows of A, gathered per filter tap
 bool conv_gemm_select(const Conv2dShape& c, int in_dtype, ConvLaunch* l, stripe_block_info_t* info);
-hipError_t launch_conv_gemm(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, hipStream_t st);
+hipError_t launch_conv_gemm(const Conv2dShape& c, const ConvLaunch& l, const void* in, const void* flt, void* out, const void* bias, int epi,
+                            hipStream_t st);
 // bias != nullptr: the fused form of a following statement O = relu(T + bias[k]) (float blocks only)
 hipError_t launch_conv_igemm(const Conv2dShape& c, const ConvLaunch& l, int in_dtype, bool out_bf16, const void* in, const void* flt, void* out,
                              const void* bias, hipStream_t stream);

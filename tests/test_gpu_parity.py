@@ -394,7 +394,7 @@ def test_fused_convolution_bias_relu(N, H, Wd, out_dt, fuse, monkeypatch):
         assert " ; " in info["kernel"], info["kernel"]
 
 
-@pytest.mark.parametrize("fuse", [1, 2, 0])
+@pytest.mark.parametrize("fuse", [1, 2, 3, 0])
 @pytest.mark.parametrize("out_dt", ["bf16", "f32"])
 @pytest.mark.parametrize("shape", [(2, 14, 14, 128, 128, 3, 1, 1), (2, 17, 19, 64, 128, 3, 2, 1), (1, 12, 40, 32, 96, 5, 1, 2),
                                    (3, 9, 11, 64, 36, 1, 1, 0), (1, 30, 30, 32, 64, 3, 2, 0)])
@@ -403,10 +403,13 @@ def test_fused_convolution_bias_relu_general_kernel(shape, out_dt, fuse, monkeyp
     extents and paddings the tuned kernel does not take; ragged pixel and channel tiles): fused into its store phase,
     (fuse=2: on the kernel's largest tile, 256 pixels x 128 channels), and unfused through a temporary; all against
     the oracle's serial evaluation."""
-    monkeypatch.setenv("STRIPE_TUNE", f"fuse={min(fuse, 1)}" + (",conv_igemm_tn=128,conv_igemm_tm=256" if fuse == 2 else ""))
+    monkeypatch.setenv("STRIPE_TUNE", f"fuse={min(fuse, 1)}" + (",conv_igemm_tn=128,conv_igemm_tm=256" if fuse == 2 else ",conv_gemm=2" if fuse == 3 else ""))
     info = program_parity(*shape, "bf16", out_dt)
-    if fuse:
-        assert fuse == 1 or "_256x128x" in info["kernel"], info["kernel"]
+    if fuse == 3 and (shape[5] * shape[5] * (shape[3] // 32)) % 4 == 0:
+        # (fuse=3: the contraction kernel's convolution mode, which takes reductions of a multiple of four K tiles)
+        assert info["kernel"].startswith("conv_gemm_bf16_256x256x32") and info["kernel"].endswith("+bias_relu" + ("_bf16" if out_dt == "bf16" else "")), info
+    elif fuse:
+        assert fuse != 2 or "_256x128x" in info["kernel"], info["kernel"]
         assert info["kernel"].startswith("conv_igemm_bf16_") and info["kernel"].endswith("+bias_relu" + ("_bf16" if out_dt == "bf16" else "")), info
     else:
         assert " ; " in info["kernel"] and "conv_igemm_bf16_" in info["kernel"], info["kernel"]
