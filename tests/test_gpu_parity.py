@@ -28,6 +28,9 @@ def say(msg):
     sys.stdout.flush()
 
 
+_FAMILY_ORACLE = {}   # oracle results of cases that run through several kernel variants (see tests.util.parity)
+
+
 def taps(y, s, p, R, H):
     return sum(1 for i in range(R) if 0 <= s * y + i - p < H)
 
@@ -927,7 +930,7 @@ def test_conv_mfma_bf16_small(N, H, Wd, w4, monkeypatch):
     monkeypatch.setenv("STRIPE_TUNE", conv_tune(w4))
     blk = W.conv2d_block(N, H, Wd, 64, 64, 3, 3, 1, 1, "bf16", "f32")
     ins = [W.seeded_tensor((N, H, Wd, 64), "bf16", 0), W.seeded_tensor((3, 3, 64, 64), "bf16", 1)]
-    info, score = parity(blk, ins, what=f"conv mfma {N}x{H}x{Wd}")
+    info, score = parity(blk, ins, what=f"conv mfma {N}x{H}x{Wd}", cache=_FAMILY_ORACLE, key=("3x3c64", N, H, Wd))   # one oracle run per shape
     say(f"conv mfma {N}x{H}x{Wd}: {info['kernel']} err/bound {score:.3f}")
     patch = 9 * (Wd + 2) * 128
     if w4 >= 3:
@@ -1043,7 +1046,7 @@ def test_conv_family_on_the_matrix_cores(case, tile, monkeypatch):
                 want[n0, y, x, :] = f[a, b, :, c0].double().numpy()
     assert np.array_equal(gpu.reshape(want.shape).astype(np.float64), want)
     ins = [W.seeded_tensor((N, H, Wd, Ci), dt, 0), f]
-    parity(blk, ins, what=f"conv family {case}")
+    parity(blk, ins, what=f"conv family {case}", threads=16, cache=_FAMILY_ORACLE, key=case)   # one oracle run per case, whatever the tile
     if dt == "i8":
         assert np.array_equal(run_gpu(blk, ins), run_gpu(blk, ins, "generic"))
 
@@ -1094,7 +1097,8 @@ CONV_FAMILY_KERNELS = {   # the benchmark's shapes of the general kernel (one: o
 def test_conv_family_bench_shapes_full_size(name):
     """The general kernel at the sizes and in the launch configurations bench.py times: all-ones operands give
     Ci * (taps inside the image) exactly on every element (pixels without any are left as they were); seeded data against the oracle on two whole images (the
-    first, whose tiles start at pixel 0, and one in the middle, whose tiles straddle image borders)."""
+    first, whose tiles start at pixel 0, and one in the middle, whose tiles straddle image borders; the two largest
+    workloads: the middle one)."""
     N, H, Wd, Ci, Co, R, S, st, pad, dt = W.CONV_FAMILY[name]
     blk, ins = W.extra_block(name), W.extra_inputs(name)
     Ho, Wo = (H + 2 * pad - R) // st + 1, (Wd + 2 * pad - S) // st + 1
@@ -1110,7 +1114,8 @@ def test_conv_family_bench_shapes_full_size(name):
     gpu = run_gpu(blk, ins)
     np_ins = [W.to_numpy(t).ravel() for t in ins]
     np_abs = None if dt == "i8" else abs_inputs(np_ins, ["bf16", "bf16"])
-    for n in (0, N // 2 + 1):
+    per_image = Ho * Wo * R * S * Ci * Co
+    for n in ((0, N // 2 + 1) if per_image < 600e6 else (N // 2 + 1,)):      # (the largest: the middle image only)
         lo, hi = [n, 0, 0, 0, 0, 0, 0], [n + 1, Ho, Wo, R, S, Ci, Co]
         res = O.evaluate(blk, np_ins, window=(lo, hi), threads=16, split_index=1)
         ares = None if np_abs is None else O.evaluate(blk, np_abs, window=(lo, hi), threads=16, split_index=1)

@@ -118,18 +118,25 @@ def check_untouched(gpu_out, oracle_res, odt):
         assert np.all(gpu_out[untouched] == want), "an element no iteration writes was modified"
 
 
-def parity(root, inputs, path="auto", window=None, threads=8, split_index=0, what=""):
+def parity(root, inputs, path="auto", window=None, threads=8, split_index=0, what="", cache=None, key=None):
     """Run GPU and oracle on the same inputs and compare.  With a window the
-    oracle computes only a slab of outputs and only that slab is compared."""
+    oracle computes only a slab of outputs and only that slab is compared.
+    cache / key: a dict that keeps the oracle's results for tests that run one block and one set of inputs through
+    several kernel variants (the oracle does not depend on the variant; the GPU side runs every time)."""
     gpu, blk = run_gpu(root, inputs, path, return_block=True)
     info = dict(blk.info)
     blk.close()
-    np_ins = [W.to_numpy(t).ravel() for t in inputs]
-    res = O.evaluate(root, np_ins, window=window, threads=threads, split_index=split_index)
-    abs_res = None
-    if root.refs[0].dtype == "bf16" and is_sum_of_products(root):
-        abs_res = O.evaluate(root, abs_inputs(np_ins, [r.dtype for r in root.refs[:-1]]), window=window, threads=threads,
-                             split_index=split_index)
+    if cache is not None and key in cache:
+        res, abs_res = cache[key]
+    else:
+        np_ins = [W.to_numpy(t).ravel() for t in inputs]
+        res = O.evaluate(root, np_ins, window=window, threads=threads, split_index=split_index)
+        abs_res = None
+        if root.refs[0].dtype == "bf16" and is_sum_of_products(root):
+            abs_res = O.evaluate(root, abs_inputs(np_ins, [r.dtype for r in root.refs[:-1]]), window=window, threads=threads,
+                                 split_index=split_index)
+        if cache is not None:
+            cache[key] = (res, abs_res)
     score = compare(root, inputs, gpu, res, what, abs_res)
     if window is None:
         check_untouched(gpu, res, root.refs[-1].dtype)
